@@ -1,0 +1,242 @@
+/*
+ * saap.h -- C ABI of the SAAP decode hot path for AMD MI355X (gfx950).
+ *
+ * SAAP ("self-attention with asymmetric partitions", arXiv 2502.08246) keeps a
+ * long-context KV cache in buckets.  Keys are assigned to buckets at prefill
+ * (nearest centroid of a pre-trained k-means, Section 4); at decode a small
+ * query classifier scores the buckets (Section 4, "Asymmetric assignment"),
+ * the nprobe best buckets are taken jointly for the query heads that share a
+ * KV head (Section 5, "Batched queries"), and exact softmax attention runs
+ * over every key of the visited buckets (Section 4, "Beyond top-k";
+ * Appendix F, Algorithms 1 and 2).
+ *
+ * Conventions shared by every call
+ *   - All data pointers are DEVICE pointers unless a comment says "host".
+ *     The caller owns every buffer.  The library allocates no device memory,
+ *     never synchronises and never copies to the host: all work is enqueued
+ *     on `stream` (a hipStream_t passed as void*, NULL = the null stream).
+ *   - Data pointers must be 16-byte aligned.
+ *   - Tensors are dense, row-major, innermost dimension last.
+ *   - Indices are int32, 0-based (the paper's bucket ids are 1-based).
+ *   - dtype: SAAP_F32 (0) or SAAP_BF16 (1).  bf16 is the upper 16 bits of
+ *     the IEEE fp32 pattern.
+ *   - Shapes: S sequences, Hq query heads, Hkv KV heads, G = Hq/Hkv query
+ *     heads per KV head (1, 2, 4 or 8), d = 128 features per head, N keys
+ *     per KV head, B buckets per KV head (the paper's C), nprobe visited
+ *     buckets (the paper's l).
+ *   - Return value: SAAP_OK or a negative status.  Argument checks happen
+ *     on the host before anything is enqueued; a failing call enqueues
+ *     nothing.  A status is also what a call returns when run on a machine
+ *     without a usable GPU (SAAP_HIP_ERROR).
+ *   - Workspace.  `ws` is caller-provided device scratch of at least
+ *     saap_workspace_bytes(op, ...) bytes.  Its first SAAP_WS_HEADER_BYTES
+ *     bytes hold arrival counters: they must be zero before the first call
+ *     that uses the buffer (saap_workspace_reset does that) and every call
+ *     leaves them zero again when its kernels have finished.  The rest is
+ *     scratch without meaning between calls.  Two calls that run
+ *     concurrently must not share a workspace.
+ */
+#ifndef SAAP_H
+#define SAAP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  SAAP_OK = 0,
+  SAAP_INVALID_ARG = -1,         /* null/misaligned pointer, bad shape, nprobe > B ... */
+  SAAP_UNSUPPORTED = -2,         /* dtype / d / G / size outside what the kernels cover */
+  SAAP_WORKSPACE_TOO_SMALL = -3,
+  SAAP_BUCKET_FULL = -4,         /* reserved: reported through overflow_flag on the device */
+  SAAP_HIP_ERROR = -5            /* a HIP runtime call failed (no GPU, launch error) */
+};
+
+enum { SAAP_F32 = 0, SAAP_BF16 = 1 };
+
+/* select_buckets / sparse_decode_attention routing modes */
+enum {
+  SAAP_GROUP_SUM = 0,   /* one bucket list per KV head from the summed scores of its G heads */
+  SAAP_INDEPENDENT = 1  /* one bucket list per query head */
+};
+
+/* classify_queries output kinds */
+enum { SAAP_PROBS = 0, SAAP_LOGITS = 1 };
+
+/* operation ids for saap_workspace_bytes */
+enum {
+  SAAP_OP_ASSIGN_KEYS = 0,
+  SAAP_OP_BUILD_BUCKET_INDEX = 1,
+  SAAP_OP_CLASSIFY_QUERIES = 2,
+  SAAP_OP_SELECT_BUCKETS = 3,
+  SAAP_OP_SPARSE_DECODE_ATTENTION = 4,
+  SAAP_OP_DENSE_DECODE_ATTENTION = 5,
+  SAAP_OP_APPEND_KEYS = 6
+};
+
+#define SAAP_WS_HEADER_BYTES 65536u
+#define SAAP_MAX_BUCKETS 8192      /* B and nprobe limit of select / sparse attention */
+#define SAAP_HEAD_DIM 128
+
+/* Shape record used only by saap_workspace_bytes; unused fields may be 0. */
+typedef struct {
+  int32_t S, Hq, Hkv, N, B, nprobe, d, hidden, dtype, mode;
+} saap_shape;
+
+/* Bytes of workspace `op` needs for `shape` (header included); 0 if the op or
+ * shape is invalid.  Pure host arithmetic. */
+size_t saap_workspace_bytes(int32_t op, const saap_shape* shape /* host */);
+
+/* Enqueue a fill kernel that zeroes the workspace header. */
+int32_t saap_workspace_reset(void* ws, size_t ws_bytes, void* stream);
+
+/* Human-readable name of a status code (host string, never NULL). */
+const char* saap_status_string(int32_t status);
+
+/* Number of compute units of the current device (host query; <= 0 on error). */
+int32_t saap_device_compute_units(void);
+
+/*
+ * assign_keys -- prefill-time assignment of keys to buckets.
+ * Section 2 ("Vector search based on partitions", indexing step) and Section 4:
+ * a key goes to exactly one bucket, that of its nearest centroid.
+ *   bucket_ids[s,h,n] = argmax_b ( <x[s,h,n,:], centroids[h,b,:]> + bias[h,b] )
+ * with the inner product taken as the sum, in index order, of the exact
+ * products in double precision, and the lowest b winning exact ties.  bias ==
+ * NULL is maximum inner product (spherical k-means with unit centroids);
+ * bias[b] = -|c_b|^2/2 is the Euclidean nearest centroid.  The features x are
+ * what the clustering was trained on (keys before RoPE, Section 4
+ * "Assigning with(out) RoPE"), not necessarily the cached keys.
+ *   x          [S,Hkv,N,d]  dtype
+ *   centroids  [Hkv,B,d]    dtype
+ *   bias       [Hkv,B]      fp32 or NULL
+ *   bucket_ids [S,Hkv,N]    int32, out
+ * bf16 inputs run on the matrix cores with fp32 accumulation; rows whose best
+ * two scores are closer than the accumulation error bound are re-scored in
+ * double precision, so the result is the argmax defined above bit for bit.
+ */
+int32_t saap_assign_keys(const void* x, const void* centroids, const float* bias,
+                         int32_t* bucket_ids,
+                         int32_t S, int32_t Hkv, int32_t N, int32_t B, int32_t d, int32_t dtype,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * build_bucket_index -- the CSR index of Appendix F (tensors Off and Idx) plus
+ * a bucket-sorted copy of K and V, so that a bucket is one contiguous run
+ * (Section 2 notes that an inverted file ideally stores a bucket contiguously).
+ *   len[s,h,b]   = number of keys n with bucket_ids[s,h,n] == b
+ *   off[s,h,0]   = 0,  off[s,h,b+1] = off[s,h,b] + len[s,h,b] + slack
+ *   idx[s,h,off[b]+r] = position of the r-th member of b, members in
+ *                  ascending position (stable); slack slots hold -1
+ *   Ksorted[s,h,j,:] = K[s,h,idx[j],:] (likewise V) for member slots;
+ *                  slack slots are left untouched
+ * The paper's Off has no slack (slack = 0 gives off[B] = N).  slack > 0
+ * reserves free slots behind every bucket for saap_append_keys.
+ * Ncap must equal N + B*slack.
+ *   bucket_ids [S,Hkv,N] int32; K,V [S,Hkv,N,d] dtype
+ *   off [S,Hkv,B+1], len [S,Hkv,B], idx [S,Hkv,Ncap] int32, out
+ *   Ksorted,Vsorted [S,Hkv,Ncap,d] dtype, out
+ * Ids outside [0,B) are a caller error; such keys are dropped from the index.
+ */
+int32_t saap_build_bucket_index(const int32_t* bucket_ids, const void* K, const void* V,
+                                int32_t* off, int32_t* len, int32_t* idx,
+                                void* Ksorted, void* Vsorted,
+                                int32_t S, int32_t Hkv, int32_t N, int32_t Ncap, int32_t B,
+                                int32_t d, int32_t dtype, int32_t slack,
+                                void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * append_keys -- one decode step's new key per (sequence, KV head): assign it
+ * as in saap_assign_keys and store it in the first free slot of its bucket.
+ * The paper needs the index to absorb keys during generation (Section 1) and
+ * gives no mechanism; this layout uses the slack slots of build_bucket_index.
+ *   x_new [S,Hkv,d] features; k_new, v_new [S,Hkv,d] cache rows (dtype)
+ *   pos_new [S] int32 or NULL: position recorded in idx (NULL records -2)
+ *   new_bucket_ids [S,Hkv] int32, out
+ *   overflow_flag  device int32: set to 1 if some bucket had no free slot;
+ *                  that key is not stored (len unchanged), others are.
+ */
+int32_t saap_append_keys(const void* x_new, const void* k_new, const void* v_new,
+                         const int32_t* pos_new,
+                         const void* centroids, const float* bias,
+                         const int32_t* off, int32_t* len, int32_t* idx,
+                         void* Ksorted, void* Vsorted,
+                         int32_t* new_bucket_ids, int32_t* overflow_flag,
+                         int32_t S, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype,
+                         void* stream);
+
+/*
+ * classify_queries -- the query assignment model f_q of Section 4 (a two-layer
+ * perceptron with ReLU, Section 6.1; batch-norm folded into W1,b1 by the caller):
+ *   h = max(0, W1 x + b1);  z = W2 h + b2;  scores = softmax(z)  (or z itself)
+ *   xq [S,Hq,d] dtype (query features, before RoPE)
+ *   W1 [Hw,hidden,d], W2 [Hw,B,hidden] dtype; b1 [Hw,hidden], b2 [Hw,B] fp32 or NULL
+ *   Hw weight sets: 1 (shared), Hkv (one per KV head) or Hq (one per query head)
+ *   scores [S,Hq,B] fp32, out
+ * hidden must be a multiple of 32 and B a multiple of 16.
+ */
+int32_t saap_classify_queries(const void* xq, const void* W1, const float* b1,
+                              const void* W2, const float* b2, int32_t Hw,
+                              float* scores,
+                              int32_t S, int32_t Hq, int32_t Hkv, int32_t d, int32_t hidden, int32_t B,
+                              int32_t dtype, int32_t output_kind,
+                              void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * select_buckets -- the nprobe most promising buckets (Section 4; Section 5
+ * "Batched queries": the scores of the G heads sharing a KV head are summed and
+ * one list is taken for the group).
+ *   GROUP_SUM:   g[s,h,b] = ((p_0 + p_1) + p_2) + ... over the group's heads in
+ *                head order, in fp32; selected [S,Hkv,nprobe]
+ *   INDEPENDENT: g = the head's own scores; selected [S,Hq,nprobe]
+ * The list holds the nprobe largest g, ordered by (g descending, id
+ * ascending); equal scores resolve to the lower id.  Scores must be finite.
+ * 0 <= nprobe <= B <= SAAP_MAX_BUCKETS.
+ */
+int32_t saap_select_buckets(const float* scores, int32_t* selected,
+                            int32_t S, int32_t Hq, int32_t Hkv, int32_t B, int32_t nprobe,
+                            int32_t mode, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * sparse_decode_attention -- exact softmax attention over the union of the
+ * selected buckets (Section 4 "Beyond top-k"; Appendix F Algorithms 1 and 2:
+ * partial attention with a running maximum, then a log-sum-exp merge):
+ *   U = all member slots of the selected buckets
+ *   a_n = scale * <q, k_n>,  out = sum_n softmax(a)_n v_n,  lse = log sum_n exp(a_n)
+ *   q [S,Hq,d] dtype (after RoPE); Ksorted,Vsorted [S,Hkv,Ncap,d] dtype
+ *   off [S,Hkv,B+1], len [S,Hkv,B]; selected as written by saap_select_buckets
+ *   out [S,Hq,d] of out_dtype; lse [S,Hq] fp32 or NULL
+ * All G heads of a group are computed together from one read of K and V
+ * (GROUP_SUM).  An empty selection gives out = 0, lse = -inf.
+ * Bucket ids in `selected` must be distinct and inside [0,B).
+ */
+int32_t saap_sparse_decode_attention(const void* q, const void* Ksorted, const void* Vsorted,
+                                     const int32_t* off, const int32_t* len,
+                                     const int32_t* selected, int32_t nprobe, int32_t mode,
+                                     float scale, void* out, int32_t out_dtype, float* lse,
+                                     int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
+                                     int32_t d, int32_t dtype,
+                                     void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * dense_decode_attention -- softmax attention over every key (the full-attention
+ * baseline of Section 6.2), as a uniform split of the keys over workgroups with
+ * the same merge (the Flash-Decoding scheme Section 5 refers to).
+ *   off == NULL: K,V are packed [S,Hkv,N,d].
+ *   off != NULL: K,V are a bucket-sorted cache [S,Hkv,N,d] with N = Ncap; only
+ *                member slots (off[b] .. off[b]+len[b]) are attended; B buckets.
+ */
+int32_t saap_dense_decode_attention(const void* q, const void* K, const void* V,
+                                    const int32_t* off, const int32_t* len, int32_t B,
+                                    float scale, void* out, int32_t out_dtype, float* lse,
+                                    int32_t S, int32_t Hq, int32_t Hkv, int32_t N, int32_t d,
+                                    int32_t dtype,
+                                    void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAAP_H */

@@ -1,0 +1,180 @@
+"""ctypes front end of the CPU oracle (oracle/saap_ref.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg.  The product package never imports this module.
+
+Every function takes and returns numpy arrays on the host.  Floating-point
+inputs are converted to float32 (exact for bf16 and fp32 data); attention
+results come back in float64.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "saap_ref.c")
+_LIB = os.path.join(_HERE, "libsaap_ref.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile saap_ref.c with gcc into oracle/libsaap_ref.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.ref_selectivity.restype = ctypes.c_double
+        _lib.ref_get_threads.restype = ctypes.c_int
+        _lib.ref_append_keys.restype = ctypes.c_int
+    return _lib
+
+
+def _f32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float32))
+
+
+def _i32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def set_threads(n: int) -> None:
+    lib().ref_set_threads(int(n))
+
+
+def get_threads() -> int:
+    return int(lib().ref_get_threads())
+
+
+def assign_keys(x, centroids, bias=None):
+    """x [S,Hkv,N,d], centroids [Hkv,B,d], bias [Hkv,B] or None -> ids int32 [S,Hkv,N]."""
+    x = _f32(x)
+    c = _f32(centroids)
+    S, Hkv, N, d = x.shape
+    B = c.shape[1]
+    assert c.shape == (Hkv, B, d)
+    bias = None if bias is None else _f32(bias)
+    ids = np.empty((S, Hkv, N), dtype=np.int32)
+    lib().ref_assign_keys(_p(x), _p(c), _p(bias), _p(ids), S, Hkv, N, B, d)
+    return ids
+
+
+def build_bucket_index(ids, K, V, B, slack=0):
+    """-> off [S,Hkv,B+1], len [S,Hkv,B], idx [S,Hkv,Ncap], Ks, Vs [S,Hkv,Ncap,d] (float32)."""
+    ids = _i32(ids)
+    K = _f32(K)
+    V = _f32(V)
+    S, Hkv, N, d = K.shape
+    Ncap = N + B * slack
+    off = np.empty((S, Hkv, B + 1), dtype=np.int32)
+    ln = np.empty((S, Hkv, B), dtype=np.int32)
+    idx = np.empty((S, Hkv, Ncap), dtype=np.int32)
+    Ks = np.zeros((S, Hkv, Ncap, d), dtype=np.float32)
+    Vs = np.zeros((S, Hkv, Ncap, d), dtype=np.float32)
+    lib().ref_build_bucket_index(_p(ids), _p(K), _p(V), _p(off), _p(ln), _p(idx), _p(Ks), _p(Vs),
+                                 S, Hkv, N, Ncap, B, d, slack)
+    return off, ln, idx, Ks, Vs
+
+
+def append_keys(x_new, k_new, v_new, pos_new, centroids, bias, off, ln, idx, Ks, Vs):
+    """In-place append on (ln, idx, Ks, Vs); -> (new_ids [S,Hkv], overflow flag)."""
+    x_new = _f32(x_new)
+    k_new = _f32(k_new)
+    v_new = _f32(v_new)
+    c = _f32(centroids)
+    bias = None if bias is None else _f32(bias)
+    pos = None if pos_new is None else _i32(pos_new)
+    S, Hkv, d = x_new.shape
+    B = c.shape[1]
+    Ncap = idx.shape[2]
+    for a, dt in ((off, np.int32), (ln, np.int32), (idx, np.int32), (Ks, np.float32), (Vs, np.float32)):
+        assert a.dtype == dt and a.flags["C_CONTIGUOUS"]
+    new_ids = np.empty((S, Hkv), dtype=np.int32)
+    flag = lib().ref_append_keys(_p(x_new), _p(k_new), _p(v_new), _p(pos), _p(c), _p(bias), _p(off), _p(ln),
+                                 _p(idx), _p(Ks), _p(Vs), _p(new_ids), S, Hkv, Ncap, B, d)
+    return new_ids, int(flag)
+
+
+def classify_queries(xq, W1, b1, W2, b2, Hkv, output_kind=0):
+    """xq [S,Hq,d]; W1 [Hw,hidden,d]; W2 [Hw,B,hidden] -> scores float32 [S,Hq,B]."""
+    xq = _f32(xq)
+    W1 = _f32(W1)
+    W2 = _f32(W2)
+    b1 = None if b1 is None else _f32(b1)
+    b2 = None if b2 is None else _f32(b2)
+    S, Hq, d = xq.shape
+    Hw, hidden, _ = W1.shape
+    B = W2.shape[1]
+    assert W2.shape == (Hw, B, hidden) and Hw in (1, Hkv, Hq)
+    scores = np.empty((S, Hq, B), dtype=np.float32)
+    lib().ref_classify_queries(_p(xq), _p(W1), _p(b1), _p(W2), _p(b2), Hw, _p(scores), S, Hq, Hkv, d,
+                               hidden, B, output_kind)
+    return scores
+
+
+def select_buckets(scores, Hkv, nprobe, mode=0):
+    """scores float32 [S,Hq,B] -> selected int32 [S,Hkv or Hq,nprobe]."""
+    scores = _f32(scores)
+    S, Hq, B = scores.shape
+    lists = Hq if mode == 1 else Hkv
+    sel = np.empty((S, lists, nprobe), dtype=np.int32)
+    lib().ref_select_buckets(_p(scores), _p(sel), S, Hq, Hkv, B, nprobe, mode)
+    return sel
+
+
+def sparse_decode_attention(q, K, V, off, ln, idx, selected, scale, mode=0):
+    """q [S,Hq,d]; K,V position-ordered [S,Hkv,Nrows,d]; -> out float64 [S,Hq,d], lse float64 [S,Hq]."""
+    q = _f32(q)
+    K = _f32(K)
+    V = _f32(V)
+    off = _i32(off)
+    ln = _i32(ln)
+    idx = _i32(idx)
+    selected = _i32(selected)
+    S, Hq, d = q.shape
+    _, Hkv, Nrows, _ = K.shape
+    B = ln.shape[2]
+    Ncap = idx.shape[2]
+    nprobe = selected.shape[2]
+    out = np.empty((S, Hq, d), dtype=np.float64)
+    lse = np.empty((S, Hq), dtype=np.float64)
+    lib().ref_sparse_decode_attention(_p(q), _p(K), _p(V), _p(off), _p(ln), _p(idx), _p(selected), nprobe,
+                                      mode, ctypes.c_float(scale), _p(out), _p(lse), S, Hq, Hkv, Nrows,
+                                      Ncap, B, d)
+    return out, lse
+
+
+def dense_decode_attention(q, K, V, scale):
+    q = _f32(q)
+    K = _f32(K)
+    V = _f32(V)
+    S, Hq, d = q.shape
+    _, Hkv, N, _ = K.shape
+    out = np.empty((S, Hq, d), dtype=np.float64)
+    lse = np.empty((S, Hq), dtype=np.float64)
+    lib().ref_dense_decode_attention(_p(q), _p(K), _p(V), ctypes.c_float(scale), _p(out), _p(lse), S, Hq,
+                                     Hkv, N, d)
+    return out, lse
+
+
+def selectivity(ln, selected, n_keys):
+    """ln [lists,B], selected [lists,nprobe] -> mean fraction of keys visited."""
+    ln = _i32(ln)
+    selected = _i32(selected)
+    lists, B = ln.shape
+    nprobe = selected.shape[1]
+    return float(lib().ref_selectivity(_p(ln), _p(selected), lists, B, nprobe, ctypes.c_long(int(n_keys))))

@@ -1,0 +1,292 @@
+/*
+ * saap_ref.c -- CPU oracle of the SAAP decode hot path (arXiv 2502.08246).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU library is checked against.  It shares no code with the GPU path and the
+ * product never calls it: only the tests, the smoke check and the benchmark's
+ * cpu_baseline leg load it.
+ *
+ * Every function works on host arrays.  Floating-point inputs are `float`
+ * arrays (bf16 inputs are widened to float by the caller, which is exact);
+ * all arithmetic is double precision, written as the definition reads:
+ * no blocking, no partial results, no merge.  Given the bucket ids and the
+ * selected buckets the method computes exactly softmax attention restricted to
+ * a subset of the keys (Section 4, "Beyond top-k"), so the oracle for attention
+ * is that restricted softmax written out; Algorithms 1 and 2 of Appendix F are
+ * one way of evaluating it and are deliberately NOT followed here.
+ *
+ * Parity pins (tests/test_oracle_*.py): numpy brute force on tiny inputs,
+ * closed forms (equal keys -> mean of values, one key -> its value), nprobe = B
+ * equals dense attention, library softmax/matmul/argsort, CSR invariants, the
+ * balanced-selectivity column of the paper's Table "nprobe_selectivity".
+ * The paper prints no numeric attention output, score or index, so beyond
+ * those pins the values are unpinned by the paper itself.
+ *
+ * Build: gcc -O2 -fopenmp -ffp-contract=off -shared -fPIC saap_ref.c -lm
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static int g_threads = 1;
+
+/* Number of host threads the attention loops may use (over (sequence, head)). */
+void ref_set_threads(int n) { g_threads = n > 0 ? n : 1; }
+int ref_get_threads(void) { return g_threads; }
+
+/* Inner product as the definition of saap_assign_keys states it: exact products
+ * (a float times a float is exact in double), summed in index order. */
+static double dot_in_order(const float* a, const float* b, int d) {
+  double t = 0.0;
+  for (int j = 0; j < d; ++j) t += (double)a[j] * (double)b[j];
+  return t;
+}
+
+/* Section 2 (indexing step) / Section 4: each key goes to the bucket of its
+ * nearest centroid.  argmax_b <x, c_b> + bias_b, lowest b on exact ties. */
+void ref_assign_keys(const float* x, const float* cent, const float* bias, int32_t* ids,
+                     int S, int Hkv, int N, int B, int d) {
+  for (int s = 0; s < S; ++s)
+    for (int h = 0; h < Hkv; ++h)
+      for (int n = 0; n < N; ++n) {
+        const float* xr = x + (((size_t)s * Hkv + h) * N + n) * d;
+        int best = 0;
+        double best_t = 0.0;
+        for (int b = 0; b < B; ++b) {
+          double t = dot_in_order(xr, cent + ((size_t)h * B + b) * d, d);
+          if (bias) t += (double)bias[(size_t)h * B + b];
+          if (b == 0 || t > best_t) { best_t = t; best = b; }
+        }
+        ids[((size_t)s * Hkv + h) * N + n] = best;
+      }
+}
+
+/* Appendix F: Off and Idx group the keys of a bucket together; bucket c holds
+ * Idx[Off[c] : Off[c] + len[c]].  Members are listed in ascending position.
+ * `slack` free slots follow every bucket (0 reproduces the paper's tensors).
+ * Slack slots: idx = -1, Ks/Vs rows untouched. */
+void ref_build_bucket_index(const int32_t* ids, const float* K, const float* V,
+                            int32_t* off, int32_t* len, int32_t* idx, float* Ks, float* Vs,
+                            int S, int Hkv, int N, int Ncap, int B, int d, int slack) {
+  for (int u = 0; u < S * Hkv; ++u) {
+    const int32_t* id = ids + (size_t)u * N;
+    int32_t* o = off + (size_t)u * (B + 1);
+    int32_t* l = len + (size_t)u * B;
+    int32_t* ix = idx + (size_t)u * Ncap;
+    for (int b = 0; b < B; ++b) l[b] = 0;
+    for (int n = 0; n < N; ++n)
+      if (id[n] >= 0 && id[n] < B) l[id[n]] += 1;
+    o[0] = 0;
+    for (int b = 0; b < B; ++b) o[b + 1] = o[b] + l[b] + slack;
+    for (int j = 0; j < Ncap; ++j) ix[j] = -1;
+    int32_t* fill = (int32_t*)calloc((size_t)B, sizeof(int32_t));
+    for (int n = 0; n < N; ++n) {
+      int b = id[n];
+      if (b < 0 || b >= B) continue;
+      int j = o[b] + fill[b]++;
+      ix[j] = n;
+      if (K && Ks) memcpy(Ks + ((size_t)u * Ncap + j) * d, K + ((size_t)u * N + n) * d, sizeof(float) * d);
+      if (V && Vs) memcpy(Vs + ((size_t)u * Ncap + j) * d, V + ((size_t)u * N + n) * d, sizeof(float) * d);
+    }
+    free(fill);
+  }
+}
+
+/* One new key per (sequence, KV head): assign as above, store it in the first
+ * free slot of its bucket.  A full bucket leaves everything unchanged for that
+ * key and raises the returned flag. */
+int ref_append_keys(const float* x_new, const float* k_new, const float* v_new,
+                    const int32_t* pos_new, const float* cent, const float* bias,
+                    const int32_t* off, int32_t* len, int32_t* idx, float* Ks, float* Vs,
+                    int32_t* new_ids, int S, int Hkv, int Ncap, int B, int d) {
+  int overflow = 0;
+  for (int s = 0; s < S; ++s)
+    for (int h = 0; h < Hkv; ++h) {
+      int u = s * Hkv + h;
+      int32_t b;
+      ref_assign_keys(x_new + (size_t)u * d, cent + (size_t)h * B * d, bias ? bias + (size_t)h * B : NULL,
+                      &b, 1, 1, 1, B, d);
+      new_ids[u] = b;
+      const int32_t* o = off + (size_t)u * (B + 1);
+      int32_t* l = len + (size_t)u * B;
+      if (o[b] + l[b] >= o[b + 1]) { overflow = 1; continue; }
+      int j = o[b] + l[b];
+      idx[(size_t)u * Ncap + j] = pos_new ? pos_new[s] : -2;
+      memcpy(Ks + ((size_t)u * Ncap + j) * d, k_new + (size_t)u * d, sizeof(float) * d);
+      memcpy(Vs + ((size_t)u * Ncap + j) * d, v_new + (size_t)u * d, sizeof(float) * d);
+      l[b] += 1;
+    }
+  return overflow;
+}
+
+/* Which of the Hw weight sets serves query head hq. */
+static int weight_set(int hq, int Hq, int Hkv, int Hw) {
+  if (Hw == Hq) return hq;
+  if (Hw == Hkv) return hq / (Hq / Hkv);
+  return 0;
+}
+
+/* Section 4 / Section 6.1: f_q is a two-layer perceptron with a ReLU; its
+ * output is a distribution over the buckets (softmax of the logits). */
+void ref_classify_queries(const float* xq, const float* W1, const float* b1, const float* W2,
+                          const float* b2, int Hw, float* scores, int S, int Hq, int Hkv, int d,
+                          int hidden, int B, int output_kind) {
+  double* hbuf = (double*)malloc(sizeof(double) * hidden);
+  double* z = (double*)malloc(sizeof(double) * B);
+  for (int s = 0; s < S; ++s)
+    for (int hq = 0; hq < Hq; ++hq) {
+      int w = weight_set(hq, Hq, Hkv, Hw);
+      const float* x = xq + ((size_t)s * Hq + hq) * d;
+      for (int i = 0; i < hidden; ++i) {
+        const float* wr = W1 + ((size_t)w * hidden + i) * d;
+        double t = 0.0;
+        for (int j = 0; j < d; ++j) t += (double)wr[j] * (double)x[j];
+        if (b1) t += (double)b1[(size_t)w * hidden + i];
+        hbuf[i] = t > 0.0 ? t : 0.0;
+      }
+      double zmax = -INFINITY;
+      for (int b = 0; b < B; ++b) {
+        const float* wr = W2 + ((size_t)w * B + b) * hidden;
+        double t = 0.0;
+        for (int i = 0; i < hidden; ++i) t += (double)wr[i] * hbuf[i];
+        if (b2) t += (double)b2[(size_t)w * B + b];
+        z[b] = t;
+        if (t > zmax) zmax = t;
+      }
+      float* out = scores + ((size_t)s * Hq + hq) * B;
+      if (output_kind == 1) {
+        for (int b = 0; b < B; ++b) out[b] = (float)z[b];
+      } else {
+        double sum = 0.0;
+        for (int b = 0; b < B; ++b) sum += exp(z[b] - zmax);
+        for (int b = 0; b < B; ++b) out[b] = (float)(exp(z[b] - zmax) / sum);
+      }
+    }
+  free(hbuf);
+  free(z);
+}
+
+typedef struct { float g; int32_t id; } scored;
+
+static int by_score_then_id(const void* a, const void* b) {
+  const scored* x = (const scored*)a;
+  const scored* y = (const scored*)b;
+  if (x->g > y->g) return -1;
+  if (x->g < y->g) return 1;
+  return (x->id > y->id) - (x->id < y->id);
+}
+
+/* Section 5 "Batched queries": sum f_q over the heads that share a KV head and
+ * take the nprobe largest entries.  The sum is taken in single precision in
+ * head order (this is the one place where the precision is part of the
+ * definition: it decides integers).  mode 1 ranks each query head alone. */
+void ref_select_buckets(const float* scores, int32_t* selected, int S, int Hq, int Hkv, int B,
+                        int nprobe, int mode) {
+  int G = Hq / Hkv;
+  int lists = mode == 1 ? Hq : Hkv;
+  int heads = mode == 1 ? 1 : G;
+  scored* arr = (scored*)malloc(sizeof(scored) * (size_t)B);
+  for (int s = 0; s < S; ++s)
+    for (int l = 0; l < lists; ++l) {
+      for (int b = 0; b < B; ++b) {
+        volatile float g = scores[((size_t)s * Hq + (size_t)l * heads) * B + b];
+        for (int i = 1; i < heads; ++i) g = g + scores[((size_t)s * Hq + (size_t)l * heads + i) * B + b];
+        arr[b].g = g;
+        arr[b].id = b;
+      }
+      qsort(arr, (size_t)B, sizeof(scored), by_score_then_id);
+      for (int j = 0; j < nprobe; ++j) selected[((size_t)s * lists + l) * nprobe + j] = arr[j].id;
+    }
+  free(arr);
+}
+
+/* Softmax attention of one query over the keys whose positions are listed in
+ * `members` (count entries): a_n = scale <q,k_n>; out = sum softmax(a)_n v_n;
+ * lse = log sum exp a_n.  Empty list: out = 0, lse = -inf. */
+static void attend_list(const float* q, const float* K, const float* V, const int32_t* members,
+                        long count, double scale, int d, double* out, double* lse) {
+  for (int e = 0; e < d; ++e) out[e] = 0.0;
+  if (count == 0) { if (lse) *lse = -INFINITY; return; }
+  double* a = (double*)malloc(sizeof(double) * (size_t)count);
+  double amax = -INFINITY;
+  for (long i = 0; i < count; ++i) {
+    long n = members ? members[i] : i;
+    const float* k = K + (size_t)n * d;
+    double t = 0.0;
+    for (int e = 0; e < d; ++e) t += (double)q[e] * (double)k[e];
+    a[i] = t * scale;
+    if (a[i] > amax) amax = a[i];
+  }
+  double sum = 0.0;
+  for (long i = 0; i < count; ++i) {
+    long n = members ? members[i] : i;
+    double w = exp(a[i] - amax);
+    sum += w;
+    const float* v = V + (size_t)n * d;
+    for (int e = 0; e < d; ++e) out[e] += w * (double)v[e];
+  }
+  for (int e = 0; e < d; ++e) out[e] /= sum;
+  if (lse) *lse = amax + log(sum);
+  free(a);
+}
+
+/* Section 4 "Beyond top-k": every key of the visited buckets enters the softmax.
+ * K,V are in POSITION order [S,Hkv,Nrows,d]; the visited keys are found through
+ * the index, idx[off[b] : off[b]+len[b]], as in Appendix F.  Positions of keys
+ * appended after the build must be < Nrows. */
+void ref_sparse_decode_attention(const float* q, const float* K, const float* V,
+                                 const int32_t* off, const int32_t* len, const int32_t* idx,
+                                 const int32_t* selected, int nprobe, int mode, float scale,
+                                 double* out, double* lse, int S, int Hq, int Hkv, int Nrows,
+                                 int Ncap, int B, int d) {
+  int G = Hq / Hkv;
+  int units = S * Hq;
+#pragma omp parallel for num_threads(g_threads) schedule(dynamic)
+  for (int t = 0; t < units; ++t) {
+    int s = t / Hq, hq = t % Hq, h = hq / G;
+    size_t u = (size_t)s * Hkv + h;
+    const int32_t* sel = mode == 1 ? selected + (size_t)t * nprobe : selected + u * nprobe;
+    long count = 0;
+    for (int j = 0; j < nprobe; ++j) count += len[u * B + sel[j]];
+    int32_t* members = (int32_t*)malloc(sizeof(int32_t) * (size_t)(count > 0 ? count : 1));
+    long c = 0;
+    for (int j = 0; j < nprobe; ++j) {
+      int b = sel[j];
+      for (int r = 0; r < len[u * B + b]; ++r) members[c++] = idx[u * Ncap + off[u * (B + 1) + b] + r];
+    }
+    attend_list(q + (size_t)t * d, K + u * Nrows * d, V + u * Nrows * d, members, count,
+                (double)scale, d, out + (size_t)t * d, lse ? lse + t : NULL);
+    free(members);
+  }
+}
+
+/* Full softmax attention over the N keys of the head (Section 6.2 baseline). */
+void ref_dense_decode_attention(const float* q, const float* K, const float* V, float scale,
+                                double* out, double* lse, int S, int Hq, int Hkv, int N, int d) {
+  int G = Hq / Hkv;
+  int units = S * Hq;
+#pragma omp parallel for num_threads(g_threads) schedule(dynamic)
+  for (int t = 0; t < units; ++t) {
+    int s = t / Hq, hq = t % Hq, h = hq / G;
+    size_t u = (size_t)s * Hkv + h;
+    attend_list(q + (size_t)t * d, K + u * N * d, V + u * N * d, NULL, N, (double)scale, d,
+                out + (size_t)t * d, lse ? lse + t : NULL);
+  }
+}
+
+/* Selectivity (Section 6.1): the fraction of keys that take part in the
+ * computation, averaged over the lists (heads).  n_keys = keys per head. */
+double ref_selectivity(const int32_t* len, const int32_t* selected, int lists, int B, int nprobe,
+                       long n_keys) {
+  double acc = 0.0;
+  for (int l = 0; l < lists; ++l) {
+    long c = 0;
+    for (int j = 0; j < nprobe; ++j) c += len[(size_t)l * B + selected[(size_t)l * nprobe + j]];
+    acc += (double)c / (double)n_keys;
+  }
+  return acc / lists;
+}
