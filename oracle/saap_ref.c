@@ -34,7 +34,7 @@
 
 static int g_threads = 1;
 
-/* Number of host threads the attention loops may use (over (sequence, head)). */
+/* Number of host threads the loops over independent rows / (sequence, head) pairs may use. */
 void ref_set_threads(int n) { g_threads = n > 0 ? n : 1; }
 int ref_get_threads(void) { return g_threads; }
 
@@ -52,6 +52,7 @@ void ref_assign_keys(const float* x, const float* cent, const float* bias, int32
                      int S, int Hkv, int N, int B, int d) {
   for (int s = 0; s < S; ++s)
     for (int h = 0; h < Hkv; ++h)
+#pragma omp parallel for num_threads(g_threads) schedule(static)
       for (int n = 0; n < N; ++n) {
         const float* xr = x + (((size_t)s * Hkv + h) * N + n) * d;
         int best = 0;

@@ -1,0 +1,12 @@
+"""MI355X-native SAAP decode hot path (arXiv 2502.08246): thin Python binding over libsaap.so.
+
+The package holds the HIP sources (csrc/), their build script and a ctypes binding whose
+functions carry the names of the C entry points.  Every step runs in the HIP kernels; torch
+is used for device memory and streams only.  There is no CPU fallback: calling an operation
+without the built library or without a GPU raises.
+"""
+from .binding import (  # noqa: F401
+    BF16, F32, GROUP_SUM, INDEPENDENT, LOGITS, PROBS, SaapError,
+    append_keys, assign_keys, build_bucket_index, classify_queries, dense_decode_attention,
+    library_path, load_library, select_buckets, sparse_decode_attention, workspace, workspace_bytes,
+)

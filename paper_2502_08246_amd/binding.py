@@ -1,0 +1,247 @@
+"""ctypes binding of libsaap.so (declared in include/saap.h).
+
+Argument marshalling only: shapes are read off the tensors, pointers and the current HIP
+stream are handed to the C entry points, status codes become exceptions.  Outputs are
+allocated with torch (device memory) unless the caller passes them in.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+F32, BF16 = 0, 1
+GROUP_SUM, INDEPENDENT = 0, 1
+PROBS, LOGITS = 0, 1
+OP_ASSIGN_KEYS, OP_BUILD_BUCKET_INDEX, OP_CLASSIFY_QUERIES, OP_SELECT_BUCKETS = 0, 1, 2, 3
+OP_SPARSE_DECODE_ATTENTION, OP_DENSE_DECODE_ATTENTION, OP_APPEND_KEYS = 4, 5, 6
+WS_HEADER_BYTES = 65536
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsaap.so")
+_lib = None
+
+EXPORTS = (
+    "saap_workspace_bytes", "saap_workspace_reset", "saap_status_string", "saap_device_compute_units",
+    "saap_assign_keys", "saap_build_bucket_index", "saap_append_keys", "saap_classify_queries",
+    "saap_select_buckets", "saap_sparse_decode_attention", "saap_dense_decode_attention",
+)
+
+
+class SaapError(RuntimeError):
+    def __init__(self, call: str, status: int):
+        self.status = status
+        super().__init__(f"{call} failed: {status_string(status)} ({status})")
+
+
+class _Shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("S", "Hq", "Hkv", "N", "B", "nprobe", "d", "hidden", "dtype", "mode")]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the built library; build it first (python -m paper_2502_08246_amd.build) if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            from . import build as _build
+            _build.build()
+        lib = ctypes.CDLL(_LIB_PATH)
+        lib.saap_workspace_bytes.restype = ctypes.c_size_t
+        lib.saap_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.POINTER(_Shape)]
+        lib.saap_status_string.restype = ctypes.c_char_p
+        lib.saap_status_string.argtypes = [ctypes.c_int32]
+        for name in EXPORTS[4:] + ("saap_workspace_reset", "saap_device_compute_units"):
+            getattr(lib, name).restype = ctypes.c_int32
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load_library().saap_status_string(int(status)).decode()
+
+
+def _check(call: str, status: int) -> None:
+    if status != 0:
+        raise SaapError(call, status)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t):
+    if t is None:
+        return ctypes.c_void_p(0)
+    if not t.is_cuda:
+        raise ValueError("SAAP tensors must live in GPU memory; there is no CPU path")
+    if not t.is_contiguous():
+        raise ValueError("SAAP tensors must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _i32(v):
+    return ctypes.c_int32(int(v))
+
+
+def workspace_bytes(op: int, **shape) -> int:
+    sh = _Shape(**{k: int(v) for k, v in shape.items()})
+    return int(load_library().saap_workspace_bytes(op, ctypes.byref(sh)))
+
+
+class _Workspace:
+    """Device scratch handed to the calls.  Zero-filled once at allocation, which is what the
+    header of arrival counters needs; grown (and zero-filled again) on demand."""
+
+    def __init__(self):
+        self.buf = None
+
+    def get(self, nbytes: int, device) -> torch.Tensor:
+        if self.buf is None or self.buf.numel() < nbytes or self.buf.device != torch.device(device):
+            self.buf = torch.zeros(max(nbytes, WS_HEADER_BYTES), dtype=torch.uint8, device=device)
+        return self.buf
+
+
+_default_ws = _Workspace()
+
+
+def workspace(nbytes: int, device) -> torch.Tensor:
+    """The binding's shared workspace buffer, at least nbytes long."""
+    return _default_ws.get(nbytes, device)
+
+
+def _ws(op, device, ws, **shape):
+    need = workspace_bytes(op, **shape)
+    if need == 0:
+        raise SaapError("saap_workspace_bytes", -1)
+    if ws is None:
+        ws = workspace(need, device)
+    return ws, ctypes.c_size_t(ws.numel())
+
+
+def assign_keys(x, centroids, bias=None, out=None, ws=None):
+    """x [S,Hkv,N,d], centroids [Hkv,B,d], bias [Hkv,B] fp32 or None -> bucket_ids int32 [S,Hkv,N]."""
+    S, Hkv, N, d = x.shape
+    B = centroids.shape[1]
+    if centroids.shape != (Hkv, B, d) or centroids.dtype != x.dtype:
+        raise ValueError("centroids must be [Hkv,B,d] in the dtype of x")
+    ids = out if out is not None else torch.empty(S, Hkv, N, dtype=torch.int32, device=x.device)
+    ws, wsb = _ws(OP_ASSIGN_KEYS, x.device, ws, S=S, Hkv=Hkv, N=N, B=B, d=d)
+    st = load_library().saap_assign_keys(_ptr(x), _ptr(centroids), _ptr(bias), _ptr(ids), _i32(S), _i32(Hkv),
+                                         _i32(N), _i32(B), _i32(d), _i32(_dtype_code(x)), _ptr(ws), wsb, _stream())
+    _check("saap_assign_keys", st)
+    return ids
+
+
+def build_bucket_index(bucket_ids, K, V, B, slack=0, ws=None):
+    """-> off [S,Hkv,B+1], len [S,Hkv,B], idx [S,Hkv,Ncap] (int32), Ksorted, Vsorted [S,Hkv,Ncap,d]."""
+    S, Hkv, N, d = K.shape
+    Ncap = N + B * slack
+    dev = K.device
+    off = torch.empty(S, Hkv, B + 1, dtype=torch.int32, device=dev)
+    ln = torch.empty(S, Hkv, B, dtype=torch.int32, device=dev)
+    idx = torch.empty(S, Hkv, Ncap, dtype=torch.int32, device=dev)
+    alloc = torch.zeros if slack > 0 else torch.empty
+    Ks = alloc(S, Hkv, Ncap, d, dtype=K.dtype, device=dev)
+    Vs = alloc(S, Hkv, Ncap, d, dtype=K.dtype, device=dev)
+    ws, wsb = _ws(OP_BUILD_BUCKET_INDEX, dev, ws, S=S, Hkv=Hkv, N=N, B=B)
+    st = load_library().saap_build_bucket_index(_ptr(bucket_ids), _ptr(K), _ptr(V), _ptr(off), _ptr(ln), _ptr(idx),
+                                                _ptr(Ks), _ptr(Vs), _i32(S), _i32(Hkv), _i32(N), _i32(Ncap), _i32(B),
+                                                _i32(d), _i32(_dtype_code(K)), _i32(slack), _ptr(ws), wsb, _stream())
+    _check("saap_build_bucket_index", st)
+    return off, ln, idx, Ks, Vs
+
+
+def append_keys(x_new, k_new, v_new, pos_new, centroids, bias, off, ln, idx, Ks, Vs, overflow_flag=None):
+    """In-place append of one key per (sequence, KV head). -> (new_bucket_ids [S,Hkv], overflow_flag [1])."""
+    S, Hkv, d = x_new.shape
+    B = centroids.shape[1]
+    Ncap = idx.shape[2]
+    dev = x_new.device
+    new_ids = torch.empty(S, Hkv, dtype=torch.int32, device=dev)
+    if overflow_flag is None:
+        overflow_flag = torch.zeros(4, dtype=torch.int32, device=dev)
+    st = load_library().saap_append_keys(_ptr(x_new), _ptr(k_new), _ptr(v_new), _ptr(pos_new), _ptr(centroids),
+                                         _ptr(bias), _ptr(off), _ptr(ln), _ptr(idx), _ptr(Ks), _ptr(Vs),
+                                         _ptr(new_ids), _ptr(overflow_flag), _i32(S), _i32(Hkv), _i32(Ncap), _i32(B),
+                                         _i32(d), _i32(_dtype_code(x_new)), _stream())
+    _check("saap_append_keys", st)
+    return new_ids, overflow_flag
+
+
+def classify_queries(xq, W1, b1, W2, b2, Hkv, output_kind=PROBS, out=None, ws=None):
+    """xq [S,Hq,d]; W1 [Hw,hidden,d]; W2 [Hw,B,hidden]; b1,b2 fp32 or None -> scores fp32 [S,Hq,B]."""
+    S, Hq, d = xq.shape
+    Hw, hidden, _ = W1.shape
+    B = W2.shape[1]
+    if W2.shape != (Hw, B, hidden) or W1.dtype != xq.dtype or W2.dtype != xq.dtype:
+        raise ValueError("W1 [Hw,hidden,d] and W2 [Hw,B,hidden] must match xq's dtype")
+    scores = out if out is not None else torch.empty(S, Hq, B, dtype=torch.float32, device=xq.device)
+    ws, wsb = _ws(OP_CLASSIFY_QUERIES, xq.device, ws, S=S, Hq=Hq, hidden=hidden)
+    st = load_library().saap_classify_queries(_ptr(xq), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _i32(Hw),
+                                              _ptr(scores), _i32(S), _i32(Hq), _i32(Hkv), _i32(d), _i32(hidden),
+                                              _i32(B), _i32(_dtype_code(xq)), _i32(output_kind), _ptr(ws), wsb,
+                                              _stream())
+    _check("saap_classify_queries", st)
+    return scores
+
+
+def select_buckets(scores, Hkv, nprobe, mode=GROUP_SUM, out=None, ws=None):
+    """scores fp32 [S,Hq,B] -> selected int32 [S,Hkv,nprobe] (GROUP_SUM) or [S,Hq,nprobe] (INDEPENDENT)."""
+    S, Hq, B = scores.shape
+    lists = Hq if mode == INDEPENDENT else Hkv
+    sel = out if out is not None else torch.empty(S, lists, nprobe, dtype=torch.int32, device=scores.device)
+    ws, wsb = _ws(OP_SELECT_BUCKETS, scores.device, ws)
+    st = load_library().saap_select_buckets(_ptr(scores), _ptr(sel), _i32(S), _i32(Hq), _i32(Hkv), _i32(B),
+                                            _i32(nprobe), _i32(mode), _ptr(ws), wsb, _stream())
+    _check("saap_select_buckets", st)
+    return sel
+
+
+def sparse_decode_attention(q, Ks, Vs, off, ln, selected, scale, mode=GROUP_SUM, out_dtype=torch.float32,
+                            out=None, lse=None, ws=None):
+    """q [S,Hq,d]; Ks,Vs [S,Hkv,Ncap,d]; off,ln from build_bucket_index; selected from select_buckets
+    -> out [S,Hq,d] (out_dtype), lse fp32 [S,Hq]."""
+    S, Hq, d = q.shape
+    _, Hkv, Ncap, _ = Ks.shape
+    B = ln.shape[2]
+    nprobe = selected.shape[2]
+    dev = q.device
+    out = out if out is not None else torch.empty(S, Hq, d, dtype=out_dtype, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Hq, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_SPARSE_DECODE_ATTENTION, dev, ws, S=S, Hq=Hq, Hkv=Hkv, mode=mode)
+    st = load_library().saap_sparse_decode_attention(
+        _ptr(q), _ptr(Ks), _ptr(Vs), _ptr(off), _ptr(ln), _ptr(selected) if nprobe > 0 else ctypes.c_void_p(0),
+        _i32(nprobe), _i32(mode), ctypes.c_float(scale), _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S),
+        _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _ptr(ws), wsb, _stream())
+    _check("saap_sparse_decode_attention", st)
+    return out, lse
+
+
+def dense_decode_attention(q, K, V, scale, off=None, ln=None, out_dtype=torch.float32, out=None, lse=None, ws=None):
+    """q [S,Hq,d]; K,V [S,Hkv,N,d] (packed, or a bucket-sorted cache with off/ln) -> out, lse."""
+    S, Hq, d = q.shape
+    _, Hkv, N, _ = K.shape
+    B = ln.shape[2] if ln is not None else 0
+    dev = q.device
+    out = out if out is not None else torch.empty(S, Hq, d, dtype=out_dtype, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Hq, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_DENSE_DECODE_ATTENTION, dev, ws, S=S, Hq=Hq, Hkv=Hkv)
+    st = load_library().saap_dense_decode_attention(
+        _ptr(q), _ptr(K), _ptr(V), _ptr(off), _ptr(ln), _i32(B), ctypes.c_float(scale), _ptr(out),
+        _i32(_dtype_code(out)), _ptr(lse), _i32(S), _i32(Hq), _i32(Hkv), _i32(N), _i32(d), _i32(_dtype_code(q)),
+        _ptr(ws), wsb, _stream())
+    _check("saap_dense_decode_attention", st)
+    return out, lse

@@ -1,0 +1,309 @@
+// assign_keys: nearest-centroid assignment of keys at prefill (Section 2, indexing step, and
+// Section 4 of arXiv 2502.08246): bucket = argmax_b <x, c_b> + bias_b.
+//
+// The result is DEFINED on double-precision scores (in-order sum of exact products, lowest id
+// on ties).  Two kernels produce exactly that:
+//   * mfma kernel (bf16 inputs): scores on the matrix cores, fp32 accumulation.  A workgroup
+//     holds 256 keys in registers as the B operand of v_mfma_f32_32x32x16_bf16 and streams the
+//     centroids through LDS in tiles of 32 as the A operand, so one lane owns one key and its 16
+//     accumulator registers are 16 different centroids.  Per key the lane tracks the best and
+//     second-best score; the low 4 bits of a score carry the accumulator register number, so
+//     the running argmax costs three vector instructions per score.
+//   * exact kernel: a key whose best two fp32 scores are closer than the accumulation error
+//     bound is re-scored against all centroids in double precision (fp64 vector rate equals the
+//     fp32 rate on this chip).  fp32 inputs use the exact kernel for every key.
+// No score matrix is ever written to memory.
+#include "common.h"
+
+namespace saap {
+namespace {
+
+constexpr int kRowsPerWg = 256;   // keys per workgroup of the mfma kernel (4 waves x 64)
+constexpr int kCentTile = 32;     // centroids per LDS tile
+constexpr int kPitch = 136;       // bf16 elements per LDS row (272 bytes: conflict-free b128 reads)
+
+template <typename T> __device__ __forceinline__ double to_f64(T v);
+template <> __device__ __forceinline__ double to_f64<float>(float v) { return (double)v; }
+template <> __device__ __forceinline__ double to_f64<bf16_t>(bf16_t v) {
+  return (double)__uint_as_float((uint32_t)v << 16);
+}
+
+// max_b |c_b| per KV head (fp32, rounded up a little by the caller's tolerance factor).
+__global__ void __launch_bounds__(256)
+cent_norm_kernel(const bf16_t* __restrict__ cent, float* __restrict__ cmax, int B) {
+  __shared__ float s_m[256];
+  const int h = blockIdx.x;
+  float mx = 0.f;
+  for (int b = threadIdx.x; b < B; b += blockDim.x) {
+    const bf16_t* c = cent + ((size_t)h * B + b) * kD;
+    float s = 0.f;
+    for (int j = 0; j < kD; ++j) {
+      const float v = __uint_as_float((uint32_t)c[j] << 16);
+      s = fmaf(v, v, s);
+    }
+    mx = fmaxf(mx, s);
+  }
+  s_m[threadIdx.x] = mx;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (threadIdx.x < s) s_m[threadIdx.x] = fmaxf(s_m[threadIdx.x], s_m[threadIdx.x + s]);
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) cmax[h] = sqrtf(s_m[0]) * 1.0001f;
+}
+
+template <bool HAS_BIAS>
+__global__ void __launch_bounds__(256)
+assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent, const float* __restrict__ bias,
+                   const float* __restrict__ cmax, int32_t* __restrict__ ids, int32_t* __restrict__ flagged,
+                   unsigned* __restrict__ n_flagged, int Hkv, int N, int B, float tol) {
+  __shared__ __align__(16) bf16_t s_c[2][kCentTile * kPitch];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int unit = blockIdx.y, h = unit % Hkv;
+  const int col = lane & 31, half = lane >> 5;
+  const bf16_t* cu = cent + (size_t)h * B * kD;
+
+  // B operand: two tiles of 32 keys per wave; lane holds features 16*step + 8*half .. +7 of key `col`.
+  const int row_base = blockIdx.x * kRowsPerWg + wave * 64;
+  bf16x8_t xb[2][8];
+  float xnorm2[2];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) {
+    const int r = min(row_base + rt * 32 + col, N - 1);
+    const bf16_t* xr = x + ((size_t)unit * N + r) * kD + half * 8;
+    float s = 0.f;
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(xr + st * 16);
+      xb[rt][st] = __builtin_bit_cast(bf16x8_t, raw);
+      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        s = fmaf(bf16_lo(w[i]), bf16_lo(w[i]), s);
+        s = fmaf(bf16_hi(w[i]), bf16_hi(w[i]), s);
+      }
+    }
+    s += __shfl_xor(s, 32);
+    xnorm2[rt] = s;
+  }
+
+  // centroid tile loader: 32 rows x 16 pieces of 16 bytes = 512 pieces, two per thread
+  const int n_tiles = (B + kCentTile - 1) / kCentTile;
+  uint4 stage[2];
+  auto fetch = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int piece = tid + i * 256, r = piece >> 4, pc = piece & 15;
+      int b = t * kCentTile + r;
+      if (b >= B) b = 0;   // padding repeats centroid 0: it can tie with bucket 0 but never beat it
+      stage[i] = *reinterpret_cast<const uint4*>(cu + (size_t)b * kD + pc * 8);
+    }
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int piece = tid + i * 256, r = piece >> 4, pc = piece & 15;
+      *reinterpret_cast<uint4*>(&s_c[buf][r * kPitch + pc * 8]) = stage[i];
+    }
+  };
+  fetch(0);
+  stash(0);
+  __syncthreads();
+
+  const uint32_t keep = 0xFFFFFFF0u;
+  float best[2], second[2];
+  int best_tile[2];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) {
+    best[rt] = -INFINITY;
+    second[rt] = -INFINITY;
+    best_tile[rt] = 0;
+  }
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const int buf = t & 1;
+    if (t + 1 < n_tiles) fetch(t + 1);
+    // 32x32 accumulator as 16 floats; the builtin wants one 16-wide vector
+    typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+    f32x16_t c0 = {0}, c1 = {0};
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(&s_c[buf][col * kPitch + st * 16 + half * 8]);
+      const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw);
+      c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[0][st], c0, 0, 0, 0);
+      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[1][st], c1, 0, 0, 0);
+    }
+    // accumulator register r of this lane is centroid 8*(r/4) + 4*half + r%4 of the tile
+    const float old0 = best[0], old1 = best[1];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float s0 = c0[r], s1 = c1[r];
+      if (HAS_BIAS) {
+        int b = t * kCentTile + 8 * (r / 4) + 4 * half + (r % 4);
+        const float bv = bias[(size_t)h * B + (b < B ? b : 0)];
+        s0 += bv;
+        s1 += bv;
+      }
+      const float p0 = __uint_as_float((__float_as_uint(s0) & keep) | (uint32_t)r);
+      const float p1 = __uint_as_float((__float_as_uint(s1) & keep) | (uint32_t)r);
+      second[0] = __builtin_amdgcn_fmed3f(best[0], second[0], p0);
+      best[0] = fmaxf(best[0], p0);
+      second[1] = __builtin_amdgcn_fmed3f(best[1], second[1], p1);
+      best[1] = fmaxf(best[1], p1);
+    }
+    best_tile[0] = best[0] != old0 ? t : best_tile[0];
+    best_tile[1] = best[1] != old1 ? t : best_tile[1];
+    if (t + 1 < n_tiles) stash(buf ^ 1);
+    __syncthreads();
+  }
+
+  // lanes l and l+32 own the same key: merge their candidates, lower id on equal packed scores
+  const float tol_c = tol * cmax[h];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) {
+    const int r = (int)(__float_as_uint(best[rt]) & 15u);
+    int id = best_tile[rt] * kCentTile + 8 * (r / 4) + 4 * half + (r % 4);
+    const float ob = __shfl_xor(best[rt], 32);
+    const float os = __shfl_xor(second[rt], 32);
+    const int oid = __shfl_xor(id, 32);
+    float b1 = best[rt], s1 = second[rt];
+    float nb, ns;
+    if (ob > b1 || (ob == b1 && oid < id)) {
+      nb = ob;
+      ns = fmaxf(b1, os);
+      id = oid;
+    } else {
+      nb = b1;
+      ns = fmaxf(ob, s1);
+    }
+    const int row = row_base + rt * 32 + col;
+    if (half == 0 && row < N) {
+      const size_t g = (size_t)unit * N + row;
+      ids[g] = id;
+      // error bound of the fp32 accumulation plus the 4 mantissa bits used for the register tag
+      const float thr = tol_c * sqrtf(xnorm2[rt]) + 5e-6f * fabsf(nb);
+      if (!(nb - ns > thr) || id >= B) {
+        const unsigned slot = atomicAdd(n_flagged, 1u);
+        flagged[slot] = (int32_t)g;   // global row index fits: checked on the host
+      }
+    }
+  }
+}
+
+// Exact scoring in double precision.  One workgroup per listed row (grid-stride over the list);
+// `rows` null = every row in [0, n_all).
+template <typename T>
+__global__ void __launch_bounds__(256)
+assign_exact_kernel(const T* __restrict__ x, const T* __restrict__ cent, const float* __restrict__ bias,
+                    int32_t* __restrict__ ids, const int32_t* __restrict__ rows,
+                    const unsigned* __restrict__ n_rows_dev, long long n_all, int Hkv, int N, int B) {
+  __shared__ double s_x[kD];
+  __shared__ double s_best[256];
+  __shared__ int s_id[256];
+  const int tid = threadIdx.x;
+  const long long n_rows = rows ? (long long)*n_rows_dev : n_all;
+  for (long long i = blockIdx.x; i < n_rows; i += gridDim.x) {
+    const long long g = rows ? (long long)rows[i] : i;
+    const int h = (int)((g / N) % Hkv);
+    __syncthreads();
+    if (tid < kD) s_x[tid] = to_f64<T>(x[(size_t)g * kD + tid]);
+    __syncthreads();
+    double best = 0.0;
+    int best_id = -1;
+    for (int b = tid; b < B; b += blockDim.x) {
+      const T* c = cent + ((size_t)h * B + b) * kD;
+      double t = 0.0;
+      if (sizeof(T) == 2) {
+        for (int j = 0; j < kD; j += 8) {
+          const uint4 raw = *reinterpret_cast<const uint4*>(c + j);
+          const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            t = fma(s_x[j + 2 * k], (double)bf16_lo(w[k]), t);
+            t = fma(s_x[j + 2 * k + 1], (double)bf16_hi(w[k]), t);
+          }
+        }
+      } else {
+        for (int j = 0; j < kD; ++j) t = fma(s_x[j], to_f64<T>(c[j]), t);
+      }
+      if (bias) t += (double)bias[(size_t)h * B + b];
+      if (best_id < 0 || t > best) {
+        best = t;
+        best_id = b;
+      }
+    }
+    s_best[tid] = best;
+    s_id[tid] = best_id;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+      if (tid < s) {
+        const int oid = s_id[tid + s], mid = s_id[tid];
+        const double ob = s_best[tid + s];
+        if (oid >= 0 && (mid < 0 || ob > s_best[tid] || (ob == s_best[tid] && oid < mid))) {
+          s_best[tid] = ob;
+          s_id[tid] = oid;
+        }
+      }
+      __syncthreads();
+    }
+    if (tid == 0) ids[g] = s_id[0];
+  }
+}
+
+__global__ void clear_counter_kernel(unsigned* c) { *c = 0u; }
+
+}  // namespace
+
+// header | cmax[<=4096 floats, 16 KiB] | flagged row list [rows] int32
+size_t assign_workspace_bytes(long long rows) {
+  return (size_t)SAAP_WS_HEADER_BYTES + 16384 + (size_t)rows * sizeof(int32_t);
+}
+
+}  // namespace saap
+
+using namespace saap;
+
+extern "C" int32_t saap_assign_keys(const void* x, const void* centroids, const float* bias,
+                                    int32_t* bucket_ids, int32_t S, int32_t Hkv, int32_t N, int32_t B,
+                                    int32_t d, int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
+  if (!x || !centroids || !bucket_ids || !ws) return SAAP_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(centroids) || !aligned16(bucket_ids) || !aligned16(ws)) return SAAP_INVALID_ARG;
+  if (S <= 0 || Hkv <= 0 || N <= 0 || B <= 0) return SAAP_INVALID_ARG;
+  if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
+  if (d != kD) return SAAP_UNSUPPORTED;
+  const long long units = (long long)S * Hkv;
+  const long long rows = units * N;
+  if (rows > 0x7fffffffLL || units > 65535 || Hkv > 4096) return SAAP_UNSUPPORTED;
+  if (ws_bytes < assign_workspace_bytes(rows)) return SAAP_WORKSPACE_TOO_SMALL;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const int cus = device_cus();
+
+  if (dtype == SAAP_F32) {
+    const long long grid = rows < (long long)cus * 8 ? rows : (long long)cus * 8;
+    hipLaunchKernelGGL(assign_exact_kernel<float>, dim3((unsigned)grid), dim3(256), 0, hs,
+                       static_cast<const float*>(x), static_cast<const float*>(centroids), bias, bucket_ids,
+                       (const int32_t*)nullptr, (const unsigned*)nullptr, rows, Hkv, N, B);
+    return launch_status();
+  }
+
+  unsigned* n_flagged = reinterpret_cast<unsigned*>(ws);   // header word 0, zero on entry
+  float* cmax = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
+  int32_t* flagged = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES + 16384);
+  const bf16_t* xb = static_cast<const bf16_t*>(x);
+  const bf16_t* cb = static_cast<const bf16_t*>(centroids);
+  // fp32 accumulation of 128 exact products: |error| <= 128 * 2^-24 * |x| |c| per score; two scores
+  // are compared, and a factor 4 of head-room covers the matrix core's internal summation order.
+  const float tol = 8.0f * 128.0f * 5.9604645e-8f;
+  hipLaunchKernelGGL(cent_norm_kernel, dim3((unsigned)Hkv), dim3(256), 0, hs, cb, cmax, B);
+  const dim3 grid((unsigned)((N + kRowsPerWg - 1) / kRowsPerWg), (unsigned)units);
+  if (bias)
+    hipLaunchKernelGGL(assign_mfma_kernel<true>, grid, dim3(256), 0, hs, xb, cb, bias, cmax, bucket_ids, flagged,
+                       n_flagged, Hkv, N, B, tol);
+  else
+    hipLaunchKernelGGL(assign_mfma_kernel<false>, grid, dim3(256), 0, hs, xb, cb, bias, cmax, bucket_ids,
+                       flagged, n_flagged, Hkv, N, B, tol);
+  hipLaunchKernelGGL(assign_exact_kernel<bf16_t>, dim3((unsigned)(cus * 8)), dim3(256), 0, hs, xb, cb, bias,
+                     bucket_ids, flagged, n_flagged, rows, Hkv, N, B);
+  hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, hs, n_flagged);
+  return launch_status();
+}

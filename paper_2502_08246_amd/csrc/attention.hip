@@ -1,0 +1,451 @@
+// Decode attention kernels: sparse attention over the visited buckets of a bucket-sorted
+// KV cache, and dense attention over all keys (Section 4 "Beyond top-k", Section 5 "On GPU",
+// Appendix F Algorithms 1 and 2 of arXiv 2502.08246).
+//
+// Design for gfx950 (not the paper's one-block-per-bucket scheme):
+//   * A "unit" is one (sequence, KV head) with its G query heads.  The visited buckets of
+//     a unit are contiguous runs of the sorted cache; concatenated they form a virtual key
+//     range [0,T).  The unit's P workgroups take equal slices of that range, so the load
+//     is balanced whatever the bucket sizes are.
+//   * Inside a wavefront, 16 lanes read one 256-byte bf16 row with one 16-byte load each
+//     (four rows per wave instruction, whole cache lines).  Each 16-lane group is a "key
+//     processor" with its own running maximum, sum and output accumulator for all G heads
+//     (Algorithm 1), so K and V are read once for the whole group of heads.
+//   * Dot products are reduced over the 16 lanes with DPP lane exchanges; the four key
+//     processors of a wave, the waves of a workgroup (through LDS) and the P workgroups of a
+//     unit (through the workspace) are combined with the log-sum-exp merge of Algorithm 2.
+//     The last workgroup of a unit to arrive (atomic counter) performs the final merge, so
+//     partial attention and merge are one launch.
+#include "common.h"
+
+namespace saap {
+namespace {
+
+constexpr int kKeysPerBatch = 4;   // keys a key processor has in flight per iteration
+constexpr int kMaxP = 128;         // workgroups per unit (workspace is sized for this)
+
+struct AttnParams {
+  const void* q;          // [S,Hq,d]
+  const void* K;          // [kv units, rows, d]
+  const void* V;
+  const int32_t* off;     // [kv units, B+1] or null
+  const int32_t* len;     // [kv units, B]   or null
+  const int32_t* selected;  // [units, nseg] or null (identity list)
+  void* out;              // [S,Hq,d]
+  float* lse;             // [S,Hq] or null
+  float* part_o;          // [units, P, G, d]
+  float* part_ml;         // [units, P, G, 2]
+  unsigned* counters;     // [units], zero on entry and on exit
+  long long rows;         // rows per kv unit
+  int nseg;               // segments (visited buckets) per unit; list mode only
+  int B;
+  int n_units;
+  int P;
+  int Hq, Hkv;
+  int independent;        // unit = (sequence, query head) instead of (sequence, KV head)
+  int out_bf16;
+  int n_dense;            // keys per unit in dense mode
+  float scale_log2;       // scale * log2(e)
+};
+
+__device__ __forceinline__ int wave_incl_scan(int x, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int y = __shfl_up(x, o);
+    if (lane >= o) x += y;
+  }
+  return x;
+}
+
+// Merge `n` partial results (m_i, l_i, o_i[e]) for one (head, feature) pair:
+// M = max m_i; o = sum 2^(m_i-M) o_i; l = sum 2^(m_i-M) l_i   (Algorithm 2, symmetric form).
+template <typename FM, typename FL, typename FO>
+__device__ __forceinline__ void lse_merge(int n, FM get_m, FL get_l, FO get_o, float& M, float& l, float& o) {
+  M = kNegBig;
+  for (int i = 0; i < n; ++i) M = fmaxf(M, get_m(i));
+  l = 0.f;
+  o = 0.f;
+  for (int i = 0; i < n; ++i) {
+    float w = fast_exp2(get_m(i) - M);
+    l = fmaf(w, get_l(i), l);
+    o = fmaf(w, get_o(i), o);
+  }
+}
+
+__device__ __forceinline__ void store_out(const AttnParams& p, int qrow, int e, float M, float l, float o) {
+  float r = l > 0.f ? o / l : 0.f;
+  if (p.out_bf16) reinterpret_cast<bf16_t*>(p.out)[(size_t)qrow * kD + e] = (bf16_t)f32_to_bf16_bits(r);
+  else reinterpret_cast<float*>(p.out)[(size_t)qrow * kD + e] = r;
+  if (e == 0 && p.lse) p.lse[qrow] = l > 0.f ? (M + __log2f(l)) * kLn2 : -INFINITY;
+}
+
+template <typename T, int G, bool LIST>
+__global__ void __launch_bounds__(512) attn_kernel(AttnParams p) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int s_wsum[16];
+  __shared__ int s_last;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+  const int sub = lane & 15, grp = lane >> 4;
+  const int unit = blockIdx.x % p.n_units;
+  const int wg = blockIdx.x / p.n_units;
+
+  // unit -> kv unit and first query row
+  int kvu, qrow0;
+  if (p.independent) {
+    const int s = unit / p.Hq, hq = unit % p.Hq;
+    kvu = s * p.Hkv + hq / (p.Hq / p.Hkv);
+    qrow0 = unit;
+  } else {
+    kvu = unit;
+    qrow0 = unit * G;   // (s*Hkv + h) * G == s*Hq + h*G
+  }
+  const T* Kb = reinterpret_cast<const T*>(p.K) + (size_t)kvu * p.rows * kD + sub * 8;
+  const T* Vb = reinterpret_cast<const T*>(p.V) + (size_t)kvu * p.rows * kD + sub * 8;
+
+  // query slices: 8 features of each of the G heads
+  Vec8<T> qv[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) qv[g].load(reinterpret_cast<const T*>(p.q) + (size_t)(qrow0 + g) * kD + sub * 8);
+
+  int* pre = reinterpret_cast<int*>(smem);          // [nseg+1] exclusive prefix of run lengths
+  int* rowoff = pre + (p.nseg + 1);                 // [nseg]   first row of each run
+  long long T_total;
+  if (LIST) {
+    const int nseg = p.nseg;
+    const int per = (nseg + blockDim.x - 1) / blockDim.x;
+    const int j0 = tid * per, j1 = min(j0 + per, nseg);
+    const int32_t* lenu = p.len + (size_t)kvu * p.B;
+    const int32_t* offu = p.off + (size_t)kvu * (p.B + 1);
+    const int32_t* sel = p.selected ? p.selected + (size_t)unit * nseg : nullptr;
+    int mine = 0;
+    for (int j = j0; j < j1; ++j) {
+      const int b = sel ? sel[j] : j;
+      const int ln = lenu[b];
+      pre[j + 1] = ln;            // temporarily the length; turned into a prefix below
+      rowoff[j] = offu[b];
+      mine += ln;
+    }
+    const int incl = wave_incl_scan(mine, lane);
+    if (lane == 63) s_wsum[wave] = incl;
+    __syncthreads();
+    int base = 0;
+    for (int w = 0; w < wave; ++w) base += s_wsum[w];
+    int run = base + incl - mine;
+    for (int j = j0; j < j1; ++j) {
+      const int ln = pre[j + 1];
+      if (j == 0) pre[0] = 0;
+      run += ln;
+      pre[j + 1] = run;
+    }
+    if (nseg == 0 && tid == 0) pre[0] = 0;
+    __syncthreads();
+    T_total = pre[nseg];
+  } else {
+    T_total = p.n_dense;
+  }
+
+  const int lo = (int)(T_total * wg / p.P);
+  const int hi = (int)(T_total * (wg + 1) / p.P);
+
+  float m[G], l[G], O[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = kNegBig;
+    l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) O[g][e] = 0.f;
+  }
+
+  const int NG = nw * 4;               // key processors in the workgroup
+  const int kp = wave * 4 + grp;
+  const int stride = NG * kKeysPerBatch;
+  for (int base = lo; base < hi; base += stride) {
+    // Virtual key of (this processor, slot i) is base + i*NG + kp.  Lane `sub` resolves slot sub%4.
+    int row;
+    {
+      int v = base + (sub & (kKeysPerBatch - 1)) * NG + kp;
+      v = min(v, hi - 1);
+      if (LIST) {
+        int a = 0, b = p.nseg;
+        while (b - a > 1) {
+          const int mid = (a + b) >> 1;
+          if (pre[mid] <= v) a = mid; else b = mid;
+        }
+        row = rowoff[a] + (v - pre[a]);
+      } else {
+        row = v;
+      }
+    }
+    Vec8<T> kx[kKeysPerBatch], vx[kKeysPerBatch];
+    bool valid[kKeysPerBatch];
+#pragma unroll
+    for (int i = 0; i < kKeysPerBatch; ++i) {
+      const int r = __shfl(row, (lane & 48) + i);
+      valid[i] = base + i * NG + kp < hi;
+      kx[i].load(Kb + (size_t)r * kD);
+      vx[i].load(Vb + (size_t)r * kD);
+    }
+    float t[kKeysPerBatch][G];
+#pragma unroll
+    for (int i = 0; i < kKeysPerBatch; ++i)
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float s = sum16(kx[i].dot(qv[g]));
+        t[i][g] = valid[i] ? s * p.scale_log2 : -INFINITY;
+      }
+    // Algorithm 1: one running-maximum update for the batch
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float bm = t[0][g];
+#pragma unroll
+      for (int i = 1; i < kKeysPerBatch; ++i) bm = fmaxf(bm, t[i][g]);
+      const float mn = fmaxf(m[g], bm);
+      const float alpha = fast_exp2(m[g] - mn);
+      m[g] = mn;
+      l[g] *= alpha;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) O[g][e] *= alpha;
+#pragma unroll
+      for (int i = 0; i < kKeysPerBatch; ++i) t[i][g] = fast_exp2(t[i][g] - mn);
+    }
+#pragma unroll
+    for (int i = 0; i < kKeysPerBatch; ++i) {
+      float vf[8];
+      vx[i].to_float(vf);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        l[g] += t[i][g];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) O[g][e] = fmaf(t[i][g], vf[e], O[g][e]);
+      }
+    }
+  }
+
+  // combine the four key processors of the wave
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float mw = fmaxf(m[g], __shfl_xor(m[g], 16));
+    mw = fmaxf(mw, __shfl_xor(mw, 32));
+    const float a = fast_exp2(m[g] - mw);
+    m[g] = mw;
+    l[g] *= a;
+    l[g] += __shfl_xor(l[g], 16);
+    l[g] += __shfl_xor(l[g], 32);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float o = O[g][e] * a;
+      o += __shfl_xor(o, 16);
+      o += __shfl_xor(o, 32);
+      O[g][e] = o;
+    }
+  }
+
+  // waves -> LDS (the prefix arrays are dead from here on)
+  __syncthreads();
+  float* w_o = reinterpret_cast<float*>(smem);            // [nw][G][d]
+  float* w_m = w_o + nw * G * kD;                         // [nw][G]
+  float* w_l = w_m + nw * G;                              // [nw][G]
+  if (grp == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) w_o[(wave * G + g) * kD + sub * 8 + e] = O[g][e];
+      if (sub == 0) {
+        w_m[wave * G + g] = m[g];
+        w_l[wave * G + g] = l[g];
+      }
+    }
+  }
+  __syncthreads();
+
+  for (int x = tid; x < G * kD; x += blockDim.x) {
+    const int g = x / kD, e = x % kD;
+    float M, L, Ov;
+    lse_merge(
+        nw, [&](int w) { return w_m[w * G + g]; }, [&](int w) { return w_l[w * G + g]; },
+        [&](int w) { return w_o[(w * G + g) * kD + e]; }, M, L, Ov);
+    if (p.P == 1) {
+      store_out(p, qrow0 + g, e, M, L, Ov);
+    } else {
+      const size_t slot = ((size_t)unit * p.P + wg) * G + g;
+      p.part_o[slot * kD + e] = Ov;
+      if (e == 0) {
+        p.part_ml[slot * 2 + 0] = M;
+        p.part_ml[slot * 2 + 1] = L;
+      }
+    }
+  }
+  if (p.P == 1) return;
+
+  // last workgroup of the unit to arrive merges the P partial results
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const unsigned old = atomicAdd(&p.counters[unit], 1u);
+    s_last = (old == (unsigned)(p.P - 1));
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  for (int x = tid; x < G * kD; x += blockDim.x) {
+    const int g = x / kD, e = x % kD;
+    const size_t slot0 = (size_t)unit * p.P * G + g;
+    float M, L, Ov;
+    lse_merge(
+        p.P, [&](int i) { return p.part_ml[(slot0 + (size_t)i * G) * 2 + 0]; },
+        [&](int i) { return p.part_ml[(slot0 + (size_t)i * G) * 2 + 1]; },
+        [&](int i) { return p.part_o[(slot0 + (size_t)i * G) * kD + e]; }, M, L, Ov);
+    store_out(p, qrow0 + g, e, M, L, Ov);
+  }
+  if (tid == 0) p.counters[unit] = 0u;
+}
+
+struct LaunchPlan {
+  int P, threads;
+  size_t lds;
+};
+
+LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, int G, int nseg, bool list) {
+  int threads = env_int("SAAP_ATTN_THREADS", 512);
+  if (threads != 64 && threads != 128 && threads != 256 && threads != 512) threads = 512;
+  const int wgs_per_cu = env_int("SAAP_ATTN_WGS_PER_CU", 2);
+  const int cus = device_cus();
+  const long long keys_per_wg_min = (long long)(threads / 16) * kKeysPerBatch;
+  long long P = (long long)cus * wgs_per_cu / n_units;
+  const long long by_work = (est_keys_per_unit + keys_per_wg_min - 1) / keys_per_wg_min;
+  if (P > by_work) P = by_work;
+  if (P > kMaxP) P = kMaxP;
+  if (P < 1) P = 1;
+  const int force_p = env_int("SAAP_ATTN_P", 0);
+  if (force_p > 0 && force_p <= kMaxP) P = force_p;
+  LaunchPlan lp;
+  lp.P = (int)P;
+  lp.threads = threads;
+  size_t a = list ? (size_t)(2 * nseg + 1) * sizeof(int) : 0;
+  size_t b = (size_t)(threads / 64) * G * (kD + 2) * sizeof(float);
+  lp.lds = a > b ? a : b;
+  return lp;
+}
+
+template <typename T, int G, bool LIST>
+int32_t launch_one(const AttnParams& p, const LaunchPlan& lp, hipStream_t stream) {
+  auto kern = attn_kernel<T, G, LIST>;
+  if (lp.lds > 48 * 1024) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lp.lds) != hipSuccess)
+      return SAAP_HIP_ERROR;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)(p.n_units * p.P)), dim3((unsigned)lp.threads), lp.lds, stream, p);
+  return launch_status();
+}
+
+template <bool LIST>
+int32_t launch_attn(const AttnParams& p, const LaunchPlan& lp, int G, int dtype, hipStream_t stream) {
+#define SAAP_CASE(TT, GG) return launch_one<TT, GG, LIST>(p, lp, stream)
+  if (dtype == SAAP_BF16) {
+    switch (G) {
+      case 1: SAAP_CASE(bf16_t, 1);
+      case 2: SAAP_CASE(bf16_t, 2);
+      case 4: SAAP_CASE(bf16_t, 4);
+      case 8: SAAP_CASE(bf16_t, 8);
+    }
+  } else {
+    switch (G) {
+      case 1: SAAP_CASE(float, 1);
+      case 2: SAAP_CASE(float, 2);
+      case 4: SAAP_CASE(float, 4);
+      case 8: SAAP_CASE(float, 8);
+    }
+  }
+#undef SAAP_CASE
+  return SAAP_UNSUPPORTED;
+}
+
+}  // namespace
+
+// Workspace bytes of the attention calls for `units` units of G heads.
+size_t attn_workspace_bytes(long long units, int G) {
+  return (size_t)SAAP_WS_HEADER_BYTES + (size_t)units * kMaxP * G * (kD + 2) * sizeof(float);
+}
+
+}  // namespace saap
+
+using namespace saap;
+
+static int32_t check_common(const void* q, const void* K, const void* V, void* out, int S, int Hq, int Hkv,
+                            int d, int dtype, int out_dtype, const void* ws) {
+  if (!q || !K || !V || !out || !ws) return SAAP_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(out) || !aligned16(ws)) return SAAP_INVALID_ARG;
+  if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return SAAP_INVALID_ARG;
+  if ((dtype != SAAP_F32 && dtype != SAAP_BF16) || (out_dtype != SAAP_F32 && out_dtype != SAAP_BF16))
+    return SAAP_INVALID_ARG;
+  if (d != kD) return SAAP_UNSUPPORTED;
+  const int G = Hq / Hkv;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return SAAP_UNSUPPORTED;
+  return SAAP_OK;
+}
+
+extern "C" int32_t saap_sparse_decode_attention(const void* q, const void* Ksorted, const void* Vsorted,
+                                                const int32_t* off, const int32_t* len,
+                                                const int32_t* selected, int32_t nprobe, int32_t mode,
+                                                float scale, void* out, int32_t out_dtype, float* lse,
+                                                int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
+                                                int32_t d, int32_t dtype, void* ws, size_t ws_bytes,
+                                                void* stream) {
+  int32_t st = check_common(q, Ksorted, Vsorted, out, S, Hq, Hkv, d, dtype, out_dtype, ws);
+  if (st != SAAP_OK) return st;
+  if (!off || !len || (nprobe > 0 && !selected)) return SAAP_INVALID_ARG;
+  if (mode != SAAP_GROUP_SUM && mode != SAAP_INDEPENDENT) return SAAP_INVALID_ARG;
+  if (B <= 0 || Ncap <= 0 || nprobe < 0 || nprobe > B) return SAAP_INVALID_ARG;
+  if (nprobe > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
+  const bool indep = mode == SAAP_INDEPENDENT;
+  const int G = indep ? 1 : Hq / Hkv;
+  const long long units = indep ? (long long)S * Hq : (long long)S * Hkv;
+  if (units * sizeof(unsigned) > SAAP_WS_HEADER_BYTES) return SAAP_UNSUPPORTED;
+  if (ws_bytes < attn_workspace_bytes(units, G)) return SAAP_WORKSPACE_TOO_SMALL;
+
+  AttnParams p{};
+  p.q = q; p.K = Ksorted; p.V = Vsorted; p.off = off; p.len = len; p.selected = selected;
+  p.out = out; p.lse = lse;
+  p.counters = reinterpret_cast<unsigned*>(ws);
+  p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
+  p.part_o = p.part_ml + (size_t)units * kMaxP * G * 2;
+  p.rows = Ncap; p.nseg = nprobe; p.B = B; p.n_units = (int)units;
+  p.Hq = Hq; p.Hkv = Hkv; p.independent = indep ? 1 : 0; p.out_bf16 = out_dtype == SAAP_BF16;
+  p.n_dense = 0; p.scale_log2 = scale * kLog2e;
+  const long long est = (long long)Ncap * nprobe / B;
+  LaunchPlan lp = plan_launch((int)units, est, G, nprobe, true);
+  p.P = lp.P;
+  return launch_attn<true>(p, lp, G, dtype, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int32_t saap_dense_decode_attention(const void* q, const void* K, const void* V,
+                                               const int32_t* off, const int32_t* len, int32_t B,
+                                               float scale, void* out, int32_t out_dtype, float* lse,
+                                               int32_t S, int32_t Hq, int32_t Hkv, int32_t N, int32_t d,
+                                               int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
+  int32_t st = check_common(q, K, V, out, S, Hq, Hkv, d, dtype, out_dtype, ws);
+  if (st != SAAP_OK) return st;
+  if (N <= 0) return SAAP_INVALID_ARG;
+  if ((off == nullptr) != (len == nullptr)) return SAAP_INVALID_ARG;
+  if (off && (B <= 0 || B > SAAP_MAX_BUCKETS)) return B <= 0 ? SAAP_INVALID_ARG : SAAP_UNSUPPORTED;
+  const int G = Hq / Hkv;
+  const long long units = (long long)S * Hkv;
+  if (units * sizeof(unsigned) > SAAP_WS_HEADER_BYTES) return SAAP_UNSUPPORTED;
+  if (ws_bytes < attn_workspace_bytes(units, G)) return SAAP_WORKSPACE_TOO_SMALL;
+
+  AttnParams p{};
+  p.q = q; p.K = K; p.V = V; p.off = off; p.len = len; p.selected = nullptr;
+  p.out = out; p.lse = lse;
+  p.counters = reinterpret_cast<unsigned*>(ws);
+  p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
+  p.part_o = p.part_ml + (size_t)units * kMaxP * G * 2;
+  p.rows = N; p.nseg = off ? B : 0; p.B = B; p.n_units = (int)units;
+  p.Hq = Hq; p.Hkv = Hkv; p.independent = 0; p.out_bf16 = out_dtype == SAAP_BF16;
+  p.n_dense = N; p.scale_log2 = scale * kLog2e;
+  LaunchPlan lp = plan_launch((int)units, N, G, p.nseg, off != nullptr);
+  p.P = lp.P;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  return off ? launch_attn<true>(p, lp, G, dtype, hs) : launch_attn<false>(p, lp, G, dtype, hs);
+}

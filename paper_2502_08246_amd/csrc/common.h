@@ -1,0 +1,113 @@
+// Shared device/host helpers of the SAAP HIP library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include "saap.h"
+
+namespace saap {
+
+typedef uint16_t bf16_t;  // storage type of a bfloat16 element
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+constexpr int kD = SAAP_HEAD_DIM;      // features per head
+constexpr float kNegBig = -3.0e38f;    // finite stand-in for "no score yet"
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ---- host side ---------------------------------------------------------------------------
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  return (v && *v) ? atoi(v) : dflt;
+}
+
+// Compute units of the current device; 256 (MI355X) when the query fails.
+int device_cus();
+
+inline int32_t launch_status() { return hipGetLastError() == hipSuccess ? SAAP_OK : SAAP_HIP_ERROR; }
+
+// ---- device side -------------------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// float -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Data-parallel-primitive lane exchanges (no LDS traffic).
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7-i inside each 8 lanes
+constexpr int kDppMirror = 0x140;      // lane i <-> 15-i inside each 16 lanes
+
+// Sum over each aligned group of 16 lanes; every lane of the group gets the total.
+__device__ __forceinline__ float sum16(float x) {
+  x += dpp_mov<kDppXor1>(x);
+  x += dpp_mov<kDppXor2>(x);
+  x += dpp_mov<kDppHalfMirror>(x);
+  x += dpp_mov<kDppMirror>(x);
+  return x;
+}
+
+// Eight consecutive elements of a row, as loaded by one lane.
+template <typename T> struct Vec8;
+template <> struct Vec8<float> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const float* p) {
+    a = *reinterpret_cast<const float4*>(p);
+    b = *reinterpret_cast<const float4*>(p + 4);
+  }
+  __device__ __forceinline__ void to_float(float* o) const {
+    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+  }
+  __device__ __forceinline__ float dot(const Vec8<float>& q) const {
+    float s = a.x * q.a.x;
+    s = fmaf(a.y, q.a.y, s); s = fmaf(a.z, q.a.z, s); s = fmaf(a.w, q.a.w, s);
+    s = fmaf(b.x, q.b.x, s); s = fmaf(b.y, q.b.y, s); s = fmaf(b.z, q.b.z, s); s = fmaf(b.w, q.b.w, s);
+    return s;
+  }
+};
+template <> struct Vec8<bf16_t> {
+  uint4 r;
+  __device__ __forceinline__ void load(const bf16_t* p) { r = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void to_float(float* o) const {
+    o[0] = bf16_lo(r.x); o[1] = bf16_hi(r.x); o[2] = bf16_lo(r.y); o[3] = bf16_hi(r.y);
+    o[4] = bf16_lo(r.z); o[5] = bf16_hi(r.z); o[6] = bf16_lo(r.w); o[7] = bf16_hi(r.w);
+  }
+  // Products of two bf16 numbers are exact in fp32; v_dot2_f32_bf16 adds two of them per step.
+  __device__ __forceinline__ float dot(const Vec8<bf16_t>& q) const {
+    float s = 0.f;
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, r.x), __builtin_bit_cast(bf16x2_t, q.r.x), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, r.y), __builtin_bit_cast(bf16x2_t, q.r.y), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, r.z), __builtin_bit_cast(bf16x2_t, q.r.z), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, r.w), __builtin_bit_cast(bf16x2_t, q.r.w), s, false);
+    return s;
+  }
+};
+
+// Order-preserving map float -> uint32 (larger float, larger key); -0 and +0 must be
+// canonicalised by the caller.
+__device__ __forceinline__ uint32_t float_order_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+}  // namespace saap

@@ -1,0 +1,91 @@
+// Host-side utilities of the C ABI: workspace sizing, status strings, device query, and the
+// fill kernel that zeroes the workspace header.
+#include "common.h"
+
+namespace saap {
+
+size_t attn_workspace_bytes(long long units, int G);
+size_t assign_workspace_bytes(long long rows);
+size_t build_workspace_bytes(long long units, int N, int B);
+size_t classify_workspace_bytes(long long rows, int hidden);
+
+int device_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+        prop.multiProcessorCount > 0)
+      cus = prop.multiProcessorCount;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
+namespace {
+__global__ void zero_words_kernel(uint32_t* p, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+}  // namespace
+
+}  // namespace saap
+
+using namespace saap;
+
+extern "C" size_t saap_workspace_bytes(int32_t op, const saap_shape* sh) {
+  if (!sh) return 0;
+  const long long S = sh->S, Hq = sh->Hq, Hkv = sh->Hkv;
+  switch (op) {
+    case SAAP_OP_SPARSE_DECODE_ATTENTION: {
+      if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv) return 0;
+      const bool indep = sh->mode == SAAP_INDEPENDENT;
+      return attn_workspace_bytes(indep ? S * Hq : S * Hkv, indep ? 1 : (int)(Hq / Hkv));
+    }
+    case SAAP_OP_DENSE_DECODE_ATTENTION:
+      if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv) return 0;
+      return attn_workspace_bytes(S * Hkv, (int)(Hq / Hkv));
+    case SAAP_OP_ASSIGN_KEYS:
+      if (S <= 0 || Hkv <= 0 || sh->N <= 0) return 0;
+      return assign_workspace_bytes(S * Hkv * (long long)sh->N);
+    case SAAP_OP_BUILD_BUCKET_INDEX:
+      if (S <= 0 || Hkv <= 0 || sh->N <= 0 || sh->B <= 0) return 0;
+      return build_workspace_bytes(S * Hkv, sh->N, sh->B);
+    case SAAP_OP_CLASSIFY_QUERIES:
+      if (S <= 0 || Hq <= 0 || sh->hidden <= 0) return 0;
+      return classify_workspace_bytes(S * Hq, sh->hidden);
+    case SAAP_OP_SELECT_BUCKETS:
+    case SAAP_OP_APPEND_KEYS:
+      return SAAP_WS_HEADER_BYTES;
+    default:
+      return 0;
+  }
+}
+
+extern "C" int32_t saap_workspace_reset(void* ws, size_t ws_bytes, void* stream) {
+  if (!ws || !aligned16(ws) || ws_bytes < SAAP_WS_HEADER_BYTES) return SAAP_INVALID_ARG;
+  const size_t n = SAAP_WS_HEADER_BYTES / sizeof(uint32_t);
+  hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<uint32_t*>(ws), n);
+  return launch_status();
+}
+
+extern "C" const char* saap_status_string(int32_t status) {
+  switch (status) {
+    case SAAP_OK: return "ok";
+    case SAAP_INVALID_ARG: return "invalid argument";
+    case SAAP_UNSUPPORTED: return "unsupported dtype, head size, group size or size limit";
+    case SAAP_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case SAAP_BUCKET_FULL: return "bucket full";
+    case SAAP_HIP_ERROR: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int32_t saap_device_compute_units(void) {
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return -1;
+  return prop.multiProcessorCount;
+}

@@ -1,0 +1,115 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol that
+include/saap.h declares, sizes workspaces, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2502_08246_amd as saap
+from paper_2502_08246_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return saap.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "saap.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(saap_[a-z_]+)\s*\(", header))
+    assert {"saap_assign_keys", "saap_build_bucket_index", "saap_classify_queries", "saap_select_buckets",
+            "saap_sparse_decode_attention", "saap_dense_decode_attention", "saap_append_keys"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(binding.EXPORTS)
+
+
+def test_status_strings(lib):
+    assert binding.status_string(0) == "ok"
+    for st in (-1, -2, -3, -4, -5, -99):
+        assert isinstance(binding.status_string(st), str) and binding.status_string(st)
+
+
+def test_workspace_bytes_arithmetic():
+    hdr = binding.WS_HEADER_BYTES
+    # attention: header + units * 128 partial slots * G heads * (d + 2) floats
+    got = saap.workspace_bytes(binding.OP_SPARSE_DECODE_ATTENTION, S=1, Hq=32, Hkv=8, mode=0)
+    assert got == hdr + 8 * 128 * 4 * 130 * 4
+    got = saap.workspace_bytes(binding.OP_SPARSE_DECODE_ATTENTION, S=2, Hq=32, Hkv=8, mode=1)
+    assert got == hdr + 64 * 128 * 1 * 130 * 4
+    assert saap.workspace_bytes(binding.OP_DENSE_DECODE_ATTENTION, S=1, Hq=4, Hkv=4) == hdr + 4 * 128 * 130 * 4
+    assert saap.workspace_bytes(binding.OP_SELECT_BUCKETS) == hdr
+    assert saap.workspace_bytes(binding.OP_BUILD_BUCKET_INDEX, S=1, Hkv=8, N=131072, B=1024) == hdr + 8 * 64 * 1024 * 4
+    assert saap.workspace_bytes(binding.OP_ASSIGN_KEYS, S=1, Hkv=2, N=1000) == hdr + 16384 + 2000 * 4
+    assert saap.workspace_bytes(binding.OP_SPARSE_DECODE_ATTENTION, S=1, Hq=5, Hkv=2) == 0   # Hq % Hkv != 0
+    assert saap.workspace_bytes(99, S=1) == 0
+
+
+def _fake(n=1):
+    """Aligned non-null fake device pointers: argument validation must fail before any is used."""
+    return [ctypes.c_void_p(4096 * (i + 1)) for i in range(n)]
+
+
+def test_invalid_arguments_are_rejected_on_the_host(lib):
+    q, K, V, off, ln, sel, out, lse, ws = _fake(9)
+    i32, f32 = ctypes.c_int32, ctypes.c_float
+    big = ctypes.c_size_t(1 << 30)
+
+    def sparse(**kw):
+        a = dict(q=q, K=K, V=V, off=off, ln=ln, sel=sel, nprobe=4, mode=0, scale=0.1, out=out, odt=0, lse=lse,
+                 S=1, Hq=4, Hkv=1, Ncap=100, B=8, d=128, dt=1, ws=ws, wsb=big)
+        a.update(kw)
+        return lib.saap_sparse_decode_attention(a["q"], a["K"], a["V"], a["off"], a["ln"], a["sel"], i32(a["nprobe"]),
+                                                i32(a["mode"]), f32(a["scale"]), a["out"], i32(a["odt"]), a["lse"],
+                                                i32(a["S"]), i32(a["Hq"]), i32(a["Hkv"]), i32(a["Ncap"]), i32(a["B"]),
+                                                i32(a["d"]), i32(a["dt"]), a["ws"], a["wsb"], None)
+
+    assert sparse(q=None) == -1
+    assert sparse(q=ctypes.c_void_p(4100)) == -1            # misaligned
+    assert sparse(nprobe=9) == -1                           # nprobe > B
+    assert sparse(nprobe=-1) == -1
+    assert sparse(Hq=5, Hkv=2) == -1
+    assert sparse(d=64) == -2
+    assert sparse(Hq=3, Hkv=1) == -2                        # G = 3 unsupported
+    assert sparse(dt=7) == -1
+    assert sparse(mode=2) == -1
+    assert sparse(wsb=ctypes.c_size_t(1024)) == -3
+
+    def select(**kw):
+        a = dict(sc=q, sel=sel, S=1, Hq=4, Hkv=1, B=64, nprobe=8, mode=0)
+        a.update(kw)
+        return lib.saap_select_buckets(a["sc"], a["sel"], i32(a["S"]), i32(a["Hq"]), i32(a["Hkv"]), i32(a["B"]),
+                                       i32(a["nprobe"]), i32(a["mode"]), ws, big, None)
+
+    assert select(nprobe=65) == -1
+    assert select(B=1 << 20, nprobe=8) == -2
+    assert select(sc=None) == -1
+    assert select(nprobe=0) == 0                            # nothing to do, nothing launched
+
+    st = lib.saap_build_bucket_index(q, K, V, off, ln, sel, out, lse, i32(1), i32(1), i32(100), i32(99), i32(8),
+                                     i32(128), i32(1), i32(0), ws, big, None)
+    assert st == -1                                         # Ncap != N + B*slack
+    st = lib.saap_assign_keys(q, K, None, sel, i32(1), i32(1), i32(100), i32(8), i32(128), i32(1), ws,
+                              ctypes.c_size_t(16), None)
+    assert st == -3
+    st = lib.saap_classify_queries(q, K, None, V, None, i32(3), out, i32(1), i32(4), i32(2), i32(128), i32(64),
+                                   i32(64), i32(1), i32(0), ws, big, None)
+    assert st == -1                                         # Hw must be 1, Hkv or Hq
+    st = lib.saap_classify_queries(q, K, None, V, None, i32(1), out, i32(1), i32(4), i32(2), i32(128), i32(40),
+                                   i32(64), i32(1), i32(0), ws, big, None)
+    assert st == -2                                         # hidden % 32
+    st = lib.saap_dense_decode_attention(q, K, V, off, None, i32(8), f32(0.1), out, i32(0), lse, i32(1), i32(4),
+                                         i32(1), i32(100), i32(128), i32(1), ws, big, None)
+    assert st == -1                                         # off without len
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    x = torch.zeros(1, 1, 8, 128)
+    c = torch.zeros(1, 4, 128)
+    with pytest.raises(ValueError):
+        saap.assign_keys(x, c, out=torch.zeros(1, 1, 8, dtype=torch.int32), ws=torch.zeros(1 << 20, dtype=torch.uint8))

@@ -1,0 +1,354 @@
+"""GPU parity tests: every C entry point, called through the binding on cuda:0, against the CPU
+oracle on the same seeded inputs.  Integer results (bucket ids, CSR arrays, selected buckets) must
+match bit for bit; attention outputs within the stated tolerance
+    |gpu - ref| <= 2e-3 + 1e-2 |ref|   (bf16 inputs, fp32 accumulation)
+    |gpu - ref| <= 1e-5 + 1e-5 |ref|   (fp32 inputs).
+Sizes are chosen so that the oracle finishes in seconds while the kernels still see several
+workgroups, several tiles and ragged tails."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from synth import gen
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+TOL = {"bf16": (2e-3, 1e-2), "f32": (1e-5, 1e-5)}
+SCALE = 1.0 / math.sqrt(128.0)
+
+
+@pytest.fixture(scope="module")
+def saap():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the -m gpu tests need a real device")
+    import paper_2502_08246_amd as lib
+    lib.load_library()
+    ref.set_threads(16)
+    return lib
+
+
+def h(t):
+    return gen.to_host_f32(t)
+
+
+def assert_close(got, want, dtype, what=""):
+    atol, rtol = TOL[dtype]
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    fin = np.isfinite(want)
+    assert np.array_equal(np.isfinite(got), fin), f"{what}: finiteness differs"
+    assert np.array_equal(got[~fin], want[~fin]), f"{what}: non-finite values differ"
+    err = np.abs(got[fin] - want[fin])
+    lim = atol + rtol * np.abs(want[fin])
+    bad = err > lim
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside tolerance, max err {err.max():.3e}"
+
+
+def small(name, **kw):
+    return gen.CONFIGS[name].replace(**kw)
+
+
+def make_inputs(cfg, seed=0):
+    cache = gen.make_cache(cfg, seed, DEV)
+    cent = gen.make_centroids(cfg, seed, DEV, cache, n_train=min(8192, max(4 * cfg.B, 2048)))
+    xq, q = gen.make_queries(cfg, seed, DEV)
+    W = gen.make_classifier(cfg, seed, DEV)
+    return cache, cent, xq, q, W
+
+
+# ------------------------------------------------------------------------------ dense attention
+@pytest.mark.parametrize("dtype,S,Hq,Hkv,N", [
+    ("bf16", 1, 4, 1, 5000), ("bf16", 2, 8, 2, 3001), ("f32", 1, 1, 1, 4096), ("f32", 2, 4, 2, 1237),
+    ("bf16", 1, 2, 1, 70), ("bf16", 1, 8, 1, 900), ("bf16", 1, 1, 1, 1),
+])
+def test_dense_attention(saap, dtype, S, Hq, Hkv, N):
+    cfg = small("cfg1_llama8b_128k", S=S, Hq=Hq, Hkv=Hkv, N=N, B=16, dtype=dtype)
+    cache = gen.make_cache(cfg, 3, DEV)
+    _, q = gen.make_queries(cfg, 3, DEV)
+    out, lse = saap.dense_decode_attention(q[0], cache["K"], cache["V"], SCALE)
+    torch.cuda.synchronize()
+    ro, rl = ref.dense_decode_attention(h(q[0]), h(cache["K"]), h(cache["V"]), SCALE)
+    assert_close(out.cpu().numpy(), ro, dtype, "dense out")
+    assert_close(lse.cpu().numpy(), rl, dtype, "dense lse")
+
+
+# ------------------------------------------------------------------------------ index build
+@pytest.mark.parametrize("dtype,S,Hkv,N,B,slack", [
+    ("bf16", 1, 2, 10000, 64, 0), ("bf16", 2, 2, 4097, 100, 3), ("f32", 1, 1, 4096, 64, 0), ("bf16", 1, 1, 300, 1024, 1),
+])
+def test_build_bucket_index(saap, dtype, S, Hkv, N, B, slack):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(5)
+    dt = gen.torch_dtype(dtype)
+    # skewed ids with some empty buckets
+    w = torch.rand(B, generator=g, device=DEV) ** 4
+    w[::7] = 0
+    w[0] = 1.0
+    ids = torch.multinomial(w, S * Hkv * N, replacement=True, generator=g).to(torch.int32).view(S, Hkv, N)
+    K = torch.randn(S, Hkv, N, 128, generator=g, device=DEV).to(dt)
+    V = torch.randn(S, Hkv, N, 128, generator=g, device=DEV).to(dt)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, K, V, B, slack)
+    torch.cuda.synchronize()
+    ro, rl, ri, rK, rV = ref.build_bucket_index(ids.cpu().numpy(), h(K), h(V), B, slack)
+    assert np.array_equal(off.cpu().numpy(), ro)
+    assert np.array_equal(ln.cpu().numpy(), rl)
+    assert np.array_equal(idx.cpu().numpy(), ri)          # stable order, slack slots -1
+    member = ri >= 0
+    assert np.array_equal(h(Ks)[member], rK[member])
+    assert np.array_equal(h(Vs)[member], rV[member])
+
+
+# ------------------------------------------------------------------------------ selection
+@pytest.mark.parametrize("S,Hq,Hkv,B,nprobe,mode", [
+    (1, 32, 8, 1024, 51, 0), (2, 8, 2, 4096, 410, 0), (1, 1, 1, 64, 8, 0), (1, 8, 2, 100, 100, 0),
+    (2, 8, 2, 300, 17, 1), (1, 4, 1, 8192, 1, 0), (1, 4, 4, 48, 5, 0),
+])
+def test_select_buckets(saap, S, Hq, Hkv, B, nprobe, mode):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(B + nprobe)
+    scores = torch.softmax(3 * torch.randn(S, Hq, B, generator=g, device=DEV), dim=-1)
+    scores[:, :, B // 2] = scores[:, :, 1]            # planted ties
+    scores[:, :, B - 1] = scores[:, :, 0]
+    # coarse values: many exact ties after the group sum
+    scores[0, :, : B // 4] = torch.round(scores[0, :, : B // 4] * 64) / 64
+    sel = saap.select_buckets(scores, Hkv, nprobe, mode)
+    torch.cuda.synchronize()
+    want = ref.select_buckets(scores.cpu().numpy(), Hkv, nprobe, mode)
+    assert np.array_equal(sel.cpu().numpy(), want)
+
+
+# ------------------------------------------------------------------------------ sparse attention
+def _oracle_index(cfg, cache, cent, slack):
+    ids = ref.assign_keys(h(cache["x_keys"]), h(cent))
+    return ids, ref.build_bucket_index(ids, h(cache["K"]), h(cache["V"]), cfg.B, slack)
+
+
+@pytest.mark.parametrize("dtype,S,Hq,Hkv,N,B,nprobe,slack,alpha", [
+    ("bf16", 1, 4, 1, 6000, 64, 8, 0, None),
+    ("bf16", 2, 8, 2, 5003, 128, 13, 2, 0.3),
+    ("f32", 1, 1, 1, 4096, 64, 8, 0, None),
+    ("f32", 1, 4, 2, 2500, 32, 5, 1, 0.3),
+    ("bf16", 1, 8, 1, 3000, 32, 32, 0, None),       # G = 8, all buckets
+    ("bf16", 1, 2, 1, 3000, 32, 1, 0, 0.3),         # G = 2, one bucket
+])
+def test_sparse_attention(saap, dtype, S, Hq, Hkv, N, B, nprobe, slack, alpha):
+    cfg = small("cfg1_llama8b_128k", S=S, Hq=Hq, Hkv=Hkv, N=N, B=B, nprobe=nprobe, dtype=dtype, alpha=alpha, hidden=64)
+    cache, cent, xq, q, W = make_inputs(cfg, 7)
+    ids, (off, ln, idx, rK, rV) = _oracle_index(cfg, cache, cent, slack)
+    scores = ref.classify_queries(h(xq[0]), h(W[0]), None, h(W[2]), None, Hkv)
+    sel = ref.select_buckets(scores, Hkv, nprobe)
+    # GPU side: its own index build from the oracle's ids, then attention with the oracle's selection
+    d_ids = torch.from_numpy(ids).to(DEV)
+    g_off, g_ln, g_idx, Ks, Vs = saap.build_bucket_index(d_ids, cache["K"], cache["V"], B, slack)
+    d_sel = torch.from_numpy(sel).to(DEV)
+    out, lse = saap.sparse_decode_attention(q[0], Ks, Vs, g_off, g_ln, d_sel, SCALE)
+    torch.cuda.synchronize()
+    ro, rl = ref.sparse_decode_attention(h(q[0]), h(cache["K"]), h(cache["V"]), off, ln, idx, sel, SCALE)
+    assert_close(out.cpu().numpy(), ro, dtype, "sparse out")
+    assert_close(lse.cpu().numpy(), rl, dtype, "sparse lse")
+    # bf16 output option
+    out16, _ = saap.sparse_decode_attention(q[0], Ks, Vs, g_off, g_ln, d_sel, SCALE, out_dtype=torch.bfloat16)
+    assert_close(out16.float().cpu().numpy(), ro, "bf16", "sparse out (bf16 store)")
+
+
+def test_sparse_all_buckets_equals_dense_and_empty_selection(saap):
+    cfg = small("cfg1_llama8b_128k", S=1, Hq=8, Hkv=2, N=7001, B=96, nprobe=96, hidden=64)
+    cache, cent, xq, q, W = make_inputs(cfg, 11)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, 2)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(1)
+    sel = torch.stack([torch.randperm(cfg.B, generator=g) for _ in range(2)]).view(1, 2, cfg.B).to(torch.int32).to(DEV)
+    o_sparse, l_sparse = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln, sel, SCALE)
+    o_dense, l_dense = saap.dense_decode_attention(q[0], cache["K"], cache["V"], SCALE)
+    o_gaps, l_gaps = saap.dense_decode_attention(q[0], Ks, Vs, SCALE, off=off, ln=ln)
+    torch.cuda.synchronize()
+    ro, rl = ref.dense_decode_attention(h(q[0]), h(cache["K"]), h(cache["V"]), SCALE)
+    for o, l, what in ((o_sparse, l_sparse, "nprobe=B"), (o_dense, l_dense, "dense"), (o_gaps, l_gaps, "dense over sorted")):
+        assert_close(o.cpu().numpy(), ro, "bf16", what)
+        assert_close(l.cpu().numpy(), rl, "bf16", what + " lse")
+    # nothing selected: zeros and -inf
+    empty = torch.empty(1, 2, 0, dtype=torch.int32, device=DEV)
+    o, l = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln, empty, SCALE)
+    # only empty buckets selected
+    ln2 = ln.clone()
+    ln2[:, :, 5] = 0
+    o2, l2 = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln2, torch.full((1, 2, 1), 5, dtype=torch.int32, device=DEV), SCALE)
+    torch.cuda.synchronize()
+    for oo, ll in ((o, l), (o2, l2)):
+        assert (oo == 0).all() and torch.isneginf(ll).all()
+
+
+def test_sparse_independent_mode(saap):
+    cfg = small("cfg1_llama8b_128k", S=2, Hq=8, Hkv=2, N=4000, B=64, nprobe=6, hidden=64)
+    cache, cent, xq, q, W = make_inputs(cfg, 13)
+    ids, (off, ln, idx, rK, rV) = _oracle_index(cfg, cache, cent, 0)
+    scores = ref.classify_queries(h(xq[0]), h(W[0]), None, h(W[2]), None, cfg.Hkv)
+    sel = ref.select_buckets(scores, cfg.Hkv, cfg.nprobe, mode=1)
+    g_off, g_ln, g_idx, Ks, Vs = saap.build_bucket_index(torch.from_numpy(ids).to(DEV), cache["K"], cache["V"], cfg.B, 0)
+    out, lse = saap.sparse_decode_attention(q[0], Ks, Vs, g_off, g_ln, torch.from_numpy(sel).to(DEV), SCALE,
+                                            mode=saap.INDEPENDENT)
+    torch.cuda.synchronize()
+    ro, rl = ref.sparse_decode_attention(h(q[0]), h(cache["K"]), h(cache["V"]), off, ln, idx, sel, SCALE, mode=1)
+    assert_close(out.cpu().numpy(), ro, "bf16", "independent out")
+    assert_close(lse.cpu().numpy(), rl, "bf16", "independent lse")
+
+
+def test_attention_is_deterministic_and_workspace_stays_clean(saap):
+    cfg = small("cfg1_llama8b_128k", S=1, Hq=8, Hkv=2, N=20000, B=128, nprobe=16, hidden=64)
+    cache, cent, xq, q, W = make_inputs(cfg, 17)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, 0)
+    scores = saap.classify_queries(xq[0], W[0], W[1], W[2], W[3], cfg.Hkv)
+    sel = saap.select_buckets(scores, cfg.Hkv, cfg.nprobe)
+    outs = []
+    for _ in range(5):
+        o, l = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln, sel, SCALE)
+        outs.append((o.clone(), l.clone()))
+    torch.cuda.synchronize()
+    for o, l in outs[1:]:
+        assert torch.equal(o, outs[0][0]) and torch.equal(l, outs[0][1])
+    ws = saap.workspace(0, DEV)
+    assert int(ws[:65536].to(torch.int64).sum().item()) == 0     # arrival counters are back to zero
+
+
+# ------------------------------------------------------------------------------ classifier
+@pytest.mark.parametrize("dtype,S,Hq,Hkv,hidden,B,Hw_kind,bias", [
+    ("bf16", 1, 32, 8, 512, 1024, "kv", False), ("bf16", 8, 8, 2, 256, 160, "kv", True),
+    ("f32", 1, 1, 1, 256, 64, "kv", False), ("f32", 3, 4, 2, 64, 48, "q", True), ("bf16", 2, 8, 2, 96, 64, "one", True),
+    ("bf16", 5, 4, 1, 64, 4096, "q", False),
+])
+def test_classify_queries(saap, dtype, S, Hq, Hkv, hidden, B, Hw_kind, bias):
+    cfg = small("cfg1_llama8b_128k", S=S, Hq=Hq, Hkv=Hkv, N=16, B=B, hidden=hidden, dtype=dtype)
+    Hw = {"one": 1, "kv": Hkv, "q": Hq}[Hw_kind]
+    xq, _ = gen.make_queries(cfg, 19, DEV)
+    W1, b1, W2, b2 = gen.make_classifier(cfg, 19, DEV, Hw=Hw)
+    if bias:
+        g = torch.Generator(device=DEV)
+        g.manual_seed(2)
+        b1 = torch.randn(b1.shape, generator=g, device=DEV)
+        b2 = torch.randn(b2.shape, generator=g, device=DEV)
+    else:
+        b1 = b2 = None
+    p = saap.classify_queries(xq[0], W1, b1, W2, b2, Hkv)
+    z = saap.classify_queries(xq[0], W1, b1, W2, b2, Hkv, output_kind=saap.LOGITS)
+    torch.cuda.synchronize()
+    hb = lambda t: None if t is None else h(t)
+    rp = ref.classify_queries(h(xq[0]), h(W1), hb(b1), h(W2), hb(b2), Hkv)
+    rz = ref.classify_queries(h(xq[0]), h(W1), hb(b1), h(W2), hb(b2), Hkv, output_kind=1)
+    # fp32 accumulation of exact products over d and hidden terms: logits to ~1e-5 absolute,
+    # probabilities to the same relative amount
+    np.testing.assert_allclose(z.cpu().numpy(), rz, rtol=2e-5, atol=5e-5)
+    np.testing.assert_allclose(p.cpu().numpy(), rp, rtol=1e-4, atol=1e-9)
+
+
+# ------------------------------------------------------------------------------ assignment
+def _plant_ties(x, cent):
+    """Duplicate centroids (exact ties) and keys placed exactly between two centroids (near ties)."""
+    cent = cent.clone()
+    cent[:, 5] = cent[:, 2]
+    cent[:, -1] = cent[:, 2]
+    x = x.clone()
+    x[:, :, :64] = (3.0 * cent[:, 2]).unsqueeze(0).unsqueeze(2).to(x.dtype)
+    mid = (cent[:, 7].float() + cent[:, 9].float()).to(x.dtype)
+    x[:, :, 64:128] = mid.unsqueeze(0).unsqueeze(2)
+    return x, cent
+
+
+@pytest.mark.parametrize("dtype,S,Hkv,N,B,bias", [
+    ("bf16", 1, 2, 4000, 64, False), ("bf16", 2, 2, 1031, 1024, False), ("bf16", 1, 1, 5000, 100, True),
+    ("f32", 1, 1, 4096, 64, False), ("f32", 1, 2, 500, 37, True), ("bf16", 1, 1, 700, 4096, False),
+])
+def test_assign_keys(saap, dtype, S, Hkv, N, B, bias):
+    cfg = small("cfg1_llama8b_128k", S=S, Hq=Hkv, Hkv=Hkv, N=N, B=B, dtype=dtype)
+    cache = gen.make_cache(cfg, 23, DEV)
+    cent = gen.make_centroids(cfg, 23, DEV, n_train=max(2 * B, 2048))
+    x, cent = _plant_ties(cache["x_keys"], cent)
+    b = None
+    if bias:
+        b = (-0.5 * cent.float().pow(2).sum(-1)).contiguous()
+    ids = saap.assign_keys(x, cent, b)
+    torch.cuda.synchronize()
+    want = ref.assign_keys(h(x), h(cent), None if b is None else h(b))
+    got = ids.cpu().numpy()
+    assert np.array_equal(got, want), f"{(got != want).sum()} of {got.size} ids differ"
+    assert (got[:, :, :64] == 2).all()                      # the lowest of the tied duplicates
+
+
+# ------------------------------------------------------------------------------ append
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_append_keys(saap, dtype):
+    cfg = small("cfg1_llama8b_128k", S=2, Hq=8, Hkv=2, N=2000, B=32, nprobe=32, dtype=dtype, hidden=64)
+    cache, cent, xq, q, W = make_inputs(cfg, 29)
+    slack, steps = 2, 6
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, slack)
+    torch.cuda.synchronize()
+    r_off, r_ln, r_idx, rKs, rVs = ref.build_bucket_index(ids.cpu().numpy(), h(cache["K"]), h(cache["V"]), cfg.B, slack)
+    new = gen.make_cache(cfg.replace(N=steps), 31, DEV)
+    # make every step hit the same bucket for sequence 0 / head 0 so that its slack runs out
+    new["x_keys"][0, 0, :] = (4.0 * cent[0, 3].float()).to(new["x_keys"].dtype)
+    Kall = torch.cat([cache["K"], new["K"]], dim=2)
+    Vall = torch.cat([cache["V"], new["V"]], dim=2)
+    flags = []
+    for t in range(steps):
+        pos = torch.full((cfg.S,), cfg.N + t, dtype=torch.int32, device=DEV)
+        xn, kn, vn = (new[k][:, :, t].contiguous() for k in ("x_keys", "K", "V"))
+        nid, flag = saap.append_keys(xn, kn, vn, pos, cent, None, off, ln, idx, Ks, Vs)
+        torch.cuda.synchronize()
+        rid, rflag = ref.append_keys(h(xn), h(kn), h(vn), pos.cpu().numpy(), h(cent), None, r_off, r_ln, r_idx, rKs, rVs)
+        assert np.array_equal(nid.cpu().numpy(), rid)
+        flags.append(rflag)
+        assert (flag[0].item() != 0) == (rflag != 0)        # a fresh flag per call
+        assert np.array_equal(ln.cpu().numpy(), r_ln)
+        assert np.array_equal(idx.cpu().numpy(), r_idx)
+    assert flags[-1] == 1 and flags[0] == 0                 # overflow happened, and only after the slack ran out
+    member = r_idx != -1
+    assert np.array_equal(h(Ks)[member], rKs[member])
+    # attention over the grown cache, all buckets
+    sel = torch.arange(cfg.B, dtype=torch.int32, device=DEV).repeat(cfg.S, cfg.Hkv, 1)
+    out, lse = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln, sel, SCALE)
+    torch.cuda.synchronize()
+    ro, rl = ref.sparse_decode_attention(h(q[0]), h(Kall), h(Vall), r_off, r_ln, r_idx, sel.cpu().numpy(), SCALE)
+    assert_close(out.cpu().numpy(), ro, dtype, "attention after append")
+    assert_close(lse.cpu().numpy(), rl, dtype, "lse after append")
+
+
+# ------------------------------------------------------------------------------ whole path, config 0
+def test_config0_end_to_end(saap):
+    """BASELINE config 0: fp32, one head, N=4096, B=64, classifier 128->256->64, 16 queries, nprobe 8 and 64."""
+    cfg = gen.CONFIGS["cfg0_tiny_f32"]
+    cache, cent, xq, q, (W1, b1, W2, b2) = make_inputs(cfg, 0)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, 0)
+    torch.cuda.synchronize()
+    r_ids = ref.assign_keys(h(cache["x_keys"]), h(cent))
+    assert np.array_equal(ids.cpu().numpy(), r_ids)
+    r_off, r_ln, r_idx, _, _ = ref.build_bucket_index(r_ids, h(cache["K"]), h(cache["V"]), cfg.B, 0)
+    assert np.array_equal(off.cpu().numpy(), r_off) and np.array_equal(ln.cpu().numpy(), r_ln)
+    assert np.array_equal(idx.cpu().numpy(), r_idx)
+    hK, hV = h(cache["K"]), h(cache["V"])
+    for t in range(cfg.n_queries):
+        scores = saap.classify_queries(xq[t], W1, b1, W2, b2, cfg.Hkv)
+        sel = saap.select_buckets(scores, cfg.Hkv, cfg.nprobe)
+        out, lse = saap.sparse_decode_attention(q[t], Ks, Vs, off, ln, sel, SCALE)
+        sel_all = saap.select_buckets(scores, cfg.Hkv, cfg.B)
+        out_all, lse_all = saap.sparse_decode_attention(q[t], Ks, Vs, off, ln, sel_all, SCALE)
+        out_d, lse_d = saap.dense_decode_attention(q[t], cache["K"], cache["V"], SCALE)
+        torch.cuda.synchronize()
+        r_scores = ref.classify_queries(h(xq[t]), h(W1), h(b1), h(W2), h(b2), cfg.Hkv)
+        np.testing.assert_allclose(scores.cpu().numpy(), r_scores, rtol=1e-4, atol=1e-9)
+        # selection is bit-exact on the same score buffer (here: the GPU's)
+        r_sel = ref.select_buckets(scores.cpu().numpy(), cfg.Hkv, cfg.nprobe)
+        assert np.array_equal(sel.cpu().numpy(), r_sel)
+        ro, rl = ref.sparse_decode_attention(h(q[t]), hK, hV, r_off, r_ln, r_idx, r_sel, SCALE)
+        assert_close(out.cpu().numpy(), ro, "f32", f"cfg0 query {t}")
+        assert_close(lse.cpu().numpy(), rl, "f32", f"cfg0 lse {t}")
+        rd, rdl = ref.dense_decode_attention(h(q[t]), hK, hV, SCALE)
+        assert_close(out_all.cpu().numpy(), rd, "f32", "cfg0 nprobe=64 vs dense")
+        assert_close(out_d.cpu().numpy(), rd, "f32", "cfg0 dense")
+        assert_close(lse_all.cpu().numpy(), rdl, "f32", "cfg0 nprobe=64 lse")
