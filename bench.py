@@ -1,0 +1,277 @@
+"""Benchmark of the SAAP decode hot path on one MI355X.
+
+One "step" is the decode-time hot path for one token of one layer over a resident, bucket-sorted
+KV cache: classify_queries -> select_buckets -> sparse_decode_attention (partials + merge in one
+launch).  The prefill half (assign_keys, build_bucket_index) runs once during set-up and is timed
+separately; dense_decode_attention on the same cache is the in-repo baseline.
+
+Cache hygiene: the timed loop cycles through `--query-sets` different queries (hence different
+bucket selections), so that consecutive steps do not re-read the same 27 MB from the 256 MB
+last-level cache.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+BYTES_PER_KEY = 512     # one bf16 K row + one bf16 V row, d = 128
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="cfg1_llama8b_128k")
+    ap.add_argument("--nprobe", type=int, default=0, help="override the workload's nprobe")
+    ap.add_argument("--query-sets", type=int, default=64)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg (0 = skip)")
+    ap.add_argument("--slack", type=int, default=0)
+    return ap.parse_args()
+
+
+def timed(fn, iters, torch):
+    """Average milliseconds of fn(i) over iters eager calls, bracketed by events on the current stream."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(iters):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+class GraphLoop:
+    """`count` consecutive calls fn(i), i = 0..count-1, captured once as a HIP graph (the calls are
+    launch-bound otherwise: a decode step is a handful of kernels of a few microseconds each).
+    The captured work is exactly the eager work; nothing is skipped."""
+
+    def __init__(self, fn, count, torch):
+        self.torch, self.count = torch, count
+        fn(0)                                   # allocate workspaces before the capture
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            for i in range(count):
+                fn(i)
+        torch.cuda.synchronize()
+
+    def run(self, replays=1):
+        for _ in range(replays):
+            self.graph.replay()
+
+    def timed_ms_per_call(self, replays):
+        torch = self.torch
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        self.run(1)
+        torch.cuda.synchronize()
+        e0.record()
+        self.run(replays)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (replays * self.count)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2502_08246_amd as saap
+    from synth import gen
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    saap.load_library()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = gen.CONFIGS[args.workload]
+    if args.nprobe:
+        cfg = cfg.replace(nprobe=args.nprobe)
+    scale = 1.0 / math.sqrt(cfg.d)
+    T = args.query_sets
+
+    # ---------------------------------------------------------------- inputs (synthetic, seeded)
+    cache = gen.make_cache(cfg, args.seed, dev)
+    cent = gen.make_centroids(cfg, args.seed, dev, cache)
+    xq, q = gen.make_queries(cfg, args.seed, dev, n_steps=T)
+    W1, b1, W2, b2 = gen.make_classifier(cfg, args.seed, dev)
+    torch.cuda.synchronize()
+
+    # ---------------------------------------------------------------- prefill half, timed once warm
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    torch.cuda.synchronize()
+    ws = saap.workspace(0, dev)
+    rescored = int(ws[65536 + 16380:65536 + 16384].view(torch.int32).item())   # diagnostic word of assign_keys
+    index = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, args.slack)
+    torch.cuda.synchronize()
+    ms_assign = timed(lambda i: saap.assign_keys(cache["x_keys"], cent, out=ids), 3, torch)
+    ms_build = timed(lambda i: saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, args.slack), 3, torch)
+    off, ln, idx, Ks, Vs = index
+    n_keys_total = cfg.S * cfg.Hkv * cfg.N
+    assign_flop = 2.0 * n_keys_total * cfg.B * cfg.d
+    x_keys = cache.pop("x_keys")
+    del x_keys
+
+    # ---------------------------------------------------------------- decode buffers
+    scores = torch.empty(cfg.S, cfg.Hq, cfg.B, dtype=torch.float32, device=dev)
+    sel = torch.empty(cfg.S, cfg.Hkv, cfg.nprobe, dtype=torch.int32, device=dev)
+    out = torch.empty(cfg.S, cfg.Hq, cfg.d, dtype=torch.float32, device=dev)
+    lse = torch.empty(cfg.S, cfg.Hq, dtype=torch.float32, device=dev)
+    sel_sets = torch.empty(T, cfg.S, cfg.Hkv, cfg.nprobe, dtype=torch.int32, device=dev)
+
+    def classify(i):
+        saap.classify_queries(xq[i % T], W1, b1, W2, b2, cfg.Hkv, out=scores)
+
+    def select(i):
+        saap.select_buckets(scores, cfg.Hkv, cfg.nprobe, out=sel)
+
+    def attend(i):
+        saap.sparse_decode_attention(q[i % T], Ks, Vs, off, ln, sel, scale, out=out, lse=lse)
+
+    def step(i):
+        classify(i)
+        select(i)
+        attend(i)
+
+    # selections of every query set (for the byte accounting and the per-kernel loops)
+    for t in range(T):
+        classify(t)
+        saap.select_buckets(scores, cfg.Hkv, cfg.nprobe, out=sel_sets[t])
+    torch.cuda.synchronize()
+    keys_per_set = torch.gather(ln.unsqueeze(0).expand(T, -1, -1, -1).to(torch.int64), 3, sel_sets.to(torch.int64)).sum(dim=(1, 2, 3))
+    keys_touched = float(keys_per_set.to(torch.float64).mean().item())   # per step (all sequences, all KV heads)
+    bytes_step = keys_touched * BYTES_PER_KEY
+
+    # ---------------------------------------------------------------- the timed region
+    # K steps = K // T replays of a T-step graph plus one replay of a (K % T)-step graph.
+    g_full = GraphLoop(step, T, torch)
+    rem = args.steps % T
+    g_rem = GraphLoop(step, rem, torch) if rem else None
+    warm = args.warmup
+    while warm > 0:
+        g_full.run(1)
+        warm -= T
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g_full.run(args.steps // T)
+    if g_rem:
+        g_rem.run(1)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    us_token_layer = wall_ms * 1e3 / cfg.S
+
+    # ---------------------------------------------------------------- per-call timings (events, same stream)
+    def attend_set(i):
+        saap.sparse_decode_attention(q[i % T], Ks, Vs, off, ln, sel_sets[i % T], scale, out=out, lse=lse)
+
+    def dense(i):
+        saap.dense_decode_attention(q[i % T], Ks, Vs, scale, off=off, ln=ln, out=out, lse=lse)
+
+    reps = max(2, args.steps // T)
+    ms_attn = GraphLoop(attend_set, T, torch).timed_ms_per_call(reps)
+    ms_classify = GraphLoop(classify, T, torch).timed_ms_per_call(reps)
+    ms_select = GraphLoop(select, T, torch).timed_ms_per_call(reps)
+    ms_dense = GraphLoop(dense, 8, torch).timed_ms_per_call(3)
+    achieved = bytes_step / (ms_attn * 1e-3) / 1e9
+
+    result = {
+        "metric": "sparse decode attention us/token/layer @128k-500k ctx; HBM GB/s vs roofline",
+        "value": round(us_token_layer, 3),
+        "unit": "us/token/layer",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": cfg.name, "S": cfg.S, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "d": cfg.d, "N": cfg.N, "B": cfg.B,
+            "nprobe": cfg.nprobe, "classifier": f"{cfg.d}->{cfg.hidden}->{cfg.B}", "query_sets": T,
+            "step": "classify_queries + select_buckets + sparse_decode_attention", "launch": "hip graph",
+        },
+        "roofline": {
+            "kernel": "attn_kernel<bf16,G=4,list> (sparse_decode_attention, partials + merge)",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "bytes_per_launch": round(bytes_step),
+            "avg_launch_us": round(ms_attn * 1e3, 3),
+        },
+        "breakdown_us": {
+            "classify_queries": round(ms_classify * 1e3, 3),
+            "select_buckets": round(ms_select * 1e3, 3),
+            "sparse_decode_attention": round(ms_attn * 1e3, 3),
+            "dense_decode_attention": round(ms_dense * 1e3, 3),
+        },
+        "dense": {
+            "us": round(ms_dense * 1e3, 3),
+            "GBps": round(n_keys_total * BYTES_PER_KEY / (ms_dense * 1e-3) / 1e9, 1),
+            "speedup_sparse_vs_dense": round(ms_dense / ms_attn, 2),
+        },
+        "selectivity": round(keys_touched / n_keys_total, 5),
+        "prefill": {
+            "assign_keys_ms": round(ms_assign, 3),
+            "assign_keys_TFLOPs": round(assign_flop / (ms_assign * 1e-3) / 1e12, 1),
+            "assign_keys_rescored": rescored,
+            "build_bucket_index_ms": round(ms_build, 3),
+            "build_bucket_index_GBps": round(2.0 * n_keys_total * BYTES_PER_KEY / (ms_build * 1e-3) / 1e9, 1),
+        },
+        "paper_context": {"flashattention_v2_us": 50, "saap_us": 18, "hardware": "H100 80GB, one head, 171k context"},
+    }
+
+    # ---------------------------------------------------------------- oracle timing leg (host cores)
+    if args.cpu_seconds > 0:
+        from oracle import ref
+        h = gen.to_host_f32
+        threads = min(16, os.cpu_count() or 1)
+        ref.set_threads(threads)
+        hK, hV = h(cache["K"]), h(cache["V"])
+        h_off, h_ln, h_idx = off.cpu().numpy(), ln.cpu().numpy(), idx.cpu().numpy()
+        hW1, hb1, hW2, hb2 = h(W1), h(b1), h(W2), h(b2)
+        hxq, hq = h(xq), h(q)
+        done, t_cpu0 = 0, time.perf_counter()
+        while True:
+            sc = ref.classify_queries(hxq[done % T], hW1, hb1, hW2, hb2, cfg.Hkv)
+            se = ref.select_buckets(sc, cfg.Hkv, cfg.nprobe)
+            ref.sparse_decode_attention(hq[done % T], hK, hV, h_off, h_ln, h_idx, se, scale)
+            done += 1
+            el = time.perf_counter() - t_cpu0
+            if el > args.cpu_seconds or done >= 10 * T:
+                break
+        result["cpu_baseline"] = {
+            "value": round(el / done * 1e6 / cfg.S, 1),
+            "unit": "us/token/layer",
+            "cores": threads,
+            "kind": "oracle",
+            "sample": f"{done} decode steps (classify + select + sparse attention) of the same workload, "
+                      f"{threads} OpenMP threads over (sequence, head) in attention; classifier and selection single-threaded",
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -250,11 +250,16 @@ assign_exact_kernel(const T* __restrict__ x, const T* __restrict__ cent, const f
   }
 }
 
-__global__ void clear_counter_kernel(unsigned* c) { *c = 0u; }
+// Leaves the arrival counter zero again; the number of re-scored keys of this call is kept in
+// the scratch area for diagnostics.
+__global__ void clear_counter_kernel(unsigned* c, unsigned* stat) {
+  *stat = *c;
+  *c = 0u;
+}
 
 }  // namespace
 
-// header | cmax[<=4096 floats, 16 KiB] | flagged row list [rows] int32
+// header | cmax[<=4095 floats] + 1 word: keys re-scored by the last call (16 KiB) | flagged row list [rows] int32
 size_t assign_workspace_bytes(long long rows) {
   return (size_t)SAAP_WS_HEADER_BYTES + 16384 + (size_t)rows * sizeof(int32_t);
 }
@@ -273,7 +278,7 @@ extern "C" int32_t saap_assign_keys(const void* x, const void* centroids, const 
   if (d != kD) return SAAP_UNSUPPORTED;
   const long long units = (long long)S * Hkv;
   const long long rows = units * N;
-  if (rows > 0x7fffffffLL || units > 65535 || Hkv > 4096) return SAAP_UNSUPPORTED;
+  if (rows > 0x7fffffffLL || units > 65535 || Hkv > 4095) return SAAP_UNSUPPORTED;
   if (ws_bytes < assign_workspace_bytes(rows)) return SAAP_WORKSPACE_TOO_SMALL;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   const int cus = device_cus();
@@ -304,6 +309,7 @@ extern "C" int32_t saap_assign_keys(const void* x, const void* centroids, const 
                        flagged, n_flagged, Hkv, N, B, tol);
   hipLaunchKernelGGL(assign_exact_kernel<bf16_t>, dim3((unsigned)(cus * 8)), dim3(256), 0, hs, xb, cb, bias,
                      bucket_ids, flagged, n_flagged, rows, Hkv, N, B);
-  hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, hs, n_flagged);
+  hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, hs, n_flagged,
+                     reinterpret_cast<unsigned*>(cmax) + 4095);
   return launch_status();
 }

@@ -18,6 +18,13 @@
 //     partial attention and merge are one launch.
 #include "common.h"
 
+#ifdef SAAP_ATTN_TRACE
+// Debug build only: wall-clock stamps (100 MHz) of the workgroup's phases into p.trace.
+#define SAAP_TRACE(i) do { if (p.trace && threadIdx.x == 0) p.trace[(size_t)blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define SAAP_TRACE(i) do { } while (0)
+#endif
+
 namespace saap {
 namespace {
 
@@ -46,7 +53,20 @@ struct AttnParams {
   int out_bf16;
   int n_dense;            // keys per unit in dense mode
   float scale_log2;       // scale * log2(e)
+  unsigned long long* trace;  // debug builds only
 };
+
+// Partial results cross workgroups inside one launch.  The writer stores them write-through to
+// the device-coherent level and counts its arrival once the stores are acknowledged; the last
+// workgroup to arrive invalidates its non-coherent cache lines once (acquire fence) and then
+// reads the partials with ordinary loads.  A release fence per writer is avoided on purpose: it
+// writes back the whole L2 and costs more than the attention itself when hundreds of
+// workgroups do it.
+__device__ __forceinline__ void coherent_store(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Wait until every outstanding store of this wave has been acknowledged.
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 __device__ __forceinline__ int wave_incl_scan(int x, int lane) {
 #pragma unroll
@@ -62,9 +82,11 @@ __device__ __forceinline__ int wave_incl_scan(int x, int lane) {
 template <typename FM, typename FL, typename FO>
 __device__ __forceinline__ void lse_merge(int n, FM get_m, FL get_l, FO get_o, float& M, float& l, float& o) {
   M = kNegBig;
+#pragma unroll
   for (int i = 0; i < n; ++i) M = fmaxf(M, get_m(i));
   l = 0.f;
   o = 0.f;
+#pragma unroll
   for (int i = 0; i < n; ++i) {
     float w = fast_exp2(get_m(i) - M);
     l = fmaf(w, get_l(i), l);
@@ -79,14 +101,23 @@ __device__ __forceinline__ void store_out(const AttnParams& p, int qrow, int e, 
   if (e == 0 && p.lse) p.lse[qrow] = l > 0.f ? (M + __log2f(l)) * kLn2 : -INFINITY;
 }
 
-template <typename T, int G, bool LIST>
-__global__ void __launch_bounds__(512) attn_kernel(AttnParams p) {
+// One batch of a key processor: kKeysPerBatch rows of K and V, and which of them are real.
+template <typename T>
+struct Batch {
+  Vec8<T> k[kKeysPerBatch], v[kKeysPerBatch];
+  unsigned valid;   // bit i: slot i holds a key of the range
+};
+
+template <typename T, int G, bool LIST, int NT>
+__global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_wsum[16];
   __shared__ int s_last;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+  constexpr int nw = NT / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane & 15, grp = lane >> 4;
+  SAAP_TRACE(0);
   const int unit = blockIdx.x % p.n_units;
   const int wg = blockIdx.x / p.n_units;
 
@@ -110,10 +141,10 @@ __global__ void __launch_bounds__(512) attn_kernel(AttnParams p) {
 
   int* pre = reinterpret_cast<int*>(smem);          // [nseg+1] exclusive prefix of run lengths
   int* rowoff = pre + (p.nseg + 1);                 // [nseg]   first row of each run
-  long long T_total;
+  int T_total;
   if (LIST) {
     const int nseg = p.nseg;
-    const int per = (nseg + blockDim.x - 1) / blockDim.x;
+    const int per = (nseg + NT - 1) / NT;
     const int j0 = tid * per, j1 = min(j0 + per, nseg);
     const int32_t* lenu = p.len + (size_t)kvu * p.B;
     const int32_t* offu = p.off + (size_t)kvu * (p.B + 1);
@@ -144,9 +175,7 @@ __global__ void __launch_bounds__(512) attn_kernel(AttnParams p) {
   } else {
     T_total = p.n_dense;
   }
-
-  const int lo = (int)(T_total * wg / p.P);
-  const int hi = (int)(T_total * (wg + 1) / p.P);
+  SAAP_TRACE(1);
 
   float m[G], l[G], O[G][8];
 #pragma unroll
@@ -157,15 +186,19 @@ __global__ void __launch_bounds__(512) attn_kernel(AttnParams p) {
     for (int e = 0; e < 8; ++e) O[g][e] = 0.f;
   }
 
-  const int NG = nw * 4;               // key processors in the workgroup
+  // The virtual key range [0,T) is cut into chunks of NG*kKeysPerBatch keys; chunk c belongs to
+  // workgroup c % P, so neighbouring workgroups stream neighbouring memory at any moment.
+  constexpr int NG = nw * 4;           // key processors in the workgroup
   const int kp = wave * 4 + grp;
-  const int stride = NG * kKeysPerBatch;
-  for (int base = lo; base < hi; base += stride) {
-    // Virtual key of (this processor, slot i) is base + i*NG + kp.  Lane `sub` resolves slot sub%4.
+  constexpr int chunk = NG * kKeysPerBatch;
+  const long long stride = (long long)chunk * p.P;
+
+  // Virtual key of (this processor, slot i) of the chunk at `base` is base + i*NG + kp.
+  auto load_batch = [&](long long base, Batch<T>& bt) {
     int row;
     {
-      int v = base + (sub & (kKeysPerBatch - 1)) * NG + kp;
-      v = min(v, hi - 1);
+      long long vl = base + (sub & (kKeysPerBatch - 1)) * NG + kp;   // lane `sub` resolves slot sub%4
+      int v = (int)(vl < T_total ? vl : T_total - 1);
       if (LIST) {
         int a = 0, b = p.nseg;
         while (b - a > 1) {
@@ -177,22 +210,24 @@ __global__ void __launch_bounds__(512) attn_kernel(AttnParams p) {
         row = v;
       }
     }
-    Vec8<T> kx[kKeysPerBatch], vx[kKeysPerBatch];
-    bool valid[kKeysPerBatch];
+    bt.valid = 0u;
 #pragma unroll
     for (int i = 0; i < kKeysPerBatch; ++i) {
       const int r = __shfl(row, (lane & 48) + i);
-      valid[i] = base + i * NG + kp < hi;
-      kx[i].load(Kb + (size_t)r * kD);
-      vx[i].load(Vb + (size_t)r * kD);
+      if (base + i * NG + kp < T_total) bt.valid |= 1u << i;
+      bt.k[i].load(Kb + (size_t)r * kD);
+      bt.v[i].load(Vb + (size_t)r * kD);
     }
+  };
+
+  auto consume = [&](const Batch<T>& bt) {
     float t[kKeysPerBatch][G];
 #pragma unroll
     for (int i = 0; i < kKeysPerBatch; ++i)
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const float s = sum16(kx[i].dot(qv[g]));
-        t[i][g] = valid[i] ? s * p.scale_log2 : -INFINITY;
+        const float s = sum16(bt.k[i].dot(qv[g]));
+        t[i][g] = (bt.valid >> i) & 1u ? s * p.scale_log2 : -INFINITY;
       }
     // Algorithm 1: one running-maximum update for the batch
 #pragma unroll
@@ -212,7 +247,7 @@ __global__ void __launch_bounds__(512) attn_kernel(AttnParams p) {
 #pragma unroll
     for (int i = 0; i < kKeysPerBatch; ++i) {
       float vf[8];
-      vx[i].to_float(vf);
+      bt.v[i].to_float(vf);
 #pragma unroll
       for (int g = 0; g < G; ++g) {
         l[g] += t[i][g];
@@ -220,8 +255,24 @@ __global__ void __launch_bounds__(512) attn_kernel(AttnParams p) {
         for (int e = 0; e < 8; ++e) O[g][e] = fmaf(t[i][g], vf[e], O[g][e]);
       }
     }
+  };
+
+  {
+    long long base = (long long)wg * chunk;
+    if (base < T_total) {
+      Batch<T> cur;
+      load_batch(base, cur);
+      for (base += stride; base < T_total; base += stride) {
+        Batch<T> nxt;
+        load_batch(base, nxt);     // in flight while the current batch is consumed
+        consume(cur);
+        cur = nxt;
+      }
+      consume(cur);
+    }
   }
 
+  SAAP_TRACE(3);
   // combine the four key processors of the wave
 #pragma unroll
   for (int g = 0; g < G; ++g) {
@@ -242,7 +293,9 @@ __global__ void __launch_bounds__(512) attn_kernel(AttnParams p) {
   }
 
   // waves -> LDS (the prefix arrays are dead from here on)
+  SAAP_TRACE(9);
   __syncthreads();
+  SAAP_TRACE(10);
   float* w_o = reinterpret_cast<float*>(smem);            // [nw][G][d]
   float* w_m = w_o + nw * G * kD;                         // [nw][G]
   float* w_l = w_m + nw * G;                              // [nw][G]
@@ -258,8 +311,9 @@ __global__ void __launch_bounds__(512) attn_kernel(AttnParams p) {
     }
   }
   __syncthreads();
+  SAAP_TRACE(11);
 
-  for (int x = tid; x < G * kD; x += blockDim.x) {
+  for (int x = tid; x < G * kD; x += NT) {
     const int g = x / kD, e = x % kD;
     float M, L, Ov;
     lse_merge(
@@ -269,36 +323,135 @@ __global__ void __launch_bounds__(512) attn_kernel(AttnParams p) {
       store_out(p, qrow0 + g, e, M, L, Ov);
     } else {
       const size_t slot = ((size_t)unit * p.P + wg) * G + g;
-      p.part_o[slot * kD + e] = Ov;
+      coherent_store(&p.part_o[slot * kD + e], Ov);
       if (e == 0) {
-        p.part_ml[slot * 2 + 0] = M;
-        p.part_ml[slot * 2 + 1] = L;
+        coherent_store(&p.part_ml[slot * 2 + 0], M);
+        coherent_store(&p.part_ml[slot * 2 + 1], L);
       }
     }
   }
   if (p.P == 1) return;
 
-  // last workgroup of the unit to arrive merges the P partial results
-  __threadfence();
+  // The last workgroup of the unit to arrive merges the P partial results (Algorithm 2).
+  // The partials were stored write-through; once every store of the workgroup is acknowledged
+  // the arrival is counted.
+  SAAP_TRACE(4);
+  wait_stores();
+  SAAP_TRACE(5);
   __syncthreads();
   if (tid == 0) {
-    const unsigned old = atomicAdd(&p.counters[unit], 1u);
+    const unsigned old = __hip_atomic_fetch_add(&p.counters[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (old == (unsigned)(p.P - 1));
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
-  for (int x = tid; x < G * kD; x += blockDim.x) {
-    const int g = x / kD, e = x % kD;
-    const size_t slot0 = (size_t)unit * p.P * G + g;
-    float M, L, Ov;
-    lse_merge(
-        p.P, [&](int i) { return p.part_ml[(slot0 + (size_t)i * G) * 2 + 0]; },
-        [&](int i) { return p.part_ml[(slot0 + (size_t)i * G) * 2 + 1]; },
-        [&](int i) { return p.part_o[(slot0 + (size_t)i * G) * kD + e]; }, M, L, Ov);
-    store_out(p, qrow0 + g, e, M, L, Ov);
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  SAAP_TRACE(6);
+
+  // Merge layout: one partial is kCols = G*d/4 float4 columns.  The workgroup's threads form
+  // blockDim/kCols groups that take the partials round-robin, eight loads in flight each, while
+  // one wave per head turns the partial maxima into weights.
+  constexpr int kCols = G * kD / 4;
+  constexpr int kInFlight = 8;
+  const int P = p.P;
+  constexpr int n_groups = NT / kCols;                // >= 1: NT >= 256 >= kCols
+  const int colx = tid % kCols, pgrp = tid / kCols;
+  const int g_col = colx / (kD / 4);
+  const float4* po = reinterpret_cast<const float4*>(p.part_o) + (size_t)unit * P * kCols + colx;
+  const float2* pml = reinterpret_cast<const float2*>(p.part_ml) + (size_t)unit * P * G;
+  float* s_w = reinterpret_cast<float*>(smem);         // [P*G] weights 2^(m_i - M)
+  float* s_M = s_w + P * G;                            // [G]
+  float* s_L = s_M + G;                                // [G]
+  float4* s_acc = reinterpret_cast<float4*>(s_L + G + ((4 - (P * G + 2 * G) % 4) % 4));   // [n_groups][kCols]
+
+  // every load of the first round goes out before anything waits: the (max, sum) pairs first,
+  // they are needed first
+  float2 ml[2];
+  const int g_w = wave < G ? wave : 0;               // wave w weighs head w (and w+nw, ... below)
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int pi = lane + 64 * k;
+    ml[k] = pi < P ? pml[(size_t)pi * G + g_w] : make_float2(kNegBig, 0.f);
   }
-  if (tid == 0) p.counters[unit] = 0u;
+  float4 v[kInFlight];
+#pragma unroll
+  for (int k = 0; k < kInFlight; ++k) {
+    const int pi = pgrp + k * n_groups;
+    v[k] = pi < P ? po[(size_t)pi * kCols] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  for (int g = wave; g < G; g += nw) {
+    if (g != g_w) {
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int pi = lane + 64 * k;
+        ml[k] = pi < P ? pml[(size_t)pi * G + g] : make_float2(kNegBig, 0.f);
+      }
+    }
+    float mx = fmaxf(ml[0].x, ml[1].x);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float lsum = 0.f;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int pi = lane + 64 * k;
+      const float w = fast_exp2(ml[k].x - mx);
+      if (pi < P) s_w[pi * G + g] = w;
+      lsum = fmaf(w, ml[k].y, lsum);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lsum += __shfl_xor(lsum, o);
+    if (lane == 0) {
+      s_M[g] = mx;
+      s_L[g] = lsum;
+    }
+  }
+  __syncthreads();
+  SAAP_TRACE(7);
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int p0 = pgrp;; p0 += n_groups * kInFlight) {
+#pragma unroll
+    for (int k = 0; k < kInFlight; ++k) {
+      const int pi = p0 + k * n_groups;
+      if (pi < P) {
+        const float w = s_w[pi * G + g_col];
+        acc.x = fmaf(w, v[k].x, acc.x);
+        acc.y = fmaf(w, v[k].y, acc.y);
+        acc.z = fmaf(w, v[k].z, acc.z);
+        acc.w = fmaf(w, v[k].w, acc.w);
+      }
+    }
+    const int nxt = p0 + n_groups * kInFlight;
+    if (nxt - pgrp >= P) break;     // uniform over the workgroup: depends on P and n_groups only
+#pragma unroll
+    for (int k = 0; k < kInFlight; ++k) {
+      const int pi = nxt + k * n_groups;
+      v[k] = pi < P ? po[(size_t)pi * kCols] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+  if (pgrp < n_groups) s_acc[pgrp * kCols + colx] = acc;
+  __syncthreads();
+  if (tid < kCols) {
+    float4 r = s_acc[tid];
+    for (int gi = 1; gi < n_groups; ++gi) {
+      const float4 a = s_acc[gi * kCols + tid];
+      r.x += a.x; r.y += a.y; r.z += a.z; r.w += a.w;
+    }
+    const float L = s_L[g_col], M = s_M[g_col];
+    const float inv = L > 0.f ? 1.0f / L : 0.f;
+    r.x *= inv; r.y *= inv; r.z *= inv; r.w *= inv;
+    const int qrow = qrow0 + g_col, e0 = (colx % (kD / 4)) * 4;
+    if (p.out_bf16) {
+      uint2 pk;
+      pk.x = f32_to_bf16_bits(r.x) | (f32_to_bf16_bits(r.y) << 16);
+      pk.y = f32_to_bf16_bits(r.z) | (f32_to_bf16_bits(r.w) << 16);
+      *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(p.out) + (size_t)qrow * kD + e0) = pk;
+    } else {
+      *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.out) + (size_t)qrow * kD + e0) = r;
+    }
+    if (e0 == 0 && p.lse) p.lse[qrow] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
+  }
+  SAAP_TRACE(8);
+  if (tid == 0) __hip_atomic_store(&p.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 struct LaunchPlan {
@@ -308,12 +461,12 @@ struct LaunchPlan {
 
 LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, int G, int nseg, bool list) {
   int threads = env_int("SAAP_ATTN_THREADS", 512);
-  if (threads != 64 && threads != 128 && threads != 256 && threads != 512) threads = 512;
-  const int wgs_per_cu = env_int("SAAP_ATTN_WGS_PER_CU", 2);
+  if (threads != 256 && threads != 512) threads = 512;
+  const int wgs_per_cu = env_int("SAAP_ATTN_WGS_PER_CU", threads == 256 ? 3 : 1);
   const int cus = device_cus();
-  const long long keys_per_wg_min = (long long)(threads / 16) * kKeysPerBatch;
+  const long long chunk = (long long)(threads / 16) * kKeysPerBatch;   // keys per workgroup batch
   long long P = (long long)cus * wgs_per_cu / n_units;
-  const long long by_work = (est_keys_per_unit + keys_per_wg_min - 1) / keys_per_wg_min;
+  const long long by_work = (est_keys_per_unit + chunk - 1) / chunk;
   if (P > by_work) P = by_work;
   if (P > kMaxP) P = kMaxP;
   if (P < 1) P = 1;
@@ -322,15 +475,17 @@ LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, int G, int nseg
   LaunchPlan lp;
   lp.P = (int)P;
   lp.threads = threads;
-  size_t a = list ? (size_t)(2 * nseg + 1) * sizeof(int) : 0;
-  size_t b = (size_t)(threads / 64) * G * (kD + 2) * sizeof(float);
+  const size_t a = list ? (size_t)(2 * nseg + 1) * sizeof(int) : 0;
+  const size_t b = (size_t)(threads / 64) * G * (kD + 2) * sizeof(float);
+  const size_t c = (size_t)(P * G + 2 * G + 4) * sizeof(float) + (size_t)threads * sizeof(float4);
   lp.lds = a > b ? a : b;
+  if (c > lp.lds) lp.lds = c;
   return lp;
 }
 
-template <typename T, int G, bool LIST>
-int32_t launch_one(const AttnParams& p, const LaunchPlan& lp, hipStream_t stream) {
-  auto kern = attn_kernel<T, G, LIST>;
+template <typename T, int G, bool LIST, int NT>
+int32_t launch_nt(const AttnParams& p, const LaunchPlan& lp, hipStream_t stream) {
+  auto kern = attn_kernel<T, G, LIST, NT>;
   if (lp.lds > 48 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lp.lds) != hipSuccess)
@@ -338,6 +493,11 @@ int32_t launch_one(const AttnParams& p, const LaunchPlan& lp, hipStream_t stream
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)(p.n_units * p.P)), dim3((unsigned)lp.threads), lp.lds, stream, p);
   return launch_status();
+}
+
+template <typename T, int G, bool LIST>
+int32_t launch_one(const AttnParams& p, const LaunchPlan& lp, hipStream_t stream) {
+  return lp.threads == 256 ? launch_nt<T, G, LIST, 256>(p, lp, stream) : launch_nt<T, G, LIST, 512>(p, lp, stream);
 }
 
 template <bool LIST>
@@ -414,6 +574,9 @@ extern "C" int32_t saap_sparse_decode_attention(const void* q, const void* Ksort
   p.rows = Ncap; p.nseg = nprobe; p.B = B; p.n_units = (int)units;
   p.Hq = Hq; p.Hkv = Hkv; p.independent = indep ? 1 : 0; p.out_bf16 = out_dtype == SAAP_BF16;
   p.n_dense = 0; p.scale_log2 = scale * kLog2e;
+#ifdef SAAP_ATTN_TRACE
+  if (const char* tp = getenv("SAAP_TRACE_PTR")) p.trace = reinterpret_cast<unsigned long long*>(strtoull(tp, nullptr, 16));
+#endif
   const long long est = (long long)Ncap * nprobe / B;
   LaunchPlan lp = plan_launch((int)units, est, G, nprobe, true);
   p.P = lp.P;

@@ -26,10 +26,15 @@ hist_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ slice_hist, i
   __syncthreads();
   const int n0 = slice * kSlice, n1 = min(n0 + kSlice, N);
   const int32_t* idu = ids + (size_t)unit * N;
-  for (int n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
-    const int b = idu[n];
-    if (b >= 0 && b < B) atomicAdd(&s_cnt[b], 1);
+  int mine[kSlice / 256];
+#pragma unroll
+  for (int k = 0; k < kSlice / 256; ++k) {
+    const int n = n0 + threadIdx.x + k * 256;
+    mine[k] = n < n1 ? idu[n] : -1;
   }
+#pragma unroll
+  for (int k = 0; k < kSlice / 256; ++k)
+    if (mine[k] >= 0 && mine[k] < B) atomicAdd(&s_cnt[mine[k]], 1);
   __syncthreads();
   int32_t* out = slice_hist + ((size_t)unit * n_slices + slice) * B;
   for (int b = threadIdx.x; b < B; b += blockDim.x) out[b] = s_cnt[b];
@@ -109,13 +114,22 @@ scatter_kernel(const int32_t* __restrict__ ids, const int32_t* __restrict__ slic
   const int32_t* idu = ids + (size_t)unit * N;
   int32_t* ix = idx + (size_t)unit * Ncap;
   const unsigned long long below = (1ull << lane) - 1ull;
-  for (int c = n0; c < n1; c += 64) {
+  int mine[kSlice / 64];       // the wave's ids, loaded up front
+#pragma unroll
+  for (int k = 0; k < kSlice / 64; ++k) {
+    const int n = n0 + k * 64 + lane;
+    mine[k] = n < n1 ? idu[n] : -1;
+  }
+#pragma unroll
+  for (int k = 0; k < kSlice / 64; ++k) {
+    const int c = n0 + k * 64;
+    if (c >= n1) break;
     const int n = c + lane;
-    const int b = n < n1 ? idu[n] : -1;
+    const int b = mine[k];
     const bool ok = b >= 0 && b < B;
     unsigned long long eq = __ballot(ok);
-    for (int k = 0; k < id_bits; ++k) {
-      const bool bit = (b >> k) & 1;
+    for (int i = 0; i < id_bits; ++i) {
+      const bool bit = (b >> i) & 1;
       const unsigned long long m = __ballot(bit);
       eq &= bit ? m : ~m;
     }

@@ -4,13 +4,30 @@
 //
 // One workgroup per list.  Every bucket becomes a 64-bit key
 //     (order-preserving image of the fp32 score) << 32 | (0xFFFFFFFF - bucket id)
-// so keys are unique and "larger key" means (higher score, then lower id).  The keys are
-// sorted in LDS with a bitonic network and the first nprobe ids are written out, which is
-// exactly the (score descending, id ascending) order of the definition and is deterministic.
+// so keys are unique and "larger key" means (higher score, then lower id).
+//   * radix kernel (nprobe well below B): a most-significant-digit radix select over the 32-bit
+//     score images (four passes of 8 bits, LDS histogram + one-wave scan) finds the score of the
+//     nprobe-th bucket; buckets above it, and the lowest-id buckets equal to it, are compacted
+//     and only those nprobe keys are sorted (inside one wavefront when nprobe <= 64).
+//   * sort kernel (nprobe close to B): all keys are sorted in LDS with a bitonic network.
+// Both give exactly the (score descending, id ascending) order of the definition.
 #include "common.h"
 
 namespace saap {
 namespace {
+
+// Sum of the heads' scores of bucket b, in fp32 in head order.  All loads go out before the
+// first add (heads <= 8).
+__device__ __forceinline__ float group_score(const float* sc, int heads, int B, int b) {
+  float v[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = i < heads ? sc[(size_t)i * B + b] : 0.f;
+  float g = v[0];
+#pragma unroll
+  for (int i = 1; i < 8; ++i)
+    if (i < heads) g = g + v[i];
+  return g + 0.0f;                                                // -0 -> +0
+}
 
 __global__ void __launch_bounds__(1024)
 select_kernel(const float* __restrict__ scores, int32_t* __restrict__ selected, int Hq, int Hkv, int B,
@@ -27,9 +44,7 @@ select_kernel(const float* __restrict__ scores, int32_t* __restrict__ selected, 
   for (int b = threadIdx.x; b < n_pow2; b += blockDim.x) {
     unsigned long long key = 0ull;   // padding sorts below every finite score
     if (b < B) {
-      float g = sc[b];
-      for (int i = 1; i < heads; ++i) g = g + sc[(size_t)i * B + b];   // fp32, head order
-      g = g + 0.0f;                                                    // -0 -> +0
+      const float g = group_score(sc, heads, B, b);
       key = ((unsigned long long)float_order_key(g) << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)b);
     }
     keys[b] = key;
@@ -57,6 +72,148 @@ select_kernel(const float* __restrict__ scores, int32_t* __restrict__ selected, 
     selected[(size_t)unit * nprobe + j] = (int32_t)(0xFFFFFFFFu - (unsigned)(keys[j] & 0xFFFFFFFFull));
 }
 
+
+// Bitonic sort (descending) of n <= 64 keys held one per lane of a single wavefront.
+__device__ __forceinline__ unsigned long long wave_sort_desc(unsigned long long key, int lane) {
+  for (int k = 2; k <= 64; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      const unsigned lo = __shfl_xor((unsigned)(key & 0xFFFFFFFFull), j);
+      const unsigned hi = __shfl_xor((unsigned)(key >> 32), j);
+      const unsigned long long other = ((unsigned long long)hi << 32) | lo;
+      const bool lower_lane = (lane & j) == 0;
+      const bool descending = (lane & k) == 0;
+      const bool take_max = lower_lane == descending;
+      const unsigned long long mx = key > other ? key : other, mn = key > other ? other : key;
+      key = take_max ? mx : mn;
+    }
+  }
+  return key;
+}
+
+template <int EPT>
+__global__ void __launch_bounds__(1024)
+select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ selected, int Hq, int Hkv, int B,
+                    int nprobe, int independent, int n_sort) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned long long* sortbuf = reinterpret_cast<unsigned long long*>(smem);   // [n_sort]
+  unsigned* eqbits = reinterpret_cast<unsigned*>(sortbuf + n_sort);            // [B/32 + 1]
+  __shared__ unsigned s_hist[256];
+  __shared__ unsigned s_digit, s_krem, s_cnt, s_neq;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nt = blockDim.x;
+  const int unit = blockIdx.x;
+  const int G = Hq / Hkv;
+  const int heads = independent ? 1 : G;
+  const size_t row0 = independent ? (size_t)unit : (size_t)unit * G;
+  const float* sc = scores + row0 * B;
+
+  unsigned key[EPT];
+  {
+    float gs[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const int b = tid + e * nt;
+      gs[e] = group_score(sc, heads, B, b < B ? b : 0);
+    }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) key[e] = tid + e * nt < B ? float_order_key(gs[e]) : 0u;   // 0 sorts below every finite score
+  }
+  if (tid == 0) { s_cnt = 0u; s_neq = 0u; }
+  for (int i = tid; i < n_sort; i += nt) sortbuf[i] = 0ull;
+  for (int i = tid; i <= B / 32; i += nt) eqbits[i] = 0u;
+
+  // radix select: after the passes `prefix` is the score image of the nprobe-th largest bucket
+  unsigned prefix = 0u, mask = 0u, k_rem = (unsigned)nprobe;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    for (int i = tid; i < 256; i += nt) s_hist[i] = 0u;
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+      if (tid + e * nt < B && (key[e] & mask) == prefix) atomicAdd(&s_hist[(key[e] >> shift) & 255u], 1u);
+    __syncthreads();
+    if (wave == 0) {
+      const unsigned c0 = s_hist[4 * lane], c1 = s_hist[4 * lane + 1], c2 = s_hist[4 * lane + 2], c3 = s_hist[4 * lane + 3];
+      const unsigned tot = c0 + c1 + c2 + c3;
+      unsigned incl = tot;                       // inclusive sum over lanes >= this one
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const unsigned y = __shfl_down(incl, o);
+        if (lane + o < 64) incl += y;
+      }
+      unsigned cum = incl - tot;                 // buckets in bins above this lane's four
+      const unsigned c[4] = {c0, c1, c2, c3};
+#pragma unroll
+      for (int b = 3; b >= 0; --b) {
+        if (cum < k_rem && cum + c[b] >= k_rem) {
+          s_digit = (unsigned)(4 * lane + b);
+          s_krem = k_rem - cum;
+        }
+        cum += c[b];
+      }
+    }
+    __syncthreads();
+    prefix |= s_digit << shift;
+    mask |= 255u << shift;
+    k_rem = s_krem;
+  }
+  // buckets scoring exactly `prefix`: k_rem of them are taken, lowest ids first
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int b = tid + e * nt;
+    if (b < B && key[e] == prefix) {
+      atomicAdd(&s_neq, 1u);
+      atomicOr(&eqbits[b >> 5], 1u << (b & 31));
+    }
+  }
+  __syncthreads();
+  const bool all_equal_taken = s_neq == k_rem;
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int b = tid + e * nt;
+    if (b >= B) continue;
+    bool take = key[e] > prefix;
+    if (key[e] == prefix) {
+      if (all_equal_taken) {
+        take = true;
+      } else {
+        unsigned rank = __popc(eqbits[b >> 5] & ((1u << (b & 31)) - 1u));
+        for (int w = 0; w < (b >> 5); ++w) rank += __popc(eqbits[w]);
+        take = rank < k_rem;
+      }
+    }
+    if (take) {
+      const unsigned pos = atomicAdd(&s_cnt, 1u);
+      sortbuf[pos] = ((unsigned long long)key[e] << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)b);
+    }
+  }
+  __syncthreads();
+  int32_t* out = selected + (size_t)unit * nprobe;
+  if (n_sort <= 64) {
+    if (wave == 0) {
+      unsigned long long k = lane < n_sort ? sortbuf[lane] : 0ull;
+      k = wave_sort_desc(k, lane);
+      if (lane < nprobe) out[lane] = (int32_t)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull));
+    }
+    return;
+  }
+  for (int k = 2; k <= n_sort; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = tid; i < n_sort; i += nt) {
+        const int x = i ^ j;
+        if (x > i) {
+          const unsigned long long a = sortbuf[i], c = sortbuf[x];
+          const bool descending = (i & k) == 0;
+          if (descending ? (a < c) : (a > c)) {
+            sortbuf[i] = c;
+            sortbuf[x] = a;
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  for (int j = tid; j < nprobe; j += nt) out[j] = (int32_t)(0xFFFFFFFFu - (unsigned)(sortbuf[j] & 0xFFFFFFFFull));
+}
+
 }  // namespace
 }  // namespace saap
 
@@ -76,18 +233,35 @@ extern "C" int32_t saap_select_buckets(const float* scores, int32_t* selected, i
   if (!selected || !aligned16(selected)) return SAAP_INVALID_ARG;
   int n_pow2 = 2;
   while (n_pow2 < B) n_pow2 <<= 1;
+  int n_sort = 2;
+  while (n_sort < nprobe) n_sort <<= 1;
+  const long long units = mode == SAAP_INDEPENDENT ? (long long)S * Hq : (long long)S * Hkv;
+  const int indep = mode == SAAP_INDEPENDENT ? 1 : 0;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (n_sort < n_pow2 && env_int("SAAP_SELECT_FULL_SORT", 0) == 0) {
+    // radix select + sort of the selected keys only
+    int threads = (B + 3) / 4;
+    threads = (threads + 63) / 64 * 64;
+    if (threads > 1024) threads = 1024;
+    const size_t lds = (size_t)n_sort * sizeof(unsigned long long) + (size_t)(B / 32 + 1) * sizeof(unsigned);
+    if (B <= 4 * threads)
+      hipLaunchKernelGGL(select_radix_kernel<4>, dim3((unsigned)units), dim3((unsigned)threads), lds, hs, scores,
+                         selected, Hq, Hkv, B, nprobe, indep, n_sort);
+    else
+      hipLaunchKernelGGL(select_radix_kernel<8>, dim3((unsigned)units), dim3((unsigned)threads), lds, hs, scores,
+                         selected, Hq, Hkv, B, nprobe, indep, n_sort);
+    return launch_status();
+  }
   int threads = n_pow2 / 2;
   if (threads < 64) threads = 64;
   if (threads > 1024) threads = 1024;
-  const long long units = mode == SAAP_INDEPENDENT ? (long long)S * Hq : (long long)S * Hkv;
   const size_t lds = (size_t)n_pow2 * sizeof(unsigned long long);
   if (lds > 48 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return SAAP_HIP_ERROR;
   }
-  hipLaunchKernelGGL(select_kernel, dim3((unsigned)units), dim3((unsigned)threads), lds,
-                     static_cast<hipStream_t>(stream), scores, selected, Hq, Hkv, B, nprobe,
-                     mode == SAAP_INDEPENDENT ? 1 : 0, n_pow2);
+  hipLaunchKernelGGL(select_kernel, dim3((unsigned)units), dim3((unsigned)threads), lds, hs, scores, selected, Hq,
+                     Hkv, B, nprobe, indep, n_pow2);
   return launch_status();
 }

@@ -121,6 +121,20 @@ def test_select_buckets(saap, S, Hq, Hkv, B, nprobe, mode):
     assert np.array_equal(sel.cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("B,nprobe", [(1024, 51), (4096, 410), (64, 8), (512, 64), (2048, 65)])
+def test_select_buckets_with_ties_at_the_threshold(saap, B, nprobe):
+    """Equal scores straddling the nprobe-th place: the lowest ids must be taken."""
+    S, Hq, Hkv = 2, 8, 2
+    scores = torch.full((S, Hq, B), 1.0 / B, device=DEV)                  # all equal
+    scores[1, :, 10::3] = 2.0 / B                                          # sequence 1: two plateaus
+    scores[1, 4:, 7] = 0.5                                                 # head group 1: one clear winner
+    sel = saap.select_buckets(scores, Hkv, nprobe)
+    torch.cuda.synchronize()
+    want = ref.select_buckets(scores.cpu().numpy(), Hkv, nprobe)
+    assert np.array_equal(sel.cpu().numpy(), want)
+    assert sel[0, 0].tolist() == list(range(nprobe))
+
+
 # ------------------------------------------------------------------------------ sparse attention
 def _oracle_index(cfg, cache, cent, slack):
     ids = ref.assign_keys(h(cache["x_keys"]), h(cent))
