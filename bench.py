@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg (0 = skip)")
     ap.add_argument("--slack", type=int, default=0)
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense baseline (keeps profiler summaries to the sparse path)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain device copies of 256 MiB (reference for the HBM byte counters)")
     return ap.parse_args()
 
 
@@ -189,8 +192,17 @@ def main():
     ms_attn = GraphLoop(attend_set, T, torch).timed_ms_per_call(reps)
     ms_classify = GraphLoop(classify, T, torch).timed_ms_per_call(reps)
     ms_select = GraphLoop(select, T, torch).timed_ms_per_call(reps)
-    ms_dense = GraphLoop(dense, 8, torch).timed_ms_per_call(3)
+    ms_dense = None if args.no_dense else GraphLoop(dense, 8, torch).timed_ms_per_call(3)
     achieved = bytes_step / (ms_attn * 1e-3) / 1e9
+
+    # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary of
+    # this workload (a separate profiling run; see profiles/): null if there is none.
+    traffic = None
+    prof = os.path.join(ROOT, "profiles", f"sparse_attention_{cfg.name}_hbm_traffic.md")
+    if os.path.exists(prof) and not args.nprobe:
+        for line in open(prof):
+            if line.startswith("attn_kernel traffic_bytes_per_launch:"):
+                traffic = int(line.split(":")[1])
 
     result = {
         "metric": "sparse decode attention us/token/layer @128k-500k ctx; HBM GB/s vs roofline",
@@ -217,7 +229,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": traffic,
             "bytes_per_launch": round(bytes_step),
             "avg_launch_us": round(ms_attn * 1e3, 3),
         },
@@ -225,9 +237,9 @@ def main():
             "classify_queries": round(ms_classify * 1e3, 3),
             "select_buckets": round(ms_select * 1e3, 3),
             "sparse_decode_attention": round(ms_attn * 1e3, 3),
-            "dense_decode_attention": round(ms_dense * 1e3, 3),
+            "dense_decode_attention": None if ms_dense is None else round(ms_dense * 1e3, 3),
         },
-        "dense": {
+        "dense": None if ms_dense is None else {
             "us": round(ms_dense * 1e3, 3),
             "GBps": round(n_keys_total * BYTES_PER_KEY / (ms_dense * 1e-3) / 1e9, 1),
             "speedup_sparse_vs_dense": round(ms_dense / ms_attn, 2),
@@ -242,6 +254,16 @@ def main():
         },
         "paper_context": {"flashattention_v2_us": 50, "saap_us": 18, "hardware": "H100 80GB, one head, 171k context"},
     }
+
+    if args.calibrate_copy:
+        # a plain copy of known size: the profiler's FETCH_SIZE / WRITE_SIZE for it give the
+        # scale between counter units and bytes
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        result["calibrate_copy_bytes"] = int(src.numel())
 
     # ---------------------------------------------------------------- oracle timing leg (host cores)
     if args.cpu_seconds > 0:

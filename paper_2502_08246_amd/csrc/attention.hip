@@ -18,13 +18,6 @@
 //     partial attention and merge are one launch.
 #include "common.h"
 
-#ifdef SAAP_ATTN_TRACE
-// Debug build only: wall-clock stamps (100 MHz) of the workgroup's phases into p.trace.
-#define SAAP_TRACE(i) do { if (p.trace && threadIdx.x == 0) p.trace[(size_t)blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
-#else
-#define SAAP_TRACE(i) do { } while (0)
-#endif
-
 namespace saap {
 namespace {
 
@@ -50,10 +43,10 @@ struct AttnParams {
   int P;
   int Hq, Hkv;
   int independent;        // unit = (sequence, query head) instead of (sequence, KV head)
+  int stage;              // list mode: copy the unit's len/off arrays to LDS (needs nseg <= 2*NT, B <= 8*NT)
   int out_bf16;
   int n_dense;            // keys per unit in dense mode
   float scale_log2;       // scale * log2(e)
-  unsigned long long* trace;  // debug builds only
 };
 
 // Partial results cross workgroups inside one launch.  The writer stores them write-through to
@@ -150,12 +143,57 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     const int32_t* offu = p.off + (size_t)kvu * (p.B + 1);
     const int32_t* sel = p.selected ? p.selected + (size_t)unit * nseg : nullptr;
     int mine = 0;
-    for (int j = j0; j < j1; ++j) {
-      const int b = sel ? sel[j] : j;
-      const int ln = lenu[b];
-      pre[j + 1] = ln;            // temporarily the length; turned into a prefix below
-      rowoff[j] = offu[b];
-      mine += ln;
+    if (p.stage) {
+      // One memory round trip instead of two: the selected list and the unit's whole len/off
+      // arrays are fetched together into LDS, the gather by bucket id then reads LDS.
+      int* s_len = rowoff + nseg;                       // [B]
+      int* s_off = s_len + p.B;                         // [B]
+      int sv[2], lv[8], ov[8];
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int j = tid + k * NT;
+        sv[k] = j < nseg ? sel[j] : 0;
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int b = tid + k * NT;
+        if (b < p.B) {
+          lv[k] = lenu[b];
+          ov[k] = offu[b];
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int b = tid + k * NT;
+        if (b < p.B) {
+          s_len[b] = lv[k];
+          s_off[b] = ov[k];
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int j = tid + k * NT;
+        if (j < nseg) pre[j + 1] = sv[k];               // bucket id for now
+      }
+      __syncthreads();
+      int bsel[2];                                       // per <= 2 in this mode
+      for (int j = j0; j < j1; ++j) bsel[j - j0] = pre[j + 1];
+      __syncthreads();
+      for (int j = j0; j < j1; ++j) {
+        const int b = bsel[j - j0];
+        const int ln = s_len[b];
+        pre[j + 1] = ln;
+        rowoff[j] = s_off[b];
+        mine += ln;
+      }
+    } else {
+      for (int j = j0; j < j1; ++j) {
+        const int b = sel ? sel[j] : j;
+        const int ln = lenu[b];
+        pre[j + 1] = ln;            // temporarily the length; turned into a prefix below
+        rowoff[j] = offu[b];
+        mine += ln;
+      }
     }
     const int incl = wave_incl_scan(mine, lane);
     if (lane == 63) s_wsum[wave] = incl;
@@ -455,11 +493,12 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
 }
 
 struct LaunchPlan {
-  int P, threads;
+  int P, threads, stage;
   size_t lds;
 };
 
-LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, int G, int nseg, bool list) {
+LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, int G, int nseg, bool list, int B,
+                       bool has_selection) {
   int threads = env_int("SAAP_ATTN_THREADS", 512);
   if (threads != 256 && threads != 512) threads = 512;
   const int wgs_per_cu = env_int("SAAP_ATTN_WGS_PER_CU", threads == 256 ? 3 : 1);
@@ -475,7 +514,9 @@ LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, int G, int nseg
   LaunchPlan lp;
   lp.P = (int)P;
   lp.threads = threads;
-  const size_t a = list ? (size_t)(2 * nseg + 1) * sizeof(int) : 0;
+  size_t a = list ? (size_t)(2 * nseg + 1) * sizeof(int) : 0;
+  lp.stage = list && has_selection && nseg <= 2 * threads && B <= 8 * threads && env_int("SAAP_ATTN_STAGE", 1);
+  if (lp.stage) a += (size_t)2 * B * sizeof(int);
   const size_t b = (size_t)(threads / 64) * G * (kD + 2) * sizeof(float);
   const size_t c = (size_t)(P * G + 2 * G + 4) * sizeof(float) + (size_t)threads * sizeof(float4);
   lp.lds = a > b ? a : b;
@@ -491,6 +532,7 @@ int32_t launch_nt(const AttnParams& p, const LaunchPlan& lp, hipStream_t stream)
                             (int)lp.lds) != hipSuccess)
       return SAAP_HIP_ERROR;
   }
+  saap_trace_arm();
   hipLaunchKernelGGL(kern, dim3((unsigned)(p.n_units * p.P)), dim3((unsigned)lp.threads), lp.lds, stream, p);
   return launch_status();
 }
@@ -574,12 +616,10 @@ extern "C" int32_t saap_sparse_decode_attention(const void* q, const void* Ksort
   p.rows = Ncap; p.nseg = nprobe; p.B = B; p.n_units = (int)units;
   p.Hq = Hq; p.Hkv = Hkv; p.independent = indep ? 1 : 0; p.out_bf16 = out_dtype == SAAP_BF16;
   p.n_dense = 0; p.scale_log2 = scale * kLog2e;
-#ifdef SAAP_ATTN_TRACE
-  if (const char* tp = getenv("SAAP_TRACE_PTR")) p.trace = reinterpret_cast<unsigned long long*>(strtoull(tp, nullptr, 16));
-#endif
   const long long est = (long long)Ncap * nprobe / B;
-  LaunchPlan lp = plan_launch((int)units, est, G, nprobe, true);
+  LaunchPlan lp = plan_launch((int)units, est, G, nprobe, true, B, nprobe > 0);
   p.P = lp.P;
+  p.stage = lp.stage;
   return launch_attn<true>(p, lp, G, dtype, static_cast<hipStream_t>(stream));
 }
 
@@ -607,8 +647,9 @@ extern "C" int32_t saap_dense_decode_attention(const void* q, const void* K, con
   p.rows = N; p.nseg = off ? B : 0; p.B = B; p.n_units = (int)units;
   p.Hq = Hq; p.Hkv = Hkv; p.independent = 0; p.out_bf16 = out_dtype == SAAP_BF16;
   p.n_dense = N; p.scale_log2 = scale * kLog2e;
-  LaunchPlan lp = plan_launch((int)units, N, G, p.nseg, off != nullptr);
+  LaunchPlan lp = plan_launch((int)units, N, G, p.nseg, off != nullptr, B, false);
   p.P = lp.P;
+  p.stage = 0;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   return off ? launch_attn<true>(p, lp, G, dtype, hs) : launch_attn<false>(p, lp, G, dtype, hs);
 }

@@ -181,13 +181,19 @@ mlp_fused_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__ W1, c
                  MlpShape sh) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int btile = blockIdx.x * 4 + wave;           // tile of 16 buckets
-  const int mt = blockIdx.y, w = blockIdx.z;
+  // 1-D grid, weight set fastest: workgroups are handed to the 8 XCDs round-robin, so with Hw a
+  // multiple of 8 all workgroups of a weight set share one L2 and W1 leaves HBM once.
+  const int w = blockIdx.x % sh.Hw;
+  const int rest = blockIdx.x / sh.Hw;
+  const int m_tiles = sh.m_pad / 16;
+  const int mt = rest % m_tiles;
+  const int btile = (rest / m_tiles) * 4 + wave;     // tile of 16 buckets
   const int rc = lane & 15, kg = lane >> 4;
   const bool active = btile * 16 < sh.B;
   const int pitch = sh.hidden + 8;
   bf16_t* s_h = reinterpret_cast<bf16_t*>(smem);     // [3 planes][16 rows][pitch]
 
+  SAAP_TRACE(0);
   constexpr int kBlock = 16;                          // W2 steps (32 hidden units each) per load block
   const int steps = sh.hidden / 32;
   const bf16_t* wr = W2 + ((size_t)w * sh.B + (active ? btile * 16 + rc : 0)) * sh.hidden + kg * 8;
@@ -217,9 +223,11 @@ mlp_fused_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__ W1, c
         bv[j] = b1 ? b1[(size_t)w * sh.hidden + ut * 16 + rc] : 0.f;
       }
     }
+    SAAP_TRACE(5);
 #pragma unroll
     for (int j = 0; j < kTiles; ++j) {
       const int ut = u0 + 4 * j;
+      if (j == 1) SAAP_TRACE(6);
       if (ut < n_utiles) {
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -244,7 +252,9 @@ mlp_fused_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__ W1, c
       }
     }
   }
+  SAAP_TRACE(1);
   __syncthreads();
+  SAAP_TRACE(2);
 
   // layer 2
   f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
@@ -269,6 +279,7 @@ mlp_fused_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__ W1, c
         if (s0 + kBlock + i < steps) wreg[i] = *reinterpret_cast<const uint4*>(wr + (s0 + kBlock + i) * 32);
     }
   }
+  SAAP_TRACE(3);
   if (!active) return;
   const int bucket = btile * 16 + rc;
   const float bo = b2 ? b2[(size_t)w * sh.B + bucket] : 0.f;
@@ -277,6 +288,7 @@ mlp_fused_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__ W1, c
     const int mm = mt * 16 + 4 * kg + i;
     if (mm < sh.rows_per_set) scores[(size_t)query_row(sh, w, mm) * sh.B + bucket] = acc[i] + bo;
   }
+  SAAP_TRACE(4);
 }
 
 // Row softmax in place; the row is held in registers between the passes.
@@ -362,7 +374,8 @@ extern "C" int32_t saap_classify_queries(const void* xq, const void* W1, const f
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return SAAP_HIP_ERROR;
     }
-    hipLaunchKernelGGL(mlp_fused_kernel, g2, dim3(256), lds, hs, static_cast<const bf16_t*>(xq),
+    saap_trace_arm();
+    hipLaunchKernelGGL(mlp_fused_kernel, dim3(g2.x * g2.y * g2.z), dim3(256), lds, hs, static_cast<const bf16_t*>(xq),
                        static_cast<const bf16_t*>(W1), b1, static_cast<const bf16_t*>(W2), b2, scores, sh);
   } else {
     hipLaunchKernelGGL(mlp_hidden_kernel<float>, g1, dim3(256), 0, hs, static_cast<const float*>(xq),

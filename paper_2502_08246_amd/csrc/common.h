@@ -111,3 +111,23 @@ __device__ __forceinline__ uint32_t float_order_key(float f) {
 }
 
 }  // namespace saap
+
+// Debug builds (-DSAAP_TRACE_BUILD) stamp the 100 MHz wall clock at marked points of a kernel:
+// thread 0 of every workgroup writes slot i of its 16-slot record.  The buffer address comes from
+// the environment variable SAAP_TRACE_PTR (hex).  Release builds compile the marks away.
+#ifdef SAAP_TRACE_BUILD
+static __device__ unsigned long long* saap_trace_buf;
+#define SAAP_TRACE(i)                                                                              \
+  do {                                                                                             \
+    if (saap_trace_buf && threadIdx.x == 0)                                                        \
+      saap_trace_buf[((size_t)blockIdx.x + (size_t)gridDim.x * (blockIdx.y + (size_t)gridDim.y * blockIdx.z)) * 16 + (i)] = wall_clock64(); \
+  } while (0)
+static inline void saap_trace_arm() {
+  const char* tp = getenv("SAAP_TRACE_PTR");
+  unsigned long long* ptr = tp ? reinterpret_cast<unsigned long long*>(strtoull(tp, nullptr, 16)) : nullptr;
+  (void)hipMemcpyToSymbol(HIP_SYMBOL(saap_trace_buf), &ptr, sizeof(ptr));
+}
+#else
+#define SAAP_TRACE(i) do { } while (0)
+static inline void saap_trace_arm() {}
+#endif

@@ -97,8 +97,8 @@ select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ sele
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned long long* sortbuf = reinterpret_cast<unsigned long long*>(smem);   // [n_sort]
   unsigned* eqbits = reinterpret_cast<unsigned*>(sortbuf + n_sort);            // [B/32 + 1]
-  __shared__ unsigned s_hist[256];
-  __shared__ unsigned s_digit, s_krem, s_cnt, s_neq;
+  __shared__ unsigned s_hist[2][256];
+  __shared__ unsigned s_digit, s_krem, s_cnt, s_neq, s_and, s_or;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nt = blockDim.x;
   const int unit = blockIdx.x;
   const int G = Hq / Hkv;
@@ -106,6 +106,7 @@ select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ sele
   const size_t row0 = independent ? (size_t)unit : (size_t)unit * G;
   const float* sc = scores + row0 * B;
 
+  SAAP_TRACE(0);
   unsigned key[EPT];
   {
     float gs[EPT];
@@ -117,21 +118,49 @@ select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ sele
 #pragma unroll
     for (int e = 0; e < EPT; ++e) key[e] = tid + e * nt < B ? float_order_key(gs[e]) : 0u;   // 0 sorts below every finite score
   }
-  if (tid == 0) { s_cnt = 0u; s_neq = 0u; }
+  if (tid == 0) { s_cnt = 0u; s_neq = 0u; s_and = 0xFFFFFFFFu; s_or = 0u; }
   for (int i = tid; i < n_sort; i += nt) sortbuf[i] = 0ull;
   for (int i = tid; i <= B / 32; i += nt) eqbits[i] = 0u;
+  for (int i = tid; i < 256; i += nt) s_hist[0][i] = 0u;
+  __syncthreads();
 
-  // radix select: after the passes `prefix` is the score image of the nprobe-th largest bucket
-  unsigned prefix = 0u, mask = 0u, k_rem = (unsigned)nprobe;
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    for (int i = tid; i < 256; i += nt) s_hist[i] = 0u;
-    __syncthreads();
+  // Bits shared by every score image need no pass (softmax outputs share most exponent bits,
+  // which would otherwise pile all buckets into two or three histogram bins).
+  {
+    unsigned a = 0xFFFFFFFFu, o = 0u;
 #pragma unroll
     for (int e = 0; e < EPT; ++e)
-      if (tid + e * nt < B && (key[e] & mask) == prefix) atomicAdd(&s_hist[(key[e] >> shift) & 255u], 1u);
+      if (tid + e * nt < B) { a &= key[e]; o |= key[e]; }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+      a &= __shfl_xor(a, d);
+      o |= __shfl_xor(o, d);
+    }
+    if (lane == 0) { atomicAnd(&s_and, a); atomicOr(&s_or, o); }
+  }
+  __syncthreads();
+  SAAP_TRACE(1);
+  const unsigned diff = s_and ^ s_or;
+  int rem = diff ? 32 - __clz(diff) : 0;                 // undetermined low bits
+  unsigned mask = rem >= 32 ? 0u : ~((1u << rem) - 1u);
+  unsigned prefix = s_and & mask, k_rem = (unsigned)nprobe;
+
+  // most-significant-digit radix select: afterwards `prefix` is the score image of the
+  // nprobe-th largest bucket and k_rem the number of buckets equal to it that are taken
+  int pass = 0;
+  while (rem > 0) {
+    const int width = rem < 8 ? rem : 8;
+    const int shift = rem - width;
+    const unsigned dmask = (1u << width) - 1u;
+    unsigned* hist = s_hist[pass & 1];
+    unsigned* hist_next = s_hist[(pass + 1) & 1];
+    for (int i = tid; i < 256; i += nt) hist_next[i] = 0u;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+      if (tid + e * nt < B && (key[e] & mask) == prefix) atomicAdd(&hist[(key[e] >> shift) & dmask], 1u);
     __syncthreads();
     if (wave == 0) {
-      const unsigned c0 = s_hist[4 * lane], c1 = s_hist[4 * lane + 1], c2 = s_hist[4 * lane + 2], c3 = s_hist[4 * lane + 3];
+      const unsigned c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
       const unsigned tot = c0 + c1 + c2 + c3;
       unsigned incl = tot;                       // inclusive sum over lanes >= this one
 #pragma unroll
@@ -152,9 +181,12 @@ select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ sele
     }
     __syncthreads();
     prefix |= s_digit << shift;
-    mask |= 255u << shift;
+    mask |= dmask << shift;
     k_rem = s_krem;
+    rem = shift;
+    ++pass;
   }
+  SAAP_TRACE(2);
   // buckets scoring exactly `prefix`: k_rem of them are taken, lowest ids first
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
@@ -186,12 +218,14 @@ select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ sele
     }
   }
   __syncthreads();
+  SAAP_TRACE(3);
   int32_t* out = selected + (size_t)unit * nprobe;
   if (n_sort <= 64) {
     if (wave == 0) {
       unsigned long long k = lane < n_sort ? sortbuf[lane] : 0ull;
       k = wave_sort_desc(k, lane);
       if (lane < nprobe) out[lane] = (int32_t)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull));
+      SAAP_TRACE(4);
     }
     return;
   }
@@ -244,6 +278,7 @@ extern "C" int32_t saap_select_buckets(const float* scores, int32_t* selected, i
     threads = (threads + 63) / 64 * 64;
     if (threads > 1024) threads = 1024;
     const size_t lds = (size_t)n_sort * sizeof(unsigned long long) + (size_t)(B / 32 + 1) * sizeof(unsigned);
+    saap_trace_arm();
     if (B <= 4 * threads)
       hipLaunchKernelGGL(select_radix_kernel<4>, dim3((unsigned)units), dim3((unsigned)threads), lds, hs, scores,
                          selected, Hq, Hkv, B, nprobe, indep, n_sort);
