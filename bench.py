@@ -194,6 +194,16 @@ def main():
     ms_select = GraphLoop(select, T, torch).timed_ms_per_call(reps)
     ms_dense = None if args.no_dense else GraphLoop(dense, 8, torch).timed_ms_per_call(3)
     achieved = bytes_step / (ms_attn * 1e-3) / 1e9
+    # streaming-read ceiling of this device: plain 16-byte loads over the whole sorted cache
+    sink = torch.zeros(4096, dtype=torch.int32, device=dev)
+    kv_bytes = Ks.numel() * Ks.element_size() + Vs.numel() * Vs.element_size()
+
+    def probe(i):
+        saap.stream_read_probe(Ks, sink)
+        saap.stream_read_probe(Vs, sink)
+
+    ms_probe = GraphLoop(probe, 4, torch).timed_ms_per_call(3)
+    ceiling = kv_bytes / (ms_probe * 1e-3) / 1e9
 
     # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary of
     # this workload (a separate profiling run; see profiles/): null if there is none.
@@ -232,6 +242,8 @@ def main():
             "traffic": traffic,
             "bytes_per_launch": round(bytes_step),
             "avg_launch_us": round(ms_attn * 1e3, 3),
+            "stream_read_ceiling_GBps": round(ceiling, 1),
+            "frac_of_stream_read_ceiling": round(achieved / ceiling, 4),
         },
         "breakdown_us": {
             "classify_queries": round(ms_classify * 1e3, 3),

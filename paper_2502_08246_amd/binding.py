@@ -25,7 +25,7 @@ _lib = None
 EXPORTS = (
     "saap_workspace_bytes", "saap_workspace_reset", "saap_status_string", "saap_device_compute_units",
     "saap_assign_keys", "saap_build_bucket_index", "saap_append_keys", "saap_classify_queries",
-    "saap_select_buckets", "saap_sparse_decode_attention", "saap_dense_decode_attention",
+    "saap_select_buckets", "saap_sparse_decode_attention", "saap_dense_decode_attention", "saap_stream_read_probe",
 )
 
 
@@ -129,6 +129,13 @@ def _ws(op, device, ws, **shape):
     if ws is None:
         ws = workspace(need, device)
     return ws, ctypes.c_size_t(ws.numel())
+
+
+def stream_read_probe(src: torch.Tensor, sink: torch.Tensor) -> None:
+    """Measurement aid: one pass of plain 16-byte loads over `src` (see saap_stream_read_probe)."""
+    st = load_library().saap_stream_read_probe(_ptr(src), ctypes.c_size_t(src.numel() * src.element_size()), _ptr(sink),
+                                               ctypes.c_size_t(sink.numel() * sink.element_size()), _stream())
+    _check("saap_stream_read_probe", st)
 
 
 def assign_keys(x, centroids, bias=None, out=None, ws=None):

@@ -21,7 +21,6 @@
 namespace saap {
 namespace {
 
-constexpr int kKeysPerBatch = 4;   // keys a key processor has in flight per iteration
 constexpr int kMaxP = 128;         // workgroups per unit (workspace is sized for this)
 
 struct AttnParams {
@@ -38,6 +37,7 @@ struct AttnParams {
   unsigned* counters;     // [units], zero on entry and on exit
   long long rows;         // rows per kv unit
   int nseg;               // segments (visited buckets) per unit; list mode only
+  int max_chunks;         // upper bound on the chunks one workgroup processes (sizes the LDS tables)
   int B;
   int n_units;
   int P;
@@ -94,12 +94,62 @@ __device__ __forceinline__ void store_out(const AttnParams& p, int qrow, int e, 
   if (e == 0 && p.lse) p.lse[qrow] = l > 0.f ? (M + __log2f(l)) * kLn2 : -INFINITY;
 }
 
-// One batch of a key processor: kKeysPerBatch rows of K and V, and which of them are real.
-template <typename T>
+// One batch of a key processor: KB rows of K and V, and which of them are real keys.
+template <typename T, int KB>
 struct Batch {
-  Vec8<T> k[kKeysPerBatch], v[kKeysPerBatch];
+  Vec8<T> k[KB], v[KB];
   unsigned valid;   // bit i: slot i holds a key of the range
 };
+
+// One stage of the reduction of N partial sums over a 16-lane group.  The lane keeps the half
+// of the values selected by `bit` (its partner under the lane exchange CTRL keeps the other
+// half) and adds the partner's contribution: v[0 .. N/2) afterwards.
+template <int N, int CTRL>
+__device__ __forceinline__ void scatter_stage(float* v, bool bit) {
+#pragma unroll
+  for (int j = 0; j < N / 2; ++j) {
+    const float keep = bit ? v[N / 2 + j] : v[j];
+    const float give = bit ? v[j] : v[N / 2 + j];
+    v[j] = keep + dpp_mov<CTRL>(give);
+  }
+}
+template <int N, int CTRL>
+__device__ __forceinline__ void allreduce_stage(float* v) {
+#pragma unroll
+  for (int j = 0; j < N; ++j) v[j] += dpp_mov<CTRL>(v[j]);
+}
+// Sums each of C (4, 8 or 16) values over the 16 lanes of a group; lane s returns the total of
+// value (s & (C-1)).  45 instructions for C = 16 against 64 for an all-reduce of every value.
+template <int C>
+__device__ __forceinline__ float reduce_scatter16(float* v, int sub) {
+  if constexpr (C == 16) scatter_stage<16, kDppMirror>(v, sub & 8); else allreduce_stage<C, kDppMirror>(v);
+  if constexpr (C >= 8) scatter_stage<(C >= 16 ? 8 : C), kDppHalfMirror>(v, sub & 4); else allreduce_stage<C, kDppHalfMirror>(v);
+  scatter_stage<4, kDppXor2>(v, sub & 2);
+  scatter_stage<2, kDppXor1>(v, sub & 1);
+  return v[0];
+}
+// max / sum over the lanes s, s+ST, s+2ST, ... of a 16-lane group that hold the same head.
+template <int ST, int END>
+__device__ __forceinline__ float ror_max(float x) {
+  if constexpr (ST < END) {
+    x = fmaxf(x, dpp_mov<0x120 + ST>(x));
+    return ror_max<ST * 2, END>(x);
+  } else {
+    return x;
+  }
+}
+template <int ST, int END>
+__device__ __forceinline__ float ror_sum(float x) {
+  if constexpr (ST < END) {
+    x += dpp_mov<0x120 + ST>(x);
+    return ror_sum<ST * 2, END>(x);
+  } else {
+    return x;
+  }
+}
+// value of lane L of the 16-lane group, in every lane of the group
+template <int L>
+__device__ __forceinline__ float group_bcast(float x) { return dpp_mov<0x150 + L>(x); }
 
 template <typename T, int G, bool LIST, int NT>
 __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
@@ -108,8 +158,13 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   __shared__ int s_last;
 
   constexpr int nw = NT / 64;
+  constexpr int KB = G == 8 ? 2 : 4;            // keys a key processor has in flight per batch
+  constexpr int C = KB * G;                     // (key, head) combinations per batch: 4, 8 or 16
+  constexpr bool kPrefetch = sizeof(T) == 2;    // fp32 rows are too wide to double-buffer
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane & 15, grp = lane >> 4;
+  const int c_own = sub & (C - 1);              // the combination this lane owns after the reduction
+  const int i_own = c_own / G;                  // ... its key slot
   SAAP_TRACE(0);
   const int unit = blockIdx.x % p.n_units;
   const int wg = blockIdx.x / p.n_units;
@@ -132,8 +187,14 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
 #pragma unroll
   for (int g = 0; g < G; ++g) qv[g].load(reinterpret_cast<const T*>(p.q) + (size_t)(qrow0 + g) * kD + sub * 8);
 
+  constexpr int NG = nw * 4;            // key processors in the workgroup
+  constexpr int chunk = NG * KB;        // keys the workgroup consumes per batch
+  const int kp = wave * 4 + grp;
+
   int* pre = reinterpret_cast<int*>(smem);          // [nseg+1] exclusive prefix of run lengths
   int* rowoff = pre + (p.nseg + 1);                 // [nseg]   first row of each run
+  int* seglo = rowoff + p.nseg;                     // [max_chunks] run holding the first key of my k-th chunk
+  int* seghi = seglo + p.max_chunks;                // [max_chunks] run holding its last key
   int T_total;
   if (LIST) {
     const int nseg = p.nseg;
@@ -146,7 +207,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     if (p.stage) {
       // One memory round trip instead of two: the selected list and the unit's whole len/off
       // arrays are fetched together into LDS, the gather by bucket id then reads LDS.
-      int* s_len = rowoff + nseg;                       // [B]
+      int* s_len = seghi + p.max_chunks;                // [B]
       int* s_off = s_len + p.B;                         // [B]
       int sv[2], lv[8], ov[8];
 #pragma unroll
@@ -210,35 +271,48 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     if (nseg == 0 && tid == 0) pre[0] = 0;
     __syncthreads();
     T_total = pre[nseg];
+    // runs that hold the first and the last key of each of this workgroup's chunks, so that the
+    // per-key lookups in the loop search a handful of runs instead of all of them
+    for (int k = tid;; k += NT) {
+      const long long first = ((long long)wg + (long long)k * p.P) * chunk;
+      if (first >= T_total || k >= p.max_chunks) break;
+      const int v0 = (int)first;
+      const int v1 = (int)min((long long)T_total, first + chunk) - 1;
+      int a0 = 0, b0 = nseg, a1 = 0, b1 = nseg;
+      while (b0 - a0 > 1 || b1 - a1 > 1) {
+        const int m0 = (a0 + b0) >> 1, m1 = (a1 + b1) >> 1;
+        if (b0 - a0 > 1) { if (pre[m0] <= v0) a0 = m0; else b0 = m0; }
+        if (b1 - a1 > 1) { if (pre[m1] <= v1) a1 = m1; else b1 = m1; }
+      }
+      seglo[k] = a0;
+      seghi[k] = a1;
+    }
+    __syncthreads();
   } else {
     T_total = p.n_dense;
   }
   SAAP_TRACE(1);
 
-  float m[G], l[G], O[G][8];
+  // per lane: running maximum of its head, sum of its own (key slot, head) weights, and the
+  // output slices of all G heads
+  float m = kNegBig, l = 0.f, O[G][8];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    m[g] = kNegBig;
-    l[g] = 0.f;
+  for (int g = 0; g < G; ++g)
 #pragma unroll
     for (int e = 0; e < 8; ++e) O[g][e] = 0.f;
-  }
 
-  // The virtual key range [0,T) is cut into chunks of NG*kKeysPerBatch keys; chunk c belongs to
+  // The virtual key range [0,T) is cut into chunks of NG*KB keys; chunk c belongs to
   // workgroup c % P, so neighbouring workgroups stream neighbouring memory at any moment.
-  constexpr int NG = nw * 4;           // key processors in the workgroup
-  const int kp = wave * 4 + grp;
-  constexpr int chunk = NG * kKeysPerBatch;
+  // Virtual key of (this processor, slot i) of the chunk at `base` is base + i*NG + kp.
   const long long stride = (long long)chunk * p.P;
 
-  // Virtual key of (this processor, slot i) of the chunk at `base` is base + i*NG + kp.
-  auto load_batch = [&](long long base, Batch<T>& bt) {
+  auto load_batch = [&](long long base, int k, Batch<T, KB>& bt) {
     int row;
     {
-      long long vl = base + (sub & (kKeysPerBatch - 1)) * NG + kp;   // lane `sub` resolves slot sub%4
+      long long vl = base + (sub & (KB - 1)) * NG + kp;   // lane `sub` resolves slot sub % KB
       int v = (int)(vl < T_total ? vl : T_total - 1);
       if (LIST) {
-        int a = 0, b = p.nseg;
+        int a = seglo[k], b = seghi[k] + 1;
         while (b - a > 1) {
           const int mid = (a + b) >> 1;
           if (pre[mid] <= v) a = mid; else b = mid;
@@ -250,7 +324,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     }
     bt.valid = 0u;
 #pragma unroll
-    for (int i = 0; i < kKeysPerBatch; ++i) {
+    for (int i = 0; i < KB; ++i) {
       const int r = __shfl(row, (lane & 48) + i);
       if (base + i * NG + kp < T_total) bt.valid |= 1u << i;
       bt.k[i].load(Kb + (size_t)r * kD);
@@ -258,105 +332,127 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     }
   };
 
-  auto consume = [&](const Batch<T>& bt) {
-    float t[kKeysPerBatch][G];
+  auto consume = [&](const Batch<T, KB>& bt) {
+    // partial dot products of the lane's 8 features, all (key slot, head) combinations ...
+    float d[C];
 #pragma unroll
-    for (int i = 0; i < kKeysPerBatch; ++i)
+    for (int i = 0; i < KB; ++i)
+#pragma unroll
+      for (int g = 0; g < G; ++g) d[i * G + g] = bt.k[i].dot(qv[g]);
+    // ... reduced over the 16 lanes so that each lane ends up with ONE complete score
+    const float dot = reduce_scatter16<C>(d, sub);
+    const float t = (bt.valid >> i_own) & 1u ? dot * p.scale_log2 : -INFINITY;
+    // Algorithm 1, one step per batch: the head's running maximum lives in the lanes that own it
+    const float bm = ror_max<G, C>(t);
+    const float mn = fmaxf(m, bm);
+    if (__builtin_amdgcn_ballot_w64(mn > m) != 0ull) {      // some maximum moved: rescale (wave-uniform branch)
+      const float alpha = fast_exp2(m - mn);
+      l *= alpha;
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const float s = sum16(bt.k[i].dot(qv[g]));
-        t[i][g] = (bt.valid >> i) & 1u ? s * p.scale_log2 : -INFINITY;
+        float ag;
+        if constexpr (G == 1) ag = alpha; else ag = g == 0 ? group_bcast<0>(alpha) : g == 1 ? group_bcast<1>(alpha) : g == 2 ? group_bcast<2>(alpha) : g == 3 ? group_bcast<3>(alpha) : g == 4 ? group_bcast<4>(alpha) : g == 5 ? group_bcast<5>(alpha) : g == 6 ? group_bcast<6>(alpha) : group_bcast<7>(alpha);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) O[g][e] *= ag;
       }
-    // Algorithm 1: one running-maximum update for the batch
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float bm = t[0][g];
-#pragma unroll
-      for (int i = 1; i < kKeysPerBatch; ++i) bm = fmaxf(bm, t[i][g]);
-      const float mn = fmaxf(m[g], bm);
-      const float alpha = fast_exp2(m[g] - mn);
-      m[g] = mn;
-      l[g] *= alpha;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) O[g][e] *= alpha;
-#pragma unroll
-      for (int i = 0; i < kKeysPerBatch; ++i) t[i][g] = fast_exp2(t[i][g] - mn);
+      m = mn;
+    }
+    const float pw = fast_exp2(t - m);          // weight of the lane's own (key slot, head)
+    l += pw;
+    // every lane needs every weight of its group for the value update: broadcast from the owner
+    float pb[C];
+    pb[0] = group_bcast<0>(pw); pb[1] = group_bcast<1>(pw); pb[2] = group_bcast<2>(pw); pb[3] = group_bcast<3>(pw);
+    if constexpr (C >= 8) { pb[4] = group_bcast<4>(pw); pb[5] = group_bcast<5>(pw); pb[6] = group_bcast<6>(pw); pb[7] = group_bcast<7>(pw); }
+    if constexpr (C == 16) {
+      pb[8] = group_bcast<8>(pw); pb[9] = group_bcast<9>(pw); pb[10] = group_bcast<10>(pw); pb[11] = group_bcast<11>(pw);
+      pb[12] = group_bcast<12>(pw); pb[13] = group_bcast<13>(pw); pb[14] = group_bcast<14>(pw); pb[15] = group_bcast<15>(pw);
     }
 #pragma unroll
-    for (int i = 0; i < kKeysPerBatch; ++i) {
+    for (int i = 0; i < KB; ++i) {
       float vf[8];
       bt.v[i].to_float(vf);
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        l[g] += t[i][g];
+      for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) O[g][e] = fmaf(t[i][g], vf[e], O[g][e]);
-      }
+        for (int e = 0; e < 8; ++e) O[g][e] = fmaf(pb[i * G + g], vf[e], O[g][e]);
     }
   };
 
   {
     long long base = (long long)wg * chunk;
+    int k = 0;
     if (base < T_total) {
-      Batch<T> cur;
-      load_batch(base, cur);
-      for (base += stride; base < T_total; base += stride) {
-        Batch<T> nxt;
-        load_batch(base, nxt);     // in flight while the current batch is consumed
+      Batch<T, KB> cur;
+      load_batch(base, k, cur);
+      if constexpr (kPrefetch) {
+        for (base += stride, ++k; base < T_total; base += stride, ++k) {
+          Batch<T, KB> nxt;
+          load_batch(base, k, nxt);     // in flight while the current batch is consumed
+          consume(cur);
+          cur = nxt;
+        }
         consume(cur);
-        cur = nxt;
+      } else {
+        consume(cur);
+        for (base += stride, ++k; base < T_total; base += stride, ++k) {
+          load_batch(base, k, cur);
+          consume(cur);
+        }
       }
-      consume(cur);
     }
   }
 
   SAAP_TRACE(3);
-  // combine the four key processors of the wave
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float mw = fmaxf(m[g], __shfl_xor(m[g], 16));
-    mw = fmaxf(mw, __shfl_xor(mw, 32));
-    const float a = fast_exp2(m[g] - mw);
-    m[g] = mw;
-    l[g] *= a;
-    l[g] += __shfl_xor(l[g], 16);
-    l[g] += __shfl_xor(l[g], 32);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float o = O[g][e] * a;
-      o += __shfl_xor(o, 16);
-      o += __shfl_xor(o, 32);
-      O[g][e] = o;
-    }
-  }
+  // the head's sum of weights: add up the key slots (lanes s, s+G, ... of the group)
+  l = ror_sum<G, C>(l);
 
-  // waves -> LDS (the prefix arrays are dead from here on)
+  // key processors -> LDS (the index arrays are dead from here on)
   SAAP_TRACE(9);
   __syncthreads();
   SAAP_TRACE(10);
-  float* w_o = reinterpret_cast<float*>(smem);            // [nw][G][d]
-  float* w_m = w_o + nw * G * kD;                         // [nw][G]
-  float* w_l = w_m + nw * G;                              // [nw][G]
-  if (grp == 0) {
+  float* w_o = reinterpret_cast<float*>(smem);            // [NG][G][d] unnormalised outputs
+  float* w_m = w_o + NG * G * kD;                         // [NG][G] maxima, then weights 2^(m - M)
+  float* w_l = w_m + NG * G;                              // [NG][G] sums of weights
+  float* w_M = w_l + NG * G;                              // [G] workgroup maximum
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) w_o[(wave * G + g) * kD + sub * 8 + e] = O[g][e];
-      if (sub == 0) {
-        w_m[wave * G + g] = m[g];
-        w_l[wave * G + g] = l[g];
-      }
-    }
+  for (int g = 0; g < G; ++g) {
+    float4* dst = reinterpret_cast<float4*>(w_o + (kp * G + g) * kD + sub * 8);
+    dst[0] = make_float4(O[g][0], O[g][1], O[g][2], O[g][3]);
+    dst[1] = make_float4(O[g][4], O[g][5], O[g][6], O[g][7]);
+  }
+  if (sub < G) {            // lane `sub` of a group owns head `sub` (key slot 0)
+    w_m[kp * G + sub] = m;
+    w_l[kp * G + sub] = l;
   }
   __syncthreads();
   SAAP_TRACE(11);
-
+  // weights 2^(m - M) of the NG partial results, NG*G <= NT/2 of them: one per thread
+  {
+    const bool has = tid < NG * G;
+    float wgt = 0.f, Mh = kNegBig;
+    if (has) {
+      const int g = tid % G;
+#pragma unroll
+      for (int j = 0; j < NG; ++j) Mh = fmaxf(Mh, w_m[j * G + g]);
+      wgt = fast_exp2(w_m[tid] - Mh);
+    }
+    __syncthreads();          // every maximum is read before any is overwritten
+    if (has) {
+      w_m[tid] = wgt;
+      if (tid < G) w_M[tid] = Mh;
+    }
+    __syncthreads();
+  }
   for (int x = tid; x < G * kD; x += NT) {
     const int g = x / kD, e = x % kD;
-    float M, L, Ov;
-    lse_merge(
-        nw, [&](int w) { return w_m[w * G + g]; }, [&](int w) { return w_l[w * G + g]; },
-        [&](int w) { return w_o[(w * G + g) * kD + e]; }, M, L, Ov);
+    float L = 0.f, Ov = 0.f;
+#pragma unroll
+    for (int j = 0; j < NG; ++j) {
+      const float w = w_m[j * G + g];
+      L = fmaf(w, w_l[j * G + g], L);
+      Ov = fmaf(w, w_o[(j * G + g) * kD + e], Ov);
+    }
+    const float M = w_M[g];
     if (p.P == 1) {
       store_out(p, qrow0 + g, e, M, L, Ov);
     } else {
@@ -493,17 +589,19 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
 }
 
 struct LaunchPlan {
-  int P, threads, stage;
+  int P, threads, stage, max_chunks;
   size_t lds;
 };
 
-LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, int G, int nseg, bool list, int B,
-                       bool has_selection) {
-  int threads = env_int("SAAP_ATTN_THREADS", 512);
+LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, long long max_keys_per_unit, int G, int nseg,
+                       bool list, int B, bool has_selection) {
+  int threads = env_int("SAAP_ATTN_THREADS", 0);
   if (threads != 256 && threads != 512) threads = 512;
-  const int wgs_per_cu = env_int("SAAP_ATTN_WGS_PER_CU", threads == 256 ? 3 : 1);
+  if (G == 8) threads = 256;                            // keeps the per-processor partials within LDS
+  const int kb = G == 8 ? 2 : 4;
+  const int wgs_per_cu = env_int("SAAP_ATTN_WGS_PER_CU", threads == 256 ? 2 : 1);
   const int cus = device_cus();
-  const long long chunk = (long long)(threads / 16) * kKeysPerBatch;   // keys per workgroup batch
+  const long long chunk = (long long)(threads / 16) * kb;   // keys per workgroup batch
   long long P = (long long)cus * wgs_per_cu / n_units;
   const long long by_work = (est_keys_per_unit + chunk - 1) / chunk;
   if (P > by_work) P = by_work;
@@ -514,10 +612,11 @@ LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, int G, int nseg
   LaunchPlan lp;
   lp.P = (int)P;
   lp.threads = threads;
-  size_t a = list ? (size_t)(2 * nseg + 1) * sizeof(int) : 0;
+  lp.max_chunks = (int)(((max_keys_per_unit + chunk - 1) / chunk + P - 1) / P + 1);
+  size_t a = list ? (size_t)(2 * nseg + 1 + 2 * lp.max_chunks) * sizeof(int) : 0;
   lp.stage = list && has_selection && nseg <= 2 * threads && B <= 8 * threads && env_int("SAAP_ATTN_STAGE", 1);
   if (lp.stage) a += (size_t)2 * B * sizeof(int);
-  const size_t b = (size_t)(threads / 64) * G * (kD + 2) * sizeof(float);
+  const size_t b = (size_t)(threads / 16) * G * (kD + 2) * sizeof(float) + G * sizeof(float);
   const size_t c = (size_t)(P * G + 2 * G + 4) * sizeof(float) + (size_t)threads * sizeof(float4);
   lp.lds = a > b ? a : b;
   if (c > lp.lds) lp.lds = c;
@@ -617,9 +716,10 @@ extern "C" int32_t saap_sparse_decode_attention(const void* q, const void* Ksort
   p.Hq = Hq; p.Hkv = Hkv; p.independent = indep ? 1 : 0; p.out_bf16 = out_dtype == SAAP_BF16;
   p.n_dense = 0; p.scale_log2 = scale * kLog2e;
   const long long est = (long long)Ncap * nprobe / B;
-  LaunchPlan lp = plan_launch((int)units, est, G, nprobe, true, B, nprobe > 0);
+  LaunchPlan lp = plan_launch((int)units, est, Ncap, G, nprobe, true, B, nprobe > 0);
   p.P = lp.P;
   p.stage = lp.stage;
+  p.max_chunks = lp.max_chunks;
   return launch_attn<true>(p, lp, G, dtype, static_cast<hipStream_t>(stream));
 }
 
@@ -647,9 +747,10 @@ extern "C" int32_t saap_dense_decode_attention(const void* q, const void* K, con
   p.rows = N; p.nseg = off ? B : 0; p.B = B; p.n_units = (int)units;
   p.Hq = Hq; p.Hkv = Hkv; p.independent = 0; p.out_bf16 = out_dtype == SAAP_BF16;
   p.n_dense = N; p.scale_log2 = scale * kLog2e;
-  LaunchPlan lp = plan_launch((int)units, N, G, p.nseg, off != nullptr, B, false);
+  LaunchPlan lp = plan_launch((int)units, N, N, G, p.nseg, off != nullptr, B, false);
   p.P = lp.P;
   p.stage = 0;
+  p.max_chunks = lp.max_chunks;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   return off ? launch_attn<true>(p, lp, G, dtype, hs) : launch_attn<false>(p, lp, G, dtype, hs);
 }

@@ -28,11 +28,38 @@ __global__ void zero_words_kernel(uint32_t* p, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0u;
 }
+// Reads `n` 16-byte words once (grid-stride, four loads in flight per lane) and folds them into
+// one word per workgroup: the streaming-read ceiling of the device for the benchmark report.
+__global__ void __launch_bounds__(512) stream_read_kernel(const uint4* __restrict__ src, size_t n, uint32_t* __restrict__ sink) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  uint32_t acc = 0u;
+  for (; i + 3 * stride < n; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  }
+  for (; i < n; i += stride) {
+    const uint4 a = src[i];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) acc ^= __shfl_xor(acc, o);
+  if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], acc);
+}
 }  // namespace
 
 }  // namespace saap
 
 using namespace saap;
+
+extern "C" int32_t saap_stream_read_probe(const void* src, size_t bytes, void* sink, size_t sink_bytes, void* stream) {
+  if (!src || !sink || !aligned16(src) || !aligned16(sink) || bytes < 16) return SAAP_INVALID_ARG;
+  const unsigned grid = (unsigned)(device_cus() * 4);
+  if (sink_bytes < (size_t)grid * sizeof(uint32_t)) return SAAP_WORKSPACE_TOO_SMALL;
+  hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(512), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint4*>(src), bytes / 16, static_cast<uint32_t*>(sink));
+  return launch_status();
+}
 
 extern "C" size_t saap_workspace_bytes(int32_t op, const saap_shape* sh) {
   if (!sh) return 0;
