@@ -61,15 +61,6 @@ __device__ __forceinline__ void coherent_store(float* p, float v) {
 // Wait until every outstanding store of this wave has been acknowledged.
 __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-__device__ __forceinline__ int wave_incl_scan(int x, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    int y = __shfl_up(x, o);
-    if (lane >= o) x += y;
-  }
-  return x;
-}
-
 // Merge `n` partial results (m_i, l_i, o_i[e]) for one (head, feature) pair:
 // M = max m_i; o = sum 2^(m_i-M) o_i; l = sum 2^(m_i-M) l_i   (Algorithm 2, symmetric form).
 template <typename FM, typename FL, typename FO>
@@ -256,7 +247,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
         mine += ln;
       }
     }
-    const int incl = wave_incl_scan(mine, lane);
+    const int incl = (int)wave_prefix_sum((unsigned)mine);
     if (lane == 63) s_wsum[wave] = incl;
     __syncthreads();
     int base = 0;

@@ -67,6 +67,39 @@ __device__ __forceinline__ float sum16(float x) {
   return x;
 }
 
+// ---- wave-wide scans and reductions on DPP (no LDS crossbar round trips) ------------------------
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ unsigned dpp_u32(unsigned x) {
+  return (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xf, true);
+}
+// Inclusive prefix sum over the 64 lanes (lane order).
+__device__ __forceinline__ unsigned wave_prefix_sum(unsigned x) {
+  x += dpp_u32<0x111>(x);          // row_shr:1 (lanes shifted in from outside the row read 0)
+  x += dpp_u32<0x112>(x);          // row_shr:2
+  x += dpp_u32<0x114>(x);          // row_shr:4
+  x += dpp_u32<0x118>(x);          // row_shr:8
+  x += dpp_u32<0x142, 0xa>(x);     // row_bcast:15 into rows 1 and 3
+  x += dpp_u32<0x143, 0xc>(x);     // row_bcast:31 into rows 2 and 3
+  return x;
+}
+// Bitwise AND / OR over the 64 lanes; every lane gets the result.
+__device__ __forceinline__ unsigned wave_and(unsigned x) {
+  x &= dpp_u32<kDppXor1>(x);
+  x &= dpp_u32<kDppXor2>(x);
+  x &= dpp_u32<kDppHalfMirror>(x);
+  x &= dpp_u32<kDppMirror>(x);
+  return (unsigned)__builtin_amdgcn_readlane((int)x, 0) & (unsigned)__builtin_amdgcn_readlane((int)x, 16) &
+         (unsigned)__builtin_amdgcn_readlane((int)x, 32) & (unsigned)__builtin_amdgcn_readlane((int)x, 48);
+}
+__device__ __forceinline__ unsigned wave_or(unsigned x) {
+  x |= dpp_u32<kDppXor1>(x);
+  x |= dpp_u32<kDppXor2>(x);
+  x |= dpp_u32<kDppHalfMirror>(x);
+  x |= dpp_u32<kDppMirror>(x);
+  return (unsigned)__builtin_amdgcn_readlane((int)x, 0) | (unsigned)__builtin_amdgcn_readlane((int)x, 16) |
+         (unsigned)__builtin_amdgcn_readlane((int)x, 32) | (unsigned)__builtin_amdgcn_readlane((int)x, 48);
+}
+
 // Eight consecutive elements of a row, as loaded by one lane.
 template <typename T> struct Vec8;
 template <> struct Vec8<float> {

@@ -77,12 +77,7 @@ offscan_kernel(const int32_t* __restrict__ len, int32_t* __restrict__ off, int B
   int32_t* o = off + (size_t)unit * (B + 1);
   int mine = 0;
   for (int b = b0; b < b1; ++b) mine += l[b] + slack;
-  int incl = mine;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const int y = __shfl_up(incl, d);
-    if (lane >= d) incl += y;
-  }
+  const int incl = (int)wave_prefix_sum((unsigned)mine);
   if (lane == 63) s_wsum[wave] = incl;
   __syncthreads();
   int run = incl - mine;

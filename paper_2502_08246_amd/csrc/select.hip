@@ -8,7 +8,8 @@
 //   * radix kernel (nprobe well below B): a most-significant-digit radix select over the 32-bit
 //     score images (four passes of 8 bits, LDS histogram + one-wave scan) finds the score of the
 //     nprobe-th bucket; buckets above it, and the lowest-id buckets equal to it, are compacted
-//     and only those nprobe keys are sorted (inside one wavefront when nprobe <= 64).
+//     and only those nprobe keys are put in order (by counting larger keys when nprobe <= 64,
+//     by a bitonic network otherwise).
 //   * sort kernel (nprobe close to B): all keys are sorted in LDS with a bitonic network.
 // Both give exactly the (score descending, id ascending) order of the definition.
 #include "common.h"
@@ -73,23 +74,6 @@ select_kernel(const float* __restrict__ scores, int32_t* __restrict__ selected, 
 }
 
 
-// Bitonic sort (descending) of n <= 64 keys held one per lane of a single wavefront.
-__device__ __forceinline__ unsigned long long wave_sort_desc(unsigned long long key, int lane) {
-  for (int k = 2; k <= 64; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      const unsigned lo = __shfl_xor((unsigned)(key & 0xFFFFFFFFull), j);
-      const unsigned hi = __shfl_xor((unsigned)(key >> 32), j);
-      const unsigned long long other = ((unsigned long long)hi << 32) | lo;
-      const bool lower_lane = (lane & j) == 0;
-      const bool descending = (lane & k) == 0;
-      const bool take_max = lower_lane == descending;
-      const unsigned long long mx = key > other ? key : other, mn = key > other ? other : key;
-      key = take_max ? mx : mn;
-    }
-  }
-  return key;
-}
-
 template <int EPT>
 __global__ void __launch_bounds__(1024)
 select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ selected, int Hq, int Hkv, int B,
@@ -131,11 +115,8 @@ select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ sele
 #pragma unroll
     for (int e = 0; e < EPT; ++e)
       if (tid + e * nt < B) { a &= key[e]; o |= key[e]; }
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) {
-      a &= __shfl_xor(a, d);
-      o |= __shfl_xor(o, d);
-    }
+    a = wave_and(a);
+    o = wave_or(o);
     if (lane == 0) { atomicAnd(&s_and, a); atomicOr(&s_or, o); }
   }
   __syncthreads();
@@ -160,20 +141,16 @@ select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ sele
       if (tid + e * nt < B && (key[e] & mask) == prefix) atomicAdd(&hist[(key[e] >> shift) & dmask], 1u);
     __syncthreads();
     if (wave == 0) {
-      const unsigned c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
-      const unsigned tot = c0 + c1 + c2 + c3;
-      unsigned incl = tot;                       // inclusive sum over lanes >= this one
+      // lane i looks at bins 255-4i .. 252-4i, so a prefix sum over the lanes counts the
+      // buckets in higher bins
+      const int top = 255 - 4 * lane;
+      const unsigned c[4] = {hist[top], hist[top - 1], hist[top - 2], hist[top - 3]};
+      const unsigned tot = c[0] + c[1] + c[2] + c[3];
+      unsigned cum = wave_prefix_sum(tot) - tot;
 #pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const unsigned y = __shfl_down(incl, o);
-        if (lane + o < 64) incl += y;
-      }
-      unsigned cum = incl - tot;                 // buckets in bins above this lane's four
-      const unsigned c[4] = {c0, c1, c2, c3};
-#pragma unroll
-      for (int b = 3; b >= 0; --b) {
+      for (int b = 0; b < 4; ++b) {
         if (cum < k_rem && cum + c[b] >= k_rem) {
-          s_digit = (unsigned)(4 * lane + b);
+          s_digit = (unsigned)(top - b);
           s_krem = k_rem - cum;
         }
         cum += c[b];
@@ -221,12 +198,15 @@ select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ sele
   SAAP_TRACE(3);
   int32_t* out = selected + (size_t)unit * nprobe;
   if (n_sort <= 64) {
-    if (wave == 0) {
-      unsigned long long k = lane < n_sort ? sortbuf[lane] : 0ull;
-      k = wave_sort_desc(k, lane);
-      if (lane < nprobe) out[lane] = (int32_t)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull));
-      SAAP_TRACE(4);
+    // keys are distinct: the place of a key is the number of larger keys
+    if (tid < nprobe) {
+      const unsigned long long mine = sortbuf[tid];
+      int rank = 0;
+#pragma unroll 8
+      for (int j = 0; j < nprobe; ++j) rank += sortbuf[j] > mine ? 1 : 0;
+      out[rank] = (int32_t)(0xFFFFFFFFu - (unsigned)(mine & 0xFFFFFFFFull));
     }
+    SAAP_TRACE(4);
     return;
   }
   for (int k = 2; k <= n_sort; k <<= 1) {

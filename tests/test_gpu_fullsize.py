@@ -1,0 +1,217 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times (default
+workspace, default launch plan, outputs preallocated, all KV heads at once).  Where the oracle
+can finish in seconds it checks everything; otherwise it checks a seeded sample of rows / heads
+that it computes one by one, plus properties that hold at any size (CSR invariants, nprobe = B
+equals dense)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from synth import gen
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+SCALE = 1.0 / math.sqrt(128.0)
+
+
+@pytest.fixture(scope="module")
+def saap():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the -m gpu tests need a real device")
+    import paper_2502_08246_amd as lib
+    lib.load_library()
+    ref.set_threads(16)
+    return lib
+
+
+def h(t):
+    return gen.to_host_f32(t)
+
+
+def close(got, want, atol=2e-3, rtol=1e-2):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    err = np.abs(got - want)
+    assert (err <= atol + rtol * np.abs(want)).all(), f"max err {err.max():.3e}"
+
+
+def csr_invariants(ids, off, ln, idx, B, slack):
+    """Properties of the index that hold at any size, checked with torch on the device."""
+    S, Hkv, N = ids.shape
+    cnt = torch.zeros(S * Hkv, B, dtype=torch.int64, device=ids.device)
+    cnt.scatter_add_(1, ids.view(S * Hkv, N).long(), torch.ones(S * Hkv, N, dtype=torch.int64, device=ids.device))
+    assert torch.equal(cnt.view(S, Hkv, B), ln.long())
+    assert (off[..., 0] == 0).all()
+    assert torch.equal((off[..., 1:] - off[..., :-1]).long(), ln.long() + slack)
+    members = idx >= 0
+    assert int(members.sum()) == S * Hkv * N
+    srt = torch.sort(torch.where(members, idx, torch.full_like(idx, 2 ** 30)), dim=-1).values[..., :N]
+    assert torch.equal(srt, torch.arange(N, device=idx.device, dtype=idx.dtype).expand(S, Hkv, N))
+
+
+def test_cfg1_full_size_every_call(saap):
+    """BASELINE config 1 (the benchmark workload): all calls at full size against the oracle."""
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"]
+    cache = gen.make_cache(cfg, 0, DEV)
+    cent = gen.make_centroids(cfg, 0, DEV)
+    xq, q = gen.make_queries(cfg, 0, DEV, n_steps=3)
+    W1, b1, W2, b2 = gen.make_classifier(cfg, 0, DEV)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, 0)
+    torch.cuda.synchronize()
+    csr_invariants(ids, off, ln, idx, cfg.B, 0)
+    # assignment: two whole heads against the oracle, bit for bit
+    hx, hc = h(cache["x_keys"][:, :2]), h(cent[:2])
+    r_ids2 = ref.assign_keys(hx, hc)
+    got = ids.cpu().numpy()
+    assert np.array_equal(got[:, :2], r_ids2), f"{(got[:, :2] != r_ids2).sum()} ids differ"
+    # index: exact against the oracle's build from the GPU's ids (all heads)
+    hK, hV = h(cache["K"]), h(cache["V"])
+    r_off, r_ln, r_idx, rKs, rVs = ref.build_bucket_index(got, hK, hV, cfg.B, 0)
+    assert np.array_equal(off.cpu().numpy(), r_off) and np.array_equal(ln.cpu().numpy(), r_ln)
+    assert np.array_equal(idx.cpu().numpy(), r_idx)
+    assert np.array_equal(h(Ks), rKs) and np.array_equal(h(Vs), rVs)
+    del rKs, rVs
+    scores = torch.empty(cfg.S, cfg.Hq, cfg.B, dtype=torch.float32, device=DEV)
+    sel = torch.empty(cfg.S, cfg.Hkv, cfg.nprobe, dtype=torch.int32, device=DEV)
+    out = torch.empty(cfg.S, cfg.Hq, cfg.d, dtype=torch.float32, device=DEV)
+    lse = torch.empty(cfg.S, cfg.Hq, dtype=torch.float32, device=DEV)
+    for t in range(3):
+        saap.classify_queries(xq[t], W1, b1, W2, b2, cfg.Hkv, out=scores)
+        saap.select_buckets(scores, cfg.Hkv, cfg.nprobe, out=sel)
+        saap.sparse_decode_attention(q[t], Ks, Vs, off, ln, sel, SCALE, out=out, lse=lse)
+        o_d, l_d = saap.dense_decode_attention(q[t], Ks, Vs, SCALE, off=off, ln=ln)
+        torch.cuda.synchronize()
+        r_scores = ref.classify_queries(h(xq[t]), h(W1), h(b1), h(W2), h(b2), cfg.Hkv)
+        np.testing.assert_allclose(scores.cpu().numpy(), r_scores, rtol=1e-4, atol=1e-9)
+        r_sel = ref.select_buckets(scores.cpu().numpy(), cfg.Hkv, cfg.nprobe)
+        assert np.array_equal(sel.cpu().numpy(), r_sel)
+        ro, rl = ref.sparse_decode_attention(h(q[t]), hK, hV, r_off, r_ln, r_idx, r_sel, SCALE)
+        close(out.cpu().numpy(), ro)
+        close(lse.cpu().numpy(), rl)
+        rd, rdl = ref.dense_decode_attention(h(q[t]), hK, hV, SCALE)
+        close(o_d.cpu().numpy(), rd)
+        close(l_d.cpu().numpy(), rdl)
+
+
+def test_cfg2_skewed_500k_sampled(saap):
+    """BASELINE config 2: N = 500000 (ragged), B = 4096, Dirichlet(0.3) bucket sizes, nprobe sweep."""
+    cfg = gen.CONFIGS["cfg2_llama8b_500k_skew"]
+    cache = gen.make_cache(cfg, 0, DEV)
+    cent = gen.make_centroids(cfg, 0, DEV)
+    xq, q = gen.make_queries(cfg, 0, DEV, n_steps=1)
+    W1, b1, W2, b2 = gen.make_classifier(cfg, 0, DEV)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, 0)
+    torch.cuda.synchronize()
+    csr_invariants(ids, off, ln, idx, cfg.B, 0)
+    # assignment: a seeded sample of rows of every head, one by one on the oracle
+    rng = np.random.default_rng(7)
+    rows = np.sort(rng.choice(cfg.N, size=4096, replace=False))
+    hx = h(cache["x_keys"][:, :, torch.from_numpy(rows).to(DEV)])
+    want = ref.assign_keys(hx, h(cent))
+    assert np.array_equal(ids.cpu().numpy()[:, :, rows], want)
+    # rows of the sorted cache are the rows the index names
+    sample = torch.from_numpy(rng.choice(cfg.N, size=2048, replace=False)).to(DEV)
+    src = idx[0, 3, sample].long()
+    assert torch.equal(Ks[0, 3, sample], cache["K"][0, 3, src]) and torch.equal(Vs[0, 3, sample], cache["V"][0, 3, src])
+    del cache["x_keys"]
+    scores = saap.classify_queries(xq[0], W1, b1, W2, b2, cfg.Hkv)
+    hK, hV = h(cache["K"]), h(cache["V"])
+    h_off, h_ln, h_idx = off.cpu().numpy(), ln.cpu().numpy(), idx.cpu().numpy()
+    for nprobe in (41, 82, 205, 410):
+        sel = saap.select_buckets(scores, cfg.Hkv, nprobe)
+        out, lse = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln, sel, SCALE)
+        torch.cuda.synchronize()
+        r_sel = ref.select_buckets(scores.cpu().numpy(), cfg.Hkv, nprobe)
+        assert np.array_equal(sel.cpu().numpy(), r_sel)
+        ro, rl = ref.sparse_decode_attention(h(q[0]), hK, hV, h_off, h_ln, h_idx, r_sel, SCALE)
+        close(out.cpu().numpy(), ro)
+        close(lse.cpu().numpy(), rl)
+    # all buckets = dense attention, at full size, GPU against GPU and against the oracle
+    sel_all = saap.select_buckets(scores, cfg.Hkv, cfg.B)
+    o_all, l_all = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln, sel_all, SCALE)
+    o_d, l_d = saap.dense_decode_attention(q[0], cache["K"], cache["V"], SCALE)
+    torch.cuda.synchronize()
+    rd, rdl = ref.dense_decode_attention(h(q[0]), hK, hV, SCALE)
+    close(o_all.cpu().numpy(), rd)
+    close(o_d.cpu().numpy(), rd)
+    close(l_all.cpu().numpy(), rdl)
+
+
+def test_cfg3_batch8_prefill_decode_append(saap):
+    """BASELINE config 3: batch 8, prefill assignment + index, then decode steps that append the
+    step's key.  The oracle follows two of the eight sequences in full."""
+    cfg = gen.CONFIGS["cfg3_batch8_128k"]
+    slack, steps = 16, 4
+    cache = gen.make_cache(cfg, 0, DEV)
+    cent = gen.make_centroids(cfg, 0, DEV)
+    xq, q = gen.make_queries(cfg, 0, DEV, n_steps=steps)
+    W1, b1, W2, b2 = gen.make_classifier(cfg, 0, DEV)
+    new = gen.make_cache(cfg.replace(N=steps), 99, DEV)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, slack)
+    torch.cuda.synchronize()
+    csr_invariants(ids, off, ln, idx, cfg.B, slack)
+    seqs = [1, 6]
+    st = torch.tensor(seqs, device=DEV)
+    # oracle state for the two sequences, built from the GPU's ids (checked on a sample below)
+    rows = np.sort(np.random.default_rng(3).choice(cfg.N, size=2048, replace=False))
+    want = ref.assign_keys(h(cache["x_keys"][st][:, :, torch.from_numpy(rows).to(DEV)]), h(cent))
+    assert np.array_equal(ids[st].cpu().numpy()[:, :, rows], want)
+    Kall = torch.cat([cache["K"][st], new["K"][st]], dim=2)
+    Vall = torch.cat([cache["V"][st], new["V"][st]], dim=2)
+    hKall, hVall = h(Kall), h(Vall)
+    r_off, r_ln, r_idx, rKs, rVs = ref.build_bucket_index(ids[st].cpu().numpy(), hKall[:, :, :cfg.N], hVall[:, :, :cfg.N], cfg.B, slack)
+    assert np.array_equal(off[st].cpu().numpy(), r_off) and np.array_equal(idx[st].cpu().numpy(), r_idx)
+    hc = h(cent)
+    for t in range(steps):
+        scores = saap.classify_queries(xq[t], W1, b1, W2, b2, cfg.Hkv)
+        sel = saap.select_buckets(scores, cfg.Hkv, cfg.nprobe)
+        out, lse = saap.sparse_decode_attention(q[t], Ks, Vs, off, ln, sel, SCALE)
+        pos = torch.full((cfg.S,), cfg.N + t, dtype=torch.int32, device=DEV)
+        xn, kn, vn = (new[k][:, :, t].contiguous() for k in ("x_keys", "K", "V"))
+        nid, flag = saap.append_keys(xn, kn, vn, pos, cent, None, off, ln, idx, Ks, Vs)
+        torch.cuda.synchronize()
+        assert flag[0].item() == 0
+        r_sel = ref.select_buckets(scores[st].cpu().numpy(), cfg.Hkv, cfg.nprobe)
+        assert np.array_equal(sel[st].cpu().numpy(), r_sel)
+        ro, rl = ref.sparse_decode_attention(h(q[t][st]), hKall, hVall, r_off, r_ln, r_idx, r_sel, SCALE)
+        close(out[st].cpu().numpy(), ro)
+        close(lse[st].cpu().numpy(), rl)
+        rid, rflag = ref.append_keys(h(xn[st]), h(kn[st]), h(vn[st]), pos[st].cpu().numpy(), hc, None, r_off, r_ln, r_idx, rKs, rVs)
+        assert rflag == 0 and np.array_equal(nid[st].cpu().numpy(), rid)
+        assert np.array_equal(ln[st].cpu().numpy(), r_ln) and np.array_equal(idx[st].cpu().numpy(), r_idx)
+
+
+def test_cfg4_one_layer_262k(saap):
+    """BASELINE config 4, one of its 32 layers: N = 262144, B = 2048, nprobe = 102."""
+    cfg = gen.CONFIGS["cfg4_layer_262k"]
+    cache = gen.make_cache(cfg, 5, DEV)
+    cent = gen.make_centroids(cfg, 5, DEV)
+    xq, q = gen.make_queries(cfg, 5, DEV, n_steps=1)
+    W1, b1, W2, b2 = gen.make_classifier(cfg, 5, DEV)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, 0)
+    scores = saap.classify_queries(xq[0], W1, b1, W2, b2, cfg.Hkv)
+    sel = saap.select_buckets(scores, cfg.Hkv, cfg.nprobe)
+    out, lse = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln, sel, SCALE)
+    o_d, l_d = saap.dense_decode_attention(q[0], cache["K"], cache["V"], SCALE)
+    torch.cuda.synchronize()
+    csr_invariants(ids, off, ln, idx, cfg.B, 0)
+    rows = np.sort(np.random.default_rng(11).choice(cfg.N, size=4096, replace=False))
+    want = ref.assign_keys(h(cache["x_keys"][:, :, torch.from_numpy(rows).to(DEV)]), h(cent))
+    assert np.array_equal(ids.cpu().numpy()[:, :, rows], want)
+    r_scores = ref.classify_queries(h(xq[0]), h(W1), h(b1), h(W2), h(b2), cfg.Hkv)
+    np.testing.assert_allclose(scores.cpu().numpy(), r_scores, rtol=1e-4, atol=1e-9)
+    r_sel = ref.select_buckets(scores.cpu().numpy(), cfg.Hkv, cfg.nprobe)
+    assert np.array_equal(sel.cpu().numpy(), r_sel)
+    hK, hV = h(cache["K"]), h(cache["V"])
+    ro, rl = ref.sparse_decode_attention(h(q[0]), hK, hV, off.cpu().numpy(), ln.cpu().numpy(), idx.cpu().numpy(), r_sel, SCALE)
+    close(out.cpu().numpy(), ro)
+    close(lse.cpu().numpy(), rl)
+    rd, rdl = ref.dense_decode_attention(h(q[0]), hK, hV, SCALE)
+    close(o_d.cpu().numpy(), rd)
+    close(l_d.cpu().numpy(), rdl)
