@@ -19,7 +19,8 @@ namespace saap {
 namespace {
 
 constexpr int kRowsPerWg = 256;   // keys per workgroup of the mfma kernel (4 waves x 64)
-constexpr int kCentTile = 32;     // centroids per LDS tile
+constexpr int kCentTile = 32;     // centroids per matrix tile
+constexpr int kSlab = 64;         // centroids per LDS slab (two matrix tiles)
 constexpr int kPitch = 136;       // bf16 elements per LDS row (272 bytes: conflict-free b128 reads)
 
 template <typename T> __device__ __forceinline__ double to_f64(T v);
@@ -53,11 +54,11 @@ cent_norm_kernel(const bf16_t* __restrict__ cent, float* __restrict__ cmax, int 
 }
 
 template <bool HAS_BIAS>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent, const float* __restrict__ bias,
                    const float* __restrict__ cmax, int32_t* __restrict__ ids, int32_t* __restrict__ flagged,
                    unsigned* __restrict__ n_flagged, int Hkv, int N, int B, float tol) {
-  __shared__ __align__(16) bf16_t s_c[2][kCentTile * kPitch];
+  __shared__ __align__(16) bf16_t s_c[2][kSlab * kPitch];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int unit = blockIdx.y, h = unit % Hkv;
   const int col = lane & 31, half = lane >> 5;
@@ -87,21 +88,23 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
     xnorm2[rt] = s;
   }
 
-  // centroid tile loader: 32 rows x 16 pieces of 16 bytes = 512 pieces, two per thread
-  const int n_tiles = (B + kCentTile - 1) / kCentTile;
-  uint4 stage[2];
+  // Centroids stream through LDS in slabs of kSlab = 64 (two matrix tiles of 32), double
+  // buffered: a slab is 1024 pieces of 16 bytes, four per thread, fetched into registers one
+  // slab ahead (a slab's worth of matrix work covers the L2 latency) and stored after the compute.
+  const int n_slabs = (B + kSlab - 1) / kSlab;
+  uint4 stage[kSlab / 16];
   auto fetch = [&](int t) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < kSlab / 16; ++i) {
       const int piece = tid + i * 256, r = piece >> 4, pc = piece & 15;
-      int b = t * kCentTile + r;
-      if (b >= B) b = 0;   // padding repeats centroid 0: it can tie with bucket 0 but never beat it
+      int b = t * kSlab + r;
+      if (b >= B) b = 0;   // padding repeats centroid 0; a padded winner is re-scored (id >= B below)
       stage[i] = *reinterpret_cast<const uint4*>(cu + (size_t)b * kD + pc * 8);
     }
   };
   auto stash = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < kSlab / 16; ++i) {
       const int piece = tid + i * 256, r = piece >> 4, pc = piece & 15;
       *reinterpret_cast<uint4*>(&s_c[buf][r * kPitch + pc * 8]) = stage[i];
     }
@@ -120,26 +123,28 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
     best_tile[rt] = 0;
   }
 
-  for (int t = 0; t < n_tiles; ++t) {
-    const int buf = t & 1;
-    if (t + 1 < n_tiles) fetch(t + 1);
-    // 32x32 accumulator as 16 floats; the builtin wants one 16-wide vector
-    typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-    f32x16_t c0 = {0}, c1 = {0};
+  typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+  // scores of matrix tile `sub` of the slab in `buf`: two 32x32 accumulators (the wave's two key tiles)
+  auto tile_mfma = [&](int buf, int sub, f32x16_t& c0, f32x16_t& c1) {
+    c0 = (f32x16_t){0};
+    c1 = (f32x16_t){0};
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
-      const uint4 raw = *reinterpret_cast<const uint4*>(&s_c[buf][col * kPitch + st * 16 + half * 8]);
+      const uint4 raw = *reinterpret_cast<const uint4*>(&s_c[buf][(sub * kCentTile + col) * kPitch + st * 16 + half * 8]);
       const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw);
       c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[0][st], c0, 0, 0, 0);
       c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[1][st], c1, 0, 0, 0);
     }
-    // accumulator register r of this lane is centroid 8*(r/4) + 4*half + r%4 of the tile
+  };
+  // running best / second best; accumulator register r of this lane is centroid
+  // 8*(r/4) + 4*half + r%4 of matrix tile `tile` (global tile number)
+  auto track = [&](const f32x16_t& c0, const f32x16_t& c1, int tile) {
     const float old0 = best[0], old1 = best[1];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       float s0 = c0[r], s1 = c1[r];
       if (HAS_BIAS) {
-        int b = t * kCentTile + 8 * (r / 4) + 4 * half + (r % 4);
+        const int b = tile * kCentTile + 8 * (r / 4) + 4 * half + (r % 4);
         const float bv = bias[(size_t)h * B + (b < B ? b : 0)];
         s0 += bv;
         s1 += bv;
@@ -151,9 +156,21 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
       second[1] = __builtin_amdgcn_fmed3f(best[1], second[1], p1);
       best[1] = fmaxf(best[1], p1);
     }
-    best_tile[0] = best[0] != old0 ? t : best_tile[0];
-    best_tile[1] = best[1] != old1 ? t : best_tile[1];
-    if (t + 1 < n_tiles) stash(buf ^ 1);
+    best_tile[0] = best[0] != old0 ? tile : best_tile[0];
+    best_tile[1] = best[1] != old1 ? tile : best_tile[1];
+  };
+
+  for (int t = 0; t < n_slabs; ++t) {
+    const int buf = t & 1;
+    if (t + 1 < n_slabs) fetch(t + 1);
+    // the matrix instructions of the second tile are issued before the vector work on the first,
+    // so both pipes are busy within one wave
+    f32x16_t a0, a1, b0, b1;
+    tile_mfma(buf, 0, a0, a1);
+    tile_mfma(buf, 1, b0, b1);
+    track(a0, a1, t * 2 + 0);
+    track(b0, b1, t * 2 + 1);
+    if (t + 1 < n_slabs) stash(buf ^ 1);
     __syncthreads();
   }
 

@@ -43,6 +43,7 @@ struct AttnParams {
   int P;
   int Hq, Hkv;
   int independent;        // unit = (sequence, query head) instead of (sequence, KV head)
+  int use_table;          // list mode: build the per-chunk run table (pays off from a few chunks per workgroup)
   int stage;              // list mode: copy the unit's len/off arrays to LDS (needs nseg <= 2*NT, B <= 8*NT)
   int out_bf16;
   int n_dense;            // keys per unit in dense mode
@@ -264,7 +265,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     T_total = pre[nseg];
     // runs that hold the first and the last key of each of this workgroup's chunks, so that the
     // per-key lookups in the loop search a handful of runs instead of all of them
-    for (int k = tid;; k += NT) {
+    for (int k = tid; p.use_table; k += NT) {
       const long long first = ((long long)wg + (long long)k * p.P) * chunk;
       if (first >= T_total || k >= p.max_chunks) break;
       const int v0 = (int)first;
@@ -278,7 +279,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
       seglo[k] = a0;
       seghi[k] = a1;
     }
-    __syncthreads();
+    if (p.use_table) __syncthreads();
   } else {
     T_total = p.n_dense;
   }
@@ -303,7 +304,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
       long long vl = base + (sub & (KB - 1)) * NG + kp;   // lane `sub` resolves slot sub % KB
       int v = (int)(vl < T_total ? vl : T_total - 1);
       if (LIST) {
-        int a = seglo[k], b = seghi[k] + 1;
+        int a = p.use_table ? seglo[k] : 0, b = p.use_table ? seghi[k] + 1 : p.nseg;
         while (b - a > 1) {
           const int mid = (a + b) >> 1;
           if (pre[mid] <= v) a = mid; else b = mid;
@@ -396,35 +397,52 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   SAAP_TRACE(3);
   // the head's sum of weights: add up the key slots (lanes s, s+G, ... of the group)
   l = ror_sum<G, C>(l);
+  // combine the four key processors of the wave (Algorithm 2 on registers): common maximum per
+  // head, rescale, add up across the four 16-lane rows
+  {
+    const float mw = max_rows(m);
+    const float a = fast_exp2(m - mw);          // scale of this processor's sums for the lane's own head
+    m = mw;
+    l = sum_rows(l * a);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float ag;
+      if constexpr (G == 1) ag = a; else ag = g == 0 ? group_bcast<0>(a) : g == 1 ? group_bcast<1>(a) : g == 2 ? group_bcast<2>(a) : g == 3 ? group_bcast<3>(a) : g == 4 ? group_bcast<4>(a) : g == 5 ? group_bcast<5>(a) : g == 6 ? group_bcast<6>(a) : group_bcast<7>(a);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) O[g][e] = sum_rows(O[g][e] * ag);
+    }
+  }
 
-  // key processors -> LDS (the index arrays are dead from here on)
+  // waves -> LDS (the index arrays are dead from here on)
   SAAP_TRACE(9);
   __syncthreads();
   SAAP_TRACE(10);
-  float* w_o = reinterpret_cast<float*>(smem);            // [NG][G][d] unnormalised outputs
-  float* w_m = w_o + NG * G * kD;                         // [NG][G] maxima, then weights 2^(m - M)
-  float* w_l = w_m + NG * G;                              // [NG][G] sums of weights
-  float* w_M = w_l + NG * G;                              // [G] workgroup maximum
+  float* w_o = reinterpret_cast<float*>(smem);            // [nw][G][d] unnormalised outputs
+  float* w_m = w_o + nw * G * kD;                         // [nw][G] maxima, then weights 2^(m - M)
+  float* w_l = w_m + nw * G;                              // [nw][G] sums of weights
+  float* w_M = w_l + nw * G;                              // [G] workgroup maximum
+  if (grp == 0) {
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float4* dst = reinterpret_cast<float4*>(w_o + (kp * G + g) * kD + sub * 8);
-    dst[0] = make_float4(O[g][0], O[g][1], O[g][2], O[g][3]);
-    dst[1] = make_float4(O[g][4], O[g][5], O[g][6], O[g][7]);
-  }
-  if (sub < G) {            // lane `sub` of a group owns head `sub` (key slot 0)
-    w_m[kp * G + sub] = m;
-    w_l[kp * G + sub] = l;
+    for (int g = 0; g < G; ++g) {
+      float4* dst = reinterpret_cast<float4*>(w_o + (wave * G + g) * kD + sub * 8);
+      dst[0] = make_float4(O[g][0], O[g][1], O[g][2], O[g][3]);
+      dst[1] = make_float4(O[g][4], O[g][5], O[g][6], O[g][7]);
+    }
+    if (sub < G) {            // lane `sub` owns head `sub` (key slot 0)
+      w_m[wave * G + sub] = m;
+      w_l[wave * G + sub] = l;
+    }
   }
   __syncthreads();
   SAAP_TRACE(11);
-  // weights 2^(m - M) of the NG partial results, NG*G <= NT/2 of them: one per thread
+  // weights 2^(m - M) of the nw partial results, one per thread
   {
-    const bool has = tid < NG * G;
+    const bool has = tid < nw * G;
     float wgt = 0.f, Mh = kNegBig;
     if (has) {
       const int g = tid % G;
 #pragma unroll
-      for (int j = 0; j < NG; ++j) Mh = fmaxf(Mh, w_m[j * G + g]);
+      for (int j = 0; j < nw; ++j) Mh = fmaxf(Mh, w_m[j * G + g]);
       wgt = fast_exp2(w_m[tid] - Mh);
     }
     __syncthreads();          // every maximum is read before any is overwritten
@@ -438,7 +456,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     const int g = x / kD, e = x % kD;
     float L = 0.f, Ov = 0.f;
 #pragma unroll
-    for (int j = 0; j < NG; ++j) {
+    for (int j = 0; j < nw; ++j) {
       const float w = w_m[j * G + g];
       L = fmaf(w, w_l[j * G + g], L);
       Ov = fmaf(w, w_o[(j * G + g) * kD + e], Ov);
@@ -588,7 +606,6 @@ LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, long long max_k
                        bool list, int B, bool has_selection) {
   int threads = env_int("SAAP_ATTN_THREADS", 0);
   if (threads != 256 && threads != 512) threads = 512;
-  if (G == 8) threads = 256;                            // keeps the per-processor partials within LDS
   const int kb = G == 8 ? 2 : 4;
   const int wgs_per_cu = env_int("SAAP_ATTN_WGS_PER_CU", threads == 256 ? 2 : 1);
   const int cus = device_cus();
@@ -607,7 +624,7 @@ LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, long long max_k
   size_t a = list ? (size_t)(2 * nseg + 1 + 2 * lp.max_chunks) * sizeof(int) : 0;
   lp.stage = list && has_selection && nseg <= 2 * threads && B <= 8 * threads && env_int("SAAP_ATTN_STAGE", 1);
   if (lp.stage) a += (size_t)2 * B * sizeof(int);
-  const size_t b = (size_t)(threads / 16) * G * (kD + 2) * sizeof(float) + G * sizeof(float);
+  const size_t b = (size_t)(threads / 64) * G * (kD + 2) * sizeof(float) + G * sizeof(float);
   const size_t c = (size_t)(P * G + 2 * G + 4) * sizeof(float) + (size_t)threads * sizeof(float4);
   lp.lds = a > b ? a : b;
   if (c > lp.lds) lp.lds = c;
@@ -711,6 +728,7 @@ extern "C" int32_t saap_sparse_decode_attention(const void* q, const void* Ksort
   p.P = lp.P;
   p.stage = lp.stage;
   p.max_chunks = lp.max_chunks;
+  p.use_table = (est + (long long)lp.P * (lp.threads / 16 * (G == 8 ? 2 : 4)) - 1) / ((long long)lp.P * (lp.threads / 16 * (G == 8 ? 2 : 4))) > 2;
   return launch_attn<true>(p, lp, G, dtype, static_cast<hipStream_t>(stream));
 }
 
@@ -742,6 +760,7 @@ extern "C" int32_t saap_dense_decode_attention(const void* q, const void* K, con
   p.P = lp.P;
   p.stage = 0;
   p.max_chunks = lp.max_chunks;
+  p.use_table = 1;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   return off ? launch_attn<true>(p, lp, G, dtype, hs) : launch_attn<false>(p, lp, G, dtype, hs);
 }

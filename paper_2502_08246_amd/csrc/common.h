@@ -100,6 +100,20 @@ __device__ __forceinline__ unsigned wave_or(unsigned x) {
          (unsigned)__builtin_amdgcn_readlane((int)x, 32) | (unsigned)__builtin_amdgcn_readlane((int)x, 48);
 }
 
+// Exchanges across the four 16-lane rows of a wave with the gfx950 row-swap instructions:
+// combines a value with the one held by the same lane of the other three rows.
+template <typename F>
+__device__ __forceinline__ float across_rows(float x, F op) {
+  const unsigned u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);   // {own, row ^ 1} in some order
+  x = op(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const unsigned v = __float_as_uint(x);
+  const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);   // {own, lane ^ 32}
+  return op(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float sum_rows(float x) { return across_rows(x, [](float a, float b) { return a + b; }); }
+__device__ __forceinline__ float max_rows(float x) { return across_rows(x, [](float a, float b) { return fmaxf(a, b); }); }
+
 // Eight consecutive elements of a row, as loaded by one lane.
 template <typename T> struct Vec8;
 template <> struct Vec8<float> {
