@@ -8,14 +8,16 @@
 //   * radix kernel (nprobe well below B): a most-significant-digit radix select over the 32-bit
 //     score images (four passes of 8 bits, LDS histogram + one-wave scan) finds the score of the
 //     nprobe-th bucket; buckets above it, and the lowest-id buckets equal to it, are compacted
-//     and only those nprobe keys are put in order (by counting larger keys when nprobe <= 64,
-//     by a bitonic network otherwise).
+//     and only those nprobe keys are put in order (by counting larger keys for lists up to
+//     1024, by a bitonic network beyond).
 //   * sort kernel (nprobe close to B): all keys are sorted in LDS with a bitonic network.
 // Both give exactly the (score descending, id ascending) order of the definition.
 #include "common.h"
 
 namespace saap {
 namespace {
+
+constexpr int kRankSortMax = 1024;   // selected lists up to this length are ordered by counting larger keys
 
 // Sum of the heads' scores of bucket b, in fp32 in head order.  All loads go out before the
 // first add (heads <= 8).
@@ -190,7 +192,12 @@ select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ sele
       }
     }
     if (take) {
-      const unsigned pos = atomicAdd(&s_cnt, 1u);
+      // one LDS atomic per wave: the first taking lane reserves slots for all of them
+      const unsigned long long takers = __ballot(1);
+      unsigned base = 0u;
+      if (lane == __ffsll((long long)takers) - 1) base = atomicAdd(&s_cnt, (unsigned)__popcll(takers));
+      base = (unsigned)__builtin_amdgcn_readfirstlane((int)base);
+      const unsigned pos = base + (unsigned)__popcll(takers & ((1ull << lane) - 1ull));
       sortbuf[pos] = ((unsigned long long)key[e] << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)b);
     }
   }
@@ -207,6 +214,28 @@ select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ sele
       out[rank] = (int32_t)(0xFFFFFFFFu - (unsigned)(mine & 0xFFFFFFFFull));
     }
     SAAP_TRACE(4);
+    return;
+  }
+  if (n_sort <= kRankSortMax) {
+    // same idea with the comparisons of one key split over several threads: work item
+    // (key i, part) counts the larger keys in its slice and adds the count to rank[i]
+    unsigned* rank = eqbits + (B / 32 + 1);            // [n_sort], zeroed below
+    for (int i = tid; i < nprobe; i += nt) rank[i] = 0u;
+    __syncthreads();
+    const int parts = nt >= 2 * nprobe ? nt / nprobe : 1;
+    const int slice = (nprobe + parts - 1) / parts;
+    for (int w = tid; w < nprobe * parts; w += nt) {
+      const int i = w % nprobe, part = w / nprobe;
+      const int j0 = part * slice, j1 = min(j0 + slice, nprobe);
+      const unsigned long long mine = sortbuf[i];
+      unsigned cnt = 0u;
+#pragma unroll 8
+      for (int j = j0; j < j1; ++j) cnt += sortbuf[j] > mine ? 1u : 0u;
+      if (cnt) atomicAdd(&rank[i], cnt);
+    }
+    __syncthreads();
+    for (int i = tid; i < nprobe; i += nt)
+      out[rank[i]] = (int32_t)(0xFFFFFFFFu - (unsigned)(sortbuf[i] & 0xFFFFFFFFull));
     return;
   }
   for (int k = 2; k <= n_sort; k <<= 1) {
@@ -257,7 +286,8 @@ extern "C" int32_t saap_select_buckets(const float* scores, int32_t* selected, i
     int threads = (B + 3) / 4;
     threads = (threads + 63) / 64 * 64;
     if (threads > 1024) threads = 1024;
-    const size_t lds = (size_t)n_sort * sizeof(unsigned long long) + (size_t)(B / 32 + 1) * sizeof(unsigned);
+    const size_t lds = (size_t)n_sort * sizeof(unsigned long long) + (size_t)(B / 32 + 1) * sizeof(unsigned) +
+                       (n_sort <= kRankSortMax ? (size_t)n_sort * sizeof(unsigned) : 0);
     saap_trace_arm();
     if (B <= 4 * threads)
       hipLaunchKernelGGL(select_radix_kernel<4>, dim3((unsigned)units), dim3((unsigned)threads), lds, hs, scores,

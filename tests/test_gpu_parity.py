@@ -230,6 +230,32 @@ def test_attention_is_deterministic_and_workspace_stays_clean(saap):
     assert int(ws[:65536].to(torch.int64).sum().item()) == 0     # arrival counters are back to zero
 
 
+def test_limits_max_buckets_and_group_of_eight(saap):
+    """The largest supported bucket count (8192) with every bucket visited, one bucket per few keys,
+    many empty buckets, G = 8 and G = 1, and more units than compute units."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(3)
+    for (S, Hq, Hkv, N, B, nprobe) in [(1, 8, 1, 20000, 8192, 8192), (1, 2, 2, 9000, 8192, 5000), (40, 8, 8, 600, 16, 3)]:
+        dt = torch.bfloat16
+        K = torch.randn(S, Hkv, N, 128, generator=g, device=DEV).to(dt)
+        V = torch.randn(S, Hkv, N, 128, generator=g, device=DEV).to(dt)
+        q = torch.randn(S, Hq, 128, generator=g, device=DEV).to(dt)
+        ids = torch.randint(0, B, (S, Hkv, N), generator=g, device=DEV, dtype=torch.int32)
+        ids[ids % 3 == 1] = 0                                   # a third of the buckets stay empty, bucket 0 is huge
+        off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, K, V, B, 0)
+        scores = torch.rand(S, Hq, B, generator=g, device=DEV)
+        sel = saap.select_buckets(scores, Hkv, nprobe)
+        out, lse = saap.sparse_decode_attention(q, Ks, Vs, off, ln, sel, SCALE)
+        torch.cuda.synchronize()
+        r_off, r_ln, r_idx, _, _ = ref.build_bucket_index(ids.cpu().numpy(), h(K), h(V), B, 0)
+        assert np.array_equal(off.cpu().numpy(), r_off) and np.array_equal(idx.cpu().numpy(), r_idx)
+        r_sel = ref.select_buckets(scores.cpu().numpy(), Hkv, nprobe)
+        assert np.array_equal(sel.cpu().numpy(), r_sel)
+        ro, rl = ref.sparse_decode_attention(h(q), h(K), h(V), r_off, r_ln, r_idx, r_sel, SCALE)
+        assert_close(out.cpu().numpy(), ro, "bf16", f"limits {S},{Hq},{Hkv},{B},{nprobe}")
+        assert_close(lse.cpu().numpy(), rl, "bf16", "limits lse")
+
+
 # ------------------------------------------------------------------------------ classifier
 @pytest.mark.parametrize("dtype,S,Hq,Hkv,hidden,B,Hw_kind,bias", [
     ("bf16", 1, 32, 8, 512, 1024, "kv", False), ("bf16", 8, 8, 2, 256, 160, "kv", True),
