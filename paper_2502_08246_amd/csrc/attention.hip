@@ -34,7 +34,7 @@ struct AttnParams {
   float* lse;             // [S,Hq] or null
   float* part_o;          // [units, P, G, d]
   float* part_ml;         // [units, P, G, 2]
-  unsigned* counters;     // [units], zero on entry and on exit
+  unsigned long long* counters;   // [units] arrivals, eight 8-bit fields (one per XCD); zero on entry and on exit
   long long rows;         // rows per kv unit
   int nseg;               // segments (visited buckets) per unit; list mode only
   int max_chunks;         // upper bound on the chunks one workgroup processes (sizes the LDS tables)
@@ -483,12 +483,27 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   SAAP_TRACE(5);
   __syncthreads();
   if (tid == 0) {
-    const unsigned old = __hip_atomic_fetch_add(&p.counters[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_last = (old == (unsigned)(p.P - 1));
+    // The arrival counter has one 8-bit field per XCD (P <= 128 fits): besides "am I last" it
+    // tells the last workgroup whether every partial was written through its own XCD's L2.
+    const unsigned xcc = (unsigned)__builtin_amdgcn_s_getreg(20 | (3 << 11)) & 7u;   // HW_REG_XCC_ID[3:0]
+    const unsigned long long old = __hip_atomic_fetch_add(&p.counters[unit], 1ull << (8 * xcc), __ATOMIC_RELAXED,
+                                                          __HIP_MEMORY_SCOPE_AGENT);
+    unsigned total = 0;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) total += (unsigned)(old >> (8 * x)) & 0xffu;
+    const unsigned mine = (unsigned)(old >> (8 * xcc)) & 0xffu;
+    s_last = total == (unsigned)(p.P - 1) ? (mine == total ? 2 : 1) : 0;
   }
   __syncthreads();
   if (!s_last) return;
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  if (s_last == 2) {
+    // all partials went through this XCD's L2, which is coherent for its compute units: dropping
+    // this compute unit's L1 lines is enough
+    asm volatile("buffer_inv sc0" ::: "memory");
+    SAAP_TRACE(12);
+  } else {
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  }
   SAAP_TRACE(6);
 
   // Merge layout: one partial is kCols = G*d/4 float4 columns.  The workgroup's threads form
@@ -594,7 +609,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     if (e0 == 0 && p.lse) p.lse[qrow] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
   }
   SAAP_TRACE(8);
-  if (tid == 0) __hip_atomic_store(&p.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid == 0) __hip_atomic_store(&p.counters[unit], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 struct LaunchPlan {
@@ -711,13 +726,13 @@ extern "C" int32_t saap_sparse_decode_attention(const void* q, const void* Ksort
   const bool indep = mode == SAAP_INDEPENDENT;
   const int G = indep ? 1 : Hq / Hkv;
   const long long units = indep ? (long long)S * Hq : (long long)S * Hkv;
-  if (units * sizeof(unsigned) > SAAP_WS_HEADER_BYTES) return SAAP_UNSUPPORTED;
+  if (units * sizeof(unsigned long long) > SAAP_WS_HEADER_BYTES) return SAAP_UNSUPPORTED;
   if (ws_bytes < attn_workspace_bytes(units, G)) return SAAP_WORKSPACE_TOO_SMALL;
 
   AttnParams p{};
   p.q = q; p.K = Ksorted; p.V = Vsorted; p.off = off; p.len = len; p.selected = selected;
   p.out = out; p.lse = lse;
-  p.counters = reinterpret_cast<unsigned*>(ws);
+  p.counters = reinterpret_cast<unsigned long long*>(ws);
   p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   p.part_o = p.part_ml + (size_t)units * kMaxP * G * 2;
   p.rows = Ncap; p.nseg = nprobe; p.B = B; p.n_units = (int)units;
@@ -744,13 +759,13 @@ extern "C" int32_t saap_dense_decode_attention(const void* q, const void* K, con
   if (off && (B <= 0 || B > SAAP_MAX_BUCKETS)) return B <= 0 ? SAAP_INVALID_ARG : SAAP_UNSUPPORTED;
   const int G = Hq / Hkv;
   const long long units = (long long)S * Hkv;
-  if (units * sizeof(unsigned) > SAAP_WS_HEADER_BYTES) return SAAP_UNSUPPORTED;
+  if (units * sizeof(unsigned long long) > SAAP_WS_HEADER_BYTES) return SAAP_UNSUPPORTED;
   if (ws_bytes < attn_workspace_bytes(units, G)) return SAAP_WORKSPACE_TOO_SMALL;
 
   AttnParams p{};
   p.q = q; p.K = K; p.V = V; p.off = off; p.len = len; p.selected = nullptr;
   p.out = out; p.lse = lse;
-  p.counters = reinterpret_cast<unsigned*>(ws);
+  p.counters = reinterpret_cast<unsigned long long*>(ws);
   p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   p.part_o = p.part_ml + (size_t)units * kMaxP * G * 2;
   p.rows = N; p.nseg = off ? B : 0; p.B = B; p.n_units = (int)units;

@@ -3,18 +3,26 @@
 //
 // At decode only a handful of rows (G per KV head per sequence) meet each weight set, so the
 // call is bound by streaming the weights once; the matrix cores are the instruction that does
-// the (padded 16-row) products:
-//   fused kernel   (bf16) one workgroup per (64 buckets, 16 rows, weight set): h = relu(W1 x + b1)
-//                  for all hidden units into LDS, split into three bf16 planes (8+8+8 mantissa
-//                  bits = the fp32 value exactly), so the second layer again multiplies exact
-//                  bf16 operands and accumulates in fp32; then z = W2 h + b2.
-//   softmax kernel one workgroup per row, in place.
-// fp32 weights use v_mfma_f32_16x16x4_f32 in two launches (hidden, output) with h in the
-// workspace as one fp32 plane.
+// the (padded 16-row) products.  Three launches:
+//   hidden kernel   h = relu(W1 x + b1): one workgroup per (weight set, 16-row tile, 64 hidden
+//                   units); h goes to the workspace in fp32.
+//   output kernel   z = W2 h + b2: one workgroup per (weight set, 16-row tile, 32 buckets), so
+//                   that a 1024-bucket classifier for 8 KV heads fills all 256 compute units with
+//                   about 40 KB of loads each (one compute unit was measured to stream only
+//                   20-35 GB/s, so the bytes per workgroup set the time).
+//                   h is split into three bf16 planes (8+8+8 mantissa bits = the fp32 value
+//                   exactly), so the matrix cores multiply exact operands and accumulate in fp32.
+//   softmax kernel  one workgroup per row, in place.
+// Every global load is a whole 128-byte line per 8 lanes, issued before the first LDS store so
+// that a workgroup's loads are all in flight together; matrix operands are read from LDS with a
+// padded row pitch (no bank conflicts).  fp32 weights use v_mfma_f32_16x16x4_f32 with operands
+// straight from memory (correctness configuration, not tuned).
 #include "common.h"
 
 namespace saap {
 namespace {
+
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
 
 struct MlpShape {
   int S, Hq, Hw, hidden, B;
@@ -29,138 +37,206 @@ __device__ __forceinline__ int query_row(const MlpShape& sh, int w, int m) {
   return s * sh.Hq + hq;
 }
 
-template <typename T>
+// 16-byte global load.  The batches of loads below are kept ahead of the LDS stores that consume
+// them by straight-line code (clamped, unconditional stores) and a scheduling barrier, so that a
+// workgroup's loads are all in flight together.  (A volatile load would do that too, but every
+// volatile access is followed by a full wait.)
+__device__ __forceinline__ u32x4_t load16(const void* p) { return *reinterpret_cast<const u32x4_t*>(p); }
+
+// Decode a 1-D grid with the weight set fastest: workgroups are handed to the 8 XCDs round-robin,
+// so with Hw a multiple of 8 all workgroups of a weight set share one L2.
+__device__ __forceinline__ void decode_block(const MlpShape& sh, int& w, int& mt, int& slab) {
+  w = blockIdx.x % sh.Hw;
+  const int rest = blockIdx.x / sh.Hw;
+  const int m_tiles = sh.m_pad / 16;
+  mt = rest % m_tiles;
+  slab = rest / m_tiles;
+}
+
+constexpr int kPitchD = kD + 8;     // LDS row pitch (bf16 elements) of d-wide tiles
+
+// ---- bf16: hidden layer ------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-mlp_hidden_kernel(const T* __restrict__ xq, const T* __restrict__ W1, const float* __restrict__ b1,
-                  void* __restrict__ hbuf, MlpShape sh) {
+mlp_hidden_bf16_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__ W1, const float* __restrict__ b1,
+                       float* __restrict__ hbuf, MlpShape sh) {
+  __shared__ __align__(16) bf16_t s_x[16 * kPitchD];
+  __shared__ __align__(16) bf16_t s_w1[64 * kPitchD];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int w, mt, slab;
+  decode_block(sh, w, mt, slab);
+  const int rc = lane & 15, kg = lane >> 4;
+  SAAP_TRACE(0);
+  // coalesced loads: the 16 query rows (one piece per thread) and 64 rows of W1 (four pieces)
+  const int prow = tid >> 4, pc = tid & 15;
+  const int m = min(mt * 16 + prow, sh.rows_per_set - 1);
+  const u32x4_t xr = load16(xq + (size_t)query_row(sh, w, m) * kD + pc * 8);
+  u32x4_t wr[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int unit = min(slab * 64 + prow + 16 * i, sh.hidden - 1);
+    wr[i] = load16(W1 + ((size_t)w * sh.hidden + unit) * kD + pc * 8);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  *reinterpret_cast<u32x4_t*>(s_x + prow * kPitchD + pc * 8) = xr;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4_t*>(s_w1 + (prow + 16 * i) * kPitchD + pc * 8) = wr[i];
+  __syncthreads();
+  SAAP_TRACE(1);
+  const int unit = slab * 64 + wave * 16 + rc;
+  if (slab * 64 + wave * 16 >= sh.hidden) return;     // whole tile beyond the layer (hidden % 64 == 32)
+  f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int st = 0; st < kD / 32; ++st) {
+    const bf16x8_t a = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(s_x + rc * kPitchD + st * 32 + kg * 8));
+    const bf16x8_t b = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(s_w1 + (wave * 16 + rc) * kPitchD + st * 32 + kg * 8));
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
+  }
+  // accumulator i of this lane: row 4*kg + i, hidden unit `unit`
+  const float bv = b1 ? b1[(size_t)w * sh.hidden + unit] : 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = mt * 16 + 4 * kg + i;
+    hbuf[((size_t)w * sh.m_pad + row) * sh.hidden + unit] = fmaxf(acc[i] + bv, 0.f);
+  }
+  SAAP_TRACE(2);
+}
+
+// ---- bf16: output layer ------------------------------------------------------------------------
+constexpr int kOutChunk = 512;      // hidden units per LDS pass of the output kernel
+
+__global__ void __launch_bounds__(128)
+mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W2, const float* __restrict__ b2,
+                    float* __restrict__ scores, MlpShape sh) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int w, mt, slab;
+  decode_block(sh, w, mt, slab);
+  const int rc = lane & 15, kg = lane >> 4;
+  const int b0 = slab * 32;
+  const int chunk_max = min(sh.hidden, kOutChunk);
+  const int pitch = chunk_max + 8;
+  bf16_t* s_h = reinterpret_cast<bf16_t*>(smem);       // [3][16][pitch]
+  bf16_t* s_w2 = s_h + 3 * 16 * pitch;                 // [32][pitch]
+  const float* hrows = hbuf + ((size_t)w * sh.m_pad + mt * 16) * sh.hidden;
+  const int rows_here = min(16, sh.rows_per_set - mt * 16);    // real rows of this tile (>= 1)
+  // one accumulator per plane: three independent chains of matrix instructions, added at the end
+  f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0, acc2 = acc0;
+  SAAP_TRACE(0);
+  for (int c0 = 0; c0 < sh.hidden; c0 += kOutChunk) {
+    const int kc = min(kOutChunk, sh.hidden - c0);      // multiple of 32
+    // all loads of the pass first: 32 rows of W2 (kc/8 pieces each) and 16 rows of h (kc/4 pieces)
+    const int pw = kc / 8, ph = kc / 4;
+    u32x4_t wv[16], hv[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int q = min(tid + 128 * i, 32 * pw - 1), row = q / pw, pc = q % pw;
+      const int b = min(b0 + row, sh.B - 1);
+      wv[i] = load16(W2 + ((size_t)w * sh.B + b) * sh.hidden + c0 + pc * 8);
+    }
+    // only the tile's real rows are fetched (4 of 16 at batch 1); the other LDS rows keep
+    // whatever they hold: a row of A only reaches the same row of the product, which is dropped
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int q = min(tid + 128 * i, rows_here * ph - 1), row = q / ph, pc = q % ph;
+      hv[i] = load16(hrows + (size_t)row * sh.hidden + c0 + pc * 4);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (c0 > 0) __syncthreads();                        // the previous pass is done with the LDS tiles
+    // stores use the same clamped piece index as the loads: surplus threads rewrite the last
+    // piece with identical data, and the code stays free of branches
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int q = min(tid + 128 * i, 32 * pw - 1);
+      *reinterpret_cast<u32x4_t*>(s_w2 + (q / pw) * pitch + (q % pw) * 8) = wv[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int q = min(tid + 128 * i, rows_here * ph - 1);
+      {
+        // four activations -> three planes of truncated bf16 pieces: h == p0 + p1 + p2 exactly
+        uint32_t p0[4], p1[4], p2[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float hval = __uint_as_float(hv[i][j]);
+          p0[j] = __float_as_uint(hval) & 0xffff0000u;
+          const float r1 = hval - __uint_as_float(p0[j]);
+          p1[j] = __float_as_uint(r1) & 0xffff0000u;
+          const float r2 = r1 - __uint_as_float(p1[j]);
+          p2[j] = __float_as_uint(r2) & 0xffff0000u;
+        }
+        bf16_t* dst = s_h + (q / ph) * pitch + (q % ph) * 4;
+        *reinterpret_cast<uint2*>(dst) = make_uint2((p0[0] >> 16) | p0[1], (p0[2] >> 16) | p0[3]);
+        *reinterpret_cast<uint2*>(dst + 16 * pitch) = make_uint2((p1[0] >> 16) | p1[1], (p1[2] >> 16) | p1[3]);
+        *reinterpret_cast<uint2*>(dst + 32 * pitch) = make_uint2((p2[0] >> 16) | p2[1], (p2[2] >> 16) | p2[3]);
+      }
+    }
+    __syncthreads();
+    if (c0 == 0) SAAP_TRACE(1);
+    const bf16_t* wrow = s_w2 + (wave * 16 + rc) * pitch + kg * 8;
+    const bf16_t* hrow = s_h + rc * pitch + kg * 8;
+    for (int st = 0; st < kc / 32; ++st) {
+      const bf16x8_t b = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wrow + st * 32));
+      const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(hrow + st * 32));
+      const bf16x8_t a1 = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(hrow + 16 * pitch + st * 32));
+      const bf16x8_t a2 = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(hrow + 32 * pitch + st * 32));
+      acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, b, acc2, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc0, 0, 0, 0);
+    }
+  }
+  // smallest pieces first
+  const f32x4_t acc = (acc2 + acc1) + acc0;
+  SAAP_TRACE(2);
+  const int bucket = b0 + wave * 16 + rc;
+  if (bucket < sh.B) {
+    const float bo = b2 ? b2[(size_t)w * sh.B + bucket] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int mm = mt * 16 + 4 * kg + i;
+      if (mm < sh.rows_per_set) scores[(size_t)query_row(sh, w, mm) * sh.B + bucket] = acc[i] + bo;
+    }
+  }
+  SAAP_TRACE(3);
+}
+
+// ---- fp32 (correctness configuration): operands straight from memory ------------------------------
+__global__ void __launch_bounds__(256)
+mlp_hidden_f32_kernel(const float* __restrict__ xq, const float* __restrict__ W1, const float* __restrict__ b1,
+                      float* __restrict__ hbuf, MlpShape sh) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int utile = blockIdx.x * 4 + wave;           // tile of 16 hidden units
   if (utile * 16 >= sh.hidden) return;
   const int mt = blockIdx.y, w = blockIdx.z;
   const int rc = lane & 15, kg = lane >> 4;
   const int m = min(mt * 16 + rc, sh.rows_per_set - 1);
-  const T* xr = xq + (size_t)query_row(sh, w, m) * kD;
-  const T* wr = W1 + ((size_t)w * sh.hidden + utile * 16 + rc) * kD;
+  const float* xr = xq + (size_t)query_row(sh, w, m) * kD;
+  const float* wr = W1 + ((size_t)w * sh.hidden + utile * 16 + rc) * kD;
   f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-  if constexpr (sizeof(T) == 2) {
-#pragma unroll
-    for (int st = 0; st < kD / 32; ++st) {
-      const bf16x8_t a = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(xr + st * 32 + kg * 8));
-      const bf16x8_t b = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wr + st * 32 + kg * 8));
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
-    }
-  } else {
 #pragma unroll 8
-    for (int st = 0; st < kD / 4; ++st)
-      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xr[st * 4 + kg], wr[st * 4 + kg], acc, 0, 0, 0);
-  }
-  // accumulator i of this lane: row 4*kg + i, hidden unit utile*16 + rc
+  for (int st = 0; st < kD / 4; ++st)
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(xr[st * 4 + kg], wr[st * 4 + kg], acc, 0, 0, 0);
   const int unit = utile * 16 + rc;
   const float bv = b1 ? b1[(size_t)w * sh.hidden + unit] : 0.f;
-  const size_t plane = (size_t)sh.Hw * sh.m_pad * sh.hidden;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = mt * 16 + 4 * kg + i;
-    const float hval = fmaxf(acc[i] + bv, 0.f);
-    const size_t o = ((size_t)w * sh.m_pad + row) * sh.hidden + unit;
-    if constexpr (sizeof(T) == 2) {
-      bf16_t* hp = static_cast<bf16_t*>(hbuf);
-      // three truncated bf16 pieces: hval == p0 + p1 + p2 exactly
-      const uint32_t u0 = __float_as_uint(hval) & 0xffff0000u;
-      const float r1 = hval - __uint_as_float(u0);
-      const uint32_t u1 = __float_as_uint(r1) & 0xffff0000u;
-      const float r2 = r1 - __uint_as_float(u1);
-      const uint32_t u2 = __float_as_uint(r2) & 0xffff0000u;
-      hp[o] = (bf16_t)(u0 >> 16);
-      hp[plane + o] = (bf16_t)(u1 >> 16);
-      hp[2 * plane + o] = (bf16_t)(u2 >> 16);
-    } else {
-      static_cast<float*>(hbuf)[o] = hval;
-    }
+    hbuf[((size_t)w * sh.m_pad + row) * sh.hidden + unit] = fmaxf(acc[i] + bv, 0.f);
   }
 }
 
-// Output layer.  The four waves of a workgroup share one (weight set, 16-row tile): the
-// activations (all planes) are staged in LDS once, every wave streams the W2 rows of its 16
-// buckets with all loads of a 16-step block issued before the first matrix instruction.
-template <typename T>
 __global__ void __launch_bounds__(256)
-mlp_out_kernel(const void* __restrict__ hbuf, const T* __restrict__ W2, const float* __restrict__ b2,
-               float* __restrict__ scores, MlpShape sh) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+mlp_out_f32_kernel(const float* __restrict__ hbuf, const float* __restrict__ W2, const float* __restrict__ b2,
+                   float* __restrict__ scores, MlpShape sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int btile = blockIdx.x * 4 + wave;           // tile of 16 buckets
+  if (btile * 16 >= sh.B) return;
   const int mt = blockIdx.y, w = blockIdx.z;
   const int rc = lane & 15, kg = lane >> 4;
-  const size_t plane = (size_t)sh.Hw * sh.m_pad * sh.hidden;
-  const size_t hrow0 = ((size_t)w * sh.m_pad + mt * 16) * sh.hidden;
-  const bool active = btile * 16 < sh.B;
+  const float* hp = hbuf + ((size_t)w * sh.m_pad + mt * 16 + rc) * sh.hidden;
+  const float* wr = W2 + ((size_t)w * sh.B + btile * 16 + rc) * sh.hidden;
   f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-  if constexpr (sizeof(T) == 2) {
-    // LDS image: [plane][16 rows][hidden + 8] bf16 (row pitch padded against bank conflicts)
-    const int pitch = sh.hidden + 8;
-    bf16_t* s_h = reinterpret_cast<bf16_t*>(smem);
-    const bf16_t* hp = static_cast<const bf16_t*>(hbuf) + hrow0;
-    const int pieces_per_row = sh.hidden / 8;          // 16-byte pieces
-    const T* wr = W2 + ((size_t)w * sh.B + (active ? btile * 16 + rc : 0)) * sh.hidden + kg * 8;
-    constexpr int kBlock = 16;                          // steps of 32 hidden units per load block
-    const int steps = sh.hidden / 32;
-    uint4 wreg[kBlock];
-#pragma unroll
-    for (int i = 0; i < kBlock; ++i)
-      if (i < steps) wreg[i] = *reinterpret_cast<const uint4*>(wr + i * 32);
-    const int n_pieces = 3 * 16 * pieces_per_row;
-    constexpr int kStage = 12;                          // pieces in flight per thread
-    for (int i0 = tid; i0 < n_pieces; i0 += 256 * kStage) {
-      uint4 tmp[kStage];
-#pragma unroll
-      for (int k = 0; k < kStage; ++k) {
-        const int i = i0 + k * 256;
-        if (i < n_pieces) {
-          const int pl = i / (16 * pieces_per_row), rem = i % (16 * pieces_per_row);
-          const int r = rem / pieces_per_row, pc = rem % pieces_per_row;
-          tmp[k] = *reinterpret_cast<const uint4*>(hp + (size_t)pl * plane + (size_t)r * sh.hidden + pc * 8);
-        }
-      }
-#pragma unroll
-      for (int k = 0; k < kStage; ++k) {
-        const int i = i0 + k * 256;
-        if (i < n_pieces) {
-          const int pl = i / (16 * pieces_per_row), rem = i % (16 * pieces_per_row);
-          const int r = rem / pieces_per_row, pc = rem % pieces_per_row;
-          *reinterpret_cast<uint4*>(s_h + ((size_t)pl * 16 + r) * pitch + pc * 8) = tmp[k];
-        }
-      }
-    }
-    __syncthreads();
-    for (int s0 = 0; s0 < steps; s0 += kBlock) {
-#pragma unroll
-      for (int i = 0; i < kBlock; ++i) {
-        if (s0 + i < steps) {
-          const int k = (s0 + i) * 32 + kg * 8;
-          const bf16x8_t b = __builtin_bit_cast(bf16x8_t, wreg[i]);
-          const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(s_h + (size_t)(0 * 16 + rc) * pitch + k));
-          const bf16x8_t a1 = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(s_h + (size_t)(1 * 16 + rc) * pitch + k));
-          const bf16x8_t a2 = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(s_h + (size_t)(2 * 16 + rc) * pitch + k));
-          // smallest pieces first: their sum is rounded least by the fp32 accumulator
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, b, acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc, 0, 0, 0);
-        }
-      }
-      if (s0 + kBlock < steps) {
-#pragma unroll
-        for (int i = 0; i < kBlock; ++i)
-          if (s0 + kBlock + i < steps) wreg[i] = *reinterpret_cast<const uint4*>(wr + (s0 + kBlock + i) * 32);
-      }
-    }
-  } else {
-    const float* hp = static_cast<const float*>(hbuf) + hrow0 + (size_t)rc * sh.hidden;
-    const T* wr = W2 + ((size_t)w * sh.B + (active ? btile * 16 + rc : 0)) * sh.hidden;
-    for (int st = 0; st < sh.hidden / 4; ++st)
-      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hp[st * 4 + kg], wr[st * 4 + kg], acc, 0, 0, 0);
-  }
-  if (!active) return;
+  for (int st = 0; st < sh.hidden / 4; ++st)
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hp[st * 4 + kg], wr[st * 4 + kg], acc, 0, 0, 0);
   const int bucket = btile * 16 + rc;
   const float bv = b2 ? b2[(size_t)w * sh.B + bucket] : 0.f;
 #pragma unroll
@@ -168,127 +244,6 @@ mlp_out_kernel(const void* __restrict__ hbuf, const T* __restrict__ W2, const fl
     const int m = mt * 16 + 4 * kg + i;
     if (m < sh.rows_per_set) scores[(size_t)query_row(sh, w, m) * sh.B + bucket] = acc[i] + bv;
   }
-}
-
-// Both layers in one launch (bf16).  A workgroup owns (weight set, 16-row tile, 64 buckets):
-// its four waves first compute ALL hidden units of the 16 rows (each wave a quarter of the
-// hidden tiles; W1 is small and comes from L2 for every workgroup but the first), leave them in
-// LDS as three exact bf16 planes, then each wave multiplies its 16 W2 rows.  The W2 loads are
-// issued before the first layer starts, so one memory round trip covers x, W1 and W2.
-__global__ void __launch_bounds__(256)
-mlp_fused_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__ W1, const float* __restrict__ b1,
-                 const bf16_t* __restrict__ W2, const float* __restrict__ b2, float* __restrict__ scores,
-                 MlpShape sh) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // 1-D grid, weight set fastest: workgroups are handed to the 8 XCDs round-robin, so with Hw a
-  // multiple of 8 all workgroups of a weight set share one L2 and W1 leaves HBM once.
-  const int w = blockIdx.x % sh.Hw;
-  const int rest = blockIdx.x / sh.Hw;
-  const int m_tiles = sh.m_pad / 16;
-  const int mt = rest % m_tiles;
-  const int btile = (rest / m_tiles) * 4 + wave;     // tile of 16 buckets
-  const int rc = lane & 15, kg = lane >> 4;
-  const bool active = btile * 16 < sh.B;
-  const int pitch = sh.hidden + 8;
-  bf16_t* s_h = reinterpret_cast<bf16_t*>(smem);     // [3 planes][16 rows][pitch]
-
-  SAAP_TRACE(0);
-  constexpr int kBlock = 16;                          // W2 steps (32 hidden units each) per load block
-  const int steps = sh.hidden / 32;
-  const bf16_t* wr = W2 + ((size_t)w * sh.B + (active ? btile * 16 + rc : 0)) * sh.hidden + kg * 8;
-  uint4 wreg[kBlock];
-#pragma unroll
-  for (int i = 0; i < kBlock; ++i)
-    if (i < steps) wreg[i] = *reinterpret_cast<const uint4*>(wr + i * 32);
-
-  // layer 1: A = the 16 query rows, B = 16 hidden units of W1, K = d = 128 in four steps
-  const int m = min(mt * 16 + rc, sh.rows_per_set - 1);
-  const bf16_t* xr = xq + (size_t)query_row(sh, w, m) * kD + kg * 8;
-  uint4 xa[kD / 32];
-#pragma unroll
-  for (int st = 0; st < kD / 32; ++st) xa[st] = *reinterpret_cast<const uint4*>(xr + st * 32);
-  constexpr int kTiles = 8;                           // hidden tiles per wave per round
-  const int n_utiles = sh.hidden / 16;
-  for (int u0 = wave; u0 < n_utiles; u0 += 4 * kTiles) {
-    uint4 w1[kTiles][kD / 32];
-    float bv[kTiles];
-#pragma unroll
-    for (int j = 0; j < kTiles; ++j) {
-      const int ut = u0 + 4 * j;
-      if (ut < n_utiles) {
-        const bf16_t* w1r = W1 + ((size_t)w * sh.hidden + ut * 16 + rc) * kD + kg * 8;
-#pragma unroll
-        for (int st = 0; st < kD / 32; ++st) w1[j][st] = *reinterpret_cast<const uint4*>(w1r + st * 32);
-        bv[j] = b1 ? b1[(size_t)w * sh.hidden + ut * 16 + rc] : 0.f;
-      }
-    }
-    SAAP_TRACE(5);
-#pragma unroll
-    for (int j = 0; j < kTiles; ++j) {
-      const int ut = u0 + 4 * j;
-      if (j == 1) SAAP_TRACE(6);
-      if (ut < n_utiles) {
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int st = 0; st < kD / 32; ++st)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xa[st]),
-                                                        __builtin_bit_cast(bf16x8_t, w1[j][st]), acc, 0, 0, 0);
-        // accumulator i: row 4*kg + i, hidden unit ut*16 + rc; split into three exact bf16 pieces
-        const int unit = ut * 16 + rc;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int row = 4 * kg + i;
-          const float hval = fmaxf(acc[i] + bv[j], 0.f);
-          const uint32_t u0b = __float_as_uint(hval) & 0xffff0000u;
-          const float r1 = hval - __uint_as_float(u0b);
-          const uint32_t u1b = __float_as_uint(r1) & 0xffff0000u;
-          const float r2 = r1 - __uint_as_float(u1b);
-          const uint32_t u2b = __float_as_uint(r2) & 0xffff0000u;
-          s_h[(size_t)(0 * 16 + row) * pitch + unit] = (bf16_t)(u0b >> 16);
-          s_h[(size_t)(1 * 16 + row) * pitch + unit] = (bf16_t)(u1b >> 16);
-          s_h[(size_t)(2 * 16 + row) * pitch + unit] = (bf16_t)(u2b >> 16);
-        }
-      }
-    }
-  }
-  SAAP_TRACE(1);
-  __syncthreads();
-  SAAP_TRACE(2);
-
-  // layer 2
-  f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-  for (int s0 = 0; s0 < steps; s0 += kBlock) {
-#pragma unroll
-    for (int i = 0; i < kBlock; ++i) {
-      if (s0 + i < steps) {
-        const int k = (s0 + i) * 32 + kg * 8;
-        const bf16x8_t b = __builtin_bit_cast(bf16x8_t, wreg[i]);
-        const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(s_h + (size_t)(0 * 16 + rc) * pitch + k));
-        const bf16x8_t a1 = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(s_h + (size_t)(1 * 16 + rc) * pitch + k));
-        const bf16x8_t a2 = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(s_h + (size_t)(2 * 16 + rc) * pitch + k));
-        // smallest pieces first: their sum is rounded least by the fp32 accumulator
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, b, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc, 0, 0, 0);
-      }
-    }
-    if (s0 + kBlock < steps) {
-#pragma unroll
-      for (int i = 0; i < kBlock; ++i)
-        if (s0 + kBlock + i < steps) wreg[i] = *reinterpret_cast<const uint4*>(wr + (s0 + kBlock + i) * 32);
-    }
-  }
-  SAAP_TRACE(3);
-  if (!active) return;
-  const int bucket = btile * 16 + rc;
-  const float bo = b2 ? b2[(size_t)w * sh.B + bucket] : 0.f;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int mm = mt * 16 + 4 * kg + i;
-    if (mm < sh.rows_per_set) scores[(size_t)query_row(sh, w, mm) * sh.B + bucket] = acc[i] + bo;
-  }
-  SAAP_TRACE(4);
 }
 
 // Row softmax in place; the row is held in registers between the passes.
@@ -332,11 +287,10 @@ __global__ void __launch_bounds__(256) softmax_rows_kernel(float* __restrict__ s
 
 }  // namespace
 
-// header | hidden activations: up to 3 planes of [rows padded to 16 per set][hidden] (4 bytes each bounds both dtypes)
+// header | hidden activations fp32 [weight sets][rows padded to 16][hidden]; every weight set pads
+// its rows to a multiple of 16 and there are at most `rows` sets of one row each
 size_t classify_workspace_bytes(long long rows, int hidden) {
-  // every weight set pads its rows to a multiple of 16; at most `rows` sets of one row each
-  const long long padded = rows * 16;
-  return (size_t)SAAP_WS_HEADER_BYTES + (size_t)padded * hidden * 6;
+  return (size_t)SAAP_WS_HEADER_BYTES + (size_t)rows * 16 * hidden * sizeof(float);
 }
 
 }  // namespace saap
@@ -359,29 +313,34 @@ extern "C" int32_t saap_classify_queries(const void* xq, const void* W1, const f
   sh.S = S; sh.Hq = Hq; sh.Hw = Hw; sh.hidden = hidden; sh.B = B;
   sh.rows_per_set = S * (Hq / Hw);
   sh.m_pad = (sh.rows_per_set + 15) / 16 * 16;
-  const size_t need = (size_t)SAAP_WS_HEADER_BYTES + (size_t)Hw * sh.m_pad * hidden * (dtype == SAAP_BF16 ? 6 : 4);
+  const size_t need = (size_t)SAAP_WS_HEADER_BYTES + (size_t)Hw * sh.m_pad * hidden * sizeof(float);
   if (ws_bytes < need) return SAAP_WORKSPACE_TOO_SMALL;
   const int m_tiles = sh.m_pad / 16;
   if (m_tiles > 65535 || Hw > 65535) return SAAP_UNSUPPORTED;
-  void* hbuf = static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES;
+  float* hbuf = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  const dim3 g1((unsigned)((hidden / 16 + 3) / 4), (unsigned)m_tiles, (unsigned)Hw);
-  const dim3 g2((unsigned)((B / 16 + 3) / 4), (unsigned)m_tiles, (unsigned)Hw);
+  saap_trace_arm();
   if (dtype == SAAP_BF16) {
-    const size_t lds = (size_t)3 * 16 * (hidden + 8) * sizeof(bf16_t);
+    const unsigned g1 = (unsigned)((hidden + 63) / 64) * m_tiles * Hw;
+    const unsigned g2 = (unsigned)((B + 31) / 32) * m_tiles * Hw;
+    hipLaunchKernelGGL(mlp_hidden_bf16_kernel, dim3(g1), dim3(256), 0, hs, static_cast<const bf16_t*>(xq),
+                       static_cast<const bf16_t*>(W1), b1, hbuf, sh);
+    const int chunk = hidden < kOutChunk ? hidden : kOutChunk;
+    const size_t lds = (size_t)(3 * 16 + 32) * (chunk + 8) * sizeof(bf16_t);
     if (lds > 48 * 1024) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_fused_kernel),
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_out_bf16_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return SAAP_HIP_ERROR;
     }
-    saap_trace_arm();
-    hipLaunchKernelGGL(mlp_fused_kernel, dim3(g2.x * g2.y * g2.z), dim3(256), lds, hs, static_cast<const bf16_t*>(xq),
-                       static_cast<const bf16_t*>(W1), b1, static_cast<const bf16_t*>(W2), b2, scores, sh);
-  } else {
-    hipLaunchKernelGGL(mlp_hidden_kernel<float>, g1, dim3(256), 0, hs, static_cast<const float*>(xq),
-                       static_cast<const float*>(W1), b1, hbuf, sh);
-    hipLaunchKernelGGL(mlp_out_kernel<float>, g2, dim3(256), 0, hs, hbuf, static_cast<const float*>(W2), b2,
+    hipLaunchKernelGGL(mlp_out_bf16_kernel, dim3(g2), dim3(128), lds, hs, hbuf, static_cast<const bf16_t*>(W2), b2,
                        scores, sh);
+  } else {
+    const dim3 g1((unsigned)((hidden / 16 + 3) / 4), (unsigned)m_tiles, (unsigned)Hw);
+    const dim3 g2((unsigned)((B / 16 + 3) / 4), (unsigned)m_tiles, (unsigned)Hw);
+    hipLaunchKernelGGL(mlp_hidden_f32_kernel, g1, dim3(256), 0, hs, static_cast<const float*>(xq),
+                       static_cast<const float*>(W1), b1, hbuf, sh);
+    hipLaunchKernelGGL(mlp_out_f32_kernel, g2, dim3(256), 0, hs, hbuf, static_cast<const float*>(W2), b2, scores,
+                       sh);
   }
   if (output_kind == SAAP_PROBS)
     hipLaunchKernelGGL(softmax_rows_kernel, dim3((unsigned)(S * Hq)), dim3(256), 0, hs, scores, B);
