@@ -87,6 +87,19 @@ class GraphLoop:
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / (replays * self.count)
 
+    def replay_ms_per_call(self, replays):
+        """Per-replay mean call time (ms), one event pair per replay: the spread over replays."""
+        torch = self.torch
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(replays + 1)]
+        self.run(1)
+        torch.cuda.synchronize()
+        ev[0].record()
+        for r in range(replays):
+            self.graph.replay()
+            ev[r + 1].record()
+        torch.cuda.synchronize()
+        return [ev[r].elapsed_time(ev[r + 1]) / self.count for r in range(replays)]
+
 
 def main():
     args = parse()
@@ -189,7 +202,9 @@ def main():
         saap.dense_decode_attention(q[i % T], Ks, Vs, scale, off=off, ln=ln, out=out, lse=lse)
 
     reps = max(2, args.steps // T)
-    ms_attn = GraphLoop(attend_set, T, torch).timed_ms_per_call(reps)
+    g_attn = GraphLoop(attend_set, T, torch)
+    ms_attn = g_attn.timed_ms_per_call(reps)
+    spread = np.percentile(np.array(g_attn.replay_ms_per_call(max(reps, 20))) * 1e3, [10, 50, 90])
     ms_classify = GraphLoop(classify, T, torch).timed_ms_per_call(reps)
     ms_select = GraphLoop(select, T, torch).timed_ms_per_call(reps)
     ms_dense = None if args.no_dense else GraphLoop(dense, 8, torch).timed_ms_per_call(3)
@@ -242,6 +257,7 @@ def main():
             "traffic": traffic,
             "bytes_per_launch": round(bytes_step),
             "avg_launch_us": round(ms_attn * 1e3, 3),
+            "launch_us_p10_p50_p90": [round(float(v), 3) for v in spread],
             "stream_read_ceiling_GBps": round(ceiling, 1),
             "frac_of_stream_read_ceiling": round(achieved / ceiling, 4),
         },
@@ -296,6 +312,17 @@ def main():
             el = time.perf_counter() - t_cpu0
             if el > args.cpu_seconds or done >= 10 * T:
                 break
+        # context figures, one call each: the same sparse step on one thread, and the dense oracle
+        ref.set_threads(1)
+        t1 = time.perf_counter()
+        sc = ref.classify_queries(hxq[0], hW1, hb1, hW2, hb2, cfg.Hkv)
+        se = ref.select_buckets(sc, cfg.Hkv, cfg.nprobe)
+        ref.sparse_decode_attention(hq[0], hK, hV, h_off, h_ln, h_idx, se, scale)
+        single_us = (time.perf_counter() - t1) * 1e6 / cfg.S
+        ref.set_threads(threads)
+        t1 = time.perf_counter()
+        ref.dense_decode_attention(np.ascontiguousarray(hq[0][:1]), np.ascontiguousarray(hK[:1]), np.ascontiguousarray(hV[:1]), scale)
+        dense_cpu_us = (time.perf_counter() - t1) * 1e6
         result["cpu_baseline"] = {
             "value": round(el / done * 1e6 / cfg.S, 1),
             "unit": "us/token/layer",
@@ -303,6 +330,9 @@ def main():
             "kind": "oracle",
             "sample": f"{done} decode steps (classify + select + sparse attention) of the same workload, "
                       f"{threads} OpenMP threads over (sequence, head) in attention; classifier and selection single-threaded",
+            "single_thread_us": round(single_us, 1),
+            "dense_oracle_us": round(dense_cpu_us, 1),
+            "dense_oracle_sample": f"one dense call on sequence 0 (all {cfg.Hkv} KV heads, N={cfg.N}), {threads} threads",
         }
     print(json.dumps(result))
 
