@@ -37,6 +37,7 @@ def lib():
         _lib.ref_selectivity.restype = ctypes.c_double
         _lib.ref_get_threads.restype = ctypes.c_int
         _lib.ref_append_keys.restype = ctypes.c_int
+        _lib.ref_window_push.restype = ctypes.c_int
     return _lib
 
 
@@ -107,6 +108,70 @@ def append_keys(x_new, k_new, v_new, pos_new, centroids, bias, off, ln, idx, Ks,
     flag = lib().ref_append_keys(_p(x_new), _p(k_new), _p(v_new), _p(pos), _p(c), _p(bias), _p(off), _p(ln),
                                  _p(idx), _p(Ks), _p(Vs), _p(new_ids), S, Hkv, Ncap, B, d)
     return new_ids, int(flag)
+
+
+def windowed_capacity(N, B, slack, n_sink, n_recent):
+    """Rows of the sorted cache with a resident block: non-resident keys + slack + the block itself."""
+    W = n_sink + n_recent
+    return max(N - W, 0) + B * slack + W
+
+
+def build_windowed_index(ids, K, V, B, slack, n_sink, n_recent):
+    """-> off [S,Hkv,B+2], len [S,Hkv,B+1], idx [S,Hkv,Ncap], Ks, Vs [S,Hkv,Ncap,d], res_ids [S,Hkv,W]."""
+    ids = _i32(ids)
+    K = _f32(K)
+    V = _f32(V)
+    S, Hkv, N, d = K.shape
+    W = n_sink + n_recent
+    Ncap = windowed_capacity(N, B, slack, n_sink, n_recent)
+    off = np.empty((S, Hkv, B + 2), dtype=np.int32)
+    ln = np.empty((S, Hkv, B + 1), dtype=np.int32)
+    idx = np.empty((S, Hkv, Ncap), dtype=np.int32)
+    Ks = np.zeros((S, Hkv, Ncap, d), dtype=np.float32)
+    Vs = np.zeros((S, Hkv, Ncap, d), dtype=np.float32)
+    res = np.empty((S, Hkv, W), dtype=np.int32)
+    lib().ref_build_windowed_index(_p(ids), _p(K), _p(V), _p(off), _p(ln), _p(idx), _p(Ks), _p(Vs), _p(res),
+                                   S, Hkv, N, Ncap, B, d, slack, n_sink, n_recent)
+    return off, ln, idx, Ks, Vs, res
+
+
+def window_push(x_new, k_new, v_new, pos_new, centroids, bias, off, ln, idx, Ks, Vs, res_ids, n_sink, n_recent):
+    """In-place push on (ln, idx, Ks, Vs, res_ids); -> (new_ids [S,Hkv], overflow flag)."""
+    x_new = _f32(x_new)
+    k_new = _f32(k_new)
+    v_new = _f32(v_new)
+    c = _f32(centroids)
+    bias = None if bias is None else _f32(bias)
+    pos = _i32(pos_new)
+    S, Hkv, d = x_new.shape
+    B = c.shape[1]
+    Ncap = idx.shape[2]
+    for a, dt in ((off, np.int32), (ln, np.int32), (idx, np.int32), (Ks, np.float32), (Vs, np.float32),
+                  (res_ids, np.int32)):
+        assert a.dtype == dt and a.flags["C_CONTIGUOUS"]
+    assert off.shape[2] == B + 2 and ln.shape[2] == B + 1 and res_ids.shape[2] == n_sink + n_recent
+    new_ids = np.empty((S, Hkv), dtype=np.int32)
+    flag = lib().ref_window_push(_p(x_new), _p(k_new), _p(v_new), _p(pos), _p(c), _p(bias), _p(off), _p(ln),
+                                 _p(idx), _p(Ks), _p(Vs), _p(res_ids), _p(new_ids), S, Hkv, Ncap, B, d,
+                                 n_sink, n_recent)
+    return new_ids, int(flag)
+
+
+def windowed_decode_attention(q, K, V, ids, selected, n_sink, n_recent, scale, B, mode=0):
+    """Position-ordered K,V [S,Hkv,Nt,d], ids [S,Hkv,Nt] -> out float64 [S,Hq,d], lse float64 [S,Hq]."""
+    q = _f32(q)
+    K = _f32(K)
+    V = _f32(V)
+    ids = _i32(ids)
+    selected = _i32(selected)
+    S, Hq, d = q.shape
+    _, Hkv, Nt, _ = K.shape
+    nprobe = selected.shape[2]
+    out = np.empty((S, Hq, d), dtype=np.float64)
+    lse = np.empty((S, Hq), dtype=np.float64)
+    lib().ref_windowed_decode_attention(_p(q), _p(K), _p(V), _p(ids), _p(selected), nprobe, mode, n_sink,
+                                        n_recent, ctypes.c_float(scale), _p(out), _p(lse), S, Hq, Hkv, Nt, B, d)
+    return out, lse
 
 
 def classify_queries(xq, W1, b1, W2, b2, Hkv, output_kind=0):

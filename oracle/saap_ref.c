@@ -279,6 +279,149 @@ void ref_dense_decode_attention(const float* q, const float* K, const float* V, 
   }
 }
 
+/* Section 3 "Per-head attention span" + Appendix F: the first n_sink keys (attention
+ * sink) and the n_recent most recent keys are always attended; every other key takes
+ * part only if its bucket is visited.  Written on POSITION-ordered tensors, no index:
+ * K,V [S,Hkv,Nt,d], ids [S,Hkv,Nt] (bucket of every key), selected [S,Hkv,nprobe]
+ * (mode 1: [S,Hq,nprobe]).  U = { n : n < n_sink  or  n >= Nt - n_recent  or
+ * ids[n] in selected }. */
+void ref_windowed_decode_attention(const float* q, const float* K, const float* V, const int32_t* ids,
+                                   const int32_t* selected, int nprobe, int mode, int n_sink,
+                                   int n_recent, float scale, double* out, double* lse, int S, int Hq,
+                                   int Hkv, int Nt, int B, int d) {
+  int G = Hq / Hkv;
+  int units = S * Hq;
+#pragma omp parallel for num_threads(g_threads) schedule(dynamic)
+  for (int t = 0; t < units; ++t) {
+    int s = t / Hq, hq = t % Hq, h = hq / G;
+    size_t u = (size_t)s * Hkv + h;
+    const int32_t* sel = mode == 1 ? selected + (size_t)t * nprobe : selected + u * nprobe;
+    char* visit = (char*)calloc((size_t)B, 1);
+    for (int j = 0; j < nprobe; ++j) visit[sel[j]] = 1;
+    int32_t* members = (int32_t*)malloc(sizeof(int32_t) * (size_t)(Nt > 0 ? Nt : 1));
+    long c = 0;
+    for (int n = 0; n < Nt; ++n) {
+      int b = ids[u * Nt + n];
+      if (n < n_sink || n >= Nt - n_recent || (b >= 0 && b < B && visit[b])) members[c++] = n;
+    }
+    attend_list(q + (size_t)t * d, K + u * Nt * d, V + u * Nt * d, members, c, (double)scale, d,
+                out + (size_t)t * d, lse ? lse + t : NULL);
+    free(members);
+    free(visit);
+  }
+}
+
+/* ---- index with a resident block ------------------------------------------------------
+ * The paper keeps the sink + recent keys in dense tensors (K_l, V_l of Appendix F) and
+ * says nothing of how a key moves from there into its bucket as generation goes on.
+ * Layout used here (a reading; both sides follow it so that the state can be compared
+ * bit for bit): the index has B regular buckets and one more run, number B, of exactly
+ * W = n_sink + n_recent slots, the resident block.  Key at position p is resident while
+ * p < n_sink or p >= Nt - n_recent, and then sits in slot
+ *     r(p) = p                                   if p < n_sink
+ *            n_sink + (p - n_sink) mod n_recent  otherwise,
+ * so the recent part is a ring: the key entering at position p takes the slot of the key
+ * at p - n_recent, which moves to the first free slot of its own bucket.
+ * off [.,B+2], len [.,B+1], idx [.,Ncap], res_ids [.,W] = bucket id of each resident key
+ * (-1 for an empty slot), Ncap = max(N - W, 0) + B*slack + W. */
+static int resident_slot(int p, int n_sink, int n_recent) {
+  return p < n_sink ? p : n_sink + (p - n_sink) % n_recent;
+}
+
+void ref_build_windowed_index(const int32_t* ids, const float* K, const float* V, int32_t* off,
+                              int32_t* len, int32_t* idx, float* Ks, float* Vs, int32_t* res_ids,
+                              int S, int Hkv, int N, int Ncap, int B, int d, int slack, int n_sink,
+                              int n_recent) {
+  int W = n_sink + n_recent;
+  for (int u = 0; u < S * Hkv; ++u) {
+    const int32_t* id = ids + (size_t)u * N;
+    int32_t* o = off + (size_t)u * (B + 2);
+    int32_t* l = len + (size_t)u * (B + 1);
+    int32_t* ix = idx + (size_t)u * Ncap;
+    int32_t* rid = res_ids + (size_t)u * W;
+    for (int b = 0; b <= B; ++b) l[b] = 0;
+    for (int j = 0; j < W; ++j) rid[j] = -1;
+    for (int n = 0; n < N; ++n) {
+      int resident = n < n_sink || n >= N - n_recent;
+      if (resident) l[B] += 1;
+      else if (id[n] >= 0 && id[n] < B) l[id[n]] += 1;
+    }
+    o[0] = 0;
+    for (int b = 0; b < B; ++b) o[b + 1] = o[b] + l[b] + slack;
+    o[B + 1] = o[B] + W;
+    for (int j = 0; j < Ncap; ++j) ix[j] = -1;
+    int32_t* fill = (int32_t*)calloc((size_t)B, sizeof(int32_t));
+    for (int n = 0; n < N; ++n) {
+      int resident = n < n_sink || n >= N - n_recent;
+      int j;
+      if (resident) {
+        int r = resident_slot(n, n_sink, n_recent);
+        j = o[B] + r;
+        rid[r] = id[n];
+      } else {
+        int b = id[n];
+        if (b < 0 || b >= B) continue;
+        j = o[b] + fill[b]++;
+      }
+      ix[j] = n;
+      memcpy(Ks + ((size_t)u * Ncap + j) * d, K + ((size_t)u * N + n) * d, sizeof(float) * d);
+      memcpy(Vs + ((size_t)u * Ncap + j) * d, V + ((size_t)u * N + n) * d, sizeof(float) * d);
+    }
+    free(fill);
+  }
+}
+
+/* One new key per (sequence, KV head) at position pos_new[s] (= the number of keys the
+ * sequence held before).  The key's bucket is found as in ref_assign_keys.  It becomes
+ * resident; the key it displaces (position pos - n_recent) is appended to its bucket.
+ * If that bucket has no free slot nothing at all changes for this (sequence, head) and
+ * the returned flag is set.  With n_recent = 0 the new key goes straight to its bucket. */
+int ref_window_push(const float* x_new, const float* k_new, const float* v_new, const int32_t* pos_new,
+                    const float* cent, const float* bias, const int32_t* off, int32_t* len,
+                    int32_t* idx, float* Ks, float* Vs, int32_t* res_ids, int32_t* new_ids, int S,
+                    int Hkv, int Ncap, int B, int d, int n_sink, int n_recent) {
+  int overflow = 0;
+  int W = n_sink + n_recent;
+  for (int s = 0; s < S; ++s)
+    for (int h = 0; h < Hkv; ++h) {
+      int u = s * Hkv + h;
+      int pos = pos_new[s];
+      int32_t b;
+      ref_assign_keys(x_new + (size_t)u * d, cent + (size_t)h * B * d, bias ? bias + (size_t)h * B : NULL,
+                      &b, 1, 1, 1, B, d);
+      new_ids[u] = b;
+      const int32_t* o = off + (size_t)u * (B + 2);
+      int32_t* l = len + (size_t)u * (B + 1);
+      int32_t* ix = idx + (size_t)u * Ncap;
+      float* Ku = Ks + (size_t)u * Ncap * d;
+      float* Vu = Vs + (size_t)u * Ncap * d;
+      int j;                      /* slot that receives the new key */
+      if (pos < W) {              /* the resident block is not full yet */
+        j = o[B] + resident_slot(pos, n_sink, n_recent);
+        l[B] += 1;
+      } else if (n_recent == 0) { /* no ring: straight into the bucket */
+        if (o[b] + l[b] >= o[b + 1]) { overflow = 1; continue; }
+        j = o[b] + l[b];
+        l[b] += 1;
+      } else {
+        int r = resident_slot(pos, n_sink, n_recent);
+        int e = res_ids[(size_t)u * W + r];
+        j = o[B] + r;
+        if (o[e] + l[e] >= o[e + 1]) { overflow = 1; continue; }
+        int dst = o[e] + l[e];
+        ix[dst] = ix[j];
+        memcpy(Ku + (size_t)dst * d, Ku + (size_t)j * d, sizeof(float) * d);
+        memcpy(Vu + (size_t)dst * d, Vu + (size_t)j * d, sizeof(float) * d);
+        l[e] += 1;
+      }
+      if (j >= o[B]) res_ids[(size_t)u * W + (j - o[B])] = b;
+      ix[j] = pos;
+      memcpy(Ku + (size_t)j * d, k_new + (size_t)u * d, sizeof(float) * d);
+      memcpy(Vu + (size_t)j * d, v_new + (size_t)u * d, sizeof(float) * d);
+    }
+  return overflow;
+}
+
 /* Selectivity (Section 6.1): the fraction of keys that take part in the
  * computation, averaged over the lists (heads).  n_keys = keys per head. */
 double ref_selectivity(const int32_t* len, const int32_t* selected, int lists, int B, int nprobe,
