@@ -242,6 +242,78 @@ int32_t saap_dense_decode_attention(const void* q, const void* K, const void* V,
                                     int32_t dtype,
                                     void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * ---- attention sink and recent keys (Section 3 "Per-head attention span"; Appendix F) ----
+ * The paper attends the first key(s) of the sequence and the most recent ones exhaustively
+ * ("1+2047") and searches only the remaining keys through the buckets; Algorithm 2 of
+ * Appendix F gives those dense keys one more block of the partial-attention launch.  The
+ * paper keeps them in separate tensors and does not say how a key moves into its bucket
+ * when it leaves the window.  Layout used here: the sorted cache has B regular buckets and
+ * one more run, number B, of exactly W = n_sink + n_recent slots, the resident block.
+ * The key at position p is resident while p < n_sink or p >= (keys so far) - n_recent and
+ * then sits in slot  r(p) = p  for p < n_sink,  n_sink + (p - n_sink) mod n_recent
+ * otherwise: the recent part is a ring.
+ *
+ * build_windowed_index -- saap_build_bucket_index with the resident keys kept out of the
+ * buckets.
+ *   off [S,Hkv,B+2]: off[b+1] = off[b] + len[b] + slack for b < B, off[B+1] = off[B] + W
+ *   len [S,Hkv,B+1]: len[B] = number of resident keys (min(N, W) after the build)
+ *   idx [S,Hkv,Ncap], Ksorted, Vsorted [S,Hkv,Ncap,d]; free slots hold idx = -1
+ *   resident_ids [S,Hkv,W] int32, out: bucket id of the key in each resident slot (-1: empty)
+ *   Ncap must equal max(N - W, 0) + B*slack + W.  n_sink, n_recent >= 0.
+ * Workspace: as SAAP_OP_BUILD_BUCKET_INDEX for the same S, Hkv, N, B.
+ */
+int32_t saap_build_windowed_index(const int32_t* bucket_ids, const void* K, const void* V,
+                                  int32_t* off, int32_t* len, int32_t* idx,
+                                  void* Ksorted, void* Vsorted, int32_t* resident_ids,
+                                  int32_t S, int32_t Hkv, int32_t N, int32_t Ncap, int32_t B,
+                                  int32_t d, int32_t dtype, int32_t slack,
+                                  int32_t n_sink, int32_t n_recent,
+                                  void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * window_push -- one decode step's new key per (sequence, KV head) enters the resident
+ * block; the key it displaces (position pos - n_recent) is appended to the first free slot
+ * of its own bucket (its id was kept in resident_ids).  The new key's bucket is found as in
+ * saap_assign_keys (double precision, lowest id on ties) and stored for its later move.
+ *   x_new, k_new, v_new [S,Hkv,d] dtype; pos_new [S] int32: position of the new key
+ *   (= number of keys the sequence held before; pushes must come in position order);
+ *   centroids [Hkv,B,d], bias [Hkv,B] or NULL; off, len, idx, Ksorted, Vsorted,
+ *   resident_ids as written by saap_build_windowed_index (updated in place);
+ *   new_bucket_ids [S,Hkv] int32, out; overflow_flag: one device int32.
+ * While the block is not full (pos < W) the key takes slot r(pos) and nothing moves.  With
+ * n_recent = 0 the new key goes straight into its bucket.  If the bucket that must take a
+ * key has no free slot, nothing changes for that (sequence, head), *overflow_flag is set
+ * to 1 and the caller rebuilds the index; the flag is never cleared by the library.
+ */
+int32_t saap_window_push(const void* x_new, const void* k_new, const void* v_new,
+                         const int32_t* pos_new, const void* centroids, const float* bias,
+                         const int32_t* off, int32_t* len, int32_t* idx,
+                         void* Ksorted, void* Vsorted, int32_t* resident_ids,
+                         int32_t* new_bucket_ids, int32_t* overflow_flag,
+                         int32_t S, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype,
+                         int32_t n_sink, int32_t n_recent, void* stream);
+
+/*
+ * windowed_decode_attention -- saap_sparse_decode_attention over the selected buckets
+ * AND one run that is always visited (Algorithm 2 of Appendix F: block 0 handles the dense
+ * keys, blocks 1..nprobe the buckets; here it is one more run of the same launch).
+ *   runs            number of runs per (sequence, head) in `len` (B + 1 for an index made
+ *                   by saap_build_windowed_index); off [S,Hkv,runs+1], len [S,Hkv,runs]
+ *   resident_run    the run that is always visited (B for such an index), or -1 for none
+ *   selected        [S,Hkv,nprobe] (or [S,Hq,nprobe]); must not contain resident_run
+ * nprobe = 0 attends the resident block alone (sink + recent keys only).
+ * Workspace: as SAAP_OP_SPARSE_DECODE_ATTENTION.
+ */
+int32_t saap_windowed_decode_attention(const void* q, const void* Ksorted, const void* Vsorted,
+                                       const int32_t* off, const int32_t* len,
+                                       const int32_t* selected, int32_t nprobe, int32_t mode,
+                                       int32_t resident_run,
+                                       float scale, void* out, int32_t out_dtype, float* lse,
+                                       int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t runs,
+                                       int32_t d, int32_t dtype,
+                                       void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

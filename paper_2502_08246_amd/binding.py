@@ -26,6 +26,7 @@ EXPORTS = (
     "saap_workspace_bytes", "saap_workspace_reset", "saap_status_string", "saap_device_compute_units",
     "saap_assign_keys", "saap_build_bucket_index", "saap_append_keys", "saap_classify_queries",
     "saap_select_buckets", "saap_sparse_decode_attention", "saap_dense_decode_attention", "saap_stream_read_probe",
+    "saap_build_windowed_index", "saap_window_push", "saap_windowed_decode_attention",
 )
 
 
@@ -234,6 +235,68 @@ def sparse_decode_attention(q, Ks, Vs, off, ln, selected, scale, mode=GROUP_SUM,
         _i32(nprobe), _i32(mode), ctypes.c_float(scale), _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S),
         _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _ptr(ws), wsb, _stream())
     _check("saap_sparse_decode_attention", st)
+    return out, lse
+
+
+def build_windowed_index(bucket_ids, K, V, B, slack, n_sink, n_recent, ws=None):
+    """Index with a resident run of W = n_sink + n_recent slots behind the B buckets.
+    -> off [S,Hkv,B+2], len [S,Hkv,B+1], idx [S,Hkv,Ncap], Ksorted, Vsorted [S,Hkv,Ncap,d], resident_ids [S,Hkv,W]."""
+    S, Hkv, N, d = K.shape
+    W = n_sink + n_recent
+    Ncap = max(N - W, 0) + B * slack + W
+    dev = K.device
+    off = torch.empty(S, Hkv, B + 2, dtype=torch.int32, device=dev)
+    ln = torch.empty(S, Hkv, B + 1, dtype=torch.int32, device=dev)
+    idx = torch.empty(S, Hkv, Ncap, dtype=torch.int32, device=dev)
+    Ks = torch.zeros(S, Hkv, Ncap, d, dtype=K.dtype, device=dev)
+    Vs = torch.zeros(S, Hkv, Ncap, d, dtype=K.dtype, device=dev)
+    res = torch.empty(S, Hkv, max(W, 1), dtype=torch.int32, device=dev)[:, :, :W]
+    ws, wsb = _ws(OP_BUILD_BUCKET_INDEX, dev, ws, S=S, Hkv=Hkv, N=N, B=B)
+    st = load_library().saap_build_windowed_index(
+        _ptr(bucket_ids), _ptr(K), _ptr(V), _ptr(off), _ptr(ln), _ptr(idx), _ptr(Ks), _ptr(Vs), _ptr(res), _i32(S),
+        _i32(Hkv), _i32(N), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(K)), _i32(slack), _i32(n_sink),
+        _i32(n_recent), _ptr(ws), wsb, _stream())
+    _check("saap_build_windowed_index", st)
+    return off, ln, idx, Ks, Vs, res
+
+
+def window_push(x_new, k_new, v_new, pos_new, centroids, bias, off, ln, idx, Ks, Vs, resident_ids, n_sink, n_recent,
+                overflow_flag=None):
+    """In-place push of one key per (sequence, KV head) into the resident run; the displaced key moves
+    to its bucket. -> (new_bucket_ids [S,Hkv], overflow_flag)."""
+    S, Hkv, d = x_new.shape
+    B = centroids.shape[1]
+    Ncap = idx.shape[2]
+    dev = x_new.device
+    new_ids = torch.empty(S, Hkv, dtype=torch.int32, device=dev)
+    if overflow_flag is None:
+        overflow_flag = torch.zeros(4, dtype=torch.int32, device=dev)
+    st = load_library().saap_window_push(
+        _ptr(x_new), _ptr(k_new), _ptr(v_new), _ptr(pos_new), _ptr(centroids), _ptr(bias), _ptr(off), _ptr(ln),
+        _ptr(idx), _ptr(Ks), _ptr(Vs), _ptr(resident_ids), _ptr(new_ids), _ptr(overflow_flag), _i32(S), _i32(Hkv),
+        _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(x_new)), _i32(n_sink), _i32(n_recent), _stream())
+    _check("saap_window_push", st)
+    return new_ids, overflow_flag
+
+
+def windowed_decode_attention(q, Ks, Vs, off, ln, selected, resident_run, scale, mode=GROUP_SUM,
+                              out_dtype=torch.float32, out=None, lse=None, ws=None):
+    """sparse_decode_attention over the selected buckets plus the always-visited run `resident_run`
+    (-1 for none); off [S,Hkv,runs+1], ln [S,Hkv,runs]."""
+    S, Hq, d = q.shape
+    _, Hkv, Ncap, _ = Ks.shape
+    runs = ln.shape[2]
+    nprobe = selected.shape[2]
+    dev = q.device
+    out = out if out is not None else torch.empty(S, Hq, d, dtype=out_dtype, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Hq, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_SPARSE_DECODE_ATTENTION, dev, ws, S=S, Hq=Hq, Hkv=Hkv, mode=mode)
+    st = load_library().saap_windowed_decode_attention(
+        _ptr(q), _ptr(Ks), _ptr(Vs), _ptr(off), _ptr(ln), _ptr(selected) if nprobe > 0 else ctypes.c_void_p(0),
+        _i32(nprobe), _i32(mode), _i32(resident_run), ctypes.c_float(scale), _ptr(out), _i32(_dtype_code(out)),
+        _ptr(lse), _i32(S), _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(runs), _i32(d), _i32(_dtype_code(q)), _ptr(ws),
+        wsb, _stream())
+    _check("saap_windowed_decode_attention", st)
     return out, lse
 
 

@@ -36,7 +36,9 @@ struct AttnParams {
   float* part_ml;         // [units, P, G, 2]
   unsigned long long* counters;   // [units] arrivals, eight 8-bit fields (one per XCD); zero on entry and on exit
   long long rows;         // rows per kv unit
-  int nseg;               // segments (visited buckets) per unit; list mode only
+  int nseg;               // runs visited per unit (selected buckets + the always-visited run); list mode only
+  int nsel;               // entries per unit in `selected` (the first nsel runs of the list)
+  int resident;           // run visited after the selected ones (list entry nsel), or -1
   int max_chunks;         // upper bound on the chunks one workgroup processes (sizes the LDS tables)
   int B;
   int n_units;
@@ -194,7 +196,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     const int j0 = tid * per, j1 = min(j0 + per, nseg);
     const int32_t* lenu = p.len + (size_t)kvu * p.B;
     const int32_t* offu = p.off + (size_t)kvu * (p.B + 1);
-    const int32_t* sel = p.selected ? p.selected + (size_t)unit * nseg : nullptr;
+    const int32_t* sel = p.selected ? p.selected + (size_t)unit * p.nsel : nullptr;
     int mine = 0;
     if (p.stage) {
       // One memory round trip instead of two: the selected list and the unit's whole len/off
@@ -205,7 +207,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
 #pragma unroll
       for (int k = 0; k < 2; ++k) {
         const int j = tid + k * NT;
-        sv[k] = j < nseg ? sel[j] : 0;
+        sv[k] = j < p.nsel ? sel[j] : p.resident;      // entry nsel (if any) is the always-visited run
       }
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
@@ -241,7 +243,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
       }
     } else {
       for (int j = j0; j < j1; ++j) {
-        const int b = sel ? sel[j] : j;
+        const int b = j < p.nsel ? (sel ? sel[j] : j) : p.resident;
         const int ln = lenu[b];
         pre[j + 1] = ln;            // temporarily the length; turned into a prefix below
         rowoff[j] = offu[b];
@@ -304,12 +306,16 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
       long long vl = base + (sub & (KB - 1)) * NG + kp;   // lane `sub` resolves slot sub % KB
       int v = (int)(vl < T_total ? vl : T_total - 1);
       if (LIST) {
-        int a = p.use_table ? seglo[k] : 0, b = p.use_table ? seghi[k] + 1 : p.nseg;
+        const bool tab = p.use_table && k < p.max_chunks;
+        int a = tab ? seglo[k] : 0, b = tab ? seghi[k] + 1 : p.nseg;
         while (b - a > 1) {
           const int mid = (a + b) >> 1;
           if (pre[mid] <= v) a = mid; else b = mid;
         }
         row = rowoff[a] + (v - pre[a]);
+        // a list that breaks the contract (repeated or overlapping runs, a damaged index) must
+        // not turn into a read outside the cache
+        row = min(max(row, 0), (int)p.rows - 1);
       } else {
         row = v;
       }
@@ -710,19 +716,21 @@ static int32_t check_common(const void* q, const void* K, const void* V, void* o
   return SAAP_OK;
 }
 
-extern "C" int32_t saap_sparse_decode_attention(const void* q, const void* Ksorted, const void* Vsorted,
-                                                const int32_t* off, const int32_t* len,
-                                                const int32_t* selected, int32_t nprobe, int32_t mode,
-                                                float scale, void* out, int32_t out_dtype, float* lse,
-                                                int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
-                                                int32_t d, int32_t dtype, void* ws, size_t ws_bytes,
-                                                void* stream) {
+// Attention over the selected runs plus, if resident_run >= 0, one run that is always visited.
+// B = runs per unit in `len`.
+static int32_t sparse_attention(const void* q, const void* Ksorted, const void* Vsorted, const int32_t* off,
+                                const int32_t* len, const int32_t* selected, int32_t nprobe, int32_t mode,
+                                int32_t resident_run, float scale, void* out, int32_t out_dtype, float* lse,
+                                int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d,
+                                int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_common(q, Ksorted, Vsorted, out, S, Hq, Hkv, d, dtype, out_dtype, ws);
   if (st != SAAP_OK) return st;
   if (!off || !len || (nprobe > 0 && !selected)) return SAAP_INVALID_ARG;
   if (mode != SAAP_GROUP_SUM && mode != SAAP_INDEPENDENT) return SAAP_INVALID_ARG;
-  if (B <= 0 || Ncap <= 0 || nprobe < 0 || nprobe > B) return SAAP_INVALID_ARG;
-  if (nprobe > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
+  if (B <= 0 || Ncap <= 0 || nprobe < 0 || resident_run < -1 || resident_run >= B) return SAAP_INVALID_ARG;
+  const int nseg = nprobe + (resident_run >= 0 ? 1 : 0);
+  if (nseg > B) return SAAP_INVALID_ARG;
+  if (nseg > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
   const bool indep = mode == SAAP_INDEPENDENT;
   const int G = indep ? 1 : Hq / Hkv;
   const long long units = indep ? (long long)S * Hq : (long long)S * Hkv;
@@ -735,16 +743,39 @@ extern "C" int32_t saap_sparse_decode_attention(const void* q, const void* Ksort
   p.counters = reinterpret_cast<unsigned long long*>(ws);
   p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   p.part_o = p.part_ml + (size_t)units * kMaxP * G * 2;
-  p.rows = Ncap; p.nseg = nprobe; p.B = B; p.n_units = (int)units;
+  p.rows = Ncap; p.nsel = nprobe; p.resident = resident_run; p.nseg = nseg; p.B = B; p.n_units = (int)units;
   p.Hq = Hq; p.Hkv = Hkv; p.independent = indep ? 1 : 0; p.out_bf16 = out_dtype == SAAP_BF16;
   p.n_dense = 0; p.scale_log2 = scale * kLog2e;
-  const long long est = (long long)Ncap * nprobe / B;
-  LaunchPlan lp = plan_launch((int)units, est, Ncap, G, nprobe, true, B, nprobe > 0);
+  // expected keys per unit: balanced buckets, plus the paper's default window for the resident run
+  const long long est = (long long)Ncap * nprobe / B + (resident_run >= 0 ? 2048 : 0);
+  LaunchPlan lp = plan_launch((int)units, est, Ncap, G, nseg, true, B, nseg > 0);
   p.P = lp.P;
   p.stage = lp.stage;
   p.max_chunks = lp.max_chunks;
   p.use_table = (est + (long long)lp.P * (lp.threads / 16 * (G == 8 ? 2 : 4)) - 1) / ((long long)lp.P * (lp.threads / 16 * (G == 8 ? 2 : 4))) > 2;
   return launch_attn<true>(p, lp, G, dtype, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int32_t saap_sparse_decode_attention(const void* q, const void* Ksorted, const void* Vsorted,
+                                                const int32_t* off, const int32_t* len,
+                                                const int32_t* selected, int32_t nprobe, int32_t mode,
+                                                float scale, void* out, int32_t out_dtype, float* lse,
+                                                int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
+                                                int32_t d, int32_t dtype, void* ws, size_t ws_bytes,
+                                                void* stream) {
+  return sparse_attention(q, Ksorted, Vsorted, off, len, selected, nprobe, mode, -1, scale, out, out_dtype, lse, S,
+                          Hq, Hkv, Ncap, B, d, dtype, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t saap_windowed_decode_attention(const void* q, const void* Ksorted, const void* Vsorted,
+                                                  const int32_t* off, const int32_t* len,
+                                                  const int32_t* selected, int32_t nprobe, int32_t mode,
+                                                  int32_t resident_run, float scale, void* out,
+                                                  int32_t out_dtype, float* lse, int32_t S, int32_t Hq,
+                                                  int32_t Hkv, int32_t Ncap, int32_t runs, int32_t d,
+                                                  int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
+  return sparse_attention(q, Ksorted, Vsorted, off, len, selected, nprobe, mode, resident_run, scale, out, out_dtype,
+                          lse, S, Hq, Hkv, Ncap, runs, d, dtype, ws, ws_bytes, stream);
 }
 
 extern "C" int32_t saap_dense_decode_attention(const void* q, const void* K, const void* V,
@@ -768,7 +799,7 @@ extern "C" int32_t saap_dense_decode_attention(const void* q, const void* K, con
   p.counters = reinterpret_cast<unsigned long long*>(ws);
   p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   p.part_o = p.part_ml + (size_t)units * kMaxP * G * 2;
-  p.rows = N; p.nseg = off ? B : 0; p.B = B; p.n_units = (int)units;
+  p.rows = N; p.nseg = off ? B : 0; p.nsel = p.nseg; p.resident = -1; p.B = B; p.n_units = (int)units;
   p.Hq = Hq; p.Hkv = Hkv; p.independent = 0; p.out_bf16 = out_dtype == SAAP_BF16;
   p.n_dense = N; p.scale_log2 = scale * kLog2e;
   LaunchPlan lp = plan_launch((int)units, N, N, G, p.nseg, off != nullptr, B, false);

@@ -11,6 +11,11 @@
 //                a position among equal ids inside the 64 comes from ballots, the running
 //                position of every bucket is kept in LDS -> idx
 //   5. permute   rows of K and V are copied to their slot, 16 bytes per lane, whole rows
+//
+// With a resident block (attention sink + recent keys, Section 3 "Per-head attention span")
+// only the positions [lo, hi) go through steps 1-4; the resident positions are placed by
+// their slot rule into one more run behind the B buckets, and window_push moves one key per
+// decode step from that run into its bucket.
 #include "common.h"
 
 namespace saap {
@@ -19,7 +24,8 @@ namespace {
 constexpr int kSlice = 2048;   // positions per slice (one histogram / one scatter wave each)
 
 __global__ void __launch_bounds__(256)
-hist_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ slice_hist, int N, int B, int n_slices) {
+hist_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ slice_hist, int N, int B, int n_slices,
+            int lo, int hi) {
   extern __shared__ int s_cnt[];
   const int slice = blockIdx.x, unit = blockIdx.y;
   for (int b = threadIdx.x; b < B; b += blockDim.x) s_cnt[b] = 0;
@@ -30,7 +36,7 @@ hist_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ slice_hist, i
 #pragma unroll
   for (int k = 0; k < kSlice / 256; ++k) {
     const int n = n0 + threadIdx.x + k * 256;
-    mine[k] = n < n1 ? idu[n] : -1;
+    mine[k] = n < n1 && n >= lo && n < hi ? idu[n] : -1;
   }
 #pragma unroll
   for (int k = 0; k < kSlice / 256; ++k)
@@ -42,7 +48,7 @@ hist_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ slice_hist, i
 
 // One thread per (unit, bucket): counts of the slices -> exclusive bases, total -> len.
 __global__ void __launch_bounds__(256)
-colscan_kernel(int32_t* __restrict__ slice_hist, int32_t* __restrict__ len, int B, int n_slices) {
+colscan_kernel(int32_t* __restrict__ slice_hist, int32_t* __restrict__ len, int B, int n_slices, int lstride) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x, unit = blockIdx.y;
   if (b >= B) return;
   int32_t* col = slice_hist + (size_t)unit * n_slices * B + b;
@@ -63,18 +69,20 @@ colscan_kernel(int32_t* __restrict__ slice_hist, int32_t* __restrict__ len, int 
     col[(size_t)s * B] = run;
     run += c;
   }
-  len[(size_t)unit * B + b] = run;
+  len[(size_t)unit * lstride + b] = run;
 }
 
-// One workgroup per unit: off[0] = 0, off[b+1] = off[b] + len[b] + slack.
+// One workgroup per unit: off[0] = 0, off[b+1] = off[b] + len[b] + slack.  With a resident
+// block (W >= 0) len has B+1 and off B+2 entries per unit: len[B] = n_res, off[B+1] = off[B] + W.
 __global__ void __launch_bounds__(1024)
-offscan_kernel(const int32_t* __restrict__ len, int32_t* __restrict__ off, int B, int slack) {
+offscan_kernel(int32_t* __restrict__ len, int32_t* __restrict__ off, int B, int slack, int W, int n_res) {
   __shared__ int s_wsum[16];
   const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int per = (B + blockDim.x - 1) / blockDim.x;
   const int b0 = tid * per, b1 = min(b0 + per, B);
-  const int32_t* l = len + (size_t)unit * B;
-  int32_t* o = off + (size_t)unit * (B + 1);
+  const int lstride = W >= 0 ? B + 1 : B;
+  int32_t* l = len + (size_t)unit * lstride;
+  int32_t* o = off + (size_t)unit * (lstride + 1);
   int mine = 0;
   for (int b = b0; b < b1; ++b) mine += l[b] + slack;
   const int incl = (int)wave_prefix_sum((unsigned)mine);
@@ -86,7 +94,31 @@ offscan_kernel(const int32_t* __restrict__ len, int32_t* __restrict__ off, int B
   for (int b = b0; b < b1; ++b) {
     run += l[b] + slack;
     o[b + 1] = run;
+    if (W >= 0 && b == B - 1) {
+      o[B + 1] = run + W;
+      l[B] = n_res;
+    }
   }
+}
+
+// Resident keys of a unit: position -> slot of the resident run, ids kept for the later move.
+__global__ void __launch_bounds__(256)
+resident_kernel(const int32_t* __restrict__ ids, const int32_t* __restrict__ off, int32_t* __restrict__ idx,
+                int32_t* __restrict__ res_ids, int N, int Ncap, int B, int n_sink, int n_recent, int n_res) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x, unit = blockIdx.y;
+  const int W = n_sink + n_recent;
+  if (j >= W) return;
+  int32_t* rid = res_ids + (size_t)unit * W;
+  if (j >= n_res) {              // slot r(p) = p while the block is not full: slots n_res.. are empty
+    rid[j] = -1;
+    return;
+  }
+  // j-th resident position in ascending order
+  const int p = (N <= W || j < n_sink) ? j : N - n_recent + (j - n_sink);
+  const int r = p < n_sink ? p : n_sink + (p - n_sink) % n_recent;
+  const int base = off[(size_t)unit * (B + 2) + B];
+  idx[(size_t)unit * Ncap + base + r] = p;
+  rid[r] = ids[(size_t)unit * N + p];
 }
 
 __global__ void __launch_bounds__(256) fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
@@ -98,11 +130,11 @@ __global__ void __launch_bounds__(256) fill_i32_kernel(int32_t* p, size_t n, int
 __global__ void __launch_bounds__(64)
 scatter_kernel(const int32_t* __restrict__ ids, const int32_t* __restrict__ slice_base,
                const int32_t* __restrict__ off, int32_t* __restrict__ idx, int N, int Ncap, int B,
-               int n_slices, int id_bits) {
+               int n_slices, int id_bits, int lo, int hi, int ostride) {
   extern __shared__ int s_next[];
   const int slice = blockIdx.x, unit = blockIdx.y, lane = threadIdx.x;
   const int32_t* base = slice_base + ((size_t)unit * n_slices + slice) * B;
-  const int32_t* o = off + (size_t)unit * (B + 1);
+  const int32_t* o = off + (size_t)unit * ostride;
   for (int b = lane; b < B; b += 64) s_next[b] = o[b] + base[b];
   __syncthreads();
   const int n0 = slice * kSlice, n1 = min(n0 + kSlice, N);
@@ -113,7 +145,7 @@ scatter_kernel(const int32_t* __restrict__ ids, const int32_t* __restrict__ slic
 #pragma unroll
   for (int k = 0; k < kSlice / 64; ++k) {
     const int n = n0 + k * 64 + lane;
-    mine[k] = n < n1 ? idu[n] : -1;
+    mine[k] = n < n1 && n >= lo && n < hi ? idu[n] : -1;
   }
 #pragma unroll
   for (int k = 0; k < kSlice / 64; ++k) {
@@ -249,6 +281,111 @@ append_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, const T*
   }
 }
 
+// One workgroup per (sequence, KV head): the new key is scored as in append_kernel and enters
+// the resident run; the key whose ring slot it takes moves to the first free slot of its own
+// bucket.  Thread 0 decides (slot, destination) and updates len / idx / res_ids; the row copies
+// are done by the first 128 threads, each reading the old element before it writes the new one.
+template <typename T>
+__global__ void __launch_bounds__(256)
+window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, const T* __restrict__ v_new,
+                   const int32_t* __restrict__ pos_new, const T* __restrict__ cent, const float* __restrict__ bias,
+                   const int32_t* __restrict__ off, int32_t* __restrict__ len, int32_t* __restrict__ idx,
+                   T* __restrict__ Ks, T* __restrict__ Vs, int32_t* __restrict__ res_ids,
+                   int32_t* __restrict__ new_ids, int32_t* __restrict__ overflow, int Hkv, int Ncap, int B,
+                   int n_sink, int n_recent) {
+  __shared__ double s_x[kD];
+  __shared__ double s_best[256];
+  __shared__ int s_id[256];
+  __shared__ int s_slot, s_dst;
+  const int unit = blockIdx.x, h = unit % Hkv, tid = threadIdx.x;
+  if (tid < kD) s_x[tid] = to_f64<T>(x_new[(size_t)unit * kD + tid]);
+  __syncthreads();
+  double best = 0.0;
+  int best_id = -1;
+  for (int b = tid; b < B; b += blockDim.x) {
+    const T* c = cent + ((size_t)h * B + b) * kD;
+    double t = 0.0;
+    for (int j = 0; j < kD; ++j) t = fma(s_x[j], to_f64<T>(c[j]), t);
+    if (bias) t += (double)bias[(size_t)h * B + b];
+    if (best_id < 0 || t > best) {
+      best = t;
+      best_id = b;
+    }
+  }
+  s_best[tid] = best;
+  s_id[tid] = best_id;
+  __syncthreads();
+  for (int s = blockDim.x >> 1; s > 0; s >>= 1) {
+    if (tid < s) {
+      const int oid = s_id[tid + s];
+      const double ob = s_best[tid + s];
+      const int mid = s_id[tid];
+      if (oid >= 0 && (mid < 0 || ob > s_best[tid] || (ob == s_best[tid] && oid < mid))) {
+        s_best[tid] = ob;
+        s_id[tid] = oid;
+      }
+    }
+    __syncthreads();
+  }
+  const int b = s_id[0];
+  const int W = n_sink + n_recent;
+  if (tid == 0) {
+    new_ids[unit] = b;
+    const int32_t* o = off + (size_t)unit * (B + 2);
+    int32_t* l = len + (size_t)unit * (B + 1);
+    int32_t* ix = idx + (size_t)unit * Ncap;
+    int32_t* rid = res_ids + (size_t)unit * W;
+    const int pos = pos_new[unit / Hkv];
+    int slot = -1, dst = -1;        // slot: receives the new key; dst: receives the displaced key
+    if (pos < 0) {
+      *overflow = 1;
+    } else if (pos < W) {           // the resident run is not full yet: r(pos) = pos
+      slot = o[B] + pos;
+      l[B] += 1;
+      rid[pos] = b;
+    } else if (n_recent == 0) {     // no ring: straight into the bucket
+      const int cur = l[b];
+      if (o[b] + cur < o[b + 1]) {
+        slot = o[b] + cur;
+        l[b] = cur + 1;
+      } else {
+        *overflow = 1;
+      }
+    } else {
+      const int r = n_sink + (pos - n_sink) % n_recent;
+      const int e = rid[r];
+      // e outside [0,B) means the caller broke the protocol (pushes out of order, foreign state):
+      // refuse like a full bucket instead of indexing with it
+      const bool ok = e >= 0 && e < B;
+      const int cur = ok ? l[e] : 0;
+      if (ok && o[e] + cur < o[e + 1]) {
+        slot = o[B] + r;
+        dst = o[e] + cur;
+        l[e] = cur + 1;
+        ix[dst] = ix[slot];
+        rid[r] = b;
+      } else {
+        *overflow = 1;
+      }
+    }
+    if (slot >= 0) ix[slot] = pos;
+    s_slot = slot;
+    s_dst = dst;
+  }
+  __syncthreads();
+  const int slot = s_slot, dst = s_dst;
+  if (slot >= 0 && tid < kD) {
+    T* ks = Ks + ((size_t)unit * Ncap + slot) * kD + tid;
+    T* vs = Vs + ((size_t)unit * Ncap + slot) * kD + tid;
+    if (dst >= 0) {
+      Ks[((size_t)unit * Ncap + dst) * kD + tid] = *ks;
+      Vs[((size_t)unit * Ncap + dst) * kD + tid] = *vs;
+    }
+    *ks = k_new[(size_t)unit * kD + tid];
+    *vs = v_new[(size_t)unit * kD + tid];
+  }
+}
+
 }  // namespace
 
 size_t build_workspace_bytes(long long units, int N, int B) {
@@ -260,18 +397,23 @@ size_t build_workspace_bytes(long long units, int N, int B) {
 
 using namespace saap;
 
-extern "C" int32_t saap_build_bucket_index(const int32_t* bucket_ids, const void* K, const void* V,
-                                           int32_t* off, int32_t* len, int32_t* idx, void* Ksorted,
-                                           void* Vsorted, int32_t S, int32_t Hkv, int32_t N, int32_t Ncap,
-                                           int32_t B, int32_t d, int32_t dtype, int32_t slack, void* ws,
-                                           size_t ws_bytes, void* stream) {
+// Shared body of the two build calls.  res_ids == nullptr: plain index (B runs); otherwise the
+// index with a resident run of W = n_sink + n_recent slots behind the B buckets.
+static int32_t build_index(const int32_t* bucket_ids, const void* K, const void* V, int32_t* off, int32_t* len,
+                           int32_t* idx, void* Ksorted, void* Vsorted, int32_t* res_ids, int32_t S, int32_t Hkv,
+                           int32_t N, int32_t Ncap, int32_t B, int32_t d, int32_t dtype, int32_t slack,
+                           int32_t n_sink, int32_t n_recent, void* ws, size_t ws_bytes, void* stream) {
+  const bool windowed = res_ids != nullptr;
   if (!bucket_ids || !K || !V || !off || !len || !idx || !Ksorted || !Vsorted || !ws) return SAAP_INVALID_ARG;
-  const void* ptrs[] = {bucket_ids, K, V, off, len, idx, Ksorted, Vsorted, ws};
+  const void* ptrs[] = {bucket_ids, K, V, off, len, idx, Ksorted, Vsorted, ws, res_ids};
   for (const void* p : ptrs)
     if (!aligned16(p)) return SAAP_INVALID_ARG;
-  if (S <= 0 || Hkv <= 0 || N <= 0 || B <= 0 || slack < 0) return SAAP_INVALID_ARG;
+  if (S <= 0 || Hkv <= 0 || N <= 0 || B <= 0 || slack < 0 || n_sink < 0 || n_recent < 0) return SAAP_INVALID_ARG;
   if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
-  if ((long long)Ncap != (long long)N + (long long)B * slack) return SAAP_INVALID_ARG;
+  const long long W = (long long)n_sink + n_recent;
+  if (W > 0x3fffffff) return SAAP_INVALID_ARG;
+  const long long n_res = windowed ? (N < W ? N : W) : 0;
+  if ((long long)Ncap != (long long)N - n_res + (long long)B * slack + (windowed ? W : 0)) return SAAP_INVALID_ARG;
   if (d != kD || B > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
   const long long units = (long long)S * Hkv;
   if (units > 65535) return SAAP_UNSUPPORTED;
@@ -281,16 +423,24 @@ extern "C" int32_t saap_build_bucket_index(const int32_t* bucket_ids, const void
   int32_t* slice_hist = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   int id_bits = 1;
   while ((1 << id_bits) < B) ++id_bits;
+  // positions [lo, hi) go into the buckets
+  const int lo = windowed ? (N <= W ? 0 : n_sink) : 0;
+  const int hi = windowed ? (N <= W ? 0 : N - n_recent) : N;
+  const int lstride = windowed ? B + 1 : B;
 
   hipLaunchKernelGGL(hist_kernel, dim3(n_slices, (unsigned)units), dim3(256), (size_t)B * sizeof(int), hs,
-                     bucket_ids, slice_hist, N, B, n_slices);
+                     bucket_ids, slice_hist, N, B, n_slices, lo, hi);
   hipLaunchKernelGGL(colscan_kernel, dim3((B + 255) / 256, (unsigned)units), dim3(256), 0, hs, slice_hist, len,
-                     B, n_slices);
-  hipLaunchKernelGGL(offscan_kernel, dim3((unsigned)units), dim3(1024), 0, hs, len, off, B, slack);
+                     B, n_slices, lstride);
+  hipLaunchKernelGGL(offscan_kernel, dim3((unsigned)units), dim3(1024), 0, hs, len, off, B, slack,
+                     windowed ? (int)W : -1, (int)n_res);
   const size_t n_idx = (size_t)units * Ncap;
   hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n_idx + 255) / 256)), dim3(256), 0, hs, idx, n_idx, -1);
   hipLaunchKernelGGL(scatter_kernel, dim3(n_slices, (unsigned)units), dim3(64), (size_t)B * sizeof(int), hs,
-                     bucket_ids, slice_hist, off, idx, N, Ncap, B, n_slices, id_bits);
+                     bucket_ids, slice_hist, off, idx, N, Ncap, B, n_slices, id_bits, lo, hi, lstride + 1);
+  if (windowed && W > 0)
+    hipLaunchKernelGGL(resident_kernel, dim3((unsigned)((W + 255) / 256), (unsigned)units), dim3(256), 0, hs,
+                       bucket_ids, off, idx, res_ids, N, Ncap, B, n_sink, n_recent, (int)n_res);
   const long long total_slots = units * Ncap;
   if (dtype == SAAP_BF16) {
     const long long threads = (total_slots + 3) / 4 * 16;
@@ -303,6 +453,56 @@ extern "C" int32_t saap_build_bucket_index(const int32_t* bucket_ids, const void
                        static_cast<const uint4*>(K), static_cast<const uint4*>(V), idx,
                        static_cast<uint4*>(Ksorted), static_cast<uint4*>(Vsorted), N, Ncap, total_slots);
   }
+  return launch_status();
+}
+
+extern "C" int32_t saap_build_bucket_index(const int32_t* bucket_ids, const void* K, const void* V,
+                                           int32_t* off, int32_t* len, int32_t* idx, void* Ksorted,
+                                           void* Vsorted, int32_t S, int32_t Hkv, int32_t N, int32_t Ncap,
+                                           int32_t B, int32_t d, int32_t dtype, int32_t slack, void* ws,
+                                           size_t ws_bytes, void* stream) {
+  return build_index(bucket_ids, K, V, off, len, idx, Ksorted, Vsorted, nullptr, S, Hkv, N, Ncap, B, d, dtype, slack,
+                     0, 0, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t saap_build_windowed_index(const int32_t* bucket_ids, const void* K, const void* V,
+                                             int32_t* off, int32_t* len, int32_t* idx, void* Ksorted,
+                                             void* Vsorted, int32_t* resident_ids, int32_t S, int32_t Hkv,
+                                             int32_t N, int32_t Ncap, int32_t B, int32_t d, int32_t dtype,
+                                             int32_t slack, int32_t n_sink, int32_t n_recent, void* ws,
+                                             size_t ws_bytes, void* stream) {
+  if (!resident_ids) return SAAP_INVALID_ARG;
+  return build_index(bucket_ids, K, V, off, len, idx, Ksorted, Vsorted, resident_ids, S, Hkv, N, Ncap, B, d, dtype,
+                     slack, n_sink, n_recent, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t saap_window_push(const void* x_new, const void* k_new, const void* v_new,
+                                    const int32_t* pos_new, const void* centroids, const float* bias,
+                                    const int32_t* off, int32_t* len, int32_t* idx, void* Ksorted,
+                                    void* Vsorted, int32_t* resident_ids, int32_t* new_bucket_ids,
+                                    int32_t* overflow_flag, int32_t S, int32_t Hkv, int32_t Ncap, int32_t B,
+                                    int32_t d, int32_t dtype, int32_t n_sink, int32_t n_recent, void* stream) {
+  if (!x_new || !k_new || !v_new || !pos_new || !centroids || !off || !len || !idx || !Ksorted || !Vsorted ||
+      !resident_ids || !new_bucket_ids || !overflow_flag)
+    return SAAP_INVALID_ARG;
+  if (S <= 0 || Hkv <= 0 || Ncap <= 0 || B <= 0 || n_sink < 0 || n_recent < 0) return SAAP_INVALID_ARG;
+  if ((long long)n_sink + n_recent > Ncap) return SAAP_INVALID_ARG;
+  if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
+  if (d != kD) return SAAP_UNSUPPORTED;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const unsigned units = (unsigned)((long long)S * Hkv);
+  if (dtype == SAAP_BF16)
+    hipLaunchKernelGGL(window_push_kernel<bf16_t>, dim3(units), dim3(256), 0, hs,
+                       static_cast<const bf16_t*>(x_new), static_cast<const bf16_t*>(k_new),
+                       static_cast<const bf16_t*>(v_new), pos_new, static_cast<const bf16_t*>(centroids), bias,
+                       off, len, idx, static_cast<bf16_t*>(Ksorted), static_cast<bf16_t*>(Vsorted),
+                       resident_ids, new_bucket_ids, overflow_flag, Hkv, Ncap, B, n_sink, n_recent);
+  else
+    hipLaunchKernelGGL(window_push_kernel<float>, dim3(units), dim3(256), 0, hs,
+                       static_cast<const float*>(x_new), static_cast<const float*>(k_new),
+                       static_cast<const float*>(v_new), pos_new, static_cast<const float*>(centroids), bias, off,
+                       len, idx, static_cast<float*>(Ksorted), static_cast<float*>(Vsorted), resident_ids,
+                       new_bucket_ids, overflow_flag, Hkv, Ncap, B, n_sink, n_recent);
   return launch_status();
 }
 

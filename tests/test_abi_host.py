@@ -106,6 +106,29 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
                                          i32(1), i32(100), i32(128), i32(1), ws, big, None)
     assert st == -1                                         # off without len
 
+    def windowed(**kw):
+        a = dict(nprobe=4, resident=8, runs=9)
+        a.update(kw)
+        return lib.saap_windowed_decode_attention(q, K, V, off, ln, sel, i32(a["nprobe"]), i32(0), i32(a["resident"]),
+                                                  f32(0.1), out, i32(0), lse, i32(1), i32(4), i32(1), i32(100),
+                                                  i32(a["runs"]), i32(128), i32(1), ws, big, None)
+
+    assert windowed(resident=9) == -1                       # the resident run must be one of the runs
+    assert windowed(resident=-2) == -1
+    assert windowed(nprobe=9) == -1                         # nprobe + the resident run > runs
+    st = lib.saap_build_windowed_index(q, K, V, off, ln, sel, out, lse, sel, i32(1), i32(1), i32(100), i32(100), i32(8),
+                                       i32(128), i32(1), i32(2), i32(1), i32(15), ws, big, None)
+    assert st == -1                                         # Ncap != N - W + B*slack + W = 116
+    st = lib.saap_build_windowed_index(q, K, V, off, ln, sel, out, lse, None, i32(1), i32(1), i32(100), i32(116), i32(8),
+                                       i32(128), i32(1), i32(2), i32(1), i32(15), ws, big, None)
+    assert st == -1                                         # resident_ids missing
+    st = lib.saap_window_push(q, K, V, None, q, None, off, ln, sel, out, lse, sel, sel, sel, i32(1), i32(1), i32(116),
+                              i32(8), i32(128), i32(1), i32(1), i32(15), None)
+    assert st == -1                                         # pos_new missing
+    st = lib.saap_window_push(q, K, V, sel, q, None, off, ln, sel, out, lse, sel, sel, sel, i32(1), i32(1), i32(10),
+                              i32(8), i32(128), i32(1), i32(1), i32(15), None)
+    assert st == -1                                         # window larger than the cache
+
 
 def test_binding_refuses_host_tensors():
     import torch
