@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg (0 = skip)")
     ap.add_argument("--slack", type=int, default=0)
     ap.add_argument("--no-dense", action="store_true", help="skip the dense baseline (keeps profiler summaries to the sparse path)")
+    ap.add_argument("--window", default="", help="also time the step with an attention sink + recent-key window, "
+                    "e.g. 1+2047 (the paper's default): adds a `window` object to the output")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of 256 MiB (reference for the HBM byte counters)")
     return ap.parse_args()
@@ -143,6 +145,14 @@ def main():
     off, ln, idx, Ks, Vs = index
     n_keys_total = cfg.S * cfg.Hkv * cfg.N
     assign_flop = 2.0 * n_keys_total * cfg.B * cfg.d
+    window = None
+    if args.window:
+        # the same cache indexed with a resident run (sink + recent keys); the step then also pushes
+        # the token's own key: classify + select + windowed attention + window_push
+        n_sink, n_recent = (int(v) for v in args.window.split("+"))
+        w_slack = 64
+        w_state = saap.build_windowed_index(ids, cache["K"], cache["V"], cfg.B, w_slack, n_sink, n_recent)
+        window = (n_sink, n_recent, w_state)
     x_keys = cache.pop("x_keys")
     del x_keys
 
@@ -220,6 +230,49 @@ def main():
     ms_probe = GraphLoop(probe, 4, torch).timed_ms_per_call(3)
     ceiling = kv_bytes / (ms_probe * 1e-3) / 1e9
 
+    window_result = None
+    if window:
+        n_sink, n_recent, (w_off, w_ln, w_idx, w_Ks, w_Vs, w_res) = window
+        new = gen.make_cache(cfg.replace(N=T), args.seed, dev)          # T tokens to push, drawn like the cache
+        xn, kn, vn = (new[k].permute(2, 0, 1, 3).contiguous() for k in ("x_keys", "K", "V"))   # [T,S,Hkv,d]
+        pos = (cfg.N + torch.arange(T, dtype=torch.int32, device=dev)).repeat_interleave(cfg.S).reshape(T, cfg.S).contiguous()
+        w_flag = torch.zeros(4, dtype=torch.int32, device=dev)
+        w_new = torch.empty(cfg.S, cfg.Hkv, dtype=torch.int32, device=dev)
+
+        def w_attend(i):
+            saap.windowed_decode_attention(q[i % T], w_Ks, w_Vs, w_off, w_ln, sel_sets[i % T], cfg.B, scale, out=out, lse=lse)
+
+        def w_push(i):
+            # replays push the same T positions again: the ring slots are rewritten and the displaced
+            # copies pile up in the slack, which is sized for the whole run
+            saap.window_push(xn[i % T], kn[i % T], vn[i % T], pos[i % T], cent, None, w_off, w_ln, w_idx, w_Ks, w_Vs,
+                             w_res, n_sink, n_recent, overflow_flag=w_flag, new_ids=w_new)
+
+        def w_step(i):
+            classify(i)
+            select(i)
+            saap.windowed_decode_attention(q[i % T], w_Ks, w_Vs, w_off, w_ln, sel, cfg.B, scale, out=out, lse=lse)
+            w_push(i)
+
+        w_keys = torch.gather(w_ln[:, :, :cfg.B].unsqueeze(0).expand(T, -1, -1, -1).to(torch.int64), 3,
+                              sel_sets.to(torch.int64)).sum(dim=(1, 2, 3)).to(torch.float64).mean().item()
+        w_keys += float(w_ln[:, :, cfg.B].sum().item())
+        w_reps = max(2, min(reps, 4))
+        ms_w_attn = GraphLoop(w_attend, T, torch).timed_ms_per_call(w_reps)
+        ms_w_push = GraphLoop(w_push, T, torch).timed_ms_per_call(w_reps)
+        ms_w_step = GraphLoop(w_step, T, torch).timed_ms_per_call(w_reps)
+        torch.cuda.synchronize()
+        window_result = {
+            "n_sink": n_sink, "n_recent": n_recent, "slack": 64,
+            "step_us_per_token_layer": round(ms_w_step * 1e3 / cfg.S, 3),
+            "step": "classify_queries + select_buckets + windowed_decode_attention + window_push",
+            "windowed_decode_attention_us": round(ms_w_attn * 1e3, 3),
+            "window_push_us": round(ms_w_push * 1e3, 3),
+            "bytes_per_launch": round(w_keys * BYTES_PER_KEY),
+            "achieved_GBps": round(w_keys * BYTES_PER_KEY / (ms_w_attn * 1e-3) / 1e9, 1),
+            "overflow_flag": int(w_flag[0].item()),
+        }
+
     # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary of
     # this workload (a separate profiling run; see profiles/): null if there is none.
     traffic = None
@@ -282,6 +335,8 @@ def main():
         },
         "paper_context": {"flashattention_v2_us": 50, "saap_us": 18, "hardware": "H100 80GB, one head, 171k context"},
     }
+    if window_result:
+        result["window"] = window_result
 
     if args.calibrate_copy:
         # a plain copy of known size: the profiler's FETCH_SIZE / WRITE_SIZE for it give the

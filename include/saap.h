@@ -74,7 +74,8 @@ enum {
   SAAP_OP_SELECT_BUCKETS = 3,
   SAAP_OP_SPARSE_DECODE_ATTENTION = 4,
   SAAP_OP_DENSE_DECODE_ATTENTION = 5,
-  SAAP_OP_APPEND_KEYS = 6
+  SAAP_OP_APPEND_KEYS = 6,
+  SAAP_OP_WINDOW_PUSH = 7
 };
 
 #define SAAP_WS_HEADER_BYTES 65536u
@@ -285,6 +286,8 @@ int32_t saap_build_windowed_index(const int32_t* bucket_ids, const void* K, cons
  * n_recent = 0 the new key goes straight into its bucket.  If the bucket that must take a
  * key has no free slot, nothing changes for that (sequence, head), *overflow_flag is set
  * to 1 and the caller rebuilds the index; the flag is never cleared by the library.
+ * Workspace: SAAP_OP_WINDOW_PUSH (S, Hkv, B): the centroids are scored by ceil(B/64)
+ * workgroups per (sequence, head), which meet through it.
  */
 int32_t saap_window_push(const void* x_new, const void* k_new, const void* v_new,
                          const int32_t* pos_new, const void* centroids, const float* bias,
@@ -292,7 +295,8 @@ int32_t saap_window_push(const void* x_new, const void* k_new, const void* v_new
                          void* Ksorted, void* Vsorted, int32_t* resident_ids,
                          int32_t* new_bucket_ids, int32_t* overflow_flag,
                          int32_t S, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype,
-                         int32_t n_sink, int32_t n_recent, void* stream);
+                         int32_t n_sink, int32_t n_recent,
+                         void* ws, size_t ws_bytes, void* stream);
 
 /*
  * windowed_decode_attention -- saap_sparse_decode_attention over the selected buckets

@@ -15,7 +15,7 @@ F32, BF16 = 0, 1
 GROUP_SUM, INDEPENDENT = 0, 1
 PROBS, LOGITS = 0, 1
 OP_ASSIGN_KEYS, OP_BUILD_BUCKET_INDEX, OP_CLASSIFY_QUERIES, OP_SELECT_BUCKETS = 0, 1, 2, 3
-OP_SPARSE_DECODE_ATTENTION, OP_DENSE_DECODE_ATTENTION, OP_APPEND_KEYS = 4, 5, 6
+OP_SPARSE_DECODE_ATTENTION, OP_DENSE_DECODE_ATTENTION, OP_APPEND_KEYS, OP_WINDOW_PUSH = 4, 5, 6, 7
 WS_HEADER_BYTES = 65536
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -261,20 +261,22 @@ def build_windowed_index(bucket_ids, K, V, B, slack, n_sink, n_recent, ws=None):
 
 
 def window_push(x_new, k_new, v_new, pos_new, centroids, bias, off, ln, idx, Ks, Vs, resident_ids, n_sink, n_recent,
-                overflow_flag=None):
+                overflow_flag=None, new_ids=None, ws=None):
     """In-place push of one key per (sequence, KV head) into the resident run; the displaced key moves
     to its bucket. -> (new_bucket_ids [S,Hkv], overflow_flag)."""
     S, Hkv, d = x_new.shape
     B = centroids.shape[1]
     Ncap = idx.shape[2]
     dev = x_new.device
-    new_ids = torch.empty(S, Hkv, dtype=torch.int32, device=dev)
+    if new_ids is None:
+        new_ids = torch.empty(S, Hkv, dtype=torch.int32, device=dev)
     if overflow_flag is None:
         overflow_flag = torch.zeros(4, dtype=torch.int32, device=dev)
+    ws, wsb = _ws(OP_WINDOW_PUSH, dev, ws, S=S, Hkv=Hkv, B=B)
     st = load_library().saap_window_push(
         _ptr(x_new), _ptr(k_new), _ptr(v_new), _ptr(pos_new), _ptr(centroids), _ptr(bias), _ptr(off), _ptr(ln),
         _ptr(idx), _ptr(Ks), _ptr(Vs), _ptr(resident_ids), _ptr(new_ids), _ptr(overflow_flag), _i32(S), _i32(Hkv),
-        _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(x_new)), _i32(n_sink), _i32(n_recent), _stream())
+        _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(x_new)), _i32(n_sink), _i32(n_recent), _ptr(ws), wsb, _stream())
     _check("saap_window_push", st)
     return new_ids, overflow_flag
 

@@ -214,52 +214,112 @@ template <> __device__ __forceinline__ double to_f64<bf16_t>(bf16_t v) {
   return (double)__uint_as_float((uint32_t)v << 16);
 }
 
-// One workgroup per (sequence, KV head): score the new key against every centroid in double
-// precision (in-order sum of exact products), pick the best bucket (lowest id on ties), and
-// store the key in the bucket's first free slot.
+constexpr int kScoreThreads = 256;    // workgroup size of append_kernel
+constexpr int kPushSlab = 64;         // centroids per workgroup (one wave) of window_push_kernel
+
+// Eight bf16 elements (one 16-byte piece of a row) -> double.
+__device__ __forceinline__ void widen8(const uint4& u, double* o) {
+  o[0] = (double)bf16_lo(u.x); o[1] = (double)bf16_hi(u.x); o[2] = (double)bf16_lo(u.y); o[3] = (double)bf16_hi(u.y);
+  o[4] = (double)bf16_lo(u.z); o[5] = (double)bf16_hi(u.z); o[6] = (double)bf16_lo(u.w); o[7] = (double)bf16_hi(u.w);
+}
+
+// Score of one centroid row against the key in s_x: the in-order double-precision sum of the
+// exact products.  All 16-byte loads of the row (of half a row for fp32) are issued before the
+// dependent chain of 128 fused multiply-adds starts.
 template <typename T>
-__global__ void __launch_bounds__(256)
+__device__ __forceinline__ double score_row(const T* __restrict__ c, const double* __restrict__ s_x);
+template <>
+__device__ __forceinline__ double score_row<bf16_t>(const bf16_t* __restrict__ c, const double* __restrict__ s_x) {
+  uint4 u[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) u[i] = reinterpret_cast<const uint4*>(c)[i];
+  double t = 0.0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    double w[8];
+    widen8(u[i], w);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t = fma(s_x[i * 8 + j], w[j], t);
+  }
+  return t;
+}
+template <>
+__device__ __forceinline__ double score_row<float>(const float* __restrict__ c, const double* __restrict__ s_x) {
+  double t = 0.0;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    float4 u[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) u[i] = reinterpret_cast<const float4*>(c)[half * 16 + i];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int j = (half * 16 + i) * 4;
+      t = fma(s_x[j + 0], (double)u[i].x, t);
+      t = fma(s_x[j + 1], (double)u[i].y, t);
+      t = fma(s_x[j + 2], (double)u[i].z, t);
+      t = fma(s_x[j + 3], (double)u[i].w, t);
+    }
+  }
+  return t;
+}
+
+// (score, id) candidates: o beats m if it exists and is larger, or equal with the lower id.
+__device__ __forceinline__ void take_better(double& best, int& best_id, double ob, int oid) {
+  if (oid >= 0 && (best_id < 0 || ob > best || (ob == best && oid < best_id))) {
+    best = ob;
+    best_id = oid;
+  }
+}
+// Best candidate of the wave, in every lane.
+__device__ __forceinline__ void wave_best(double& best, int& best_id) {
+#pragma unroll
+  for (int sh = 32; sh > 0; sh >>= 1) {
+    const double ob = __shfl_xor(best, sh);
+    const int oid = __shfl_xor(best_id, sh);
+    take_better(best, best_id, ob, oid);
+  }
+}
+
+// One workgroup per (sequence, KV head): find the new key's bucket (argmax_b <x, c_b> + bias_b in
+// double precision, lowest id on ties: the definition saap_assign_keys states) and store the key
+// in the bucket's first free slot.
+template <typename T>
+__global__ void __launch_bounds__(kScoreThreads)
 append_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, const T* __restrict__ v_new,
               const int32_t* __restrict__ pos_new, const T* __restrict__ cent, const float* __restrict__ bias,
               const int32_t* __restrict__ off, int32_t* __restrict__ len, int32_t* __restrict__ idx,
               T* __restrict__ Ks, T* __restrict__ Vs, int32_t* __restrict__ new_ids,
               int32_t* __restrict__ overflow, int Hkv, int Ncap, int B) {
   __shared__ double s_x[kD];
-  __shared__ double s_best[256];
-  __shared__ int s_id[256];
+  __shared__ double s_best[kScoreThreads / 64];
+  __shared__ int s_id[kScoreThreads / 64];
   __shared__ int s_slot;
-  const int unit = blockIdx.x, h = unit % Hkv, tid = threadIdx.x;
-  if (tid < kD) s_x[tid] = to_f64<T>(x_new[(size_t)unit * kD + tid]);
+  const int unit = blockIdx.x, h = unit % Hkv, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the row to store does not depend on the bucket: fetch it while the scores are computed
+  T kx = T(), vx = T();
+  if (tid < kD) {
+    kx = k_new[(size_t)unit * kD + tid];
+    vx = v_new[(size_t)unit * kD + tid];
+    s_x[tid] = to_f64<T>(x_new[(size_t)unit * kD + tid]);
+  }
   __syncthreads();
   double best = 0.0;
   int best_id = -1;
-  for (int b = tid; b < B; b += blockDim.x) {
-    const T* c = cent + ((size_t)h * B + b) * kD;
-    double t = 0.0;
-    for (int j = 0; j < kD; ++j) t = fma(s_x[j], to_f64<T>(c[j]), t);
+  for (int b = tid; b < B; b += kScoreThreads) {      // ascending b per thread
+    double t = score_row<T>(cent + ((size_t)h * B + b) * kD, s_x);
     if (bias) t += (double)bias[(size_t)h * B + b];
-    if (best_id < 0 || t > best) {
-      best = t;
-      best_id = b;
-    }
+    take_better(best, best_id, t, b);
   }
-  s_best[tid] = best;
-  s_id[tid] = best_id;
+  wave_best(best, best_id);
+  if (lane == 0) {
+    s_best[wave] = best;
+    s_id[wave] = best_id;
+  }
   __syncthreads();
-  for (int s = blockDim.x >> 1; s > 0; s >>= 1) {
-    if (tid < s) {
-      const int oid = s_id[tid + s];
-      const double ob = s_best[tid + s];
-      const int mid = s_id[tid];
-      if (oid >= 0 && (mid < 0 || ob > s_best[tid] || (ob == s_best[tid] && oid < mid))) {
-        s_best[tid] = ob;
-        s_id[tid] = oid;
-      }
-    }
-    __syncthreads();
-  }
-  const int b = s_id[0];
   if (tid == 0) {
+#pragma unroll
+    for (int w = 1; w < kScoreThreads / 64; ++w) take_better(best, best_id, s_best[w], s_id[w]);
+    const int b = best_id;
     new_ids[unit] = b;
     const int32_t* o = off + (size_t)unit * (B + 1);
     const int cur = len[(size_t)unit * B + b];
@@ -276,117 +336,151 @@ append_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, const T*
   __syncthreads();
   const int slot = s_slot;
   if (slot >= 0 && tid < kD) {
-    Ks[((size_t)unit * Ncap + slot) * kD + tid] = k_new[(size_t)unit * kD + tid];
-    Vs[((size_t)unit * Ncap + slot) * kD + tid] = v_new[(size_t)unit * kD + tid];
+    Ks[((size_t)unit * Ncap + slot) * kD + tid] = kx;
+    Vs[((size_t)unit * Ncap + slot) * kD + tid] = vx;
   }
 }
 
-// One workgroup per (sequence, KV head): the new key is scored as in append_kernel and enters
-// the resident run; the key whose ring slot it takes moves to the first free slot of its own
-// bucket.  Thread 0 decides (slot, destination) and updates len / idx / res_ids; the row copies
-// are done by the first 128 threads, each reading the old element before it writes the new one.
+// Best candidate of one slab of centroids, as exchanged between the workgroups of a unit.
+struct PushPartial {
+  double score;
+  int id;
+  int pad;
+};
+
+// window_push: P = ceil(B / 64) one-wave workgroups per (sequence, KV head), each scoring a slab of
+// 64 centroids (one per lane); the last to arrive picks the bucket and does the bookkeeping.
+// Which key is displaced and where it goes does not depend on the new key's bucket: every
+// workgroup reads that state up front (the loads overlap the scoring), slab 0 copies the displaced
+// row to its bucket, and the last workgroup, which runs after all of these reads, writes the new
+// row and the updated counts.
 template <typename T>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64)
 window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, const T* __restrict__ v_new,
                    const int32_t* __restrict__ pos_new, const T* __restrict__ cent, const float* __restrict__ bias,
                    const int32_t* __restrict__ off, int32_t* __restrict__ len, int32_t* __restrict__ idx,
                    T* __restrict__ Ks, T* __restrict__ Vs, int32_t* __restrict__ res_ids,
-                   int32_t* __restrict__ new_ids, int32_t* __restrict__ overflow, int Hkv, int Ncap, int B,
-                   int n_sink, int n_recent) {
+                   int32_t* __restrict__ new_ids, int32_t* __restrict__ overflow, PushPartial* __restrict__ part,
+                   unsigned* __restrict__ counters, int Hkv, int Ncap, int B, int n_sink, int n_recent, int P) {
   __shared__ double s_x[kD];
-  __shared__ double s_best[256];
-  __shared__ int s_id[256];
-  __shared__ int s_slot, s_dst;
-  const int unit = blockIdx.x, h = unit % Hkv, tid = threadIdx.x;
-  if (tid < kD) s_x[tid] = to_f64<T>(x_new[(size_t)unit * kD + tid]);
+  const int slab = blockIdx.x, unit = blockIdx.y, h = unit % Hkv, lane = threadIdx.x;
+  const int W = n_sink + n_recent;
+  const int32_t* o = off + (size_t)unit * (B + 2);
+  int32_t* l = len + (size_t)unit * (B + 1);
+  int32_t* ix = idx + (size_t)unit * Ncap;
+  int32_t* rid = res_ids + (size_t)unit * W;
+  T* Ku = Ks + (size_t)unit * Ncap * kD;
+  T* Vu = Vs + (size_t)unit * Ncap * kD;
+
+  // ---- the new key, and what can be decided without its bucket (same values in every lane) ----
+  const T x0 = x_new[(size_t)unit * kD + lane], x1 = x_new[(size_t)unit * kD + 64 + lane];
+  const T k0 = k_new[(size_t)unit * kD + lane], k1 = k_new[(size_t)unit * kD + 64 + lane];
+  const T v0 = v_new[(size_t)unit * kD + lane], v1 = v_new[(size_t)unit * kD + 64 + lane];
+  const int pos = pos_new[unit / Hkv];
+  const int res_base = o[B];
+  // -1: refused   0: slot of a run that is still filling   1: ring slot, a key is displaced   2: no ring
+  const int kind = pos < 0 ? -1 : pos < W ? 0 : n_recent > 0 ? 1 : 2;
+  int slot = -1, dst = -1, e = -1, cur = 0, moved_pos = -1;
+  bool refused = kind < 0;
+  if (kind == 0) {
+    slot = res_base + pos;                     // r(pos) = pos while the run is not full
+  } else if (kind == 1) {
+    const int r = n_sink + (pos - n_sink) % n_recent;
+    e = rid[r];
+    // e outside [0,B) means the caller broke the protocol (pushes out of order, foreign state):
+    // refuse like a full bucket instead of indexing with it
+    const bool ok = e >= 0 && e < B;
+    cur = ok ? l[e] : 0;
+    if (ok && o[e] + cur < o[e + 1]) {
+      slot = res_base + r;
+      dst = o[e] + cur;
+      moved_pos = ix[slot];
+    } else {
+      refused = true;
+    }
+  }
+  if (slab == 0 && dst >= 0) {                 // the displaced row: ring slot -> its bucket
+    Ku[(size_t)dst * kD + lane] = Ku[(size_t)slot * kD + lane];
+    Ku[(size_t)dst * kD + 64 + lane] = Ku[(size_t)slot * kD + 64 + lane];
+    Vu[(size_t)dst * kD + lane] = Vu[(size_t)slot * kD + lane];
+    Vu[(size_t)dst * kD + 64 + lane] = Vu[(size_t)slot * kD + 64 + lane];
+  }
+
+  // ---- this slab's best centroid ----
+  s_x[lane] = to_f64<T>(x0);
+  s_x[64 + lane] = to_f64<T>(x1);
   __syncthreads();
+  const int bc = slab * kPushSlab + lane;
   double best = 0.0;
   int best_id = -1;
-  for (int b = tid; b < B; b += blockDim.x) {
-    const T* c = cent + ((size_t)h * B + b) * kD;
-    double t = 0.0;
-    for (int j = 0; j < kD; ++j) t = fma(s_x[j], to_f64<T>(c[j]), t);
-    if (bias) t += (double)bias[(size_t)h * B + b];
-    if (best_id < 0 || t > best) {
-      best = t;
-      best_id = b;
-    }
+  if (bc < B) {
+    best = score_row<T>(cent + ((size_t)h * B + bc) * kD, s_x);
+    if (bias) best += (double)bias[(size_t)h * B + bc];
+    best_id = bc;
   }
-  s_best[tid] = best;
-  s_id[tid] = best_id;
-  __syncthreads();
-  for (int s = blockDim.x >> 1; s > 0; s >>= 1) {
-    if (tid < s) {
-      const int oid = s_id[tid + s];
-      const double ob = s_best[tid + s];
-      const int mid = s_id[tid];
-      if (oid >= 0 && (mid < 0 || ob > s_best[tid] || (ob == s_best[tid] && oid < mid))) {
-        s_best[tid] = ob;
-        s_id[tid] = oid;
-      }
+  wave_best(best, best_id);
+  if (P > 1) {
+    if (lane == 0) {
+      PushPartial* mine = part + (size_t)unit * P + slab;
+      __hip_atomic_store(&mine->score, best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&mine->id, best_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __syncthreads();
+    // every load above has returned and every store has been acknowledged before the arrival counts
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    unsigned old = 0;
+    if (lane == 0) old = __hip_atomic_fetch_add(&counters[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = (unsigned)__shfl((int)old, 0);
+    if (old != (unsigned)(P - 1)) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    best = 0.0;
+    best_id = -1;
+    for (int i = lane; i < P; i += 64) {       // ascending slabs per lane
+      const PushPartial* q = part + (size_t)unit * P + i;
+      take_better(best, best_id, q->score, q->id);
+    }
+    wave_best(best, best_id);
+    if (lane == 0) __hip_atomic_store(&counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  const int b = s_id[0];
-  const int W = n_sink + n_recent;
-  if (tid == 0) {
+
+  // ---- bookkeeping, by the one workgroup that knows the bucket ----
+  const int b = best_id;
+  if (kind == 2) {                             // no ring: the new key goes straight into its bucket
+    const int c2 = l[b];
+    if (o[b] + c2 < o[b + 1]) slot = o[b] + c2; else refused = true;
+    cur = c2;
+  }
+  if (lane == 0) {
     new_ids[unit] = b;
-    const int32_t* o = off + (size_t)unit * (B + 2);
-    int32_t* l = len + (size_t)unit * (B + 1);
-    int32_t* ix = idx + (size_t)unit * Ncap;
-    int32_t* rid = res_ids + (size_t)unit * W;
-    const int pos = pos_new[unit / Hkv];
-    int slot = -1, dst = -1;        // slot: receives the new key; dst: receives the displaced key
-    if (pos < 0) {
+    if (refused) {
       *overflow = 1;
-    } else if (pos < W) {           // the resident run is not full yet: r(pos) = pos
-      slot = o[B] + pos;
-      l[B] += 1;
-      rid[pos] = b;
-    } else if (n_recent == 0) {     // no ring: straight into the bucket
-      const int cur = l[b];
-      if (o[b] + cur < o[b + 1]) {
-        slot = o[b] + cur;
-        l[b] = cur + 1;
-      } else {
-        *overflow = 1;
-      }
     } else {
-      const int r = n_sink + (pos - n_sink) % n_recent;
-      const int e = rid[r];
-      // e outside [0,B) means the caller broke the protocol (pushes out of order, foreign state):
-      // refuse like a full bucket instead of indexing with it
-      const bool ok = e >= 0 && e < B;
-      const int cur = ok ? l[e] : 0;
-      if (ok && o[e] + cur < o[e + 1]) {
-        slot = o[B] + r;
-        dst = o[e] + cur;
+      if (kind == 0) {
+        l[B] += 1;
+        rid[pos] = b;
+      } else if (kind == 1) {
         l[e] = cur + 1;
-        ix[dst] = ix[slot];
-        rid[r] = b;
+        ix[dst] = moved_pos;
+        rid[slot - res_base] = b;
       } else {
-        *overflow = 1;
+        l[b] = cur + 1;
       }
+      ix[slot] = pos;
     }
-    if (slot >= 0) ix[slot] = pos;
-    s_slot = slot;
-    s_dst = dst;
   }
-  __syncthreads();
-  const int slot = s_slot, dst = s_dst;
-  if (slot >= 0 && tid < kD) {
-    T* ks = Ks + ((size_t)unit * Ncap + slot) * kD + tid;
-    T* vs = Vs + ((size_t)unit * Ncap + slot) * kD + tid;
-    if (dst >= 0) {
-      Ks[((size_t)unit * Ncap + dst) * kD + tid] = *ks;
-      Vs[((size_t)unit * Ncap + dst) * kD + tid] = *vs;
-    }
-    *ks = k_new[(size_t)unit * kD + tid];
-    *vs = v_new[(size_t)unit * kD + tid];
+  if (!refused) {
+    Ku[(size_t)slot * kD + lane] = k0;
+    Ku[(size_t)slot * kD + 64 + lane] = k1;
+    Vu[(size_t)slot * kD + lane] = v0;
+    Vu[(size_t)slot * kD + 64 + lane] = v1;
   }
 }
 
 }  // namespace
+
+size_t push_workspace_bytes(long long units, int B) {
+  const long long P = (B + kPushSlab - 1) / kPushSlab;
+  return (size_t)SAAP_WS_HEADER_BYTES + (size_t)units * P * sizeof(PushPartial);
+}
 
 size_t build_workspace_bytes(long long units, int N, int B) {
   const long long n_slices = (N + kSlice - 1) / kSlice;
@@ -481,28 +575,36 @@ extern "C" int32_t saap_window_push(const void* x_new, const void* k_new, const 
                                     const int32_t* off, int32_t* len, int32_t* idx, void* Ksorted,
                                     void* Vsorted, int32_t* resident_ids, int32_t* new_bucket_ids,
                                     int32_t* overflow_flag, int32_t S, int32_t Hkv, int32_t Ncap, int32_t B,
-                                    int32_t d, int32_t dtype, int32_t n_sink, int32_t n_recent, void* stream) {
+                                    int32_t d, int32_t dtype, int32_t n_sink, int32_t n_recent, void* ws,
+                                    size_t ws_bytes, void* stream) {
   if (!x_new || !k_new || !v_new || !pos_new || !centroids || !off || !len || !idx || !Ksorted || !Vsorted ||
-      !resident_ids || !new_bucket_ids || !overflow_flag)
+      !resident_ids || !new_bucket_ids || !overflow_flag || !ws)
     return SAAP_INVALID_ARG;
+  if (!aligned16(centroids) || !aligned16(ws)) return SAAP_INVALID_ARG;
   if (S <= 0 || Hkv <= 0 || Ncap <= 0 || B <= 0 || n_sink < 0 || n_recent < 0) return SAAP_INVALID_ARG;
   if ((long long)n_sink + n_recent > Ncap) return SAAP_INVALID_ARG;
   if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
-  if (d != kD) return SAAP_UNSUPPORTED;
+  if (d != kD || B > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
+  const long long units = (long long)S * Hkv;
+  if (units > 65535 || units * sizeof(unsigned) > SAAP_WS_HEADER_BYTES) return SAAP_UNSUPPORTED;
+  if (ws_bytes < push_workspace_bytes(units, B)) return SAAP_WORKSPACE_TOO_SMALL;
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  const unsigned units = (unsigned)((long long)S * Hkv);
+  const int P = (B + kPushSlab - 1) / kPushSlab;
+  unsigned* counters = static_cast<unsigned*>(ws);
+  PushPartial* part = reinterpret_cast<PushPartial*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
+  const dim3 grid((unsigned)P, (unsigned)units);
   if (dtype == SAAP_BF16)
-    hipLaunchKernelGGL(window_push_kernel<bf16_t>, dim3(units), dim3(256), 0, hs,
-                       static_cast<const bf16_t*>(x_new), static_cast<const bf16_t*>(k_new),
-                       static_cast<const bf16_t*>(v_new), pos_new, static_cast<const bf16_t*>(centroids), bias,
-                       off, len, idx, static_cast<bf16_t*>(Ksorted), static_cast<bf16_t*>(Vsorted),
-                       resident_ids, new_bucket_ids, overflow_flag, Hkv, Ncap, B, n_sink, n_recent);
+    hipLaunchKernelGGL(window_push_kernel<bf16_t>, grid, dim3(64), 0, hs, static_cast<const bf16_t*>(x_new),
+                       static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new), pos_new,
+                       static_cast<const bf16_t*>(centroids), bias, off, len, idx, static_cast<bf16_t*>(Ksorted),
+                       static_cast<bf16_t*>(Vsorted), resident_ids, new_bucket_ids, overflow_flag, part, counters,
+                       Hkv, Ncap, B, n_sink, n_recent, P);
   else
-    hipLaunchKernelGGL(window_push_kernel<float>, dim3(units), dim3(256), 0, hs,
-                       static_cast<const float*>(x_new), static_cast<const float*>(k_new),
-                       static_cast<const float*>(v_new), pos_new, static_cast<const float*>(centroids), bias, off,
-                       len, idx, static_cast<float*>(Ksorted), static_cast<float*>(Vsorted), resident_ids,
-                       new_bucket_ids, overflow_flag, Hkv, Ncap, B, n_sink, n_recent);
+    hipLaunchKernelGGL(window_push_kernel<float>, grid, dim3(64), 0, hs, static_cast<const float*>(x_new),
+                       static_cast<const float*>(k_new), static_cast<const float*>(v_new), pos_new,
+                       static_cast<const float*>(centroids), bias, off, len, idx, static_cast<float*>(Ksorted),
+                       static_cast<float*>(Vsorted), resident_ids, new_bucket_ids, overflow_flag, part, counters,
+                       Hkv, Ncap, B, n_sink, n_recent, P);
   return launch_status();
 }
 
@@ -515,19 +617,20 @@ extern "C" int32_t saap_append_keys(const void* x_new, const void* k_new, const 
   if (!x_new || !k_new || !v_new || !centroids || !off || !len || !idx || !Ksorted || !Vsorted ||
       !new_bucket_ids || !overflow_flag)
     return SAAP_INVALID_ARG;
+  if (!aligned16(centroids)) return SAAP_INVALID_ARG;
   if (S <= 0 || Hkv <= 0 || Ncap <= 0 || B <= 0) return SAAP_INVALID_ARG;
   if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
   if (d != kD) return SAAP_UNSUPPORTED;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   const unsigned units = (unsigned)((long long)S * Hkv);
   if (dtype == SAAP_BF16)
-    hipLaunchKernelGGL(append_kernel<bf16_t>, dim3(units), dim3(256), 0, hs,
+    hipLaunchKernelGGL(append_kernel<bf16_t>, dim3(units), dim3(kScoreThreads), 0, hs,
                        static_cast<const bf16_t*>(x_new), static_cast<const bf16_t*>(k_new),
                        static_cast<const bf16_t*>(v_new), pos_new, static_cast<const bf16_t*>(centroids), bias,
                        off, len, idx, static_cast<bf16_t*>(Ksorted), static_cast<bf16_t*>(Vsorted),
                        new_bucket_ids, overflow_flag, Hkv, Ncap, B);
   else
-    hipLaunchKernelGGL(append_kernel<float>, dim3(units), dim3(256), 0, hs, static_cast<const float*>(x_new),
+    hipLaunchKernelGGL(append_kernel<float>, dim3(units), dim3(kScoreThreads), 0, hs, static_cast<const float*>(x_new),
                        static_cast<const float*>(k_new), static_cast<const float*>(v_new), pos_new,
                        static_cast<const float*>(centroids), bias, off, len, idx,
                        static_cast<float*>(Ksorted), static_cast<float*>(Vsorted), new_bucket_ids,

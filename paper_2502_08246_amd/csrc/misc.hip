@@ -7,6 +7,7 @@ namespace saap {
 size_t attn_workspace_bytes(long long units, int G);
 size_t assign_workspace_bytes(long long rows);
 size_t build_workspace_bytes(long long units, int N, int B);
+size_t push_workspace_bytes(long long units, int B);
 size_t classify_workspace_bytes(long long rows, int hidden);
 
 int device_cus() {
@@ -82,6 +83,9 @@ extern "C" size_t saap_workspace_bytes(int32_t op, const saap_shape* sh) {
     case SAAP_OP_CLASSIFY_QUERIES:
       if (S <= 0 || Hq <= 0 || sh->hidden <= 0) return 0;
       return classify_workspace_bytes(S * Hq, sh->hidden);
+    case SAAP_OP_WINDOW_PUSH:
+      if (S <= 0 || Hkv <= 0 || sh->B <= 0) return 0;
+      return push_workspace_bytes(S * Hkv, sh->B);
     case SAAP_OP_SELECT_BUCKETS:
     case SAAP_OP_APPEND_KEYS:
       return SAAP_WS_HEADER_BYTES;

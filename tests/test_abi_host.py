@@ -123,11 +123,14 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
                                        i32(128), i32(1), i32(2), i32(1), i32(15), ws, big, None)
     assert st == -1                                         # resident_ids missing
     st = lib.saap_window_push(q, K, V, None, q, None, off, ln, sel, out, lse, sel, sel, sel, i32(1), i32(1), i32(116),
-                              i32(8), i32(128), i32(1), i32(1), i32(15), None)
+                              i32(8), i32(128), i32(1), i32(1), i32(15), ws, big, None)
     assert st == -1                                         # pos_new missing
     st = lib.saap_window_push(q, K, V, sel, q, None, off, ln, sel, out, lse, sel, sel, sel, i32(1), i32(1), i32(10),
-                              i32(8), i32(128), i32(1), i32(1), i32(15), None)
+                              i32(8), i32(128), i32(1), i32(1), i32(15), ws, big, None)
     assert st == -1                                         # window larger than the cache
+    st = lib.saap_window_push(q, K, V, sel, q, None, off, ln, sel, out, lse, sel, sel, sel, i32(1), i32(1), i32(116),
+                              i32(8), i32(128), i32(1), i32(1), i32(15), ws, ctypes.c_size_t(100), None)
+    assert st == -3
 
 
 def test_binding_refuses_host_tensors():
