@@ -208,6 +208,23 @@ int32_t saap_select_buckets(const float* scores, int32_t* selected,
                             int32_t mode, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * select_buckets_from_logits -- saap_select_buckets with the last step of the query
+ * classifier folded in (Section 4 "Asymmetric assignment": f_q ends in a distribution over
+ * the buckets; Section 5 "Batched queries": the distributions of a group are summed), one
+ * launch less per decode step:
+ *   p[s,hq,:] = softmax(logits[s,hq,:]) in fp32,  then select as saap_select_buckets does on p.
+ *   logits [S,Hq,B] fp32 as written by saap_classify_queries with SAAP_LOGITS
+ *   probs  [S,Hq,B] fp32 out, or NULL: the probabilities the selection was made from
+ *          (written when nprobe > 0)
+ * Covers nprobe up to half of B rounded up to a power of two (the range served by the radix
+ * selection) and G in {1, 2, 4, 8}; otherwise SAAP_UNSUPPORTED, and the caller uses SAAP_PROBS +
+ * saap_select_buckets.
+ */
+int32_t saap_select_buckets_from_logits(const float* logits, float* probs, int32_t* selected,
+                                        int32_t S, int32_t Hq, int32_t Hkv, int32_t B, int32_t nprobe,
+                                        int32_t mode, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * sparse_decode_attention -- exact softmax attention over the union of the
  * selected buckets (Section 4 "Beyond top-k"; Appendix F Algorithms 1 and 2:
  * partial attention with a running maximum, then a log-sum-exp merge):

@@ -27,6 +27,7 @@ EXPORTS = (
     "saap_assign_keys", "saap_build_bucket_index", "saap_append_keys", "saap_classify_queries",
     "saap_select_buckets", "saap_sparse_decode_attention", "saap_dense_decode_attention", "saap_stream_read_probe",
     "saap_build_windowed_index", "saap_window_push", "saap_windowed_decode_attention",
+    "saap_select_buckets_from_logits",
 )
 
 
@@ -215,6 +216,20 @@ def select_buckets(scores, Hkv, nprobe, mode=GROUP_SUM, out=None, ws=None):
     st = load_library().saap_select_buckets(_ptr(scores), _ptr(sel), _i32(S), _i32(Hq), _i32(Hkv), _i32(B),
                                             _i32(nprobe), _i32(mode), _ptr(ws), wsb, _stream())
     _check("saap_select_buckets", st)
+    return sel
+
+
+def select_buckets_from_logits(logits, Hkv, nprobe, mode=GROUP_SUM, probs=None, out=None, ws=None):
+    """logits fp32 [S,Hq,B] (classify_queries with LOGITS) -> selected; `probs` (optional fp32 [S,Hq,B]) receives
+    the softmax the selection was made from."""
+    S, Hq, B = logits.shape
+    lists = Hq if mode == INDEPENDENT else Hkv
+    sel = out if out is not None else torch.empty(S, lists, nprobe, dtype=torch.int32, device=logits.device)
+    ws, wsb = _ws(OP_SELECT_BUCKETS, logits.device, ws)
+    st = load_library().saap_select_buckets_from_logits(_ptr(logits), _ptr(probs), _ptr(sel), _i32(S), _i32(Hq),
+                                                        _i32(Hkv), _i32(B), _i32(nprobe), _i32(mode), _ptr(ws), wsb,
+                                                        _stream())
+    _check("saap_select_buckets_from_logits", st)
     return sel
 
 

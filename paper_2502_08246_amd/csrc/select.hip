@@ -76,10 +76,91 @@ select_kernel(const float* __restrict__ scores, int32_t* __restrict__ selected, 
 }
 
 
-template <int EPT>
+// max / sum over the 64 lanes of a wave on DPP and row swaps (no LDS crossbar); every lane gets it
+__device__ __forceinline__ float wave_max_f32(float x) {
+  x = fmaxf(x, dpp_mov<kDppXor1>(x));
+  x = fmaxf(x, dpp_mov<kDppXor2>(x));
+  x = fmaxf(x, dpp_mov<kDppHalfMirror>(x));
+  x = fmaxf(x, dpp_mov<kDppMirror>(x));
+  return max_rows(x);
+}
+__device__ __forceinline__ float wave_sum_f32(float x) { return sum_rows(sum16(x)); }
+
+// Softmax of the list's HEADS rows of logits, held EPT per thread, and their sum over the heads:
+// p = exp(z - max z) / sum exp(z - max z) per row in fp32, g = ((p_0 + p_1) + p_2) + ... in head
+// order.  The probabilities are also written to `p_rows` if it is not null, so that what was
+// selected from can be checked.  Called by the whole workgroup.
+template <int EPT, int HEADS>
+__device__ __forceinline__ void softmax_group_scores(const float* __restrict__ z_rows, float* __restrict__ p_rows,
+                                                     int B, float* gs) {
+  __shared__ float s_red[2][16][HEADS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nt = blockDim.x, nw = nt >> 6;
+  float z[EPT][HEADS];
+  // every load is unconditional (clamped index) so that all of them are in flight together;
+  // what lies outside the row becomes -inf afterwards
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int b = min(tid + e * nt, B - 1);
+#pragma unroll
+    for (int i = 0; i < HEADS; ++i) z[e][i] = z_rows[(size_t)i * B + b];
+  }
+  float red[HEADS];
+#pragma unroll
+  for (int i = 0; i < HEADS; ++i) {
+    float m = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if (tid + e * nt >= B) z[e][i] = -INFINITY;
+      m = fmaxf(m, z[e][i]);
+    }
+    red[i] = wave_max_f32(m);
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int i = 0; i < HEADS; ++i) s_red[0][wave][i] = red[i];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < HEADS; ++i) {
+    float m = s_red[0][0][i];
+    for (int w = 1; w < nw; ++w) m = fmaxf(m, s_red[0][w][i]);
+    float sum = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      z[e][i] = __expf(z[e][i] - m);      // exp(-inf) = 0 for the padding
+      sum += z[e][i];
+    }
+    red[i] = wave_sum_f32(sum);
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int i = 0; i < HEADS; ++i) s_red[1][wave][i] = red[i];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < HEADS; ++i) {
+    float sum = s_red[1][0][i];
+    for (int w = 1; w < nw; ++w) sum += s_red[1][w][i];
+    red[i] = 1.0f / sum;
+  }
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int b = tid + e * nt;
+    float g = 0.f;
+#pragma unroll
+    for (int i = 0; i < HEADS; ++i) {
+      const float pr = z[e][i] * red[i];
+      if (p_rows && b < B) p_rows[(size_t)i * B + b] = pr;
+      g = i == 0 ? pr : g + pr;
+    }
+    gs[e] = g + 0.0f;
+  }
+}
+
+template <int EPT, bool LOGITS>
 __global__ void __launch_bounds__(1024)
-select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ selected, int Hq, int Hkv, int B,
-                    int nprobe, int independent, int n_sort) {
+select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs, int32_t* __restrict__ selected,
+                    int Hq, int Hkv, int B, int nprobe, int independent, int n_sort) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned long long* sortbuf = reinterpret_cast<unsigned long long*>(smem);   // [n_sort]
   unsigned* eqbits = reinterpret_cast<unsigned*>(sortbuf + n_sort);            // [B/32 + 1]
@@ -96,10 +177,21 @@ select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ sele
   unsigned key[EPT];
   {
     float gs[EPT];
+    if constexpr (LOGITS) {
+      float* pr = probs ? probs + row0 * B : nullptr;
+      switch (heads) {
+        case 1: softmax_group_scores<EPT, 1>(sc, pr, B, gs); break;
+        case 2: softmax_group_scores<EPT, 2>(sc, pr, B, gs); break;
+        case 4: softmax_group_scores<EPT, 4>(sc, pr, B, gs); break;
+        default: softmax_group_scores<EPT, 8>(sc, pr, B, gs); break;
+      }
+      SAAP_TRACE(5);
+    } else {
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      const int b = tid + e * nt;
-      gs[e] = group_score(sc, heads, B, b < B ? b : 0);
+      for (int e = 0; e < EPT; ++e) {
+        const int b = tid + e * nt;
+        gs[e] = group_score(sc, heads, B, b < B ? b : 0);
+      }
     }
 #pragma unroll
     for (int e = 0; e < EPT; ++e) key[e] = tid + e * nt < B ? float_order_key(gs[e]) : 0u;   // 0 sorts below every finite score
@@ -262,16 +354,19 @@ select_radix_kernel(const float* __restrict__ scores, int32_t* __restrict__ sele
 
 using namespace saap;
 
-extern "C" int32_t saap_select_buckets(const float* scores, int32_t* selected, int32_t S, int32_t Hq,
-                                       int32_t Hkv, int32_t B, int32_t nprobe, int32_t mode, void* ws,
-                                       size_t ws_bytes, void* stream) {
-  (void)ws;
-  (void)ws_bytes;
-  if (!scores || !aligned16(scores)) return SAAP_INVALID_ARG;
+// Shared body: `logits` false selects from `scores` as given; true applies the row softmax first
+// (and writes the probabilities to `probs` if it is not null).
+static int32_t select_impl(const float* scores, bool logits, float* probs, int32_t* selected, int32_t S,
+                           int32_t Hq, int32_t Hkv, int32_t B, int32_t nprobe, int32_t mode, void* stream) {
+  if (!scores || !aligned16(scores) || !aligned16(probs)) return SAAP_INVALID_ARG;
   if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || B <= 0) return SAAP_INVALID_ARG;
   if (mode != SAAP_GROUP_SUM && mode != SAAP_INDEPENDENT) return SAAP_INVALID_ARG;
   if (nprobe < 0 || nprobe > B) return SAAP_INVALID_ARG;
   if (B > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
+  if (logits && mode == SAAP_GROUP_SUM) {
+    const int G = Hq / Hkv;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return SAAP_UNSUPPORTED;
+  }
   if (nprobe == 0) return SAAP_OK;
   if (!selected || !aligned16(selected)) return SAAP_INVALID_ARG;
   int n_pow2 = 2;
@@ -281,7 +376,8 @@ extern "C" int32_t saap_select_buckets(const float* scores, int32_t* selected, i
   const long long units = mode == SAAP_INDEPENDENT ? (long long)S * Hq : (long long)S * Hkv;
   const int indep = mode == SAAP_INDEPENDENT ? 1 : 0;
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  if (n_sort < n_pow2 && env_int("SAAP_SELECT_FULL_SORT", 0) == 0) {
+  if (logits && !(n_sort < n_pow2)) return SAAP_UNSUPPORTED;     // the fused softmax lives in the radix kernel
+  if (n_sort < n_pow2 && (logits || env_int("SAAP_SELECT_FULL_SORT", 0) == 0)) {
     // radix select + sort of the selected keys only
     int threads = (B + 3) / 4;
     threads = (threads + 63) / 64 * 64;
@@ -289,12 +385,22 @@ extern "C" int32_t saap_select_buckets(const float* scores, int32_t* selected, i
     const size_t lds = (size_t)n_sort * sizeof(unsigned long long) + (size_t)(B / 32 + 1) * sizeof(unsigned) +
                        (n_sort <= kRankSortMax ? (size_t)n_sort * sizeof(unsigned) : 0);
     saap_trace_arm();
-    if (B <= 4 * threads)
-      hipLaunchKernelGGL(select_radix_kernel<4>, dim3((unsigned)units), dim3((unsigned)threads), lds, hs, scores,
-                         selected, Hq, Hkv, B, nprobe, indep, n_sort);
-    else
-      hipLaunchKernelGGL(select_radix_kernel<8>, dim3((unsigned)units), dim3((unsigned)threads), lds, hs, scores,
-                         selected, Hq, Hkv, B, nprobe, indep, n_sort);
+    const dim3 grid((unsigned)units), block((unsigned)threads);
+    if (B <= 4 * threads) {
+      if (logits)
+        hipLaunchKernelGGL((select_radix_kernel<4, true>), grid, block, lds, hs, scores, probs, selected, Hq, Hkv, B,
+                           nprobe, indep, n_sort);
+      else
+        hipLaunchKernelGGL((select_radix_kernel<4, false>), grid, block, lds, hs, scores, probs, selected, Hq, Hkv, B,
+                           nprobe, indep, n_sort);
+    } else {
+      if (logits)
+        hipLaunchKernelGGL((select_radix_kernel<8, true>), grid, block, lds, hs, scores, probs, selected, Hq, Hkv, B,
+                           nprobe, indep, n_sort);
+      else
+        hipLaunchKernelGGL((select_radix_kernel<8, false>), grid, block, lds, hs, scores, probs, selected, Hq, Hkv, B,
+                           nprobe, indep, n_sort);
+    }
     return launch_status();
   }
   int threads = n_pow2 / 2;
@@ -309,4 +415,22 @@ extern "C" int32_t saap_select_buckets(const float* scores, int32_t* selected, i
   hipLaunchKernelGGL(select_kernel, dim3((unsigned)units), dim3((unsigned)threads), lds, hs, scores, selected, Hq,
                      Hkv, B, nprobe, indep, n_pow2);
   return launch_status();
+}
+
+extern "C" int32_t saap_select_buckets(const float* scores, int32_t* selected, int32_t S, int32_t Hq,
+                                       int32_t Hkv, int32_t B, int32_t nprobe, int32_t mode, void* ws,
+                                       size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  return select_impl(scores, false, nullptr, selected, S, Hq, Hkv, B, nprobe, mode, stream);
+}
+
+extern "C" int32_t saap_select_buckets_from_logits(const float* logits, float* probs, int32_t* selected,
+                                                   int32_t S, int32_t Hq, int32_t Hkv, int32_t B,
+                                                   int32_t nprobe, int32_t mode, void* ws, size_t ws_bytes,
+                                                   void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  if (!logits) return SAAP_INVALID_ARG;
+  return select_impl(logits, true, probs, selected, S, Hq, Hkv, B, nprobe, mode, stream);
 }

@@ -135,6 +135,37 @@ def test_select_buckets_with_ties_at_the_threshold(saap, B, nprobe):
     assert sel[0, 0].tolist() == list(range(nprobe))
 
 
+@pytest.mark.parametrize("S,Hq,Hkv,B,nprobe,mode", [
+    (1, 32, 8, 1024, 51, 0), (1, 32, 8, 4096, 410, 0), (2, 8, 2, 2048, 102, 0), (1, 4, 1, 64, 8, 0), (2, 4, 4, 96, 5, 0),
+    (1, 8, 1, 1000, 37, 0), (1, 8, 4, 1024, 51, 1), (1, 16, 8, 8192, 300, 0), (3, 2, 1, 16, 3, 0),
+])
+def test_select_buckets_from_logits(saap, S, Hq, Hkv, B, nprobe, mode):
+    """The fused softmax + selection: its probabilities against the definition in float64, its selection
+    bit for bit against the oracle's selection made on those same fp32 probabilities."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(3 * B + nprobe)
+    logits = 4 * torch.randn(S, Hq, B, generator=g, device=DEV)
+    logits[:, :, B // 2] = logits[:, :, 1]            # planted ties
+    logits[0, :, : B // 4] = torch.round(logits[0, :, : B // 4] * 2) / 2
+    probs = torch.empty_like(logits)
+    sel = saap.select_buckets_from_logits(logits, Hkv, nprobe, mode, probs=probs)
+    sel_only = saap.select_buckets_from_logits(logits, Hkv, nprobe, mode)
+    torch.cuda.synchronize()
+    z = logits.cpu().numpy().astype(np.float64)
+    e = np.exp(z - z.max(axis=-1, keepdims=True))
+    np.testing.assert_allclose(probs.cpu().numpy(), e / e.sum(axis=-1, keepdims=True), rtol=1e-5, atol=1e-12)
+    want = ref.select_buckets(probs.cpu().numpy(), Hkv, nprobe, mode)
+    assert np.array_equal(sel.cpu().numpy(), want)
+    assert torch.equal(sel, sel_only)                  # the optional output changes nothing
+    # and the two-call route (softmax kernel of classify_queries, then select_buckets) agrees wherever
+    # the group sums are not within rounding of each other at the threshold
+    two = saap.select_buckets(torch.softmax(logits, dim=-1), Hkv, nprobe, mode)
+    torch.cuda.synchronize()
+    a, b = sel.cpu().numpy(), two.cpu().numpy()
+    differ = sum(len(set(x.tolist()) ^ set(y.tolist())) for x, y in zip(a.reshape(-1, nprobe), b.reshape(-1, nprobe)))
+    assert differ <= 2 * a.shape[0] * a.shape[1], differ      # at most one swap at the threshold per list
+
+
 # ------------------------------------------------------------------------------ sparse attention
 def _oracle_index(cfg, cache, cent, slack):
     ids = ref.assign_keys(h(cache["x_keys"]), h(cent))
