@@ -424,9 +424,8 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   __syncthreads();
   SAAP_TRACE(10);
   float* w_o = reinterpret_cast<float*>(smem);            // [nw][G][d] unnormalised outputs
-  float* w_m = w_o + nw * G * kD;                         // [nw][G] maxima, then weights 2^(m - M)
+  float* w_m = w_o + nw * G * kD;                         // [nw][G] maxima
   float* w_l = w_m + nw * G;                              // [nw][G] sums of weights
-  float* w_M = w_l + nw * G;                              // [G] workgroup maximum
   if (grp == 0) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -441,33 +440,25 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   }
   __syncthreads();
   SAAP_TRACE(11);
-  // weights 2^(m - M) of the nw partial results, one per thread
-  {
-    const bool has = tid < nw * G;
-    float wgt = 0.f, Mh = kNegBig;
-    if (has) {
-      const int g = tid % G;
-#pragma unroll
-      for (int j = 0; j < nw; ++j) Mh = fmaxf(Mh, w_m[j * G + g]);
-      wgt = fast_exp2(w_m[tid] - Mh);
-    }
-    __syncthreads();          // every maximum is read before any is overwritten
-    if (has) {
-      w_m[tid] = wgt;
-      if (tid < G) w_M[tid] = Mh;
-    }
-    __syncthreads();
-  }
+  // Algorithm 2 over the nw partial results of the workgroup, one (head, feature) per thread; every
+  // thread derives the weights 2^(m_j - M) of its head itself (nw exponentials) rather than
+  // waiting for a shared table
   for (int x = tid; x < G * kD; x += NT) {
     const int g = x / kD, e = x % kD;
+    float mj[nw];
+    float M = kNegBig;
+#pragma unroll
+    for (int j = 0; j < nw; ++j) {
+      mj[j] = w_m[j * G + g];
+      M = fmaxf(M, mj[j]);
+    }
     float L = 0.f, Ov = 0.f;
 #pragma unroll
     for (int j = 0; j < nw; ++j) {
-      const float w = w_m[j * G + g];
+      const float w = fast_exp2(mj[j] - M);
       L = fmaf(w, w_l[j * G + g], L);
       Ov = fmaf(w, w_o[(j * G + g) * kD + e], Ov);
     }
-    const float M = w_M[g];
     if (p.P == 1) {
       store_out(p, qrow0 + g, e, M, L, Ov);
     } else {
