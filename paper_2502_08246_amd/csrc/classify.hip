@@ -103,8 +103,14 @@ mlp_hidden_bf16_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__
 
 // ---- bf16: output layer ------------------------------------------------------------------------
 constexpr int kOutChunk = 512;      // hidden units per LDS pass of the output kernel
+// Eight waves per workgroup: what one compute unit pulls from memory grows with the number of
+// waves that have loads in flight (two waves were measured at a third of the rate of eight).
+// For the matrix products wave (t, kq) takes bucket tile t of the two and every fourth k-step
+// starting at kq; the four partial products of a tile are added through LDS in a fixed order.
+constexpr int kOutThreads = 512;
+constexpr int kOutLoads = 16 * 128 / kOutThreads;     // 16-byte loads per thread and operand
 
-__global__ void __launch_bounds__(128)
+__global__ void __launch_bounds__(kOutThreads)
 mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W2, const float* __restrict__ b2,
                     float* __restrict__ scores, MlpShape sh) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -126,32 +132,48 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
     const int kc = min(kOutChunk, sh.hidden - c0);      // multiple of 32
     // all loads of the pass first: 32 rows of W2 (kc/8 pieces each) and 16 rows of h (kc/4 pieces)
     const int pw = kc / 8, ph = kc / 4;
-    u32x4_t wv[16], hv[16];
+    // piece index -> (row, piece of the row); a shift when the pieces per row are a power of two
+    // (hidden = 256, 512, 1024: the usual case), a division otherwise
+    const int pw_sh = (pw & (pw - 1)) == 0 ? 31 - __clz(pw) : -1;
+    const int ph_sh = pw_sh >= 0 ? pw_sh + 1 : -1;
+    auto split_w = [&](int q, int& row, int& pc) {
+      if (pw_sh >= 0) { row = q >> pw_sh; pc = q & (pw - 1); } else { row = q / pw; pc = q % pw; }
+    };
+    auto split_h = [&](int q, int& row, int& pc) {
+      if (ph_sh >= 0) { row = q >> ph_sh; pc = q & (ph - 1); } else { row = q / ph; pc = q % ph; }
+    };
+    u32x4_t wv[kOutLoads], hv[kOutLoads];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int q = min(tid + 128 * i, 32 * pw - 1), row = q / pw, pc = q % pw;
+    for (int i = 0; i < kOutLoads; ++i) {
+      int row, pc;
+      split_w(min(tid + kOutThreads * i, 32 * pw - 1), row, pc);
       const int b = min(b0 + row, sh.B - 1);
       wv[i] = load16(W2 + ((size_t)w * sh.B + b) * sh.hidden + c0 + pc * 8);
     }
     // only the tile's real rows are fetched (4 of 16 at batch 1); the other LDS rows keep
     // whatever they hold: a row of A only reaches the same row of the product, which is dropped
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int q = min(tid + 128 * i, rows_here * ph - 1), row = q / ph, pc = q % ph;
+    for (int i = 0; i < kOutLoads; ++i) {
+      int row, pc;
+      split_h(min(tid + kOutThreads * i, rows_here * ph - 1), row, pc);
       hv[i] = load16(hrows + (size_t)row * sh.hidden + c0 + pc * 4);
     }
     __builtin_amdgcn_sched_barrier(0);
+    if (c0 == 0) SAAP_TRACE(4);
     if (c0 > 0) __syncthreads();                        // the previous pass is done with the LDS tiles
     // stores use the same clamped piece index as the loads: surplus threads rewrite the last
     // piece with identical data, and the code stays free of branches
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int q = min(tid + 128 * i, 32 * pw - 1);
-      *reinterpret_cast<u32x4_t*>(s_w2 + (q / pw) * pitch + (q % pw) * 8) = wv[i];
+    for (int i = 0; i < kOutLoads; ++i) {
+      int row, pc;
+      split_w(min(tid + kOutThreads * i, 32 * pw - 1), row, pc);
+      *reinterpret_cast<u32x4_t*>(s_w2 + row * pitch + pc * 8) = wv[i];
     }
+    if (c0 == 0) SAAP_TRACE(5);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int q = min(tid + 128 * i, rows_here * ph - 1);
+    for (int i = 0; i < kOutLoads; ++i) {
+      int hrow_i, hpc_i;
+      split_h(min(tid + kOutThreads * i, rows_here * ph - 1), hrow_i, hpc_i);
       {
         // four activations -> three planes of truncated bf16 pieces: h == p0 + p1 + p2 exactly
         uint32_t p0[4], p1[4], p2[4];
@@ -164,7 +186,7 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
           const float r2 = r1 - __uint_as_float(p1[j]);
           p2[j] = __float_as_uint(r2) & 0xffff0000u;
         }
-        bf16_t* dst = s_h + (q / ph) * pitch + (q % ph) * 4;
+        bf16_t* dst = s_h + hrow_i * pitch + hpc_i * 4;
         *reinterpret_cast<uint2*>(dst) = make_uint2((p0[0] >> 16) | p0[1], (p0[2] >> 16) | p0[3]);
         *reinterpret_cast<uint2*>(dst + 16 * pitch) = make_uint2((p1[0] >> 16) | p1[1], (p1[2] >> 16) | p1[3]);
         *reinterpret_cast<uint2*>(dst + 32 * pitch) = make_uint2((p2[0] >> 16) | p2[1], (p2[2] >> 16) | p2[3]);
@@ -172,20 +194,46 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
     }
     __syncthreads();
     if (c0 == 0) SAAP_TRACE(1);
-    const bf16_t* wrow = s_w2 + (wave * 16 + rc) * pitch + kg * 8;
+    const int tile = wave & 1, kq = wave >> 1;
+    const bf16_t* wrow = s_w2 + (tile * 16 + rc) * pitch + kg * 8;
     const bf16_t* hrow = s_h + rc * pitch + kg * 8;
-    for (int st = 0; st < kc / 32; ++st) {
-      const bf16x8_t b = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(wrow + st * 32));
-      const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(hrow + st * 32));
-      const bf16x8_t a1 = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(hrow + 16 * pitch + st * 32));
-      const bf16x8_t a2 = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(hrow + 32 * pitch + st * 32));
-      acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, b, acc2, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc1, 0, 0, 0);
-      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc0, 0, 0, 0);
+    auto lds16 = [](const bf16_t* ptr) { return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(ptr)); };
+    const int nst = kc / 32;
+    int st = kq;
+    // four of the wave's k-steps at a time: their sixteen LDS reads go out before the twelve
+    // matrix instructions, so the read latency is paid once per group instead of once per step
+    for (; st + 12 < nst; st += 16) {
+      bf16x8_t b[4], a0[4], a1[4], a2[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        b[u] = lds16(wrow + (st + 4 * u) * 32);
+        a0[u] = lds16(hrow + (st + 4 * u) * 32);
+        a1[u] = lds16(hrow + 16 * pitch + (st + 4 * u) * 32);
+        a2[u] = lds16(hrow + 32 * pitch + (st + 4 * u) * 32);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2[u], b[u], acc2, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[u], b[u], acc1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[u], b[u], acc0, 0, 0, 0);
+      }
+    }
+    for (; st < nst; st += 4) {
+      const bf16x8_t b = lds16(wrow + st * 32);
+      acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds16(hrow + 32 * pitch + st * 32), b, acc2, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds16(hrow + 16 * pitch + st * 32), b, acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds16(hrow + st * 32), b, acc0, 0, 0, 0);
     }
   }
-  // smallest pieces first
-  const f32x4_t acc = (acc2 + acc1) + acc0;
+  // smallest pieces first; then the four k-quarters of a bucket tile, in order, through LDS
+  f32x4_t acc = (acc2 + acc1) + acc0;
+  __syncthreads();                                      // the operand tiles are dead
+  f32x4_t* s_part = reinterpret_cast<f32x4_t*>(smem);   // [8 waves][64 lanes]
+  s_part[wave * 64 + lane] = acc;
+  __syncthreads();
+  if (wave >= 2) return;
+  acc = ((s_part[wave * 64 + lane] + s_part[(wave + 2) * 64 + lane]) + s_part[(wave + 4) * 64 + lane]) +
+        s_part[(wave + 6) * 64 + lane];
   SAAP_TRACE(2);
   const int bucket = b0 + wave * 16 + rc;
   if (bucket < sh.B) {
@@ -326,13 +374,15 @@ extern "C" int32_t saap_classify_queries(const void* xq, const void* W1, const f
     hipLaunchKernelGGL(mlp_hidden_bf16_kernel, dim3(g1), dim3(256), 0, hs, static_cast<const bf16_t*>(xq),
                        static_cast<const bf16_t*>(W1), b1, hbuf, sh);
     const int chunk = hidden < kOutChunk ? hidden : kOutChunk;
-    const size_t lds = (size_t)(3 * 16 + 32) * (chunk + 8) * sizeof(bf16_t);
+    size_t lds = (size_t)(3 * 16 + 32) * (chunk + 8) * sizeof(bf16_t);
+    const size_t lds_part = (size_t)kOutThreads * sizeof(f32x4_t);      // partial products of the eight waves
+    if (lds < lds_part) lds = lds_part;
     if (lds > 48 * 1024) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_out_bf16_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return SAAP_HIP_ERROR;
     }
-    hipLaunchKernelGGL(mlp_out_bf16_kernel, dim3(g2), dim3(128), lds, hs, hbuf, static_cast<const bf16_t*>(W2), b2,
+    hipLaunchKernelGGL(mlp_out_bf16_kernel, dim3(g2), dim3(kOutThreads), lds, hs, hbuf, static_cast<const bf16_t*>(W2), b2,
                        scores, sh);
   } else {
     const dim3 g1((unsigned)((hidden / 16 + 3) / 4), (unsigned)m_tiles, (unsigned)Hw);
