@@ -122,8 +122,8 @@ __device__ __forceinline__ void softmax_group_scores(const float* __restrict__ z
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < HEADS; ++i) {
-    float m = s_red[0][0][i];
-    for (int w = 1; w < nw; ++w) m = fmaxf(m, s_red[0][w][i]);
+    // the waves' partial results, one per lane, reduced again inside every wave
+    const float m = wave_max_f32(lane < nw ? s_red[0][lane][i] : -INFINITY);
     float sum = 0.f;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
@@ -139,9 +139,7 @@ __device__ __forceinline__ void softmax_group_scores(const float* __restrict__ z
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < HEADS; ++i) {
-    float sum = s_red[1][0][i];
-    for (int w = 1; w < nw; ++w) sum += s_red[1][w][i];
-    red[i] = 1.0f / sum;
+    red[i] = 1.0f / wave_sum_f32(lane < nw ? s_red[1][lane][i] : 0.f);
   }
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
@@ -160,12 +158,12 @@ __device__ __forceinline__ void softmax_group_scores(const float* __restrict__ z
 template <int EPT, bool LOGITS>
 __global__ void __launch_bounds__(1024)
 select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs, int32_t* __restrict__ selected,
-                    int Hq, int Hkv, int B, int nprobe, int independent, int n_sort) {
+                    int Hq, int Hkv, int B, int nprobe, int independent, int n_sort, int cap) {
   extern __shared__ __align__(16) unsigned char smem[];
-  unsigned long long* sortbuf = reinterpret_cast<unsigned long long*>(smem);   // [n_sort]
-  unsigned* eqbits = reinterpret_cast<unsigned*>(sortbuf + n_sort);            // [B/32 + 1]
+  unsigned long long* sortbuf = reinterpret_cast<unsigned long long*>(smem);   // [cap] candidates, cap >= n_sort
+  unsigned* eqbits = reinterpret_cast<unsigned*>(sortbuf + cap);               // [B/32 + 1]
   __shared__ unsigned s_hist[2][256];
-  __shared__ unsigned s_digit, s_krem, s_cnt, s_neq, s_and, s_or;
+  __shared__ unsigned s_digit, s_krem, s_bin, s_cnt, s_neq, s_and, s_or;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nt = blockDim.x;
   const int unit = blockIdx.x;
   const int G = Hq / Hkv;
@@ -197,7 +195,7 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
     for (int e = 0; e < EPT; ++e) key[e] = tid + e * nt < B ? float_order_key(gs[e]) : 0u;   // 0 sorts below every finite score
   }
   if (tid == 0) { s_cnt = 0u; s_neq = 0u; s_and = 0xFFFFFFFFu; s_or = 0u; }
-  for (int i = tid; i < n_sort; i += nt) sortbuf[i] = 0ull;
+  for (int i = tid; i < cap; i += nt) sortbuf[i] = 0ull;
   for (int i = tid; i <= B / 32; i += nt) eqbits[i] = 0u;
   for (int i = tid; i < 256; i += nt) s_hist[0][i] = 0u;
   __syncthreads();
@@ -220,9 +218,13 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
   unsigned mask = rem >= 32 ? 0u : ~((1u << rem) - 1u);
   unsigned prefix = s_and & mask, k_rem = (unsigned)nprobe;
 
-  // most-significant-digit radix select: afterwards `prefix` is the score image of the
-  // nprobe-th largest bucket and k_rem the number of buckets equal to it that are taken
+  // most-significant-digit radix select: after all digits `prefix` is the score image of the
+  // nprobe-th largest bucket and k_rem the number of buckets equal to it that are taken.  The
+  // passes stop early once the buckets above the bin that holds the nprobe-th one, plus that
+  // bin, fit the candidate buffer: ordering the candidates settles the rest (the usual case after
+  // one or two digits).
   int pass = 0;
+  bool early = false;
   while (rem > 0) {
     const int width = rem < 8 ? rem : 8;
     const int shift = rem - width;
@@ -246,6 +248,7 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
         if (cum < k_rem && cum + c[b] >= k_rem) {
           s_digit = (unsigned)(top - b);
           s_krem = k_rem - cum;
+          s_bin = c[b];
         }
         cum += c[b];
       }
@@ -256,69 +259,81 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
     k_rem = s_krem;
     rem = shift;
     ++pass;
+    if (rem > 0 && (unsigned)nprobe - k_rem + s_bin <= (unsigned)cap) {
+      early = true;
+      break;
+    }
   }
   SAAP_TRACE(2);
-  // buckets scoring exactly `prefix`: k_rem of them are taken, lowest ids first
+  int n_cand = nprobe;                 // entries of sortbuf to put in order; the first nprobe are the result
+  if (early) {
+    // candidates: every bucket whose determined digits are at or above the threshold bin
+    n_cand = (int)((unsigned)nprobe - k_rem + s_bin);
 #pragma unroll
-  for (int e = 0; e < EPT; ++e) {
-    const int b = tid + e * nt;
-    if (b < B && key[e] == prefix) {
-      atomicAdd(&s_neq, 1u);
-      atomicOr(&eqbits[b >> 5], 1u << (b & 31));
-    }
-  }
-  __syncthreads();
-  const bool all_equal_taken = s_neq == k_rem;
-#pragma unroll
-  for (int e = 0; e < EPT; ++e) {
-    const int b = tid + e * nt;
-    if (b >= B) continue;
-    bool take = key[e] > prefix;
-    if (key[e] == prefix) {
-      if (all_equal_taken) {
-        take = true;
-      } else {
-        unsigned rank = __popc(eqbits[b >> 5] & ((1u << (b & 31)) - 1u));
-        for (int w = 0; w < (b >> 5); ++w) rank += __popc(eqbits[w]);
-        take = rank < k_rem;
+    for (int e = 0; e < EPT; ++e) {
+      const int b = tid + e * nt;
+      if (b < B && (key[e] & mask) >= prefix) {
+        const unsigned long long takers = __ballot(1);
+        unsigned base = 0u;
+        if (lane == __ffsll((long long)takers) - 1) base = atomicAdd(&s_cnt, (unsigned)__popcll(takers));
+        base = (unsigned)__builtin_amdgcn_readfirstlane((int)base);
+        const unsigned pos = base + (unsigned)__popcll(takers & ((1ull << lane) - 1ull));
+        sortbuf[pos] = ((unsigned long long)key[e] << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)b);
       }
     }
-    if (take) {
-      // one LDS atomic per wave: the first taking lane reserves slots for all of them
-      const unsigned long long takers = __ballot(1);
-      unsigned base = 0u;
-      if (lane == __ffsll((long long)takers) - 1) base = atomicAdd(&s_cnt, (unsigned)__popcll(takers));
-      base = (unsigned)__builtin_amdgcn_readfirstlane((int)base);
-      const unsigned pos = base + (unsigned)__popcll(takers & ((1ull << lane) - 1ull));
-      sortbuf[pos] = ((unsigned long long)key[e] << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)b);
+    __syncthreads();
+  } else {
+    // buckets scoring exactly `prefix`: k_rem of them are taken, lowest ids first
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const int b = tid + e * nt;
+      if (b < B && key[e] == prefix) {
+        atomicAdd(&s_neq, 1u);
+        atomicOr(&eqbits[b >> 5], 1u << (b & 31));
+      }
     }
+    __syncthreads();
+    const bool all_equal_taken = s_neq == k_rem;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const int b = tid + e * nt;
+      if (b >= B) continue;
+      bool take = key[e] > prefix;
+      if (key[e] == prefix) {
+        if (all_equal_taken) {
+          take = true;
+        } else {
+          unsigned rank = __popc(eqbits[b >> 5] & ((1u << (b & 31)) - 1u));
+          for (int w = 0; w < (b >> 5); ++w) rank += __popc(eqbits[w]);
+          take = rank < k_rem;
+        }
+      }
+      if (take) {
+        // one LDS atomic per wave: the first taking lane reserves slots for all of them
+        const unsigned long long takers = __ballot(1);
+        unsigned base = 0u;
+        if (lane == __ffsll((long long)takers) - 1) base = atomicAdd(&s_cnt, (unsigned)__popcll(takers));
+        base = (unsigned)__builtin_amdgcn_readfirstlane((int)base);
+        const unsigned pos = base + (unsigned)__popcll(takers & ((1ull << lane) - 1ull));
+        sortbuf[pos] = ((unsigned long long)key[e] << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)b);
+      }
+    }
+    __syncthreads();
   }
-  __syncthreads();
   SAAP_TRACE(3);
   int32_t* out = selected + (size_t)unit * nprobe;
-  if (n_sort <= 64) {
-    // keys are distinct: the place of a key is the number of larger keys
-    if (tid < nprobe) {
-      const unsigned long long mine = sortbuf[tid];
-      int rank = 0;
-#pragma unroll 8
-      for (int j = 0; j < nprobe; ++j) rank += sortbuf[j] > mine ? 1 : 0;
-      out[rank] = (int32_t)(0xFFFFFFFFu - (unsigned)(mine & 0xFFFFFFFFull));
-    }
-    SAAP_TRACE(4);
-    return;
-  }
   if (n_sort <= kRankSortMax) {
-    // same idea with the comparisons of one key split over several threads: work item
-    // (key i, part) counts the larger keys in its slice and adds the count to rank[i]
-    unsigned* rank = eqbits + (B / 32 + 1);            // [n_sort], zeroed below
-    for (int i = tid; i < nprobe; i += nt) rank[i] = 0u;
+    // keys are distinct: the place of a key is the number of larger keys.  The comparisons of one
+    // key are split over several threads: work item (key i, part) counts the larger keys in its
+    // slice and adds the count to rank[i]
+    unsigned* rank = eqbits + (B / 32 + 1);            // [cap], zeroed below
+    for (int i = tid; i < n_cand; i += nt) rank[i] = 0u;
     __syncthreads();
-    const int parts = nt >= 2 * nprobe ? nt / nprobe : 1;
-    const int slice = (nprobe + parts - 1) / parts;
-    for (int w = tid; w < nprobe * parts; w += nt) {
-      const int i = w % nprobe, part = w / nprobe;
-      const int j0 = part * slice, j1 = min(j0 + slice, nprobe);
+    const int parts = nt >= 2 * n_cand ? nt / n_cand : 1;
+    const int slice = (n_cand + parts - 1) / parts;
+    for (int w = tid; w < n_cand * parts; w += nt) {
+      const int i = w % n_cand, part = w / n_cand;
+      const int j0 = part * slice, j1 = min(j0 + slice, n_cand);
       const unsigned long long mine = sortbuf[i];
       unsigned cnt = 0u;
 #pragma unroll 8
@@ -326,8 +341,8 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
       if (cnt) atomicAdd(&rank[i], cnt);
     }
     __syncthreads();
-    for (int i = tid; i < nprobe; i += nt)
-      out[rank[i]] = (int32_t)(0xFFFFFFFFu - (unsigned)(sortbuf[i] & 0xFFFFFFFFull));
+    for (int i = tid; i < n_cand; i += nt)
+      if (rank[i] < (unsigned)nprobe) out[rank[i]] = (int32_t)(0xFFFFFFFFu - (unsigned)(sortbuf[i] & 0xFFFFFFFFull));
     return;
   }
   for (int k = 2; k <= n_sort; k <<= 1) {
@@ -379,28 +394,37 @@ static int32_t select_impl(const float* scores, bool logits, float* probs, int32
   if (logits && !(n_sort < n_pow2)) return SAAP_UNSUPPORTED;     // the fused softmax lives in the radix kernel
   if (n_sort < n_pow2 && (logits || env_int("SAAP_SELECT_FULL_SORT", 0) == 0)) {
     // radix select + sort of the selected keys only
-    int threads = (B + 3) / 4;
+    // elements per thread: 2 up to 2048 buckets (measured best at 1024: more waves with loads in
+    // flight pull the score rows in faster, up to the point where the barriers cost more), then 4, 8
+    int ept = env_int("SAAP_SELECT_EPT", 0);
+    if (ept != 1 && ept != 2 && ept != 4 && ept != 8) ept = B <= 2048 ? 2 : B <= 4096 ? 4 : 8;
+    while (ept < 8 && (long long)ept * 1024 < B) ept *= 2;
+    int threads = (B + ept - 1) / ept;
     threads = (threads + 63) / 64 * 64;
     if (threads > 1024) threads = 1024;
-    const size_t lds = (size_t)n_sort * sizeof(unsigned long long) + (size_t)(B / 32 + 1) * sizeof(unsigned) +
-                       (n_sort <= kRankSortMax ? (size_t)n_sort * sizeof(unsigned) : 0);
+    // candidate buffer: twice the list where the candidates are put in order by counting, the
+    // padded list itself where a bitonic network does it
+    const int cap = n_sort <= kRankSortMax ? 2 * n_sort : n_sort;
+    const size_t lds = (size_t)cap * sizeof(unsigned long long) + (size_t)(B / 32 + 1) * sizeof(unsigned) +
+                       (n_sort <= kRankSortMax ? (size_t)cap * sizeof(unsigned) : 0);
     saap_trace_arm();
     const dim3 grid((unsigned)units), block((unsigned)threads);
-    if (B <= 4 * threads) {
-      if (logits)
-        hipLaunchKernelGGL((select_radix_kernel<4, true>), grid, block, lds, hs, scores, probs, selected, Hq, Hkv, B,
-                           nprobe, indep, n_sort);
-      else
-        hipLaunchKernelGGL((select_radix_kernel<4, false>), grid, block, lds, hs, scores, probs, selected, Hq, Hkv, B,
-                           nprobe, indep, n_sort);
-    } else {
-      if (logits)
-        hipLaunchKernelGGL((select_radix_kernel<8, true>), grid, block, lds, hs, scores, probs, selected, Hq, Hkv, B,
-                           nprobe, indep, n_sort);
-      else
-        hipLaunchKernelGGL((select_radix_kernel<8, false>), grid, block, lds, hs, scores, probs, selected, Hq, Hkv, B,
-                           nprobe, indep, n_sort);
+#define SAAP_SELECT_CASE(E)                                                                                  \
+  case E:                                                                                                    \
+    if (logits)                                                                                              \
+      hipLaunchKernelGGL((select_radix_kernel<E, true>), grid, block, lds, hs, scores, probs, selected, Hq, Hkv, B, \
+                         nprobe, indep, n_sort, cap);                                                        \
+    else                                                                                                     \
+      hipLaunchKernelGGL((select_radix_kernel<E, false>), grid, block, lds, hs, scores, probs, selected, Hq, Hkv, B, \
+                         nprobe, indep, n_sort, cap);                                                        \
+    break
+    switch (ept) {
+      SAAP_SELECT_CASE(1);
+      SAAP_SELECT_CASE(2);
+      SAAP_SELECT_CASE(4);
+      default: SAAP_SELECT_CASE(8);
     }
+#undef SAAP_SELECT_CASE
     return launch_status();
   }
   int threads = n_pow2 / 2;
