@@ -121,8 +121,12 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
   const int b0 = slab * 32;
   const int chunk_max = min(sh.hidden, kOutChunk);
   const int pitch = chunk_max + 8;
-  bf16_t* s_h = reinterpret_cast<bf16_t*>(smem);       // [3][16][pitch]
-  bf16_t* s_w2 = s_h + 3 * 16 * pitch;                 // [32][pitch]
+  // LDS rows per plane of h: the real rows only (4 of a 16-row tile at batch 1), which lets three
+  // workgroups share a compute unit; rows of A beyond them repeat the last real row, and a row of
+  // A only reaches the same row of the product, which is dropped
+  const int h_rows = min(16, sh.rows_per_set);
+  bf16_t* s_h = reinterpret_cast<bf16_t*>(smem);       // [3][h_rows][pitch]
+  bf16_t* s_w2 = s_h + 3 * h_rows * pitch;             // [32][pitch]
   const float* hrows = hbuf + ((size_t)w * sh.m_pad + mt * 16) * sh.hidden;
   const int rows_here = min(16, sh.rows_per_set - mt * 16);    // real rows of this tile (>= 1)
   // one accumulator per plane: three independent chains of matrix instructions, added at the end
@@ -150,8 +154,7 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
       const int b = min(b0 + row, sh.B - 1);
       wv[i] = load16(W2 + ((size_t)w * sh.B + b) * sh.hidden + c0 + pc * 8);
     }
-    // only the tile's real rows are fetched (4 of 16 at batch 1); the other LDS rows keep
-    // whatever they hold: a row of A only reaches the same row of the product, which is dropped
+    // only the tile's real rows are fetched
 #pragma unroll
     for (int i = 0; i < kOutLoads; ++i) {
       int row, pc;
@@ -188,15 +191,15 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
         }
         bf16_t* dst = s_h + hrow_i * pitch + hpc_i * 4;
         *reinterpret_cast<uint2*>(dst) = make_uint2((p0[0] >> 16) | p0[1], (p0[2] >> 16) | p0[3]);
-        *reinterpret_cast<uint2*>(dst + 16 * pitch) = make_uint2((p1[0] >> 16) | p1[1], (p1[2] >> 16) | p1[3]);
-        *reinterpret_cast<uint2*>(dst + 32 * pitch) = make_uint2((p2[0] >> 16) | p2[1], (p2[2] >> 16) | p2[3]);
+        *reinterpret_cast<uint2*>(dst + h_rows * pitch) = make_uint2((p1[0] >> 16) | p1[1], (p1[2] >> 16) | p1[3]);
+        *reinterpret_cast<uint2*>(dst + 2 * h_rows * pitch) = make_uint2((p2[0] >> 16) | p2[1], (p2[2] >> 16) | p2[3]);
       }
     }
     __syncthreads();
     if (c0 == 0) SAAP_TRACE(1);
     const int tile = wave & 1, kq = wave >> 1;
     const bf16_t* wrow = s_w2 + (tile * 16 + rc) * pitch + kg * 8;
-    const bf16_t* hrow = s_h + rc * pitch + kg * 8;
+    const bf16_t* hrow = s_h + min(rc, rows_here - 1) * pitch + kg * 8;
     auto lds16 = [](const bf16_t* ptr) { return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(ptr)); };
     const int nst = kc / 32;
     int st = kq;
@@ -208,8 +211,8 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
       for (int u = 0; u < 4; ++u) {
         b[u] = lds16(wrow + (st + 4 * u) * 32);
         a0[u] = lds16(hrow + (st + 4 * u) * 32);
-        a1[u] = lds16(hrow + 16 * pitch + (st + 4 * u) * 32);
-        a2[u] = lds16(hrow + 32 * pitch + (st + 4 * u) * 32);
+        a1[u] = lds16(hrow + h_rows * pitch + (st + 4 * u) * 32);
+        a2[u] = lds16(hrow + 2 * h_rows * pitch + (st + 4 * u) * 32);
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -220,8 +223,8 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
     }
     for (; st < nst; st += 4) {
       const bf16x8_t b = lds16(wrow + st * 32);
-      acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds16(hrow + 32 * pitch + st * 32), b, acc2, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds16(hrow + 16 * pitch + st * 32), b, acc1, 0, 0, 0);
+      acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds16(hrow + 2 * h_rows * pitch + st * 32), b, acc2, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds16(hrow + h_rows * pitch + st * 32), b, acc1, 0, 0, 0);
       acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds16(hrow + st * 32), b, acc0, 0, 0, 0);
     }
   }
@@ -374,7 +377,8 @@ extern "C" int32_t saap_classify_queries(const void* xq, const void* W1, const f
     hipLaunchKernelGGL(mlp_hidden_bf16_kernel, dim3(g1), dim3(256), 0, hs, static_cast<const bf16_t*>(xq),
                        static_cast<const bf16_t*>(W1), b1, hbuf, sh);
     const int chunk = hidden < kOutChunk ? hidden : kOutChunk;
-    size_t lds = (size_t)(3 * 16 + 32) * (chunk + 8) * sizeof(bf16_t);
+    const int h_rows = sh.rows_per_set < 16 ? sh.rows_per_set : 16;
+    size_t lds = (size_t)(3 * h_rows + 32) * (chunk + 8) * sizeof(bf16_t);
     const size_t lds_part = (size_t)kOutThreads * sizeof(f32x4_t);      // partial products of the eight waves
     if (lds < lds_part) lds = lds_part;
     if (lds > 48 * 1024) {
