@@ -96,7 +96,7 @@ mlp_hidden_bf16_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = mt * 16 + 4 * kg + i;
-    hbuf[((size_t)w * sh.m_pad + row) * sh.hidden + unit] = fmaxf(acc[i] + bv, 0.f);
+    if (row < sh.rows_per_set) hbuf[((size_t)w * sh.m_pad + row) * sh.hidden + unit] = fmaxf(acc[i] + bv, 0.f);
   }
   SAAP_TRACE(2);
 }
