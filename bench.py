@@ -1,8 +1,8 @@
 """Benchmark of the SAAP decode hot path on one MI355X.
 
 One "step" is the decode-time hot path for one token of one layer over a resident, bucket-sorted
-KV cache: classify_queries -> select_buckets -> sparse_decode_attention (partials + merge in one
-launch).  The prefill half (assign_keys, build_bucket_index) runs once during set-up and is timed
+KV cache: classify_queries (logits) -> select_buckets_from_logits (the classifier's softmax folded
+into the selection kernel) -> sparse_decode_attention (partials + merge in one launch).  The prefill half (assign_keys, build_bucket_index) runs once during set-up and is timed
 separately; dense_decode_attention on the same cache is the in-repo baseline.
 
 Cache hygiene: the timed loop cycles through `--query-sets` different queries (hence different

@@ -1,0 +1,64 @@
+"""The decode step under HIP graph capture: the three calls of a step are recorded once and replayed
+with new inputs several times, with eager work and synchronisations between the replays; every
+replay must give exactly what the same calls give when launched eagerly (the library takes its
+scratch from the caller's workspace, allocates nothing and records no memset, so nothing in it
+should depend on how it is launched)."""
+import math
+
+import pytest
+import torch
+
+from synth import gen
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+SCALE = 1.0 / math.sqrt(128.0)
+
+
+def test_step_replays_match_eager_launches():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the -m gpu tests need a real device")
+    import paper_2502_08246_amd as saap
+    saap.load_library()
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(N=16384, B=256, nprobe=13, hidden=128)
+    cache = gen.make_cache(cfg, 5, DEV)
+    cent = gen.make_centroids(cfg, 5, DEV, cache, n_train=4096)
+    xq, q = gen.make_queries(cfg, 5, DEV, n_steps=6)
+    W1, b1, W2, b2 = gen.make_classifier(cfg, 5, DEV)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, 0)
+
+    x_in, q_in = xq[0].clone(), q[0].clone()
+    logits = torch.empty(cfg.S, cfg.Hq, cfg.B, dtype=torch.float32, device=DEV)
+    sel = torch.empty(cfg.S, cfg.Hkv, cfg.nprobe, dtype=torch.int32, device=DEV)
+    out = torch.empty(cfg.S, cfg.Hq, cfg.d, dtype=torch.float32, device=DEV)
+    lse = torch.empty(cfg.S, cfg.Hq, dtype=torch.float32, device=DEV)
+
+    def step():
+        saap.classify_queries(x_in, W1, b1, W2, b2, cfg.Hkv, output_kind=saap.LOGITS, out=logits)
+        saap.select_buckets_from_logits(logits, cfg.Hkv, cfg.nprobe, out=sel)
+        saap.sparse_decode_attention(q_in, Ks, Vs, off, ln, sel, SCALE, out=out, lse=lse)
+
+    step()                                   # sizes the binding's workspace before the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+
+    for t in range(1, 6):
+        x_in.copy_(xq[t])
+        q_in.copy_(q[t])
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [a.clone() for a in (logits, sel, out, lse)]
+        # eager work of the program itself between the replays: the same step, launched directly
+        for a in (logits, sel, out, lse):
+            a.zero_()
+        step()
+        torch.cuda.synchronize()
+        for g, w, name in zip(got, (logits, sel, out, lse), ("logits", "selected", "out", "lse")):
+            assert torch.equal(g, w), f"replay {t}: {name} differs from the eager launch"
+        ws = saap.workspace(0, DEV)
+        assert int(ws[:65536].view(torch.int64).abs().sum().item()) == 0, "arrival counters must be zero between calls"
