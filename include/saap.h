@@ -184,6 +184,9 @@ int32_t saap_append_keys(const void* x_new, const void* k_new, const void* v_new
  *   Hw weight sets: 1 (shared), Hkv (one per KV head) or Hq (one per query head)
  *   scores [S,Hq,B] fp32, out
  * hidden must be a multiple of 32 and B a multiple of 16.
+ * hidden = 0 selects the one-layer model z = W2 x + b2 with W2 [Hw,B,d] (W1, b1 unused, may
+ * be NULL): with the key centroids as W2 and Hw = Hkv it is the symmetric "K-means" routing
+ * of Section 6.1, where a query goes to the buckets of its nearest centroids as a key does.
  */
 int32_t saap_classify_queries(const void* xq, const void* W1, const float* b1,
                               const void* W2, const float* b2, int32_t Hw,

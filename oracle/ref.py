@@ -175,16 +175,22 @@ def windowed_decode_attention(q, K, V, ids, selected, n_sink, n_recent, scale, B
 
 
 def classify_queries(xq, W1, b1, W2, b2, Hkv, output_kind=0):
-    """xq [S,Hq,d]; W1 [Hw,hidden,d]; W2 [Hw,B,hidden] -> scores float32 [S,Hq,B]."""
+    """xq [S,Hq,d]; W1 [Hw,hidden,d]; W2 [Hw,B,hidden] -> scores float32 [S,Hq,B].
+    W1 = None: the one-layer model, W2 [Hw,B,d]."""
     xq = _f32(xq)
-    W1 = _f32(W1)
     W2 = _f32(W2)
-    b1 = None if b1 is None else _f32(b1)
     b2 = None if b2 is None else _f32(b2)
     S, Hq, d = xq.shape
-    Hw, hidden, _ = W1.shape
-    B = W2.shape[1]
-    assert W2.shape == (Hw, B, hidden) and Hw in (1, Hkv, Hq)
+    if W1 is None:
+        Hw, B, hidden = W2.shape[0], W2.shape[1], 0
+        assert W2.shape == (Hw, B, d) and Hw in (1, Hkv, Hq)
+        b1 = None
+    else:
+        W1 = _f32(W1)
+        b1 = None if b1 is None else _f32(b1)
+        Hw, hidden, _ = W1.shape
+        B = W2.shape[1]
+        assert W2.shape == (Hw, B, hidden) and Hw in (1, Hkv, Hq)
     scores = np.empty((S, Hq, B), dtype=np.float32)
     lib().ref_classify_queries(_p(xq), _p(W1), _p(b1), _p(W2), _p(b2), Hw, _p(scores), S, Hq, Hkv, d,
                                hidden, B, output_kind)

@@ -132,11 +132,14 @@ static int weight_set(int hq, int Hq, int Hkv, int Hw) {
 }
 
 /* Section 4 / Section 6.1: f_q is a two-layer perceptron with a ReLU; its
- * output is a distribution over the buckets (softmax of the logits). */
+ * output is a distribution over the buckets (softmax of the logits).
+ * hidden == 0 is the one-layer model z = W2 x + b2 with W2 [Hw,B,d]: with the
+ * key centroids as W2 it is the symmetric "K-means" routing baseline of
+ * Section 6.1 (queries are assigned like keys). */
 void ref_classify_queries(const float* xq, const float* W1, const float* b1, const float* W2,
                           const float* b2, int Hw, float* scores, int S, int Hq, int Hkv, int d,
                           int hidden, int B, int output_kind) {
-  double* hbuf = (double*)malloc(sizeof(double) * hidden);
+  double* hbuf = (double*)malloc(sizeof(double) * (hidden > 0 ? hidden : 1));
   double* z = (double*)malloc(sizeof(double) * B);
   for (int s = 0; s < S; ++s)
     for (int hq = 0; hq < Hq; ++hq) {
@@ -151,9 +154,14 @@ void ref_classify_queries(const float* xq, const float* W1, const float* b1, con
       }
       double zmax = -INFINITY;
       for (int b = 0; b < B; ++b) {
-        const float* wr = W2 + ((size_t)w * B + b) * hidden;
         double t = 0.0;
-        for (int i = 0; i < hidden; ++i) t += (double)wr[i] * hbuf[i];
+        if (hidden > 0) {
+          const float* wr = W2 + ((size_t)w * B + b) * hidden;
+          for (int i = 0; i < hidden; ++i) t += (double)wr[i] * hbuf[i];
+        } else {
+          const float* wr = W2 + ((size_t)w * B + b) * d;
+          for (int j = 0; j < d; ++j) t += (double)wr[j] * (double)x[j];
+        }
         if (b2) t += (double)b2[(size_t)w * B + b];
         z[b] = t;
         if (t > zmax) zmax = t;

@@ -191,12 +191,19 @@ def append_keys(x_new, k_new, v_new, pos_new, centroids, bias, off, ln, idx, Ks,
 
 
 def classify_queries(xq, W1, b1, W2, b2, Hkv, output_kind=PROBS, out=None, ws=None):
-    """xq [S,Hq,d]; W1 [Hw,hidden,d]; W2 [Hw,B,hidden]; b1,b2 fp32 or None -> scores fp32 [S,Hq,B]."""
+    """xq [S,Hq,d]; W1 [Hw,hidden,d]; W2 [Hw,B,hidden]; b1,b2 fp32 or None -> scores fp32 [S,Hq,B].
+    W1 = None: the one-layer model z = W2 x + b2 with W2 [Hw,B,d]."""
     S, Hq, d = xq.shape
-    Hw, hidden, _ = W1.shape
-    B = W2.shape[1]
-    if W2.shape != (Hw, B, hidden) or W1.dtype != xq.dtype or W2.dtype != xq.dtype:
-        raise ValueError("W1 [Hw,hidden,d] and W2 [Hw,B,hidden] must match xq's dtype")
+    if W1 is None:
+        Hw, B, hidden = W2.shape[0], W2.shape[1], 0
+        if W2.shape != (Hw, B, d) or W2.dtype != xq.dtype:
+            raise ValueError("one-layer model: W2 must be [Hw,B,d] in xq's dtype")
+        b1 = None
+    else:
+        Hw, hidden, _ = W1.shape
+        B = W2.shape[1]
+        if W2.shape != (Hw, B, hidden) or W1.dtype != xq.dtype or W2.dtype != xq.dtype:
+            raise ValueError("W1 [Hw,hidden,d] and W2 [Hw,B,hidden] must match xq's dtype")
     scores = out if out is not None else torch.empty(S, Hq, B, dtype=torch.float32, device=xq.device)
     ws, wsb = _ws(OP_CLASSIFY_QUERIES, xq.device, ws, S=S, Hq=Hq, hidden=hidden)
     st = load_library().saap_classify_queries(_ptr(xq), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _i32(Hw),

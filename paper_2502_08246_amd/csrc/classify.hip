@@ -56,6 +56,9 @@ __device__ __forceinline__ void decode_block(const MlpShape& sh, int& w, int& mt
 constexpr int kPitchD = kD + 8;     // LDS row pitch (bf16 elements) of d-wide tiles
 
 // ---- bf16: hidden layer ------------------------------------------------------------------------
+// LINEAR: the same product without the ReLU, written straight to the score rows: the one-layer
+// model z = W x + b (sh.hidden is then the number of outputs).
+template <bool LINEAR>
 __global__ void __launch_bounds__(256)
 mlp_hidden_bf16_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__ W1, const float* __restrict__ b1,
                        float* __restrict__ hbuf, MlpShape sh) {
@@ -96,7 +99,10 @@ mlp_hidden_bf16_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = mt * 16 + 4 * kg + i;
-    if (row < sh.rows_per_set) hbuf[((size_t)w * sh.m_pad + row) * sh.hidden + unit] = fmaxf(acc[i] + bv, 0.f);
+    if (row < sh.rows_per_set) {
+      if constexpr (LINEAR) hbuf[(size_t)query_row(sh, w, row) * sh.hidden + unit] = acc[i] + bv;
+      else hbuf[((size_t)w * sh.m_pad + row) * sh.hidden + unit] = fmaxf(acc[i] + bv, 0.f);
+    }
   }
   SAAP_TRACE(2);
 }
@@ -251,6 +257,7 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
 }
 
 // ---- fp32 (correctness configuration): operands straight from memory ------------------------------
+template <bool LINEAR>
 __global__ void __launch_bounds__(256)
 mlp_hidden_f32_kernel(const float* __restrict__ xq, const float* __restrict__ W1, const float* __restrict__ b1,
                       float* __restrict__ hbuf, MlpShape sh) {
@@ -271,7 +278,11 @@ mlp_hidden_f32_kernel(const float* __restrict__ xq, const float* __restrict__ W1
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = mt * 16 + 4 * kg + i;
-    hbuf[((size_t)w * sh.m_pad + row) * sh.hidden + unit] = fmaxf(acc[i] + bv, 0.f);
+    if constexpr (LINEAR) {
+      if (row < sh.rows_per_set) hbuf[(size_t)query_row(sh, w, row) * sh.hidden + unit] = acc[i] + bv;
+    } else {
+      hbuf[((size_t)w * sh.m_pad + row) * sh.hidden + unit] = fmaxf(acc[i] + bv, 0.f);
+    }
   }
 }
 
@@ -352,16 +363,17 @@ extern "C" int32_t saap_classify_queries(const void* xq, const void* W1, const f
                                          const float* b2, int32_t Hw, float* scores, int32_t S, int32_t Hq,
                                          int32_t Hkv, int32_t d, int32_t hidden, int32_t B, int32_t dtype,
                                          int32_t output_kind, void* ws, size_t ws_bytes, void* stream) {
-  if (!xq || !W1 || !W2 || !scores || !ws) return SAAP_INVALID_ARG;
+  const bool linear = hidden == 0;      // one-layer model z = W2 x + b2, W2 [Hw,B,d]; W1 and b1 unused
+  if (!xq || (!linear && !W1) || !W2 || !scores || !ws) return SAAP_INVALID_ARG;
   if (!aligned16(xq) || !aligned16(W1) || !aligned16(W2) || !aligned16(scores) || !aligned16(ws))
     return SAAP_INVALID_ARG;
-  if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || hidden <= 0 || B <= 0) return SAAP_INVALID_ARG;
+  if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || hidden < 0 || B <= 0) return SAAP_INVALID_ARG;
   if (Hw != 1 && Hw != Hkv && Hw != Hq) return SAAP_INVALID_ARG;
   if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
   if (output_kind != SAAP_PROBS && output_kind != SAAP_LOGITS) return SAAP_INVALID_ARG;
   if (d != kD || hidden % 32 != 0 || B % 16 != 0 || B > SAAP_MAX_BUCKETS || hidden > 1536) return SAAP_UNSUPPORTED;
   MlpShape sh;
-  sh.S = S; sh.Hq = Hq; sh.Hw = Hw; sh.hidden = hidden; sh.B = B;
+  sh.S = S; sh.Hq = Hq; sh.Hw = Hw; sh.hidden = linear ? B : hidden; sh.B = B;
   sh.rows_per_set = S * (Hq / Hw);
   sh.m_pad = (sh.rows_per_set + 15) / 16 * 16;
   const size_t need = (size_t)SAAP_WS_HEADER_BYTES + (size_t)Hw * sh.m_pad * hidden * sizeof(float);
@@ -371,10 +383,20 @@ extern "C" int32_t saap_classify_queries(const void* xq, const void* W1, const f
   float* hbuf = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   hipStream_t hs = static_cast<hipStream_t>(stream);
   saap_trace_arm();
-  if (dtype == SAAP_BF16) {
+  if (linear) {
+    if (dtype == SAAP_BF16) {
+      const unsigned g = (unsigned)((B + 63) / 64) * m_tiles * Hw;
+      hipLaunchKernelGGL(mlp_hidden_bf16_kernel<true>, dim3(g), dim3(256), 0, hs, static_cast<const bf16_t*>(xq),
+                         static_cast<const bf16_t*>(W2), b2, scores, sh);
+    } else {
+      const dim3 g((unsigned)((B / 16 + 3) / 4), (unsigned)m_tiles, (unsigned)Hw);
+      hipLaunchKernelGGL(mlp_hidden_f32_kernel<true>, g, dim3(256), 0, hs, static_cast<const float*>(xq),
+                         static_cast<const float*>(W2), b2, scores, sh);
+    }
+  } else if (dtype == SAAP_BF16) {
     const unsigned g1 = (unsigned)((hidden + 63) / 64) * m_tiles * Hw;
     const unsigned g2 = (unsigned)((B + 31) / 32) * m_tiles * Hw;
-    hipLaunchKernelGGL(mlp_hidden_bf16_kernel, dim3(g1), dim3(256), 0, hs, static_cast<const bf16_t*>(xq),
+    hipLaunchKernelGGL(mlp_hidden_bf16_kernel<false>, dim3(g1), dim3(256), 0, hs, static_cast<const bf16_t*>(xq),
                        static_cast<const bf16_t*>(W1), b1, hbuf, sh);
     const int chunk = hidden < kOutChunk ? hidden : kOutChunk;
     const int h_rows = sh.rows_per_set < 16 ? sh.rows_per_set : 16;
@@ -391,7 +413,7 @@ extern "C" int32_t saap_classify_queries(const void* xq, const void* W1, const f
   } else {
     const dim3 g1((unsigned)((hidden / 16 + 3) / 4), (unsigned)m_tiles, (unsigned)Hw);
     const dim3 g2((unsigned)((B / 16 + 3) / 4), (unsigned)m_tiles, (unsigned)Hw);
-    hipLaunchKernelGGL(mlp_hidden_f32_kernel, g1, dim3(256), 0, hs, static_cast<const float*>(xq),
+    hipLaunchKernelGGL(mlp_hidden_f32_kernel<false>, g1, dim3(256), 0, hs, static_cast<const float*>(xq),
                        static_cast<const float*>(W1), b1, hbuf, sh);
     hipLaunchKernelGGL(mlp_out_f32_kernel, g2, dim3(256), 0, hs, hbuf, static_cast<const float*>(W2), b2, scores,
                        sh);

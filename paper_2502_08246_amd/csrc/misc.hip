@@ -81,7 +81,7 @@ extern "C" size_t saap_workspace_bytes(int32_t op, const saap_shape* sh) {
       if (S <= 0 || Hkv <= 0 || sh->N <= 0 || sh->B <= 0) return 0;
       return build_workspace_bytes(S * Hkv, sh->N, sh->B);
     case SAAP_OP_CLASSIFY_QUERIES:
-      if (S <= 0 || Hq <= 0 || sh->hidden <= 0) return 0;
+      if (S <= 0 || Hq <= 0 || sh->hidden < 0) return 0;
       return classify_workspace_bytes(S * Hq, sh->hidden);
     case SAAP_OP_WINDOW_PUSH:
       if (S <= 0 || Hkv <= 0 || sh->B <= 0) return 0;

@@ -317,6 +317,29 @@ def test_classify_queries(saap, dtype, S, Hq, Hkv, hidden, B, Hw_kind, bias):
     np.testing.assert_allclose(p.cpu().numpy(), rp, rtol=1e-4, atol=1e-9)
 
 
+@pytest.mark.parametrize("dtype,S,Hq,Hkv,B,Hw_kind,bias", [
+    ("bf16", 1, 32, 8, 1024, "kv", False), ("bf16", 3, 8, 2, 176, "kv", True), ("f32", 2, 4, 2, 64, "q", True),
+    ("bf16", 2, 4, 1, 4096, "one", False),
+])
+def test_classify_queries_one_layer(saap, dtype, S, Hq, Hkv, B, Hw_kind, bias):
+    """hidden = 0: z = W2 x + b2, the centroid routing of the paper's K-means baseline when W2 holds centroids."""
+    cfg = small("cfg1_llama8b_128k", S=S, Hq=Hq, Hkv=Hkv, N=16, B=B, hidden=32, dtype=dtype)
+    Hw = {"one": 1, "kv": Hkv, "q": Hq}[Hw_kind]
+    xq, _ = gen.make_queries(cfg, 23, DEV)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(4)
+    W = (torch.randn(Hw, B, cfg.d, generator=g, device=DEV) / math.sqrt(cfg.d)).to(xq.dtype)
+    b2 = torch.randn(Hw, B, generator=g, device=DEV) if bias else None
+    z = saap.classify_queries(xq[0], None, None, W, b2, Hkv, output_kind=saap.LOGITS)
+    p = saap.classify_queries(xq[0], None, None, W, b2, Hkv)
+    torch.cuda.synchronize()
+    hb = None if b2 is None else h(b2)
+    rz = ref.classify_queries(h(xq[0]), None, None, h(W), hb, Hkv, output_kind=1)
+    rp = ref.classify_queries(h(xq[0]), None, None, h(W), hb, Hkv)
+    np.testing.assert_allclose(z.cpu().numpy(), rz, rtol=2e-5, atol=5e-5)
+    np.testing.assert_allclose(p.cpu().numpy(), rp, rtol=1e-4, atol=1e-9)
+
+
 # ------------------------------------------------------------------------------ assignment
 def _plant_ties(x, cent):
     """Duplicate centroids (exact ties) and keys placed exactly between two centroids (near ties)."""

@@ -359,3 +359,21 @@ def test_bf16_inputs_are_exact_in_oracle(rng):
             if best is None or t > best:
                 best, bid = t, b
         assert ids[0, 0, n] == bid
+
+
+def test_one_layer_classifier_is_the_centroid_routing_of_the_kmeans_baseline():
+    """hidden = 0: logits are the inner products with the rows of W2 (library matmul), and their
+    arg-max agrees with assign_keys on the same vectors: a query routed like a key (Section 6.1)."""
+    rng = np.random.default_rng(11)
+    S, Hq, Hkv, B, d = 2, 4, 2, 16, 128
+    xq = rng.standard_normal((S, Hq, d)).astype(np.float32)
+    cent = rng.standard_normal((Hkv, B, d)).astype(np.float32)
+    bias = rng.standard_normal((Hkv, B)).astype(np.float32)
+    z = ref.classify_queries(xq, None, None, cent, bias, Hkv, output_kind=1)
+    want = np.stack([[xq[s, hq].astype(np.float64) @ cent[hq // 2].astype(np.float64).T + bias[hq // 2]
+                      for hq in range(Hq)] for s in range(S)])
+    np.testing.assert_allclose(z, want, rtol=1e-6, atol=1e-6)
+    ids = ref.assign_keys(xq.reshape(S, Hkv, 2, d), cent, bias)          # the same vectors seen as keys
+    np.testing.assert_array_equal(z.argmax(-1).reshape(S, Hkv, 2), ids)
+    p = ref.classify_queries(xq, None, None, cent, bias, Hkv)
+    np.testing.assert_allclose(p.sum(-1), 1.0, rtol=1e-6)
