@@ -338,6 +338,22 @@ int32_t saap_windowed_decode_attention(const void* q, const void* Ksorted, const
                                        int32_t d, int32_t dtype,
                                        void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * update_centroids -- the centroid step of the k-means that defines the buckets (Section 4
+ * "Learning the key assignment"; the spherical variant is the one Section 3 uses; Appendix A):
+ *   c_b <- mean of the member features of bucket b over all sequences, divided by its norm if
+ *   normalize != 0; a bucket without members keeps centroids_old[b].
+ * saap_assign_keys (assignment), saap_build_bucket_index applied to the FEATURES (grouping) and
+ * this call make one Lloyd iteration on the device.
+ *   x_sorted [S,Hkv,Ncap,d] dtype: features grouped by bucket; off [S,Hkv,B+1], len [S,Hkv,B]
+ *   centroids_old, centroids_new [Hkv,B,d] dtype (may be the same buffer)
+ * Sums are taken in fp32 in a fixed order (reproducible); the result is rounded to dtype.
+ */
+int32_t saap_update_centroids(const void* x_sorted, const int32_t* off, const int32_t* len,
+                              const void* centroids_old, void* centroids_new,
+                              int32_t S, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype,
+                              int32_t normalize, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

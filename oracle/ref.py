@@ -174,6 +174,18 @@ def windowed_decode_attention(q, K, V, ids, selected, n_sink, n_recent, scale, B
     return out, lse
 
 
+def update_centroids(x, ids, centroids_old, normalize=True):
+    """x [S,Hkv,N,d] position-ordered features, ids [S,Hkv,N] -> new centroids float64 [Hkv,B,d]."""
+    x = _f32(x)
+    ids = _i32(ids)
+    c = _f32(centroids_old)
+    S, Hkv, N, d = x.shape
+    B = c.shape[1]
+    out = np.empty((Hkv, B, d), dtype=np.float64)
+    lib().ref_update_centroids(_p(x), _p(ids), _p(c), _p(out), S, Hkv, N, B, d, 1 if normalize else 0)
+    return out
+
+
 def classify_queries(xq, W1, b1, W2, b2, Hkv, output_kind=0):
     """xq [S,Hq,d]; W1 [Hw,hidden,d]; W2 [Hw,B,hidden] -> scores float32 [S,Hq,B].
     W1 = None: the one-layer model, W2 [Hw,B,d]."""

@@ -430,6 +430,37 @@ int ref_window_push(const float* x_new, const float* k_new, const float* v_new, 
   return overflow;
 }
 
+/* Centroid step of k-means (Section 4; spherical variant of Section 3): on
+ * POSITION-ordered features x [S,Hkv,N,d] with their bucket ids.  c_b = mean of the
+ * members of b over all sequences, divided by its norm if normalize; a bucket without
+ * members keeps cent_old[b].  Output in double, not rounded. */
+void ref_update_centroids(const float* x, const int32_t* ids, const float* cent_old, double* cent_new,
+                          int S, int Hkv, int N, int B, int d, int normalize) {
+  for (int h = 0; h < Hkv; ++h)
+    for (int b = 0; b < B; ++b) {
+      double* c = cent_new + ((size_t)h * B + b) * d;
+      for (int e = 0; e < d; ++e) c[e] = 0.0;
+      long count = 0;
+      for (int s = 0; s < S; ++s)
+        for (int n = 0; n < N; ++n)
+          if (ids[((size_t)s * Hkv + h) * N + n] == b) {
+            const float* xr = x + (((size_t)s * Hkv + h) * N + n) * d;
+            for (int e = 0; e < d; ++e) c[e] += (double)xr[e];
+            count += 1;
+          }
+      if (count == 0) {
+        for (int e = 0; e < d; ++e) c[e] = (double)cent_old[((size_t)h * B + b) * d + e];
+        continue;
+      }
+      double sq = 0.0;
+      for (int e = 0; e < d; ++e) { c[e] /= (double)count; sq += c[e] * c[e]; }
+      if (normalize && sq > 0.0) {
+        double nrm = sqrt(sq);
+        for (int e = 0; e < d; ++e) c[e] /= nrm;
+      }
+    }
+}
+
 /* Selectivity (Section 6.1): the fraction of keys that take part in the
  * computation, averaged over the lists (heads).  n_keys = keys per head. */
 double ref_selectivity(const int32_t* len, const int32_t* selected, int lists, int B, int nprobe,

@@ -27,7 +27,7 @@ EXPORTS = (
     "saap_assign_keys", "saap_build_bucket_index", "saap_append_keys", "saap_classify_queries",
     "saap_select_buckets", "saap_sparse_decode_attention", "saap_dense_decode_attention", "saap_stream_read_probe",
     "saap_build_windowed_index", "saap_window_push", "saap_windowed_decode_attention",
-    "saap_select_buckets_from_logits",
+    "saap_select_buckets_from_logits", "saap_update_centroids",
 )
 
 
@@ -322,6 +322,18 @@ def windowed_decode_attention(q, Ks, Vs, off, ln, selected, resident_run, scale,
         wsb, _stream())
     _check("saap_windowed_decode_attention", st)
     return out, lse
+
+
+def update_centroids(x_sorted, off, ln, centroids_old, normalize=True, out=None):
+    """x_sorted [S,Hkv,Ncap,d] (features grouped by build_bucket_index), off, ln -> new centroids [Hkv,B,d]."""
+    S, Hkv, Ncap, d = x_sorted.shape
+    B = ln.shape[2]
+    new = out if out is not None else torch.empty_like(centroids_old)
+    st = load_library().saap_update_centroids(_ptr(x_sorted), _ptr(off), _ptr(ln), _ptr(centroids_old), _ptr(new),
+                                              _i32(S), _i32(Hkv), _i32(Ncap), _i32(B), _i32(d),
+                                              _i32(_dtype_code(x_sorted)), _i32(1 if normalize else 0), _stream())
+    _check("saap_update_centroids", st)
+    return new
 
 
 def dense_decode_attention(q, K, V, scale, off=None, ln=None, out_dtype=torch.float32, out=None, lse=None, ws=None):

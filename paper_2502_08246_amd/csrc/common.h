@@ -125,6 +125,8 @@ template <> struct Vec8<float> {
   __device__ __forceinline__ void to_float(float* o) const {
     o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
   }
+  static __device__ __forceinline__ float widen(float v) { return v; }
+  static __device__ __forceinline__ float narrow(float v) { return v; }
   __device__ __forceinline__ float dot(const Vec8<float>& q) const {
     float s = a.x * q.a.x;
     s = fmaf(a.y, q.a.y, s); s = fmaf(a.z, q.a.z, s); s = fmaf(a.w, q.a.w, s);
@@ -139,6 +141,8 @@ template <> struct Vec8<bf16_t> {
     o[0] = bf16_lo(r.x); o[1] = bf16_hi(r.x); o[2] = bf16_lo(r.y); o[3] = bf16_hi(r.y);
     o[4] = bf16_lo(r.z); o[5] = bf16_hi(r.z); o[6] = bf16_lo(r.w); o[7] = bf16_hi(r.w);
   }
+  static __device__ __forceinline__ float widen(bf16_t v) { return __uint_as_float((uint32_t)v << 16); }
+  static __device__ __forceinline__ bf16_t narrow(float v) { return (bf16_t)f32_to_bf16_bits(v); }   // round to nearest even
   // Products of two bf16 numbers are exact in fp32; v_dot2_f32_bf16 adds two of them per step.
   __device__ __forceinline__ float dot(const Vec8<bf16_t>& q) const {
     float s = 0.f;

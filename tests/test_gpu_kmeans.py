@@ -1,0 +1,85 @@
+"""GPU parity of update_centroids (the centroid step of the k-means behind the buckets, Section 4 of
+arXiv 2502.08246) and of a short Lloyd loop made of assign_keys + build_bucket_index + update_centroids.
+The oracle works in float64 on position-ordered features; the GPU sums in fp32 and rounds to the
+storage type, so centroids are compared to within one unit in the last place of that type."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from synth import gen
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def saap():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the -m gpu tests need a real device")
+    import paper_2502_08246_amd as lib
+    lib.load_library()
+    ref.set_threads(16)
+    return lib
+
+
+def h(t):
+    return gen.to_host_f32(t)
+
+
+def ulp_tolerance(dtype):
+    # relative spacing of the storage type, plus the fp32 summation error (far smaller)
+    return {"bf16": 2.0 ** -8, "f32": 2e-6}[dtype]
+
+
+@pytest.mark.parametrize("dtype,S,Hkv,N,B,normalize", [
+    ("bf16", 2, 2, 5000, 64, True), ("f32", 1, 1, 3000, 16, True), ("bf16", 1, 3, 2000, 32, False),
+])
+def test_update_centroids(saap, dtype, S, Hkv, N, B, normalize):
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(S=S, Hq=Hkv, Hkv=Hkv, N=N, B=B, nprobe=4, dtype=dtype, hidden=64)
+    cache = gen.make_cache(cfg, 51, DEV)
+    cent = gen.make_centroids(cfg, 51, DEV, cache, n_train=2048)
+    x = cache["x_keys"]
+    ids = saap.assign_keys(x, cent)
+    ids[:, :, :] = torch.where(ids == 3, torch.full_like(ids, 2), ids)      # bucket 3 ends up empty
+    off, ln, idx, xs, _ = saap.build_bucket_index(ids, x, x, B, 0)
+    new = saap.update_centroids(xs, off, ln, cent, normalize=normalize)
+    torch.cuda.synchronize()
+    want = ref.update_centroids(h(x), ids.cpu().numpy(), h(cent), normalize=normalize)
+    got = h(new).astype(np.float64)
+    tol = ulp_tolerance(dtype)
+    assert (np.abs(got - want) <= tol * np.abs(want) + 1e-7).all(), np.abs(got - want).max()
+    assert np.array_equal(h(new)[:, 3], h(cent)[:, 3])                      # the empty bucket kept its centroid
+    again = saap.update_centroids(xs, off, ln, cent, normalize=normalize)
+    torch.cuda.synchronize()
+    assert torch.equal(new, again)                                          # fixed summation order
+
+
+def test_lloyd_loop_on_the_device_tracks_the_oracle(saap):
+    """Three Lloyd iterations on the GPU against three in float64: the objective rises on both sides and ends
+    within a small margin; centroids agree closely (rounding to bf16 between iterations lets a few keys switch)."""
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(S=1, Hq=2, Hkv=2, N=8192, B=32, nprobe=4, hidden=64)
+    cache = gen.make_cache(cfg, 53, DEV)
+    x = cache["x_keys"]
+    hx = h(x)
+    c0 = x[0, :, :cfg.B].float()
+    c0 = (c0 / c0.norm(dim=-1, keepdim=True)).to(x.dtype).contiguous()       # first B keys, unit norm
+    c_gpu, c_ref = c0.clone(), h(c0).astype(np.float64)
+
+    def objective(c64):
+        a = ref.assign_keys(hx, c64.astype(np.float32))
+        return sum(float((hx[0, hh].astype(np.float64) * c64[hh][a[0, hh]]).sum()) for hh in range(cfg.Hkv))
+
+    obj0 = objective(c_ref)
+    for _ in range(3):
+        ids = saap.assign_keys(x, c_gpu)
+        off, ln, idx, xs, _ = saap.build_bucket_index(ids, x, x, cfg.B, 0)
+        c_gpu = saap.update_centroids(xs, off, ln, c_gpu)
+        r_ids = ref.assign_keys(hx, c_ref.astype(np.float32))
+        c_ref = ref.update_centroids(hx, r_ids, c_ref.astype(np.float32))
+    torch.cuda.synchronize()
+    og, orf = objective(h(c_gpu).astype(np.float64)), objective(c_ref)
+    assert og > obj0 and orf > obj0
+    assert abs(og - orf) <= 2e-3 * abs(orf)
+    cos = (h(c_gpu).astype(np.float64) * c_ref).sum(-1) / np.linalg.norm(h(c_gpu).astype(np.float64), axis=-1)
+    assert (cos > 0.995).all(), cos.min()

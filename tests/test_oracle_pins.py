@@ -377,3 +377,38 @@ def test_one_layer_classifier_is_the_centroid_routing_of_the_kmeans_baseline():
     np.testing.assert_array_equal(z.argmax(-1).reshape(S, Hkv, 2), ids)
     p = ref.classify_queries(xq, None, None, cent, bias, Hkv)
     np.testing.assert_allclose(p.sum(-1), 1.0, rtol=1e-6)
+
+
+def test_centroid_update_is_the_normalised_member_mean():
+    """Against numpy: mean of the members, unit norm; an empty bucket keeps its centroid; one more
+    Lloyd step never lowers the spherical k-means objective (sum of <x, c_assigned>) for unit-norm x."""
+    rng = np.random.default_rng(12)
+    S, Hkv, N, B, d = 2, 2, 400, 8, 128
+    x = rng.standard_normal((S, Hkv, N, d)).astype(np.float32)
+    x /= np.linalg.norm(x, axis=-1, keepdims=True)
+    cent = rng.standard_normal((Hkv, B, d)).astype(np.float32)
+    cent /= np.linalg.norm(cent, axis=-1, keepdims=True)
+    ids = ref.assign_keys(x, cent)
+    ids[ids == 3] = 2                                   # bucket 3 loses its members
+    new = ref.update_centroids(x, ids, cent)
+    for h in range(Hkv):
+        for b in range(B):
+            members = np.concatenate([x[s, h][ids[s, h] == b] for s in range(S)]).astype(np.float64)
+            if b == 3:
+                np.testing.assert_array_equal(new[h, b], cent[h, b].astype(np.float64))
+                continue
+            m = members.mean(0)
+            np.testing.assert_allclose(new[h, b], m / np.linalg.norm(m), rtol=1e-12, atol=1e-14)
+    plain = ref.update_centroids(x, ids, cent, normalize=False)
+    np.testing.assert_allclose(plain[0, 0], np.concatenate([x[s, 0][ids[s, 0] == 0] for s in range(S)]).astype(np.float64).mean(0),
+                               rtol=1e-12, atol=1e-14)
+    # monotone objective over two full iterations
+    def objective(c):
+        a = ref.assign_keys(x, c.astype(np.float32))
+        return sum(float((x[s, h].astype(np.float64) * c[h][a[s, h]]).sum()) for s in range(S) for h in range(Hkv)), a
+    o0, a0 = objective(cent.astype(np.float64))
+    c1 = ref.update_centroids(x, a0, cent)
+    o1, a1 = objective(c1)
+    c2 = ref.update_centroids(x, a1, c1.astype(np.float32))
+    o2, _ = objective(c2)
+    assert o1 >= o0 - 1e-6 and o2 >= o1 - 1e-3          # c1 is rounded to float32 for the second assignment
