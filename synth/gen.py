@@ -50,7 +50,7 @@ class Workload:
         return dataclasses.replace(self, **kw)
 
 
-# The five workloads of the benchmark spec, in order.
+# The five workloads of the benchmark spec, in order, and one more for context.
 CONFIGS = {
     "cfg0_tiny_f32": Workload("cfg0_tiny_f32", S=1, Hq=1, Hkv=1, N=4096, B=64, hidden=256, nprobe=8,
                               dtype="f32", lloyd_on_keys=True, n_queries=16),
@@ -62,6 +62,10 @@ CONFIGS = {
                                  nprobe=51, dtype="bf16"),
     "cfg4_layer_262k": Workload("cfg4_layer_262k", S=1, Hq=32, Hkv=8, N=262144, B=2048, hidden=512,
                                 nprobe=102, dtype="bf16"),
+    # Not in BASELINE.json: the shape of the paper's own timing (Section 6.2 "Timings": one KV head
+    # with its 4 query heads, 171k keys, 32 of 1024 buckets visited), for context beside its figures.
+    "paper_timing_1head_171k": Workload("paper_timing_1head_171k", S=1, Hq=4, Hkv=1, N=171000, B=1024,
+                                        hidden=512, nprobe=32, dtype="bf16"),
 }
 
 
