@@ -402,9 +402,10 @@ static int32_t select_impl(const float* scores, bool logits, float* probs, int32
     int threads = (B + ept - 1) / ept;
     threads = (threads + 63) / 64 * 64;
     if (threads > 1024) threads = 1024;
-    // candidate buffer: twice the list where the candidates are put in order by counting, the
-    // padded list itself where a bitonic network does it
-    const int cap = n_sort <= kRankSortMax ? 2 * n_sort : n_sort;
+    // candidate buffer: the padded list plus some room (the counting that orders the candidates
+    // grows with the square of their number, another radix pass costs less than that for long
+    // lists), the padded list itself where a bitonic network does the ordering
+    const int cap = n_sort <= kRankSortMax ? (n_sort <= 128 ? 2 * n_sort : n_sort + 128) : n_sort;
     const size_t lds = (size_t)cap * sizeof(unsigned long long) + (size_t)(B / 32 + 1) * sizeof(unsigned) +
                        (n_sort <= kRankSortMax ? (size_t)cap * sizeof(unsigned) : 0);
     saap_trace_arm();
