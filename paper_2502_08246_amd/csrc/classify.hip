@@ -111,11 +111,14 @@ mlp_hidden_bf16_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__
 constexpr int kOutChunk = 512;      // hidden units per LDS pass of the output kernel
 // Eight waves per workgroup: what one compute unit pulls from memory grows with the number of
 // waves that have loads in flight (two waves were measured at a third of the rate of eight).
-// For the matrix products wave (t, kq) takes bucket tile t of the two and every fourth k-step
-// starting at kq; the four partial products of a tile are added through LDS in a fixed order.
+// A workgroup takes SLAB = 32 buckets, or 64 when 32 would make more workgroups than the device
+// holds at once.  For the matrix products wave (t, kq) takes bucket tile t of the SLAB/16 and
+// every KQ-th k-step starting at kq (KQ = 8 / tiles); the KQ partial products of a tile are added
+// through LDS in a fixed order.
 constexpr int kOutThreads = 512;
-constexpr int kOutLoads = 16 * 128 / kOutThreads;     // 16-byte loads per thread and operand
+constexpr int kOutLoads = 16 * 128 / kOutThreads;     // 16-byte loads of activations per thread
 
+template <int SLAB>
 __global__ void __launch_bounds__(kOutThreads)
 mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W2, const float* __restrict__ b2,
                     float* __restrict__ scores, MlpShape sh) {
@@ -124,7 +127,9 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
   int w, mt, slab;
   decode_block(sh, w, mt, slab);
   const int rc = lane & 15, kg = lane >> 4;
-  const int b0 = slab * 32;
+  constexpr int kTiles = SLAB / 16, KQ = 8 / kTiles;
+  constexpr int kWLoads = SLAB * 64 / kOutThreads;      // 16-byte loads of weights per thread (chunk of 512)
+  const int b0 = slab * SLAB;
   const int chunk_max = min(sh.hidden, kOutChunk);
   const int pitch = chunk_max + 8;
   // LDS rows per plane of h: the real rows only (4 of a 16-row tile at batch 1), which lets three
@@ -132,7 +137,7 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
   // A only reaches the same row of the product, which is dropped
   const int h_rows = min(16, sh.rows_per_set);
   bf16_t* s_h = reinterpret_cast<bf16_t*>(smem);       // [3][h_rows][pitch]
-  bf16_t* s_w2 = s_h + 3 * h_rows * pitch;             // [32][pitch]
+  bf16_t* s_w2 = s_h + 3 * h_rows * pitch;             // [SLAB][pitch]
   const float* hrows = hbuf + ((size_t)w * sh.m_pad + mt * 16) * sh.hidden;
   const int rows_here = min(16, sh.rows_per_set - mt * 16);    // real rows of this tile (>= 1)
   // one accumulator per plane: three independent chains of matrix instructions, added at the end
@@ -140,7 +145,7 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
   SAAP_TRACE(0);
   for (int c0 = 0; c0 < sh.hidden; c0 += kOutChunk) {
     const int kc = min(kOutChunk, sh.hidden - c0);      // multiple of 32
-    // all loads of the pass first: 32 rows of W2 (kc/8 pieces each) and 16 rows of h (kc/4 pieces)
+    // all loads of the pass first: SLAB rows of W2 (kc/8 pieces each) and 16 rows of h (kc/4 pieces)
     const int pw = kc / 8, ph = kc / 4;
     // piece index -> (row, piece of the row); a shift when the pieces per row are a power of two
     // (hidden = 256, 512, 1024: the usual case), a division otherwise
@@ -152,11 +157,11 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
     auto split_h = [&](int q, int& row, int& pc) {
       if (ph_sh >= 0) { row = q >> ph_sh; pc = q & (ph - 1); } else { row = q / ph; pc = q % ph; }
     };
-    u32x4_t wv[kOutLoads], hv[kOutLoads];
+    u32x4_t wv[kWLoads], hv[kOutLoads];
 #pragma unroll
-    for (int i = 0; i < kOutLoads; ++i) {
+    for (int i = 0; i < kWLoads; ++i) {
       int row, pc;
-      split_w(min(tid + kOutThreads * i, 32 * pw - 1), row, pc);
+      split_w(min(tid + kOutThreads * i, SLAB * pw - 1), row, pc);
       const int b = min(b0 + row, sh.B - 1);
       wv[i] = load16(W2 + ((size_t)w * sh.B + b) * sh.hidden + c0 + pc * 8);
     }
@@ -173,9 +178,9 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
     // stores use the same clamped piece index as the loads: surplus threads rewrite the last
     // piece with identical data, and the code stays free of branches
 #pragma unroll
-    for (int i = 0; i < kOutLoads; ++i) {
+    for (int i = 0; i < kWLoads; ++i) {
       int row, pc;
-      split_w(min(tid + kOutThreads * i, 32 * pw - 1), row, pc);
+      split_w(min(tid + kOutThreads * i, SLAB * pw - 1), row, pc);
       *reinterpret_cast<u32x4_t*>(s_w2 + row * pitch + pc * 8) = wv[i];
     }
     if (c0 == 0) SAAP_TRACE(5);
@@ -203,7 +208,7 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
     }
     __syncthreads();
     if (c0 == 0) SAAP_TRACE(1);
-    const int tile = wave & 1, kq = wave >> 1;
+    const int tile = wave % kTiles, kq = wave / kTiles;
     const bf16_t* wrow = s_w2 + (tile * 16 + rc) * pitch + kg * 8;
     const bf16_t* hrow = s_h + min(rc, rows_here - 1) * pitch + kg * 8;
     auto lds16 = [](const bf16_t* ptr) { return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(ptr)); };
@@ -211,14 +216,14 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
     int st = kq;
     // four of the wave's k-steps at a time: their sixteen LDS reads go out before the twelve
     // matrix instructions, so the read latency is paid once per group instead of once per step
-    for (; st + 12 < nst; st += 16) {
+    for (; st + 3 * KQ < nst; st += 4 * KQ) {
       bf16x8_t b[4], a0[4], a1[4], a2[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        b[u] = lds16(wrow + (st + 4 * u) * 32);
-        a0[u] = lds16(hrow + (st + 4 * u) * 32);
-        a1[u] = lds16(hrow + h_rows * pitch + (st + 4 * u) * 32);
-        a2[u] = lds16(hrow + 2 * h_rows * pitch + (st + 4 * u) * 32);
+        b[u] = lds16(wrow + (st + KQ * u) * 32);
+        a0[u] = lds16(hrow + (st + KQ * u) * 32);
+        a1[u] = lds16(hrow + h_rows * pitch + (st + KQ * u) * 32);
+        a2[u] = lds16(hrow + 2 * h_rows * pitch + (st + KQ * u) * 32);
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -227,7 +232,7 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
         acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[u], b[u], acc0, 0, 0, 0);
       }
     }
-    for (; st < nst; st += 4) {
+    for (; st < nst; st += KQ) {
       const bf16x8_t b = lds16(wrow + st * 32);
       acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds16(hrow + 2 * h_rows * pitch + st * 32), b, acc2, 0, 0, 0);
       acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds16(hrow + h_rows * pitch + st * 32), b, acc1, 0, 0, 0);
@@ -240,9 +245,10 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
   f32x4_t* s_part = reinterpret_cast<f32x4_t*>(smem);   // [8 waves][64 lanes]
   s_part[wave * 64 + lane] = acc;
   __syncthreads();
-  if (wave >= 2) return;
-  acc = ((s_part[wave * 64 + lane] + s_part[(wave + 2) * 64 + lane]) + s_part[(wave + 4) * 64 + lane]) +
-        s_part[(wave + 6) * 64 + lane];
+  if (wave >= kTiles) return;
+  acc = s_part[wave * 64 + lane];
+#pragma unroll
+  for (int j = 1; j < KQ; ++j) acc += s_part[(wave + kTiles * j) * 64 + lane];
   SAAP_TRACE(2);
   const int bucket = b0 + wave * 16 + rc;
   if (bucket < sh.B) {
@@ -395,21 +401,26 @@ extern "C" int32_t saap_classify_queries(const void* xq, const void* W1, const f
     }
   } else if (dtype == SAAP_BF16) {
     const unsigned g1 = (unsigned)((hidden + 63) / 64) * m_tiles * Hw;
-    const unsigned g2 = (unsigned)((B + 31) / 32) * m_tiles * Hw;
+    // 64 buckets per workgroup when 32 would give more workgroups than fit the device at three per
+    // compute unit (they would run in two rounds)
+    const bool wide = (long long)((B + 31) / 32) * m_tiles * Hw > 3LL * device_cus();
+    const int slab_rows = wide ? 64 : 32;
+    const unsigned g2 = (unsigned)((B + slab_rows - 1) / slab_rows) * m_tiles * Hw;
     hipLaunchKernelGGL(mlp_hidden_bf16_kernel<false>, dim3(g1), dim3(256), 0, hs, static_cast<const bf16_t*>(xq),
                        static_cast<const bf16_t*>(W1), b1, hbuf, sh);
     const int chunk = hidden < kOutChunk ? hidden : kOutChunk;
     const int h_rows = sh.rows_per_set < 16 ? sh.rows_per_set : 16;
-    size_t lds = (size_t)(3 * h_rows + 32) * (chunk + 8) * sizeof(bf16_t);
+    size_t lds = (size_t)(3 * h_rows + slab_rows) * (chunk + 8) * sizeof(bf16_t);
     const size_t lds_part = (size_t)kOutThreads * sizeof(f32x4_t);      // partial products of the eight waves
     if (lds < lds_part) lds = lds_part;
+    auto kern = wide ? mlp_out_bf16_kernel<64> : mlp_out_bf16_kernel<32>;
     if (lds > 48 * 1024) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_out_bf16_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds) != hipSuccess)
         return SAAP_HIP_ERROR;
     }
-    hipLaunchKernelGGL(mlp_out_bf16_kernel, dim3(g2), dim3(kOutThreads), lds, hs, hbuf, static_cast<const bf16_t*>(W2), b2,
-                       scores, sh);
+    hipLaunchKernelGGL(kern, dim3(g2), dim3(kOutThreads), lds, hs, hbuf, static_cast<const bf16_t*>(W2), b2, scores,
+                       sh);
   } else {
     const dim3 g1((unsigned)((hidden / 16 + 3) / 4), (unsigned)m_tiles, (unsigned)Hw);
     const dim3 g2((unsigned)((B / 16 + 3) / 4), (unsigned)m_tiles, (unsigned)Hw);
