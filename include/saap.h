@@ -339,6 +339,26 @@ int32_t saap_windowed_decode_attention(const void* q, const void* Ksorted, const
                                        void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * recompact_index -- index maintenance during long generations: when a bucket's slack has
+ * run out (overflow flag of saap_append_keys / saap_window_push) the cache is laid out afresh
+ * with `slack_new` free slots behind every bucket, WITHOUT assigning any key again: every
+ * member keeps its bucket and its order, only the offsets change.  (The paper needs the index
+ * to take new keys during generation, Section 1, and gives no mechanism.)
+ *   off, len, idx, Ksorted, Vsorted: the current index ([.,runs+1], [.,runs], [.,Ncap], [.,Ncap,d])
+ *   resident: 1 if the index has a resident run behind its B buckets (it keeps its slot count)
+ *   off_new [S,Hkv,runs+1], idx_new [S,Hkv,Ncap_new], Ksorted_new, Vsorted_new [S,Hkv,Ncap_new,d]: out;
+ *   they must not alias the inputs.  len is valid for both layouts.  resident_ids stays valid.
+ *   Ncap_new must hold sum(len) + B*slack_new (+ the resident slots) of every (sequence, head);
+ *   if it does not, *overflow_flag (device int32, zeroed by the caller) is set and nothing is moved.
+ */
+int32_t saap_recompact_index(const int32_t* off, const int32_t* len, const int32_t* idx,
+                             const void* Ksorted, const void* Vsorted,
+                             int32_t* off_new, int32_t* idx_new, void* Ksorted_new, void* Vsorted_new,
+                             int32_t* overflow_flag,
+                             int32_t S, int32_t Hkv, int32_t Ncap, int32_t Ncap_new, int32_t B,
+                             int32_t resident, int32_t d, int32_t dtype, int32_t slack_new, void* stream);
+
+/*
  * update_centroids -- the centroid step of the k-means that defines the buckets (Section 4
  * "Learning the key assignment"; the spherical variant is the one Section 3 uses; Appendix A):
  *   c_b <- mean of the member features of bucket b over all sequences, divided by its norm if

@@ -38,6 +38,7 @@ def lib():
         _lib.ref_get_threads.restype = ctypes.c_int
         _lib.ref_append_keys.restype = ctypes.c_int
         _lib.ref_window_push.restype = ctypes.c_int
+        _lib.ref_recompact_index.restype = ctypes.c_int
     return _lib
 
 
@@ -172,6 +173,22 @@ def windowed_decode_attention(q, K, V, ids, selected, n_sink, n_recent, scale, B
     lib().ref_windowed_decode_attention(_p(q), _p(K), _p(V), _p(ids), _p(selected), nprobe, mode, n_sink,
                                         n_recent, ctypes.c_float(scale), _p(out), _p(lse), S, Hq, Hkv, Nt, B, d)
     return out, lse
+
+
+def recompact_index(off, ln, idx, Ks, Vs, slack_new, Ncap_new, resident=False):
+    """-> (off_new, idx_new, Ks_new, Vs_new, overflow flag); ln stays valid."""
+    S, Hkv, Ncap, d = Ks.shape
+    runs = ln.shape[2]
+    B = runs - (1 if resident else 0)
+    for a, dt in ((off, np.int32), (ln, np.int32), (idx, np.int32), (Ks, np.float32), (Vs, np.float32)):
+        assert a.dtype == dt and a.flags["C_CONTIGUOUS"]
+    off_new = np.zeros_like(off)
+    idx_new = np.full((S, Hkv, Ncap_new), -1, dtype=np.int32)
+    Kn = np.zeros((S, Hkv, Ncap_new, d), dtype=np.float32)
+    Vn = np.zeros((S, Hkv, Ncap_new, d), dtype=np.float32)
+    flag = lib().ref_recompact_index(_p(off), _p(ln), _p(idx), _p(Ks), _p(Vs), _p(off_new), _p(idx_new), _p(Kn), _p(Vn),
+                                     S, Hkv, Ncap, Ncap_new, B, 1 if resident else 0, d, slack_new)
+    return off_new, idx_new, Kn, Vn, int(flag)
 
 
 def update_centroids(x, ids, centroids_old, normalize=True):

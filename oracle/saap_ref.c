@@ -430,6 +430,38 @@ int ref_window_push(const float* x_new, const float* k_new, const float* v_new, 
   return overflow;
 }
 
+/* Fresh slack behind every bucket, nothing assigned again: members keep their bucket and
+ * their order.  runs = B, or B + 1 with a resident run that keeps its slot count.
+ * Returns 1 (and moves nothing) if Ncap_new is too small for some (sequence, head). */
+int ref_recompact_index(const int32_t* off, const int32_t* len, const int32_t* idx, const float* Ks,
+                        const float* Vs, int32_t* off_new, int32_t* idx_new, float* Kn, float* Vn,
+                        int S, int Hkv, int Ncap, int Ncap_new, int B, int resident, int d, int slack_new) {
+  int runs = B + resident;
+  for (int u = 0; u < S * Hkv; ++u) {
+    const int32_t* o = off + (size_t)u * (runs + 1);
+    const int32_t* l = len + (size_t)u * runs;
+    int32_t* on = off_new + (size_t)u * (runs + 1);
+    on[0] = 0;
+    for (int b = 0; b < B; ++b) on[b + 1] = on[b] + l[b] + slack_new;
+    if (resident) on[B + 1] = on[B] + (o[B + 1] - o[B]);
+    if (on[runs] > Ncap_new) return 1;
+  }
+  for (int u = 0; u < S * Hkv; ++u) {
+    const int32_t* o = off + (size_t)u * (runs + 1);
+    const int32_t* l = len + (size_t)u * runs;
+    const int32_t* on = off_new + (size_t)u * (runs + 1);
+    for (int j = 0; j < Ncap_new; ++j) idx_new[(size_t)u * Ncap_new + j] = -1;
+    for (int b = 0; b < runs; ++b)
+      for (int r = 0; r < l[b]; ++r) {
+        size_t src = (size_t)u * Ncap + o[b] + r, dst = (size_t)u * Ncap_new + on[b] + r;
+        idx_new[dst] = idx[src];
+        memcpy(Kn + dst * d, Ks + src * d, sizeof(float) * d);
+        memcpy(Vn + dst * d, Vs + src * d, sizeof(float) * d);
+      }
+  }
+  return 0;
+}
+
 /* Centroid step of k-means (Section 4; spherical variant of Section 3): on
  * POSITION-ordered features x [S,Hkv,N,d] with their bucket ids.  c_b = mean of the
  * members of b over all sequences, divided by its norm if normalize; a bucket without

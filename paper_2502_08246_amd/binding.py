@@ -27,7 +27,7 @@ EXPORTS = (
     "saap_assign_keys", "saap_build_bucket_index", "saap_append_keys", "saap_classify_queries",
     "saap_select_buckets", "saap_sparse_decode_attention", "saap_dense_decode_attention", "saap_stream_read_probe",
     "saap_build_windowed_index", "saap_window_push", "saap_windowed_decode_attention",
-    "saap_select_buckets_from_logits", "saap_update_centroids",
+    "saap_select_buckets_from_logits", "saap_update_centroids", "saap_recompact_index",
 )
 
 
@@ -322,6 +322,27 @@ def windowed_decode_attention(q, Ks, Vs, off, ln, selected, resident_run, scale,
         wsb, _stream())
     _check("saap_windowed_decode_attention", st)
     return out, lse
+
+
+def recompact_index(off, ln, idx, Ks, Vs, slack_new, Ncap_new, resident=False, overflow_flag=None):
+    """Fresh slack behind every bucket without re-assignment. -> (off_new, idx_new, Ks_new, Vs_new, overflow_flag);
+    ln stays valid."""
+    S, Hkv, Ncap, d = Ks.shape
+    runs = ln.shape[2]
+    B = runs - (1 if resident else 0)
+    dev = Ks.device
+    off_new = torch.empty_like(off)
+    idx_new = torch.empty(S, Hkv, Ncap_new, dtype=torch.int32, device=dev)
+    Kn = torch.zeros(S, Hkv, Ncap_new, d, dtype=Ks.dtype, device=dev)
+    Vn = torch.zeros(S, Hkv, Ncap_new, d, dtype=Ks.dtype, device=dev)
+    if overflow_flag is None:
+        overflow_flag = torch.zeros(4, dtype=torch.int32, device=dev)
+    st = load_library().saap_recompact_index(_ptr(off), _ptr(ln), _ptr(idx), _ptr(Ks), _ptr(Vs), _ptr(off_new),
+                                             _ptr(idx_new), _ptr(Kn), _ptr(Vn), _ptr(overflow_flag), _i32(S), _i32(Hkv),
+                                             _i32(Ncap), _i32(Ncap_new), _i32(B), _i32(1 if resident else 0), _i32(d),
+                                             _i32(_dtype_code(Ks)), _i32(slack_new), _stream())
+    _check("saap_recompact_index", st)
+    return off_new, idx_new, Kn, Vn, overflow_flag
 
 
 def update_centroids(x_sorted, off, ln, centroids_old, normalize=True, out=None):

@@ -475,6 +475,64 @@ window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, con
   }
 }
 
+// ---- recompact: fresh slack behind every bucket without assigning the keys again ---------------
+// One workgroup per unit: new offsets from the current lengths.  `runs` = B, or B + 1 with a
+// resident run, which keeps its fixed number of slots.
+__global__ void __launch_bounds__(1024)
+reoffset_kernel(const int32_t* __restrict__ len, const int32_t* __restrict__ off, int32_t* __restrict__ off_new,
+                int runs, int B, int slack, int Ncap_new, int32_t* __restrict__ overflow) {
+  __shared__ int s_wsum[16];
+  const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per = (B + blockDim.x - 1) / blockDim.x;
+  const int b0 = tid * per, b1 = min(b0 + per, B);
+  const int32_t* l = len + (size_t)unit * runs;
+  const int32_t* o = off + (size_t)unit * (runs + 1);
+  int32_t* on = off_new + (size_t)unit * (runs + 1);
+  int mine = 0;
+  for (int b = b0; b < b1; ++b) mine += l[b] + slack;
+  const int incl = (int)wave_prefix_sum((unsigned)mine);
+  if (lane == 63) s_wsum[wave] = incl;
+  __syncthreads();
+  int run = incl - mine;
+  for (int w = 0; w < wave; ++w) run += s_wsum[w];
+  if (tid == 0) on[0] = 0;
+  for (int b = b0; b < b1; ++b) {
+    run += l[b] + slack;
+    on[b + 1] = run;
+    if (b == B - 1) {
+      int end = run;
+      if (runs > B) {
+        end += o[B + 1] - o[B];
+        on[B + 1] = end;
+      }
+      if (end > Ncap_new) *overflow = 1;
+    }
+  }
+}
+
+// One workgroup per (run, unit): the run's member slots move to their place in the new cache.
+template <int CHUNKS /* 16-byte pieces per row */>
+__global__ void __launch_bounds__(256)
+recopy_kernel(const int32_t* __restrict__ off, const int32_t* __restrict__ len, const int32_t* __restrict__ off_new,
+              const int32_t* __restrict__ idx, int32_t* __restrict__ idx_new, const uint4* __restrict__ Ks,
+              const uint4* __restrict__ Vs, uint4* __restrict__ Kn, uint4* __restrict__ Vn, int runs, int B, int Ncap,
+              int Ncap_new, const int32_t* __restrict__ overflow) {
+  if (*overflow) return;                       // the new cache is too small: nothing is moved
+  const int b = blockIdx.x, unit = blockIdx.y, tid = threadIdx.x;
+  const int first = off[(size_t)unit * (runs + 1) + b], dst = off_new[(size_t)unit * (runs + 1) + b];
+  // a resident run is a ring: every slot up to its length moves, whatever position it holds
+  const int n = len[(size_t)unit * runs + b];
+  for (int r = tid; r < n; r += 256) idx_new[(size_t)unit * Ncap_new + dst + r] = idx[(size_t)unit * Ncap + first + r];
+  constexpr int kRowsPerPass = 256 / CHUNKS;
+  const int piece = tid % CHUNKS;
+  for (int r = tid / CHUNKS; r < n; r += kRowsPerPass) {
+    const size_t src = ((size_t)unit * Ncap + first + r) * CHUNKS + piece;
+    const size_t out = ((size_t)unit * Ncap_new + dst + r) * CHUNKS + piece;
+    Kn[out] = Ks[src];
+    Vn[out] = Vs[src];
+  }
+}
+
 }  // namespace
 
 size_t push_workspace_bytes(long long units, int B) {
@@ -635,5 +693,44 @@ extern "C" int32_t saap_append_keys(const void* x_new, const void* k_new, const 
                        static_cast<const float*>(centroids), bias, off, len, idx,
                        static_cast<float*>(Ksorted), static_cast<float*>(Vsorted), new_bucket_ids,
                        overflow_flag, Hkv, Ncap, B);
+  return launch_status();
+}
+
+extern "C" int32_t saap_recompact_index(const int32_t* off, const int32_t* len, const int32_t* idx,
+                                        const void* Ksorted, const void* Vsorted, int32_t* off_new,
+                                        int32_t* idx_new, void* Ksorted_new, void* Vsorted_new,
+                                        int32_t* overflow_flag, int32_t S, int32_t Hkv, int32_t Ncap,
+                                        int32_t Ncap_new, int32_t B, int32_t resident, int32_t d, int32_t dtype,
+                                        int32_t slack_new, void* stream) {
+  if (!off || !len || !idx || !Ksorted || !Vsorted || !off_new || !idx_new || !Ksorted_new || !Vsorted_new ||
+      !overflow_flag)
+    return SAAP_INVALID_ARG;
+  const void* ptrs[] = {idx, Ksorted, Vsorted, idx_new, Ksorted_new, Vsorted_new};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return SAAP_INVALID_ARG;
+  if (S <= 0 || Hkv <= 0 || Ncap <= 0 || Ncap_new <= 0 || B <= 0 || slack_new < 0) return SAAP_INVALID_ARG;
+  if (resident != 0 && resident != 1) return SAAP_INVALID_ARG;
+  if (Ksorted == Ksorted_new || Vsorted == Vsorted_new || idx == idx_new || off == off_new) return SAAP_INVALID_ARG;
+  if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
+  if (d != kD || B > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
+  const long long units = (long long)S * Hkv;
+  if (units > 65535) return SAAP_UNSUPPORTED;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const int runs = B + resident;
+  hipLaunchKernelGGL(reoffset_kernel, dim3((unsigned)units), dim3(1024), 0, hs, len, off, off_new, runs, B, slack_new,
+                     Ncap_new, overflow_flag);
+  const size_t n_idx = (size_t)units * Ncap_new;
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n_idx + 255) / 256)), dim3(256), 0, hs, idx_new, n_idx, -1);
+  const dim3 grid((unsigned)runs, (unsigned)units);
+  if (dtype == SAAP_BF16)
+    hipLaunchKernelGGL(recopy_kernel<16>, grid, dim3(256), 0, hs, off, len, off_new, idx, idx_new,
+                       static_cast<const uint4*>(Ksorted), static_cast<const uint4*>(Vsorted),
+                       static_cast<uint4*>(Ksorted_new), static_cast<uint4*>(Vsorted_new), runs, B, Ncap, Ncap_new,
+                       overflow_flag);
+  else
+    hipLaunchKernelGGL(recopy_kernel<32>, grid, dim3(256), 0, hs, off, len, off_new, idx, idx_new,
+                       static_cast<const uint4*>(Ksorted), static_cast<const uint4*>(Vsorted),
+                       static_cast<uint4*>(Ksorted_new), static_cast<uint4*>(Vsorted_new), runs, B, Ncap, Ncap_new,
+                       overflow_flag);
   return launch_status();
 }

@@ -160,3 +160,76 @@ def test_resident_run_minus_one_is_plain_sparse_attention(saap):
     b, bl = saap.windowed_decode_attention(q[0], Ks, Vs, off, ln, sel, -1, SCALE)
     torch.cuda.synchronize()
     assert torch.equal(a, b) and torch.equal(al, bl)
+
+
+@pytest.mark.parametrize("dtype,resident", [("bf16", True), ("f32", False)])
+def test_recompact_index(saap, dtype, resident):
+    """Slack runs out during generation; recompact_index lays the cache out afresh without re-assignment:
+    state bit for bit against the oracle, attention unchanged, generation goes on."""
+    S, Hq, Hkv, N, B, slack, steps = 2, 4, 2, 3000, 16, 6, 120
+    n_sink, n_recent = (1, 63) if resident else (0, 0)
+    W = n_sink + n_recent
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(S=S, Hq=Hq, Hkv=Hkv, N=N + steps, B=B, nprobe=4, dtype=dtype, hidden=64)
+    cache = gen.make_cache(cfg, 61, DEV)
+    cent = gen.make_centroids(cfg, 61, DEV, cache, n_train=2048)
+    _, q = gen.make_queries(cfg, 61, DEV, n_steps=2)
+    x, K, V = cache["x_keys"], cache["K"], cache["V"]
+    hK, hV, hx, hc = h(K), h(V), h(x), h(cent)
+    ids_all = saap.assign_keys(x, cent)
+    h_ids = ids_all.cpu().numpy()
+    ids0, K0, V0 = (a[:, :, :N].contiguous() for a in (ids_all, K, V))
+    if resident:
+        off, ln, idx, Ks, Vs, res = saap.build_windowed_index(ids0, K0, V0, B, slack, n_sink, n_recent)
+        want = list(ref.build_windowed_index(h_ids[:, :, :N], hK[:, :, :N], hV[:, :, :N], B, slack, n_sink, n_recent))
+    else:
+        off, ln, idx, Ks, Vs = saap.build_bucket_index(ids0, K0, V0, B, slack)
+        want = list(ref.build_bucket_index(h_ids[:, :, :N], hK[:, :, :N], hV[:, :, :N], B, slack))
+
+    def push(t, state, rstate):
+        pos = torch.full((S,), N + t, dtype=torch.int32, device=DEV)
+        xn, kn, vn = (a[:, :, N + t].contiguous() for a in (x, K, V))
+        o, l, i, ks, vs = state[:5]
+        if resident:
+            _, flag = saap.window_push(xn, kn, vn, pos, cent, None, o, l, i, ks, vs, state[5], n_sink, n_recent)
+            _, rflag = ref.window_push(hx[:, :, N + t], hK[:, :, N + t], hV[:, :, N + t], pos.cpu().numpy(), hc, None,
+                                       rstate[0], rstate[1], rstate[2], rstate[3], rstate[4], rstate[5], n_sink, n_recent)
+        else:
+            _, flag = saap.append_keys(xn, kn, vn, pos, cent, None, o, l, i, ks, vs)
+            _, rflag = ref.append_keys(hx[:, :, N + t], hK[:, :, N + t], hV[:, :, N + t], pos.cpu().numpy(), hc, None,
+                                       rstate[0], rstate[1], rstate[2], rstate[3], rstate[4])
+        torch.cuda.synchronize()
+        assert (flag[0].item() != 0) == (rflag != 0)
+        return rflag
+
+    state = [off, ln, idx, Ks, Vs] + ([res] if resident else [])
+    t = 0
+    while not push(t, state, want):
+        t += 1
+        assert t < steps, "test sizing: the slack must run out"
+    # the refused step left some heads pushed and one not: both sides are in that same state
+    assert np.array_equal(ln.cpu().numpy(), want[1]) and np.array_equal(idx.cpu().numpy(), want[2])
+    Ncap_new = int(want[1][..., :B].sum(axis=-1).max()) + B * 24 + W
+    off2, idx2, K2, V2, flag = saap.recompact_index(off, ln, idx, Ks, Vs, 24, Ncap_new, resident=resident)
+    torch.cuda.synchronize()
+    r_off2, r_idx2, rK2, rV2, rflag = ref.recompact_index(want[0], want[1], want[2], want[3], want[4], 24, Ncap_new,
+                                                          resident=resident)
+    assert flag[0].item() == 0 and rflag == 0
+    assert np.array_equal(off2.cpu().numpy(), r_off2) and np.array_equal(idx2.cpu().numpy(), r_idx2)
+    live = r_idx2 >= 0
+    assert np.array_equal(h(K2)[live], rK2[live]) and np.array_equal(h(V2)[live], rV2[live])
+    # attention through the old and the new layout: same keys, same order inside every run -> same bits
+    sel = torch.arange(3, dtype=torch.int32, device=DEV).repeat(S, Hkv, 1)
+    a, al = saap.windowed_decode_attention(q[0], Ks, Vs, off, ln, sel, B if resident else -1, SCALE)
+    b, bl = saap.windowed_decode_attention(q[0], K2, V2, off2, ln, sel, B if resident else -1, SCALE)
+    torch.cuda.synchronize()
+    assert_close(b.cpu().numpy(), a.cpu().numpy(), dtype, "attention after recompact")
+    # generation goes on in the new layout
+    state2 = [off2, ln, idx2, K2, V2] + ([res] if resident else [])
+    want2 = [r_off2, want[1], r_idx2, rK2, rV2] + ([want[5]] if resident else [])
+    for tt in range(t + 1, t + 11):
+        assert push(tt, state2, want2) == 0
+    assert np.array_equal(ln.cpu().numpy(), want2[1]) and np.array_equal(idx2.cpu().numpy(), want2[2])
+    # a cache that cannot hold the keys is refused and nothing moves
+    _, _, _, _, flag = saap.recompact_index(off2, ln, idx2, K2, V2, 24, 64, resident=resident)
+    torch.cuda.synchronize()
+    assert flag[0].item() == 1

@@ -155,3 +155,48 @@ def test_push_into_a_full_bucket_changes_nothing_and_raises_the_flag():
     assert flag == 1
     for a, b in zip(before, (off, ln, idx, Ks, Vs, res)):
         np.testing.assert_array_equal(a, b)
+
+
+def test_recompact_keeps_every_member_and_restores_the_slack():
+    """After pushes have eaten the slack: the recompacted index holds the same keys in the same buckets in the
+    same order (position meaning unchanged, by brute force), every bucket has its fresh slack again, the
+    attention through it is unchanged, and a cache that is too small is refused."""
+    N, n_sink, n_recent, slack, steps = 300, 2, 30, 12, 60
+    x, K, V, cent, q, ids = make(6, N=N, extra=steps + 10)
+    S, Hkv, Nt, d = K.shape
+    B = cent.shape[1]
+    off, ln, idx, Ks, Vs, res = ref.build_windowed_index(ids[:, :, :N], K[:, :, :N], V[:, :, :N], B, slack, n_sink, n_recent)
+    t = 0
+    while True:                                            # push until some bucket is full
+        pos = np.full((S,), N + t, dtype=np.int32)
+        state = [a.copy() for a in (ln, idx, Ks, Vs, res)]
+        _, flag = ref.window_push(x[:, :, N + t], K[:, :, N + t], V[:, :, N + t], pos, cent, None, off, ln, idx, Ks, Vs, res,
+                                  n_sink, n_recent)
+        if flag:
+            ln, idx, Ks, Vs, res = state               # a refused push changes nothing for its head; undo the others too
+            break
+        t += 1
+        assert t < steps
+    n_now = N + t
+    W = n_sink + n_recent
+    Ncap_new = n_now - W + B * 20 + W
+    off2, idx2, K2, V2, flag = ref.recompact_index(off, ln, idx, Ks, Vs, 20, Ncap_new, resident=True)
+    assert flag == 0
+    check_state(off2, ln, idx2, K2, V2, res, K, V, ids, n_now, B, 20, n_sink, n_recent)
+    for s in range(S):
+        for h in range(Hkv):
+            for b in range(B):
+                assert off2[s, h, b + 1] - off2[s, h, b] == ln[s, h, b] + 20
+    scale = 0.125
+    sel = np.broadcast_to(np.array([1, 4, 6], dtype=np.int32), (S, Hkv, 3)).copy()
+    sel_plus = np.concatenate([sel, np.full((S, Hkv, 1), B, dtype=np.int32)], axis=2)
+    a, _ = ref.sparse_decode_attention(q, K[:, :, :n_now], V[:, :, :n_now], off, ln, idx, sel_plus, scale)
+    b, _ = ref.sparse_decode_attention(q, K[:, :, :n_now], V[:, :, :n_now], off2, ln, idx2, sel_plus, scale)
+    np.testing.assert_array_equal(a, b)
+    # the push that was refused goes through now
+    pos = np.full((S,), n_now, dtype=np.int32)
+    _, flag = ref.window_push(x[:, :, n_now], K[:, :, n_now], V[:, :, n_now], pos, cent, None, off2, ln, idx2, K2, V2, res,
+                              n_sink, n_recent)
+    assert flag == 0
+    _, _, _, _, flag = ref.recompact_index(off2, ln, idx2, K2, V2, 20, Ncap_new - 1 - B * 20, resident=True)
+    assert flag == 1
