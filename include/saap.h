@@ -237,7 +237,10 @@ int32_t saap_select_buckets_from_logits(const float* logits, float* probs, int32
  *   off [S,Hkv,B+1], len [S,Hkv,B]; selected as written by saap_select_buckets
  *   out [S,Hq,d] of out_dtype; lse [S,Hq] fp32 or NULL
  * All G heads of a group are computed together from one read of K and V
- * (GROUP_SUM).  An empty selection gives out = 0, lse = -inf.
+ * (GROUP_SUM).  With INDEPENDENT lists (selected [S,Hq,nprobe]) the union of the
+ * G lists of a group is read once and every head attends only the keys of its own
+ * list (B <= 8192; beyond that every head reads its list separately).
+ * An empty selection gives out = 0, lse = -inf.
  * Bucket ids in `selected` must be distinct and inside [0,B).
  */
 int32_t saap_sparse_decode_attention(const void* q, const void* Ksorted, const void* Vsorted,

@@ -45,6 +45,7 @@ struct AttnParams {
   int P;
   int Hq, Hkv;
   int independent;        // unit = (sequence, query head) instead of (sequence, KV head)
+  int masked_lists;       // MASKED kernels: lists per unit in `selected` (one per head), nsel entries each
   int use_table;          // list mode: build the per-chunk run table (pays off from a few chunks per workgroup)
   int stage;              // list mode: copy the unit's len/off arrays to LDS (needs nseg <= 2*NT, B <= 8*NT)
   int out_bf16;
@@ -93,6 +94,7 @@ template <typename T, int KB>
 struct Batch {
   Vec8<T> k[KB], v[KB];
   unsigned valid;   // bit i: slot i holds a key of the range
+  unsigned heads;   // MASKED kernels: bits 8i .. 8i+7 = heads that attend the key in slot i
 };
 
 // One stage of the reduction of N partial sums over a 16-lane group.  The lane keeps the half
@@ -145,7 +147,10 @@ __device__ __forceinline__ float ror_sum(float x) {
 template <int L>
 __device__ __forceinline__ float group_bcast(float x) { return dpp_mov<0x150 + L>(x); }
 
-template <typename T, int G, bool LIST, int NT>
+// MASKED (with LIST): every head of the group brings its own list of runs (independent routing).
+// The union of the lists is visited once; a key takes part only for the heads whose list holds
+// its run (the others see a score of -inf for it).
+template <typename T, int G, bool LIST, int NT, bool MASKED = false>
 __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_wsum[16];
@@ -189,9 +194,76 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   int* rowoff = pre + (p.nseg + 1);                 // [nseg]   first row of each run
   int* seglo = rowoff + p.nseg;                     // [max_chunks] run holding the first key of my k-th chunk
   int* seghi = seglo + p.max_chunks;                // [max_chunks] run holding its last key
+  int* segm = seghi + p.max_chunks;                 // MASKED: [nseg] heads that attend each run
   int T_total;
-  if (LIST) {
-    const int nseg = p.nseg;
+  int nseg = p.nseg;                                // MASKED: p.nseg is the capacity, the union may be shorter
+  if constexpr (LIST && MASKED) {
+    // Union of the G lists in ascending bucket order.  Every thread owns B/NT consecutive buckets:
+    // their len/off loads go out first and are in flight while the head masks are collected.
+    int* hm = segm + p.nseg;                        // [B] heads that selected each bucket
+    const int32_t* lenu = p.len + (size_t)kvu * p.B;
+    const int32_t* offu = p.off + (size_t)kvu * (p.B + 1);
+    const int perb = (p.B + NT - 1) / NT;           // <= 16: B <= SAAP_MAX_BUCKETS + 1, NT >= 512 checked on the host
+    const int bb0 = tid * perb;
+    int lv[16], ov[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const int b = min(bb0 + k, p.B - 1);
+      lv[k] = lenu[b];
+      ov[k] = offu[b];
+    }
+    const int n_entries = p.masked_lists * p.nsel;
+    const int32_t* selu = p.selected + (size_t)unit * n_entries;
+    int sv[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) sv[k] = n_entries > 0 ? selu[min(tid + k * NT, n_entries - 1)] : 0;
+    for (int b = tid; b < p.B; b += NT) hm[b] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int j = tid + k * NT;
+      if (j < n_entries) atomicOr(&hm[min(max(sv[k], 0), p.B - 1)], 1 << (j / p.nsel));
+    }
+    for (int j = tid + 4 * NT; j < n_entries; j += NT)
+      atomicOr(&hm[min(max(selu[j], 0), p.B - 1)], 1 << (j / p.nsel));
+    if (tid == 0 && p.resident >= 0) atomicOr(&hm[p.resident], (1 << G) - 1);
+    __syncthreads();
+    int cnt = 0, mine = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+      if (k < perb && bb0 + k < p.B && hm[bb0 + k] != 0) {
+        ++cnt;
+        mine += lv[k];
+      }
+    const unsigned incl_c = wave_prefix_sum((unsigned)cnt), incl_k = wave_prefix_sum((unsigned)mine);
+    __shared__ int s_csum[16];
+    if (lane == 63) {
+      s_csum[wave] = (int)incl_c;
+      s_wsum[wave] = (int)incl_k;
+    }
+    __syncthreads();
+    int j = (int)incl_c - cnt, run = (int)incl_k - mine, total_c = 0;
+    for (int w = 0; w < nw; ++w) {
+      if (w < wave) {
+        j += s_csum[w];
+        run += s_wsum[w];
+      }
+      total_c += s_csum[w];
+    }
+    nseg = total_c;
+    if (tid == 0) pre[0] = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+      if (k < perb && bb0 + k < p.B && hm[bb0 + k] != 0) {
+        run += lv[k];
+        pre[j + 1] = run;
+        rowoff[j] = ov[k];
+        segm[j] = hm[bb0 + k];
+        ++j;
+      }
+    __syncthreads();
+    T_total = pre[nseg];
+  } else if (LIST) {
     const int per = (nseg + NT - 1) / NT;
     const int j0 = tid * per, j1 = min(j0 + per, nseg);
     const int32_t* lenu = p.len + (size_t)kvu * p.B;
@@ -265,6 +337,10 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     if (nseg == 0 && tid == 0) pre[0] = 0;
     __syncthreads();
     T_total = pre[nseg];
+  } else {
+    T_total = p.n_dense;
+  }
+  if (LIST) {
     // runs that hold the first and the last key of each of this workgroup's chunks, so that the
     // per-key lookups in the loop search a handful of runs instead of all of them
     for (int k = tid; p.use_table; k += NT) {
@@ -282,8 +358,6 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
       seghi[k] = a1;
     }
     if (p.use_table) __syncthreads();
-  } else {
-    T_total = p.n_dense;
   }
   SAAP_TRACE(1);
 
@@ -301,13 +375,13 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   const long long stride = (long long)chunk * p.P;
 
   auto load_batch = [&](long long base, int k, Batch<T, KB>& bt) {
-    int row;
+    int row, hmask = 0;
     {
       long long vl = base + (sub & (KB - 1)) * NG + kp;   // lane `sub` resolves slot sub % KB
       int v = (int)(vl < T_total ? vl : T_total - 1);
       if (LIST) {
         const bool tab = p.use_table && k < p.max_chunks;
-        int a = tab ? seglo[k] : 0, b = tab ? seghi[k] + 1 : p.nseg;
+        int a = tab ? seglo[k] : 0, b = tab ? seghi[k] + 1 : nseg;
         while (b - a > 1) {
           const int mid = (a + b) >> 1;
           if (pre[mid] <= v) a = mid; else b = mid;
@@ -316,14 +390,17 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
         // a list that breaks the contract (repeated or overlapping runs, a damaged index) must
         // not turn into a read outside the cache
         row = min(max(row, 0), (int)p.rows - 1);
+        if constexpr (MASKED) hmask = segm[a];
       } else {
         row = v;
       }
     }
     bt.valid = 0u;
+    bt.heads = 0u;
 #pragma unroll
     for (int i = 0; i < KB; ++i) {
       const int r = __shfl(row, (lane & 48) + i);
+      if constexpr (MASKED) bt.heads |= (unsigned)__shfl(hmask, (lane & 48) + i) << (8 * i);
       if (base + i * NG + kp < T_total) bt.valid |= 1u << i;
       bt.k[i].load(Kb + (size_t)r * kD);
       bt.v[i].load(Vb + (size_t)r * kD);
@@ -339,7 +416,9 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
       for (int g = 0; g < G; ++g) d[i * G + g] = bt.k[i].dot(qv[g]);
     // ... reduced over the 16 lanes so that each lane ends up with ONE complete score
     const float dot = reduce_scatter16<C>(d, sub);
-    const float t = (bt.valid >> i_own) & 1u ? dot * p.scale_log2 : -INFINITY;
+    bool live = (bt.valid >> i_own) & 1u;
+    if constexpr (MASKED) live = live && ((bt.heads >> (8 * i_own + c_own % G)) & 1u);
+    const float t = live ? dot * p.scale_log2 : -INFINITY;
     // Algorithm 1, one step per batch: the head's running maximum lives in the lanes that own it
     const float bm = ror_max<G, C>(t);
     const float mn = fmaxf(m, bm);
@@ -615,9 +694,9 @@ struct LaunchPlan {
 };
 
 LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, long long max_keys_per_unit, int G, int nseg,
-                       bool list, int B, bool has_selection) {
+                       bool list, int B, bool has_selection, bool masked = false) {
   int threads = env_int("SAAP_ATTN_THREADS", 0);
-  if (threads != 256 && threads != 512) threads = 512;
+  if ((threads != 256 && threads != 512) || masked) threads = 512;
   const int kb = G == 8 ? 2 : 4;
   const int wgs_per_cu = env_int("SAAP_ATTN_WGS_PER_CU", threads == 256 ? 2 : 1);
   const int cus = device_cus();
@@ -634,8 +713,9 @@ LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, long long max_k
   lp.threads = threads;
   lp.max_chunks = (int)(((max_keys_per_unit + chunk - 1) / chunk + P - 1) / P + 1);
   size_t a = list ? (size_t)(2 * nseg + 1 + 2 * lp.max_chunks) * sizeof(int) : 0;
-  lp.stage = list && has_selection && nseg <= 2 * threads && B <= 8 * threads && env_int("SAAP_ATTN_STAGE", 1);
+  lp.stage = !masked && list && has_selection && nseg <= 2 * threads && B <= 8 * threads && env_int("SAAP_ATTN_STAGE", 1);
   if (lp.stage) a += (size_t)2 * B * sizeof(int);
+  if (masked) a += (size_t)(nseg + B) * sizeof(int);     // heads per run, heads per bucket
   const size_t b = (size_t)(threads / 64) * G * (kD + 2) * sizeof(float) + G * sizeof(float);
   const size_t c = (size_t)(P * G + 2 * G + 4) * sizeof(float) + (size_t)threads * sizeof(float4);
   lp.lds = a > b ? a : b;
@@ -643,9 +723,9 @@ LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, long long max_k
   return lp;
 }
 
-template <typename T, int G, bool LIST, int NT>
+template <typename T, int G, bool LIST, int NT, bool MASKED = false>
 int32_t launch_nt(const AttnParams& p, const LaunchPlan& lp, hipStream_t stream) {
-  auto kern = attn_kernel<T, G, LIST, NT>;
+  auto kern = attn_kernel<T, G, LIST, NT, MASKED>;
   if (lp.lds > 48 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lp.lds) != hipSuccess)
@@ -659,6 +739,26 @@ int32_t launch_nt(const AttnParams& p, const LaunchPlan& lp, hipStream_t stream)
 template <typename T, int G, bool LIST>
 int32_t launch_one(const AttnParams& p, const LaunchPlan& lp, hipStream_t stream) {
   return lp.threads == 256 ? launch_nt<T, G, LIST, 256>(p, lp, stream) : launch_nt<T, G, LIST, 512>(p, lp, stream);
+}
+
+// Independent routing with G > 1 heads per KV head: the masked kernels, 512 threads only.
+int32_t launch_masked(const AttnParams& p, const LaunchPlan& lp, int G, int dtype, hipStream_t stream) {
+#define SAAP_CASE(TT, GG) return launch_nt<TT, GG, true, 512, true>(p, lp, stream)
+  if (dtype == SAAP_BF16) {
+    switch (G) {
+      case 2: SAAP_CASE(bf16_t, 2);
+      case 4: SAAP_CASE(bf16_t, 4);
+      case 8: SAAP_CASE(bf16_t, 8);
+    }
+  } else {
+    switch (G) {
+      case 2: SAAP_CASE(float, 2);
+      case 4: SAAP_CASE(float, 4);
+      case 8: SAAP_CASE(float, 8);
+    }
+  }
+#undef SAAP_CASE
+  return SAAP_UNSUPPORTED;
 }
 
 template <bool LIST>
@@ -719,12 +819,21 @@ static int32_t sparse_attention(const void* q, const void* Ksorted, const void* 
   if (!off || !len || (nprobe > 0 && !selected)) return SAAP_INVALID_ARG;
   if (mode != SAAP_GROUP_SUM && mode != SAAP_INDEPENDENT) return SAAP_INVALID_ARG;
   if (B <= 0 || Ncap <= 0 || nprobe < 0 || resident_run < -1 || resident_run >= B) return SAAP_INVALID_ARG;
-  const int nseg = nprobe + (resident_run >= 0 ? 1 : 0);
+  int nseg = nprobe + (resident_run >= 0 ? 1 : 0);
   if (nseg > B) return SAAP_INVALID_ARG;
   if (nseg > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
   const bool indep = mode == SAAP_INDEPENDENT;
-  const int G = indep ? 1 : Hq / Hkv;
-  const long long units = indep ? (long long)S * Hq : (long long)S * Hkv;
+  // Independent routing of G > 1 heads that share a KV head: one unit per KV head visits the union
+  // of the heads' lists once, each head attending only its own runs (masked kernels).  They hold
+  // 16 buckets per thread at most; beyond that every head is a unit of its own.
+  const int heads = Hq / Hkv;
+  const bool masked = indep && heads > 1 && B <= 16 * 512;
+  const int G = masked ? heads : indep ? 1 : heads;
+  const long long units = indep && !masked ? (long long)S * Hq : (long long)S * Hkv;
+  if (masked) {
+    const long long cap = (long long)heads * nprobe + (resident_run >= 0 ? 1 : 0);
+    nseg = (int)(cap < B ? cap : B);
+  }
   if (units * sizeof(unsigned long long) > SAAP_WS_HEADER_BYTES) return SAAP_UNSUPPORTED;
   if (ws_bytes < attn_workspace_bytes(units, G)) return SAAP_WORKSPACE_TOO_SMALL;
 
@@ -735,15 +844,17 @@ static int32_t sparse_attention(const void* q, const void* Ksorted, const void* 
   p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   p.part_o = p.part_ml + (size_t)units * kMaxP * G * 2;
   p.rows = Ncap; p.nsel = nprobe; p.resident = resident_run; p.nseg = nseg; p.B = B; p.n_units = (int)units;
-  p.Hq = Hq; p.Hkv = Hkv; p.independent = indep ? 1 : 0; p.out_bf16 = out_dtype == SAAP_BF16;
+  p.Hq = Hq; p.Hkv = Hkv; p.independent = indep && !masked ? 1 : 0; p.masked_lists = masked ? heads : 0;
+  p.out_bf16 = out_dtype == SAAP_BF16;
   p.n_dense = 0; p.scale_log2 = scale * kLog2e;
   // expected keys per unit: balanced buckets, plus the paper's default window for the resident run
-  const long long est = (long long)Ncap * nprobe / B + (resident_run >= 0 ? 2048 : 0);
-  LaunchPlan lp = plan_launch((int)units, est, Ncap, G, nseg, true, B, nseg > 0);
+  const long long est = (long long)Ncap * (masked ? nseg : nprobe) / B + (resident_run >= 0 ? 2048 : 0);
+  LaunchPlan lp = plan_launch((int)units, est, Ncap, G, nseg, true, B, nseg > 0, masked);
   p.P = lp.P;
   p.stage = lp.stage;
   p.max_chunks = lp.max_chunks;
   p.use_table = (est + (long long)lp.P * (lp.threads / 16 * (G == 8 ? 2 : 4)) - 1) / ((long long)lp.P * (lp.threads / 16 * (G == 8 ? 2 : 4))) > 2;
+  if (masked) return launch_masked(p, lp, G, dtype, static_cast<hipStream_t>(stream));
   return launch_attn<true>(p, lp, G, dtype, static_cast<hipStream_t>(stream));
 }
 

@@ -243,6 +243,40 @@ def test_sparse_independent_mode(saap):
     assert_close(lse.cpu().numpy(), rl, "bf16", "independent lse")
 
 
+@pytest.mark.parametrize("dtype,S,Hq,Hkv,N,B,nprobe,kind", [
+    ("bf16", 1, 32, 8, 30000, 256, 13, "random"), ("bf16", 2, 4, 2, 5000, 64, 6, "same"), ("f32", 1, 8, 1, 3000, 48, 5, "disjoint"),
+    ("bf16", 1, 8, 2, 6000, 128, 128, "all"), ("bf16", 1, 4, 1, 2500, 48, 0, "random"), ("bf16", 3, 4, 2, 700, 8192, 20, "random"),
+])
+def test_independent_lists_share_one_pass_over_the_union(saap, dtype, S, Hq, Hkv, N, B, nprobe, kind):
+    """Independent routing with several heads per KV head: lists that overlap, coincide, are disjoint or hold
+    every bucket; each head must see exactly the keys of its own list (oracle: per-head restricted softmax)."""
+    cfg = small("cfg1_llama8b_128k", S=S, Hq=Hq, Hkv=Hkv, N=N, B=B, nprobe=max(nprobe, 1), dtype=dtype, hidden=64)
+    cache = gen.make_cache(cfg, 71, DEV)
+    cent = gen.make_centroids(cfg, 71, DEV, cache, n_train=max(2048, B))
+    _, q = gen.make_queries(cfg, 71, DEV)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], B, 0)
+    rng = np.random.default_rng(B + nprobe)
+    G = Hq // Hkv
+    sel = np.zeros((S, Hq, nprobe), dtype=np.int32)
+    for s in range(S):
+        for hq in range(Hq):
+            if kind == "random":
+                sel[s, hq] = rng.permutation(B)[:nprobe]
+            elif kind == "same":
+                sel[s, hq] = (np.arange(nprobe) * 7 + 3 * (hq // G)) % B
+            elif kind == "disjoint":
+                sel[s, hq] = (hq % G) * nprobe + np.arange(nprobe)
+            else:
+                sel[s, hq] = rng.permutation(B)
+    out, lse = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln, torch.from_numpy(sel).to(DEV), SCALE, mode=saap.INDEPENDENT)
+    torch.cuda.synchronize()
+    ro, rl = ref.sparse_decode_attention(h(q[0]), h(cache["K"]), h(cache["V"]), off.cpu().numpy(), ln.cpu().numpy(),
+                                         idx.cpu().numpy(), sel, SCALE, mode=1)
+    assert_close(out.cpu().numpy(), ro, dtype, "independent out")
+    assert_close(lse.cpu().numpy(), rl, dtype, "independent lse")
+
+
 def test_attention_is_deterministic_and_workspace_stays_clean(saap):
     cfg = small("cfg1_llama8b_128k", S=1, Hq=8, Hkv=2, N=20000, B=128, nprobe=16, hidden=64)
     cache, cent, xq, q, W = make_inputs(cfg, 17)
