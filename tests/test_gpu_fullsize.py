@@ -215,3 +215,48 @@ def test_cfg4_one_layer_262k(saap):
     rd, rdl = ref.dense_decode_attention(h(q[0]), hK, hV, SCALE)
     close(o_d.cpu().numpy(), rd)
     close(l_d.cpu().numpy(), rdl)
+
+
+def test_cfg1_with_the_papers_window_and_fused_selection(saap):
+    """The benchmark workload with the paper's 1+2047 dense block (Section 3 "Per-head attention span"): index
+    with a resident run, the decode step bench.py times (logits -> fused selection -> windowed attention ->
+    push), three steps, every output against the oracle; the oracle's attention is the position-based definition."""
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"]
+    n_sink, n_recent, slack, steps = 1, 2047, 8, 3
+    N = cfg.N - steps
+    cache = gen.make_cache(cfg, 2, DEV)
+    cent = gen.make_centroids(cfg, 2, DEV)
+    xq, q = gen.make_queries(cfg, 2, DEV, n_steps=steps)
+    W1, b1, W2, b2 = gen.make_classifier(cfg, 2, DEV)
+    x, K, V = cache["x_keys"], cache["K"], cache["V"]
+    ids_all = saap.assign_keys(x, cent)
+    state = saap.build_windowed_index(ids_all[:, :, :N].contiguous(), K[:, :, :N].contiguous(), V[:, :, :N].contiguous(),
+                                      cfg.B, slack, n_sink, n_recent)
+    off, ln, idx, Ks, Vs, res = state
+    torch.cuda.synchronize()
+    hK, hV, h_ids = h(K), h(V), ids_all.cpu().numpy()
+    assert np.array_equal(h_ids, ref.assign_keys(h(x), h(cent)))
+    want = ref.build_windowed_index(h_ids[:, :, :N], hK[:, :, :N], hV[:, :, :N], cfg.B, slack, n_sink, n_recent)
+    for g, w in zip((off, ln, idx, res), (want[0], want[1], want[2], want[5])):
+        assert np.array_equal(g.cpu().numpy(), w)
+    flag = torch.zeros(4, dtype=torch.int32, device=DEV)
+    for t in range(steps):
+        logits = saap.classify_queries(xq[t], W1, b1, W2, b2, cfg.Hkv, output_kind=saap.LOGITS)
+        probs = torch.empty_like(logits)
+        sel = saap.select_buckets_from_logits(logits, cfg.Hkv, cfg.nprobe, probs=probs)
+        out, lse = saap.windowed_decode_attention(q[t], Ks, Vs, off, ln, sel, cfg.B, SCALE)
+        torch.cuda.synchronize()
+        r_sel = ref.select_buckets(probs.cpu().numpy(), cfg.Hkv, cfg.nprobe)
+        assert np.array_equal(sel.cpu().numpy(), r_sel)
+        Nt = N + t
+        ro, rl = ref.windowed_decode_attention(h(q[t]), hK[:, :, :Nt], hV[:, :, :Nt], h_ids[:, :, :Nt], r_sel, n_sink, n_recent,
+                                               SCALE, cfg.B)
+        close(out.cpu().numpy(), ro)
+        close(lse.cpu().numpy(), rl)
+        pos = torch.full((cfg.S,), Nt, dtype=torch.int32, device=DEV)
+        nid, _ = saap.window_push(x[:, :, Nt].contiguous(), K[:, :, Nt].contiguous(), V[:, :, Nt].contiguous(), pos, cent, None,
+                                  off, ln, idx, Ks, Vs, res, n_sink, n_recent, overflow_flag=flag)
+        torch.cuda.synchronize()
+        assert np.array_equal(nid.cpu().numpy(), h_ids[:, :, Nt])
+    assert flag[0].item() == 0
+    assert int(ln.sum().item()) == cfg.S * cfg.Hkv * (N + steps)
