@@ -18,6 +18,14 @@ namespace saap {
 namespace {
 
 constexpr int kRankSortMax = 1024;   // selected lists up to this length are ordered by counting larger keys
+constexpr int kBucketRankMin = 384;  // ... candidate lists longer than this by bucketing first (measured break-even)
+
+// Words of the tie bitmap in LDS: one bit per bucket, at least 256 words (the region doubles as the
+// bucket offsets of the bucketed ranking) and an even count (what follows holds 8-byte entries).
+__host__ __device__ constexpr int bitmap_words(int B) {
+  const int w = B / 32 + 1 < 256 ? 256 : B / 32 + 1;
+  return (w + 1) & ~1;
+}
 
 // Sum of the heads' scores of bucket b, in fp32 in head order.  All loads go out before the
 // first add (heads <= 8).
@@ -322,13 +330,69 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
   }
   SAAP_TRACE(3);
   int32_t* out = selected + (size_t)unit * nprobe;
+  if (n_sort <= kRankSortMax && n_cand > kBucketRankMin) {
+    // Long candidate lists: counting every larger key costs n^2 comparisons on one compute unit.
+    // Instead the candidates are dealt into 256 buckets by the leading bits of (score image - lowest
+    // image), largest first; the place of a key is the number of keys in earlier buckets plus the
+    // number of larger keys in its own bucket (a handful).
+    unsigned long long* tmp = reinterpret_cast<unsigned long long*>(eqbits + bitmap_words(B) + cap);   // [cap]
+    unsigned* cnt = s_hist[0];
+    unsigned* fill = s_hist[1];
+    if (tid == 0) { s_and = 0xFFFFFFFFu; s_or = 0u; }            // lowest / highest score image
+    for (int i = tid; i < 256; i += nt) { cnt[i] = 0u; fill[i] = 0u; }
+    __syncthreads();
+    {
+      unsigned lo = 0xFFFFFFFFu, hi = 0u;
+      for (int i = tid; i < n_cand; i += nt) {
+        const unsigned k32 = (unsigned)(sortbuf[i] >> 32);
+        lo = min(lo, k32);
+        hi = max(hi, k32);
+      }
+      if (lo <= hi) { atomicMin(&s_and, lo); atomicMax(&s_or, hi); }
+    }
+    __syncthreads();
+    const unsigned lo32 = s_and, span = s_or - s_and;
+    const int bshift = span < 256u ? 0 : (32 - __clz(span)) - 8;
+    auto bucket_of = [&](unsigned long long key) { return 255 - (int)(((unsigned)(key >> 32) - lo32) >> bshift); };
+    for (int i = tid; i < n_cand; i += nt) atomicAdd(&cnt[bucket_of(sortbuf[i])], 1u);
+    __syncthreads();
+    unsigned* bbase = eqbits;                                    // [256] first place of each bucket (the bitmap is dead)
+    if (wave == 0) {
+      const unsigned c[4] = {cnt[4 * lane], cnt[4 * lane + 1], cnt[4 * lane + 2], cnt[4 * lane + 3]};
+      const unsigned tot = c[0] + c[1] + c[2] + c[3];
+      unsigned cum = wave_prefix_sum(tot) - tot;
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        bbase[4 * lane + b] = cum;
+        cum += c[b];
+      }
+    }
+    __syncthreads();
+    for (int i = tid; i < n_cand; i += nt) {
+      const unsigned long long key = sortbuf[i];
+      const int bk = bucket_of(key);
+      tmp[bbase[bk] + atomicAdd(&fill[bk], 1u)] = key;
+    }
+    __syncthreads();
+    for (int i = tid; i < n_cand; i += nt) {
+      const unsigned long long mine = tmp[i];
+      const int bk = bucket_of(mine);
+      const unsigned first = bbase[bk], n = cnt[bk];
+      unsigned place = first;
+      for (unsigned j = first; j < first + n; ++j) place += tmp[j] > mine ? 1u : 0u;
+      if (place < (unsigned)nprobe) out[place] = (int32_t)(0xFFFFFFFFu - (unsigned)(mine & 0xFFFFFFFFull));
+    }
+    SAAP_TRACE(4);
+    return;
+  }
   if (n_sort <= kRankSortMax) {
     // keys are distinct: the place of a key is the number of larger keys.  The comparisons of one
     // key are split over several threads: work item (key i, part) counts the larger keys in its
     // slice and adds the count to rank[i]
-    unsigned* rank = eqbits + (B / 32 + 1);            // [cap], zeroed below
+    unsigned* rank = eqbits + bitmap_words(B);         // [cap], zeroed below
     for (int i = tid; i < n_cand; i += nt) rank[i] = 0u;
     __syncthreads();
+    if (tid == 0) SAAP_TRACE_VALUE(6, n_cand);
     const int parts = nt >= 2 * n_cand ? nt / n_cand : 1;
     const int slice = (n_cand + parts - 1) / parts;
     for (int w = tid; w < n_cand * parts; w += nt) {
@@ -343,6 +407,7 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
     __syncthreads();
     for (int i = tid; i < n_cand; i += nt)
       if (rank[i] < (unsigned)nprobe) out[rank[i]] = (int32_t)(0xFFFFFFFFu - (unsigned)(sortbuf[i] & 0xFFFFFFFFull));
+    SAAP_TRACE(4);
     return;
   }
   for (int k = 2; k <= n_sort; k <<= 1) {
@@ -406,8 +471,9 @@ static int32_t select_impl(const float* scores, bool logits, float* probs, int32
     // grows with the square of their number, another radix pass costs less than that for long
     // lists), the padded list itself where a bitonic network does the ordering
     const int cap = n_sort <= kRankSortMax ? (n_sort <= 128 ? 2 * n_sort : n_sort + 128) : n_sort;
-    const size_t lds = (size_t)cap * sizeof(unsigned long long) + (size_t)(B / 32 + 1) * sizeof(unsigned) +
-                       (n_sort <= kRankSortMax ? (size_t)cap * sizeof(unsigned) : 0);
+    // sortbuf [cap] | bitmap [B/32 + 1, padded to 256 words and to an even count] | rank [cap] | bucketed copy [cap]
+    const size_t lds = (size_t)cap * sizeof(unsigned long long) + (size_t)bitmap_words(B) * sizeof(unsigned) +
+                       (n_sort <= kRankSortMax ? (size_t)cap * (sizeof(unsigned) + sizeof(unsigned long long)) : 0);
     saap_trace_arm();
     const dim3 grid((unsigned)units), block((unsigned)threads);
 #define SAAP_SELECT_CASE(E)                                                                                  \
