@@ -465,6 +465,9 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
         for (base += stride, ++k; base < T_total; base += stride, ++k) {
           Batch<T, KB> nxt;
           load_batch(base, k, nxt);     // in flight while the current batch is consumed
+          // keep it that way: without the fence the scheduler starts on the current batch (and its
+          // wait for memory) before the next batch's loads have been issued
+          __builtin_amdgcn_sched_barrier(0);
           consume(cur);
           cur = nxt;
         }
