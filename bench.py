@@ -38,7 +38,10 @@ def parse():
     ap.add_argument("--query-sets", type=int, default=64)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg (0 = skip)")
-    ap.add_argument("--slack", type=int, default=0)
+    ap.add_argument("--slack", type=int, default=-1, help="free slots behind every bucket (default: 0, or 64 when the step appends)")
+    ap.add_argument("--append", choices=["auto", "on", "off"], default="auto",
+                    help="the step also stores the token's new key in its bucket (append_keys); "
+                         "auto: on for the batched-decode workload, whose definition includes it")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense baseline (keeps profiler summaries to the sparse path)")
     ap.add_argument("--window", default="", help="also time the step with an attention sink + recent-key window, "
                     "e.g. 1+2047 (the paper's default): adds a `window` object to the output")
@@ -125,6 +128,9 @@ def main():
         cfg = cfg.replace(nprobe=args.nprobe)
     scale = 1.0 / math.sqrt(cfg.d)
     T = args.query_sets
+    with_append = args.append == "on" or (args.append == "auto" and cfg.name == "cfg3_batch8_128k")
+    if args.slack < 0:
+        args.slack = 64 if with_append else 0
 
     # ---------------------------------------------------------------- inputs (synthetic, seeded)
     cache = gen.make_cache(cfg, args.seed, dev)
@@ -173,10 +179,25 @@ def main():
     def attend(i):
         saap.sparse_decode_attention(q[i % T], Ks, Vs, off, ln, sel, scale, out=out, lse=lse)
 
+    if with_append:
+        # the T tokens whose keys get appended, drawn like the cache; replays append the same T keys
+        # again, the copies pile up in the slack (64 slots per bucket hold the whole run)
+        new = gen.make_cache(cfg.replace(N=T), args.seed, dev)
+        a_x, a_k, a_v = (new[k].permute(2, 0, 1, 3).contiguous() for k in ("x_keys", "K", "V"))   # [T,S,Hkv,d]
+        a_pos = (cfg.N + torch.arange(T, dtype=torch.int32, device=dev)).repeat_interleave(cfg.S).reshape(T, cfg.S).contiguous()
+        a_flag = torch.zeros(4, dtype=torch.int32, device=dev)
+        a_ids = torch.empty(cfg.S, cfg.Hkv, dtype=torch.int32, device=dev)
+
+    def append(i):
+        saap.append_keys(a_x[i % T], a_k[i % T], a_v[i % T], a_pos[i % T], cent, None, off, ln, idx, Ks, Vs,
+                         overflow_flag=a_flag, new_ids=a_ids)
+
     def step(i):
         classify(i)
         select(i)
         attend(i)
+        if with_append:
+            append(i)
 
     # selections of every query set (for the byte accounting and the per-kernel loops)
     for t in range(T):
@@ -218,6 +239,7 @@ def main():
     spread = np.percentile(np.array(g_attn.replay_ms_per_call(max(reps, 20))) * 1e3, [10, 50, 90])
     ms_classify = GraphLoop(classify, T, torch).timed_ms_per_call(reps)
     ms_select = GraphLoop(select, T, torch).timed_ms_per_call(reps)
+    ms_append = GraphLoop(append, T, torch).timed_ms_per_call(2) if with_append else None
     ms_dense = None if args.no_dense else GraphLoop(dense, 8, torch).timed_ms_per_call(3)
     achieved = bytes_step / (ms_attn * 1e-3) / 1e9
     # streaming-read ceiling of this device: plain 16-byte loads over the whole sorted cache
@@ -299,7 +321,9 @@ def main():
         "config": {
             "workload": cfg.name, "S": cfg.S, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "d": cfg.d, "N": cfg.N, "B": cfg.B,
             "nprobe": cfg.nprobe, "classifier": f"{cfg.d}->{cfg.hidden}->{cfg.B}", "query_sets": T,
-            "step": "classify_queries (logits) + select_buckets_from_logits + sparse_decode_attention", "launch": "hip graph",
+            "step": "classify_queries (logits) + select_buckets_from_logits + sparse_decode_attention"
+                    + (" + append_keys" if with_append else ""),
+            "slack": args.slack, "launch": "hip graph",
         },
         "roofline": {
             "kernel": "attn_kernel<bf16,G=4,list> (sparse_decode_attention, partials + merge)",
@@ -320,6 +344,7 @@ def main():
             "select_buckets_from_logits": round(ms_select * 1e3, 3),
             "sparse_decode_attention": round(ms_attn * 1e3, 3),
             "dense_decode_attention": None if ms_dense is None else round(ms_dense * 1e3, 3),
+            "append_keys": None if ms_append is None else round(ms_append * 1e3, 3),
         },
         "dense": None if ms_dense is None else {
             "us": round(ms_dense * 1e3, 3),
@@ -338,6 +363,8 @@ def main():
     }
     if window_result:
         result["window"] = window_result
+    if with_append:
+        result["append_overflow_flag"] = int(a_flag[0].item())
 
     if args.calibrate_copy:
         # a plain copy of known size: the profiler's FETCH_SIZE / WRITE_SIZE for it give the

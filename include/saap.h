@@ -161,10 +161,12 @@ int32_t saap_build_bucket_index(const int32_t* bucket_ids, const void* K, const 
  * The paper needs the index to absorb keys during generation (Section 1) and
  * gives no mechanism; this layout uses the slack slots of build_bucket_index.
  *   x_new [S,Hkv,d] features; k_new, v_new [S,Hkv,d] cache rows (dtype)
- *   pos_new [S] int32 or NULL: position recorded in idx (NULL records -2)
+ *   pos_new [S] int32 (>= 0) or NULL: position recorded in idx (NULL records -2)
  *   new_bucket_ids [S,Hkv] int32, out
  *   overflow_flag  device int32: set to 1 if some bucket had no free slot;
  *                  that key is not stored (len unchanged), others are.
+ * Workspace: SAAP_OP_APPEND_KEYS (S, Hkv, B): the centroids are scored by ceil(B/64)
+ * workgroups per (sequence, head), which meet through it.
  */
 int32_t saap_append_keys(const void* x_new, const void* k_new, const void* v_new,
                          const int32_t* pos_new,
@@ -173,7 +175,7 @@ int32_t saap_append_keys(const void* x_new, const void* k_new, const void* v_new
                          void* Ksorted, void* Vsorted,
                          int32_t* new_bucket_ids, int32_t* overflow_flag,
                          int32_t S, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype,
-                         void* stream);
+                         void* ws, size_t ws_bytes, void* stream);
 
 /*
  * classify_queries -- the query assignment model f_q of Section 4 (a two-layer

@@ -173,19 +173,22 @@ def build_bucket_index(bucket_ids, K, V, B, slack=0, ws=None):
     return off, ln, idx, Ks, Vs
 
 
-def append_keys(x_new, k_new, v_new, pos_new, centroids, bias, off, ln, idx, Ks, Vs, overflow_flag=None):
+def append_keys(x_new, k_new, v_new, pos_new, centroids, bias, off, ln, idx, Ks, Vs, overflow_flag=None, new_ids=None,
+                ws=None):
     """In-place append of one key per (sequence, KV head). -> (new_bucket_ids [S,Hkv], overflow_flag [1])."""
     S, Hkv, d = x_new.shape
     B = centroids.shape[1]
     Ncap = idx.shape[2]
     dev = x_new.device
-    new_ids = torch.empty(S, Hkv, dtype=torch.int32, device=dev)
+    if new_ids is None:
+        new_ids = torch.empty(S, Hkv, dtype=torch.int32, device=dev)
     if overflow_flag is None:
         overflow_flag = torch.zeros(4, dtype=torch.int32, device=dev)
+    ws, wsb = _ws(OP_APPEND_KEYS, dev, ws, S=S, Hkv=Hkv, B=B)
     st = load_library().saap_append_keys(_ptr(x_new), _ptr(k_new), _ptr(v_new), _ptr(pos_new), _ptr(centroids),
                                          _ptr(bias), _ptr(off), _ptr(ln), _ptr(idx), _ptr(Ks), _ptr(Vs),
                                          _ptr(new_ids), _ptr(overflow_flag), _i32(S), _i32(Hkv), _i32(Ncap), _i32(B),
-                                         _i32(d), _i32(_dtype_code(x_new)), _stream())
+                                         _i32(d), _i32(_dtype_code(x_new)), _ptr(ws), wsb, _stream())
     _check("saap_append_keys", st)
     return new_ids, overflow_flag
 

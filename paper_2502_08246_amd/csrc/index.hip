@@ -214,7 +214,6 @@ template <> __device__ __forceinline__ double to_f64<bf16_t>(bf16_t v) {
   return (double)__uint_as_float((uint32_t)v << 16);
 }
 
-constexpr int kScoreThreads = 256;    // workgroup size of append_kernel
 constexpr int kPushSlab = 64;         // centroids per workgroup (one wave) of window_push_kernel
 
 // Eight bf16 elements (one 16-byte piece of a row) -> double.
@@ -280,67 +279,6 @@ __device__ __forceinline__ void wave_best(double& best, int& best_id) {
   }
 }
 
-// One workgroup per (sequence, KV head): find the new key's bucket (argmax_b <x, c_b> + bias_b in
-// double precision, lowest id on ties: the definition saap_assign_keys states) and store the key
-// in the bucket's first free slot.
-template <typename T>
-__global__ void __launch_bounds__(kScoreThreads)
-append_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, const T* __restrict__ v_new,
-              const int32_t* __restrict__ pos_new, const T* __restrict__ cent, const float* __restrict__ bias,
-              const int32_t* __restrict__ off, int32_t* __restrict__ len, int32_t* __restrict__ idx,
-              T* __restrict__ Ks, T* __restrict__ Vs, int32_t* __restrict__ new_ids,
-              int32_t* __restrict__ overflow, int Hkv, int Ncap, int B) {
-  __shared__ double s_x[kD];
-  __shared__ double s_best[kScoreThreads / 64];
-  __shared__ int s_id[kScoreThreads / 64];
-  __shared__ int s_slot;
-  const int unit = blockIdx.x, h = unit % Hkv, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // the row to store does not depend on the bucket: fetch it while the scores are computed
-  T kx = T(), vx = T();
-  if (tid < kD) {
-    kx = k_new[(size_t)unit * kD + tid];
-    vx = v_new[(size_t)unit * kD + tid];
-    s_x[tid] = to_f64<T>(x_new[(size_t)unit * kD + tid]);
-  }
-  __syncthreads();
-  double best = 0.0;
-  int best_id = -1;
-  for (int b = tid; b < B; b += kScoreThreads) {      // ascending b per thread
-    double t = score_row<T>(cent + ((size_t)h * B + b) * kD, s_x);
-    if (bias) t += (double)bias[(size_t)h * B + b];
-    take_better(best, best_id, t, b);
-  }
-  wave_best(best, best_id);
-  if (lane == 0) {
-    s_best[wave] = best;
-    s_id[wave] = best_id;
-  }
-  __syncthreads();
-  if (tid == 0) {
-#pragma unroll
-    for (int w = 1; w < kScoreThreads / 64; ++w) take_better(best, best_id, s_best[w], s_id[w]);
-    const int b = best_id;
-    new_ids[unit] = b;
-    const int32_t* o = off + (size_t)unit * (B + 1);
-    const int cur = len[(size_t)unit * B + b];
-    int slot = -1;
-    if (o[b] + cur < o[b + 1]) {
-      slot = o[b] + cur;
-      len[(size_t)unit * B + b] = cur + 1;
-      idx[(size_t)unit * Ncap + slot] = pos_new ? pos_new[unit / Hkv] : -2;
-    } else {
-      *overflow = 1;
-    }
-    s_slot = slot;
-  }
-  __syncthreads();
-  const int slot = s_slot;
-  if (slot >= 0 && tid < kD) {
-    Ks[((size_t)unit * Ncap + slot) * kD + tid] = kx;
-    Vs[((size_t)unit * Ncap + slot) * kD + tid] = vx;
-  }
-}
-
 // Best candidate of one slab of centroids, as exchanged between the workgroups of a unit.
 struct PushPartial {
   double score;
@@ -361,12 +299,15 @@ window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, con
                    const int32_t* __restrict__ off, int32_t* __restrict__ len, int32_t* __restrict__ idx,
                    T* __restrict__ Ks, T* __restrict__ Vs, int32_t* __restrict__ res_ids,
                    int32_t* __restrict__ new_ids, int32_t* __restrict__ overflow, PushPartial* __restrict__ part,
-                   unsigned* __restrict__ counters, int Hkv, int Ncap, int B, int n_sink, int n_recent, int P) {
+                   unsigned* __restrict__ counters, int Hkv, int Ncap, int B, int runs, int n_sink, int n_recent,
+                   int P, int cpl /* centroids per lane: a workgroup scores 64 * cpl */) {
+  // runs = B + 1: index with a resident run.  runs = B: plain index (append_keys): W = 0, every key
+  // goes straight into its bucket, res_ids is not touched and pos_new may be null (idx gets -2).
   __shared__ double s_x[kD];
   const int slab = blockIdx.x, unit = blockIdx.y, h = unit % Hkv, lane = threadIdx.x;
   const int W = n_sink + n_recent;
-  const int32_t* o = off + (size_t)unit * (B + 2);
-  int32_t* l = len + (size_t)unit * (B + 1);
+  const int32_t* o = off + (size_t)unit * (runs + 1);
+  int32_t* l = len + (size_t)unit * runs;
   int32_t* ix = idx + (size_t)unit * Ncap;
   int32_t* rid = res_ids + (size_t)unit * W;
   T* Ku = Ks + (size_t)unit * Ncap * kD;
@@ -376,7 +317,7 @@ window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, con
   const T x0 = x_new[(size_t)unit * kD + lane], x1 = x_new[(size_t)unit * kD + 64 + lane];
   const T k0 = k_new[(size_t)unit * kD + lane], k1 = k_new[(size_t)unit * kD + 64 + lane];
   const T v0 = v_new[(size_t)unit * kD + lane], v1 = v_new[(size_t)unit * kD + 64 + lane];
-  const int pos = pos_new[unit / Hkv];
+  const int pos = pos_new ? pos_new[unit / Hkv] : 0x7fffffff;
   const int res_base = o[B];
   // -1: refused   0: slot of a run that is still filling   1: ring slot, a key is displaced   2: no ring
   const int kind = pos < 0 ? -1 : pos < W ? 0 : n_recent > 0 ? 1 : 2;
@@ -410,13 +351,15 @@ window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, con
   s_x[lane] = to_f64<T>(x0);
   s_x[64 + lane] = to_f64<T>(x1);
   __syncthreads();
-  const int bc = slab * kPushSlab + lane;
   double best = 0.0;
   int best_id = -1;
-  if (bc < B) {
-    best = score_row<T>(cent + ((size_t)h * B + bc) * kD, s_x);
-    if (bias) best += (double)bias[(size_t)h * B + bc];
-    best_id = bc;
+  for (int c = 0; c < cpl; ++c) {                // ascending ids per lane: ties keep the lowest
+    const int bc = (slab * cpl + c) * kPushSlab + lane;
+    if (bc < B) {
+      double t = score_row<T>(cent + ((size_t)h * B + bc) * kD, s_x);
+      if (bias) t += (double)bias[(size_t)h * B + bc];
+      take_better(best, best_id, t, bc);
+    }
   }
   wave_best(best, best_id);
   if (P > 1) {
@@ -464,7 +407,7 @@ window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, con
       } else {
         l[b] = cur + 1;
       }
-      ix[slot] = pos;
+      ix[slot] = pos_new ? pos : -2;
     }
   }
   if (!refused) {
@@ -536,8 +479,20 @@ recopy_kernel(const int32_t* __restrict__ off, const int32_t* __restrict__ len, 
 }  // namespace
 
 size_t push_workspace_bytes(long long units, int B) {
-  const long long P = (B + kPushSlab - 1) / kPushSlab;
+  const long long P = (B + kPushSlab - 1) / kPushSlab;       // the most workgroups per unit any plan uses
   return (size_t)SAAP_WS_HEADER_BYTES + (size_t)units * P * sizeof(PushPartial);
+}
+
+// Centroids per lane of the scoring workgroups: one when few units leave the device empty, more
+// when there are enough units to fill it anyway (about two workgroups per compute unit in all).
+static int push_centroids_per_lane(long long units, int B) {
+  const long long slabs = (B + kPushSlab - 1) / kPushSlab;
+  long long want = 2LL * device_cus() / units;                // workgroups per unit
+  if (want < 1) want = 1;
+  long long cpl = (slabs + want - 1) / want;
+  if (cpl < 1) cpl = 1;
+  if (cpl > 8) cpl = 8;
+  return (int)cpl;
 }
 
 size_t build_workspace_bytes(long long units, int N, int B) {
@@ -647,7 +602,8 @@ extern "C" int32_t saap_window_push(const void* x_new, const void* k_new, const 
   if (units > 65535 || units * sizeof(unsigned) > SAAP_WS_HEADER_BYTES) return SAAP_UNSUPPORTED;
   if (ws_bytes < push_workspace_bytes(units, B)) return SAAP_WORKSPACE_TOO_SMALL;
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  const int P = (B + kPushSlab - 1) / kPushSlab;
+  const int cpl = push_centroids_per_lane(units, B);
+  const int P = (B + kPushSlab * cpl - 1) / (kPushSlab * cpl);
   unsigned* counters = static_cast<unsigned*>(ws);
   PushPartial* part = reinterpret_cast<PushPartial*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   const dim3 grid((unsigned)P, (unsigned)units);
@@ -656,13 +612,13 @@ extern "C" int32_t saap_window_push(const void* x_new, const void* k_new, const 
                        static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new), pos_new,
                        static_cast<const bf16_t*>(centroids), bias, off, len, idx, static_cast<bf16_t*>(Ksorted),
                        static_cast<bf16_t*>(Vsorted), resident_ids, new_bucket_ids, overflow_flag, part, counters,
-                       Hkv, Ncap, B, n_sink, n_recent, P);
+                       Hkv, Ncap, B, B + 1, n_sink, n_recent, P, cpl);
   else
     hipLaunchKernelGGL(window_push_kernel<float>, grid, dim3(64), 0, hs, static_cast<const float*>(x_new),
                        static_cast<const float*>(k_new), static_cast<const float*>(v_new), pos_new,
                        static_cast<const float*>(centroids), bias, off, len, idx, static_cast<float*>(Ksorted),
                        static_cast<float*>(Vsorted), resident_ids, new_bucket_ids, overflow_flag, part, counters,
-                       Hkv, Ncap, B, n_sink, n_recent, P);
+                       Hkv, Ncap, B, B + 1, n_sink, n_recent, P, cpl);
   return launch_status();
 }
 
@@ -670,29 +626,38 @@ extern "C" int32_t saap_append_keys(const void* x_new, const void* k_new, const 
                                     const int32_t* pos_new, const void* centroids, const float* bias,
                                     const int32_t* off, int32_t* len, int32_t* idx, void* Ksorted,
                                     void* Vsorted, int32_t* new_bucket_ids, int32_t* overflow_flag, int32_t S,
-                                    int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype,
-                                    void* stream) {
+                                    int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype, void* ws,
+                                    size_t ws_bytes, void* stream) {
   if (!x_new || !k_new || !v_new || !centroids || !off || !len || !idx || !Ksorted || !Vsorted ||
-      !new_bucket_ids || !overflow_flag)
+      !new_bucket_ids || !overflow_flag || !ws)
     return SAAP_INVALID_ARG;
-  if (!aligned16(centroids)) return SAAP_INVALID_ARG;
+  if (!aligned16(centroids) || !aligned16(ws)) return SAAP_INVALID_ARG;
   if (S <= 0 || Hkv <= 0 || Ncap <= 0 || B <= 0) return SAAP_INVALID_ARG;
   if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
-  if (d != kD) return SAAP_UNSUPPORTED;
+  if (d != kD || B > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
+  const long long units = (long long)S * Hkv;
+  if (units > 65535 || units * sizeof(unsigned) > SAAP_WS_HEADER_BYTES) return SAAP_UNSUPPORTED;
+  if (ws_bytes < push_workspace_bytes(units, B)) return SAAP_WORKSPACE_TOO_SMALL;
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  const unsigned units = (unsigned)((long long)S * Hkv);
+  const int cpl = push_centroids_per_lane(units, B);
+  const int P = (B + kPushSlab * cpl - 1) / (kPushSlab * cpl);
+  unsigned* counters = static_cast<unsigned*>(ws);
+  PushPartial* part = reinterpret_cast<PushPartial*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
+  const dim3 grid((unsigned)P, (unsigned)units);
+  int32_t* no_resident = nullptr;
+  // the push kernel on a plain index: no resident run, the key goes straight into its bucket
   if (dtype == SAAP_BF16)
-    hipLaunchKernelGGL(append_kernel<bf16_t>, dim3(units), dim3(kScoreThreads), 0, hs,
-                       static_cast<const bf16_t*>(x_new), static_cast<const bf16_t*>(k_new),
-                       static_cast<const bf16_t*>(v_new), pos_new, static_cast<const bf16_t*>(centroids), bias,
-                       off, len, idx, static_cast<bf16_t*>(Ksorted), static_cast<bf16_t*>(Vsorted),
-                       new_bucket_ids, overflow_flag, Hkv, Ncap, B);
+    hipLaunchKernelGGL(window_push_kernel<bf16_t>, grid, dim3(64), 0, hs, static_cast<const bf16_t*>(x_new),
+                       static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new), pos_new,
+                       static_cast<const bf16_t*>(centroids), bias, off, len, idx, static_cast<bf16_t*>(Ksorted),
+                       static_cast<bf16_t*>(Vsorted), no_resident, new_bucket_ids, overflow_flag, part, counters, Hkv,
+                       Ncap, B, B, 0, 0, P, cpl);
   else
-    hipLaunchKernelGGL(append_kernel<float>, dim3(units), dim3(kScoreThreads), 0, hs, static_cast<const float*>(x_new),
+    hipLaunchKernelGGL(window_push_kernel<float>, grid, dim3(64), 0, hs, static_cast<const float*>(x_new),
                        static_cast<const float*>(k_new), static_cast<const float*>(v_new), pos_new,
-                       static_cast<const float*>(centroids), bias, off, len, idx,
-                       static_cast<float*>(Ksorted), static_cast<float*>(Vsorted), new_bucket_ids,
-                       overflow_flag, Hkv, Ncap, B);
+                       static_cast<const float*>(centroids), bias, off, len, idx, static_cast<float*>(Ksorted),
+                       static_cast<float*>(Vsorted), no_resident, new_bucket_ids, overflow_flag, part, counters, Hkv,
+                       Ncap, B, B, 0, 0, P, cpl);
   return launch_status();
 }
 

@@ -84,10 +84,10 @@ extern "C" size_t saap_workspace_bytes(int32_t op, const saap_shape* sh) {
       if (S <= 0 || Hq <= 0 || sh->hidden < 0) return 0;
       return classify_workspace_bytes(S * Hq, sh->hidden);
     case SAAP_OP_WINDOW_PUSH:
+    case SAAP_OP_APPEND_KEYS:
       if (S <= 0 || Hkv <= 0 || sh->B <= 0) return 0;
       return push_workspace_bytes(S * Hkv, sh->B);
     case SAAP_OP_SELECT_BUCKETS:
-    case SAAP_OP_APPEND_KEYS:
       return SAAP_WS_HEADER_BYTES;
     default:
       return 0;
