@@ -5,8 +5,11 @@
 // Design for gfx950 (not the paper's one-block-per-bucket scheme):
 //   * A "unit" is one (sequence, KV head) with its G query heads.  The visited buckets of
 //     a unit are contiguous runs of the sorted cache; concatenated they form a virtual key
-//     range [0,T).  The unit's P workgroups take equal slices of that range, so the load
-//     is balanced whatever the bucket sizes are.
+//     range [0,T), cut into chunks of 128 keys that are dealt round-robin to the unit's P
+//     workgroups, so the load is balanced whatever the bucket sizes are and neighbouring
+//     workgroups stream neighbouring memory.  One more run can be visited always (the
+//     attention sink + recent keys of Section 3), and with independent routing the union of
+//     the heads' lists is visited once with a head mask per run.
 //   * Inside a wavefront, 16 lanes read one 256-byte bf16 row with one 16-byte load each
 //     (four rows per wave instruction, whole cache lines).  Each 16-lane group is a "key
 //     processor" with its own running maximum, sum and output accumulator for all G heads

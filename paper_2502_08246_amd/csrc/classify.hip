@@ -3,16 +3,19 @@
 //
 // At decode only a handful of rows (G per KV head per sequence) meet each weight set, so the
 // call is bound by streaming the weights once; the matrix cores are the instruction that does
-// the (padded 16-row) products.  Three launches:
+// the (padded 16-row) products.  Two launches, three when probabilities are asked for:
 //   hidden kernel   h = relu(W1 x + b1): one workgroup per (weight set, 16-row tile, 64 hidden
-//                   units); h goes to the workspace in fp32.
-//   output kernel   z = W2 h + b2: one workgroup per (weight set, 16-row tile, 32 buckets), so
-//                   that a 1024-bucket classifier for 8 KV heads fills all 256 compute units with
-//                   about 40 KB of loads each (one compute unit was measured to stream only
-//                   20-35 GB/s, so the bytes per workgroup set the time).
+//                   units); h goes to the workspace in fp32.  With hidden = 0 the same kernel
+//                   without the ReLU is the whole (one-layer) model.
+//   output kernel   z = W2 h + b2: one workgroup of eight waves per (weight set, 16-row tile,
+//                   32 or 64 buckets), so that a 1024-bucket classifier for 8 KV heads fills all
+//                   256 compute units with about 40 KB of loads each.  What one compute unit
+//                   pulls from memory grows with the number of waves that have loads in flight,
+//                   hence eight waves with few loads each rather than two with many.
 //                   h is split into three bf16 planes (8+8+8 mantissa bits = the fp32 value
 //                   exactly), so the matrix cores multiply exact operands and accumulate in fp32.
-//   softmax kernel  one workgroup per row, in place.
+//   softmax kernel  one workgroup per row, in place (the decode step skips it: the selection
+//                   kernel can take logits and do the softmax itself).
 // Every global load is a whole 128-byte line per 8 lanes, issued before the first LDS store so
 // that a workgroup's loads are all in flight together; matrix operands are read from LDS with a
 // padded row pitch (no bank conflicts).  fp32 weights use v_mfma_f32_16x16x4_f32 with operands
