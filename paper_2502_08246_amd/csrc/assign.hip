@@ -8,7 +8,7 @@
 //     centroids through LDS in tiles of 32 as the A operand, so one lane owns one key and its 16
 //     accumulator registers are 16 different centroids.  Per key the lane tracks the best and
 //     second-best score; the low 4 bits of a score carry the accumulator register number, so
-//     the running argmax costs three vector instructions per score.
+//     the running argmax costs 2.5 vector instructions per score (tag; max3 and med3 + max per pair).
 //   * exact kernel: a key whose best two fp32 scores are closer than the accumulation error
 //     bound is re-scored against all centroids in double precision (fp64 vector rate equals the
 //     fp32 rate on this chip).  fp32 inputs use the exact kernel for every key.
@@ -140,21 +140,27 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
   // 8*(r/4) + 4*half + r%4 of matrix tile `tile` (global tile number)
   auto track = [&](const f32x16_t& c0, const f32x16_t& c1, int tile) {
     const float old0 = best[0], old1 = best[1];
+    // two scores per step: with s <= b the second largest of {b, s, x, y} is max(s, med3(b, x, y)),
+    // the largest max3(b, x, y): 2.5 vector instructions per score with the tag, not 3
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float s0 = c0[r], s1 = c1[r];
-      if (HAS_BIAS) {
-        const int b = tile * kCentTile + 8 * (r / 4) + 4 * half + (r % 4);
-        const float bv = bias[(size_t)h * B + (b < B ? b : 0)];
-        s0 += bv;
-        s1 += bv;
+    for (int r = 0; r < 16; r += 2) {
+      float p0[2], p1[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        float s0 = c0[r + u], s1 = c1[r + u];
+        if (HAS_BIAS) {
+          const int b = tile * kCentTile + 8 * ((r + u) / 4) + 4 * half + ((r + u) % 4);
+          const float bv = bias[(size_t)h * B + (b < B ? b : 0)];
+          s0 += bv;
+          s1 += bv;
+        }
+        p0[u] = __uint_as_float((__float_as_uint(s0) & keep) | (uint32_t)(r + u));
+        p1[u] = __uint_as_float((__float_as_uint(s1) & keep) | (uint32_t)(r + u));
       }
-      const float p0 = __uint_as_float((__float_as_uint(s0) & keep) | (uint32_t)r);
-      const float p1 = __uint_as_float((__float_as_uint(s1) & keep) | (uint32_t)r);
-      second[0] = __builtin_amdgcn_fmed3f(best[0], second[0], p0);
-      best[0] = fmaxf(best[0], p0);
-      second[1] = __builtin_amdgcn_fmed3f(best[1], second[1], p1);
-      best[1] = fmaxf(best[1], p1);
+      second[0] = fmaxf(second[0], __builtin_amdgcn_fmed3f(best[0], p0[0], p0[1]));
+      best[0] = fmaxf(fmaxf(best[0], p0[0]), p0[1]);
+      second[1] = fmaxf(second[1], __builtin_amdgcn_fmed3f(best[1], p1[0], p1[1]));
+      best[1] = fmaxf(fmaxf(best[1], p1[0]), p1[1]);
     }
     best_tile[0] = best[0] != old0 ? tile : best_tile[0];
     best_tile[1] = best[1] != old1 ? tile : best_tile[1];
