@@ -54,7 +54,7 @@ cent_norm_kernel(const bf16_t* __restrict__ cent, float* __restrict__ cmax, int 
 }
 
 template <bool HAS_BIAS>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256, 3)
 assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent, const float* __restrict__ bias,
                    const float* __restrict__ cmax, int32_t* __restrict__ ids, int32_t* __restrict__ flagged,
                    unsigned* __restrict__ n_flagged, int Hkv, int N, int B, float tol) {
@@ -92,21 +92,26 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
   // buffered: a slab is 1024 pieces of 16 bytes, four per thread, fetched into registers one
   // slab ahead (a slab's worth of matrix work covers the L2 latency) and stored after the compute.
   const int n_slabs = (B + kSlab - 1) / kSlab;
-  uint4 stage[kSlab / 16];
+  // The staging registers must stay registers: fetch and stash run unconditionally (the last
+  // pass fetches the last slab again and stores it into the idle buffer), which keeps them out of
+  // control flow; behind a branch the compiler parked them in scratch memory and waited for every
+  // load right after issuing it.
+  typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+  u32x4_t stage[kSlab / 16];
   auto fetch = [&](int t) {
 #pragma unroll
     for (int i = 0; i < kSlab / 16; ++i) {
       const int piece = tid + i * 256, r = piece >> 4, pc = piece & 15;
       int b = t * kSlab + r;
       if (b >= B) b = 0;   // padding repeats centroid 0; a padded winner is re-scored (id >= B below)
-      stage[i] = *reinterpret_cast<const uint4*>(cu + (size_t)b * kD + pc * 8);
+      stage[i] = *reinterpret_cast<const u32x4_t*>(cu + (size_t)b * kD + pc * 8);
     }
   };
   auto stash = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < kSlab / 16; ++i) {
       const int piece = tid + i * 256, r = piece >> 4, pc = piece & 15;
-      *reinterpret_cast<uint4*>(&s_c[buf][r * kPitch + pc * 8]) = stage[i];
+      *reinterpret_cast<u32x4_t*>(&s_c[buf][r * kPitch + pc * 8]) = stage[i];
     }
   };
   fetch(0);
@@ -168,7 +173,7 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
 
   for (int t = 0; t < n_slabs; ++t) {
     const int buf = t & 1;
-    if (t + 1 < n_slabs) fetch(t + 1);
+    fetch(min(t + 1, n_slabs - 1));
     // the matrix instructions of the second tile are issued before the vector work on the first,
     // so both pipes are busy within one wave
     f32x16_t a0, a1, b0, b1;
@@ -176,7 +181,7 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
     tile_mfma(buf, 1, b0, b1);
     track(a0, a1, t * 2 + 0);
     track(b0, b1, t * 2 + 1);
-    if (t + 1 < n_slabs) stash(buf ^ 1);
+    stash(buf ^ 1);
     __syncthreads();
   }
 
@@ -237,13 +242,18 @@ assign_exact_kernel(const T* __restrict__ x, const T* __restrict__ cent, const f
       const T* c = cent + ((size_t)h * B + b) * kD;
       double t = 0.0;
       if (sizeof(T) == 2) {
-        for (int j = 0; j < kD; j += 8) {
-          const uint4 raw = *reinterpret_cast<const uint4*>(c + j);
-          const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+        // the whole row first (sixteen 16-byte loads in flight), then the in-order chain of 128
+        // fused multiply-adds: one memory latency per centroid instead of sixteen
+        uint4 raw[kD / 8];
+#pragma unroll
+        for (int j = 0; j < kD / 8; ++j) raw[j] = reinterpret_cast<const uint4*>(c)[j];
+#pragma unroll
+        for (int j = 0; j < kD / 8; ++j) {
+          const uint32_t w[4] = {raw[j].x, raw[j].y, raw[j].z, raw[j].w};
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
-            t = fma(s_x[j + 2 * k], (double)bf16_lo(w[k]), t);
-            t = fma(s_x[j + 2 * k + 1], (double)bf16_hi(w[k]), t);
+            t = fma(s_x[8 * j + 2 * k], (double)bf16_lo(w[k]), t);
+            t = fma(s_x[8 * j + 2 * k + 1], (double)bf16_hi(w[k]), t);
           }
         }
       } else {
