@@ -9,9 +9,11 @@
 //     accumulator registers are 16 different centroids.  Per key the lane tracks the best and
 //     second-best score; the low 4 bits of a score carry the accumulator register number, so
 //     the running argmax costs 2.5 vector instructions per score (tag; max3 and med3 + max per pair).
-//   * exact kernel: a key whose best two fp32 scores are closer than the accumulation error
-//     bound is re-scored against all centroids in double precision (fp64 vector rate equals the
-//     fp32 rate on this chip).  fp32 inputs use the exact kernel for every key.
+//   * re-scoring kernel: a key whose best two fp32 scores are closer than the accumulation error
+//     bound is scored again: fp32 against all centroids with whole-row loads, then double
+//     precision for the few centroids within the bound of that maximum.
+//   * exact kernel: double precision against every centroid; used for fp32 inputs (every key) and
+//     for re-scoring when there are more buckets than the re-scoring kernel keeps scores for.
 // No score matrix is ever written to memory.
 #include "common.h"
 
@@ -283,6 +285,112 @@ assign_exact_kernel(const T* __restrict__ x, const T* __restrict__ cent, const f
   }
 }
 
+// Re-scoring of the listed keys (bf16), one workgroup per key.  A first pass scores every
+// centroid in fp32 (16 lanes per centroid row, so the loads are whole contiguous rows; the order
+// of that sum is free, its error is inside the bound below) and leaves the scores in LDS.  Only
+// centroids whose fp32 score is within the bound of the fp32 maximum can be the double-precision
+// argmax; those few (typically two) are then scored in double precision, in order.  Any score
+// that does not compare (NaN) counts as a candidate, so odd inputs fall back to the full scan.
+constexpr int kRescoreMaxB = 4096;   // scores kept in LDS
+__global__ void __launch_bounds__(256)
+assign_rescore_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent,
+                      const float* __restrict__ bias, const float* __restrict__ cmax,
+                      int32_t* __restrict__ ids, const int32_t* __restrict__ rows,
+                      const unsigned* __restrict__ n_rows_dev, int Hkv, int N, int B, float tol) {
+  __shared__ float s_score[kRescoreMaxB];
+  __shared__ float s_wmax[4];
+  __shared__ double s_best[4];
+  __shared__ int s_id[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int piece = lane & 15, sub = lane >> 4;
+  const unsigned n_rows = *n_rows_dev;
+  for (unsigned i = blockIdx.x; i < n_rows; i += gridDim.x) {
+    const size_t g = (size_t)rows[i];
+    const int h = (int)((g / (size_t)N) % (size_t)Hkv);
+    const bf16_t* xr = x + g * kD;
+    const bf16_t* cu = cent + (size_t)h * B * kD;
+    const float* bu = bias ? bias + (size_t)h * B : nullptr;
+    Vec8<bf16_t> xv;
+    xv.load(xr + piece * 8);
+    const float xnorm2 = sum16(xv.dot(xv));
+
+    // pass 1: fp32 scores of all centroids; a wave takes 4 rows per load, the workgroup 16
+    float mx = -INFINITY;
+    for (int bb = 0; bb < B; bb += 128) {
+      const int b0 = bb + wave * 4 + sub;
+      Vec8<bf16_t> cv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) cv[u].load(cu + (size_t)min(b0 + 16 * u, B - 1) * kD + piece * 8);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int b = b0 + 16 * u;
+        float sc = sum16(cv[u].dot(xv));
+        if (b < B) {
+          if (bu) sc += bu[b];
+          if (piece == 0) s_score[b] = sc;
+          mx = fmaxf(mx, sc);
+        }
+      }
+    }
+    mx = max_rows(mx);
+    if (lane == 0) s_wmax[wave] = mx;
+    __syncthreads();
+    const float m = fmaxf(fmaxf(s_wmax[0], s_wmax[1]), fmaxf(s_wmax[2], s_wmax[3]));
+    // two fp32 scores are compared: the same bound as for the matrix-core scores
+    const float lim = m - (tol * cmax[h] * sqrtf(xnorm2) + 5e-6f * fabsf(m));
+
+    // pass 2: double precision for the candidates
+    double best = 0.0;
+    int best_id = -1;
+    for (int b = tid; b < B; b += 256) {
+      if (s_score[b] < lim) continue;
+      const uint4* c = reinterpret_cast<const uint4*>(cu + (size_t)b * kD);
+      const uint4* xq = reinterpret_cast<const uint4*>(xr);
+      double t = 0.0;
+      for (int j = 0; j < kD / 8; ++j) {
+        const uint4 cw = c[j], xw = xq[j];
+        const uint32_t w[4] = {cw.x, cw.y, cw.z, cw.w}, v[4] = {xw.x, xw.y, xw.z, xw.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          t = fma((double)bf16_lo(v[k]), (double)bf16_lo(w[k]), t);
+          t = fma((double)bf16_hi(v[k]), (double)bf16_hi(w[k]), t);
+        }
+      }
+      if (bu) t += (double)bu[b];
+      if (best_id < 0 || t > best) {
+        best = t;
+        best_id = b;
+      }
+    }
+    // larger score wins, lower id on equal scores; a lane without candidate has id -1
+    for (int o = 1; o < 64; o <<= 1) {
+      const double ob = __shfl_xor(best, o);
+      const int oid = __shfl_xor(best_id, o);
+      if (oid >= 0 && (best_id < 0 || ob > best || (ob == best && oid < best_id))) {
+        best = ob;
+        best_id = oid;
+      }
+    }
+    if (lane == 0) {
+      s_best[wave] = best;
+      s_id[wave] = best_id;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      for (int w = 1; w < 4; ++w) {
+        const double ob = s_best[w];
+        const int oid = s_id[w];
+        if (oid >= 0 && (best_id < 0 || ob > best || (ob == best && oid < best_id))) {
+          best = ob;
+          best_id = oid;
+        }
+      }
+      ids[g] = best_id;
+    }
+    __syncthreads();
+  }
+}
+
 // Leaves the arrival counter zero again; the number of re-scored keys of this call is kept in
 // the scratch area for diagnostics.
 __global__ void clear_counter_kernel(unsigned* c, unsigned* stat) {
@@ -340,8 +448,12 @@ extern "C" int32_t saap_assign_keys(const void* x, const void* centroids, const 
   else
     hipLaunchKernelGGL(assign_mfma_kernel<false>, grid, dim3(256), 0, hs, xb, cb, bias, cmax, bucket_ids,
                        flagged, n_flagged, Hkv, N, B, tol);
-  hipLaunchKernelGGL(assign_exact_kernel<bf16_t>, dim3((unsigned)(cus * 8)), dim3(256), 0, hs, xb, cb, bias,
-                     bucket_ids, flagged, n_flagged, rows, Hkv, N, B);
+  if (B <= kRescoreMaxB)
+    hipLaunchKernelGGL(assign_rescore_kernel, dim3((unsigned)(cus * 8)), dim3(256), 0, hs, xb, cb, bias, cmax,
+                       bucket_ids, flagged, n_flagged, Hkv, N, B, tol);
+  else
+    hipLaunchKernelGGL(assign_exact_kernel<bf16_t>, dim3((unsigned)(cus * 8)), dim3(256), 0, hs, xb, cb, bias,
+                       bucket_ids, flagged, n_flagged, rows, Hkv, N, B);
   hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, hs, n_flagged,
                      reinterpret_cast<unsigned*>(cmax) + 4095);
   return launch_status();

@@ -390,6 +390,7 @@ def _plant_ties(x, cent):
 @pytest.mark.parametrize("dtype,S,Hkv,N,B,bias", [
     ("bf16", 1, 2, 4000, 64, False), ("bf16", 2, 2, 1031, 1024, False), ("bf16", 1, 1, 5000, 100, True),
     ("f32", 1, 1, 4096, 64, False), ("f32", 1, 2, 500, 37, True), ("bf16", 1, 1, 700, 4096, False),
+    ("bf16", 1, 2, 300, 4100, True),            # more buckets than the re-scoring pass keeps scores for
 ])
 def test_assign_keys(saap, dtype, S, Hkv, N, B, bias):
     cfg = small("cfg1_llama8b_128k", S=S, Hq=Hkv, Hkv=Hkv, N=N, B=B, dtype=dtype)
@@ -405,6 +406,24 @@ def test_assign_keys(saap, dtype, S, Hkv, N, B, bias):
     got = ids.cpu().numpy()
     assert np.array_equal(got, want), f"{(got != want).sum()} of {got.size} ids differ"
     assert (got[:, :, :64] == 2).all()                      # the lowest of the tied duplicates
+
+
+def test_assign_keys_degenerate_rows(saap):
+    """Zero keys score the same against every centroid (all of them are candidates of the re-scoring
+    pass), and keys equal to a centroid shared by two ids: the lowest id wins in both cases."""
+    cfg = small("cfg1_llama8b_128k", S=1, Hq=2, Hkv=2, N=600, B=200, dtype="bf16")
+    cache = gen.make_cache(cfg, 61, DEV)
+    cent = gen.make_centroids(cfg, 61, DEV, n_train=2048)
+    x = cache["x_keys"].clone()
+    x[:, :, 100:300] = 0
+    cent[:, 150] = cent[:, 17]
+    x[:, :, 300:320] = cent[:, 17].unsqueeze(0).unsqueeze(2)
+    ids = saap.assign_keys(x, cent)
+    torch.cuda.synchronize()
+    want = ref.assign_keys(h(x), h(cent), None)
+    got = ids.cpu().numpy()
+    assert np.array_equal(got, want)
+    assert (got[:, :, 100:300] == 0).all()
 
 
 # ------------------------------------------------------------------------------ append
