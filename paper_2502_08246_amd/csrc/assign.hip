@@ -31,32 +31,32 @@ template <> __device__ __forceinline__ double to_f64<bf16_t>(bf16_t v) {
   return (double)__uint_as_float((uint32_t)v << 16);
 }
 
-// max_b |c_b| per KV head (fp32, rounded up a little by the caller's tolerance factor).
-__global__ void __launch_bounds__(256)
+// max_b |c_b| per KV head (fp32, rounded up a little).  16 lanes per centroid row.
+constexpr int kNormThreads = 1024;
+__global__ void __launch_bounds__(kNormThreads)
 cent_norm_kernel(const bf16_t* __restrict__ cent, float* __restrict__ cmax, int B) {
-  __shared__ float s_m[256];
-  const int h = blockIdx.x;
+  __shared__ float s_m[kNormThreads / 64];
+  const int h = blockIdx.x, tid = threadIdx.x, piece = tid & 15, sub = tid >> 4;
+  const bf16_t* cu = cent + (size_t)h * B * kD;
   float mx = 0.f;
-  for (int b = threadIdx.x; b < B; b += blockDim.x) {
-    const bf16_t* c = cent + ((size_t)h * B + b) * kD;
-    float s = 0.f;
-    for (int j = 0; j < kD; ++j) {
-      const float v = __uint_as_float((uint32_t)c[j] << 16);
-      s = fmaf(v, v, s);
-    }
-    mx = fmaxf(mx, s);
+  for (int b0 = 0; b0 < B; b0 += kNormThreads / 16 * 4) {
+    Vec8<bf16_t> v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u].load(cu + (size_t)min(b0 + u * (kNormThreads / 16) + sub, B - 1) * kD + piece * 8);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) mx = fmaxf(mx, sum16(v[u].dot(v[u])));
   }
-  s_m[threadIdx.x] = mx;
+  mx = max_rows(mx);
+  if ((tid & 63) == 0) s_m[tid >> 6] = mx;
   __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (threadIdx.x < s) s_m[threadIdx.x] = fmaxf(s_m[threadIdx.x], s_m[threadIdx.x + s]);
-    __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < kNormThreads / 64; ++w) mx = fmaxf(mx, s_m[w]);
+    cmax[h] = sqrtf(mx) * 1.0001f;
   }
-  if (threadIdx.x == 0) cmax[h] = sqrtf(s_m[0]) * 1.0001f;
 }
 
 template <bool HAS_BIAS>
-__global__ void __launch_bounds__(256, 3)
+__global__ void __launch_bounds__(256, 2)
 assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent, const float* __restrict__ bias,
                    const float* __restrict__ cmax, int32_t* __restrict__ ids, int32_t* __restrict__ flagged,
                    unsigned* __restrict__ n_flagged, int Hkv, int N, int B, float tol) {
@@ -92,7 +92,8 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
 
   // Centroids stream through LDS in slabs of kSlab = 64 (two matrix tiles of 32), double
   // buffered: a slab is 1024 pieces of 16 bytes, four per thread, fetched into registers one
-  // slab ahead (a slab's worth of matrix work covers the L2 latency) and stored after the compute.
+  // slab ahead (a slab's worth of matrix work covers the L2 latency) and stored mid-way through
+  // the compute of the slab before.
   const int n_slabs = (B + kSlab - 1) / kSlab;
   // The staging registers must stay registers: fetch and stash run unconditionally (the last
   // pass fetches the last slab again and stores it into the idle buffer), which keeps them out of
@@ -118,6 +119,7 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
   };
   fetch(0);
   stash(0);
+  fetch(min(1, n_slabs - 1));
   __syncthreads();
 
   const uint32_t keep = 0xFFFFFFF0u;
@@ -131,61 +133,77 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
   }
 
   typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-  // scores of matrix tile `sub` of the slab in `buf`: two 32x32 accumulators (the wave's two key tiles)
-  auto tile_mfma = [&](int buf, int sub, f32x16_t& c0, f32x16_t& c1) {
-    c0 = (f32x16_t){0};
-    c1 = (f32x16_t){0};
+  // A operand of k-step `st` of matrix tile `sub` of the slab in `buf`
+  auto a_frag = [&](int buf, int sub, int st) {
+    const uint4 raw = *reinterpret_cast<const uint4*>(&s_c[buf][(sub * kCentTile + col) * kPitch + st * 16 + half * 8]);
+    return __builtin_bit_cast(bf16x8_t, raw);
+  };
+  // running best / second best over accumulator registers r, r+1 of both key tiles; register r
+  // of this lane is centroid 8*(r/4) + 4*half + r%4 of matrix tile `tile` (global tile number).
+  // Two scores per step: with s <= b the second largest of {b, s, x, y} is max(s, med3(b, x, y)),
+  // the largest max3(b, x, y): 2.5 vector instructions per score with the tag, not 3.
+  auto track_pair = [&](const f32x16_t& c0, const f32x16_t& c1, int tile, int r) {
+    float p0[2], p1[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      float s0 = c0[r + u], s1 = c1[r + u];
+      if (HAS_BIAS) {
+        const int b = tile * kCentTile + 8 * ((r + u) / 4) + 4 * half + ((r + u) % 4);
+        const float bv = bias[(size_t)h * B + (b < B ? b : 0)];
+        s0 += bv;
+        s1 += bv;
+      }
+      p0[u] = __uint_as_float((__float_as_uint(s0) & keep) | (uint32_t)(r + u));
+      p1[u] = __uint_as_float((__float_as_uint(s1) & keep) | (uint32_t)(r + u));
+    }
+    second[0] = fmaxf(second[0], __builtin_amdgcn_fmed3f(best[0], p0[0], p0[1]));
+    best[0] = fmaxf(fmaxf(best[0], p0[0]), p0[1]);
+    second[1] = fmaxf(second[1], __builtin_amdgcn_fmed3f(best[1], p1[0], p1[1]));
+    best[1] = fmaxf(fmaxf(best[1], p1[0]), p1[1]);
+  };
+  // Software pipeline over matrix tiles: while the matrix cores work on tile (buf, sub) into
+  // n0/n1, the vector pipe ranks the finished scores o0/o1 of the tile before.  One k-step (two
+  // matrix instructions, 2 x 8 passes) is paired with one register pair of ranking (ten vector
+  // instructions) between scheduling fences; left alone the compiler issues all sixteen matrix
+  // instructions first and the two pipes run one after the other.
+  auto step = [&](int buf, int sub, f32x16_t& n0, f32x16_t& n1, const f32x16_t& o0, const f32x16_t& o1,
+                  int tile_old, bool has_new, bool has_old) {
+    const float old0 = best[0], old1 = best[1];
+    bf16x8_t a = a_frag(buf, sub, 0);
+    if (has_new) {
+      n0 = (f32x16_t){0};
+      n1 = (f32x16_t){0};
+    }
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
-      const uint4 raw = *reinterpret_cast<const uint4*>(&s_c[buf][(sub * kCentTile + col) * kPitch + st * 16 + half * 8]);
-      const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw);
-      c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[0][st], c0, 0, 0, 0);
-      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[1][st], c1, 0, 0, 0);
-    }
-  };
-  // running best / second best; accumulator register r of this lane is centroid
-  // 8*(r/4) + 4*half + r%4 of matrix tile `tile` (global tile number)
-  auto track = [&](const f32x16_t& c0, const f32x16_t& c1, int tile) {
-    const float old0 = best[0], old1 = best[1];
-    // two scores per step: with s <= b the second largest of {b, s, x, y} is max(s, med3(b, x, y)),
-    // the largest max3(b, x, y): 2.5 vector instructions per score with the tag, not 3
-#pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-      float p0[2], p1[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        float s0 = c0[r + u], s1 = c1[r + u];
-        if (HAS_BIAS) {
-          const int b = tile * kCentTile + 8 * ((r + u) / 4) + 4 * half + ((r + u) % 4);
-          const float bv = bias[(size_t)h * B + (b < B ? b : 0)];
-          s0 += bv;
-          s1 += bv;
-        }
-        p0[u] = __uint_as_float((__float_as_uint(s0) & keep) | (uint32_t)(r + u));
-        p1[u] = __uint_as_float((__float_as_uint(s1) & keep) | (uint32_t)(r + u));
+      __builtin_amdgcn_sched_barrier(0);
+      if (has_new) {
+        const bf16x8_t a_next = a_frag(buf, sub, min(st + 1, 7));
+        n0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[0][st], n0, 0, 0, 0);
+        n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[1][st], n1, 0, 0, 0);
+        a = a_next;
       }
-      second[0] = fmaxf(second[0], __builtin_amdgcn_fmed3f(best[0], p0[0], p0[1]));
-      best[0] = fmaxf(fmaxf(best[0], p0[0]), p0[1]);
-      second[1] = fmaxf(second[1], __builtin_amdgcn_fmed3f(best[1], p1[0], p1[1]));
-      best[1] = fmaxf(fmaxf(best[1], p1[0]), p1[1]);
+      if (has_old) track_pair(o0, o1, tile_old, 2 * st);
     }
-    best_tile[0] = best[0] != old0 ? tile : best_tile[0];
-    best_tile[1] = best[1] != old1 ? tile : best_tile[1];
+    __builtin_amdgcn_sched_barrier(0);
+    if (has_old) {
+      best_tile[0] = best[0] != old0 ? tile_old : best_tile[0];
+      best_tile[1] = best[1] != old1 ? tile_old : best_tile[1];
+    }
   };
 
-  for (int t = 0; t < n_slabs; ++t) {
+  f32x16_t a0, a1, b0, b1;
+  step(0, 0, a0, a1, b0, b1, 0, true, false);
+  for (int t = 0; t < n_slabs - 1; ++t) {
     const int buf = t & 1;
-    fetch(min(t + 1, n_slabs - 1));
-    // the matrix instructions of the second tile are issued before the vector work on the first,
-    // so both pipes are busy within one wave
-    f32x16_t a0, a1, b0, b1;
-    tile_mfma(buf, 0, a0, a1);
-    tile_mfma(buf, 1, b0, b1);
-    track(a0, a1, t * 2 + 0);
-    track(b0, b1, t * 2 + 1);
+    step(buf, 1, b0, b1, a0, a1, t * 2 + 0, true, true);
     stash(buf ^ 1);
+    fetch(min(t + 2, n_slabs - 1));
     __syncthreads();
+    step(buf ^ 1, 0, a0, a1, b0, b1, t * 2 + 1, true, true);
   }
+  step((n_slabs - 1) & 1, 1, b0, b1, a0, a1, (n_slabs - 1) * 2 + 0, true, true);
+  step(0, 0, a0, a1, b0, b1, (n_slabs - 1) * 2 + 1, false, true);
 
   // lanes l and l+32 own the same key: merge their candidates, lower id on equal packed scores
   const float tol_c = tol * cmax[h];
@@ -292,18 +310,20 @@ assign_exact_kernel(const T* __restrict__ x, const T* __restrict__ cent, const f
 // argmax; those few (typically two) are then scored in double precision, in order.  Any score
 // that does not compare (NaN) counts as a candidate, so odd inputs fall back to the full scan.
 constexpr int kRescoreMaxB = 4096;   // scores kept in LDS
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 5)
 assign_rescore_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent,
                       const float* __restrict__ bias, const float* __restrict__ cmax,
                       int32_t* __restrict__ ids, const int32_t* __restrict__ rows,
-                      const unsigned* __restrict__ n_rows_dev, int Hkv, int N, int B, float tol) {
+                      unsigned* __restrict__ counters, unsigned* __restrict__ stat, int Hkv, int N, int B,
+                      float tol) {
   __shared__ float s_score[kRescoreMaxB];
+  __shared__ __align__(16) uint4 s_x[kD / 8];
   __shared__ float s_wmax[4];
   __shared__ double s_best[4];
   __shared__ int s_id[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int piece = lane & 15, sub = lane >> 4;
-  const unsigned n_rows = *n_rows_dev;
+  const unsigned n_rows = counters[0];   // counters[1]: workgroups that have finished
   for (unsigned i = blockIdx.x; i < n_rows; i += gridDim.x) {
     const size_t g = (size_t)rows[i];
     const int h = (int)((g / (size_t)N) % (size_t)Hkv);
@@ -313,6 +333,7 @@ assign_rescore_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ c
     Vec8<bf16_t> xv;
     xv.load(xr + piece * 8);
     const float xnorm2 = sum16(xv.dot(xv));
+    if (tid < 16) s_x[piece] = xv.r;
 
     // pass 1: fp32 scores of all centroids; a wave takes 4 rows per load, the workgroup 16
     float mx = -INFINITY;
@@ -345,10 +366,16 @@ assign_rescore_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ c
     for (int b = tid; b < B; b += 256) {
       if (s_score[b] < lim) continue;
       const uint4* c = reinterpret_cast<const uint4*>(cu + (size_t)b * kD);
-      const uint4* xq = reinterpret_cast<const uint4*>(xr);
+      // the key's conversions to double stay inside the (rarely taken) candidate path: hoisted
+      // out of the loop they would hold 256 registers for the whole kernel
+      asm volatile("" ::: "memory");
+      uint4 craw[kD / 8];   // the whole row in flight, then the chain
+#pragma unroll
+      for (int j = 0; j < kD / 8; ++j) craw[j] = c[j];
       double t = 0.0;
+#pragma unroll
       for (int j = 0; j < kD / 8; ++j) {
-        const uint4 cw = c[j], xw = xq[j];
+        const uint4 cw = craw[j], xw = s_x[j];
         const uint32_t w[4] = {cw.x, cw.y, cw.z, cw.w}, v[4] = {xw.x, xw.y, xw.z, xw.w};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -388,6 +415,16 @@ assign_rescore_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ c
       ids[g] = best_id;
     }
     __syncthreads();
+  }
+  // Every workgroup has read the list length by now; the last one to leave keeps it for
+  // diagnostics and leaves both counters zero for the next call.
+  __syncthreads();
+  if (tid == 0) {
+    if (atomicAdd(counters + 1, 1u) == gridDim.x - 1) {
+      *stat = n_rows;
+      counters[0] = 0u;
+      counters[1] = 0u;
+    }
   }
 }
 
@@ -440,7 +477,7 @@ extern "C" int32_t saap_assign_keys(const void* x, const void* centroids, const 
   // fp32 accumulation of 128 exact products: |error| <= 128 * 2^-24 * |x| |c| per score; two scores
   // are compared, and a factor 4 of head-room covers the matrix core's internal summation order.
   const float tol = 8.0f * 128.0f * 5.9604645e-8f;
-  hipLaunchKernelGGL(cent_norm_kernel, dim3((unsigned)Hkv), dim3(256), 0, hs, cb, cmax, B);
+  hipLaunchKernelGGL(cent_norm_kernel, dim3((unsigned)Hkv), dim3(kNormThreads), 0, hs, cb, cmax, B);
   const dim3 grid((unsigned)((N + kRowsPerWg - 1) / kRowsPerWg), (unsigned)units);
   if (bias)
     hipLaunchKernelGGL(assign_mfma_kernel<true>, grid, dim3(256), 0, hs, xb, cb, bias, cmax, bucket_ids, flagged,
@@ -448,13 +485,14 @@ extern "C" int32_t saap_assign_keys(const void* x, const void* centroids, const 
   else
     hipLaunchKernelGGL(assign_mfma_kernel<false>, grid, dim3(256), 0, hs, xb, cb, bias, cmax, bucket_ids,
                        flagged, n_flagged, Hkv, N, B, tol);
-  if (B <= kRescoreMaxB)
+  unsigned* stat = reinterpret_cast<unsigned*>(cmax) + 4095;
+  if (B <= kRescoreMaxB) {
     hipLaunchKernelGGL(assign_rescore_kernel, dim3((unsigned)(cus * 8)), dim3(256), 0, hs, xb, cb, bias, cmax,
-                       bucket_ids, flagged, n_flagged, Hkv, N, B, tol);
-  else
+                       bucket_ids, flagged, n_flagged, stat, Hkv, N, B, tol);
+  } else {
     hipLaunchKernelGGL(assign_exact_kernel<bf16_t>, dim3((unsigned)(cus * 8)), dim3(256), 0, hs, xb, cb, bias,
                        bucket_ids, flagged, n_flagged, rows, Hkv, N, B);
-  hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, hs, n_flagged,
-                     reinterpret_cast<unsigned*>(cmax) + 4095);
+    hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, hs, n_flagged, stat);
+  }
   return launch_status();
 }
