@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense baseline (keeps profiler summaries to the sparse path)")
     ap.add_argument("--window", default="", help="also time the step with an attention sink + recent-key window, "
                     "e.g. 1+2047 (the paper's default): adds a `window` object to the output")
+    ap.add_argument("--layers", type=int, default=1,
+                    help="also time a decode step through this many layers, each with its own synthetic cache, "
+                         "centroids, classifier and index (e.g. 32 with --workload cfg4_layer_262k)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of 256 MiB (reference for the HBM byte counters)")
     return ap.parse_args()
@@ -296,6 +299,48 @@ def main():
             "overflow_flag": int(w_flag[0].item()),
         }
 
+    layers_result = None
+    if args.layers > 1:
+        # A decode step through L layers: every layer has its own cache (seed + layer), centroids,
+        # classifier and index, so nothing a layer reads was left in the caches by the layer before.
+        TL = min(T, 8)
+        layers = [dict(W=(W1, b1, W2, b2), off=off, ln=ln, Ks=Ks, Vs=Vs, xq=xq[:TL], q=q[:TL])]
+        t_build0 = time.perf_counter()
+        for l in range(1, args.layers):
+            c_l = gen.make_cache(cfg, args.seed + l, dev)
+            cent_l = gen.make_centroids(cfg, args.seed + l, dev, c_l)
+            ids_l = saap.assign_keys(c_l["x_keys"], cent_l)
+            o_l, n_l, _, K_l, V_l = saap.build_bucket_index(ids_l, c_l["K"], c_l["V"], cfg.B, 0)
+            xq_l, q_l = gen.make_queries(cfg, args.seed + l, dev, n_steps=TL)
+            layers.append(dict(W=gen.make_classifier(cfg, args.seed + l, dev), off=o_l, ln=n_l, Ks=K_l, Vs=V_l,
+                               xq=xq_l, q=q_l))
+            del c_l, ids_l, cent_l
+            torch.cuda.synchronize()
+            print(f"layer {l} indexed", file=sys.stderr, flush=True)
+        build_s = time.perf_counter() - t_build0
+
+        def model_step(i):
+            for L in layers:
+                saap.classify_queries(L["xq"][i % TL], *L["W"], cfg.Hkv, output_kind=saap.LOGITS, out=scores)
+                saap.select_buckets_from_logits(scores, cfg.Hkv, cfg.nprobe, out=sel)
+                saap.sparse_decode_attention(L["q"][i % TL], L["Ks"], L["Vs"], L["off"], L["ln"], sel, scale, out=out, lse=lse)
+
+        def model_dense(i):
+            for L in layers:
+                saap.dense_decode_attention(L["q"][i % TL], L["Ks"], L["Vs"], scale, off=L["off"], ln=L["ln"], out=out, lse=lse)
+
+        ms_model = GraphLoop(model_step, TL, torch).timed_ms_per_call(max(2, min(reps, 8)))
+        ms_model_dense = None if args.no_dense else GraphLoop(model_dense, 2, torch).timed_ms_per_call(2)
+        layers_result = {
+            "layers": args.layers,
+            "step": "per layer: classify_queries (logits) + select_buckets_from_logits + sparse_decode_attention",
+            "us_per_token": round(ms_model * 1e3 / cfg.S, 2),
+            "us_per_token_layer": round(ms_model * 1e3 / cfg.S / args.layers, 3),
+            "dense_attention_us_per_layer": None if ms_model_dense is None else round(ms_model_dense * 1e3 / args.layers, 3),
+            "sorted_cache_GiB": round(sum(L["Ks"].numel() * 2 * L["Ks"].element_size() for L in layers) / 2**30, 2),
+            "prefill_s_all_layers": round(build_s, 1),
+        }
+
     # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary of
     # this workload (a separate profiling run; see profiles/): null if there is none.
     traffic = None
@@ -363,6 +408,8 @@ def main():
     }
     if window_result:
         result["window"] = window_result
+    if layers_result:
+        result["model_step"] = layers_result
     if with_append:
         result["append_overflow_flag"] = int(a_flag[0].item())
 
