@@ -10,10 +10,10 @@
 //     second-best score; the low 4 bits of a score carry the accumulator register number, so
 //     the running argmax costs 2.5 vector instructions per score (tag; max3 and med3 + max per pair).
 //   * re-scoring kernel: a key whose best two fp32 scores are closer than the accumulation error
-//     bound is scored again: fp32 against all centroids with whole-row loads, then double
-//     precision for the few centroids within the bound of that maximum.
-//   * exact kernel: double precision against every centroid; used for fp32 inputs (every key) and
-//     for re-scoring when there are more buckets than the re-scoring kernel keeps scores for.
+//     bound is scored again, 32 such keys of a head at a time: two more matrix-core passes find
+//     every centroid within the bound of the key's maximum, and only those (typically two) are
+//     scored in double precision.
+//   * fp32 inputs: a plain double-precision kernel scores every key against every centroid.
 // No score matrix is ever written to memory.
 #include "common.h"
 
@@ -24,12 +24,6 @@ constexpr int kRowsPerWg = 256;   // keys per workgroup of the mfma kernel (4 wa
 constexpr int kCentTile = 32;     // centroids per matrix tile
 constexpr int kSlab = 64;         // centroids per LDS slab (two matrix tiles)
 constexpr int kPitch = 136;       // bf16 elements per LDS row (272 bytes: conflict-free b128 reads)
-
-template <typename T> __device__ __forceinline__ double to_f64(T v);
-template <> __device__ __forceinline__ double to_f64<float>(float v) { return (double)v; }
-template <> __device__ __forceinline__ double to_f64<bf16_t>(bf16_t v) {
-  return (double)__uint_as_float((uint32_t)v << 16);
-}
 
 // max_b |c_b| per KV head (fp32, rounded up a little).  16 lanes per centroid row.
 constexpr int kNormThreads = 1024;
@@ -59,7 +53,7 @@ template <bool HAS_BIAS>
 __global__ void __launch_bounds__(256, 2)
 assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent, const float* __restrict__ bias,
                    const float* __restrict__ cmax, int32_t* __restrict__ ids, int32_t* __restrict__ flagged,
-                   unsigned* __restrict__ n_flagged, int Hkv, int N, int B, float tol) {
+                   unsigned* __restrict__ n_flagged, size_t list_cap, int Hkv, int N, int B, float tol) {
   __shared__ __align__(16) bf16_t s_c[2][kSlab * kPitch];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int unit = blockIdx.y, h = unit % Hkv;
@@ -207,6 +201,11 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
 
   // lanes l and l+32 own the same key: merge their candidates, lower id on equal packed scores
   const float tol_c = tol * cmax[h];
+  __shared__ unsigned s_listed, s_list_base;
+  if (tid == 0) s_listed = 0u;
+  __syncthreads();
+  bool listed[2];
+  unsigned slot[2];
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt) {
     const int r = (int)(__float_as_uint(best[rt]) & 15u);
@@ -225,60 +224,49 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
       ns = fmaxf(ob, s1);
     }
     const int row = row_base + rt * 32 + col;
+    listed[rt] = false;
     if (half == 0 && row < N) {
       const size_t g = (size_t)unit * N + row;
       ids[g] = id;
       // error bound of the fp32 accumulation plus the 4 mantissa bits used for the register tag
       const float thr = tol_c * sqrtf(xnorm2[rt]) + 5e-6f * fabsf(nb);
       if (!(nb - ns > thr) || id >= B) {
-        const unsigned slot = atomicAdd(n_flagged, 1u);
-        flagged[slot] = (int32_t)g;   // global row index fits: checked on the host
+        listed[rt] = true;
+        slot[rt] = atomicAdd(&s_listed, 1u);
       }
     }
   }
+  // one list per KV head (the re-scoring shares centroid loads between keys of a head); the
+  // workgroup's keys are added in one piece, with one global counter update
+  __syncthreads();
+  if (tid == 0 && s_listed) s_list_base = atomicAdd(n_flagged + h, s_listed);
+  __syncthreads();
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+    if (listed[rt])   // global row index fits in 31 bits: checked on the host
+      flagged[(size_t)h * list_cap + s_list_base + slot[rt]] = (int32_t)((size_t)unit * N + row_base + rt * 32 + col);
 }
 
-// Exact scoring in double precision.  One workgroup per listed row (grid-stride over the list);
-// `rows` null = every row in [0, n_all).
-template <typename T>
+// fp32 inputs: double-precision scoring of every key against every centroid (in-order sum,
+// lowest id on ties).  One workgroup per key, grid-stride.
 __global__ void __launch_bounds__(256)
-assign_exact_kernel(const T* __restrict__ x, const T* __restrict__ cent, const float* __restrict__ bias,
-                    int32_t* __restrict__ ids, const int32_t* __restrict__ rows,
-                    const unsigned* __restrict__ n_rows_dev, long long n_all, int Hkv, int N, int B) {
+assign_exact_f32_kernel(const float* __restrict__ x, const float* __restrict__ cent, const float* __restrict__ bias,
+                        int32_t* __restrict__ ids, long long n_rows, int Hkv, int N, int B) {
   __shared__ double s_x[kD];
   __shared__ double s_best[256];
   __shared__ int s_id[256];
   const int tid = threadIdx.x;
-  const long long n_rows = rows ? (long long)*n_rows_dev : n_all;
-  for (long long i = blockIdx.x; i < n_rows; i += gridDim.x) {
-    const long long g = rows ? (long long)rows[i] : i;
+  for (long long g = blockIdx.x; g < n_rows; g += gridDim.x) {
     const int h = (int)((g / N) % Hkv);
     __syncthreads();
-    if (tid < kD) s_x[tid] = to_f64<T>(x[(size_t)g * kD + tid]);
+    if (tid < kD) s_x[tid] = (double)x[(size_t)g * kD + tid];
     __syncthreads();
     double best = 0.0;
     int best_id = -1;
     for (int b = tid; b < B; b += blockDim.x) {
-      const T* c = cent + ((size_t)h * B + b) * kD;
+      const float* c = cent + ((size_t)h * B + b) * kD;
       double t = 0.0;
-      if (sizeof(T) == 2) {
-        // the whole row first (sixteen 16-byte loads in flight), then the in-order chain of 128
-        // fused multiply-adds: one memory latency per centroid instead of sixteen
-        uint4 raw[kD / 8];
-#pragma unroll
-        for (int j = 0; j < kD / 8; ++j) raw[j] = reinterpret_cast<const uint4*>(c)[j];
-#pragma unroll
-        for (int j = 0; j < kD / 8; ++j) {
-          const uint32_t w[4] = {raw[j].x, raw[j].y, raw[j].z, raw[j].w};
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            t = fma(s_x[8 * j + 2 * k], (double)bf16_lo(w[k]), t);
-            t = fma(s_x[8 * j + 2 * k + 1], (double)bf16_hi(w[k]), t);
-          }
-        }
-      } else {
-        for (int j = 0; j < kD; ++j) t = fma(s_x[j], to_f64<T>(c[j]), t);
-      }
+      for (int j = 0; j < kD; ++j) t = fma(s_x[j], (double)c[j], t);
       if (bias) t += (double)bias[(size_t)h * B + b];
       if (best_id < 0 || t > best) {
         best = t;
@@ -303,136 +291,229 @@ assign_exact_kernel(const T* __restrict__ x, const T* __restrict__ cent, const f
   }
 }
 
-// Re-scoring of the listed keys (bf16), one workgroup per key.  A first pass scores every
-// centroid in fp32 (16 lanes per centroid row, so the loads are whole contiguous rows; the order
-// of that sum is free, its error is inside the bound below) and leaves the scores in LDS.  Only
-// centroids whose fp32 score is within the bound of the fp32 maximum can be the double-precision
-// argmax; those few (typically two) are then scored in double precision, in order.  Any score
-// that does not compare (NaN) counts as a candidate, so odd inputs fall back to the full scan.
-constexpr int kRescoreMaxB = 4096;   // scores kept in LDS
-__global__ void __launch_bounds__(256, 5)
+// Re-scoring of the listed keys (bf16).  The keys are listed per KV head; a workgroup takes 32
+// consecutive entries of one head's list as the B operand of the matrix instruction (every wave
+// holds the same 32 keys) and its sixteen waves share out the centroid tiles, so a centroid row is
+// read once for 32 keys.
+//   pass 1: fp32 scores of all centroids on the matrix cores, running maximum per key;
+//   pass 2: the same instructions again (same results bit for bit); every centroid whose score is
+//           within the error bound of the key's maximum goes into a candidate list in LDS.  Any
+//           centroid that can be the double-precision argmax is among them, because both fp32
+//           scores carry at most half the bound as error; a score that does not compare (NaN)
+//           counts as a candidate;
+//   pass 3: the candidates (typically two per key) in double precision, in order, one per thread;
+//           then one thread per key picks the largest, lowest id on ties.
+// If the list overflows (degenerate keys, e.g. all scores equal) the group's keys are scored
+// against every centroid in double precision instead.
+// Grid: (workgroups per head, Hkv).  counters[h] = length of head h's list, counters[Hkv] =
+// workgroups that have finished.
+constexpr int kGroupKeys = 32;
+constexpr int kCandCap = 2048;
+constexpr int kRescoreThreads = 1024, kRescoreWaves = kRescoreThreads / 64;
+
+// double-precision score of centroid row c against key row xr (in order), rows of 16-byte pieces
+__device__ __forceinline__ double score_bf16_f64(const uint4* __restrict__ xr, const uint4* __restrict__ c) {
+  // The loads and conversions stay inside the (rarely taken) candidate path: hoisted out of a
+  // caller's loop the key's 128 doubles would hold 256 registers for the whole kernel.
+  asm volatile("" ::: "memory");
+  double t = 0.0;
+#pragma unroll
+  for (int hh = 0; hh < 2; ++hh) {   // half a row of each in flight, then that half of the chain
+    uint4 xw[kD / 16], cw[kD / 16];
+#pragma unroll
+    for (int j = 0; j < kD / 16; ++j) {
+      xw[j] = xr[hh * (kD / 16) + j];
+      cw[j] = c[hh * (kD / 16) + j];
+    }
+#pragma unroll
+    for (int j = 0; j < kD / 16; ++j) {
+      const uint32_t w[4] = {cw[j].x, cw[j].y, cw[j].z, cw[j].w}, v[4] = {xw[j].x, xw[j].y, xw[j].z, xw[j].w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        t = fma((double)bf16_lo(v[k]), (double)bf16_lo(w[k]), t);
+        t = fma((double)bf16_hi(v[k]), (double)bf16_hi(w[k]), t);
+      }
+    }
+  }
+  return t;
+}
+
+__device__ __forceinline__ bool better(double s, int id, double best, int best_id) {
+  return id >= 0 && (best_id < 0 || s > best || (s == best && id < best_id));
+}
+
+__global__ void __launch_bounds__(kRescoreThreads)
 assign_rescore_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent,
                       const float* __restrict__ bias, const float* __restrict__ cmax,
                       int32_t* __restrict__ ids, const int32_t* __restrict__ rows,
-                      unsigned* __restrict__ counters, unsigned* __restrict__ stat, int Hkv, int N, int B,
-                      float tol) {
-  __shared__ float s_score[kRescoreMaxB];
-  __shared__ __align__(16) uint4 s_x[kD / 8];
-  __shared__ float s_wmax[4];
-  __shared__ double s_best[4];
-  __shared__ int s_id[4];
+                      unsigned* __restrict__ counters, unsigned* __restrict__ stat, size_t list_cap, int Hkv,
+                      int N, int B, float tol) {
+  typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+  __shared__ float s_max[kRescoreWaves][kGroupKeys];
+  __shared__ float s_lim[kGroupKeys];
+  __shared__ int s_key[kGroupKeys];        // global row of each key of the group
+  __shared__ unsigned s_ncand;
+  __shared__ int s_cand[kCandCap];         // key << 24 | centroid
+  __shared__ double s_cscore[kCandCap];
+  __shared__ double s_wbest[kRescoreWaves];
+  __shared__ int s_wid[kRescoreWaves];
+  __shared__ int s_flag;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int piece = lane & 15, sub = lane >> 4;
-  const unsigned n_rows = counters[0];   // counters[1]: workgroups that have finished
-  for (unsigned i = blockIdx.x; i < n_rows; i += gridDim.x) {
-    const size_t g = (size_t)rows[i];
-    const int h = (int)((g / (size_t)N) % (size_t)Hkv);
-    const bf16_t* xr = x + g * kD;
-    const bf16_t* cu = cent + (size_t)h * B * kD;
-    const float* bu = bias ? bias + (size_t)h * B : nullptr;
-    Vec8<bf16_t> xv;
-    xv.load(xr + piece * 8);
-    const float xnorm2 = sum16(xv.dot(xv));
-    if (tid < 16) s_x[piece] = xv.r;
+  const int col = lane & 31, half = lane >> 5;
+  const int h = blockIdx.y;
+  const unsigned n_rows = counters[h];
+  const unsigned n_groups = (n_rows + kGroupKeys - 1) / kGroupKeys;
+  rows += (size_t)h * list_cap;
+  const bf16_t* cu = cent + (size_t)h * B * kD;
+  const float* bu = bias ? bias + (size_t)h * B : nullptr;
+  const int n_tiles = (B + kCentTile - 1) / kCentTile;
 
-    // pass 1: fp32 scores of all centroids; a wave takes 4 rows per load, the workgroup 16
+  for (unsigned grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
+    const unsigned first = grp * kGroupKeys;
+    const int n_here = (int)min((unsigned)kGroupKeys, n_rows - first);
+    // B operand: lane holds features 16*step + 8*half .. +7 of key `col` (idle columns repeat the last key)
+    const int gk = rows[first + min(col, n_here - 1)];
+    const bf16_t* xr = x + (size_t)gk * kD + half * 8;
+    bf16x8_t xb[8];
+    float xnorm2 = 0.f;
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      Vec8<bf16_t> v;
+      v.load(xr + st * 16);
+      xb[st] = __builtin_bit_cast(bf16x8_t, v.r);
+      xnorm2 += v.dot(v);
+    }
+    xnorm2 += __shfl_xor(xnorm2, 32);
+    if (tid < kGroupKeys) s_key[tid] = gk;
+    if (tid == 0) s_ncand = 0u;
+
+    // scores of centroid tile t for the 32 keys: register r of this lane is centroid
+    // 32*t + 8*(r/4) + 4*half + r%4 against key `col`
+    auto tile_scores = [&](int t) {
+      bf16x8_t a[8];
+      const bf16_t* cr = cu + (size_t)min(t * kCentTile + col, B - 1) * kD + half * 8;
+#pragma unroll
+      for (int st = 0; st < 8; ++st) a[st] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(cr + st * 16));
+      f32x16_t acc = {0};
+#pragma unroll
+      for (int st = 0; st < 8; ++st) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[st], xb[st], acc, 0, 0, 0);
+      return acc;
+    };
+    auto centroid_of = [&](int t, int r) { return t * kCentTile + 8 * (r / 4) + 4 * half + (r % 4); };
+
     float mx = -INFINITY;
-    for (int bb = 0; bb < B; bb += 128) {
-      const int b0 = bb + wave * 4 + sub;
-      Vec8<bf16_t> cv[8];
+    for (int t = wave; t < n_tiles; t += kRescoreWaves) {
+      const f32x16_t acc = tile_scores(t);
 #pragma unroll
-      for (int u = 0; u < 8; ++u) cv[u].load(cu + (size_t)min(b0 + 16 * u, B - 1) * kD + piece * 8);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int b = b0 + 16 * u;
-        float sc = sum16(cv[u].dot(xv));
-        if (b < B) {
-          if (bu) sc += bu[b];
-          if (piece == 0) s_score[b] = sc;
-          mx = fmaxf(mx, sc);
-        }
+      for (int r = 0; r < 16; ++r) {
+        const int b = centroid_of(t, r);
+        if (b < B) mx = fmaxf(mx, acc[r] + (bu ? bu[b] : 0.f));
       }
     }
-    mx = max_rows(mx);
-    if (lane == 0) s_wmax[wave] = mx;
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    if (half == 0) s_max[wave][col] = mx;
     __syncthreads();
-    const float m = fmaxf(fmaxf(s_wmax[0], s_wmax[1]), fmaxf(s_wmax[2], s_wmax[3]));
-    // two fp32 scores are compared: the same bound as for the matrix-core scores
-    const float lim = m - (tol * cmax[h] * sqrtf(xnorm2) + 5e-6f * fabsf(m));
-
-    // pass 2: double precision for the candidates
-    double best = 0.0;
-    int best_id = -1;
-    for (int b = tid; b < B; b += 256) {
-      if (s_score[b] < lim) continue;
-      const uint4* c = reinterpret_cast<const uint4*>(cu + (size_t)b * kD);
-      // the key's conversions to double stay inside the (rarely taken) candidate path: hoisted
-      // out of the loop they would hold 256 registers for the whole kernel
-      asm volatile("" ::: "memory");
-      uint4 craw[kD / 8];   // the whole row in flight, then the chain
-#pragma unroll
-      for (int j = 0; j < kD / 8; ++j) craw[j] = c[j];
-      double t = 0.0;
-#pragma unroll
-      for (int j = 0; j < kD / 8; ++j) {
-        const uint4 cw = craw[j], xw = s_x[j];
-        const uint32_t w[4] = {cw.x, cw.y, cw.z, cw.w}, v[4] = {xw.x, xw.y, xw.z, xw.w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          t = fma((double)bf16_lo(v[k]), (double)bf16_lo(w[k]), t);
-          t = fma((double)bf16_hi(v[k]), (double)bf16_hi(w[k]), t);
-        }
-      }
-      if (bu) t += (double)bu[b];
-      if (best_id < 0 || t > best) {
-        best = t;
-        best_id = b;
-      }
-    }
-    // larger score wins, lower id on equal scores; a lane without candidate has id -1
-    for (int o = 1; o < 64; o <<= 1) {
-      const double ob = __shfl_xor(best, o);
-      const int oid = __shfl_xor(best_id, o);
-      if (oid >= 0 && (best_id < 0 || ob > best || (ob == best && oid < best_id))) {
-        best = ob;
-        best_id = oid;
-      }
-    }
-    if (lane == 0) {
-      s_best[wave] = best;
-      s_id[wave] = best_id;
+    if (tid < kGroupKeys) {
+      float m = s_max[0][tid];
+      for (int w = 1; w < kRescoreWaves; ++w) m = fmaxf(m, s_max[w][tid]);
+      // two fp32 scores are compared: the same bound as for the first matrix pass
+      s_lim[tid] = m - (tol * cmax[h] * sqrtf(xnorm2) + 5e-6f * fabsf(m));
     }
     __syncthreads();
-    if (tid == 0) {
-      for (int w = 1; w < 4; ++w) {
-        const double ob = s_best[w];
-        const int oid = s_id[w];
-        if (oid >= 0 && (best_id < 0 || ob > best || (ob == best && oid < best_id))) {
-          best = ob;
-          best_id = oid;
+    const float lim = s_lim[col];
+    for (int t = wave; t < n_tiles; t += kRescoreWaves) {
+      const f32x16_t acc = tile_scores(t);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int b = centroid_of(t, r);
+        const float sc = acc[r] + (bu ? bu[b < B ? b : 0] : 0.f);
+        if (b < B && col < n_here && !(sc < lim)) {
+          const unsigned i = atomicAdd(&s_ncand, 1u);
+          if (i < (unsigned)kCandCap) s_cand[i] = (col << 24) | b;
         }
       }
-      ids[g] = best_id;
+    }
+    __syncthreads();
+    const unsigned n_cand = s_ncand;
+    if (n_cand <= (unsigned)kCandCap) {
+      for (unsigned i = tid; i < n_cand; i += kRescoreThreads) {
+        const int key = s_cand[i] >> 24, b = s_cand[i] & 0xffffff;
+        double t = score_bf16_f64(reinterpret_cast<const uint4*>(x + (size_t)s_key[key] * kD),
+                                  reinterpret_cast<const uint4*>(cu + (size_t)b * kD));
+        if (bu) t += (double)bu[b];
+        s_cscore[i] = t;
+      }
+      __syncthreads();
+      if (tid < n_here) {
+        double best = 0.0;
+        int best_id = -1;
+        for (unsigned i = 0; i < n_cand; ++i) {
+          const int key = s_cand[i] >> 24, b = s_cand[i] & 0xffffff;
+          if (key == tid && better(s_cscore[i], b, best, best_id)) {
+            best = s_cscore[i];
+            best_id = b;
+          }
+        }
+        ids[s_key[tid]] = best_id;
+      }
+    } else {
+      // too many candidates: every key of the group against every centroid in double precision
+      for (int key = 0; key < n_here; ++key) {
+        const uint4* xk = reinterpret_cast<const uint4*>(x + (size_t)s_key[key] * kD);
+        double best = 0.0;
+        int best_id = -1;
+        for (int b = tid; b < B; b += kRescoreThreads) {
+          double t = score_bf16_f64(xk, reinterpret_cast<const uint4*>(cu + (size_t)b * kD));
+          if (bu) t += (double)bu[b];
+          if (better(t, b, best, best_id)) {
+            best = t;
+            best_id = b;
+          }
+        }
+        for (int o = 1; o < 64; o <<= 1) {
+          const double ob = __shfl_xor(best, o);
+          const int oid = __shfl_xor(best_id, o);
+          if (better(ob, oid, best, best_id)) {
+            best = ob;
+            best_id = oid;
+          }
+        }
+        if (lane == 0) {
+          s_wbest[wave] = best;
+          s_wid[wave] = best_id;
+        }
+        __syncthreads();
+        if (tid == 0) {
+          for (int w = 1; w < kRescoreWaves; ++w)
+            if (better(s_wbest[w], s_wid[w], best, best_id)) {
+              best = s_wbest[w];
+              best_id = s_wid[w];
+            }
+          ids[s_key[key]] = best_id;
+        }
+        __syncthreads();
+      }
     }
     __syncthreads();
   }
-  // Every workgroup has read the list length by now; the last one to leave keeps it for
-  // diagnostics and leaves both counters zero for the next call.
+  // Every workgroup has read its list length by now; the last one to leave keeps the total for
+  // diagnostics and leaves all counters zero for the next call.
   __syncthreads();
-  if (tid == 0) {
-    if (atomicAdd(counters + 1, 1u) == gridDim.x - 1) {
-      *stat = n_rows;
-      counters[0] = 0u;
-      counters[1] = 0u;
+  if (tid == 0) s_flag = atomicAdd(counters + Hkv, 1u) == gridDim.x * gridDim.y - 1 ? 1 : 0;
+  __syncthreads();
+  if (s_flag) {
+    unsigned total = 0;
+    for (int i = tid; i < Hkv; i += kRescoreThreads) {
+      total += __hip_atomic_load(counters + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      counters[i] = 0u;
     }
+    if (tid == 0) {
+      *stat = 0u;
+      counters[Hkv] = 0u;
+    }
+    __syncthreads();
+    if (total) atomicAdd(stat, total);
   }
-}
-
-// Leaves the arrival counter zero again; the number of re-scored keys of this call is kept in
-// the scratch area for diagnostics.
-__global__ void clear_counter_kernel(unsigned* c, unsigned* stat) {
-  *stat = *c;
-  *c = 0u;
 }
 
 }  // namespace
@@ -456,20 +537,20 @@ extern "C" int32_t saap_assign_keys(const void* x, const void* centroids, const 
   if (d != kD) return SAAP_UNSUPPORTED;
   const long long units = (long long)S * Hkv;
   const long long rows = units * N;
-  if (rows > 0x7fffffffLL || units > 65535 || Hkv > 4095) return SAAP_UNSUPPORTED;
+  if (rows > 0x7fffffffLL || units > 65535 || Hkv > 4095 || B >= (1 << 24)) return SAAP_UNSUPPORTED;
   if (ws_bytes < assign_workspace_bytes(rows)) return SAAP_WORKSPACE_TOO_SMALL;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   const int cus = device_cus();
 
   if (dtype == SAAP_F32) {
     const long long grid = rows < (long long)cus * 8 ? rows : (long long)cus * 8;
-    hipLaunchKernelGGL(assign_exact_kernel<float>, dim3((unsigned)grid), dim3(256), 0, hs,
-                       static_cast<const float*>(x), static_cast<const float*>(centroids), bias, bucket_ids,
-                       (const int32_t*)nullptr, (const unsigned*)nullptr, rows, Hkv, N, B);
+    hipLaunchKernelGGL(assign_exact_f32_kernel, dim3((unsigned)grid), dim3(256), 0, hs, static_cast<const float*>(x),
+                       static_cast<const float*>(centroids), bias, bucket_ids, rows, Hkv, N, B);
     return launch_status();
   }
 
-  unsigned* n_flagged = reinterpret_cast<unsigned*>(ws);   // header word 0, zero on entry
+  unsigned* n_flagged = reinterpret_cast<unsigned*>(ws);   // header words 0..Hkv, zero on entry: list lengths, arrivals
+  const size_t list_cap = (size_t)S * N;                   // entries per head's list
   float* cmax = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   int32_t* flagged = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES + 16384);
   const bf16_t* xb = static_cast<const bf16_t*>(x);
@@ -481,18 +562,14 @@ extern "C" int32_t saap_assign_keys(const void* x, const void* centroids, const 
   const dim3 grid((unsigned)((N + kRowsPerWg - 1) / kRowsPerWg), (unsigned)units);
   if (bias)
     hipLaunchKernelGGL(assign_mfma_kernel<true>, grid, dim3(256), 0, hs, xb, cb, bias, cmax, bucket_ids, flagged,
-                       n_flagged, Hkv, N, B, tol);
+                       n_flagged, list_cap, Hkv, N, B, tol);
   else
     hipLaunchKernelGGL(assign_mfma_kernel<false>, grid, dim3(256), 0, hs, xb, cb, bias, cmax, bucket_ids,
-                       flagged, n_flagged, Hkv, N, B, tol);
+                       flagged, n_flagged, list_cap, Hkv, N, B, tol);
   unsigned* stat = reinterpret_cast<unsigned*>(cmax) + 4095;
-  if (B <= kRescoreMaxB) {
-    hipLaunchKernelGGL(assign_rescore_kernel, dim3((unsigned)(cus * 8)), dim3(256), 0, hs, xb, cb, bias, cmax,
-                       bucket_ids, flagged, n_flagged, stat, Hkv, N, B, tol);
-  } else {
-    hipLaunchKernelGGL(assign_exact_kernel<bf16_t>, dim3((unsigned)(cus * 8)), dim3(256), 0, hs, xb, cb, bias,
-                       bucket_ids, flagged, n_flagged, rows, Hkv, N, B);
-    hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, hs, n_flagged, stat);
-  }
+  // workgroups per head: enough to fill the chip twice over all heads together
+  const unsigned per_head = (unsigned)((cus * 2 + Hkv - 1) / Hkv);
+  hipLaunchKernelGGL(assign_rescore_kernel, dim3(per_head, (unsigned)Hkv), dim3(kRescoreThreads), 0, hs, xb, cb, bias, cmax,
+                     bucket_ids, flagged, n_flagged, stat, list_cap, Hkv, N, B, tol);
   return launch_status();
 }
