@@ -186,7 +186,7 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
     }
   };
 
-  f32x16_t a0, a1, b0, b1;
+  f32x16_t a0, a1, b0 = {0}, b1 = {0};   // b0, b1: not read by the first step
   step(0, 0, a0, a1, b0, b1, 0, true, false);
   for (int t = 0; t < n_slabs - 1; ++t) {
     const int buf = t & 1;
@@ -347,7 +347,7 @@ assign_rescore_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ c
                       const float* __restrict__ bias, const float* __restrict__ cmax,
                       int32_t* __restrict__ ids, const int32_t* __restrict__ rows,
                       unsigned* __restrict__ counters, unsigned* __restrict__ stat, size_t list_cap, int Hkv,
-                      int N, int B, float tol) {
+                      int B, float tol) {
   typedef __attribute__((ext_vector_type(16))) float f32x16_t;
   __shared__ float s_max[kRescoreWaves][kGroupKeys];
   __shared__ float s_lim[kGroupKeys];
@@ -570,6 +570,6 @@ extern "C" int32_t saap_assign_keys(const void* x, const void* centroids, const 
   // workgroups per head: enough to fill the chip twice over all heads together
   const unsigned per_head = (unsigned)((cus * 2 + Hkv - 1) / Hkv);
   hipLaunchKernelGGL(assign_rescore_kernel, dim3(per_head, (unsigned)Hkv), dim3(kRescoreThreads), 0, hs, xb, cb, bias, cmax,
-                     bucket_ids, flagged, n_flagged, stat, list_cap, Hkv, N, B, tol);
+                     bucket_ids, flagged, n_flagged, stat, list_cap, Hkv, B, tol);
   return launch_status();
 }

@@ -458,7 +458,7 @@ template <int CHUNKS /* 16-byte pieces per row */>
 __global__ void __launch_bounds__(256)
 recopy_kernel(const int32_t* __restrict__ off, const int32_t* __restrict__ len, const int32_t* __restrict__ off_new,
               const int32_t* __restrict__ idx, int32_t* __restrict__ idx_new, const uint4* __restrict__ Ks,
-              const uint4* __restrict__ Vs, uint4* __restrict__ Kn, uint4* __restrict__ Vn, int runs, int B, int Ncap,
+              const uint4* __restrict__ Vs, uint4* __restrict__ Kn, uint4* __restrict__ Vn, int runs, int Ncap,
               int Ncap_new, const int32_t* __restrict__ overflow) {
   if (*overflow) return;                       // the new cache is too small: nothing is moved
   const int b = blockIdx.x, unit = blockIdx.y, tid = threadIdx.x;
@@ -690,12 +690,12 @@ extern "C" int32_t saap_recompact_index(const int32_t* off, const int32_t* len, 
   if (dtype == SAAP_BF16)
     hipLaunchKernelGGL(recopy_kernel<16>, grid, dim3(256), 0, hs, off, len, off_new, idx, idx_new,
                        static_cast<const uint4*>(Ksorted), static_cast<const uint4*>(Vsorted),
-                       static_cast<uint4*>(Ksorted_new), static_cast<uint4*>(Vsorted_new), runs, B, Ncap, Ncap_new,
+                       static_cast<uint4*>(Ksorted_new), static_cast<uint4*>(Vsorted_new), runs, Ncap, Ncap_new,
                        overflow_flag);
   else
     hipLaunchKernelGGL(recopy_kernel<32>, grid, dim3(256), 0, hs, off, len, off_new, idx, idx_new,
                        static_cast<const uint4*>(Ksorted), static_cast<const uint4*>(Vsorted),
-                       static_cast<uint4*>(Ksorted_new), static_cast<uint4*>(Vsorted_new), runs, B, Ncap, Ncap_new,
+                       static_cast<uint4*>(Ksorted_new), static_cast<uint4*>(Vsorted_new), runs, Ncap, Ncap_new,
                        overflow_flag);
   return launch_status();
 }
