@@ -39,6 +39,10 @@ def lib():
         _lib.ref_append_keys.restype = ctypes.c_int
         _lib.ref_window_push.restype = ctypes.c_int
         _lib.ref_recompact_index.restype = ctypes.c_int
+        _lib.ref_fp8_e4m3_decode.restype = ctypes.c_float
+        _lib.ref_fp8_e4m3_decode.argtypes = [ctypes.c_uint8]
+        _lib.ref_fp8_e4m3_encode.restype = ctypes.c_uint8
+        _lib.ref_fp8_e4m3_encode.argtypes = [ctypes.c_float]
     return _lib
 
 
@@ -201,6 +205,34 @@ def update_centroids(x, ids, centroids_old, normalize=True):
     out = np.empty((Hkv, B, d), dtype=np.float64)
     lib().ref_update_centroids(_p(x), _p(ids), _p(c), _p(out), S, Hkv, N, B, d, 1 if normalize else 0)
     return out
+
+
+def fp8_e4m3_decode(code: int) -> float:
+    return float(lib().ref_fp8_e4m3_decode(int(code)))
+
+
+def fp8_e4m3_encode(x: float) -> int:
+    return int(lib().ref_fp8_e4m3_encode(float(x)))
+
+
+def quantize_fp8(x):
+    """x [S,Hkv,rows,d] -> codes uint8 [S,Hkv,rows,d], scale float32 [S,Hkv] (one power of two per unit)."""
+    x = _f32(x)
+    S, Hkv, rows, d = x.shape
+    codes = np.empty(x.shape, dtype=np.uint8)
+    scale = np.empty((S, Hkv), dtype=np.float32)
+    lib().ref_quantize_fp8(_p(x), _p(codes), _p(scale), ctypes.c_longlong(S * Hkv), ctypes.c_longlong(rows), d)
+    return codes, scale
+
+
+def dequantize_fp8(codes, scale):
+    """codes uint8 [S,Hkv,rows,d], scale [S,Hkv] -> float32 [S,Hkv,rows,d] = scale * value(code), exact."""
+    codes = np.ascontiguousarray(np.asarray(codes, dtype=np.uint8))
+    scale = _f32(scale)
+    S, Hkv, rows, d = codes.shape
+    x = np.empty(codes.shape, dtype=np.float32)
+    lib().ref_dequantize_fp8(_p(codes), _p(scale), _p(x), ctypes.c_longlong(S * Hkv), ctypes.c_longlong(rows), d)
+    return x
 
 
 def classify_queries(xq, W1, b1, W2, b2, Hkv, output_kind=0):

@@ -15,7 +15,8 @@
  * is that restricted softmax written out; Algorithms 1 and 2 of Appendix F are
  * one way of evaluating it and are deliberately NOT followed here.
  *
- * Parity pins (tests/test_oracle_*.py): numpy brute force on tiny inputs,
+ * Parity pins (tests/test_oracle_*.py): numpy brute force on tiny inputs, the FP8 code table
+ * against the format and its encoder against a nearest-value search,
  * closed forms (equal keys -> mean of values, one key -> its value), nprobe = B
  * equals dense attention, library softmax/matmul/argsort, CSR invariants, the
  * balanced-selectivity column of the paper's Table "nprobe_selectivity".
@@ -491,6 +492,77 @@ void ref_update_centroids(const float* x, const int32_t* ids, const float* cent_
         for (int e = 0; e < d; ++e) c[e] /= nrm;
       }
     }
+}
+
+/*
+ * 8-bit storage of the bucket-sorted K/V (the paper calls compression of the cached vectors
+ * complementary to the partition, Section 2 "Vector search based on partitions" / related work;
+ * it fixes no format, so this is a reading: OCP FP8 E4M3 -- 1 sign, 4 exponent bits with
+ * bias 7, 3 mantissa bits, subnormals, no infinities, largest finite value 448, codes 0x7f and
+ * 0xff are NaN -- with one power-of-two scale per (sequence, KV head) and tensor:
+ *   scale = 2^e, e the smallest integer with max|x| <= 448 * 2^e  (scale = 1 for an all-zero unit)
+ *   code  = round-to-nearest-even of x / scale on the E4M3 grid
+ * Attention on such a cache is attention on the decoded values scale * value(code), which are
+ * exact in float, so the attention oracle above applies to them unchanged.
+ */
+float ref_fp8_e4m3_decode(uint8_t code) {
+  const int sign = code >> 7, e = (code >> 3) & 15, m = code & 7;
+  double v;
+  if (e == 15 && m == 7) return NAN;
+  if (e == 0) v = ldexp((double)m, -9);                 /* subnormal: m * 2^-6 / 8 */
+  else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+  return (float)(sign ? -v : v);
+}
+
+uint8_t ref_fp8_e4m3_encode(float x) {
+  const uint8_t sign = signbit(x) ? 0x80 : 0x00;
+  double a = fabs((double)x);
+  if (isnan(x)) return 0x7f;
+  if (a >= 448.0) return sign | 0x7e;                   /* saturate (never reached below: |x| <= 448) */
+  if (a < ldexp(1.0, -6)) {                             /* subnormal grid: multiples of 2^-9 */
+    const int q = (int)nearbyint(ldexp(a, 9));          /* ties to even; q = 8 is the smallest normal */
+    return sign | (uint8_t)q;
+  }
+  int ex;
+  const double f = frexp(a, &ex);                       /* a = f * 2^ex, f in [0.5, 1) */
+  int e = ex - 1;                                       /* a = (2f) * 2^e, 2f in [1, 2) */
+  int q = (int)nearbyint((2.0 * f - 1.0) * 8.0);        /* ties to even */
+  if (q == 8) {
+    q = 0;
+    e += 1;
+  }
+  return sign | (uint8_t)(((e + 7) << 3) | q);
+}
+
+/* scale of one unit: 2^e with the smallest e such that amax <= 448 * 2^e; 448 = 0.875 * 2^9 */
+static float fp8_unit_scale(float amax) {
+  if (!(amax > 0.f)) return 1.f;
+  int ex;
+  const float f = frexpf(amax, &ex);                    /* amax = f * 2^ex, f in [0.5, 1) */
+  int e = f <= 0.875f ? ex - 9 : ex - 8;
+  if (e < -100) e = -100;
+  if (e > 100) e = 100;
+  return ldexpf(1.f, e);
+}
+
+/* x [units, rows, d] -> codes [units, rows, d], scale [units] */
+void ref_quantize_fp8(const float* x, uint8_t* codes, float* scale, long long units, long long rows, int d) {
+  for (long long u = 0; u < units; ++u) {
+    const float* xu = x + (size_t)u * rows * d;
+    float amax = 0.f;
+    for (long long i = 0; i < rows * d; ++i)
+      if (fabsf(xu[i]) > amax) amax = fabsf(xu[i]);
+    const float sc = fp8_unit_scale(amax);
+    scale[u] = sc;
+    for (long long i = 0; i < rows * d; ++i) codes[(size_t)u * rows * d + i] = ref_fp8_e4m3_encode(xu[i] / sc);
+  }
+}
+
+/* codes [units, rows, d], scale [units] -> x [units, rows, d] = scale * value(code) (exact in float) */
+void ref_dequantize_fp8(const uint8_t* codes, const float* scale, float* x, long long units, long long rows, int d) {
+  for (long long u = 0; u < units; ++u)
+    for (long long i = 0; i < rows * d; ++i)
+      x[(size_t)u * rows * d + i] = scale[u] * ref_fp8_e4m3_decode(codes[(size_t)u * rows * d + i]);
 }
 
 /* Selectivity (Section 6.1): the fraction of keys that take part in the
