@@ -379,6 +379,51 @@ int32_t saap_update_centroids(const void* x_sorted, const int32_t* off, const in
                               int32_t S, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype,
                               int32_t normalize, void* stream);
 
+/*
+ * quantize_kv -- 8-bit copy of a bucket-sorted K/V cache.  Section 2 (related work) calls
+ * compression of the cached vectors complementary to the partition and fixes no format; here:
+ * OCP FP8 E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, subnormals, no
+ * infinities, largest finite value 448) with one power-of-two scale per (sequence, KV head)
+ * and tensor.  It halves the bytes the decode attention reads per key (256 instead of 512).
+ *   scale = 2^e, e the smallest integer with max|x| <= 448 * 2^e (1 for an all-zero unit);
+ *   code  = x / scale rounded to the nearest E4M3 value, ties to even.
+ *   Ksorted, Vsorted [S,Hkv,Ncap,d] dtype (device, finite values; free slots count as data)
+ *   K8, V8 [S,Hkv,Ncap,d] uint8, out;  kscale, vscale [S,Hkv] fp32, out
+ * off, len, idx of the index stay valid for the 8-bit copy.
+ * Workspace: SAAP_WS_HEADER_BYTES suffice.
+ */
+int32_t saap_quantize_kv(const void* Ksorted, const void* Vsorted, uint8_t* K8, uint8_t* V8,
+                         float* kscale, float* vscale,
+                         int32_t S, int32_t Hkv, int32_t Ncap, int32_t d, int32_t dtype,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * sparse_decode_attention_fp8 / dense_decode_attention_fp8 -- saap_sparse_decode_attention and
+ * saap_dense_decode_attention on a cache written by saap_quantize_kv: the attention is that of
+ * the decoded values kscale * value(K8), vscale * value(V8) (exact softmax over the visited
+ * keys, fp32 accumulation), K and V are read as one byte per feature.
+ *   q [S,Hq,d] bf16; K8, V8 [S,Hkv,Ncap,d] uint8; kscale, vscale [S,Hkv] fp32
+ *   the remaining arguments as in the 16-bit calls (mode: SAAP_GROUP_SUM lists [S,Hkv,nprobe]
+ *   or SAAP_INDEPENDENT lists [S,Hq,nprobe], the latter read per head)
+ *   dense: off != NULL as in saap_dense_decode_attention (a bucket-sorted cache), B buckets
+ * Workspace: as SAAP_OP_SPARSE_DECODE_ATTENTION / SAAP_OP_DENSE_DECODE_ATTENTION.
+ */
+int32_t saap_sparse_decode_attention_fp8(const void* q, const uint8_t* K8, const uint8_t* V8,
+                                         const float* kscale, const float* vscale,
+                                         const int32_t* off, const int32_t* len,
+                                         const int32_t* selected, int32_t nprobe, int32_t mode,
+                                         float scale, void* out, int32_t out_dtype, float* lse,
+                                         int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
+                                         int32_t d,
+                                         void* ws, size_t ws_bytes, void* stream);
+
+int32_t saap_dense_decode_attention_fp8(const void* q, const uint8_t* K8, const uint8_t* V8,
+                                        const float* kscale, const float* vscale,
+                                        const int32_t* off, const int32_t* len, int32_t B,
+                                        float scale, void* out, int32_t out_dtype, float* lse,
+                                        int32_t S, int32_t Hq, int32_t Hkv, int32_t N, int32_t d,
+                                        void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

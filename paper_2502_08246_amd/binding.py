@@ -28,6 +28,7 @@ EXPORTS = (
     "saap_select_buckets", "saap_sparse_decode_attention", "saap_dense_decode_attention", "saap_stream_read_probe",
     "saap_build_windowed_index", "saap_window_push", "saap_windowed_decode_attention",
     "saap_select_buckets_from_logits", "saap_update_centroids", "saap_recompact_index",
+    "saap_quantize_kv", "saap_sparse_decode_attention_fp8", "saap_dense_decode_attention_fp8",
 )
 
 
@@ -260,6 +261,66 @@ def sparse_decode_attention(q, Ks, Vs, off, ln, selected, scale, mode=GROUP_SUM,
         _i32(nprobe), _i32(mode), ctypes.c_float(scale), _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S),
         _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _ptr(ws), wsb, _stream())
     _check("saap_sparse_decode_attention", st)
+    return out, lse
+
+
+def quantize_kv(Ks, Vs, ws=None):
+    """Ks, Vs [S,Hkv,Ncap,d] (bucket-sorted) -> K8, V8 uint8 [S,Hkv,Ncap,d] (OCP FP8 E4M3 codes),
+    kscale, vscale fp32 [S,Hkv] (one power of two per unit)."""
+    S, Hkv, Ncap, d = Ks.shape
+    dev = Ks.device
+    K8 = torch.empty(S, Hkv, Ncap, d, dtype=torch.uint8, device=dev)
+    V8 = torch.empty(S, Hkv, Ncap, d, dtype=torch.uint8, device=dev)
+    ks = torch.empty(S, Hkv, dtype=torch.float32, device=dev)
+    vs = torch.empty(S, Hkv, dtype=torch.float32, device=dev)
+    if ws is None:
+        ws = workspace(WS_HEADER_BYTES, dev)
+    st = load_library().saap_quantize_kv(_ptr(Ks), _ptr(Vs), _ptr(K8), _ptr(V8), _ptr(ks), _ptr(vs), _i32(S), _i32(Hkv),
+                                         _i32(Ncap), _i32(d), _i32(_dtype_code(Ks)), _ptr(ws),
+                                         ctypes.c_size_t(ws.numel()), _stream())
+    _check("saap_quantize_kv", st)
+    return K8, V8, ks, vs
+
+
+def sparse_decode_attention_fp8(q, K8, V8, kscale, vscale, off, ln, selected, scale, mode=GROUP_SUM,
+                                out_dtype=torch.float32, out=None, lse=None, ws=None):
+    """sparse_decode_attention on a cache written by quantize_kv; q bf16 [S,Hq,d]."""
+    if q.dtype != torch.bfloat16 or K8.dtype != torch.uint8 or V8.dtype != torch.uint8:
+        raise TypeError("q must be bf16, K8 and V8 uint8")
+    S, Hq, d = q.shape
+    _, Hkv, Ncap, _ = K8.shape
+    B = ln.shape[2]
+    nprobe = selected.shape[2]
+    dev = q.device
+    out = out if out is not None else torch.empty(S, Hq, d, dtype=out_dtype, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Hq, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_SPARSE_DECODE_ATTENTION, dev, ws, S=S, Hq=Hq, Hkv=Hkv, mode=mode)
+    st = load_library().saap_sparse_decode_attention_fp8(
+        _ptr(q), _ptr(K8), _ptr(V8), _ptr(kscale), _ptr(vscale), _ptr(off), _ptr(ln),
+        _ptr(selected) if nprobe > 0 else ctypes.c_void_p(0), _i32(nprobe), _i32(mode), ctypes.c_float(scale),
+        _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S), _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(B), _i32(d),
+        _ptr(ws), wsb, _stream())
+    _check("saap_sparse_decode_attention_fp8", st)
+    return out, lse
+
+
+def dense_decode_attention_fp8(q, K8, V8, kscale, vscale, scale, off=None, ln=None, out_dtype=torch.float32,
+                               out=None, lse=None, ws=None):
+    """dense_decode_attention on 8-bit K/V (packed, or a bucket-sorted cache with off/ln); q bf16."""
+    if q.dtype != torch.bfloat16 or K8.dtype != torch.uint8 or V8.dtype != torch.uint8:
+        raise TypeError("q must be bf16, K8 and V8 uint8")
+    S, Hq, d = q.shape
+    _, Hkv, N, _ = K8.shape
+    B = ln.shape[2] if ln is not None else 0
+    dev = q.device
+    out = out if out is not None else torch.empty(S, Hq, d, dtype=out_dtype, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Hq, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_DENSE_DECODE_ATTENTION, dev, ws, S=S, Hq=Hq, Hkv=Hkv)
+    st = load_library().saap_dense_decode_attention_fp8(
+        _ptr(q), _ptr(K8), _ptr(V8), _ptr(kscale), _ptr(vscale), _ptr(off), _ptr(ln), _i32(B), ctypes.c_float(scale),
+        _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S), _i32(Hq), _i32(Hkv), _i32(N), _i32(d), _ptr(ws), wsb,
+        _stream())
+    _check("saap_dense_decode_attention_fp8", st)
     return out, lse
 
 

@@ -54,7 +54,10 @@ struct AttnParams {
   int out_bf16;
   int n_dense;            // keys per unit in dense mode
   float scale_log2;       // scale * log2(e)
+  const float* kscale;    // 8-bit cache: [kv units] scale of the K codes, else null
+  const float* vscale;    // 8-bit cache: [kv units] scale of the V codes, else null
 };
+constexpr int kDtypeFp8 = 2;   // internal dtype code of an 8-bit cache (queries are bf16)
 
 // Partial results cross workgroups inside one launch.  The writer stores them write-through to
 // the device-coherent level and counts its arrival once the stores are acknowledged; the last
@@ -85,8 +88,8 @@ __device__ __forceinline__ void lse_merge(int n, FM get_m, FL get_l, FO get_o, f
   }
 }
 
-__device__ __forceinline__ void store_out(const AttnParams& p, int qrow, int e, float M, float l, float o) {
-  float r = l > 0.f ? o / l : 0.f;
+__device__ __forceinline__ void store_out(const AttnParams& p, int qrow, int e, float M, float l, float o, float vs) {
+  float r = l > 0.f ? vs * (o / l) : 0.f;
   if (p.out_bf16) reinterpret_cast<bf16_t*>(p.out)[(size_t)qrow * kD + e] = (bf16_t)f32_to_bf16_bits(r);
   else reinterpret_cast<float*>(p.out)[(size_t)qrow * kD + e] = r;
   if (e == 0 && p.lse) p.lse[qrow] = l > 0.f ? (M + __log2f(l)) * kLn2 : -INFINITY;
@@ -162,7 +165,9 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   constexpr int nw = NT / 64;
   constexpr int KB = G == 8 ? 2 : 4;            // keys a key processor has in flight per batch
   constexpr int C = KB * G;                     // (key, head) combinations per batch: 4, 8 or 16
-  constexpr bool kPrefetch = sizeof(T) == 2;    // fp32 rows are too wide to double-buffer
+  constexpr bool kPrefetch = sizeof(T) <= 2;    // fp32 rows are too wide to double-buffer
+  constexpr bool kFp8 = sizeof(T) == 1;
+  typedef typename DotType<T>::type TQ;         // queries of an 8-bit cache are bf16
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane & 15, grp = lane >> 4;
   const int c_own = sub & (C - 1);              // the combination this lane owns after the reduction
@@ -185,9 +190,15 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   const T* Vb = reinterpret_cast<const T*>(p.V) + (size_t)kvu * p.rows * kD + sub * 8;
 
   // query slices: 8 features of each of the G heads
-  Vec8<T> qv[G];
+  Vec8<TQ> qv[G];
 #pragma unroll
-  for (int g = 0; g < G; ++g) qv[g].load(reinterpret_cast<const T*>(p.q) + (size_t)(qrow0 + g) * kD + sub * 8);
+  for (int g = 0; g < G; ++g) qv[g].load(reinterpret_cast<const TQ*>(p.q) + (size_t)(qrow0 + g) * kD + sub * 8);
+  // 8-bit cache: the codes' scales fold into the score scale and into the final division
+  float scale_log2 = p.scale_log2, vs = 1.f;
+  if constexpr (kFp8) {
+    scale_log2 *= p.kscale[kvu];
+    vs = p.vscale[kvu];
+  }
 
   constexpr int NG = nw * 4;            // key processors in the workgroup
   constexpr int chunk = NG * KB;        // keys the workgroup consumes per batch
@@ -414,14 +425,16 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     // partial dot products of the lane's 8 features, all (key slot, head) combinations ...
     float d[C];
 #pragma unroll
-    for (int i = 0; i < KB; ++i)
+    for (int i = 0; i < KB; ++i) {
+      const Vec8<TQ> kw = dot_operand(bt.k[i]);
 #pragma unroll
-      for (int g = 0; g < G; ++g) d[i * G + g] = bt.k[i].dot(qv[g]);
+      for (int g = 0; g < G; ++g) d[i * G + g] = kw.dot(qv[g]);
+    }
     // ... reduced over the 16 lanes so that each lane ends up with ONE complete score
     const float dot = reduce_scatter16<C>(d, sub);
     bool live = (bt.valid >> i_own) & 1u;
     if constexpr (MASKED) live = live && ((bt.heads >> (8 * i_own + c_own % G)) & 1u);
-    const float t = live ? dot * p.scale_log2 : -INFINITY;
+    const float t = live ? dot * scale_log2 : -INFINITY;
     // Algorithm 1, one step per batch: the head's running maximum lives in the lanes that own it
     const float bm = ror_max<G, C>(t);
     const float mn = fmaxf(m, bm);
@@ -545,7 +558,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
       Ov = fmaf(w, w_o[(j * G + g) * kD + e], Ov);
     }
     if (p.P == 1) {
-      store_out(p, qrow0 + g, e, M, L, Ov);
+      store_out(p, qrow0 + g, e, M, L, Ov, vs);
     } else {
       const size_t slot = ((size_t)unit * p.P + wg) * G + g;
       coherent_store(&p.part_o[slot * kD + e], Ov);
@@ -677,7 +690,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
       r.x += a.x; r.y += a.y; r.z += a.z; r.w += a.w;
     }
     const float L = s_L[g_col], M = s_M[g_col];
-    const float inv = L > 0.f ? 1.0f / L : 0.f;
+    const float inv = L > 0.f ? vs * (1.0f / L) : 0.f;   // vs: scale of an 8-bit cache's V codes, else 1
     r.x *= inv; r.y *= inv; r.z *= inv; r.w *= inv;
     const int qrow = qrow0 + g_col, e0 = (colx % (kD / 4)) * 4;
     if (p.out_bf16) {
@@ -770,7 +783,14 @@ int32_t launch_masked(const AttnParams& p, const LaunchPlan& lp, int G, int dtyp
 template <bool LIST>
 int32_t launch_attn(const AttnParams& p, const LaunchPlan& lp, int G, int dtype, hipStream_t stream) {
 #define SAAP_CASE(TT, GG) return launch_one<TT, GG, LIST>(p, lp, stream)
-  if (dtype == SAAP_BF16) {
+  if (dtype == kDtypeFp8) {
+    switch (G) {
+      case 1: SAAP_CASE(fp8_t, 1);
+      case 2: SAAP_CASE(fp8_t, 2);
+      case 4: SAAP_CASE(fp8_t, 4);
+      case 8: SAAP_CASE(fp8_t, 8);
+    }
+  } else if (dtype == SAAP_BF16) {
     switch (G) {
       case 1: SAAP_CASE(bf16_t, 1);
       case 2: SAAP_CASE(bf16_t, 2);
@@ -805,7 +825,7 @@ static int32_t check_common(const void* q, const void* K, const void* V, void* o
   if (!q || !K || !V || !out || !ws) return SAAP_INVALID_ARG;
   if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(out) || !aligned16(ws)) return SAAP_INVALID_ARG;
   if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return SAAP_INVALID_ARG;
-  if ((dtype != SAAP_F32 && dtype != SAAP_BF16) || (out_dtype != SAAP_F32 && out_dtype != SAAP_BF16))
+  if ((dtype != SAAP_F32 && dtype != SAAP_BF16 && dtype != kDtypeFp8) || (out_dtype != SAAP_F32 && out_dtype != SAAP_BF16))
     return SAAP_INVALID_ARG;
   if (d != kD) return SAAP_UNSUPPORTED;
   const int G = Hq / Hkv;
@@ -815,7 +835,9 @@ static int32_t check_common(const void* q, const void* K, const void* V, void* o
 
 // Attention over the selected runs plus, if resident_run >= 0, one run that is always visited.
 // B = runs per unit in `len`.
-static int32_t sparse_attention(const void* q, const void* Ksorted, const void* Vsorted, const int32_t* off,
+// dtype kDtypeFp8: Ksorted, Vsorted hold E4M3 codes with the per-unit scales kscale, vscale; q is bf16.
+static int32_t sparse_attention(const void* q, const void* Ksorted, const void* Vsorted, const float* kscale,
+                                const float* vscale, const int32_t* off,
                                 const int32_t* len, const int32_t* selected, int32_t nprobe, int32_t mode,
                                 int32_t resident_run, float scale, void* out, int32_t out_dtype, float* lse,
                                 int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d,
@@ -833,7 +855,8 @@ static int32_t sparse_attention(const void* q, const void* Ksorted, const void* 
   // of the heads' lists once, each head attending only its own runs (masked kernels).  They hold
   // 16 buckets per thread at most; beyond that every head is a unit of its own.
   const int heads = Hq / Hkv;
-  const bool masked = indep && heads > 1 && B <= 16 * 512;
+  const bool masked = indep && heads > 1 && B <= 16 * 512 && dtype != kDtypeFp8;
+  if (dtype == kDtypeFp8 && (!kscale || !vscale)) return SAAP_INVALID_ARG;
   const int G = masked ? heads : indep ? 1 : heads;
   const long long units = indep && !masked ? (long long)S * Hq : (long long)S * Hkv;
   if (masked) {
@@ -852,7 +875,7 @@ static int32_t sparse_attention(const void* q, const void* Ksorted, const void* 
   p.rows = Ncap; p.nsel = nprobe; p.resident = resident_run; p.nseg = nseg; p.B = B; p.n_units = (int)units;
   p.Hq = Hq; p.Hkv = Hkv; p.independent = indep && !masked ? 1 : 0; p.masked_lists = masked ? heads : 0;
   p.out_bf16 = out_dtype == SAAP_BF16;
-  p.n_dense = 0; p.scale_log2 = scale * kLog2e;
+  p.n_dense = 0; p.scale_log2 = scale * kLog2e; p.kscale = kscale; p.vscale = vscale;
   // expected keys per unit: balanced buckets, plus the paper's default window for the resident run
   const long long est = (long long)Ncap * (masked ? nseg : nprobe) / B + (resident_run >= 0 ? 2048 : 0);
   LaunchPlan lp = plan_launch((int)units, est, Ncap, G, nseg, true, B, nseg > 0, masked);
@@ -871,8 +894,8 @@ extern "C" int32_t saap_sparse_decode_attention(const void* q, const void* Ksort
                                                 int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
                                                 int32_t d, int32_t dtype, void* ws, size_t ws_bytes,
                                                 void* stream) {
-  return sparse_attention(q, Ksorted, Vsorted, off, len, selected, nprobe, mode, -1, scale, out, out_dtype, lse, S,
-                          Hq, Hkv, Ncap, B, d, dtype, ws, ws_bytes, stream);
+  return sparse_attention(q, Ksorted, Vsorted, nullptr, nullptr, off, len, selected, nprobe, mode, -1, scale, out,
+                          out_dtype, lse, S, Hq, Hkv, Ncap, B, d, dtype, ws, ws_bytes, stream);
 }
 
 extern "C" int32_t saap_windowed_decode_attention(const void* q, const void* Ksorted, const void* Vsorted,
@@ -882,16 +905,16 @@ extern "C" int32_t saap_windowed_decode_attention(const void* q, const void* Kso
                                                   int32_t out_dtype, float* lse, int32_t S, int32_t Hq,
                                                   int32_t Hkv, int32_t Ncap, int32_t runs, int32_t d,
                                                   int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
-  return sparse_attention(q, Ksorted, Vsorted, off, len, selected, nprobe, mode, resident_run, scale, out, out_dtype,
-                          lse, S, Hq, Hkv, Ncap, runs, d, dtype, ws, ws_bytes, stream);
+  return sparse_attention(q, Ksorted, Vsorted, nullptr, nullptr, off, len, selected, nprobe, mode, resident_run, scale,
+                          out, out_dtype, lse, S, Hq, Hkv, Ncap, runs, d, dtype, ws, ws_bytes, stream);
 }
 
-extern "C" int32_t saap_dense_decode_attention(const void* q, const void* K, const void* V,
-                                               const int32_t* off, const int32_t* len, int32_t B,
-                                               float scale, void* out, int32_t out_dtype, float* lse,
-                                               int32_t S, int32_t Hq, int32_t Hkv, int32_t N, int32_t d,
-                                               int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
+static int32_t dense_attention(const void* q, const void* K, const void* V, const float* kscale, const float* vscale,
+                               const int32_t* off, const int32_t* len, int32_t B, float scale, void* out,
+                               int32_t out_dtype, float* lse, int32_t S, int32_t Hq, int32_t Hkv, int32_t N, int32_t d,
+                               int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_common(q, K, V, out, S, Hq, Hkv, d, dtype, out_dtype, ws);
+  if (st == SAAP_OK && dtype == kDtypeFp8 && (!kscale || !vscale)) st = SAAP_INVALID_ARG;
   if (st != SAAP_OK) return st;
   if (N <= 0) return SAAP_INVALID_ARG;
   if ((off == nullptr) != (len == nullptr)) return SAAP_INVALID_ARG;
@@ -909,7 +932,7 @@ extern "C" int32_t saap_dense_decode_attention(const void* q, const void* K, con
   p.part_o = p.part_ml + (size_t)units * kMaxP * G * 2;
   p.rows = N; p.nseg = off ? B : 0; p.nsel = p.nseg; p.resident = -1; p.B = B; p.n_units = (int)units;
   p.Hq = Hq; p.Hkv = Hkv; p.independent = 0; p.out_bf16 = out_dtype == SAAP_BF16;
-  p.n_dense = N; p.scale_log2 = scale * kLog2e;
+  p.n_dense = N; p.scale_log2 = scale * kLog2e; p.kscale = kscale; p.vscale = vscale;
   LaunchPlan lp = plan_launch((int)units, N, N, G, p.nseg, off != nullptr, B, false);
   p.P = lp.P;
   p.stage = 0;
@@ -917,4 +940,37 @@ extern "C" int32_t saap_dense_decode_attention(const void* q, const void* K, con
   p.use_table = 1;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   return off ? launch_attn<true>(p, lp, G, dtype, hs) : launch_attn<false>(p, lp, G, dtype, hs);
+}
+
+extern "C" int32_t saap_dense_decode_attention(const void* q, const void* K, const void* V,
+                                               const int32_t* off, const int32_t* len, int32_t B,
+                                               float scale, void* out, int32_t out_dtype, float* lse,
+                                               int32_t S, int32_t Hq, int32_t Hkv, int32_t N, int32_t d,
+                                               int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
+  if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
+  return dense_attention(q, K, V, nullptr, nullptr, off, len, B, scale, out, out_dtype, lse, S, Hq, Hkv, N, d, dtype,
+                         ws, ws_bytes, stream);
+}
+
+extern "C" int32_t saap_sparse_decode_attention_fp8(const void* q, const uint8_t* K8, const uint8_t* V8,
+                                                    const float* kscale, const float* vscale,
+                                                    const int32_t* off, const int32_t* len,
+                                                    const int32_t* selected, int32_t nprobe, int32_t mode,
+                                                    float scale, void* out, int32_t out_dtype, float* lse,
+                                                    int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
+                                                    int32_t d, void* ws, size_t ws_bytes, void* stream) {
+  if (!kscale || !vscale) return SAAP_INVALID_ARG;
+  return sparse_attention(q, K8, V8, kscale, vscale, off, len, selected, nprobe, mode, -1, scale, out, out_dtype, lse,
+                          S, Hq, Hkv, Ncap, B, d, kDtypeFp8, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t saap_dense_decode_attention_fp8(const void* q, const uint8_t* K8, const uint8_t* V8,
+                                                   const float* kscale, const float* vscale,
+                                                   const int32_t* off, const int32_t* len, int32_t B,
+                                                   float scale, void* out, int32_t out_dtype, float* lse,
+                                                   int32_t S, int32_t Hq, int32_t Hkv, int32_t N, int32_t d,
+                                                   void* ws, size_t ws_bytes, void* stream) {
+  if (!kscale || !vscale) return SAAP_INVALID_ARG;
+  return dense_attention(q, K8, V8, kscale, vscale, off, len, B, scale, out, out_dtype, lse, S, Hq, Hkv, N, d,
+                         kDtypeFp8, ws, ws_bytes, stream);
 }

@@ -161,6 +161,37 @@ template <> struct Vec8<bf16_t> {
   }
 };
 
+// Eight features stored as OCP FP8 E4M3 codes (one byte each); queries against such rows are bf16.
+typedef uint8_t fp8_t;
+template <> struct Vec8<fp8_t> {
+  uint2 r;
+  __device__ __forceinline__ void load(const fp8_t* p) { r = *reinterpret_cast<const uint2*>(p); }
+  __device__ __forceinline__ void to_float(float* o) const {
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.x, true);
+    const f32x2_t c = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.y, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.y, true);
+    o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1]; o[4] = c[0]; o[5] = c[1]; o[6] = d[0]; o[7] = d[1];
+  }
+  // The same eight values as bf16 (exact: an E4M3 value has 4 significant bits), so that the
+  // dot product with a bf16 query runs on v_dot2_f32_bf16.
+  __device__ __forceinline__ Vec8<bf16_t> as_bf16() const {
+    float f[8];
+    to_float(f);
+    Vec8<bf16_t> w;
+    // upper halves of two floats packed into one word
+    w.r.x = __builtin_amdgcn_perm(__float_as_uint(f[1]), __float_as_uint(f[0]), 0x07060302u);
+    w.r.y = __builtin_amdgcn_perm(__float_as_uint(f[3]), __float_as_uint(f[2]), 0x07060302u);
+    w.r.z = __builtin_amdgcn_perm(__float_as_uint(f[5]), __float_as_uint(f[4]), 0x07060302u);
+    w.r.w = __builtin_amdgcn_perm(__float_as_uint(f[7]), __float_as_uint(f[6]), 0x07060302u);
+    return w;
+  }
+};
+// Type of the query rows and of the key operand of the dot product for a cache stored as T.
+template <typename T> struct DotType { typedef T type; };
+template <> struct DotType<fp8_t> { typedef bf16_t type; };
+template <typename T> __device__ __forceinline__ Vec8<T> dot_operand(const Vec8<T>& k) { return k; }
+__device__ __forceinline__ Vec8<bf16_t> dot_operand(const Vec8<fp8_t>& k) { return k.as_bf16(); }
+
 // Order-preserving map float -> uint32 (larger float, larger key); -0 and +0 must be
 // canonicalised by the caller.
 __device__ __forceinline__ uint32_t float_order_key(float f) {
