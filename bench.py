@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense baseline (keeps profiler summaries to the sparse path)")
     ap.add_argument("--window", default="", help="also time the step with an attention sink + recent-key window, "
                     "e.g. 1+2047 (the paper's default): adds a `window` object to the output")
+    ap.add_argument("--kv8", action="store_true",
+                    help="also time the attention and the step on an 8-bit (FP8 E4M3) copy of the cache")
     ap.add_argument("--layers", type=int, default=1,
                     help="also time a decode step through this many layers, each with its own synthetic cache, "
                          "centroids, classifier and index (e.g. 32 with --workload cfg4_layer_262k)")
@@ -299,6 +301,40 @@ def main():
             "overflow_flag": int(w_flag[0].item()),
         }
 
+    kv8_result = None
+    if args.kv8:
+        # the same index over an 8-bit copy of the sorted cache (256 bytes per visited key)
+        K8, V8, k_sc, v_sc = saap.quantize_kv(Ks, Vs)
+        torch.cuda.synchronize()
+        ms_quant = timed(lambda i: saap.quantize_kv(Ks, Vs), 2, torch)
+
+        def attend8_set(i):
+            saap.sparse_decode_attention_fp8(q[i % T], K8, V8, k_sc, v_sc, off, ln, sel_sets[i % T], scale, out=out, lse=lse)
+
+        def step8(i):
+            classify(i)
+            select(i)
+            saap.sparse_decode_attention_fp8(q[i % T], K8, V8, k_sc, v_sc, off, ln, sel, scale, out=out, lse=lse)
+
+        def dense8(i):
+            saap.dense_decode_attention_fp8(q[i % T], K8, V8, k_sc, v_sc, scale, off=off, ln=ln, out=out, lse=lse)
+
+        ms_attn8 = GraphLoop(attend8_set, T, torch).timed_ms_per_call(reps)
+        ms_step8 = GraphLoop(step8, T, torch).timed_ms_per_call(reps)
+        ms_dense8 = None if args.no_dense else GraphLoop(dense8, 8, torch).timed_ms_per_call(3)
+        kv8_result = {
+            "format": "OCP FP8 E4M3, one power-of-two scale per (sequence, KV head) and tensor",
+            "step_us_per_token_layer": round(ms_step8 * 1e3 / cfg.S, 3),
+            "step": "classify_queries (logits) + select_buckets_from_logits + sparse_decode_attention_fp8 (no append)",
+            "sparse_decode_attention_fp8_us": round(ms_attn8 * 1e3, 3),
+            "bytes_per_launch": round(keys_touched * BYTES_PER_KEY / 2),
+            "achieved_GBps": round(keys_touched * BYTES_PER_KEY / 2 / (ms_attn8 * 1e-3) / 1e9, 1),
+            "speedup_vs_16bit_attention": round(ms_attn / ms_attn8, 2),
+            "dense_decode_attention_fp8_us": None if ms_dense8 is None else round(ms_dense8 * 1e3, 3),
+            "quantize_kv_ms": round(ms_quant, 3),
+        }
+        del K8, V8
+
     layers_result = None
     if args.layers > 1:
         # A decode step through L layers: every layer has its own cache (seed + layer), centroids,
@@ -410,6 +446,8 @@ def main():
         result["window"] = window_result
     if layers_result:
         result["model_step"] = layers_result
+    if kv8_result:
+        result["kv8"] = kv8_result
     if with_append:
         result["append_overflow_flag"] = int(a_flag[0].item())
 

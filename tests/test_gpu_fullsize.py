@@ -260,3 +260,47 @@ def test_cfg1_with_the_papers_window_and_fused_selection(saap):
         assert np.array_equal(nid.cpu().numpy(), h_ids[:, :, Nt])
     assert flag[0].item() == 0
     assert int(ln.sum().item()) == cfg.S * cfg.Hkv * (N + steps)
+
+
+def test_cfg1_full_size_8bit_cache(saap):
+    """The benchmark workload on the 8-bit cache: every code and scale against the oracle's encoder,
+    sparse and dense attention against the oracle on the decoded values."""
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"]
+    cache = gen.make_cache(cfg, 0, DEV)
+    cent = gen.make_centroids(cfg, 0, DEV)
+    xq, q = gen.make_queries(cfg, 0, DEV, n_steps=2)
+    W1, b1, W2, b2 = gen.make_classifier(cfg, 0, DEV)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, 0)
+    K8, V8, ks, vs = saap.quantize_kv(Ks, Vs)
+    torch.cuda.synchronize()
+    # slack 0: the sorted cache is a permutation of the positions, so the oracle may quantise the
+    # position-ordered cache (same maxima, same codes per key)
+    hK, hV = h(cache["K"]), h(cache["V"])
+    rK8, rks = ref.quantize_fp8(hK)
+    rV8, rvs = ref.quantize_fp8(hV)
+    assert np.array_equal(ks.cpu().numpy(), rks) and np.array_equal(vs.cpu().numpy(), rvs)
+    h_idx = idx.cpu().numpy().astype(np.int64)
+    gK8, gV8 = K8.cpu().numpy(), V8.cpu().numpy()
+    for hh in range(cfg.Hkv):
+        assert np.array_equal(gK8[0, hh], rK8[0, hh][h_idx[0, hh]]), f"K codes of head {hh} differ"
+        assert np.array_equal(gV8[0, hh], rV8[0, hh][h_idx[0, hh]]), f"V codes of head {hh} differ"
+    Kd, Vd = ref.dequantize_fp8(rK8, rks), ref.dequantize_fp8(rV8, rvs)
+    del hK, hV, rK8, rV8, gK8, gV8
+    scores = torch.empty(cfg.S, cfg.Hq, cfg.B, dtype=torch.float32, device=DEV)
+    sel = torch.empty(cfg.S, cfg.Hkv, cfg.nprobe, dtype=torch.int32, device=DEV)
+    out = torch.empty(cfg.S, cfg.Hq, cfg.d, dtype=torch.float32, device=DEV)
+    lse = torch.empty(cfg.S, cfg.Hq, dtype=torch.float32, device=DEV)
+    h_off, h_ln, h_idx32 = off.cpu().numpy(), ln.cpu().numpy(), idx.cpu().numpy()
+    for t in range(2):
+        saap.classify_queries(xq[t], W1, b1, W2, b2, cfg.Hkv, output_kind=saap.LOGITS, out=scores)
+        saap.select_buckets_from_logits(scores, cfg.Hkv, cfg.nprobe, out=sel)
+        saap.sparse_decode_attention_fp8(q[t], K8, V8, ks, vs, off, ln, sel, SCALE, out=out, lse=lse)
+        o_d, l_d = saap.dense_decode_attention_fp8(q[t], K8, V8, ks, vs, SCALE, off=off, ln=ln)
+        torch.cuda.synchronize()
+        ro, rl = ref.sparse_decode_attention(h(q[t]), Kd, Vd, h_off, h_ln, h_idx32, sel.cpu().numpy(), SCALE)
+        close(out.cpu().numpy(), ro)
+        close(lse.cpu().numpy(), rl)
+        rd, rdl = ref.dense_decode_attention(h(q[t]), Kd, Vd, SCALE)
+        close(o_d.cpu().numpy(), rd)
+        close(l_d.cpu().numpy(), rdl)
