@@ -303,6 +303,17 @@ def dense_decode_attention(q, K, V, scale):
     return out, lse
 
 
+def bucket_attention_mass(q, K, ids, scale, B):
+    """q [S,Hq,d], K [S,Hkv,N,d] position order, ids [S,Hkv,N] -> mass float64 [S,Hq,B]: the share of each
+    query's softmax attention that falls into each bucket (the training target of the query model)."""
+    q, K, ids = _f32(q), _f32(K), _i32(ids)
+    S, Hq, d = q.shape
+    _, Hkv, N, _ = K.shape
+    mass = np.empty((S, Hq, B), dtype=np.float64)
+    lib().ref_bucket_attention_mass(_p(q), _p(K), _p(ids), ctypes.c_float(scale), _p(mass), S, Hq, Hkv, N, B, d)
+    return mass
+
+
 def selectivity(ln, selected, n_keys):
     """ln [lists,B], selected [lists,nprobe] -> mean fraction of keys visited."""
     ln = _i32(ln)

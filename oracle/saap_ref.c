@@ -288,6 +288,41 @@ void ref_dense_decode_attention(const float* q, const float* K, const float* V, 
   }
 }
 
+/* Section 4 "Learning the query assignment", Eq. 1: the query model is trained towards the row of
+ * A * H_k, i.e. the attention mass that falls into each bucket.  For a decode query:
+ *   mass[b] = sum over the keys n with ids[n] = b of softmax_n(scale * <q, k_n>)   (softmax over all N keys)
+ * Written on POSITION-ordered K [S,Hkv,N,d] and ids [S,Hkv,N]; mass [S,Hq,B] sums to 1 per row. */
+void ref_bucket_attention_mass(const float* q, const float* K, const int32_t* ids, float scale, double* mass,
+                               int S, int Hq, int Hkv, int N, int B, int d) {
+  int G = Hq / Hkv;
+  int units = S * Hq;
+#pragma omp parallel for num_threads(g_threads) schedule(dynamic)
+  for (int t = 0; t < units; ++t) {
+    int s = t / Hq, hq = t % Hq, h = hq / G;
+    size_t u = (size_t)s * Hkv + h;
+    const float* qq = q + (size_t)t * d;
+    double* a = (double*)malloc(sizeof(double) * (size_t)N);
+    double amax = -INFINITY;
+    for (int n = 0; n < N; ++n) {
+      const float* k = K + (u * N + n) * d;
+      double x = 0.0;
+      for (int e = 0; e < d; ++e) x += (double)qq[e] * (double)k[e];
+      a[n] = x * (double)scale;
+      if (a[n] > amax) amax = a[n];
+    }
+    double sum = 0.0;
+    double* m = mass + (size_t)t * B;
+    for (int b = 0; b < B; ++b) m[b] = 0.0;
+    for (int n = 0; n < N; ++n) {
+      double w = exp(a[n] - amax);
+      sum += w;
+      m[ids[u * N + n]] += w;
+    }
+    for (int b = 0; b < B; ++b) m[b] /= sum;
+    free(a);
+  }
+}
+
 /* Section 3 "Per-head attention span" + Appendix F: the first n_sink keys (attention
  * sink) and the n_recent most recent keys are always attended; every other key takes
  * part only if its bucket is visited.  Written on POSITION-ordered tensors, no index:
