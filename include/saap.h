@@ -75,7 +75,8 @@ enum {
   SAAP_OP_SPARSE_DECODE_ATTENTION = 4,
   SAAP_OP_DENSE_DECODE_ATTENTION = 5,
   SAAP_OP_APPEND_KEYS = 6,
-  SAAP_OP_WINDOW_PUSH = 7
+  SAAP_OP_WINDOW_PUSH = 7,
+  SAAP_OP_BUCKET_ATTENTION_MASS = 8
 };
 
 #define SAAP_WS_HEADER_BYTES 65536u
@@ -378,6 +379,25 @@ int32_t saap_update_centroids(const void* x_sorted, const int32_t* off, const in
                               const void* centroids_old, void* centroids_new,
                               int32_t S, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype,
                               int32_t normalize, void* stream);
+
+/*
+ * bucket_attention_mass -- the share of a query's softmax attention that falls into each
+ * bucket: the row of A * H_k that the query model is trained towards (Section 4 "Learning the
+ * query assignment", Eq. 1: KL divergence between f_q(q) and that row), and, summed over a
+ * selection, the attention mass the selection captures:
+ *   mass[s,hq,b] = sum over the member slots n of bucket b of softmax_n(scale * <q, k_n>),
+ *   the softmax taken over all member slots of the (sequence, KV head).
+ *   q [S,Hq,d] dtype; Ksorted [S,Hkv,Ncap,d] dtype; off [S,Hkv,B+1], len [S,Hkv,B]
+ *   mass [S,Hq,B] fp32, out (rows sum to 1; all zero for a head without keys)
+ *   lse  [S,Hq] fp32 or NULL, out: log sum_n exp(scale * <q, k_n>) over all member slots
+ * Workspace: SAAP_OP_BUCKET_ATTENTION_MASS (S, Hq, Hkv, B).
+ */
+int32_t saap_bucket_attention_mass(const void* q, const void* Ksorted,
+                                   const int32_t* off, const int32_t* len,
+                                   float scale, float* mass, float* lse,
+                                   int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
+                                   int32_t d, int32_t dtype,
+                                   void* ws, size_t ws_bytes, void* stream);
 
 /*
  * quantize_kv -- 8-bit copy of a bucket-sorted K/V cache.  Section 2 (related work) calls

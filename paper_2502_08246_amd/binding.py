@@ -16,6 +16,7 @@ GROUP_SUM, INDEPENDENT = 0, 1
 PROBS, LOGITS = 0, 1
 OP_ASSIGN_KEYS, OP_BUILD_BUCKET_INDEX, OP_CLASSIFY_QUERIES, OP_SELECT_BUCKETS = 0, 1, 2, 3
 OP_SPARSE_DECODE_ATTENTION, OP_DENSE_DECODE_ATTENTION, OP_APPEND_KEYS, OP_WINDOW_PUSH = 4, 5, 6, 7
+OP_BUCKET_ATTENTION_MASS = 8
 WS_HEADER_BYTES = 65536
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -29,6 +30,7 @@ EXPORTS = (
     "saap_build_windowed_index", "saap_window_push", "saap_windowed_decode_attention",
     "saap_select_buckets_from_logits", "saap_update_centroids", "saap_recompact_index",
     "saap_quantize_kv", "saap_sparse_decode_attention_fp8", "saap_dense_decode_attention_fp8",
+    "saap_bucket_attention_mass",
 )
 
 
@@ -262,6 +264,22 @@ def sparse_decode_attention(q, Ks, Vs, off, ln, selected, scale, mode=GROUP_SUM,
         _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _ptr(ws), wsb, _stream())
     _check("saap_sparse_decode_attention", st)
     return out, lse
+
+
+def bucket_attention_mass(q, Ks, off, ln, scale, out=None, lse=None, ws=None):
+    """q [S,Hq,d]; Ks [S,Hkv,Ncap,d]; off, ln from build_bucket_index -> mass fp32 [S,Hq,B], lse fp32 [S,Hq]."""
+    S, Hq, d = q.shape
+    _, Hkv, Ncap, _ = Ks.shape
+    B = ln.shape[2]
+    dev = q.device
+    mass = out if out is not None else torch.empty(S, Hq, B, dtype=torch.float32, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Hq, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_BUCKET_ATTENTION_MASS, dev, ws, S=S, Hq=Hq, Hkv=Hkv, B=B)
+    st = load_library().saap_bucket_attention_mass(
+        _ptr(q), _ptr(Ks), _ptr(off), _ptr(ln), ctypes.c_float(scale), _ptr(mass), _ptr(lse), _i32(S), _i32(Hq),
+        _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _ptr(ws), wsb, _stream())
+    _check("saap_bucket_attention_mass", st)
+    return mass, lse
 
 
 def quantize_kv(Ks, Vs, ws=None):

@@ -9,6 +9,7 @@ size_t assign_workspace_bytes(long long rows);
 size_t build_workspace_bytes(long long units, int N, int B);
 size_t push_workspace_bytes(long long units, int B);
 size_t classify_workspace_bytes(long long rows, int hidden);
+size_t mass_workspace_bytes(long long units, int G, int B);
 
 int device_cus() {
   static int cus = 0;
@@ -89,6 +90,9 @@ extern "C" size_t saap_workspace_bytes(int32_t op, const saap_shape* sh) {
       return push_workspace_bytes(S * Hkv, sh->B);
     case SAAP_OP_SELECT_BUCKETS:
       return SAAP_WS_HEADER_BYTES;
+    case SAAP_OP_BUCKET_ATTENTION_MASS:
+      if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || sh->B <= 0) return 0;
+      return mass_workspace_bytes(S * Hkv, (int)(Hq / Hkv), sh->B);
     default:
       return 0;
   }
