@@ -47,6 +47,9 @@ def parse():
                     "e.g. 1+2047 (the paper's default): adds a `window` object to the output")
     ap.add_argument("--kv8", action="store_true",
                     help="also time the attention and the step on an 8-bit (FP8 E4M3) copy of the cache")
+    ap.add_argument("--quality", action="store_true",
+                    help="also report the attention mass the selection captures (bucket_attention_mass), for the "
+                         "random-init classifier, for nearest-centroid routing and for the best possible selection")
     ap.add_argument("--layers", type=int, default=1,
                     help="also time a decode step through this many layers, each with its own synthetic cache, "
                          "centroids, classifier and index (e.g. 32 with --workload cfg4_layer_262k)")
@@ -301,6 +304,34 @@ def main():
             "overflow_flag": int(w_flag[0].item()),
         }
 
+    quality_result = None
+    if args.quality:
+        # Share of each query's softmax attention that lies in the visited buckets, mean over heads and
+        # query sets: for the lists of the random-init classifier (the timed step), for the symmetric
+        # "K-means" routing (queries scored against the key centroids, one-layer model) and for the
+        # nprobe buckets that hold the most attention (the ceiling for any router at this nprobe).
+        G = cfg.Hq // cfg.Hkv
+        mass = torch.empty(cfg.S, cfg.Hq, cfg.B, dtype=torch.float32, device=dev)
+        km_scores = torch.empty(cfg.S, cfg.Hq, cfg.B, dtype=torch.float32, device=dev)
+        km_sel = torch.empty(cfg.S, cfg.Hkv, cfg.nprobe, dtype=torch.int32, device=dev)
+        TQ = min(T, 16)
+        acc = {"classifier_random_init": 0.0, "kmeans_routing": 0.0, "best_possible": 0.0}
+        ms_mass = timed(lambda i: saap.bucket_attention_mass(q[i % T], Ks, off, ln, scale, out=mass), 4, torch)
+        for t in range(TQ):
+            saap.bucket_attention_mass(q[t], Ks, off, ln, scale, out=mass)
+            saap.classify_queries(xq[t], None, None, cent, None, cfg.Hkv, out=km_scores)
+            saap.select_buckets(km_scores, cfg.Hkv, cfg.nprobe, out=km_sel)
+            group_mass = mass.view(cfg.S, cfg.Hkv, G, cfg.B)
+            for key, lists in (("classifier_random_init", sel_sets[t]), ("kmeans_routing", km_sel)):
+                idx_q = lists.to(torch.int64).unsqueeze(2).expand(-1, -1, G, -1)
+                acc[key] += float(torch.gather(group_mass, 3, idx_q).sum(-1).mean().item())
+            # best lists under GQA: the nprobe buckets with the largest mass summed over the group
+            best = torch.topk(group_mass.sum(2), cfg.nprobe, dim=-1).indices.unsqueeze(2).expand(-1, -1, G, -1)
+            acc["best_possible"] += float(torch.gather(group_mass, 3, best).sum(-1).mean().item())
+        quality_result = {k: round(v / TQ, 4) for k, v in acc.items()}
+        quality_result.update({"query_sets": TQ, "metric": "mean share of softmax attention mass inside the visited buckets",
+                               "bucket_attention_mass_us": round(ms_mass * 1e3, 2)})
+
     kv8_result = None
     if args.kv8:
         # the same index over an 8-bit copy of the sorted cache (256 bytes per visited key)
@@ -448,6 +479,8 @@ def main():
         result["model_step"] = layers_result
     if kv8_result:
         result["kv8"] = kv8_result
+    if quality_result:
+        result["routing_quality"] = quality_result
     if with_append:
         result["append_overflow_flag"] = int(a_flag[0].item())
 

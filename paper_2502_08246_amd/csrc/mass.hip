@@ -6,7 +6,7 @@
 //
 // Two kernels over the bucket-sorted cache (only K is read, 256 bytes per bf16 key):
 //   * partial: a wave takes whole buckets (contiguous runs of rows); 16 lanes read one row with
-//     one 16-byte load each, four rows per group in flight; per bucket and head it keeps the
+//     one 16-byte load each, eight rows per group in flight; per bucket and head it keeps the
 //     maximum m of t = log2(e) * scale * <q,k> and s = sum 2^(t - m), and writes (m, s);
 //   * normalise: per query head, M = max_b m_b, L = sum_b s_b 2^(m_b - M), mass_b = s_b 2^(m_b - M) / L.
 #include "common.h"
@@ -15,6 +15,7 @@ namespace saap {
 namespace {
 
 constexpr int kMassThreads = 256;
+constexpr int kInFlight = 8;      // rows a 16-lane group has in flight
 
 template <typename T, int G>
 __global__ void __launch_bounds__(kMassThreads)
@@ -36,24 +37,25 @@ mass_partial_kernel(const T* __restrict__ q, const T* __restrict__ K, const int3
       m[g] = kNegBig;
       s[g] = 0.f;
     }
-    for (int r0 = grp; r0 < n; r0 += 16) {      // rows r0, r0+4, r0+8, r0+12 of this 16-lane group
-      Vec8<T> kv[4];
+    for (int r0 = grp; r0 < n; r0 += 4 * kInFlight) {      // rows r0, r0+4, ... of this 16-lane group
+      Vec8<T> kv[kInFlight];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) kv[u].load(Kb + (size_t)(first + min(r0 + 4 * u, n - 1)) * kD);
-      float t[4][G];
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          const float d = sum16(kv[u].dot(qv[g])) * scale_log2;
-          t[u][g] = r0 + 4 * u < n ? d : -INFINITY;
-        }
+      for (int u = 0; u < kInFlight; ++u) kv[u].load(Kb + (size_t)(first + min(r0 + 4 * u, n - 1)) * kD);
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const float bm = fmaxf(fmaxf(t[0][g], t[1][g]), fmaxf(t[2][g], t[3][g]));   // finite: row r0 is real
+        float t[kInFlight];
+        float bm = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) {
+          const float d = sum16(kv[u].dot(qv[g])) * scale_log2;
+          t[u] = r0 + 4 * u < n ? d : -INFINITY;
+          bm = fmaxf(bm, t[u]);                           // finite: row r0 is real
+        }
         const float mn = fmaxf(m[g], bm);
-        s[g] = s[g] * fast_exp2(m[g] - mn) + fast_exp2(t[0][g] - mn) + fast_exp2(t[1][g] - mn) +
-               fast_exp2(t[2][g] - mn) + fast_exp2(t[3][g] - mn);
+        float acc = s[g] * fast_exp2(m[g] - mn);
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) acc += fast_exp2(t[u] - mn);
+        s[g] = acc;
         m[g] = mn;
       }
     }
