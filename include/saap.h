@@ -76,7 +76,8 @@ enum {
   SAAP_OP_DENSE_DECODE_ATTENTION = 5,
   SAAP_OP_APPEND_KEYS = 6,
   SAAP_OP_WINDOW_PUSH = 7,
-  SAAP_OP_BUCKET_ATTENTION_MASS = 8
+  SAAP_OP_BUCKET_ATTENTION_MASS = 8,
+  SAAP_OP_QUERY_MODEL_LOSS_GRADS = 9   /* shape: Hkv = weight sets, N = rows per set, d, hidden, B */
 };
 
 #define SAAP_WS_HEADER_BYTES 65536u
@@ -398,6 +399,47 @@ int32_t saap_bucket_attention_mass(const void* q, const void* Ksorted,
                                    int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
                                    int32_t d, int32_t dtype,
                                    void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * ---- training of the query model (Section 4 "Query assignment function", Eq. 1) ----
+ * The two-layer model of saap_classify_queries in fp32:
+ *   z = W2 relu(W1 x + b1) + b2,  f_q(x) = softmax(z)
+ *   W1 [Hw,hidden,d], b1 [Hw,hidden], W2 [Hw,B,hidden], b2 [Hw,B]   (device, fp32; Hw weight sets)
+ */
+typedef struct {
+  float* W1;
+  float* b1;
+  float* W2;
+  float* b2;
+} saap_mlp_f32;   /* host struct of device pointers */
+
+/*
+ * query_model_loss_grads -- loss of Eq. 1 and its gradients for one batch per weight set:
+ *   L[w] = 1/R sum_r sum_b T[w,r,b] (log T[w,r,b] - log f_q(x[w,r])[b]),   0 log 0 = 0
+ * the Kullback-Leibler divergence between the target rows T (rows of A * H_k: the bucket
+ * attention mass of saap_bucket_attention_mass) and the model's distributions, averaged over
+ * the batch.  The derivative of relu at 0 is 0.
+ *   x [Hw,R,d] x_dtype; target [Hw,R,B] fp32 (>= 0); params: the model; grads: out, same shapes
+ *   loss [Hw] fp32, out.  params and grads are host structs.
+ * Sums run in a fixed order: the same inputs give the same bits.
+ * Workspace: SAAP_OP_QUERY_MODEL_LOSS_GRADS.
+ */
+int32_t saap_query_model_loss_grads(const void* x, const float* target,
+                                    const saap_mlp_f32* params /* host */,
+                                    const saap_mlp_f32* grads /* host */, float* loss,
+                                    int32_t Hw, int32_t R, int32_t d, int32_t hidden, int32_t B,
+                                    int32_t x_dtype, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * adam_update -- one step of Adam (the optimiser named in the paper's training details) on one
+ * tensor of n fp32 elements, in place:
+ *   m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2
+ *   p -= lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps),   step >= 1
+ * A training step of the query model is saap_query_model_loss_grads followed by this call on
+ * W1, b1, W2 and b2.
+ */
+int32_t saap_adam_update(float* param, const float* grad, float* m, float* v, size_t n,
+                         int32_t step, float lr, float beta1, float beta2, float eps, void* stream);
 
 /*
  * quantize_kv -- 8-bit copy of a bucket-sorted K/V cache.  Section 2 (related work) calls

@@ -16,7 +16,7 @@ GROUP_SUM, INDEPENDENT = 0, 1
 PROBS, LOGITS = 0, 1
 OP_ASSIGN_KEYS, OP_BUILD_BUCKET_INDEX, OP_CLASSIFY_QUERIES, OP_SELECT_BUCKETS = 0, 1, 2, 3
 OP_SPARSE_DECODE_ATTENTION, OP_DENSE_DECODE_ATTENTION, OP_APPEND_KEYS, OP_WINDOW_PUSH = 4, 5, 6, 7
-OP_BUCKET_ATTENTION_MASS = 8
+OP_BUCKET_ATTENTION_MASS, OP_QUERY_MODEL_LOSS_GRADS = 8, 9
 WS_HEADER_BYTES = 65536
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -30,7 +30,7 @@ EXPORTS = (
     "saap_build_windowed_index", "saap_window_push", "saap_windowed_decode_attention",
     "saap_select_buckets_from_logits", "saap_update_centroids", "saap_recompact_index",
     "saap_quantize_kv", "saap_sparse_decode_attention_fp8", "saap_dense_decode_attention_fp8",
-    "saap_bucket_attention_mass",
+    "saap_bucket_attention_mass", "saap_query_model_loss_grads", "saap_adam_update",
 )
 
 
@@ -280,6 +280,50 @@ def bucket_attention_mass(q, Ks, off, ln, scale, out=None, lse=None, ws=None):
         _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _ptr(ws), wsb, _stream())
     _check("saap_bucket_attention_mass", st)
     return mass, lse
+
+
+class _MlpF32(ctypes.Structure):
+    _fields_ = [("W1", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("W2", ctypes.c_void_p), ("b2", ctypes.c_void_p)]
+
+
+def _mlp_struct(tensors):
+    for t in tensors:
+        if t.dtype != torch.float32:
+            raise TypeError("the query model is trained in fp32")
+    return _MlpF32(*(_ptr(t) for t in tensors))
+
+
+def query_model_loss_grads(x, target, params, grads=None, loss=None, ws=None):
+    """x [Hw,R,d] (bf16 or fp32), target fp32 [Hw,R,B], params = (W1 [Hw,hidden,d], b1 [Hw,hidden], W2 [Hw,B,hidden],
+    b2 [Hw,B]) fp32 -> loss fp32 [Hw], grads (tuple shaped like params)."""
+    Hw, R, d = x.shape
+    W1, b1, W2, b2 = params
+    hidden, B = W1.shape[1], W2.shape[1]
+    if W1.shape != (Hw, hidden, d) or b1.shape != (Hw, hidden) or W2.shape != (Hw, B, hidden) or b2.shape != (Hw, B):
+        raise ValueError("parameter shapes do not fit x")
+    if target.shape != (Hw, R, B) or target.dtype != torch.float32:
+        raise ValueError("target must be fp32 [Hw,R,B]")
+    dev = x.device
+    grads = grads if grads is not None else tuple(torch.empty_like(p) for p in params)
+    loss = loss if loss is not None else torch.empty(Hw, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_QUERY_MODEL_LOSS_GRADS, dev, ws, Hkv=Hw, N=R, d=d, hidden=hidden, B=B)
+    ps, gs = _mlp_struct(params), _mlp_struct(grads)
+    st = load_library().saap_query_model_loss_grads(
+        _ptr(x), _ptr(target), ctypes.byref(ps), ctypes.byref(gs), _ptr(loss), _i32(Hw), _i32(R), _i32(d), _i32(hidden),
+        _i32(B), _i32(_dtype_code(x)), _ptr(ws), wsb, _stream())
+    _check("saap_query_model_loss_grads", st)
+    return loss, grads
+
+
+def adam_update(param, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One Adam step on one fp32 tensor, in place (param, m, v)."""
+    for t in (param, grad, m, v):
+        if t.dtype != torch.float32 or t.numel() != param.numel():
+            raise TypeError("adam_update works on fp32 tensors of one size")
+    st = load_library().saap_adam_update(_ptr(param), _ptr(grad), _ptr(m), _ptr(v), ctypes.c_size_t(param.numel()),
+                                         _i32(step), ctypes.c_float(lr), ctypes.c_float(beta1), ctypes.c_float(beta2),
+                                         ctypes.c_float(eps), _stream())
+    _check("saap_adam_update", st)
 
 
 def quantize_kv(Ks, Vs, ws=None):

@@ -1,0 +1,127 @@
+"""GPU parity of the query-model training calls against the float64 oracle (oracle/train_ref.py):
+loss and the four gradient tensors of query_model_loss_grads, the Adam update, a short run of
+training steps, and bit-for-bit reproducibility.
+Tolerances (fp32 sums of up to R or B terms against float64): loss 1e-5 relative; gradients
+|gpu - ref| <= 1e-4 * max|ref| + 1e-4 |ref|; Adam: second moment 2e-6 relative, first moment 4e-7 of its two terms, the step 2e-4 relative."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import train_ref as tr
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+# hyper-parameters as the fp32 numbers the C call receives, so that both sides start from the same values
+LR, B1, B2, EPS = (float(np.float32(v)) for v in (1e-3, 0.9, 0.999, 1e-8))
+
+
+@pytest.fixture(scope="module")
+def saap():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the -m gpu tests need a real device")
+    import paper_2502_08246_amd as lib
+    lib.load_library()
+    return lib
+
+
+def problem(seed, Hw, R, d, hidden, B, dtype=torch.float32):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    x = torch.randn(Hw, R, d, generator=g).to(dtype)
+    T = torch.rand(Hw, R, B, generator=g) ** 4
+    T[:, 0, 0] = 0.0
+    T = T / T.sum(-1, keepdim=True)
+    W1 = torch.randn(Hw, hidden, d, generator=g) / d ** 0.5
+    b1 = 0.1 * torch.randn(Hw, hidden, generator=g)
+    W2 = torch.randn(Hw, B, hidden, generator=g) / hidden ** 0.5
+    b2 = 0.1 * torch.randn(Hw, B, generator=g)
+    return x, T, (W1, b1, W2, b2)
+
+
+def to_dev(ts):
+    return tuple(t.to(DEV).contiguous() for t in ts)
+
+
+def f64(t):
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+@pytest.mark.parametrize("Hw,R,d,hidden,B,dtype", [
+    (2, 70, 128, 64, 37, torch.float32), (1, 129, 128, 96, 200, torch.bfloat16), (3, 33, 40, 17, 5, torch.float32),
+    (1, 300, 128, 512, 1024, torch.float32),
+])
+def test_loss_and_gradients(saap, Hw, R, d, hidden, B, dtype):
+    x, T, params = problem(3, Hw, R, d, hidden, B, dtype)
+    loss, grads = saap.query_model_loss_grads(x.to(DEV), T.to(DEV), to_dev(params))
+    torch.cuda.synchronize()
+    for w in range(Hw):
+        want_loss, want = tr.loss_and_grads(f64(x[w]), f64(T[w]), *(f64(p[w]) for p in params))
+        np.testing.assert_allclose(float(loss[w]), want_loss, rtol=1e-5)
+        for name, g, r in zip(("dW1", "db1", "dW2", "db2"), grads, want):
+            got = f64(g[w])
+            lim = 1e-4 * np.abs(r).max() + 1e-4 * np.abs(r)
+            assert (np.abs(got - r) <= lim).all(), f"{name}[{w}]: max err {np.abs(got - r).max():.3e} of {np.abs(r).max():.3e}"
+
+
+def test_adam_update(saap):
+    g = torch.Generator(device="cpu").manual_seed(9)
+    n = 10_007
+    p, grad = torch.randn(n, generator=g), torch.randn(n, generator=g) * torch.logspace(-8, 2, n)
+    m, v = 0.1 * torch.randn(n, generator=g), torch.rand(n, generator=g) * 1e-3
+    dp, dg, dm, dv = (t.to(DEV) for t in (p, grad, m, v))
+    for step in (1, 2, 7):
+        want_p, want_m, want_v = tr.adam_update(f64(dp), f64(dg), f64(dm), f64(dv), step, LR, B1, B2, EPS)
+        before, m_old = f64(dp), f64(dm)
+        saap.adam_update(dp, dg, dm, dv, step, LR, B1, B2, EPS)
+        torch.cuda.synchronize()
+        # the first moment is a sum of two terms that may cancel: the bound is relative to the terms
+        assert (np.abs(f64(dm) - want_m) <= 4e-7 * (np.abs(m_old) + np.abs(f64(dg)))).all()
+        np.testing.assert_allclose(f64(dv), want_v, rtol=2e-6, atol=1e-30)
+        # the parameter itself is compared through its change (the step is small against the value)
+        err = np.abs((f64(dp) - before) - (want_p - before))
+        assert (err <= 2e-4 * np.abs(want_p - before) + 1.5e-7 * (1 + np.abs(before))).all()   # + one rounding of p
+
+
+def test_training_steps_follow_the_oracle_and_are_reproducible(saap):
+    Hw, R, d, hidden, B = 2, 64, 128, 32, 19
+    x, T, params = problem(5, Hw, R, d, hidden, B)
+    lr, steps = float(np.float32(3e-3)), 5
+
+    def run():
+        P = to_dev(tuple(p.clone() for p in params))
+        M = tuple(torch.zeros_like(p) for p in P)
+        V = tuple(torch.zeros_like(p) for p in P)
+        losses = []
+        dx, dT = x.to(DEV), T.to(DEV)
+        for t in range(1, steps + 1):
+            loss, grads = saap.query_model_loss_grads(dx, dT, P)
+            for p, g, m, v in zip(P, grads, M, V):
+                saap.adam_update(p, g, m, v, t, lr, B1, B2, EPS)
+            losses.append(loss.clone())
+        torch.cuda.synchronize()
+        return torch.stack(losses), P
+
+    losses, P = run()
+    losses2, P2 = run()
+    assert torch.equal(losses, losses2) and all(torch.equal(a, b) for a, b in zip(P, P2))
+    rp = tuple(f64(p) for p in params)
+    mom = (tuple(np.zeros_like(p) for p in rp), tuple(np.zeros_like(p) for p in rp))
+    want = []
+    for t in range(1, steps + 1):
+        l, rp, mom = tr.train_step(f64(x), f64(T), rp, mom, t, lr, B1, B2, EPS)
+        want.append(l)
+    np.testing.assert_allclose(f64(losses), np.stack(want), rtol=2e-4)
+    assert (f64(losses)[-1] < f64(losses)[0]).all()
+    # Adam's first steps have the size lr whatever the gradient, so parameters are compared with an absolute bound
+    for a, b in zip(P, rp):
+        assert np.abs(f64(a) - b).max() < 0.05 * lr * steps
+
+
+def test_training_argument_checks(saap):
+    x, T, params = problem(7, 1, 8, 16, 8, 4)
+    with pytest.raises(ValueError):
+        saap.query_model_loss_grads(x.to(DEV), T[:, :, :3].contiguous().to(DEV), to_dev(params))
+    with pytest.raises(TypeError):
+        saap.query_model_loss_grads(x.to(DEV), T.to(DEV), to_dev(tuple(p.to(torch.bfloat16) for p in params)))
+    p = torch.zeros(4, device=DEV)
+    with pytest.raises(saap.SaapError):
+        saap.adam_update(p, p.clone(), p.clone(), p.clone(), 0, 1e-3)
