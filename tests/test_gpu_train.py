@@ -125,3 +125,18 @@ def test_training_argument_checks(saap):
     p = torch.zeros(4, device=DEV)
     with pytest.raises(saap.SaapError):
         saap.adam_update(p, p.clone(), p.clone(), p.clone(), 0, 1e-3)
+
+
+def test_training_driver_learns_on_a_small_workload(saap):
+    """The whole procedure (targets from bucket_attention_mass, training steps, evaluation through
+    classify_queries + select_buckets) on a small workload: the loss falls and the trained lists capture
+    more attention mass than those of the random-init model."""
+    from paper_2502_08246_amd import train_query_model
+    from synth import gen
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(S=1, Hq=4, Hkv=2, N=6000, B=32, nprobe=4, hidden=64)
+    rep = train_query_model.train(cfg, train_queries=256, eval_queries=32, steps=150, batch=256, lr=3e-3, seed=3)
+    first, last = rep["loss"][0][1], rep["loss"][-1][1]
+    assert last < 0.8 * first
+    cap = rep["captured_attention_mass"]
+    assert cap["trained"] > cap["random_init"] + 0.02
+    assert cap["best_possible"] >= cap["trained"]
