@@ -460,8 +460,8 @@ int32_t saap_quantize_kv(const void* Ksorted, const void* Vsorted, uint8_t* K8, 
                          void* ws, size_t ws_bytes, void* stream);
 
 /*
- * sparse_decode_attention_fp8 / dense_decode_attention_fp8 -- saap_sparse_decode_attention and
- * saap_dense_decode_attention on a cache written by saap_quantize_kv: the attention is that of
+ * sparse_decode_attention_fp8 / windowed_decode_attention_fp8 / dense_decode_attention_fp8 --
+ * saap_sparse_decode_attention, saap_windowed_decode_attention and saap_dense_decode_attention on a cache written by saap_quantize_kv: the attention is that of
  * the decoded values kscale * value(K8), vscale * value(V8) (exact softmax over the visited
  * keys, fp32 accumulation), K and V are read as one byte per feature.
  *   q [S,Hq,d] bf16; K8, V8 [S,Hkv,Ncap,d] uint8; kscale, vscale [S,Hkv] fp32
@@ -478,6 +478,18 @@ int32_t saap_sparse_decode_attention_fp8(const void* q, const uint8_t* K8, const
                                          int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
                                          int32_t d,
                                          void* ws, size_t ws_bytes, void* stream);
+
+/* saap_windowed_decode_attention on an 8-bit cache (saap_quantize_kv applied to the cache of
+ * saap_build_windowed_index): the resident run is visited besides the selected buckets. */
+int32_t saap_windowed_decode_attention_fp8(const void* q, const uint8_t* K8, const uint8_t* V8,
+                                           const float* kscale, const float* vscale,
+                                           const int32_t* off, const int32_t* len,
+                                           const int32_t* selected, int32_t nprobe, int32_t mode,
+                                           int32_t resident_run,
+                                           float scale, void* out, int32_t out_dtype, float* lse,
+                                           int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t runs,
+                                           int32_t d,
+                                           void* ws, size_t ws_bytes, void* stream);
 
 int32_t saap_dense_decode_attention_fp8(const void* q, const uint8_t* K8, const uint8_t* V8,
                                         const float* kscale, const float* vscale,

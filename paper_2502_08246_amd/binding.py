@@ -30,6 +30,7 @@ EXPORTS = (
     "saap_build_windowed_index", "saap_window_push", "saap_windowed_decode_attention",
     "saap_select_buckets_from_logits", "saap_update_centroids", "saap_recompact_index",
     "saap_quantize_kv", "saap_sparse_decode_attention_fp8", "saap_dense_decode_attention_fp8",
+    "saap_windowed_decode_attention_fp8",
     "saap_bucket_attention_mass", "saap_query_model_loss_grads", "saap_adam_update",
 )
 
@@ -447,6 +448,28 @@ def windowed_decode_attention(q, Ks, Vs, off, ln, selected, resident_run, scale,
         _ptr(lse), _i32(S), _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(runs), _i32(d), _i32(_dtype_code(q)), _ptr(ws),
         wsb, _stream())
     _check("saap_windowed_decode_attention", st)
+    return out, lse
+
+
+def windowed_decode_attention_fp8(q, K8, V8, kscale, vscale, off, ln, selected, resident_run, scale, mode=GROUP_SUM,
+                                  out_dtype=torch.float32, out=None, lse=None, ws=None):
+    """windowed_decode_attention on a cache written by quantize_kv; q bf16 [S,Hq,d]."""
+    if q.dtype != torch.bfloat16 or K8.dtype != torch.uint8 or V8.dtype != torch.uint8:
+        raise TypeError("q must be bf16, K8 and V8 uint8")
+    S, Hq, d = q.shape
+    _, Hkv, Ncap, _ = K8.shape
+    runs = ln.shape[2]
+    nprobe = selected.shape[2]
+    dev = q.device
+    out = out if out is not None else torch.empty(S, Hq, d, dtype=out_dtype, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Hq, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_SPARSE_DECODE_ATTENTION, dev, ws, S=S, Hq=Hq, Hkv=Hkv, mode=mode)
+    st = load_library().saap_windowed_decode_attention_fp8(
+        _ptr(q), _ptr(K8), _ptr(V8), _ptr(kscale), _ptr(vscale), _ptr(off), _ptr(ln),
+        _ptr(selected) if nprobe > 0 else ctypes.c_void_p(0), _i32(nprobe), _i32(mode), _i32(resident_run),
+        ctypes.c_float(scale), _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S), _i32(Hq), _i32(Hkv), _i32(Ncap),
+        _i32(runs), _i32(d), _ptr(ws), wsb, _stream())
+    _check("saap_windowed_decode_attention_fp8", st)
     return out, lse
 
 

@@ -964,6 +964,19 @@ extern "C" int32_t saap_sparse_decode_attention_fp8(const void* q, const uint8_t
                           S, Hq, Hkv, Ncap, B, d, kDtypeFp8, ws, ws_bytes, stream);
 }
 
+extern "C" int32_t saap_windowed_decode_attention_fp8(const void* q, const uint8_t* K8, const uint8_t* V8,
+                                                      const float* kscale, const float* vscale,
+                                                      const int32_t* off, const int32_t* len,
+                                                      const int32_t* selected, int32_t nprobe, int32_t mode,
+                                                      int32_t resident_run, float scale, void* out,
+                                                      int32_t out_dtype, float* lse, int32_t S, int32_t Hq,
+                                                      int32_t Hkv, int32_t Ncap, int32_t runs, int32_t d, void* ws,
+                                                      size_t ws_bytes, void* stream) {
+  if (!kscale || !vscale) return SAAP_INVALID_ARG;
+  return sparse_attention(q, K8, V8, kscale, vscale, off, len, selected, nprobe, mode, resident_run, scale, out,
+                          out_dtype, lse, S, Hq, Hkv, Ncap, runs, d, kDtypeFp8, ws, ws_bytes, stream);
+}
+
 extern "C" int32_t saap_dense_decode_attention_fp8(const void* q, const uint8_t* K8, const uint8_t* V8,
                                                    const float* kscale, const float* vscale,
                                                    const int32_t* off, const int32_t* len, int32_t B,

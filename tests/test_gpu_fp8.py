@@ -183,3 +183,31 @@ def test_fp8_argument_checks(saap):
         ctypes.c_float(SCALE), ctypes.c_void_p(out.data_ptr()), 0, ctypes.c_void_p(0), 1, 4, 1, 64, 2, 128, 2,
         ctypes.c_void_p(ws.data_ptr()), ctypes.c_size_t(ws.numel()), ctypes.c_void_p(0))
     assert st != 0
+
+
+@pytest.mark.parametrize("n_sink,n_recent,nprobe", [(1, 255, 5), (4, 60, 0), (0, 64, 16)])
+def test_windowed_attention_fp8(saap, n_sink, n_recent, nprobe):
+    """The always-visited run (attention sink + recent keys) on the 8-bit cache, against the oracle's
+    position-based definition on the decoded values."""
+    S, Hq, Hkv, N, B = 1, 8, 2, 5000, 16
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(S=S, Hq=Hq, Hkv=Hkv, N=N, B=B, nprobe=max(nprobe, 1), dtype="bf16", hidden=64)
+    cache = gen.make_cache(cfg, 53, DEV)
+    cent = gen.make_centroids(cfg, 53, DEV, cache, n_train=2048)
+    _, q = gen.make_queries(cfg, 53, DEV, n_steps=2)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs, res = saap.build_windowed_index(ids, cache["K"], cache["V"], B, 4, n_sink, n_recent)
+    K8, V8, ks, vs = saap.quantize_kv(Ks, Vs)
+    torch.cuda.synchronize()
+    h_idx = idx.cpu().numpy()
+    Kp = position_order(ref.dequantize_fp8(K8.cpu().numpy(), ks.cpu().numpy()), h_idx)
+    Vp = position_order(ref.dequantize_fp8(V8.cpu().numpy(), vs.cpu().numpy()), h_idx)
+    assert Kp.shape[2] == N
+    rng = np.random.default_rng(3)
+    for t in range(2):
+        sel_np = np.stack([np.stack([rng.permutation(B)[:nprobe] for _ in range(Hkv)]) for _ in range(S)]).astype(np.int32)
+        sel_np = sel_np.reshape(S, Hkv, nprobe)
+        out, lse = saap.windowed_decode_attention_fp8(q[t], K8, V8, ks, vs, off, ln, torch.from_numpy(sel_np).to(DEV), B, SCALE)
+        torch.cuda.synchronize()
+        ro, rl = ref.windowed_decode_attention(h(q[t]), Kp, Vp, ids.cpu().numpy(), sel_np, n_sink, n_recent, np.float32(SCALE), B)
+        assert_close(out.cpu().numpy(), ro, "out")
+        assert_close(lse.cpu().numpy(), rl, "lse")
