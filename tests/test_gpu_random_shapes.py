@@ -1,6 +1,7 @@
 """Seeded sweep over odd shapes: every call of the decode path on small random configurations
 (ragged N, bucket counts that are no power of two, empty buckets, G in {1,2,4,8}, both dtypes, slack,
-nprobe from 0 to B, both routing modes, with and without a resident run) against the oracle.
+nprobe from 0 to B, both routing modes, with and without a resident run; the attention mass per bucket; the
+8-bit copy of the cache and the attention on it) against the oracle.
 Integer results bit for bit, attention within the tolerances of test_gpu_parity.py."""
 import math
 
@@ -108,3 +109,35 @@ def test_random_shape(saap, case):
         ro, rl = ref.sparse_decode_attention(h(q[0]), hK, hV, r_off, r_ln, r_idx, r_sel, SCALE, mode=mode)
     close(out.cpu().numpy(), ro, dtype, "attention out")
     close(lse.cpu().numpy(), rl, dtype, "attention lse")
+
+    # the attention mass per bucket (plain index only: the resident run is no bucket)
+    if not c["window"]:
+        mass, mlse = saap.bucket_attention_mass(q[0], Ks, off, ln, SCALE)
+        torch.cuda.synchronize()
+        r_mass = ref.bucket_attention_mass(h(q[0]), hK, r_ids, np.float32(SCALE), B)
+        atol, rtol = (1e-6, 2e-3) if dtype == "bf16" else (1e-7, 1e-4)
+        err = np.abs(mass.cpu().numpy() - r_mass)
+        assert (err <= atol + rtol * r_mass).all(), f"bucket mass: max err {err.max():.3e}"
+
+    # the same attention on the 8-bit copy of the cache, against the oracle on the decoded values
+    if dtype == "bf16":
+        K8, V8, ks, vs = saap.quantize_kv(Ks, Vs)
+        torch.cuda.synchronize()
+        # free slots of the sorted cache hold zeros, so the scales are those of the position-ordered tensors
+        rK8, rks = ref.quantize_fp8(hK)
+        rV8, rvs = ref.quantize_fp8(hV)
+        assert np.array_equal(ks.cpu().numpy(), rks) and np.array_equal(vs.cpu().numpy(), rvs), "8-bit scales"
+        for s_ in range(S):
+            for hh in range(Hkv):
+                m = r_idx[s_, hh] >= 0
+                assert np.array_equal(K8.cpu().numpy()[s_, hh][m], rK8[s_, hh][r_idx[s_, hh][m]]), "K codes"
+                assert np.array_equal(V8.cpu().numpy()[s_, hh][m], rV8[s_, hh][r_idx[s_, hh][m]]), "V codes"
+        Kd, Vd = ref.dequantize_fp8(rK8, rks), ref.dequantize_fp8(rV8, rvs)
+        out8, lse8 = saap.windowed_decode_attention_fp8(q[0], K8, V8, ks, vs, off, ln, d_sel, resident, SCALE, mode=mode)
+        torch.cuda.synchronize()
+        if c["window"]:
+            ro, rl = ref.windowed_decode_attention(h(q[0]), Kd, Vd, r_ids, r_sel, n_sink, n_recent, SCALE, B, mode=mode)
+        else:
+            ro, rl = ref.sparse_decode_attention(h(q[0]), Kd, Vd, r_off, r_ln, r_idx, r_sel, SCALE, mode=mode)
+        close(out8.cpu().numpy(), ro, dtype, "8-bit attention out")
+        close(lse8.cpu().numpy(), rl, dtype, "8-bit attention lse")
