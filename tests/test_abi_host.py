@@ -139,3 +139,79 @@ def test_binding_refuses_host_tensors():
     c = torch.zeros(1, 4, 128)
     with pytest.raises(ValueError):
         saap.assign_keys(x, c, out=torch.zeros(1, 1, 8, dtype=torch.int32), ws=torch.zeros(1 << 20, dtype=torch.uint8))
+
+
+def test_invalid_arguments_of_the_later_calls_are_rejected_on_the_host(lib):
+    """8-bit cache, bucket attention mass and the training calls: argument checks fail before anything is enqueued."""
+    q, K, V, off, ln, sel, out, lse, ws, ks, vs = _fake(11)
+    i32, f32 = ctypes.c_int32, ctypes.c_float
+    big, small = ctypes.c_size_t(1 << 30), ctypes.c_size_t(1024)
+
+    def quant(**kw):
+        a = dict(K=K, ks=ks, S=1, Hkv=2, Ncap=64, d=128, dt=1, wsb=big)
+        a.update(kw)
+        return lib.saap_quantize_kv(a["K"], V, out, lse, a["ks"], vs, i32(a["S"]), i32(a["Hkv"]), i32(a["Ncap"]), i32(a["d"]),
+                                    i32(a["dt"]), ws, a["wsb"], None)
+
+    assert quant(K=None) == -1 and quant(ks=None) == -1 and quant(Ncap=0) == -1 and quant(dt=2) == -1
+    assert quant(d=64) == -2 and quant(S=70000) == -2 and quant(wsb=small) == -3
+
+    def sparse8(**kw):
+        a = dict(ks=ks, nprobe=4, mode=0, Hq=4, Hkv=1, B=8, odt=0, wsb=big)
+        a.update(kw)
+        return lib.saap_sparse_decode_attention_fp8(q, K, V, a["ks"], vs, off, ln, sel, i32(a["nprobe"]), i32(a["mode"]),
+                                                    f32(0.1), out, i32(a["odt"]), lse, i32(1), i32(a["Hq"]), i32(a["Hkv"]),
+                                                    i32(100), i32(a["B"]), i32(128), ws, a["wsb"], None)
+
+    assert sparse8(ks=None) == -1 and sparse8(nprobe=9) == -1 and sparse8(mode=3) == -1 and sparse8(odt=5) == -1
+    assert sparse8(Hq=3) == -2 and sparse8(wsb=small) == -3
+    st = lib.saap_dense_decode_attention_fp8(q, K, V, ks, None, None, None, i32(0), f32(0.1), out, i32(0), lse, i32(1), i32(4),
+                                             i32(1), i32(100), i32(128), ws, big, None)
+    assert st == -1                                         # vscale missing
+    st = lib.saap_windowed_decode_attention_fp8(q, K, V, ks, vs, off, ln, sel, i32(4), i32(0), i32(9), f32(0.1), out, i32(0),
+                                                lse, i32(1), i32(4), i32(1), i32(100), i32(9), i32(128), ws, big, None)
+    assert st == -1                                         # the resident run must be one of the runs
+    # the 16-bit entry points do not accept the internal code of the 8-bit cache
+    st = lib.saap_sparse_decode_attention(q, K, V, off, ln, sel, i32(4), i32(0), f32(0.1), out, i32(0), lse, i32(1), i32(4),
+                                          i32(1), i32(100), i32(8), i32(128), i32(2), ws, big, None)
+    assert st == -1
+
+    def mass(**kw):
+        a = dict(q=q, m=out, Hq=4, Hkv=1, B=8, d=128, dt=1, wsb=big)
+        a.update(kw)
+        return lib.saap_bucket_attention_mass(a["q"], K, off, ln, f32(0.1), a["m"], lse, i32(1), i32(a["Hq"]), i32(a["Hkv"]),
+                                              i32(100), i32(a["B"]), i32(a["d"]), i32(a["dt"]), ws, a["wsb"], None)
+
+    assert mass(q=None) == -1 and mass(m=None) == -1 and mass(B=0) == -1 and mass(Hq=5, Hkv=2) == -1 and mass(dt=3) == -1
+    assert mass(d=64) == -2 and mass(Hq=3) == -2 and mass(wsb=small) == -3
+
+    params = binding._MlpF32(*(p.value for p in _fake(4)))
+    holes = binding._MlpF32(4096, None, 8192, 12288)
+
+    def grads(**kw):
+        a = dict(x=q, p=params, g=params, Hw=2, R=16, d=128, hidden=64, B=32, dt=1, wsb=big)
+        a.update(kw)
+        return lib.saap_query_model_loss_grads(a["x"], K, ctypes.byref(a["p"]), ctypes.byref(a["g"]), lse, i32(a["Hw"]),
+                                               i32(a["R"]), i32(a["d"]), i32(a["hidden"]), i32(a["B"]), i32(a["dt"]), ws,
+                                               a["wsb"], None)
+
+    assert grads(x=None) == -1 and grads(p=holes) == -1 and grads(g=holes) == -1 and grads(R=0) == -1 and grads(dt=2) == -1
+    assert grads(Hw=70000) == -2 and grads(wsb=small) == -3
+    need = saap.workspace_bytes(binding.OP_QUERY_MODEL_LOSS_GRADS, Hkv=2, N=16, d=128, hidden=64, B=32)
+    assert need == binding.WS_HEADER_BYTES + 2 * 16 * (128 + 2 * 64 + 32 + 1) * 4
+    assert saap.workspace_bytes(binding.OP_BUCKET_ATTENTION_MASS, S=1, Hq=32, Hkv=8, B=1024) == binding.WS_HEADER_BYTES + 8 * 1024 * 4 * 8
+
+    def adam(**kw):
+        a = dict(p=q, n=100, step=1, b1=0.9, b2=0.999)
+        a.update(kw)
+        return lib.saap_adam_update(a["p"], K, V, out, ctypes.c_size_t(a["n"]), i32(a["step"]), f32(1e-3), f32(a["b1"]),
+                                    f32(a["b2"]), f32(1e-8), None)
+
+    assert adam(p=None) == -1 and adam(n=0) == -1 and adam(step=0) == -1 and adam(b1=1.0) == -1 and adam(b2=-0.1) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and not r.stdout.strip()
