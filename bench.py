@@ -25,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
 BYTES_PER_KEY = 512     # one bf16 K row + one bf16 V row, d = 128
 
 
@@ -467,6 +468,7 @@ def main():
         "prefill": {
             "assign_keys_ms": round(ms_assign, 3),
             "assign_keys_TFLOPs": round(assign_flop / (ms_assign * 1e-3) / 1e12, 1),
+            "assign_keys_frac_of_bf16_mfma_peak": round(assign_flop / (ms_assign * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
             "assign_keys_rescored": rescored,
             "build_bucket_index_ms": round(ms_build, 3),
             "build_bucket_index_GBps": round(2.0 * n_keys_total * BYTES_PER_KEY / (ms_build * 1e-3) / 1e9, 1),
