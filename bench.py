@@ -2,14 +2,18 @@
 
 One "step" is the decode-time hot path for one token of one layer over a resident, bucket-sorted
 KV cache: classify_queries (logits) -> select_buckets_from_logits (the classifier's softmax folded
-into the selection kernel) -> sparse_decode_attention (partials + merge in one launch).  The prefill half (assign_keys, build_bucket_index) runs once during set-up and is timed
-separately; dense_decode_attention on the same cache is the in-repo baseline.
+into the selection kernel) -> sparse_decode_attention (partials + merge in one launch).  The prefill
+half (assign_keys, build_bucket_index) runs once during set-up and is timed separately; dense_decode_attention on the same cache is the in-repo baseline.
 
 Cache hygiene: the timed loop cycles through `--query-sets` different queries (hence different
 bucket selections), so that consecutive steps do not re-read the same 27 MB from the 256 MB
 last-level cache.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: the step time as `value` (us per token per layer), `roofline` for the sparse
+attention launch (algorithmic bytes per launch over its HIP-event time, against the 8 TB/s HBM peak and
+against a measured streaming-read ceiling; `traffic` from the committed profiler counters),
+`breakdown_us` per call, the dense baseline, the prefill timings and `cpu_baseline` (the CPU oracle on
+the host cores).  Options add further objects: `--window`, `--layers`, `--kv8`, `--quality`.
 """
 from __future__ import annotations
 
