@@ -506,6 +506,19 @@ def update_centroids(x_sorted, off, ln, centroids_old, normalize=True, out=None)
     return new
 
 
+def lloyd_iterations(x, centroids, iters, normalize=True):
+    """`iters` iterations of (spherical) k-means on the device, composed of the library's calls: assign_keys,
+    build_bucket_index on the features (grouping) and update_centroids.  x [S,Hkv,N,d], centroids [Hkv,B,d]
+    (the initial ones; not modified) -> new centroids."""
+    B = centroids.shape[1]
+    c = centroids
+    for _ in range(iters):
+        ids = assign_keys(x, c)
+        off, ln, _, xs, _ = build_bucket_index(ids, x, x, B, 0)
+        c = update_centroids(xs, off, ln, c, normalize)
+    return c
+
+
 def dense_decode_attention(q, K, V, scale, off=None, ln=None, out_dtype=torch.float32, out=None, lse=None, ws=None):
     """q [S,Hq,d]; K,V [S,Hkv,N,d] (packed, or a bucket-sorted cache with off/ln) -> out, lse."""
     S, Hq, d = q.shape

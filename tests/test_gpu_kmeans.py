@@ -71,10 +71,8 @@ def test_lloyd_loop_on_the_device_tracks_the_oracle(saap):
         return sum(float((hx[0, hh].astype(np.float64) * c64[hh][a[0, hh]]).sum()) for hh in range(cfg.Hkv))
 
     obj0 = objective(c_ref)
+    c_gpu = saap.lloyd_iterations(x, c_gpu, 3)
     for _ in range(3):
-        ids = saap.assign_keys(x, c_gpu)
-        off, ln, idx, xs, _ = saap.build_bucket_index(ids, x, x, cfg.B, 0)
-        c_gpu = saap.update_centroids(xs, off, ln, c_gpu)
         r_ids = ref.assign_keys(hx, c_ref.astype(np.float32))
         c_ref = ref.update_centroids(hx, r_ids, c_ref.astype(np.float32))
     torch.cuda.synchronize()
