@@ -326,6 +326,8 @@ def test_limits_max_buckets_and_group_of_eight(saap):
     ("bf16", 1, 32, 8, 512, 1024, "kv", False), ("bf16", 8, 8, 2, 256, 160, "kv", True),
     ("f32", 1, 1, 1, 256, 64, "kv", False), ("f32", 3, 4, 2, 64, 48, "q", True), ("bf16", 2, 8, 2, 96, 64, "one", True),
     ("bf16", 5, 4, 1, 64, 4096, "q", False),
+    ("bf16", 1, 32, 8, 1024, 1024, "kv", True),      # the paper's model size (Section 6.1: hidden layer of 1024)
+    ("bf16", 2, 8, 2, 1536, 208, "kv", False),       # the largest hidden layer the kernels take
 ])
 def test_classify_queries(saap, dtype, S, Hq, Hkv, hidden, B, Hw_kind, bias):
     cfg = small("cfg1_llama8b_128k", S=S, Hq=Hq, Hkv=Hkv, N=16, B=B, hidden=hidden, dtype=dtype)
