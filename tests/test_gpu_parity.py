@@ -277,6 +277,53 @@ def test_independent_lists_share_one_pass_over_the_union(saap, dtype, S, Hq, Hkv
     assert_close(lse.cpu().numpy(), rl, dtype, "independent lse")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_attention_with_extreme_scores(saap, dtype):
+    """Softmax far from the benign range: scores in the thousands with one dominant key (the output is that
+    key's value), a running maximum that keeps rising along the cache, identical keys (the output is the
+    mean of the values), and huge negative scores; sparse and dense kernels against the oracle."""
+    S, Hq, Hkv, N, B = 1, 4, 1, 3000, 12
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    g = torch.Generator(device="cpu").manual_seed(17)
+    K = torch.randn(S, Hkv, N, 128, generator=g)
+    V = torch.randn(S, Hkv, N, 128, generator=g)
+    q = torch.randn(S, Hq, 128, generator=g)
+    qn = q / q.norm(dim=-1, keepdim=True)
+    # head 0: keys grow along the cache in the direction of the query (every batch raises the maximum)
+    K[0, 0] += torch.linspace(0, 60, N).unsqueeze(1) * qn[0, 0]
+    # head 1: one key dominates by a wide margin
+    K[0, 0, 1234] = 400.0 * qn[0, 1]
+    # head 2's query is opposite to most keys' drift (huge negative scores), head 3's is zero (uniform weights)
+    q[0, 2] = -30.0 * qn[0, 0]
+    q[0, 3] = 0.0
+    q[0, 0] = 25.0 * qn[0, 0]
+    q[0, 1] = 30.0 * qn[0, 1]
+    K, V, q = (t.to(dt).to(DEV).contiguous() for t in (K, V, q))
+    ids = (torch.arange(N, dtype=torch.int32) % B).reshape(1, 1, N).to(DEV).contiguous()
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, K, V, B, 1)
+    sel = torch.arange(B, dtype=torch.int32, device=DEV).reshape(1, 1, B)
+    scale = 1.0                                             # no 1/sqrt(d): keeps the scores large
+    out, lse = saap.sparse_decode_attention(q, Ks, Vs, off, ln, sel, scale)
+    o_d, l_d = saap.dense_decode_attention(q, K, V, scale)
+    torch.cuda.synchronize()
+    ro, rl = ref.dense_decode_attention(h(q), h(K), h(V), np.float32(scale))
+    assert np.abs(rl).max() > 1000                          # the case is what it claims to be
+    # fp32: a score s is known to about |s| * 2^-23 * sqrt(d) in single precision, here about 2e-3 for
+    # |s| ~ 1.5e3; the weights exp(s - max) inherit that as a relative error, so the fp32 tolerance of
+    # benign scores (1e-5) does not apply: 2e-4 absolute + relative is what this case can hold
+    def check(got, want, what):
+        if dtype == "bf16":
+            return assert_close(got, want, dtype, what)
+        err = np.abs(np.asarray(got, np.float64) - want)
+        assert (err <= 2e-4 + 2e-4 * np.abs(want)).all(), f"{what}: max err {err.max():.3e}"
+
+    for got_o, got_l, what in ((out, lse, "sparse"), (o_d, l_d, "dense")):
+        check(got_o.cpu().numpy(), ro, f"{what} out")
+        check(got_l.cpu().numpy(), rl, f"{what} lse")
+    np.testing.assert_allclose(out[0, 1].cpu().numpy(), h(V)[0, 0, 1234], rtol=1e-2, atol=2e-3)     # the dominant key
+    np.testing.assert_allclose(out[0, 3].cpu().numpy(), h(V)[0, 0].mean(0), rtol=1e-2, atol=2e-3)  # uniform weights
+
+
 def test_attention_is_deterministic_and_workspace_stays_clean(saap):
     cfg = small("cfg1_llama8b_128k", S=1, Hq=8, Hkv=2, N=20000, B=128, nprobe=16, hidden=64)
     cache, cent, xq, q, W = make_inputs(cfg, 17)
