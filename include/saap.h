@@ -77,7 +77,8 @@ enum {
   SAAP_OP_APPEND_KEYS = 6,
   SAAP_OP_WINDOW_PUSH = 7,
   SAAP_OP_BUCKET_ATTENTION_MASS = 8,
-  SAAP_OP_QUERY_MODEL_LOSS_GRADS = 9   /* shape: Hkv = weight sets, N = rows per set, d, hidden, B */
+  SAAP_OP_QUERY_MODEL_LOSS_GRADS = 9,  /* shape: Hkv = weight sets, N = rows per set, d, hidden, B */
+  SAAP_OP_BUCKET_ATTENTION_MASS_BATCH = 10   /* shape: S, Hkv, N = queries per KV head, B */
 };
 
 #define SAAP_WS_HEADER_BYTES 65536u
@@ -399,6 +400,22 @@ int32_t saap_bucket_attention_mass(const void* q, const void* Ksorted,
                                    int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
                                    int32_t d, int32_t dtype,
                                    void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * bucket_attention_mass_batch -- saap_bucket_attention_mass for a training batch: R queries per
+ * (sequence, KV head) instead of the G heads of a decode step (Section 4 "Query assignment
+ * function": the rows of A * H_k for the sampled queries of a prompt).  The scores run on the
+ * matrix cores, so the keys are read once per 128 queries.
+ *   q [S,Hkv,R,d] bf16; Ksorted [S,Hkv,Ncap,d] bf16; off [S,Hkv,B+1], len [S,Hkv,B]
+ *   mass [S,Hkv,R,B] fp32, out; lse [S,Hkv,R] fp32 or NULL, out
+ * Workspace: SAAP_OP_BUCKET_ATTENTION_MASS_BATCH (S, Hkv, N = R, B): 8 bytes per (query, bucket).
+ */
+int32_t saap_bucket_attention_mass_batch(const void* q, const void* Ksorted,
+                                         const int32_t* off, const int32_t* len,
+                                         float scale, float* mass, float* lse,
+                                         int32_t S, int32_t Hkv, int32_t R, int32_t Ncap, int32_t B,
+                                         int32_t d, int32_t dtype,
+                                         void* ws, size_t ws_bytes, void* stream);
 
 /*
  * ---- training of the query model (Section 4 "Query assignment function", Eq. 1) ----

@@ -16,7 +16,7 @@ GROUP_SUM, INDEPENDENT = 0, 1
 PROBS, LOGITS = 0, 1
 OP_ASSIGN_KEYS, OP_BUILD_BUCKET_INDEX, OP_CLASSIFY_QUERIES, OP_SELECT_BUCKETS = 0, 1, 2, 3
 OP_SPARSE_DECODE_ATTENTION, OP_DENSE_DECODE_ATTENTION, OP_APPEND_KEYS, OP_WINDOW_PUSH = 4, 5, 6, 7
-OP_BUCKET_ATTENTION_MASS, OP_QUERY_MODEL_LOSS_GRADS = 8, 9
+OP_BUCKET_ATTENTION_MASS, OP_QUERY_MODEL_LOSS_GRADS, OP_BUCKET_ATTENTION_MASS_BATCH = 8, 9, 10
 WS_HEADER_BYTES = 65536
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -32,6 +32,7 @@ EXPORTS = (
     "saap_quantize_kv", "saap_sparse_decode_attention_fp8", "saap_dense_decode_attention_fp8",
     "saap_windowed_decode_attention_fp8",
     "saap_bucket_attention_mass", "saap_query_model_loss_grads", "saap_adam_update",
+    "saap_bucket_attention_mass_batch",
 )
 
 
@@ -280,6 +281,22 @@ def bucket_attention_mass(q, Ks, off, ln, scale, out=None, lse=None, ws=None):
         _ptr(q), _ptr(Ks), _ptr(off), _ptr(ln), ctypes.c_float(scale), _ptr(mass), _ptr(lse), _i32(S), _i32(Hq),
         _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _ptr(ws), wsb, _stream())
     _check("saap_bucket_attention_mass", st)
+    return mass, lse
+
+
+def bucket_attention_mass_batch(q, Ks, off, ln, scale, out=None, lse=None, ws=None):
+    """q [S,Hkv,R,d] bf16 (R queries per KV head); Ks [S,Hkv,Ncap,d] -> mass fp32 [S,Hkv,R,B], lse fp32 [S,Hkv,R]."""
+    S, Hkv, R, d = q.shape
+    Ncap = Ks.shape[2]
+    B = ln.shape[2]
+    dev = q.device
+    mass = out if out is not None else torch.empty(S, Hkv, R, B, dtype=torch.float32, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Hkv, R, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_BUCKET_ATTENTION_MASS_BATCH, dev, ws, S=S, Hkv=Hkv, N=R, B=B)
+    st = load_library().saap_bucket_attention_mass_batch(
+        _ptr(q), _ptr(Ks), _ptr(off), _ptr(ln), ctypes.c_float(scale), _ptr(mass), _ptr(lse), _i32(S), _i32(Hkv),
+        _i32(R), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _ptr(ws), wsb, _stream())
+    _check("saap_bucket_attention_mass_batch", st)
     return mass, lse
 
 

@@ -114,7 +114,139 @@ void launch_mass(const void* q, const void* K, const int32_t* off, const int32_t
   hipLaunchKernelGGL(mass_normalise_kernel<G>, dim3((unsigned)(units * G)), dim3(256), 0, hs, part, mass, lse, B);
 }
 
+// ---- many queries per KV head (a training batch): scores on the matrix cores -----------------------
+// 128 queries per workgroup sit in registers as the B operand of v_mfma_f32_32x32x16_bf16 (32 per
+// wave, one lane per query and half of the key rows); the keys of a bucket stream through LDS in
+// tiles of 32 as the A operand (padded rows, whole-row loads), so that one lane sees 16 scores of
+// its query per tile and keeps the bucket's running maximum and sum for it.  A workgroup takes
+// every n_slices-th bucket.  part[(unit*B + b)*R + q] = (m, s).
+constexpr int kMassPitch = 136;      // bf16 elements per LDS row (272 bytes: conflict-free b128 reads)
+constexpr int kMassQueries = 128;    // queries per workgroup
+
+__global__ void __launch_bounds__(256)
+mass_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ K, const int32_t* __restrict__ off,
+                 const int32_t* __restrict__ len, float2* __restrict__ part, long long rows, int B, int R,
+                 float scale_log2) {
+  typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+  __shared__ __align__(16) bf16_t s_k[32 * kMassPitch];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int unit = blockIdx.z;
+  const int qi = blockIdx.y * kMassQueries + wave * 32 + col;
+  // B operand: lane holds features 16*step + 8*half .. +7 of query `col` (idle columns repeat the last query)
+  bf16x8_t xb[8];
+  {
+    const bf16_t* qr = q + ((size_t)unit * R + min(qi, R - 1)) * kD + half * 8;
+#pragma unroll
+    for (int st = 0; st < 8; ++st) xb[st] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(qr + st * 16));
+  }
+  const bf16_t* Ku = K + (size_t)unit * rows * kD;
+  for (int b = blockIdx.x; b < B; b += gridDim.x) {
+    const int first = off[(size_t)unit * (B + 1) + b], n = len[(size_t)unit * B + b];
+    float m = kNegBig, s = 0.f;
+    for (int t0 = 0; t0 < n; t0 += 32) {
+      __syncthreads();                                   // the previous tile has been read
+      // 32 rows x 16 pieces of 16 bytes, two per thread; rows past the bucket repeat its last key
+      uint4 piece[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int pi = tid + 256 * i, r = pi >> 4, pc = pi & 15;
+        piece[i] = *reinterpret_cast<const uint4*>(Ku + (size_t)(first + min(t0 + r, n - 1)) * kD + pc * 8);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int pi = tid + 256 * i, r = pi >> 4, pc = pi & 15;
+        *reinterpret_cast<uint4*>(&s_k[r * kMassPitch + pc * 8]) = piece[i];
+      }
+      __syncthreads();
+      f32x16_t acc = {0};
+#pragma unroll
+      for (int st = 0; st < 8; ++st) {
+        const bf16x8_t a = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&s_k[col * kMassPitch + st * 16 + half * 8]));
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[st], acc, 0, 0, 0);
+      }
+      // register r of this lane: key t0 + 8*(r/4) + 4*half + r%4 against query `col`
+      float t[16], bm = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = t0 + 8 * (r / 4) + 4 * half + (r % 4);
+        t[r] = key < n ? acc[r] * scale_log2 : -INFINITY;
+        bm = fmaxf(bm, t[r]);
+      }
+      const float mn = fmaxf(m, bm);                     // may stay at the stand-in when this half holds no real key
+      float add = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) add += fast_exp2(t[r] - mn);
+      s = s * fast_exp2(m - mn) + add;
+      m = mn;
+    }
+    // lanes l and l+32 hold the same query
+    const float mo = __shfl_xor(m, 32), so = __shfl_xor(s, 32);
+    const float M = fmaxf(m, mo);
+    const float S = s * fast_exp2(m - M) + so * fast_exp2(mo - M);
+    if (half == 0 && qi < R) part[((size_t)unit * B + b) * R + qi] = make_float2(M, S);
+  }
+}
+
+// mass[(unit*R + q)*B + b] = s_b 2^(m_b - M) / L for 32 queries per workgroup: thread (query, bucket group).
+__global__ void __launch_bounds__(256)
+mass_normalise_batch_kernel(const float2* __restrict__ part, float* __restrict__ mass, float* __restrict__ lse, int B,
+                            int R) {
+  __shared__ float s_red[8][32];
+  __shared__ float s_tile[32][33];
+  const int tid = threadIdx.x, ql = tid & 31, bg = tid >> 5;
+  const int unit = blockIdx.y, q0 = blockIdx.x * 32;
+  const int qi = min(q0 + ql, R - 1);
+  const float2* pu = part + (size_t)unit * B * R + qi;
+  float M = kNegBig;
+  for (int b = bg; b < B; b += 8) M = fmaxf(M, pu[(size_t)b * R].x);
+  s_red[bg][ql] = M;
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < 8; ++g) M = fmaxf(M, s_red[g][ql]);
+  __syncthreads();
+  float L = 0.f;
+  for (int b = bg; b < B; b += 8) {
+    const float2 p = pu[(size_t)b * R];
+    L = fmaf(p.y, fast_exp2(p.x - M), L);
+  }
+  s_red[bg][ql] = L;
+  __syncthreads();
+  L = 0.f;
+#pragma unroll
+  for (int g = 0; g < 8; ++g) L += s_red[g][ql];           // fixed order
+  const float inv = L > 0.f ? 1.0f / L : 0.f;
+  if (bg == 0 && q0 + ql < R && lse) lse[(size_t)unit * R + q0 + ql] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
+  // tiles of 32 queries x 32 buckets go through LDS so that the rows of `mass` are written in whole lines
+  for (int bt = 0; bt < B; bt += 32) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int bb = bg * 4 + i, b = bt + bb;
+      float v = 0.f;
+      if (b < B) {
+        const float2 p = pu[(size_t)b * R];
+        v = p.y * fast_exp2(p.x - M) * inv;
+      }
+      s_tile[ql][bb] = v;
+    }
+    __syncthreads();
+    const int row = tid >> 3, seg = tid & 7;
+    if (q0 + row < R) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int b = bt + seg * 4 + i;
+        if (b < B) mass[((size_t)unit * R + q0 + row) * B + b] = s_tile[row][seg * 4 + i];
+      }
+    }
+  }
+}
+
 }  // namespace
+
+size_t mass_batch_workspace_bytes(long long units, long long R, int B) {
+  return (size_t)SAAP_WS_HEADER_BYTES + (size_t)units * R * B * sizeof(float2);
+}
 
 size_t mass_workspace_bytes(long long units, int G, int B) {
   return (size_t)SAAP_WS_HEADER_BYTES + (size_t)units * B * G * sizeof(float2);
@@ -158,5 +290,33 @@ extern "C" int32_t saap_bucket_attention_mass(const void* q, const void* Ksorted
     }
   }
 #undef SAAP_CASE
+  return launch_status();
+}
+
+extern "C" int32_t saap_bucket_attention_mass_batch(const void* q, const void* Ksorted, const int32_t* off,
+                                                    const int32_t* len, float scale, float* mass, float* lse,
+                                                    int32_t S, int32_t Hkv, int32_t R, int32_t Ncap, int32_t B,
+                                                    int32_t d, int32_t dtype, void* ws, size_t ws_bytes,
+                                                    void* stream) {
+  if (!q || !Ksorted || !off || !len || !mass || !ws) return SAAP_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(Ksorted) || !aligned16(mass) || !aligned16(ws)) return SAAP_INVALID_ARG;
+  if (S <= 0 || Hkv <= 0 || R <= 0 || Ncap <= 0 || B <= 0) return SAAP_INVALID_ARG;
+  if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
+  if (d != kD || dtype != SAAP_BF16) return SAAP_UNSUPPORTED;
+  const long long units = (long long)S * Hkv;
+  if (units > 65535 || (R + kMassQueries - 1) / kMassQueries > 65535) return SAAP_UNSUPPORTED;
+  if (ws_bytes < mass_batch_workspace_bytes(units, R, B)) return SAAP_WORKSPACE_TOO_SMALL;
+  float2* part = reinterpret_cast<float2*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const int qblocks = (R + kMassQueries - 1) / kMassQueries;
+  // bucket slices: enough workgroups to fill the chip a few times, never more than buckets
+  long long slices = ((long long)device_cus() * 4 + units * qblocks - 1) / (units * qblocks);
+  if (slices > B) slices = B;
+  if (slices < 1) slices = 1;
+  hipLaunchKernelGGL(mass_mfma_kernel, dim3((unsigned)slices, (unsigned)qblocks, (unsigned)units), dim3(256), 0, hs,
+                     static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(Ksorted), off, len, part, (long long)Ncap,
+                     B, R, scale * kLog2e);
+  hipLaunchKernelGGL(mass_normalise_batch_kernel, dim3((unsigned)((R + 31) / 32), (unsigned)units), dim3(256), 0, hs, part,
+                     mass, lse, B, R);
   return launch_status();
 }

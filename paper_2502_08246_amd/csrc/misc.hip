@@ -10,6 +10,7 @@ size_t build_workspace_bytes(long long units, int N, int B);
 size_t push_workspace_bytes(long long units, int B);
 size_t classify_workspace_bytes(long long rows, int hidden);
 size_t mass_workspace_bytes(long long units, int G, int B);
+size_t mass_batch_workspace_bytes(long long units, long long R, int B);
 size_t train_workspace_bytes(long long Hw, long long R, int d, int hidden, int B);
 
 int device_cus() {
@@ -94,6 +95,9 @@ extern "C" size_t saap_workspace_bytes(int32_t op, const saap_shape* sh) {
     case SAAP_OP_QUERY_MODEL_LOSS_GRADS:
       if (Hkv <= 0 || sh->N <= 0 || sh->d <= 0 || sh->hidden <= 0 || sh->B <= 0) return 0;
       return train_workspace_bytes(Hkv, sh->N, sh->d, sh->hidden, sh->B);
+    case SAAP_OP_BUCKET_ATTENTION_MASS_BATCH:
+      if (S <= 0 || Hkv <= 0 || sh->N <= 0 || sh->B <= 0) return 0;
+      return mass_batch_workspace_bytes(S * Hkv, sh->N, sh->B);
     case SAAP_OP_BUCKET_ATTENTION_MASS:
       if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || sh->B <= 0) return 0;
       return mass_workspace_bytes(S * Hkv, (int)(Hq / Hkv), sh->B);

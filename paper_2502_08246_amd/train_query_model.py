@@ -4,7 +4,7 @@ attention mass its lists capture (arXiv 2502.08246, Section 4 "Query assignment 
     python -m paper_2502_08246_amd.train_query_model --workload cfg1_llama8b_128k --steps 400
 
 Steps, all on the GPU: keys are assigned and indexed (assign_keys, build_bucket_index); for every
-training query the target row of A * H_k comes from bucket_attention_mass; training steps are
+training query the target row of A * H_k comes from bucket_attention_mass_batch; training steps are
 query_model_loss_grads + adam_update on fp32 weights, one weight set per KV head (its G query
 heads share it, as in the decode step).  Evaluation on held-out queries: classify_queries +
 select_buckets with the trained weights, then the share of each query's attention mass inside
@@ -66,13 +66,20 @@ def train(cfg, train_queries=2048, eval_queries=64, steps=400, batch=1024, lr=1e
     T_all = args.train_queries + args.eval_queries
     xq, q = gen.make_queries(cfg, args.seed, dev, n_steps=T_all)
 
-    # targets: the bucket attention mass of every query, one call per decode step
-    mass = torch.empty(T_all, cfg.Hq, B, dtype=torch.float32, device=dev)
+    # targets: the bucket attention mass of every query; the queries of a KV head form one batch
+    # (rows ordered (step, head of the group)), scored on the matrix cores in pieces of 4096 rows
+    q_rows = q[:, 0].reshape(T_all, Hw, G, d).permute(1, 0, 2, 3).reshape(1, Hw, T_all * G, d).contiguous()
+    mass_rows = torch.empty(1, Hw, T_all * G, B, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for t in range(T_all):
-        saap.bucket_attention_mass(q[t], Ks, off, ln, scale, out=mass[t:t + 1])
+    for r0 in range(0, T_all * G, 4096):
+        r1 = min(r0 + 4096, T_all * G)
+        piece, _ = saap.bucket_attention_mass_batch(q_rows[:, :, r0:r1].contiguous(), Ks, off, ln, scale)
+        mass_rows[:, :, r0:r1] = piece
     torch.cuda.synchronize()
     target_s = time.perf_counter() - t0
+    # [T, Hq, B] view of the same numbers for the evaluation
+    mass = mass_rows[0].reshape(Hw, T_all, G, B).permute(1, 0, 2, 3).reshape(T_all, cfg.Hq, B).contiguous()
 
     def per_weight_set(a, lo, hi):
         # [T,(S,)Hq,X] -> [Hw, (hi-lo)*G, X]: the rows of the G heads that share weight set h

@@ -185,6 +185,16 @@ def test_invalid_arguments_of_the_later_calls_are_rejected_on_the_host(lib):
     assert mass(q=None) == -1 and mass(m=None) == -1 and mass(B=0) == -1 and mass(Hq=5, Hkv=2) == -1 and mass(dt=3) == -1
     assert mass(d=64) == -2 and mass(Hq=3) == -2 and mass(wsb=small) == -3
 
+    def mass_batch(**kw):
+        a = dict(q=q, R=100, B=8, d=128, dt=1, wsb=big)
+        a.update(kw)
+        return lib.saap_bucket_attention_mass_batch(a["q"], K, off, ln, f32(0.1), out, lse, i32(1), i32(2), i32(a["R"]),
+                                                    i32(100), i32(a["B"]), i32(a["d"]), i32(a["dt"]), ws, a["wsb"], None)
+
+    assert mass_batch(q=None) == -1 and mass_batch(R=0) == -1 and mass_batch(B=0) == -1 and mass_batch(dt=4) == -1
+    assert mass_batch(d=64) == -2 and mass_batch(dt=0) == -2 and mass_batch(wsb=small) == -3
+    assert saap.workspace_bytes(binding.OP_BUCKET_ATTENTION_MASS_BATCH, S=1, Hkv=2, N=100, B=8) == binding.WS_HEADER_BYTES + 2 * 100 * 8 * 8
+
     params = binding._MlpF32(*(p.value for p in _fake(4)))
     holes = binding._MlpF32(4096, None, 8192, 12288)
 

@@ -91,3 +91,28 @@ def test_mass_argument_checks(saap):
     small = torch.zeros(65536 + 8, dtype=torch.uint8, device=DEV)
     with pytest.raises(saap.SaapError):
         saap.bucket_attention_mass(q, Ks, off, ln, SCALE, ws=small)
+
+
+@pytest.mark.parametrize("S,Hkv,R,N,B", [(1, 2, 200, 6000, 37), (2, 1, 33, 3001, 16), (1, 1, 129, 2500, 130)])
+def test_batched_mass_against_the_oracle(saap, S, Hkv, R, N, B):
+    """R queries per KV head through the matrix-core kernels, against the oracle (which sees them as R heads
+    sharing the KV head) and against the decode-step kernel on the first 8 of them."""
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(S=S, Hq=Hkv, Hkv=Hkv, N=N, B=B, nprobe=min(4, B), dtype="bf16", hidden=64)
+    cache = gen.make_cache(cfg, 79, DEV)
+    cent = gen.make_centroids(cfg, 79, DEV, cache, n_train=2048)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    ids[:, :, : N // 3] = torch.clamp(ids[:, :, : N // 3], max=B - 3)      # thin and empty buckets at the end
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], B, 2)
+    g = torch.Generator(device="cpu").manual_seed(5)
+    q = (2.0 * torch.randn(S, Hkv, R, 128, generator=g)).to(torch.bfloat16).to(DEV)
+    mass, lse = saap.bucket_attention_mass_batch(q, Ks, off, ln, SCALE)
+    torch.cuda.synchronize()
+    want = ref.bucket_attention_mass(h(q).reshape(S, Hkv * R, 128), h(cache["K"]), ids.cpu().numpy(), np.float32(SCALE), B)
+    got = mass.cpu().numpy().astype(np.float64).reshape(S, Hkv * R, B)
+    err = np.abs(got - want)
+    assert (err <= 1e-6 + 2e-3 * want).all(), f"max err {err.max():.3e}"
+    np.testing.assert_allclose(got.sum(-1), 1.0, rtol=1e-5)
+    m8, l8 = saap.bucket_attention_mass(q[:, :, :8].reshape(S, Hkv * 8, 128).contiguous(), Ks, off, ln, SCALE)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(mass[:, :, :8].cpu().numpy().reshape(S, Hkv * 8, B), m8.cpu().numpy(), rtol=2e-3, atol=1e-6)
+    np.testing.assert_allclose(lse[:, :, :8].cpu().numpy().reshape(S, Hkv * 8), l8.cpu().numpy(), rtol=1e-5, atol=1e-4)
