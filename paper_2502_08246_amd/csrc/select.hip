@@ -459,10 +459,11 @@ static int32_t select_impl(const float* scores, bool logits, float* probs, int32
   if (logits && !(n_sort < n_pow2)) return SAAP_UNSUPPORTED;     // the fused softmax lives in the radix kernel
   if (n_sort < n_pow2 && (logits || env_int("SAAP_SELECT_FULL_SORT", 0) == 0)) {
     // radix select + sort of the selected keys only
-    // elements per thread: 2 up to 2048 buckets (measured best at 1024: more waves with loads in
-    // flight pull the score rows in faster, up to the point where the barriers cost more), then 4, 8
+    // elements per thread: 2 up to 1024 buckets, 4 up to 4096 (measured: 512 threads are best at 1024
+    // and at 2048 buckets; more waves with loads in flight pull the score rows in faster, up to the
+    // point where the barriers of a larger workgroup cost more), then 8
     int ept = env_int("SAAP_SELECT_EPT", 0);
-    if (ept != 1 && ept != 2 && ept != 4 && ept != 8) ept = B <= 2048 ? 2 : B <= 4096 ? 4 : 8;
+    if (ept != 1 && ept != 2 && ept != 4 && ept != 8) ept = B <= 1024 ? 2 : B <= 4096 ? 4 : 8;
     while (ept < 8 && (long long)ept * 1024 < B) ept *= 2;
     int threads = (B + ept - 1) / ept;
     threads = (threads + 63) / 64 * 64;
