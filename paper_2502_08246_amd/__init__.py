@@ -12,4 +12,5 @@ from .binding import (  # noqa: F401
     library_path, lloyd_iterations, load_library, recompact_index, select_buckets, select_buckets_from_logits, sparse_decode_attention, stream_read_probe, update_centroids, window_push, windowed_decode_attention, windowed_decode_attention_fp8,
     workspace,
     workspace_bytes,
+    workspace_reset,
 )

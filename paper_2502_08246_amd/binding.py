@@ -138,6 +138,13 @@ def _ws(op, device, ws, **shape):
     return ws, ctypes.c_size_t(ws.numel())
 
 
+def workspace_reset(ws: torch.Tensor) -> None:
+    """Zeroes the header of a caller-provided workspace (needed once before its first use, or after a
+    call was abandoned midway)."""
+    st = load_library().saap_workspace_reset(_ptr(ws), ctypes.c_size_t(ws.numel()), _stream())
+    _check("saap_workspace_reset", st)
+
+
 def stream_read_probe(src: torch.Tensor, sink: torch.Tensor) -> None:
     """Measurement aid: one pass of plain 16-byte loads over `src` (see saap_stream_read_probe)."""
     st = load_library().saap_stream_read_probe(_ptr(src), ctypes.c_size_t(src.numel() * src.element_size()), _ptr(sink),

@@ -62,3 +62,35 @@ def test_step_replays_match_eager_launches():
             assert torch.equal(g, w), f"replay {t}: {name} differs from the eager launch"
         ws = saap.workspace(0, DEV)
         assert int(ws[:65536].view(torch.int64).abs().sum().item()) == 0, "arrival counters must be zero between calls"
+
+
+def test_own_workspace_on_a_side_stream():
+    """A caller-provided workspace that starts with a dirty header is reset by workspace_reset, and the decode
+    calls run with it on a stream of the caller's; the results equal those of the default workspace and stream."""
+    import paper_2502_08246_amd as saap
+    saap.load_library()
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(S=2, Hq=8, Hkv=2, N=5000, B=32, nprobe=6, hidden=64)
+    cache = gen.make_cache(cfg, 61, DEV)
+    cent = gen.make_centroids(cfg, 61, DEV, cache, n_train=2048)
+    xq, q = gen.make_queries(cfg, 61, DEV, n_steps=1)
+    W1, b1, W2, b2 = gen.make_classifier(cfg, 61, DEV)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, 0)
+    logits = saap.classify_queries(xq[0], W1, b1, W2, b2, cfg.Hkv, output_kind=saap.LOGITS)
+    sel = saap.select_buckets_from_logits(logits, cfg.Hkv, cfg.nprobe)
+    want, want_lse = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln, sel, SCALE)
+    torch.cuda.synchronize()
+    need = saap.workspace_bytes(saap.binding.OP_SPARSE_DECODE_ATTENTION, S=cfg.S, Hq=cfg.Hq, Hkv=cfg.Hkv, mode=0)
+    ws = torch.full((need,), 0xAB, dtype=torch.uint8, device=DEV)          # arrival counters full of garbage
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        saap.workspace_reset(ws)
+        assert int(ws[:65536].view(torch.int32).abs().sum().item()) == 0
+        lg = saap.classify_queries(xq[0], W1, b1, W2, b2, cfg.Hkv, output_kind=saap.LOGITS, ws=ws)
+        sl = saap.select_buckets_from_logits(lg, cfg.Hkv, cfg.nprobe, ws=ws)
+        got, got_lse = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln, sl, SCALE, ws=ws)
+        got2, _ = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln, sl, SCALE, ws=ws)      # the header was left clean
+    side.synchronize()
+    assert torch.equal(sl, sel) and torch.equal(got, want) and torch.equal(got_lse, want_lse) and torch.equal(got2, want)
+    assert int(ws[:65536].view(torch.int32).abs().sum().item()) == 0
