@@ -483,7 +483,7 @@ int32_t saap_quantize_kv(const void* Ksorted, const void* Vsorted, uint8_t* K8, 
  * keys, fp32 accumulation), K and V are read as one byte per feature.
  *   q [S,Hq,d] bf16; K8, V8 [S,Hkv,Ncap,d] uint8; kscale, vscale [S,Hkv] fp32
  *   the remaining arguments as in the 16-bit calls (mode: SAAP_GROUP_SUM lists [S,Hkv,nprobe]
- *   or SAAP_INDEPENDENT lists [S,Hq,nprobe], the latter read per head)
+ *   or SAAP_INDEPENDENT lists [S,Hq,nprobe])
  *   dense: off != NULL as in saap_dense_decode_attention (a bucket-sorted cache), B buckets
  * Workspace: as SAAP_OP_SPARSE_DECODE_ATTENTION / SAAP_OP_DENSE_DECODE_ATTENTION.
  */

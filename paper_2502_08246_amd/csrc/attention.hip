@@ -763,7 +763,13 @@ int32_t launch_one(const AttnParams& p, const LaunchPlan& lp, hipStream_t stream
 // Independent routing with G > 1 heads per KV head: the masked kernels, 512 threads only.
 int32_t launch_masked(const AttnParams& p, const LaunchPlan& lp, int G, int dtype, hipStream_t stream) {
 #define SAAP_CASE(TT, GG) return launch_nt<TT, GG, true, 512, true>(p, lp, stream)
-  if (dtype == SAAP_BF16) {
+  if (dtype == kDtypeFp8) {
+    switch (G) {
+      case 2: SAAP_CASE(fp8_t, 2);
+      case 4: SAAP_CASE(fp8_t, 4);
+      case 8: SAAP_CASE(fp8_t, 8);
+    }
+  } else if (dtype == SAAP_BF16) {
     switch (G) {
       case 2: SAAP_CASE(bf16_t, 2);
       case 4: SAAP_CASE(bf16_t, 4);
@@ -855,7 +861,7 @@ static int32_t sparse_attention(const void* q, const void* Ksorted, const void* 
   // of the heads' lists once, each head attending only its own runs (masked kernels).  They hold
   // 16 buckets per thread at most; beyond that every head is a unit of its own.
   const int heads = Hq / Hkv;
-  const bool masked = indep && heads > 1 && B <= 16 * 512 && dtype != kDtypeFp8;
+  const bool masked = indep && heads > 1 && B <= 16 * 512;
   if (dtype == kDtypeFp8 && (!kscale || !vscale)) return SAAP_INVALID_ARG;
   const int G = masked ? heads : indep ? 1 : heads;
   const long long units = indep && !masked ? (long long)S * Hq : (long long)S * Hkv;
