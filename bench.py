@@ -201,6 +201,10 @@ def main():
         a_flag = torch.zeros(4, dtype=torch.int32, device=dev)
         a_ids = torch.empty(cfg.S, cfg.Hkv, dtype=torch.int32, device=dev)
 
+        # the index as built: the 8-bit run fills the slack from the start again, and the host timing leg
+        # reads keys by position, so it must not see the positions appended beyond the N it holds
+        ln_built, idx_built = ln.clone(), idx.clone()
+
     def append(i):
         saap.append_keys(a_x[i % T], a_k[i % T], a_v[i % T], a_pos[i % T], cent, None, off, ln, idx, Ks, Vs,
                          overflow_flag=a_flag, new_ids=a_ids)
@@ -347,10 +351,17 @@ def main():
         def attend8_set(i):
             saap.sparse_decode_attention_fp8(q[i % T], K8, V8, k_sc, v_sc, off, ln, sel_sets[i % T], scale, out=out, lse=lse)
 
+        ln8, idx8 = (ln_built.clone(), idx_built.clone()) if with_append else (ln, idx)
+        if with_append:
+            a_flag8 = torch.zeros(4, dtype=torch.int32, device=dev)
+
         def step8(i):
             classify(i)
             select(i)
-            saap.sparse_decode_attention_fp8(q[i % T], K8, V8, k_sc, v_sc, off, ln, sel, scale, out=out, lse=lse)
+            saap.sparse_decode_attention_fp8(q[i % T], K8, V8, k_sc, v_sc, off, ln8, sel, scale, out=out, lse=lse)
+            if with_append:
+                saap.append_keys_fp8(a_x[i % T], a_k[i % T], a_v[i % T], a_pos[i % T], cent, None, off, ln8, idx8, K8, V8,
+                                     k_sc, v_sc, overflow_flag=a_flag8, new_ids=a_ids)
 
         def dense8(i):
             saap.dense_decode_attention_fp8(q[i % T], K8, V8, k_sc, v_sc, scale, off=off, ln=ln, out=out, lse=lse)
@@ -361,7 +372,9 @@ def main():
         kv8_result = {
             "format": "OCP FP8 E4M3, one power-of-two scale per (sequence, KV head) and tensor",
             "step_us_per_token_layer": round(ms_step8 * 1e3 / cfg.S, 3),
-            "step": "classify_queries (logits) + select_buckets_from_logits + sparse_decode_attention_fp8 (no append)",
+            "step": "classify_queries (logits) + select_buckets_from_logits + sparse_decode_attention_fp8"
+                    + (" + append_keys_fp8" if with_append else ""),
+            "append_overflow_flag": int(a_flag8[0].item()) if with_append else None,
             "sparse_decode_attention_fp8_us": round(ms_attn8 * 1e3, 3),
             "bytes_per_launch": round(keys_touched * BYTES_PER_KEY / 2),
             "achieved_GBps": round(keys_touched * BYTES_PER_KEY / 2 / (ms_attn8 * 1e-3) / 1e9, 1),
@@ -507,7 +520,8 @@ def main():
         threads = min(16, os.cpu_count() or 1)
         ref.set_threads(threads)
         hK, hV = h(cache["K"]), h(cache["V"])
-        h_off, h_ln, h_idx = off.cpu().numpy(), ln.cpu().numpy(), idx.cpu().numpy()
+        h_off = off.cpu().numpy()
+        h_ln, h_idx = ((ln_built if with_append else ln).cpu().numpy(), (idx_built if with_append else idx).cpu().numpy())
         hW1, hb1, hW2, hb2 = h(W1), h(b1), h(W2), h(b2)
         hxq, hq = h(xq), h(q)
         done, t_cpu0 = 0, time.perf_counter()

@@ -515,6 +515,36 @@ int32_t saap_dense_decode_attention_fp8(const void* q, const uint8_t* K8, const 
                                         int32_t S, int32_t Hq, int32_t Hkv, int32_t N, int32_t d,
                                         void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * append_keys_fp8 / window_push_fp8 -- saap_append_keys and saap_window_push on an 8-bit cache:
+ * keys generated after prefill (Section 3: the key of each new token is assigned to a bucket
+ * like the prefill keys) join a cache whose scales saap_quantize_kv has fixed.
+ *   x_new, k_new, v_new [S,Hkv,d] bf16; centroids [Hkv,B,d] bf16, bias [Hkv,B] or NULL
+ *   K8, V8 [S,Hkv,Ncap,d] uint8 and kscale, vscale [S,Hkv] fp32 as written by saap_quantize_kv
+ *   every other argument, the bucket choice, the slot taken, the overflow behaviour and the
+ *   workspace as in the 16-bit call of the same name
+ * The stored row is code(x / scale) of its (sequence, head), ties to even; a feature beyond
+ * 448 * scale takes the largest finite code of its sign (the scales stay as they are: a
+ * caller that expects growing magnitudes quantises again from a 16-bit copy).  A key that a
+ * push displaces moves inside the cache as bytes.
+ */
+int32_t saap_append_keys_fp8(const void* x_new, const void* k_new, const void* v_new,
+                             const int32_t* pos_new, const void* centroids, const float* bias,
+                             const int32_t* off, int32_t* len, int32_t* idx,
+                             uint8_t* K8, uint8_t* V8, const float* kscale, const float* vscale,
+                             int32_t* new_bucket_ids, int32_t* overflow_flag,
+                             int32_t S, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d,
+                             void* ws, size_t ws_bytes, void* stream);
+
+int32_t saap_window_push_fp8(const void* x_new, const void* k_new, const void* v_new,
+                             const int32_t* pos_new, const void* centroids, const float* bias,
+                             const int32_t* off, int32_t* len, int32_t* idx,
+                             uint8_t* K8, uint8_t* V8, const float* kscale, const float* vscale,
+                             int32_t* resident_ids, int32_t* new_bucket_ids, int32_t* overflow_flag,
+                             int32_t S, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d,
+                             int32_t n_sink, int32_t n_recent,
+                             void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

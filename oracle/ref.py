@@ -225,6 +225,17 @@ def quantize_fp8(x):
     return codes, scale
 
 
+def quantize_fp8_scaled(x, scale):
+    """x [S,Hkv,rows,d] with the units' scales [S,Hkv] given -> codes uint8, saturated at +-448."""
+    x = _f32(x)
+    scale = _f32(scale)
+    S, Hkv, rows, d = x.shape
+    assert scale.shape == (S, Hkv)
+    codes = np.empty(x.shape, dtype=np.uint8)
+    lib().ref_quantize_fp8_scaled(_p(x), _p(scale), _p(codes), ctypes.c_longlong(S * Hkv), ctypes.c_longlong(rows), d)
+    return codes
+
+
 def dequantize_fp8(codes, scale):
     """codes uint8 [S,Hkv,rows,d], scale [S,Hkv] -> float32 [S,Hkv,rows,d] = scale * value(code), exact."""
     codes = np.ascontiguousarray(np.asarray(codes, dtype=np.uint8))
@@ -282,6 +293,8 @@ def sparse_decode_attention(q, K, V, off, ln, idx, selected, scale, mode=0):
     B = ln.shape[2]
     Ncap = idx.shape[2]
     nprobe = selected.shape[2]
+    if idx.size and int(idx.max()) >= Nrows:
+        raise ValueError(f"idx names position {int(idx.max())}, K holds {Nrows} rows")
     out = np.empty((S, Hq, d), dtype=np.float64)
     lse = np.empty((S, Hq), dtype=np.float64)
     lib().ref_sparse_decode_attention(_p(q), _p(K), _p(V), _p(off), _p(ln), _p(idx), _p(selected), nprobe,

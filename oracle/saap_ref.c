@@ -593,6 +593,19 @@ void ref_quantize_fp8(const float* x, uint8_t* codes, float* scale, long long un
   }
 }
 
+/* Rows that join a cache whose scales are already fixed: x [units, rows, d], scale [units] ->
+ * codes of x / scale, values beyond the format's range taking the largest finite code (+-448). */
+void ref_quantize_fp8_scaled(const float* x, const float* scale, uint8_t* codes, long long units, long long rows,
+                             int d) {
+  for (long long u = 0; u < units; ++u)
+    for (long long i = 0; i < rows * d; ++i) {
+      float y = x[(size_t)u * rows * d + i] / scale[u];
+      if (y > 448.f) y = 448.f;
+      if (y < -448.f) y = -448.f;
+      codes[(size_t)u * rows * d + i] = ref_fp8_e4m3_encode(y);
+    }
+}
+
 /* codes [units, rows, d], scale [units] -> x [units, rows, d] = scale * value(code) (exact in float) */
 void ref_dequantize_fp8(const uint8_t* codes, const float* scale, float* x, long long units, long long rows, int d) {
   for (long long u = 0; u < units; ++u)

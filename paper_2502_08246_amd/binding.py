@@ -28,6 +28,7 @@ EXPORTS = (
     "saap_assign_keys", "saap_build_bucket_index", "saap_append_keys", "saap_classify_queries",
     "saap_select_buckets", "saap_sparse_decode_attention", "saap_dense_decode_attention", "saap_stream_read_probe",
     "saap_build_windowed_index", "saap_window_push", "saap_windowed_decode_attention",
+    "saap_append_keys_fp8", "saap_window_push_fp8",
     "saap_select_buckets_from_logits", "saap_update_centroids", "saap_recompact_index",
     "saap_quantize_kv", "saap_sparse_decode_attention_fp8", "saap_dense_decode_attention_fp8",
     "saap_windowed_decode_attention_fp8",
@@ -202,6 +203,55 @@ def append_keys(x_new, k_new, v_new, pos_new, centroids, bias, off, ln, idx, Ks,
                                          _ptr(new_ids), _ptr(overflow_flag), _i32(S), _i32(Hkv), _i32(Ncap), _i32(B),
                                          _i32(d), _i32(_dtype_code(x_new)), _ptr(ws), wsb, _stream())
     _check("saap_append_keys", st)
+    return new_ids, overflow_flag
+
+
+def _bf16_only(name, *tensors):
+    for t in tensors:
+        if t.dtype != torch.bfloat16:
+            raise TypeError(f"{name}: bf16 features and rows expected, got {t.dtype}")
+
+
+def append_keys_fp8(x_new, k_new, v_new, pos_new, centroids, bias, off, ln, idx, K8, V8, kscale, vscale,
+                    overflow_flag=None, new_ids=None, ws=None):
+    """append_keys on an 8-bit cache (K8, V8 uint8 with the scales of quantize_kv), in place."""
+    _bf16_only("append_keys_fp8", x_new, k_new, v_new, centroids)
+    S, Hkv, d = x_new.shape
+    B = centroids.shape[1]
+    Ncap = idx.shape[2]
+    dev = x_new.device
+    if new_ids is None:
+        new_ids = torch.empty(S, Hkv, dtype=torch.int32, device=dev)
+    if overflow_flag is None:
+        overflow_flag = torch.zeros(4, dtype=torch.int32, device=dev)
+    ws, wsb = _ws(OP_APPEND_KEYS, dev, ws, S=S, Hkv=Hkv, B=B)
+    st = load_library().saap_append_keys_fp8(
+        _ptr(x_new), _ptr(k_new), _ptr(v_new), _ptr(pos_new), _ptr(centroids), _ptr(bias), _ptr(off), _ptr(ln),
+        _ptr(idx), _ptr(K8), _ptr(V8), _ptr(kscale), _ptr(vscale), _ptr(new_ids), _ptr(overflow_flag), _i32(S),
+        _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _ptr(ws), wsb, _stream())
+    _check("saap_append_keys_fp8", st)
+    return new_ids, overflow_flag
+
+
+def window_push_fp8(x_new, k_new, v_new, pos_new, centroids, bias, off, ln, idx, K8, V8, kscale, vscale, resident_ids,
+                    n_sink, n_recent, overflow_flag=None, new_ids=None, ws=None):
+    """window_push on an 8-bit cache (K8, V8 uint8 with the scales of quantize_kv), in place."""
+    _bf16_only("window_push_fp8", x_new, k_new, v_new, centroids)
+    S, Hkv, d = x_new.shape
+    B = centroids.shape[1]
+    Ncap = idx.shape[2]
+    dev = x_new.device
+    if new_ids is None:
+        new_ids = torch.empty(S, Hkv, dtype=torch.int32, device=dev)
+    if overflow_flag is None:
+        overflow_flag = torch.zeros(4, dtype=torch.int32, device=dev)
+    ws, wsb = _ws(OP_WINDOW_PUSH, dev, ws, S=S, Hkv=Hkv, B=B)
+    st = load_library().saap_window_push_fp8(
+        _ptr(x_new), _ptr(k_new), _ptr(v_new), _ptr(pos_new), _ptr(centroids), _ptr(bias), _ptr(off), _ptr(ln),
+        _ptr(idx), _ptr(K8), _ptr(V8), _ptr(kscale), _ptr(vscale), _ptr(resident_ids), _ptr(new_ids),
+        _ptr(overflow_flag), _i32(S), _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _i32(n_sink), _i32(n_recent), _ptr(ws),
+        wsb, _stream())
+    _check("saap_window_push_fp8", st)
     return new_ids, overflow_flag
 
 

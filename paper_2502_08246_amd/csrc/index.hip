@@ -292,12 +292,25 @@ struct PushPartial {
 // workgroup reads that state up front (the loads overlap the scoring), slab 0 copies the displaced
 // row to its bucket, and the last workgroup, which runs after all of these reads, writes the new
 // row and the updated counts.
-template <typename T>
+// C: element type of the cache.  C = T stores the new rows as they are; C = fp8_t (an 8-bit cache,
+// T = bf16) stores x / scale of the (sequence, head) rounded to E4M3, saturated at +-448.
+template <typename C, typename T>
+__device__ __forceinline__ C to_cache(T v, float inv_scale) {
+  if constexpr (sizeof(C) == sizeof(T)) {
+    return v;
+  } else {
+    const float f = fminf(fmaxf(Vec8<T>::widen(v) * inv_scale, -448.f), 448.f);
+    return (C)(__builtin_amdgcn_cvt_pk_fp8_f32(f, f, 0, false) & 0xff);
+  }
+}
+
+template <typename T, typename C = T>
 __global__ void __launch_bounds__(64)
 window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, const T* __restrict__ v_new,
                    const int32_t* __restrict__ pos_new, const T* __restrict__ cent, const float* __restrict__ bias,
                    const int32_t* __restrict__ off, int32_t* __restrict__ len, int32_t* __restrict__ idx,
-                   T* __restrict__ Ks, T* __restrict__ Vs, int32_t* __restrict__ res_ids,
+                   C* __restrict__ Ks, C* __restrict__ Vs, const float* __restrict__ kscale,
+                   const float* __restrict__ vscale, int32_t* __restrict__ res_ids,
                    int32_t* __restrict__ new_ids, int32_t* __restrict__ overflow, PushPartial* __restrict__ part,
                    unsigned* __restrict__ counters, int Hkv, int Ncap, int B, int runs, int n_sink, int n_recent,
                    int P, int cpl /* centroids per lane: a workgroup scores 64 * cpl */) {
@@ -310,8 +323,9 @@ window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, con
   int32_t* l = len + (size_t)unit * runs;
   int32_t* ix = idx + (size_t)unit * Ncap;
   int32_t* rid = res_ids + (size_t)unit * W;
-  T* Ku = Ks + (size_t)unit * Ncap * kD;
-  T* Vu = Vs + (size_t)unit * Ncap * kD;
+  C* Ku = Ks + (size_t)unit * Ncap * kD;
+  C* Vu = Vs + (size_t)unit * Ncap * kD;
+  const float k_inv = kscale ? 1.0f / kscale[unit] : 1.f, v_inv = vscale ? 1.0f / vscale[unit] : 1.f;   // powers of two
 
   // ---- the new key, and what can be decided without its bucket (same values in every lane) ----
   const T x0 = x_new[(size_t)unit * kD + lane], x1 = x_new[(size_t)unit * kD + 64 + lane];
@@ -411,10 +425,10 @@ window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, con
     }
   }
   if (!refused) {
-    Ku[(size_t)slot * kD + lane] = k0;
-    Ku[(size_t)slot * kD + 64 + lane] = k1;
-    Vu[(size_t)slot * kD + lane] = v0;
-    Vu[(size_t)slot * kD + 64 + lane] = v1;
+    Ku[(size_t)slot * kD + lane] = to_cache<C, T>(k0, k_inv);
+    Ku[(size_t)slot * kD + 64 + lane] = to_cache<C, T>(k1, k_inv);
+    Vu[(size_t)slot * kD + lane] = to_cache<C, T>(v0, v_inv);
+    Vu[(size_t)slot * kD + 64 + lane] = to_cache<C, T>(v1, v_inv);
   }
 }
 
@@ -611,13 +625,13 @@ extern "C" int32_t saap_window_push(const void* x_new, const void* k_new, const 
     hipLaunchKernelGGL(window_push_kernel<bf16_t>, grid, dim3(64), 0, hs, static_cast<const bf16_t*>(x_new),
                        static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new), pos_new,
                        static_cast<const bf16_t*>(centroids), bias, off, len, idx, static_cast<bf16_t*>(Ksorted),
-                       static_cast<bf16_t*>(Vsorted), resident_ids, new_bucket_ids, overflow_flag, part, counters,
+                       static_cast<bf16_t*>(Vsorted), nullptr, nullptr, resident_ids, new_bucket_ids, overflow_flag, part, counters,
                        Hkv, Ncap, B, B + 1, n_sink, n_recent, P, cpl);
   else
     hipLaunchKernelGGL(window_push_kernel<float>, grid, dim3(64), 0, hs, static_cast<const float*>(x_new),
                        static_cast<const float*>(k_new), static_cast<const float*>(v_new), pos_new,
                        static_cast<const float*>(centroids), bias, off, len, idx, static_cast<float*>(Ksorted),
-                       static_cast<float*>(Vsorted), resident_ids, new_bucket_ids, overflow_flag, part, counters,
+                       static_cast<float*>(Vsorted), nullptr, nullptr, resident_ids, new_bucket_ids, overflow_flag, part, counters,
                        Hkv, Ncap, B, B + 1, n_sink, n_recent, P, cpl);
   return launch_status();
 }
@@ -650,15 +664,68 @@ extern "C" int32_t saap_append_keys(const void* x_new, const void* k_new, const 
     hipLaunchKernelGGL(window_push_kernel<bf16_t>, grid, dim3(64), 0, hs, static_cast<const bf16_t*>(x_new),
                        static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new), pos_new,
                        static_cast<const bf16_t*>(centroids), bias, off, len, idx, static_cast<bf16_t*>(Ksorted),
-                       static_cast<bf16_t*>(Vsorted), no_resident, new_bucket_ids, overflow_flag, part, counters, Hkv,
+                       static_cast<bf16_t*>(Vsorted), nullptr, nullptr, no_resident, new_bucket_ids, overflow_flag, part, counters, Hkv,
                        Ncap, B, B, 0, 0, P, cpl);
   else
     hipLaunchKernelGGL(window_push_kernel<float>, grid, dim3(64), 0, hs, static_cast<const float*>(x_new),
                        static_cast<const float*>(k_new), static_cast<const float*>(v_new), pos_new,
                        static_cast<const float*>(centroids), bias, off, len, idx, static_cast<float*>(Ksorted),
-                       static_cast<float*>(Vsorted), no_resident, new_bucket_ids, overflow_flag, part, counters, Hkv,
+                       static_cast<float*>(Vsorted), nullptr, nullptr, no_resident, new_bucket_ids, overflow_flag, part, counters, Hkv,
                        Ncap, B, B, 0, 0, P, cpl);
   return launch_status();
+}
+
+// The push kernel on an 8-bit cache (bf16 features and new rows, E4M3 rows in the cache).
+// res_ids == nullptr: plain index (append), else the index with a resident run.
+static int32_t push_fp8(const void* x_new, const void* k_new, const void* v_new, const int32_t* pos_new,
+                        const void* centroids, const float* bias, const int32_t* off, int32_t* len, int32_t* idx,
+                        uint8_t* K8, uint8_t* V8, const float* kscale, const float* vscale, int32_t* res_ids,
+                        int32_t* new_bucket_ids, int32_t* overflow_flag, int32_t S, int32_t Hkv, int32_t Ncap,
+                        int32_t B, int32_t d, int32_t n_sink, int32_t n_recent, void* ws, size_t ws_bytes,
+                        void* stream) {
+  if (!x_new || !k_new || !v_new || !centroids || !off || !len || !idx || !K8 || !V8 || !kscale || !vscale ||
+      !new_bucket_ids || !overflow_flag || !ws)
+    return SAAP_INVALID_ARG;
+  if (!aligned16(centroids) || !aligned16(ws)) return SAAP_INVALID_ARG;
+  if (S <= 0 || Hkv <= 0 || Ncap <= 0 || B <= 0 || n_sink < 0 || n_recent < 0) return SAAP_INVALID_ARG;
+  if (res_ids && (!pos_new || (long long)n_sink + n_recent > Ncap)) return SAAP_INVALID_ARG;
+  if (d != kD || B > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
+  const long long units = (long long)S * Hkv;
+  if (units > 65535 || units * sizeof(unsigned) > SAAP_WS_HEADER_BYTES) return SAAP_UNSUPPORTED;
+  if (ws_bytes < push_workspace_bytes(units, B)) return SAAP_WORKSPACE_TOO_SMALL;
+  const int cpl = push_centroids_per_lane(units, B);
+  const int P = (B + kPushSlab * cpl - 1) / (kPushSlab * cpl);
+  unsigned* counters = static_cast<unsigned*>(ws);
+  PushPartial* part = reinterpret_cast<PushPartial*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
+  hipLaunchKernelGGL((window_push_kernel<bf16_t, fp8_t>), dim3((unsigned)P, (unsigned)units), dim3(64), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const bf16_t*>(x_new),
+                     static_cast<const bf16_t*>(k_new), static_cast<const bf16_t*>(v_new), pos_new,
+                     static_cast<const bf16_t*>(centroids), bias, off, len, idx, K8, V8, kscale, vscale, res_ids,
+                     new_bucket_ids, overflow_flag, part, counters, Hkv, Ncap, B, res_ids ? B + 1 : B, n_sink, n_recent,
+                     P, cpl);
+  return launch_status();
+}
+
+extern "C" int32_t saap_append_keys_fp8(const void* x_new, const void* k_new, const void* v_new,
+                                        const int32_t* pos_new, const void* centroids, const float* bias,
+                                        const int32_t* off, int32_t* len, int32_t* idx, uint8_t* K8, uint8_t* V8,
+                                        const float* kscale, const float* vscale, int32_t* new_bucket_ids,
+                                        int32_t* overflow_flag, int32_t S, int32_t Hkv, int32_t Ncap, int32_t B,
+                                        int32_t d, void* ws, size_t ws_bytes, void* stream) {
+  return push_fp8(x_new, k_new, v_new, pos_new, centroids, bias, off, len, idx, K8, V8, kscale, vscale, nullptr,
+                  new_bucket_ids, overflow_flag, S, Hkv, Ncap, B, d, 0, 0, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t saap_window_push_fp8(const void* x_new, const void* k_new, const void* v_new,
+                                        const int32_t* pos_new, const void* centroids, const float* bias,
+                                        const int32_t* off, int32_t* len, int32_t* idx, uint8_t* K8, uint8_t* V8,
+                                        const float* kscale, const float* vscale, int32_t* resident_ids,
+                                        int32_t* new_bucket_ids, int32_t* overflow_flag, int32_t S, int32_t Hkv,
+                                        int32_t Ncap, int32_t B, int32_t d, int32_t n_sink, int32_t n_recent,
+                                        void* ws, size_t ws_bytes, void* stream) {
+  if (!resident_ids) return SAAP_INVALID_ARG;
+  return push_fp8(x_new, k_new, v_new, pos_new, centroids, bias, off, len, idx, K8, V8, kscale, vscale, resident_ids,
+                  new_bucket_ids, overflow_flag, S, Hkv, Ncap, B, d, n_sink, n_recent, ws, ws_bytes, stream);
 }
 
 extern "C" int32_t saap_recompact_index(const int32_t* off, const int32_t* len, const int32_t* idx,

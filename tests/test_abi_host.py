@@ -176,6 +176,19 @@ def test_invalid_arguments_of_the_later_calls_are_rejected_on_the_host(lib):
                                           i32(1), i32(100), i32(8), i32(128), i32(2), ws, big, None)
     assert st == -1
 
+    def push8(**kw):
+        a = dict(ks=ks, pos=sel, res=sel, Ncap=116, B=8, d=128, wsb=big)
+        a.update(kw)
+        return lib.saap_window_push_fp8(q, K, V, a["pos"], q, None, off, ln, sel, out, lse, a["ks"], vs, a["res"], sel, sel,
+                                        i32(1), i32(1), i32(a["Ncap"]), i32(a["B"]), i32(a["d"]), i32(1), i32(15), ws,
+                                        a["wsb"], None)
+
+    assert push8(ks=None) == -1 and push8(pos=None) == -1 and push8(res=None) == -1 and push8(Ncap=10) == -1
+    assert push8(d=64) == -2 and push8(wsb=ctypes.c_size_t(100)) == -3
+    st = lib.saap_append_keys_fp8(q, K, V, None, q, None, off, ln, sel, out, lse, ks, None, sel, sel, i32(1), i32(1), i32(116),
+                                  i32(8), i32(128), ws, big, None)
+    assert st == -1                                         # vscale missing
+
     def mass(**kw):
         a = dict(q=q, m=out, Hq=4, Hkv=1, B=8, d=128, dt=1, wsb=big)
         a.update(kw)

@@ -211,3 +211,149 @@ def test_windowed_attention_fp8(saap, n_sink, n_recent, nprobe):
         ro, rl = ref.windowed_decode_attention(h(q[t]), Kp, Vp, ids.cpu().numpy(), sel_np, n_sink, n_recent, np.float32(SCALE), B)
         assert_close(out.cpu().numpy(), ro, "out")
         assert_close(lse.cpu().numpy(), rl, "lse")
+
+
+def _live(off, ln, idx):
+    """Boolean mask [S,Hkv,Ncap] of the slots that hold a key."""
+    live = np.zeros(idx.shape, dtype=bool)
+    S, Hkv, _ = idx.shape
+    for s in range(S):
+        for u in range(Hkv):
+            for b in range(ln.shape[2]):
+                live[s, u, off[s, u, b]:off[s, u, b] + ln[s, u, b]] = True
+    return live & (idx >= 0)
+
+
+def _oracle_scales(rKs, rVs, live):
+    """Scales of a cache as quantize_kv fixes them: free slots hold zeros."""
+    rKs = np.where(live[..., None], rKs, 0).astype(np.float32)
+    rVs = np.where(live[..., None], rVs, 0).astype(np.float32)
+    return ref.quantize_fp8(rKs)[1], ref.quantize_fp8(rVs)[1]
+
+
+def _as_stored(x, scale):
+    """Values a row has once it is in the 8-bit cache: decoded codes of x / scale (saturated)."""
+    return ref.dequantize_fp8(ref.quantize_fp8_scaled(x, scale), scale)
+
+
+@pytest.mark.parametrize("S,Hkv,N,B,slack,n_sink,n_recent,steps", [
+    (2, 2, 3000, 16, 100, 1, 63, 150),                     # the ring wraps twice: displaced rows move as bytes
+    (1, 2, 2100, 16, 16, 3, 0, 20),                        # no ring: new rows go straight to their buckets
+    (1, 1, 40, 8, 64, 2, 100, 130),                        # the window fills first, then slides
+])
+def test_window_push_fp8(saap, S, Hkv, N, B, slack, n_sink, n_recent, steps):
+    """Generation on an 8-bit cache: index state bit for bit, stored codes bit for bit against the oracle's
+    encoder with the cache's scales, attention on the grown cache against the oracle on the decoded values."""
+    Hq = 2 * Hkv
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(S=S, Hq=Hq, Hkv=Hkv, N=N + steps, B=B, nprobe=4, dtype="bf16", hidden=64)
+    cache = gen.make_cache(cfg, 67, DEV)
+    cent = gen.make_centroids(cfg, 67, DEV, cache, n_train=2048)
+    _, q = gen.make_queries(cfg, 67, DEV, n_steps=3)
+    x, K, V = cache["x_keys"], cache["K"].clone(), cache["V"].clone()
+    # two later rows leave the range that the prefill keys fixed: their features saturate at +-448 * scale
+    K[0, 0, N + 5, :4] = torch.tensor([3e4, -3e4, 1e30, -1e30]).to(K.dtype)
+    V[0, 0, N + 7, 9] = -5e4
+    ids_all = saap.assign_keys(x, cent)
+    ids0, K0, V0 = (a[:, :, :N].contiguous() for a in (ids_all, K, V))
+    off, ln, idx, Ks, Vs, res = saap.build_windowed_index(ids0, K0, V0, B, slack, n_sink, n_recent)
+    K8, V8, ks, vs = saap.quantize_kv(Ks, Vs)
+    torch.cuda.synchronize()
+    # the oracle's side, from the inputs alone
+    h_ids, hK, hV, hx, hc = ids_all.cpu().numpy(), h(K), h(V), h(x), h(cent)
+    assert np.array_equal(h_ids, ref.assign_keys(hx, hc))
+    r0 = ref.build_windowed_index(h_ids[:, :, :N], hK[:, :, :N], hV[:, :, :N], B, slack, n_sink, n_recent)
+    rks, rvs = _oracle_scales(r0[3], r0[4], _live(r0[0], r0[1], r0[2]))
+    assert np.array_equal(ks.cpu().numpy(), rks) and np.array_equal(vs.cpu().numpy(), rvs)
+    Kq, Vq = _as_stored(hK, rks), _as_stored(hV, rvs)      # every position as the cache will hold it
+    want = list(ref.build_windowed_index(h_ids[:, :, :N], Kq[:, :, :N], Vq[:, :, :N], B, slack, n_sink, n_recent))
+
+    def compare(what):
+        torch.cuda.synchronize()
+        for name, got, exp in (("off", off, want[0]), ("len", ln, want[1]), ("idx", idx, want[2]), ("resident", res, want[5])):
+            assert np.array_equal(got.cpu().numpy(), exp), f"{what}: {name}"
+        live = _live(want[0], want[1], want[2])
+        for name, got, exp, sc in (("K", K8, want[3], rks), ("V", V8, want[4], rvs)):
+            codes = ref.quantize_fp8_scaled(exp, sc)        # exact: the oracle's rows are decoded codes
+            assert np.array_equal(ref.dequantize_fp8(codes, sc)[live], exp[live])
+            assert np.array_equal(got.cpu().numpy()[live], codes[live]), f"{what}: {name} codes"
+
+    compare("after build")
+    flag = torch.zeros(4, dtype=torch.int32, device=DEV)
+    rng = np.random.default_rng(5)
+    check_at = {0, 5, 7, 8, steps // 2, steps - 1}
+    for t in range(steps):
+        pos = torch.full((S,), N + t, dtype=torch.int32, device=DEV)
+        xn, kn, vn = (a[:, :, N + t].contiguous() for a in (x, K, V))
+        nid, _ = saap.window_push_fp8(xn, kn, vn, pos, cent, None, off, ln, idx, K8, V8, ks, vs, res, n_sink, n_recent,
+                                      overflow_flag=flag)
+        rid, rflag = ref.window_push(hx[:, :, N + t], Kq[:, :, N + t], Vq[:, :, N + t], pos.cpu().numpy(), hc, None,
+                                     want[0], want[1], want[2], want[3], want[4], want[5], n_sink, n_recent)
+        assert rflag == 0, "test sizing: slack must absorb every displaced key"
+        if t in check_at:
+            compare(f"after push {t}")
+            assert np.array_equal(nid.cpu().numpy(), rid)
+            Nt = N + t + 1
+            for nprobe in (0, 4, B):
+                sel = np.stack([np.stack([rng.permutation(B)[:nprobe] for _ in range(Hkv)]) for _ in range(S)]).astype(np.int32)
+                sel = sel.reshape(S, Hkv, nprobe)
+                out, lse = saap.windowed_decode_attention_fp8(q[t % 3], K8, V8, ks, vs, off, ln, torch.from_numpy(sel).to(DEV),
+                                                              B, SCALE)
+                torch.cuda.synchronize()
+                ro, rl = ref.windowed_decode_attention(h(q[t % 3]), Kq[:, :, :Nt], Vq[:, :, :Nt], h_ids[:, :, :Nt], sel,
+                                                       n_sink, n_recent, np.float32(SCALE), B)
+                assert_close(out.cpu().numpy(), ro, f"push {t} nprobe {nprobe} out")
+                assert_close(lse.cpu().numpy(), rl, f"push {t} nprobe {nprobe} lse")
+    torch.cuda.synchronize()
+    assert flag[0].item() == 0
+    # the planted rows did saturate
+    assert float(np.abs(Kq[0, 0, N + 5, :4]).max()) == 448.0 * float(rks[0, 0])
+    assert float(Vq[0, 0, N + 7, 9]) == -448.0 * float(rvs[0, 0])
+
+
+def test_append_keys_fp8(saap):
+    """The index without a resident run: appended rows, their codes, and the overflow flag once a bucket's
+    slack has run out (nothing changes for that unit then)."""
+    S, Hkv, N, B, slack, steps = 2, 2, 2000, 32, 2, 6
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(S=S, Hq=8, Hkv=Hkv, N=N, B=B, nprobe=B, dtype="bf16", hidden=64)
+    cache = gen.make_cache(cfg, 71, DEV)
+    cent = gen.make_centroids(cfg, 71, DEV, cache, n_train=2048)
+    _, q = gen.make_queries(cfg, 71, DEV)
+    new = gen.make_cache(cfg.replace(N=steps), 73, DEV)
+    new["x_keys"][0, 0, :] = (4.0 * cent[0, 3].float()).to(new["x_keys"].dtype)   # one bucket takes every new key of unit (0,0)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], B, slack)
+    K8, V8, ks, vs = saap.quantize_kv(Ks, Vs)
+    torch.cuda.synchronize()
+    h_ids = ids.cpu().numpy()
+    hK, hV = h(cache["K"]), h(cache["V"])
+    r0 = ref.build_bucket_index(h_ids, hK, hV, B, slack)
+    rks, rvs = _oracle_scales(r0[3], r0[4], _live(r0[0], r0[1], r0[2]))
+    assert np.array_equal(ks.cpu().numpy(), rks) and np.array_equal(vs.cpu().numpy(), rvs)
+    Kq, Vq = _as_stored(hK, rks), _as_stored(hV, rvs)
+    nKq, nVq = _as_stored(h(new["K"]), rks), _as_stored(h(new["V"]), rvs)
+    r_off, r_ln, r_idx, rKs, rVs = ref.build_bucket_index(h_ids, Kq, Vq, B, slack)
+    flags = []
+    for t in range(steps):
+        pos = torch.full((S,), N + t, dtype=torch.int32, device=DEV)
+        xn, kn, vn = (new[k][:, :, t].contiguous() for k in ("x_keys", "K", "V"))
+        nid, flag = saap.append_keys_fp8(xn, kn, vn, pos, cent, None, off, ln, idx, K8, V8, ks, vs)
+        torch.cuda.synchronize()
+        rid, rflag = ref.append_keys(h(xn), nKq[:, :, t], nVq[:, :, t], pos.cpu().numpy(), h(cent), None, r_off, r_ln, r_idx,
+                                     rKs, rVs)
+        flags.append(rflag)
+        assert np.array_equal(nid.cpu().numpy(), rid)
+        assert (flag[0].item() != 0) == (rflag != 0)
+        assert np.array_equal(ln.cpu().numpy(), r_ln) and np.array_equal(idx.cpu().numpy(), r_idx)
+    assert flags[0] == 0 and flags[-1] == 1
+    live = _live(r_off, r_ln, r_idx)
+    assert np.array_equal(K8.cpu().numpy()[live], ref.quantize_fp8_scaled(rKs, rks)[live])
+    assert np.array_equal(V8.cpu().numpy()[live], ref.quantize_fp8_scaled(rVs, rvs)[live])
+    # attention over every bucket of the grown cache
+    sel = torch.arange(B, dtype=torch.int32, device=DEV).repeat(S, Hkv, 1)
+    out, lse = saap.sparse_decode_attention_fp8(q[0], K8, V8, ks, vs, off, ln, sel, SCALE)
+    torch.cuda.synchronize()
+    Kall = position_order(rKs, r_idx)
+    Vall = position_order(rVs, r_idx)
+    ro, rl = ref.sparse_decode_attention(h(q[0]), Kall, Vall, r_off, r_ln, r_idx, sel.cpu().numpy(), SCALE)
+    assert_close(out.cpu().numpy(), ro, "attention after append")
+    assert_close(lse.cpu().numpy(), rl, "lse after append")

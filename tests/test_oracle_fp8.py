@@ -94,6 +94,28 @@ def test_unit_scale_is_the_smallest_power_of_two_that_fits():
     assert np.array_equal(y, t[codes] * scale[:, :, None, None].astype(np.float64))
 
 
+def test_rows_quantised_with_given_scales_agree_with_the_unit_quantiser_and_saturate():
+    """Rows that join later: inside the range the codes are those quantize_fp8 gives with the same scale
+    (checked against the nearest-value search too); beyond it they take +-448, never a NaN code."""
+    rng = np.random.default_rng(23)
+    x = (rng.standard_normal((2, 2, 40, 128)) * np.array([0.3, 11.0])[:, None, None, None]).astype(np.float32)
+    codes, scale = ref.quantize_fp8(x)
+    assert np.array_equal(ref.quantize_fp8_scaled(x, scale), codes)
+    t = _table()
+    row = x[1, 1, :1].copy().reshape(1, 1, 1, 128)
+    sc = scale[1:2, 1:2]
+    row[0, 0, 0, :6] = np.array([448.0, 449.0, 1e9, -448.0, -460.0, -3e38], dtype=np.float32) * sc[0, 0]
+    got = ref.quantize_fp8_scaled(row, sc)[0, 0, 0]
+    assert list(got[:6]) == [0x7E, 0x7E, 0x7E, 0xFE, 0xFE, 0xFE]
+    for j in range(6, 128):
+        assert got[j] & 0x7F == _nearest_code(abs(float(row[0, 0, 0, j]) / float(sc[0, 0])), t)
+    # a scale other than the unit's own: plain division, then the same rounding
+    other = np.full((2, 2), 0.25, dtype=np.float32)
+    y = ref.quantize_fp8_scaled(x[:, :, :2], other)
+    for v, c in zip(x[0, 0, 0, :32], y[0, 0, 0, :32]):
+        assert c == ref.fp8_e4m3_encode(min(max(float(v) / 0.25, -448.0), 448.0))
+
+
 def test_attention_on_a_quantised_cache_is_attention_on_its_decoded_values():
     """Brute force in numpy on the decoded cache, against the oracle's sparse attention fed the same values."""
     rng = np.random.default_rng(11)
