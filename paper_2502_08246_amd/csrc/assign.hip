@@ -213,15 +213,15 @@ assign_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent
     const float ob = __shfl_xor(best[rt], 32);
     const float os = __shfl_xor(second[rt], 32);
     const int oid = __shfl_xor(id, 32);
-    float b1 = best[rt], s1 = second[rt];
+    const float mb = best[rt], ms = second[rt];
     float nb, ns;
-    if (ob > b1 || (ob == b1 && oid < id)) {
+    if (ob > mb || (ob == mb && oid < id)) {
       nb = ob;
-      ns = fmaxf(b1, os);
+      ns = fmaxf(mb, os);
       id = oid;
     } else {
-      nb = b1;
-      ns = fmaxf(ob, s1);
+      nb = mb;
+      ns = fmaxf(ob, ms);
     }
     const int row = row_base + rt * 32 + col;
     listed[rt] = false;

@@ -369,9 +369,9 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
     }
     __syncthreads();
     for (int i = tid; i < n_cand; i += nt) {
-      const unsigned long long key = sortbuf[i];
-      const int bk = bucket_of(key);
-      tmp[bbase[bk] + atomicAdd(&fill[bk], 1u)] = key;
+      const unsigned long long cand = sortbuf[i];
+      const int bk = bucket_of(cand);
+      tmp[bbase[bk] + atomicAdd(&fill[bk], 1u)] = cand;
     }
     __syncthreads();
     for (int i = tid; i < n_cand; i += nt) {

@@ -38,8 +38,11 @@ def parse():
     return ap.parse_args()
 
 
-def train(cfg, train_queries=2048, eval_queries=64, steps=400, batch=1024, lr=1e-3, seed=0):
-    """Runs the whole procedure on workload `cfg` (one sequence) and returns the report as a dict."""
+def train(cfg, train_queries=2048, eval_queries=64, steps=400, batch=1024, lr=1e-3, seed=0, centroids=None,
+          return_weights=False):
+    """Runs the whole procedure on workload `cfg` (one sequence) and returns the report as a dict.
+    centroids [Hkv,B,d]: the partition to train for (default: the workload's own centroids);
+    return_weights: the report also holds "weights" = (W1, b1, W2, b2) as classify_queries takes them."""
     import types
 
     import torch
@@ -59,7 +62,7 @@ def train(cfg, train_queries=2048, eval_queries=64, steps=400, batch=1024, lr=1e
     scale = 1.0 / math.sqrt(d)
 
     cache = gen.make_cache(cfg, args.seed, dev)
-    cent = gen.make_centroids(cfg, args.seed, dev, cache)
+    cent = centroids if centroids is not None else gen.make_centroids(cfg, args.seed, dev, cache)
     ids = saap.assign_keys(cache["x_keys"], cent)
     off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], B, 0)
     del cache, Vs
@@ -140,7 +143,7 @@ def train(cfg, train_queries=2048, eval_queries=64, steps=400, batch=1024, lr=1e
     train_s = time.perf_counter() - t0
     cap_trained, _ = evaluate(as_inference_weights(P))
 
-    return {
+    report = {
         "workload": cfg.name, "B": B, "nprobe": cfg.nprobe, "classifier": f"{d}->{cfg.hidden}->{B}", "weight_sets": Hw,
         "train_queries_per_head": n_tr, "eval_queries_per_head": T_all - n_tr, "steps": args.steps, "batch_rows": R,
         "lr": args.lr, "loss": losses, "ms_per_step": round(train_s / max(args.steps, 1) * 1e3, 3),
@@ -149,6 +152,9 @@ def train(cfg, train_queries=2048, eval_queries=64, steps=400, batch=1024, lr=1e
                                     "kmeans_routing": round(cap_kmeans, 4), "best_possible": round(cap_best, 4)},
         "selectivity": round(cfg.nprobe / B, 4), "data": "synthetic",
     }
+    if return_weights:
+        report["weights"] = as_inference_weights(P)
+    return report
 
 
 def main():
