@@ -448,6 +448,48 @@ int32_t saap_query_model_loss_grads(const void* x, const float* target,
                                     int32_t x_dtype, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * query_model_bn_loss_grads -- the same loss and gradients for the model WITH batch
+ * normalisation of the hidden layer (Section 6.1: two layers, batch normalisation, ReLU):
+ *   a = W1 x + b1;  h = relu(gamma * (a - mean_r a) / sqrt(var_r a + eps) + beta);  z = W2 h + b2
+ * with the statistics of the batch per weight set and hidden unit (variance with divisor R).
+ * The paper gives no constants: eps and momentum are the caller's (1e-5 and 0.1 are usual).
+ *   bn (host struct of device pointers): gamma, beta [Hw,hidden] fp32; grad_gamma, grad_beta out;
+ *   running_mean, running_var [Hw,hidden] fp32 or both NULL: updated in place as
+ *   run = (1 - momentum) run + momentum * batch, the variance entering with divisor R - 1.
+ * R >= 2.  Everything else as saap_query_model_loss_grads; same workspace.
+ */
+typedef struct {
+  float* gamma;
+  float* beta;
+  float* grad_gamma;
+  float* grad_beta;
+  float* running_mean;
+  float* running_var;
+  float momentum;
+  float eps;
+} saap_batch_norm_f32;
+
+int32_t saap_query_model_bn_loss_grads(const void* x, const float* target,
+                                       const saap_mlp_f32* params /* host */,
+                                       const saap_mlp_f32* grads /* host */,
+                                       const saap_batch_norm_f32* bn /* host */, float* loss,
+                                       int32_t Hw, int32_t R, int32_t d, int32_t hidden, int32_t B,
+                                       int32_t x_dtype, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * fold_batch_norm -- the inference form of a model trained with saap_query_model_bn_loss_grads:
+ * with fixed statistics the normalisation is an affine map, so
+ *   s = gamma / sqrt(running_var + eps);  W1' = s * W1 (row-wise);  b1' = (b1 - running_mean) s + beta
+ * and saap_classify_queries on (W1', b1', W2, b2) is the normalised model.
+ *   W1 [Hw,hidden,d], b1, gamma, beta, running_mean, running_var [Hw,hidden] fp32 (device)
+ *   W1_out [Hw,hidden,d] out_dtype (SAAP_F32 or SAAP_BF16, rounded to nearest even); b1_out fp32
+ */
+int32_t saap_fold_batch_norm(const float* W1, const float* b1, const float* gamma, const float* beta,
+                             const float* running_mean, const float* running_var, float eps,
+                             void* W1_out, float* b1_out, int32_t Hw, int32_t hidden, int32_t d,
+                             int32_t out_dtype, void* stream);
+
+/*
  * adam_update -- one step of Adam (the optimiser named in the paper's training details) on one
  * tensor of n fp32 elements, in place:
  *   m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2

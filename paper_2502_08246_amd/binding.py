@@ -33,7 +33,7 @@ EXPORTS = (
     "saap_quantize_kv", "saap_sparse_decode_attention_fp8", "saap_dense_decode_attention_fp8",
     "saap_windowed_decode_attention_fp8",
     "saap_bucket_attention_mass", "saap_query_model_loss_grads", "saap_adam_update",
-    "saap_bucket_attention_mass_batch",
+    "saap_bucket_attention_mass_batch", "saap_query_model_bn_loss_grads", "saap_fold_batch_norm",
 )
 
 
@@ -388,6 +388,58 @@ def query_model_loss_grads(x, target, params, grads=None, loss=None, ws=None):
         _i32(B), _i32(_dtype_code(x)), _ptr(ws), wsb, _stream())
     _check("saap_query_model_loss_grads", st)
     return loss, grads
+
+
+class _BatchNormF32(ctypes.Structure):
+    _fields_ = [("gamma", ctypes.c_void_p), ("beta", ctypes.c_void_p), ("grad_gamma", ctypes.c_void_p),
+                ("grad_beta", ctypes.c_void_p), ("running_mean", ctypes.c_void_p), ("running_var", ctypes.c_void_p),
+                ("momentum", ctypes.c_float), ("eps", ctypes.c_float)]
+
+
+def query_model_bn_loss_grads(x, target, params, gamma, beta, running_mean=None, running_var=None, momentum=0.1, eps=1e-5,
+                              grads=None, grad_gamma=None, grad_beta=None, loss=None, ws=None):
+    """query_model_loss_grads for the model with batch normalisation of the hidden layer; gamma, beta [Hw,hidden]
+    fp32; running_mean / running_var (both or neither) are updated in place.
+    -> loss [Hw], grads (dW1, db1, dW2, db2), grad_gamma, grad_beta."""
+    Hw, R, d = x.shape
+    W1, b1, W2, b2 = params
+    hidden, B = W1.shape[1], W2.shape[1]
+    if W1.shape != (Hw, hidden, d) or b1.shape != (Hw, hidden) or W2.shape != (Hw, B, hidden) or b2.shape != (Hw, B):
+        raise ValueError("parameter shapes do not fit x")
+    if target.shape != (Hw, R, B) or target.dtype != torch.float32:
+        raise ValueError("target must be fp32 [Hw,R,B]")
+    for t in (gamma, beta, running_mean, running_var):
+        if t is not None and (t.shape != (Hw, hidden) or t.dtype != torch.float32):
+            raise ValueError("gamma, beta and the running statistics must be fp32 [Hw,hidden]")
+    dev = x.device
+    grads = grads if grads is not None else tuple(torch.empty_like(p) for p in params)
+    grad_gamma = grad_gamma if grad_gamma is not None else torch.empty_like(gamma)
+    grad_beta = grad_beta if grad_beta is not None else torch.empty_like(beta)
+    loss = loss if loss is not None else torch.empty(Hw, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_QUERY_MODEL_LOSS_GRADS, dev, ws, Hkv=Hw, N=R, d=d, hidden=hidden, B=B)
+    ps, gs = _mlp_struct(params), _mlp_struct(grads)
+    bn = _BatchNormF32(_ptr(gamma), _ptr(beta), _ptr(grad_gamma), _ptr(grad_beta), _ptr(running_mean), _ptr(running_var),
+                       momentum, eps)
+    st = load_library().saap_query_model_bn_loss_grads(
+        _ptr(x), _ptr(target), ctypes.byref(ps), ctypes.byref(gs), ctypes.byref(bn), _ptr(loss), _i32(Hw), _i32(R),
+        _i32(d), _i32(hidden), _i32(B), _i32(_dtype_code(x)), _ptr(ws), wsb, _stream())
+    _check("saap_query_model_bn_loss_grads", st)
+    return loss, grads, grad_gamma, grad_beta
+
+
+def fold_batch_norm(W1, b1, gamma, beta, running_mean, running_var, eps=1e-5, out_dtype=torch.bfloat16):
+    """-> (W1' [Hw,hidden,d] out_dtype, b1' fp32): the inference form of the normalised first layer."""
+    Hw, hidden, d = W1.shape
+    for t in (W1, b1, gamma, beta, running_mean, running_var):
+        if t.dtype != torch.float32:
+            raise TypeError("fold_batch_norm takes fp32 tensors")
+    W1o = torch.empty(Hw, hidden, d, dtype=out_dtype, device=W1.device)
+    b1o = torch.empty(Hw, hidden, dtype=torch.float32, device=W1.device)
+    st = load_library().saap_fold_batch_norm(_ptr(W1), _ptr(b1), _ptr(gamma), _ptr(beta), _ptr(running_mean),
+                                             _ptr(running_var), ctypes.c_float(eps), _ptr(W1o), _ptr(b1o), _i32(Hw),
+                                             _i32(hidden), _i32(d), _i32(_dtype_code(W1o)), _stream())
+    _check("saap_fold_batch_norm", st)
+    return W1o, b1o
 
 
 def adam_update(param, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8):

@@ -2,6 +2,9 @@
 // 2502.08246; Appendix "Training details": Adam):
 //   z = W2 relu(W1 x + b1) + b2,  f_q(x) = softmax(z),
 //   L = 1/R sum_r sum_b T[r,b] (log T[r,b] - log f_q(x_r)[b])       (T: bucket attention mass, rows of A*H_k)
+// With batch normalisation (the model of Section 6.1) the hidden layer is
+//   relu(gamma * (a - mean_r a) / sqrt(var_r a + eps) + beta),  a = W1 x + b1,
+// and fold_batch_norm turns the trained layer into plain W1, b1 for inference.
 // query_model_loss_grads computes L and the gradients of all four parameter tensors for a batch,
 // adam_update applies one Adam step to a tensor; a training step is the first call followed by
 // the second on each tensor.  All arithmetic is fp32, every sum is taken by one thread or one
@@ -148,15 +151,148 @@ loss_mean_kernel(const float* __restrict__ loss_rows, float* __restrict__ loss, 
   if (threadIdx.x == 0) loss[blockIdx.x] = v / (float)R;
 }
 
-// out[n] = sum over the rows of X [rows, n_cols]; one thread per column, rows in order
-__global__ void __launch_bounds__(256)
+// Column sums in a fixed order.  A workgroup owns 64 columns; its 16 waves each take a contiguous slice of
+// the rows (a wave reads 64 neighbouring columns of one row at a time) and the 16 slice sums are added in
+// slice order, so the result does not depend on timing.
+constexpr int kBnCols = 64, kBnSlices = 16, kBnThreads = kBnCols * kBnSlices;
+
+// sum over the slices of v, in slice order; every thread of a column gets the same bits
+__device__ __forceinline__ float slice_sum(float v, float (*s_part)[kBnCols], int col, int slice) {
+  __syncthreads();
+  s_part[slice][col] = v;
+  __syncthreads();
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < kBnSlices; ++i) t += s_part[i][col];
+  return t;
+}
+
+// out[n] = sum over the rows of X [rows, n_cols]
+__global__ void __launch_bounds__(kBnThreads)
 colsum_kernel(const float* __restrict__ X, float* __restrict__ out, int rows, int n_cols, long long sX, long long sOut) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= n_cols) return;
-  const float* x = X + (size_t)blockIdx.y * sX + c;
+  __shared__ float s_part[kBnSlices][kBnCols];
+  const int col = threadIdx.x % kBnCols, slice = threadIdx.x / kBnCols;
+  const int c = blockIdx.x * kBnCols + col;
+  const bool live = c < n_cols;
+  const int per = (rows + kBnSlices - 1) / kBnSlices, r0 = slice * per, r1 = min(r0 + per, rows);
+  const float* x = X + (size_t)blockIdx.y * sX + (live ? c : 0);
   float v = 0.f;
-  for (int r = 0; r < rows; ++r) v += x[(size_t)r * n_cols];
-  out[(size_t)blockIdx.y * sOut + c] = v;
+  if (live)
+    for (int r = r0; r < r1; ++r) v += x[(size_t)r * n_cols];
+  v = slice_sum(v, s_part, col, slice);
+  if (live && slice == 0) out[(size_t)blockIdx.y * sOut + c] = v;
+}
+
+// Batch normalisation of the hidden pre-activations a [rows, n_cols] (Section 6.1 names the layer).
+// Columns and rows are dealt as in colsum_kernel.  The batch mean, then the variance about it (divisor rows).
+// stats [4, n_cols] per weight set: mean, 1/sqrt(var + eps), and room for the two backward sums.
+// Running statistics (optional) follow run = (1 - momentum) run + momentum batch, the variance with
+// divisor rows - 1.
+__global__ void __launch_bounds__(kBnThreads)
+bn_stats_kernel(const float* __restrict__ A, float* __restrict__ stats, float* __restrict__ run_mean,
+                float* __restrict__ run_var, int rows, int n_cols, float eps, float momentum) {
+  __shared__ float s_part[kBnSlices][kBnCols];
+  const int col = threadIdx.x % kBnCols, slice = threadIdx.x / kBnCols;
+  const int c = blockIdx.x * kBnCols + col;
+  const bool live = c < n_cols;
+  const int per = (rows + kBnSlices - 1) / kBnSlices, r0 = slice * per, r1 = min(r0 + per, rows);
+  const float* a = A + (size_t)blockIdx.y * rows * n_cols + (live ? c : 0);
+  float sum = 0.f;
+  if (live)
+    for (int r = r0; r < r1; ++r) sum += a[(size_t)r * n_cols];
+  const float mean = slice_sum(sum, s_part, col, slice) / (float)rows;
+  float sq = 0.f;
+  if (live)
+    for (int r = r0; r < r1; ++r) {
+      const float dlt = a[(size_t)r * n_cols] - mean;
+      sq += dlt * dlt;
+    }
+  sq = slice_sum(sq, s_part, col, slice);
+  if (!live || slice != 0) return;
+  float* st = stats + (size_t)blockIdx.y * 4 * n_cols;
+  st[c] = mean;
+  st[n_cols + c] = 1.0f / sqrtf(sq / (float)rows + eps);
+  if (run_mean) {
+    const size_t i = (size_t)blockIdx.y * n_cols + c;
+    run_mean[i] = (1.0f - momentum) * run_mean[i] + momentum * mean;
+    run_var[i] = (1.0f - momentum) * run_var[i] + momentum * (sq / (float)(rows - 1));
+  }
+}
+
+// h = relu(gamma * ahat + beta), ahat = (a - mean) * rstd
+__global__ void __launch_bounds__(256)
+bn_relu_kernel(const float* __restrict__ A, const float* __restrict__ stats, const float* __restrict__ gamma,
+               const float* __restrict__ beta, float* __restrict__ H, int rows, int n_cols) {
+  const size_t per_set = (size_t)rows * n_cols;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= per_set) return;
+  const int c = (int)(i % n_cols), w = blockIdx.y;
+  const float* st = stats + (size_t)w * 4 * n_cols;
+  const float ahat = (A[w * per_set + i] - st[c]) * st[n_cols + c];
+  H[w * per_set + i] = fmaxf(gamma[(size_t)w * n_cols + c] * ahat + beta[(size_t)w * n_cols + c], 0.f);
+}
+
+// Backward sums per column, rows sliced as in bn_stats_kernel: dbeta = sum dy, dgamma = sum dy * ahat.
+__global__ void __launch_bounds__(kBnThreads)
+bn_backward_sums_kernel(const float* __restrict__ A, const float* __restrict__ DY, float* __restrict__ stats,
+                        float* __restrict__ dgamma, float* __restrict__ dbeta, int rows, int n_cols) {
+  __shared__ float s_part[kBnSlices][kBnCols];
+  const int col = threadIdx.x % kBnCols, slice = threadIdx.x / kBnCols;
+  const int c = blockIdx.x * kBnCols + col;
+  const bool live = c < n_cols;
+  const int per = (rows + kBnSlices - 1) / kBnSlices, r0 = slice * per, r1 = min(r0 + per, rows);
+  const size_t base = (size_t)blockIdx.y * rows * n_cols + (live ? c : 0);
+  float* st = stats + (size_t)blockIdx.y * 4 * n_cols;
+  const float mean = live ? st[c] : 0.f, rstd = live ? st[n_cols + c] : 0.f;
+  float sb = 0.f, sg = 0.f;
+  if (live)
+    for (int r = r0; r < r1; ++r) {
+      const float dy = DY[base + (size_t)r * n_cols];
+      sb += dy;
+      sg += dy * ((A[base + (size_t)r * n_cols] - mean) * rstd);
+    }
+  sb = slice_sum(sb, s_part, col, slice);
+  sg = slice_sum(sg, s_part, col, slice);
+  if (!live || slice != 0) return;
+  st[2 * n_cols + c] = sb;
+  st[3 * n_cols + c] = sg;
+  dbeta[(size_t)blockIdx.y * n_cols + c] = sb;
+  dgamma[(size_t)blockIdx.y * n_cols + c] = sg;
+}
+
+// In place: dy -> da = gamma * rstd * (dy - dbeta / rows - ahat * dgamma / rows)
+__global__ void __launch_bounds__(256)
+bn_backward_kernel(const float* __restrict__ A, float* __restrict__ DY, const float* __restrict__ stats,
+                   const float* __restrict__ gamma, int rows, int n_cols) {
+  const size_t per_set = (size_t)rows * n_cols;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= per_set) return;
+  const int c = (int)(i % n_cols), w = blockIdx.y;
+  const float* st = stats + (size_t)w * 4 * n_cols;
+  const float rstd = st[n_cols + c], inv_rows = 1.0f / (float)rows;
+  const float ahat = (A[w * per_set + i] - st[c]) * rstd;
+  const float dy = DY[w * per_set + i];
+  DY[w * per_set + i] = gamma[(size_t)w * n_cols + c] * rstd * (dy - st[2 * n_cols + c] * inv_rows - ahat * st[3 * n_cols + c] * inv_rows);
+}
+
+// W1' = s W1 (row-wise), b1' = (b1 - mean) s + beta with s = gamma / sqrt(var + eps); one thread per row of W1
+template <typename TO>
+__global__ void __launch_bounds__(256)
+bn_fold_kernel(const float* __restrict__ W1, const float* __restrict__ b1, const float* __restrict__ gamma,
+               const float* __restrict__ beta, const float* __restrict__ mean, const float* __restrict__ var, float eps,
+               TO* __restrict__ W1o, float* __restrict__ b1o, size_t rows_total, int d) {
+  const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (j >= rows_total) return;
+  const float s = gamma[j] / sqrtf(var[j] + eps);
+  b1o[j] = (b1[j] - mean[j]) * s + beta[j];
+  for (int k = 0; k < d; ++k) {
+    const float v = W1[j * d + k] * s;
+    if constexpr (sizeof(TO) == 4) {
+      W1o[j * d + k] = v;
+    } else {
+      W1o[j * d + k] = Vec8<bf16_t>::narrow(v);
+    }
+  }
 }
 
 __global__ void __launch_bounds__(256)
@@ -175,19 +311,27 @@ adam_kernel(float* __restrict__ p, const float* __restrict__ g, float* __restric
 }  // namespace
 
 // header | x widened [Hw,R,d] | h [Hw,R,hidden] | z then dL/dz [Hw,R,B] | dL/da [Hw,R,hidden] | row losses [Hw,R]
+//        | batch-norm variant: pre-activations a [Hw,R,hidden] | column statistics [Hw,4,hidden]
 size_t train_workspace_bytes(long long Hw, long long R, int d, int hidden, int B) {
-  return (size_t)SAAP_WS_HEADER_BYTES + (size_t)Hw * R * ((size_t)d + 2 * (size_t)hidden + B + 1) * sizeof(float);
+  return (size_t)SAAP_WS_HEADER_BYTES + (size_t)Hw * R * ((size_t)d + 3 * (size_t)hidden + B + 1) * sizeof(float) +
+         (size_t)Hw * 4 * hidden * sizeof(float);
 }
 
 }  // namespace saap
 
 using namespace saap;
 
-extern "C" int32_t saap_query_model_loss_grads(const void* x, const float* target, const saap_mlp_f32* params,
-                                               const saap_mlp_f32* grads, float* loss, int32_t Hw, int32_t R,
-                                               int32_t d, int32_t hidden, int32_t B, int32_t x_dtype, void* ws,
-                                               size_t ws_bytes, void* stream) {
+// bn == nullptr: the plain model.
+static int32_t loss_grads(const void* x, const float* target, const saap_mlp_f32* params, const saap_mlp_f32* grads,
+                          const saap_batch_norm_f32* bn, float* loss, int32_t Hw, int32_t R, int32_t d, int32_t hidden,
+                          int32_t B, int32_t x_dtype, void* ws, size_t ws_bytes, void* stream) {
   if (!x || !target || !params || !grads || !loss || !ws) return SAAP_INVALID_ARG;
+  if (bn) {
+    if (!bn->gamma || !bn->beta || !bn->grad_gamma || !bn->grad_beta) return SAAP_INVALID_ARG;
+    if ((bn->running_mean == nullptr) != (bn->running_var == nullptr)) return SAAP_INVALID_ARG;
+    if (!(bn->eps > 0.f) || !(bn->momentum >= 0.f && bn->momentum <= 1.f)) return SAAP_INVALID_ARG;
+    if (R < 2) return SAAP_INVALID_ARG;   // no variance estimate from one row
+  }
   if (!params->W1 || !params->b1 || !params->W2 || !params->b2 || !grads->W1 || !grads->b1 || !grads->W2 || !grads->b2)
     return SAAP_INVALID_ARG;
   if (!aligned16(x) || !aligned16(ws)) return SAAP_INVALID_ARG;
@@ -210,8 +354,20 @@ extern "C" int32_t saap_query_model_loss_grads(const void* x, const float* targe
   }
   const long long sx = (long long)R * d, sh = (long long)R * hidden, sz = (long long)R * B;
   const long long sW1 = (long long)hidden * d, sW2 = (long long)B * hidden;
-  // h = relu(x W1^T + b1)
-  gemm<false, true, EPI_BIAS_RELU>({xin, params->W1, h, params->b1, nullptr, R, hidden, d, sx, sW1, sh, hidden, 0}, Hw, hs);
+  float* pre = loss_rows + (size_t)Hw * R;          // batch-norm variant only
+  float* stats = pre + (size_t)Hw * R * hidden;
+  const dim3 per_col((unsigned)((hidden + kBnCols - 1) / kBnCols), (unsigned)Hw);
+  const dim3 per_elem((unsigned)(((size_t)R * hidden + 255) / 256), (unsigned)Hw);
+  if (!bn) {
+    // h = relu(x W1^T + b1)
+    gemm<false, true, EPI_BIAS_RELU>({xin, params->W1, h, params->b1, nullptr, R, hidden, d, sx, sW1, sh, hidden, 0}, Hw, hs);
+  } else {
+    // a = x W1^T + b1;  h = relu(gamma * normalised(a) + beta)
+    gemm<false, true, EPI_BIAS>({xin, params->W1, pre, params->b1, nullptr, R, hidden, d, sx, sW1, sh, hidden, 0}, Hw, hs);
+    hipLaunchKernelGGL(bn_stats_kernel, per_col, dim3(kBnThreads), 0, hs, pre, stats, bn->running_mean, bn->running_var, R, hidden,
+                       bn->eps, bn->momentum);
+    hipLaunchKernelGGL(bn_relu_kernel, per_elem, dim3(256), 0, hs, pre, stats, bn->gamma, bn->beta, h, R, hidden);
+  }
   // z = h W2^T + b2
   gemm<false, true, EPI_BIAS>({h, params->W2, z, params->b2, nullptr, R, B, hidden, sh, sW2, sz, B, 0}, Hw, hs);
   // row losses; z becomes dL/dz
@@ -219,14 +375,54 @@ extern "C" int32_t saap_query_model_loss_grads(const void* x, const float* targe
   hipLaunchKernelGGL(loss_mean_kernel, dim3((unsigned)Hw), dim3(256), 0, hs, loss_rows, loss, R);
   // dW2 = dz^T h, db2 = column sums of dz
   gemm<true, false, EPI_NONE>({z, h, grads->W2, nullptr, nullptr, B, hidden, R, sz, sh, sW2, 0, 0}, Hw, hs);
-  hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((B + 255) / 256), (unsigned)Hw), dim3(256), 0, hs, z, grads->b2, R, B,
+  hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((B + kBnCols - 1) / kBnCols), (unsigned)Hw), dim3(kBnThreads), 0, hs, z,
+                     grads->b2, R, B,
                      sz, (long long)B);
   // da = (dz W2) where h > 0
   gemm<false, false, EPI_MASK>({z, params->W2, da, nullptr, h, R, hidden, B, sz, sW2, sh, 0, sh}, Hw, hs);
+  if (bn) {
+    // through the normalisation: da holds dL/dy on entry and dL/da on exit
+    hipLaunchKernelGGL(bn_backward_sums_kernel, per_col, dim3(kBnThreads), 0, hs, pre, da, stats, bn->grad_gamma, bn->grad_beta, R,
+                       hidden);
+    hipLaunchKernelGGL(bn_backward_kernel, per_elem, dim3(256), 0, hs, pre, da, stats, bn->gamma, R, hidden);
+  }
   // dW1 = da^T x, db1 = column sums of da
   gemm<true, false, EPI_NONE>({da, xin, grads->W1, nullptr, nullptr, hidden, d, R, sh, sx, sW1, 0, 0}, Hw, hs);
-  hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((hidden + 255) / 256), (unsigned)Hw), dim3(256), 0, hs, da, grads->b1,
-                     R, hidden, sh, (long long)hidden);
+  hipLaunchKernelGGL(colsum_kernel, per_col, dim3(kBnThreads), 0, hs, da, grads->b1, R, hidden, sh, (long long)hidden);
+  return launch_status();
+}
+
+extern "C" int32_t saap_query_model_loss_grads(const void* x, const float* target, const saap_mlp_f32* params,
+                                               const saap_mlp_f32* grads, float* loss, int32_t Hw, int32_t R,
+                                               int32_t d, int32_t hidden, int32_t B, int32_t x_dtype, void* ws,
+                                               size_t ws_bytes, void* stream) {
+  return loss_grads(x, target, params, grads, nullptr, loss, Hw, R, d, hidden, B, x_dtype, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t saap_query_model_bn_loss_grads(const void* x, const float* target, const saap_mlp_f32* params,
+                                                  const saap_mlp_f32* grads, const saap_batch_norm_f32* bn, float* loss,
+                                                  int32_t Hw, int32_t R, int32_t d, int32_t hidden, int32_t B,
+                                                  int32_t x_dtype, void* ws, size_t ws_bytes, void* stream) {
+  if (!bn) return SAAP_INVALID_ARG;
+  return loss_grads(x, target, params, grads, bn, loss, Hw, R, d, hidden, B, x_dtype, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t saap_fold_batch_norm(const float* W1, const float* b1, const float* gamma, const float* beta,
+                                        const float* running_mean, const float* running_var, float eps, void* W1_out,
+                                        float* b1_out, int32_t Hw, int32_t hidden, int32_t d, int32_t out_dtype,
+                                        void* stream) {
+  if (!W1 || !b1 || !gamma || !beta || !running_mean || !running_var || !W1_out || !b1_out) return SAAP_INVALID_ARG;
+  if (Hw <= 0 || hidden <= 0 || d <= 0 || !(eps > 0.f)) return SAAP_INVALID_ARG;
+  if (out_dtype != SAAP_F32 && out_dtype != SAAP_BF16) return SAAP_INVALID_ARG;
+  const size_t rows = (size_t)Hw * hidden;
+  const dim3 grid((unsigned)((rows + 255) / 256));
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (out_dtype == SAAP_F32)
+    hipLaunchKernelGGL(bn_fold_kernel<float>, grid, dim3(256), 0, hs, W1, b1, gamma, beta, running_mean, running_var, eps,
+                       static_cast<float*>(W1_out), b1_out, rows, d);
+  else
+    hipLaunchKernelGGL(bn_fold_kernel<bf16_t>, grid, dim3(256), 0, hs, W1, b1, gamma, beta, running_mean, running_var, eps,
+                       static_cast<bf16_t*>(W1_out), b1_out, rows, d);
   return launch_status();
 }
 

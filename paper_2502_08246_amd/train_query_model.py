@@ -34,15 +34,19 @@ def parse():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--batch", type=int, default=1024, help="rows per weight set and step")
     ap.add_argument("--lr", type=float, default=1e-3, help="Adam learning rate (the paper: 1e-5 for 40k iterations)")
+    ap.add_argument("--batch-norm", action="store_true",
+                    help="train the model with batch normalisation of the hidden layer (Section 6.1) and fold it for inference")
     ap.add_argument("--seed", type=int, default=0)
     return ap.parse_args()
 
 
 def train(cfg, train_queries=2048, eval_queries=64, steps=400, batch=1024, lr=1e-3, seed=0, centroids=None,
-          return_weights=False):
+          return_weights=False, batch_norm=False):
     """Runs the whole procedure on workload `cfg` (one sequence) and returns the report as a dict.
     centroids [Hkv,B,d]: the partition to train for (default: the workload's own centroids);
-    return_weights: the report also holds "weights" = (W1, b1, W2, b2) as classify_queries takes them."""
+    return_weights: the report also holds "weights" = (W1, b1, W2, b2) as classify_queries takes them;
+    batch_norm: the hidden layer is normalised over the batch during training (scale 1 and shift 0 at the
+    start, eps 1e-5, momentum 0.1) and the running statistics are folded into W1, b1 for the evaluation."""
     import types
 
     import torch
@@ -101,6 +105,12 @@ def train(cfg, train_queries=2048, eval_queries=64, steps=400, batch=1024, lr=1e
     V = tuple(torch.zeros_like(p) for p in P)
     grads = tuple(torch.empty_like(p) for p in P)
     loss = torch.empty(Hw, dtype=torch.float32, device=dev)
+    if batch_norm:
+        bn_gamma, bn_beta = torch.ones_like(P[1]), torch.zeros_like(P[1])
+        run_mean, run_var = torch.zeros_like(P[1]), torch.ones_like(P[1])
+        bn_grads = (torch.empty_like(bn_gamma), torch.empty_like(bn_beta))
+        bn_M = tuple(torch.zeros_like(t) for t in bn_grads)
+        bn_V = tuple(torch.zeros_like(t) for t in bn_grads)
 
     def evaluate(weights):
         """Mean captured attention mass on the held-out queries for lists made from `weights`
@@ -123,6 +133,9 @@ def train(cfg, train_queries=2048, eval_queries=64, steps=400, batch=1024, lr=1e
         return got / n, best / n
 
     def as_inference_weights(params):
+        if batch_norm:
+            W1f, b1f = saap.fold_batch_norm(params[0], params[1], bn_gamma, bn_beta, run_mean, run_var, out_dtype=xq.dtype)
+            return (W1f, b1f, params[2].to(xq.dtype).contiguous(), params[3].contiguous())
         return tuple(p.to(xq.dtype).contiguous() if i in (0, 2) else p.contiguous() for i, p in enumerate(params))
 
     cap_init, cap_best = evaluate((W1b, b1b, W2b, b2b))
@@ -134,7 +147,13 @@ def train(cfg, train_queries=2048, eval_queries=64, steps=400, batch=1024, lr=1e
     for step in range(1, args.steps + 1):
         pick = torch.randint(0, rows, (R,), generator=g, device=dev)
         xb, tb = x_tr[:, pick].contiguous(), t_tr[:, pick].contiguous()
-        saap.query_model_loss_grads(xb, tb, P, grads=grads, loss=loss)
+        if batch_norm:
+            saap.query_model_bn_loss_grads(xb, tb, P, bn_gamma, bn_beta, run_mean, run_var, grads=grads,
+                                           grad_gamma=bn_grads[0], grad_beta=bn_grads[1], loss=loss)
+            for p, gr, m, v in zip((bn_gamma, bn_beta), bn_grads, bn_M, bn_V):
+                saap.adam_update(p, gr, m, v, step, args.lr)
+        else:
+            saap.query_model_loss_grads(xb, tb, P, grads=grads, loss=loss)
         for p, gr, m, v in zip(P, grads, M, V):
             saap.adam_update(p, gr, m, v, step, args.lr)
         if step == 1 or step % max(args.steps // 8, 1) == 0 or step == args.steps:
@@ -145,6 +164,7 @@ def train(cfg, train_queries=2048, eval_queries=64, steps=400, batch=1024, lr=1e
 
     report = {
         "workload": cfg.name, "B": B, "nprobe": cfg.nprobe, "classifier": f"{d}->{cfg.hidden}->{B}", "weight_sets": Hw,
+        "batch_norm": bool(batch_norm),
         "train_queries_per_head": n_tr, "eval_queries_per_head": T_all - n_tr, "steps": args.steps, "batch_rows": R,
         "lr": args.lr, "loss": losses, "ms_per_step": round(train_s / max(args.steps, 1) * 1e3, 3),
         "targets_s": round(target_s, 2),
@@ -163,7 +183,7 @@ def main():
 
     try:
         report = train(gen.CONFIGS[args.workload], args.train_queries, args.eval_queries, args.steps, args.batch, args.lr,
-                       args.seed)
+                       args.seed, batch_norm=args.batch_norm)
     except RuntimeError as e:
         print(e, file=sys.stderr)
         sys.exit(2)

@@ -221,7 +221,27 @@ def test_invalid_arguments_of_the_later_calls_are_rejected_on_the_host(lib):
     assert grads(x=None) == -1 and grads(p=holes) == -1 and grads(g=holes) == -1 and grads(R=0) == -1 and grads(dt=2) == -1
     assert grads(Hw=70000) == -2 and grads(wsb=small) == -3
     need = saap.workspace_bytes(binding.OP_QUERY_MODEL_LOSS_GRADS, Hkv=2, N=16, d=128, hidden=64, B=32)
-    assert need == binding.WS_HEADER_BYTES + 2 * 16 * (128 + 2 * 64 + 32 + 1) * 4
+    assert need == binding.WS_HEADER_BYTES + 2 * 16 * (128 + 3 * 64 + 32 + 1) * 4 + 2 * 4 * 64 * 4
+
+    def bn_struct(**kw):
+        a = dict(gamma=4096, beta=8192, gg=12288, gb=16384, rm=None, rv=None, mom=0.1, eps=1e-5)
+        a.update(kw)
+        return binding._BatchNormF32(a["gamma"], a["beta"], a["gg"], a["gb"], a["rm"], a["rv"], a["mom"], a["eps"])
+
+    def grads_bn(bn, **kw):
+        a = dict(R=16, wsb=big)
+        a.update(kw)
+        return lib.saap_query_model_bn_loss_grads(q, K, ctypes.byref(params), ctypes.byref(params),
+                                                  ctypes.byref(bn) if bn is not None else None, lse, i32(2), i32(a["R"]),
+                                                  i32(128), i32(64), i32(32), i32(1), ws, a["wsb"], None)
+
+    assert grads_bn(None) == -1 and grads_bn(bn_struct(gamma=None)) == -1 and grads_bn(bn_struct(gb=None)) == -1
+    assert grads_bn(bn_struct(rm=4096)) == -1                # running mean without running variance
+    assert grads_bn(bn_struct(eps=0.0)) == -1 and grads_bn(bn_struct(mom=1.5)) == -1
+    assert grads_bn(bn_struct(), R=1) == -1 and grads_bn(bn_struct(), wsb=small) == -3
+    fold = lambda **kw: lib.saap_fold_batch_norm(kw.get("W1", q), K, K, K, K, K, f32(kw.get("eps", 1e-5)), out, lse, i32(2),
+                                                 i32(kw.get("hidden", 64)), i32(128), i32(kw.get("dt", 1)), None)
+    assert fold(W1=None) == -1 and fold(eps=0.0) == -1 and fold(hidden=0) == -1 and fold(dt=2) == -1
     assert saap.workspace_bytes(binding.OP_BUCKET_ATTENTION_MASS, S=1, Hq=32, Hkv=8, B=1024) == binding.WS_HEADER_BYTES + 8 * 1024 * 4 * 8
 
     def adam(**kw):
