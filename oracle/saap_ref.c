@@ -20,8 +20,10 @@
  * closed forms (equal keys -> mean of values, one key -> its value), nprobe = B
  * equals dense attention, library softmax/matmul/argsort, CSR invariants, the
  * balanced-selectivity column of the paper's Table "nprobe_selectivity".
- * The paper prints no numeric attention output, score or index, so beyond
- * those pins the values are unpinned by the paper itself.
+ * Every function has at least one such pin.  The paper prints no numeric
+ * attention output, score or index, so there is no worked example of those to
+ * store: the pins come from the mathematics, the number format and the one
+ * table of the paper that is a closed form.
  *
  * Build: gcc -O2 -fopenmp -ffp-contract=off -shared -fPIC saap_ref.c -lm
  */
