@@ -233,3 +233,44 @@ def test_recompact_index(saap, dtype, resident):
     _, _, _, _, flag = saap.recompact_index(off2, ln, idx2, K2, V2, 24, 64, resident=resident)
     torch.cuda.synchronize()
     assert flag[0].item() == 1
+
+
+def test_recompact_while_the_window_is_still_filling(saap):
+    """A context shorter than the window: re-compaction keeps all W slots of the resident run, pushes go on
+    in the new layout while the window fills and then slides; state bit for bit against the oracle."""
+    S, Hq, Hkv, N, B, slack, n_sink, n_recent = 1, 4, 2, 20, 8, 3, 2, 30
+    W = n_sink + n_recent
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(S=S, Hq=Hq, Hkv=Hkv, N=N + 60, B=B, nprobe=2, hidden=64)
+    cache = gen.make_cache(cfg, 89, DEV)
+    cent = gen.make_centroids(cfg, 89, DEV, cache, n_train=2048)
+    x, K, V = cache["x_keys"], cache["K"], cache["V"]
+    hK, hV, hx, hc = h(K), h(V), h(x), h(cent)
+    ids_all = saap.assign_keys(x, cent)
+    h_ids = ids_all.cpu().numpy()
+    state = list(saap.build_windowed_index(ids_all[:, :, :N].contiguous(), K[:, :, :N].contiguous(), V[:, :, :N].contiguous(),
+                                           B, slack, n_sink, n_recent))
+    want = list(ref.build_windowed_index(h_ids[:, :, :N], hK[:, :, :N], hV[:, :, :N], B, slack, n_sink, n_recent))
+
+    def push(t):
+        pos = torch.full((S,), t, dtype=torch.int32, device=DEV)
+        xn, kn, vn = (a[:, :, t].contiguous() for a in (x, K, V))
+        _, flag = saap.window_push(xn, kn, vn, pos, cent, None, *state, n_sink, n_recent)
+        _, rflag = ref.window_push(hx[:, :, t], hK[:, :, t], hV[:, :, t], pos.cpu().numpy(), hc, None, *want, n_sink, n_recent)
+        torch.cuda.synchronize()
+        assert (flag[0].item(), rflag) == (0, 0), f"push {t}"
+
+    for t in range(N, N + 5):
+        push(t)
+    compare_state(state, want, W, "before recompact")
+    Ncap_new = B * 40 + W                                   # room for every key that the window will displace
+    off2, idx2, K2, V2, flag = saap.recompact_index(state[0], state[1], state[2], state[3], state[4], 40, Ncap_new, resident=True)
+    r_off2, r_idx2, rK2, rV2, rflag = ref.recompact_index(want[0], want[1], want[2], want[3], want[4], 40, Ncap_new, resident=True)
+    torch.cuda.synchronize()
+    assert flag[0].item() == 0 and rflag == 0
+    state = [off2, state[1], idx2, K2, V2, state[5]]
+    want = [r_off2, want[1], r_idx2, rK2, rV2, want[5]]
+    assert int(r_off2[0, 0, B + 1] - r_off2[0, 0, B]) == W
+    compare_state(state, want, W, "after recompact")
+    for t in range(N + 5, N + 45):
+        push(t)
+    compare_state(state, want, W, "after the window filled and slid")

@@ -200,3 +200,30 @@ def test_recompact_keeps_every_member_and_restores_the_slack():
     assert flag == 0
     _, _, _, _, flag = ref.recompact_index(off2, ln, idx2, K2, V2, 20, Ncap_new - 1 - B * 20, resident=True)
     assert flag == 1
+
+
+def test_recompact_while_the_window_is_still_filling():
+    """A context shorter than the window: the resident run keeps all its W slots through a re-compaction
+    (not just the occupied ones), so later pushes still find their ring slots."""
+    N, n_sink, n_recent, slack = 20, 2, 30, 3
+    x, K, V, cent, q, ids = make(8, N=N, extra=60)
+    S, Hkv, Nt, d = K.shape
+    B = cent.shape[1]
+    W = n_sink + n_recent
+    off, ln, idx, Ks, Vs, res = ref.build_windowed_index(ids[:, :, :N], K[:, :, :N], V[:, :, :N], B, slack, n_sink, n_recent)
+
+    def push(t, off):
+        pos = np.full((S,), t, dtype=np.int32)
+        _, flag = ref.window_push(x[:, :, t], K[:, :, t], V[:, :, t], pos, cent, None, off, ln, idx, Ks, Vs, res, n_sink, n_recent)
+        assert flag == 0
+
+    for t in range(N, N + 5):
+        push(t, off)
+    n_now = N + 5
+    assert n_now < W and (ln[:, :, B] == n_now).all()
+    off, idx, Ks, Vs, flag = ref.recompact_index(off, ln, idx, Ks, Vs, 9, B * 9 + W, resident=True)
+    assert flag == 0
+    check_state(off, ln, idx, Ks, Vs, res, K, V, ids, n_now, B, 9, n_sink, n_recent)
+    for t in range(n_now, n_now + 40):                      # the window fills (at 32 keys), then slides
+        push(t, off)
+    check_state(off, ln, idx, Ks, Vs, res, K, V, ids, n_now + 40, B, 9, n_sink, n_recent)
