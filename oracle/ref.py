@@ -16,8 +16,10 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "saap_ref.c")
-_LIB = os.path.join(_HERE, "libsaap_ref.so")
+# SAAP_ORACLE_SRC names another copy of the source (the mutation test plants mistakes in such a copy
+# and expects the pins to fail); the library is then built next to that copy.
+_SRC = os.environ.get("SAAP_ORACLE_SRC") or os.path.join(_HERE, "saap_ref.c")
+_LIB = os.path.join(os.path.dirname(os.path.abspath(_SRC)), "libsaap_ref.so")
 _lib = None
 
 
