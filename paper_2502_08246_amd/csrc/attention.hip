@@ -416,8 +416,8 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
       const int r = __shfl(row, (lane & 48) + i);
       if constexpr (MASKED) bt.heads |= (unsigned)__shfl(hmask, (lane & 48) + i) << (8 * i);
       if (base + i * NG + kp < T_total) bt.valid |= 1u << i;
-      bt.k[i].load(Kb + (size_t)r * kD);
-      bt.v[i].load(Vb + (size_t)r * kD);
+      bt.k[i].load_stream(Kb + (size_t)r * kD);
+      bt.v[i].load_stream(Vb + (size_t)r * kD);
     }
   };
 

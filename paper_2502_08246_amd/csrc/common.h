@@ -121,6 +121,20 @@ __device__ __forceinline__ float across_rows(float x, F op) {
 __device__ __forceinline__ float sum_rows(float x) { return across_rows(x, [](float a, float b) { return a + b; }); }
 __device__ __forceinline__ float max_rows(float x) { return across_rows(x, [](float a, float b) { return fmaxf(a, b); }); }
 
+// 16 or 8 bytes read once and not again soon (the K/V rows of a decode step): the load carries the
+// non-temporal hint, so that the stream does not push the data that IS reused between launches (the
+// classifier's weights) out of the caches.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 stream_load16(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ uint2 stream_load8(const void* p) {
+  const u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+  return make_uint2(v[0], v[1]);
+}
+
 // Eight consecutive elements of a row, as loaded by one lane.
 template <typename T> struct Vec8;
 template <> struct Vec8<float> {
@@ -128,6 +142,11 @@ template <> struct Vec8<float> {
   __device__ __forceinline__ void load(const float* p) {
     a = *reinterpret_cast<const float4*>(p);
     b = *reinterpret_cast<const float4*>(p + 4);
+  }
+  __device__ __forceinline__ void load_stream(const float* p) {
+    const uint4 u = stream_load16(p), w = stream_load16(p + 4);
+    a = make_float4(__uint_as_float(u.x), __uint_as_float(u.y), __uint_as_float(u.z), __uint_as_float(u.w));
+    b = make_float4(__uint_as_float(w.x), __uint_as_float(w.y), __uint_as_float(w.z), __uint_as_float(w.w));
   }
   __device__ __forceinline__ void to_float(float* o) const {
     o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
@@ -144,6 +163,7 @@ template <> struct Vec8<float> {
 template <> struct Vec8<bf16_t> {
   uint4 r;
   __device__ __forceinline__ void load(const bf16_t* p) { r = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void load_stream(const bf16_t* p) { r = stream_load16(p); }
   __device__ __forceinline__ void to_float(float* o) const {
     o[0] = bf16_lo(r.x); o[1] = bf16_hi(r.x); o[2] = bf16_lo(r.y); o[3] = bf16_hi(r.y);
     o[4] = bf16_lo(r.z); o[5] = bf16_hi(r.z); o[6] = bf16_lo(r.w); o[7] = bf16_hi(r.w);
@@ -166,6 +186,7 @@ typedef uint8_t fp8_t;
 template <> struct Vec8<fp8_t> {
   uint2 r;
   __device__ __forceinline__ void load(const fp8_t* p) { r = *reinterpret_cast<const uint2*>(p); }
+  __device__ __forceinline__ void load_stream(const fp8_t* p) { r = stream_load8(p); }
   __device__ __forceinline__ void to_float(float* o) const {
     typedef float f32x2_t __attribute__((ext_vector_type(2)));
     const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.x, true);
