@@ -103,8 +103,9 @@ const char* saap_status_string(int32_t status);
 /* Number of compute units of the current device (host query; <= 0 on error). */
 int32_t saap_device_compute_units(void);
 
-/* Measurement aid, not part of the method: reads `bytes` of device memory once with plain
- * 16-byte loads and folds them into `sink` (device, >= 4 * 4 * compute units bytes).  Its
+/* Measurement aid, not part of the method: reads `bytes` of device memory once with 16-byte
+ * loads that carry the non-temporal hint (as the attention kernels read K and V) and folds
+ * them into `sink` (device, >= 4 * 4 * compute units bytes).  Its
  * bandwidth is the streaming-read ceiling that the attention kernels are reported against
  * beside the published HBM peak. */
 int32_t saap_stream_read_probe(const void* src, size_t bytes, void* sink, size_t sink_bytes, void* stream);

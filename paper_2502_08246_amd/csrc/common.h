@@ -130,6 +130,11 @@ __device__ __forceinline__ uint4 stream_load16(const void* p) {
   const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
   return make_uint4(v[0], v[1], v[2], v[3]);
 }
+__device__ __forceinline__ void stream_store16(void* p, const uint4& v) {
+  u32x4_t w;
+  w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+  __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t*>(p));
+}
 __device__ __forceinline__ uint2 stream_load8(const void* p) {
   const u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
   return make_uint2(v[0], v[1]);

@@ -193,15 +193,15 @@ permute_kernel(const uint4* __restrict__ K, const uint4* __restrict__ V, const i
     if (src[r] >= 0) {
       const long long unit = slot[r] / Ncap;
       const size_t in = ((size_t)unit * N + src[r]) * CHUNKS + piece;
-      kv[r] = K[in];
-      vv[r] = V[in];
+      kv[r] = stream_load16(K + in);
+      vv[r] = stream_load16(V + in);
     }
   }
 #pragma unroll
   for (int r = 0; r < kRowsPerThread; ++r) {
     if (src[r] >= 0) {
-      Ks[(size_t)slot[r] * CHUNKS + piece] = kv[r];
-      Vs[(size_t)slot[r] * CHUNKS + piece] = vv[r];
+      stream_store16(Ks + (size_t)slot[r] * CHUNKS + piece, kv[r]);
+      stream_store16(Vs + (size_t)slot[r] * CHUNKS + piece, vv[r]);
     }
   }
 }

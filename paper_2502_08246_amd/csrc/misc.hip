@@ -32,14 +32,15 @@ __global__ void zero_words_kernel(uint32_t* p, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0u;
 }
-// Reads `n` 16-byte words once (grid-stride, four loads in flight per lane) and folds them into
+// Reads `n` 16-byte words once (grid-stride, four non-temporal loads in flight per lane) and folds them into
 // one word per workgroup: the streaming-read ceiling of the device for the benchmark report.
 __global__ void __launch_bounds__(512) stream_read_kernel(const uint4* __restrict__ src, size_t n, uint32_t* __restrict__ sink) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   uint32_t acc = 0u;
   for (; i + 3 * stride < n; i += 4 * stride) {
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    const uint4 a = stream_load16(src + i), b = stream_load16(src + i + stride), c = stream_load16(src + i + 2 * stride),
+                d = stream_load16(src + i + 3 * stride);
     acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
   }
   for (; i < n; i += stride) {
