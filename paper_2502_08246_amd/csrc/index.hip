@@ -485,8 +485,8 @@ recopy_kernel(const int32_t* __restrict__ off, const int32_t* __restrict__ len, 
   for (int r = tid / CHUNKS; r < n; r += kRowsPerPass) {
     const size_t src = ((size_t)unit * Ncap + first + r) * CHUNKS + piece;
     const size_t out = ((size_t)unit * Ncap_new + dst + r) * CHUNKS + piece;
-    Kn[out] = Ks[src];
-    Vn[out] = Vs[src];
+    stream_store16(Kn + out, stream_load16(Ks + src));
+    stream_store16(Vn + out, stream_load16(Vs + src));
   }
 }
 
