@@ -66,6 +66,10 @@ CONFIGS = {
     # with its 4 query heads, 171k keys, 32 of 1024 buckets visited), for context beside its figures.
     "paper_timing_1head_171k": Workload("paper_timing_1head_171k", S=1, Hq=4, Hkv=1, N=171000, B=1024,
                                         hidden=512, nprobe=32, dtype="bf16"),
+    # Not in the benchmark spec: the batched-decode workload with 32 sequences, i.e. a launch large enough
+    # (0.85 GB of visited K/V) to show the attention kernel's streaming rate without its fixed cost.
+    "batch32_128k": Workload("batch32_128k", S=32, Hq=32, Hkv=8, N=131072, B=1024, hidden=512,
+                             nprobe=51, dtype="bf16"),
 }
 
 
