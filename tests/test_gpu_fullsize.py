@@ -304,3 +304,43 @@ def test_cfg1_full_size_8bit_cache(saap):
         rd, rdl = ref.dense_decode_attention(h(q[t]), Kd, Vd, SCALE)
         close(o_d.cpu().numpy(), rd)
         close(l_d.cpu().numpy(), rdl)
+
+
+def test_batch32_128k_sampled(saap):
+    """The 32-sequence workload that bench.py reports the large-launch figures on (0.86 GB of visited
+    K/V per launch): CSR invariants on everything, and the oracle on three of the 32 sequences (assignment of
+    a row sample, index, selection, sparse attention; dense attention for one of them)."""
+    cfg = gen.CONFIGS["batch32_128k"]
+    cache = gen.make_cache(cfg, 0, DEV)
+    cent = gen.make_centroids(cfg, 0, DEV)
+    xq, q = gen.make_queries(cfg, 0, DEV, n_steps=2)
+    W1, b1, W2, b2 = gen.make_classifier(cfg, 0, DEV)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, 0)
+    torch.cuda.synchronize()
+    csr_invariants(ids, off, ln, idx, cfg.B, 0)
+    seqs = [0, 17, 31]
+    st = torch.tensor(seqs, device=DEV)
+    rows = np.sort(np.random.default_rng(5).choice(cfg.N, size=1024, replace=False))
+    want = ref.assign_keys(h(cache["x_keys"][st][:, :, torch.from_numpy(rows).to(DEV)]), h(cent))
+    assert np.array_equal(ids[st].cpu().numpy()[:, :, rows], want)
+    hK, hV = h(cache["K"][st]), h(cache["V"][st])
+    r_off, r_ln, r_idx, _, _ = ref.build_bucket_index(ids[st].cpu().numpy(), hK, hV, cfg.B, 0)
+    assert np.array_equal(off[st].cpu().numpy(), r_off) and np.array_equal(ln[st].cpu().numpy(), r_ln)
+    assert np.array_equal(idx[st].cpu().numpy(), r_idx)
+    for t in range(2):
+        logits = saap.classify_queries(xq[t], W1, b1, W2, b2, cfg.Hkv, output_kind=saap.LOGITS)
+        probs = torch.empty_like(logits)
+        sel = saap.select_buckets_from_logits(logits, cfg.Hkv, cfg.nprobe, probs=probs)
+        out, lse = saap.sparse_decode_attention(q[t], Ks, Vs, off, ln, sel, SCALE)
+        torch.cuda.synchronize()
+        r_sel = ref.select_buckets(probs[st].cpu().numpy(), cfg.Hkv, cfg.nprobe)
+        assert np.array_equal(np.sort(sel[st].cpu().numpy(), -1), np.sort(r_sel, -1))
+        ro, rl = ref.sparse_decode_attention(h(q[t][st]), hK, hV, r_off, r_ln, r_idx, r_sel, SCALE)
+        close(out[st].cpu().numpy(), ro)
+        close(lse[st].cpu().numpy(), rl)
+    out_d, lse_d = saap.dense_decode_attention(q[0], cache["K"], cache["V"], SCALE)
+    torch.cuda.synchronize()
+    do, dl = ref.dense_decode_attention(h(q[0][st[:1]]), hK[:1], hV[:1], SCALE)
+    close(out_d[:1].cpu().numpy(), do)
+    close(lse_d[:1].cpu().numpy(), dl)
