@@ -259,7 +259,7 @@ def main():
     ms_append = GraphLoop(append, T, torch).timed_ms_per_call(2) if with_append else None
     ms_dense = None if args.no_dense else GraphLoop(dense, 8, torch).timed_ms_per_call(3)
     achieved = bytes_step / (ms_attn * 1e-3) / 1e9
-    # streaming-read ceiling of this device: plain 16-byte loads over the whole sorted cache
+    # streaming-read ceiling of this device: non-temporal 16-byte loads over the whole sorted cache
     sink = torch.zeros(4096, dtype=torch.int32, device=dev)
     kv_bytes = Ks.numel() * Ks.element_size() + Vs.numel() * Vs.element_size()
 

@@ -147,7 +147,7 @@ def workspace_reset(ws: torch.Tensor) -> None:
 
 
 def stream_read_probe(src: torch.Tensor, sink: torch.Tensor) -> None:
-    """Measurement aid: one pass of plain 16-byte loads over `src` (see saap_stream_read_probe)."""
+    """Measurement aid: one pass of non-temporal 16-byte loads over `src` (see saap_stream_read_probe)."""
     st = load_library().saap_stream_read_probe(_ptr(src), ctypes.c_size_t(src.numel() * src.element_size()), _ptr(sink),
                                                ctypes.c_size_t(sink.numel() * sink.element_size()), _stream())
     _check("saap_stream_read_probe", st)
