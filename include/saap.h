@@ -78,7 +78,8 @@ enum {
   SAAP_OP_WINDOW_PUSH = 7,
   SAAP_OP_BUCKET_ATTENTION_MASS = 8,
   SAAP_OP_QUERY_MODEL_LOSS_GRADS = 9,  /* shape: Hkv = weight sets, N = rows per set, d, hidden, B */
-  SAAP_OP_BUCKET_ATTENTION_MASS_BATCH = 10   /* shape: S, Hkv, N = queries per KV head, B */
+  SAAP_OP_BUCKET_ATTENTION_MASS_BATCH = 10,  /* shape: S, Hkv, N = queries per KV head, B */
+  SAAP_OP_PLANNED_DECODE_ATTENTION = 11      /* shape: S, Hq, Hkv, mode */
 };
 
 #define SAAP_WS_HEADER_BYTES 65536u
@@ -557,6 +558,74 @@ int32_t saap_dense_decode_attention_fp8(const void* q, const uint8_t* K8, const 
                                         float scale, void* out, int32_t out_dtype, float* lse,
                                         int32_t S, int32_t Hq, int32_t Hkv, int32_t N, int32_t d,
                                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * ---- visit plans: routing hands the attention its work list ready-made ----
+ * Section 5 ("On GPU") observes that with one block per visited bucket the largest bucket sets the
+ * run time, and Appendix F (Algorithm 2) merges one partial result per block.  Here the selection
+ * step writes, per list, a VISIT PLAN: the runs of the sorted cache to attend, as first rows and an
+ * exclusive prefix of their lengths, and their total.  saap_planned_decode_attention concatenates
+ * the key ranges of ALL lists and deals that global range to the workgroups in equal shares, so
+ * that neither a large bucket nor a large list makes one workgroup finish late; a list is merged
+ * (Algorithm 2) from as many partial results as workgroups held a piece of it.
+ *
+ * Plan layout, int32, per list (units = S*Hkv lists for SAAP_GROUP_SUM, S*Hq for SAAP_INDEPENDENT),
+ * stride = 2*nruns + 2 rounded up to a multiple of 4:
+ *   [0] total keys | [1 .. nruns+1] pre[0..nruns] (pre[0] = 0, pre[j+1] = pre[j] + len of run j) |
+ *   [nruns+2 .. 2*nruns+1] first row of run j in the (sequence, KV head)'s sorted cache
+ * nruns = nprobe (+ 1 if a resident run is always visited; it comes last).
+ *
+ * saap_visit_plan_bytes: size of the plan buffer (host arithmetic; 0 for invalid arguments).
+ */
+size_t saap_visit_plan_bytes(int32_t S, int32_t Hq, int32_t Hkv, int32_t nruns, int32_t mode);
+
+/*
+ * build_visit_plan -- the plan of given lists (any caller-made `selected`, as
+ * saap_sparse_decode_attention takes it), one small launch.
+ *   selected [S,Hkv,nprobe] or [S,Hq,nprobe] int32 (ids outside [0,runs) are clamped);
+ *   off [S,Hkv,runs+1], len [S,Hkv,runs]; resident_run: a run visited by every list, or -1
+ *   plan: out, saap_visit_plan_bytes(S, Hq, Hkv, nprobe + (resident_run >= 0), mode) bytes
+ */
+int32_t saap_build_visit_plan(const int32_t* selected, const int32_t* off, const int32_t* len,
+                              int32_t nprobe, int32_t mode, int32_t resident_run, int32_t* plan,
+                              int32_t S, int32_t Hq, int32_t Hkv, int32_t runs, void* stream);
+
+/*
+ * select_buckets_planned -- saap_select_buckets (input_kind SAAP_PROBS) or
+ * saap_select_buckets_from_logits (SAAP_LOGITS) that also writes the visit plan of its lists in the
+ * same launch: the lengths and first rows of the selected buckets are read while the scores are.
+ *   off [S,Hkv,runs+1], len [S,Hkv,runs] with runs = B, or B + 1 when resident_run = B (the index of
+ *   saap_build_windowed_index); selected, probs, the order of the list and the limits as in those calls;
+ *   plan: out, nruns = nprobe + (resident_run >= 0).
+ */
+int32_t saap_select_buckets_planned(const float* scores, int32_t input_kind, float* probs,
+                                    const int32_t* off, const int32_t* len, int32_t resident_run,
+                                    int32_t* selected, int32_t* plan,
+                                    int32_t S, int32_t Hq, int32_t Hkv, int32_t B, int32_t nprobe,
+                                    int32_t mode, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * planned_decode_attention -- saap_sparse_decode_attention / saap_windowed_decode_attention driven by
+ * a visit plan (same result: exact softmax attention over the listed runs, Section 4 "Beyond top-k",
+ * Algorithms 1 and 2 of Appendix F; a list without keys gives out = 0, lse = -inf).
+ *   q [S,Hq,d] dtype; Ksorted, Vsorted [S,Hkv,Ncap,d] dtype; plan as above with nruns runs per list
+ *   mode SAAP_GROUP_SUM: a list serves the G heads of its KV head; SAAP_INDEPENDENT: one list per
+ *   query head, every head reads its list on its own.
+ * Limits: S*lists <= 4096, nruns <= 8191, S*Hkv*Ncap < 2^31; otherwise SAAP_UNSUPPORTED.
+ * Workspace: SAAP_OP_PLANNED_DECODE_ATTENTION.  The _fp8 form reads a cache written by saap_quantize_kv.
+ */
+int32_t saap_planned_decode_attention(const void* q, const void* Ksorted, const void* Vsorted,
+                                      const int32_t* plan, int32_t nruns, int32_t mode, float scale,
+                                      void* out, int32_t out_dtype, float* lse,
+                                      int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t d, int32_t dtype,
+                                      void* ws, size_t ws_bytes, void* stream);
+
+int32_t saap_planned_decode_attention_fp8(const void* q, const uint8_t* K8, const uint8_t* V8,
+                                          const float* kscale, const float* vscale,
+                                          const int32_t* plan, int32_t nruns, int32_t mode, float scale,
+                                          void* out, int32_t out_dtype, float* lse,
+                                          int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t d,
+                                          void* ws, size_t ws_bytes, void* stream);
 
 /*
  * append_keys_fp8 / window_push_fp8 -- saap_append_keys and saap_window_push on an 8-bit cache:

@@ -17,6 +17,7 @@ PROBS, LOGITS = 0, 1
 OP_ASSIGN_KEYS, OP_BUILD_BUCKET_INDEX, OP_CLASSIFY_QUERIES, OP_SELECT_BUCKETS = 0, 1, 2, 3
 OP_SPARSE_DECODE_ATTENTION, OP_DENSE_DECODE_ATTENTION, OP_APPEND_KEYS, OP_WINDOW_PUSH = 4, 5, 6, 7
 OP_BUCKET_ATTENTION_MASS, OP_QUERY_MODEL_LOSS_GRADS, OP_BUCKET_ATTENTION_MASS_BATCH = 8, 9, 10
+OP_PLANNED_DECODE_ATTENTION = 11
 WS_HEADER_BYTES = 65536
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -34,6 +35,8 @@ EXPORTS = (
     "saap_windowed_decode_attention_fp8",
     "saap_bucket_attention_mass", "saap_query_model_loss_grads", "saap_adam_update",
     "saap_bucket_attention_mass_batch", "saap_query_model_bn_loss_grads", "saap_fold_batch_norm",
+    "saap_build_visit_plan", "saap_select_buckets_planned", "saap_planned_decode_attention",
+    "saap_planned_decode_attention_fp8", "saap_visit_plan_bytes",
 )
 
 
@@ -65,6 +68,8 @@ def load_library():
         lib.saap_status_string.argtypes = [ctypes.c_int32]
         for name in EXPORTS[4:] + ("saap_workspace_reset", "saap_device_compute_units"):
             getattr(lib, name).restype = ctypes.c_int32
+        lib.saap_visit_plan_bytes.restype = ctypes.c_size_t
+        lib.saap_visit_plan_bytes.argtypes = [ctypes.c_int32] * 5
         _lib = lib
     return _lib
 
@@ -322,6 +327,90 @@ def sparse_decode_attention(q, Ks, Vs, off, ln, selected, scale, mode=GROUP_SUM,
         _i32(nprobe), _i32(mode), ctypes.c_float(scale), _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S),
         _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _ptr(ws), wsb, _stream())
     _check("saap_sparse_decode_attention", st)
+    return out, lse
+
+
+def visit_plan_ints(S, Hq, Hkv, nruns, mode=GROUP_SUM) -> int:
+    """int32 elements of the visit plan of S*Hkv (GROUP_SUM) or S*Hq (INDEPENDENT) lists of nruns runs."""
+    nbytes = int(load_library().saap_visit_plan_bytes(int(S), int(Hq), int(Hkv), int(nruns), int(mode)))
+    if nbytes == 0:
+        raise SaapError("saap_visit_plan_bytes", -1)
+    return nbytes // 4
+
+
+def _plan_buffer(plan, S, Hq, Hkv, nruns, mode, device):
+    n = visit_plan_ints(S, Hq, Hkv, nruns, mode)
+    if plan is None:
+        plan = torch.empty(n, dtype=torch.int32, device=device)
+    elif plan.dtype != torch.int32 or plan.numel() < n:
+        raise ValueError(f"plan must be int32 with at least {n} elements")
+    return plan
+
+
+def build_visit_plan(selected, off, ln, Hq, mode=GROUP_SUM, resident_run=-1, plan=None):
+    """selected int32 [S,lists,nprobe]; off [S,Hkv,runs+1], ln [S,Hkv,runs] -> plan (int32, flat)."""
+    S, _, nprobe = selected.shape
+    Hkv, runs = ln.shape[1], ln.shape[2]
+    nruns = nprobe + (1 if resident_run >= 0 else 0)
+    plan = _plan_buffer(plan, S, Hq, Hkv, nruns, mode, ln.device)
+    st = load_library().saap_build_visit_plan(_ptr(selected) if nprobe > 0 else ctypes.c_void_p(0), _ptr(off), _ptr(ln),
+                                              _i32(nprobe), _i32(mode), _i32(resident_run), _ptr(plan), _i32(S), _i32(Hq),
+                                              _i32(Hkv), _i32(runs), _stream())
+    _check("saap_build_visit_plan", st)
+    return plan
+
+
+def select_buckets_planned(scores, off, ln, Hkv, nprobe, input_kind=PROBS, mode=GROUP_SUM, resident_run=-1, probs=None,
+                           out=None, plan=None, ws=None):
+    """select_buckets (PROBS) or select_buckets_from_logits (LOGITS) that also writes the lists' visit plan.
+    -> (selected, plan)."""
+    S, Hq, B = scores.shape
+    lists = Hq if mode == INDEPENDENT else Hkv
+    sel = out if out is not None else torch.empty(S, lists, nprobe, dtype=torch.int32, device=scores.device)
+    plan = _plan_buffer(plan, S, Hq, Hkv, nprobe + (1 if resident_run >= 0 else 0), mode, scores.device)
+    ws, wsb = _ws(OP_SELECT_BUCKETS, scores.device, ws)
+    st = load_library().saap_select_buckets_planned(
+        _ptr(scores), _i32(input_kind), _ptr(probs), _ptr(off), _ptr(ln), _i32(resident_run), _ptr(sel), _ptr(plan),
+        _i32(S), _i32(Hq), _i32(Hkv), _i32(B), _i32(nprobe), _i32(mode), _ptr(ws), wsb, _stream())
+    _check("saap_select_buckets_planned", st)
+    return sel, plan
+
+
+def planned_decode_attention(q, Ks, Vs, plan, nruns, scale, mode=GROUP_SUM, out_dtype=torch.float32, out=None, lse=None,
+                             ws=None):
+    """q [S,Hq,d]; Ks,Vs [S,Hkv,Ncap,d]; plan from select_buckets_planned / build_visit_plan -> out, lse."""
+    S, Hq, d = q.shape
+    _, Hkv, Ncap, _ = Ks.shape
+    dev = q.device
+    _plan_buffer(plan, S, Hq, Hkv, nruns, mode, dev)
+    out = out if out is not None else torch.empty(S, Hq, d, dtype=out_dtype, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Hq, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_PLANNED_DECODE_ATTENTION, dev, ws, S=S, Hq=Hq, Hkv=Hkv, mode=mode)
+    st = load_library().saap_planned_decode_attention(
+        _ptr(q), _ptr(Ks), _ptr(Vs), _ptr(plan), _i32(nruns), _i32(mode), ctypes.c_float(scale), _ptr(out),
+        _i32(_dtype_code(out)), _ptr(lse), _i32(S), _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(d), _i32(_dtype_code(q)),
+        _ptr(ws), wsb, _stream())
+    _check("saap_planned_decode_attention", st)
+    return out, lse
+
+
+def planned_decode_attention_fp8(q, K8, V8, kscale, vscale, plan, nruns, scale, mode=GROUP_SUM, out_dtype=torch.float32,
+                                 out=None, lse=None, ws=None):
+    """planned_decode_attention on a cache written by quantize_kv; q bf16 [S,Hq,d]."""
+    if q.dtype != torch.bfloat16 or K8.dtype != torch.uint8 or V8.dtype != torch.uint8:
+        raise TypeError("q must be bf16, K8 and V8 uint8")
+    S, Hq, d = q.shape
+    _, Hkv, Ncap, _ = K8.shape
+    dev = q.device
+    _plan_buffer(plan, S, Hq, Hkv, nruns, mode, dev)
+    out = out if out is not None else torch.empty(S, Hq, d, dtype=out_dtype, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Hq, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_PLANNED_DECODE_ATTENTION, dev, ws, S=S, Hq=Hq, Hkv=Hkv, mode=mode)
+    st = load_library().saap_planned_decode_attention_fp8(
+        _ptr(q), _ptr(K8), _ptr(V8), _ptr(kscale), _ptr(vscale), _ptr(plan), _i32(nruns), _i32(mode),
+        ctypes.c_float(scale), _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S), _i32(Hq), _i32(Hkv), _i32(Ncap),
+        _i32(d), _ptr(ws), wsb, _stream())
+    _check("saap_planned_decode_attention_fp8", st)
     return out, lse
 
 

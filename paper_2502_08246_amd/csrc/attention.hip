@@ -153,6 +153,248 @@ __device__ __forceinline__ float ror_sum(float x) {
 template <int L>
 __device__ __forceinline__ float group_bcast(float x) { return dpp_mov<0x150 + L>(x); }
 
+// One batch of Algorithm 1 for a key processor: scores of the batch's KB keys against the G heads, running
+// maximum / sum / output update.  `m` is the running maximum of the head the lane owns, `l` the sum of the
+// lane's own (key slot, head) weights, O the output slices of all G heads.
+template <typename T, int G, bool MASKED>
+__device__ __forceinline__ void consume_batch(const Batch<T, (G == 8 ? 2 : 4)>& bt,
+                                              const Vec8<typename DotType<T>::type> (&qv)[G], float scale_log2, int sub,
+                                              float& m, float& l, float (&O)[G][8]) {
+  constexpr int KB = G == 8 ? 2 : 4;
+  constexpr int C = KB * G;
+  typedef typename DotType<T>::type TQ;
+  const int c_own = sub & (C - 1);              // the combination this lane owns after the reduction
+  const int i_own = c_own / G;                  // ... its key slot
+  // partial dot products of the lane's 8 features, all (key slot, head) combinations ...
+  float d[C];
+#pragma unroll
+  for (int i = 0; i < KB; ++i) {
+    const Vec8<TQ> kw = dot_operand(bt.k[i]);
+#pragma unroll
+    for (int g = 0; g < G; ++g) d[i * G + g] = kw.dot(qv[g]);
+  }
+  // ... reduced over the 16 lanes so that each lane ends up with ONE complete score
+  const float dot = reduce_scatter16<C>(d, sub);
+  bool live = (bt.valid >> i_own) & 1u;
+  if constexpr (MASKED) live = live && ((bt.heads >> (8 * i_own + c_own % G)) & 1u);
+  const float t = live ? dot * scale_log2 : -INFINITY;
+  // Algorithm 1, one step per batch: the head's running maximum lives in the lanes that own it
+  const float bm = ror_max<G, C>(t);
+  const float mn = fmaxf(m, bm);
+  if (__builtin_amdgcn_ballot_w64(mn > m) != 0ull) {      // some maximum moved: rescale (wave-uniform branch)
+    const float alpha = fast_exp2(m - mn);
+    l *= alpha;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float ag;
+      if constexpr (G == 1) ag = alpha; else ag = g == 0 ? group_bcast<0>(alpha) : g == 1 ? group_bcast<1>(alpha) : g == 2 ? group_bcast<2>(alpha) : g == 3 ? group_bcast<3>(alpha) : g == 4 ? group_bcast<4>(alpha) : g == 5 ? group_bcast<5>(alpha) : g == 6 ? group_bcast<6>(alpha) : group_bcast<7>(alpha);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) O[g][e] *= ag;
+    }
+    m = mn;
+  }
+  const float pw = fast_exp2(t - m);          // weight of the lane's own (key slot, head)
+  l += pw;
+  // every lane needs every weight of its group for the value update: broadcast from the owner
+  float pb[C];
+  pb[0] = group_bcast<0>(pw); pb[1] = group_bcast<1>(pw); pb[2] = group_bcast<2>(pw); pb[3] = group_bcast<3>(pw);
+  if constexpr (C >= 8) { pb[4] = group_bcast<4>(pw); pb[5] = group_bcast<5>(pw); pb[6] = group_bcast<6>(pw); pb[7] = group_bcast<7>(pw); }
+  if constexpr (C == 16) {
+    pb[8] = group_bcast<8>(pw); pb[9] = group_bcast<9>(pw); pb[10] = group_bcast<10>(pw); pb[11] = group_bcast<11>(pw);
+    pb[12] = group_bcast<12>(pw); pb[13] = group_bcast<13>(pw); pb[14] = group_bcast<14>(pw); pb[15] = group_bcast<15>(pw);
+  }
+#pragma unroll
+  for (int i = 0; i < KB; ++i) {
+    float vf[8];
+    bt.v[i].to_float(vf);
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) O[g][e] = fmaf(pb[i * G + g], vf[e], O[g][e]);
+  }
+}
+
+// End of a key range: the head's sum of weights is added up over the key slots, then the four key
+// processors of the wave are combined (Algorithm 2 on registers): common maximum per head, rescale, add
+// up across the four 16-lane rows.
+template <int G>
+__device__ __forceinline__ void wave_combine(float& m, float& l, float (&O)[G][8]) {
+  constexpr int C = (G == 8 ? 2 : 4) * G;
+  l = ror_sum<G, C>(l);
+  const float mw = max_rows(m);
+  const float a = fast_exp2(m - mw);          // scale of this processor's sums for the lane's own head
+  m = mw;
+  l = sum_rows(l * a);
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float ag;
+    if constexpr (G == 1) ag = a; else ag = g == 0 ? group_bcast<0>(a) : g == 1 ? group_bcast<1>(a) : g == 2 ? group_bcast<2>(a) : g == 3 ? group_bcast<3>(a) : g == 4 ? group_bcast<4>(a) : g == 5 ? group_bcast<5>(a) : g == 6 ? group_bcast<6>(a) : group_bcast<7>(a);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) O[g][e] = sum_rows(O[g][e] * ag);
+  }
+}
+
+// The waves of a workgroup combine their results through LDS (`scratch`: nw * G * (d + 2) floats, free
+// for use once every wave has passed the barrier at the top): Algorithm 2 over the nw partial results,
+// one (head, feature) per thread; every thread derives the weights 2^(m_j - M) of its head itself (nw
+// exponentials) rather than waiting for a shared table.  emit(g, e, M, L, O) receives the merged values.
+template <int G, int NT, typename F>
+__device__ __forceinline__ void workgroup_combine(float* scratch, float m, float l, const float (&O)[G][8], F emit) {
+  constexpr int nw = NT / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, sub = lane & 15, grp = lane >> 4;
+  __syncthreads();
+  float* w_o = scratch;                                   // [nw][G][d] unnormalised outputs
+  float* w_m = w_o + nw * G * kD;                         // [nw][G] maxima
+  float* w_l = w_m + nw * G;                              // [nw][G] sums of weights
+  if (grp == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float4* dst = reinterpret_cast<float4*>(w_o + (wave * G + g) * kD + sub * 8);
+      dst[0] = make_float4(O[g][0], O[g][1], O[g][2], O[g][3]);
+      dst[1] = make_float4(O[g][4], O[g][5], O[g][6], O[g][7]);
+    }
+    if (sub < G) {            // lane `sub` owns head `sub` (key slot 0)
+      w_m[wave * G + sub] = m;
+      w_l[wave * G + sub] = l;
+    }
+  }
+  __syncthreads();
+  for (int x = tid; x < G * kD; x += NT) {
+    const int g = x / kD, e = x % kD;
+    float mj[nw];
+    float M = kNegBig;
+#pragma unroll
+    for (int j = 0; j < nw; ++j) {
+      mj[j] = w_m[j * G + g];
+      M = fmaxf(M, mj[j]);
+    }
+    float L = 0.f, Ov = 0.f;
+#pragma unroll
+    for (int j = 0; j < nw; ++j) {
+      const float w = fast_exp2(mj[j] - M);
+      L = fmaf(w, w_l[j * G + g], L);
+      Ov = fmaf(w, w_o[(j * G + g) * kD + e], Ov);
+    }
+    emit(g, e, M, L, Ov);
+  }
+}
+
+// Final merge of a unit by its last workgroup (Algorithm 2): P partial results, stored from slot
+// `slot0` on, become out / lse of the unit's G heads.  One partial is kCols = G*d/4 float4 columns; the
+// workgroup's threads form NT/kCols groups that take the partials round-robin, eight loads in flight
+// each, while one wave per head turns the partial maxima into weights.  `scratch` holds
+// P*G + 2G + 4 floats and NT float4.
+template <int G, int NT>
+__device__ __forceinline__ void final_merge(const float* part_o, const float* part_ml, size_t slot0, int P, int qrow0,
+                                            float vs, void* out, int out_bf16, float* lse, float* scratch) {
+  constexpr int nw = NT / 64;
+  constexpr int kCols = G * kD / 4;
+  constexpr int kInFlight = 8;
+  constexpr int n_groups = NT / kCols;                // >= 1: NT >= 256 >= kCols
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int colx = tid % kCols, pgrp = tid / kCols;
+  const int g_col = colx / (kD / 4);
+  const float4* po = reinterpret_cast<const float4*>(part_o) + slot0 * kCols + colx;
+  const float2* pml = reinterpret_cast<const float2*>(part_ml) + slot0 * G;
+  float* s_w = scratch;                                // [P*G] weights 2^(m_i - M)
+  float* s_M = s_w + P * G;                            // [G]
+  float* s_L = s_M + G;                                // [G]
+  float4* s_acc = reinterpret_cast<float4*>(s_L + G + ((4 - (P * G + 2 * G) % 4) % 4));   // [n_groups][kCols]
+
+  // every load of the first round goes out before anything waits: the (max, sum) pairs first,
+  // they are needed first
+  float2 ml[2];
+  const int g_w = wave < G ? wave : 0;               // wave w weighs head w (and w+nw, ... below)
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int pi = lane + 64 * k;
+    ml[k] = pi < P ? pml[(size_t)pi * G + g_w] : make_float2(kNegBig, 0.f);
+  }
+  float4 v[kInFlight];
+#pragma unroll
+  for (int k = 0; k < kInFlight; ++k) {
+    const int pi = pgrp + k * n_groups;
+    v[k] = pi < P ? po[(size_t)pi * kCols] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  for (int g = wave; g < G; g += nw) {
+    if (g != g_w) {
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int pi = lane + 64 * k;
+        ml[k] = pi < P ? pml[(size_t)pi * G + g] : make_float2(kNegBig, 0.f);
+      }
+    }
+    float mx = fmaxf(ml[0].x, ml[1].x);
+    for (int pi = lane + 128; pi < P; pi += 64) mx = fmaxf(mx, pml[(size_t)pi * G + g].x);   // more than 128 partials
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float lsum = 0.f;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int pi = lane + 64 * k;
+      const float w = fast_exp2(ml[k].x - mx);
+      if (pi < P) s_w[pi * G + g] = w;
+      lsum = fmaf(w, ml[k].y, lsum);
+    }
+    for (int pi = lane + 128; pi < P; pi += 64) {
+      const float2 t = pml[(size_t)pi * G + g];
+      const float w = fast_exp2(t.x - mx);
+      s_w[pi * G + g] = w;
+      lsum = fmaf(w, t.y, lsum);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lsum += __shfl_xor(lsum, o);
+    if (lane == 0) {
+      s_M[g] = mx;
+      s_L[g] = lsum;
+    }
+  }
+  __syncthreads();
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int p0 = pgrp;; p0 += n_groups * kInFlight) {
+#pragma unroll
+    for (int k = 0; k < kInFlight; ++k) {
+      const int pi = p0 + k * n_groups;
+      if (pi < P) {
+        const float w = s_w[pi * G + g_col];
+        acc.x = fmaf(w, v[k].x, acc.x);
+        acc.y = fmaf(w, v[k].y, acc.y);
+        acc.z = fmaf(w, v[k].z, acc.z);
+        acc.w = fmaf(w, v[k].w, acc.w);
+      }
+    }
+    const int nxt = p0 + n_groups * kInFlight;
+    if (nxt - pgrp >= P) break;     // uniform over the workgroup: depends on P and n_groups only
+#pragma unroll
+    for (int k = 0; k < kInFlight; ++k) {
+      const int pi = nxt + k * n_groups;
+      v[k] = pi < P ? po[(size_t)pi * kCols] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+  if (pgrp < n_groups) s_acc[pgrp * kCols + colx] = acc;
+  __syncthreads();
+  if (tid < kCols) {
+    float4 r = s_acc[tid];
+    for (int gi = 1; gi < n_groups; ++gi) {
+      const float4 a = s_acc[gi * kCols + tid];
+      r.x += a.x; r.y += a.y; r.z += a.z; r.w += a.w;
+    }
+    const float L = s_L[g_col], M = s_M[g_col];
+    const float inv = L > 0.f ? vs * (1.0f / L) : 0.f;   // vs: scale of an 8-bit cache's V codes, else 1
+    r.x *= inv; r.y *= inv; r.z *= inv; r.w *= inv;
+    const int qrow = qrow0 + g_col, e0 = (colx % (kD / 4)) * 4;
+    if (out_bf16) {
+      uint2 pk;
+      pk.x = f32_to_bf16_bits(r.x) | (f32_to_bf16_bits(r.y) << 16);
+      pk.y = f32_to_bf16_bits(r.z) | (f32_to_bf16_bits(r.w) << 16);
+      *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(out) + (size_t)qrow * kD + e0) = pk;
+    } else {
+      *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + (size_t)qrow * kD + e0) = r;
+    }
+    if (e0 == 0 && lse) lse[qrow] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
+  }
+}
+
 // MASKED (with LIST): every head of the group brings its own list of runs (independent routing).
 // The union of the lists is visited once; a key takes part only for the heads whose list holds
 // its run (the others see a score of -inf for it).
@@ -170,8 +412,6 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   typedef typename DotType<T>::type TQ;         // queries of an 8-bit cache are bf16
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane & 15, grp = lane >> 4;
-  const int c_own = sub & (C - 1);              // the combination this lane owns after the reduction
-  const int i_own = c_own / G;                  // ... its key slot
   SAAP_TRACE(0);
   const int unit = blockIdx.x % p.n_units;
   const int wg = blockIdx.x / p.n_units;
@@ -421,55 +661,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     }
   };
 
-  auto consume = [&](const Batch<T, KB>& bt) {
-    // partial dot products of the lane's 8 features, all (key slot, head) combinations ...
-    float d[C];
-#pragma unroll
-    for (int i = 0; i < KB; ++i) {
-      const Vec8<TQ> kw = dot_operand(bt.k[i]);
-#pragma unroll
-      for (int g = 0; g < G; ++g) d[i * G + g] = kw.dot(qv[g]);
-    }
-    // ... reduced over the 16 lanes so that each lane ends up with ONE complete score
-    const float dot = reduce_scatter16<C>(d, sub);
-    bool live = (bt.valid >> i_own) & 1u;
-    if constexpr (MASKED) live = live && ((bt.heads >> (8 * i_own + c_own % G)) & 1u);
-    const float t = live ? dot * scale_log2 : -INFINITY;
-    // Algorithm 1, one step per batch: the head's running maximum lives in the lanes that own it
-    const float bm = ror_max<G, C>(t);
-    const float mn = fmaxf(m, bm);
-    if (__builtin_amdgcn_ballot_w64(mn > m) != 0ull) {      // some maximum moved: rescale (wave-uniform branch)
-      const float alpha = fast_exp2(m - mn);
-      l *= alpha;
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float ag;
-        if constexpr (G == 1) ag = alpha; else ag = g == 0 ? group_bcast<0>(alpha) : g == 1 ? group_bcast<1>(alpha) : g == 2 ? group_bcast<2>(alpha) : g == 3 ? group_bcast<3>(alpha) : g == 4 ? group_bcast<4>(alpha) : g == 5 ? group_bcast<5>(alpha) : g == 6 ? group_bcast<6>(alpha) : group_bcast<7>(alpha);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) O[g][e] *= ag;
-      }
-      m = mn;
-    }
-    const float pw = fast_exp2(t - m);          // weight of the lane's own (key slot, head)
-    l += pw;
-    // every lane needs every weight of its group for the value update: broadcast from the owner
-    float pb[C];
-    pb[0] = group_bcast<0>(pw); pb[1] = group_bcast<1>(pw); pb[2] = group_bcast<2>(pw); pb[3] = group_bcast<3>(pw);
-    if constexpr (C >= 8) { pb[4] = group_bcast<4>(pw); pb[5] = group_bcast<5>(pw); pb[6] = group_bcast<6>(pw); pb[7] = group_bcast<7>(pw); }
-    if constexpr (C == 16) {
-      pb[8] = group_bcast<8>(pw); pb[9] = group_bcast<9>(pw); pb[10] = group_bcast<10>(pw); pb[11] = group_bcast<11>(pw);
-      pb[12] = group_bcast<12>(pw); pb[13] = group_bcast<13>(pw); pb[14] = group_bcast<14>(pw); pb[15] = group_bcast<15>(pw);
-    }
-#pragma unroll
-    for (int i = 0; i < KB; ++i) {
-      float vf[8];
-      bt.v[i].to_float(vf);
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) O[g][e] = fmaf(pb[i * G + g], vf[e], O[g][e]);
-    }
-  };
+  auto consume = [&](const Batch<T, KB>& bt) { consume_batch<T, G, MASKED>(bt, qv, scale_log2, sub, m, l, O); };
 
   {
     long long base = (long long)wg * chunk;
@@ -499,64 +691,11 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   }
 
   SAAP_TRACE(3);
-  // the head's sum of weights: add up the key slots (lanes s, s+G, ... of the group)
-  l = ror_sum<G, C>(l);
-  // combine the four key processors of the wave (Algorithm 2 on registers): common maximum per
-  // head, rescale, add up across the four 16-lane rows
-  {
-    const float mw = max_rows(m);
-    const float a = fast_exp2(m - mw);          // scale of this processor's sums for the lane's own head
-    m = mw;
-    l = sum_rows(l * a);
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float ag;
-      if constexpr (G == 1) ag = a; else ag = g == 0 ? group_bcast<0>(a) : g == 1 ? group_bcast<1>(a) : g == 2 ? group_bcast<2>(a) : g == 3 ? group_bcast<3>(a) : g == 4 ? group_bcast<4>(a) : g == 5 ? group_bcast<5>(a) : g == 6 ? group_bcast<6>(a) : group_bcast<7>(a);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) O[g][e] = sum_rows(O[g][e] * ag);
-    }
-  }
+  wave_combine<G>(m, l, O);
 
-  // waves -> LDS (the index arrays are dead from here on)
+  // waves -> LDS (the index arrays are dead once every wave has passed the barrier inside)
   SAAP_TRACE(9);
-  __syncthreads();
-  SAAP_TRACE(10);
-  float* w_o = reinterpret_cast<float*>(smem);            // [nw][G][d] unnormalised outputs
-  float* w_m = w_o + nw * G * kD;                         // [nw][G] maxima
-  float* w_l = w_m + nw * G;                              // [nw][G] sums of weights
-  if (grp == 0) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float4* dst = reinterpret_cast<float4*>(w_o + (wave * G + g) * kD + sub * 8);
-      dst[0] = make_float4(O[g][0], O[g][1], O[g][2], O[g][3]);
-      dst[1] = make_float4(O[g][4], O[g][5], O[g][6], O[g][7]);
-    }
-    if (sub < G) {            // lane `sub` owns head `sub` (key slot 0)
-      w_m[wave * G + sub] = m;
-      w_l[wave * G + sub] = l;
-    }
-  }
-  __syncthreads();
-  SAAP_TRACE(11);
-  // Algorithm 2 over the nw partial results of the workgroup, one (head, feature) per thread; every
-  // thread derives the weights 2^(m_j - M) of its head itself (nw exponentials) rather than
-  // waiting for a shared table
-  for (int x = tid; x < G * kD; x += NT) {
-    const int g = x / kD, e = x % kD;
-    float mj[nw];
-    float M = kNegBig;
-#pragma unroll
-    for (int j = 0; j < nw; ++j) {
-      mj[j] = w_m[j * G + g];
-      M = fmaxf(M, mj[j]);
-    }
-    float L = 0.f, Ov = 0.f;
-#pragma unroll
-    for (int j = 0; j < nw; ++j) {
-      const float w = fast_exp2(mj[j] - M);
-      L = fmaf(w, w_l[j * G + g], L);
-      Ov = fmaf(w, w_o[(j * G + g) * kD + e], Ov);
-    }
+  workgroup_combine<G, NT>(reinterpret_cast<float*>(smem), m, l, O, [&](int g, int e, float M, float L, float Ov) {
     if (p.P == 1) {
       store_out(p, qrow0 + g, e, M, L, Ov, vs);
     } else {
@@ -567,7 +706,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
         coherent_store(&p.part_ml[slot * 2 + 1], L);
       }
     }
-  }
+  });
   if (p.P == 1) return;
 
   // The last workgroup of the unit to arrive merges the P partial results (Algorithm 2).
@@ -601,110 +740,372 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   }
   SAAP_TRACE(6);
 
-  // Merge layout: one partial is kCols = G*d/4 float4 columns.  The workgroup's threads form
-  // blockDim/kCols groups that take the partials round-robin, eight loads in flight each, while
-  // one wave per head turns the partial maxima into weights.
-  constexpr int kCols = G * kD / 4;
-  constexpr int kInFlight = 8;
-  const int P = p.P;
-  constexpr int n_groups = NT / kCols;                // >= 1: NT >= 256 >= kCols
-  const int colx = tid % kCols, pgrp = tid / kCols;
-  const int g_col = colx / (kD / 4);
-  const float4* po = reinterpret_cast<const float4*>(p.part_o) + (size_t)unit * P * kCols + colx;
-  const float2* pml = reinterpret_cast<const float2*>(p.part_ml) + (size_t)unit * P * G;
-  float* s_w = reinterpret_cast<float*>(smem);         // [P*G] weights 2^(m_i - M)
-  float* s_M = s_w + P * G;                            // [G]
-  float* s_L = s_M + G;                                // [G]
-  float4* s_acc = reinterpret_cast<float4*>(s_L + G + ((4 - (P * G + 2 * G) % 4) % 4));   // [n_groups][kCols]
-
-  // every load of the first round goes out before anything waits: the (max, sum) pairs first,
-  // they are needed first
-  float2 ml[2];
-  const int g_w = wave < G ? wave : 0;               // wave w weighs head w (and w+nw, ... below)
-#pragma unroll
-  for (int k = 0; k < 2; ++k) {
-    const int pi = lane + 64 * k;
-    ml[k] = pi < P ? pml[(size_t)pi * G + g_w] : make_float2(kNegBig, 0.f);
-  }
-  float4 v[kInFlight];
-#pragma unroll
-  for (int k = 0; k < kInFlight; ++k) {
-    const int pi = pgrp + k * n_groups;
-    v[k] = pi < P ? po[(size_t)pi * kCols] : make_float4(0.f, 0.f, 0.f, 0.f);
-  }
-  for (int g = wave; g < G; g += nw) {
-    if (g != g_w) {
-#pragma unroll
-      for (int k = 0; k < 2; ++k) {
-        const int pi = lane + 64 * k;
-        ml[k] = pi < P ? pml[(size_t)pi * G + g] : make_float2(kNegBig, 0.f);
-      }
-    }
-    float mx = fmaxf(ml[0].x, ml[1].x);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-    float lsum = 0.f;
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-      const int pi = lane + 64 * k;
-      const float w = fast_exp2(ml[k].x - mx);
-      if (pi < P) s_w[pi * G + g] = w;
-      lsum = fmaf(w, ml[k].y, lsum);
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) lsum += __shfl_xor(lsum, o);
-    if (lane == 0) {
-      s_M[g] = mx;
-      s_L[g] = lsum;
-    }
-  }
-  __syncthreads();
-  SAAP_TRACE(7);
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int p0 = pgrp;; p0 += n_groups * kInFlight) {
-#pragma unroll
-    for (int k = 0; k < kInFlight; ++k) {
-      const int pi = p0 + k * n_groups;
-      if (pi < P) {
-        const float w = s_w[pi * G + g_col];
-        acc.x = fmaf(w, v[k].x, acc.x);
-        acc.y = fmaf(w, v[k].y, acc.y);
-        acc.z = fmaf(w, v[k].z, acc.z);
-        acc.w = fmaf(w, v[k].w, acc.w);
-      }
-    }
-    const int nxt = p0 + n_groups * kInFlight;
-    if (nxt - pgrp >= P) break;     // uniform over the workgroup: depends on P and n_groups only
-#pragma unroll
-    for (int k = 0; k < kInFlight; ++k) {
-      const int pi = nxt + k * n_groups;
-      v[k] = pi < P ? po[(size_t)pi * kCols] : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-  }
-  if (pgrp < n_groups) s_acc[pgrp * kCols + colx] = acc;
-  __syncthreads();
-  if (tid < kCols) {
-    float4 r = s_acc[tid];
-    for (int gi = 1; gi < n_groups; ++gi) {
-      const float4 a = s_acc[gi * kCols + tid];
-      r.x += a.x; r.y += a.y; r.z += a.z; r.w += a.w;
-    }
-    const float L = s_L[g_col], M = s_M[g_col];
-    const float inv = L > 0.f ? vs * (1.0f / L) : 0.f;   // vs: scale of an 8-bit cache's V codes, else 1
-    r.x *= inv; r.y *= inv; r.z *= inv; r.w *= inv;
-    const int qrow = qrow0 + g_col, e0 = (colx % (kD / 4)) * 4;
-    if (p.out_bf16) {
-      uint2 pk;
-      pk.x = f32_to_bf16_bits(r.x) | (f32_to_bf16_bits(r.y) << 16);
-      pk.y = f32_to_bf16_bits(r.z) | (f32_to_bf16_bits(r.w) << 16);
-      *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(p.out) + (size_t)qrow * kD + e0) = pk;
-    } else {
-      *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.out) + (size_t)qrow * kD + e0) = r;
-    }
-    if (e0 == 0 && p.lse) p.lse[qrow] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
-  }
+  final_merge<G, NT>(p.part_o, p.part_ml, (size_t)unit * p.P, p.P, qrow0, vs, p.out, p.out_bf16, p.lse,
+                     reinterpret_cast<float*>(smem));
   SAAP_TRACE(8);
   if (tid == 0) __hip_atomic_store(&p.counters[unit], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+
+// ------------------------------------------------------------------------------------------------
+// Attention from a visit plan: the work of ALL units dealt to the workgroups in equal shares.
+//
+// A visit plan lists, per unit, the runs of the sorted cache to attend (first row and an exclusive
+// prefix of the run lengths) and their total T_u.  The units' key ranges are concatenated into one
+// global range of sum T_u keys and workgroup w takes keys [w*Q, (w+1)*Q) of it, Q = ceil(sum / W):
+// every workgroup streams the same number of keys whatever the sizes of the visited buckets and of
+// the units are (Section 5 "On GPU" notes that one block per bucket makes the largest bucket set the
+// run time; with one team of workgroups per unit the largest unit does).  A workgroup whose share
+// crosses a unit boundary finishes one unit (partial result, Algorithm 2) and goes on with the next;
+// a unit is merged by the last of the workgroups that hold a piece of it.
+//
+// Plan layout per unit (stride ps = 2*nseg + 2 rounded up to a multiple of 4 ints):
+//   [0] T_u | [1 .. nseg+1] pre[0..nseg], pre[0] = 0, pre[j+1] = pre[j] + length of run j | [nseg+2 ..] first row of run j
+struct PlanParams {
+  const void* q;          // [S,Hq,d]
+  const void* K;          // [kv units, rows, d]
+  const void* V;
+  const int32_t* plan;    // [units, ps]
+  void* out;              // [S,Hq,d]
+  float* lse;             // [S,Hq] or null
+  float* part_o;          // [slots, G, d]
+  float* part_ml;         // [slots, G, 2]
+  unsigned long long* counters;   // [units] arrivals; zero on entry and on exit
+  long long rows;         // rows per kv unit
+  int nseg;               // runs per unit in the plan
+  int ps;                 // ints per unit in the plan
+  int n_units;
+  int Hq, Hkv;
+  int independent;        // unit = (sequence, query head) instead of (sequence, KV head)
+  int out_bf16;
+  int all_tables;         // every unit's table is copied to LDS at the start (one memory round trip)
+  int q_min;              // least number of keys per workgroup
+  float scale_log2;       // scale * log2(e)
+  const float* kscale;    // 8-bit cache: [kv units] scale of the K codes, else null
+  const float* vscale;
+};
+constexpr int kPlanMaxWgs = 1024;       // workgroups of a planned launch (sizes the partial results)
+constexpr int kPlanMaxUnits = 4096;
+constexpr int kPlanTableInts = 16384;   // all units' tables fit LDS up to this many ints
+
+__host__ __device__ constexpr int plan_stride(int nseg) { return (2 * nseg + 2 + 3) & ~3; }
+
+// largest j in [lo, hi) with a[j] <= v  (a non-decreasing, a[lo] <= v)
+__device__ __forceinline__ int last_not_above(const int* a, int lo, int hi, int v) {
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a[mid] <= v) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+template <typename T, int G, int NT>
+__global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int s_wsum[2][16];
+  __shared__ int s_last;
+
+  constexpr int nw = NT / 64;
+  constexpr int KB = G == 8 ? 2 : 4;            // keys a key processor has in flight per batch
+  constexpr bool kPrefetch = sizeof(T) <= 2;    // fp32 rows are too wide to double-buffer
+  constexpr bool kFp8 = sizeof(T) == 1;
+  constexpr int kTabLoads = kPlanTableInts / 4 / NT;   // 16-byte loads per thread that cover the largest table
+  typedef typename DotType<T>::type TQ;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sub = lane & 15, grp = lane >> 4;
+  constexpr int NG = nw * 4;            // key processors in the workgroup
+  constexpr int chunk = NG * KB;        // keys the workgroup consumes per batch
+  const int kp = wave * 4 + grp;
+  const int U = p.n_units, W = (int)gridDim.x, w = (int)blockIdx.x;
+  SAAP_TRACE(0);
+
+  int* s_ustart = reinterpret_cast<int*>(smem);           // [U+1] first key of each unit in the global range
+  int* s_urank = s_ustart + (U + 1);                      // [U+1] units with keys before each unit
+  int* s_tab = s_urank + (U + 1) + ((4 - (2 * (U + 1)) % 4) % 4);   // [U*ps] or [ps] plan tables (16-byte aligned)
+  float* scratch = reinterpret_cast<float*>(s_tab + (p.all_tables ? U * p.ps : p.ps));
+
+  // ---- totals of all units -> ranges of the units in the global key range
+  if (p.all_tables) {
+    const int n4 = U * p.ps / 4;
+    const int4* src = reinterpret_cast<const int4*>(p.plan);
+    int4 r[kTabLoads];
+#pragma unroll
+    for (int k = 0; k < kTabLoads; ++k) {
+      const int i = tid + k * NT;
+      if (i < n4) r[k] = src[i];
+    }
+#pragma unroll
+    for (int k = 0; k < kTabLoads; ++k) {
+      const int i = tid + k * NT;
+      if (i < n4) reinterpret_cast<int4*>(s_tab)[i] = r[k];
+    }
+    __syncthreads();
+  }
+  {
+    const int per = (U + NT - 1) / NT;                    // <= kPlanMaxUnits / NT
+    const int u0 = tid * per;
+    int tv[kPlanMaxUnits / NT];
+#pragma unroll
+    for (int k = 0; k < kPlanMaxUnits / NT; ++k) {
+      const int u = u0 + k;
+      tv[k] = (k < per && u < U) ? (p.all_tables ? s_tab[u * p.ps] : p.plan[(size_t)u * p.ps]) : 0;
+    }
+    int mine = 0, cnt = 0;
+#pragma unroll
+    for (int k = 0; k < kPlanMaxUnits / NT; ++k) {
+      tv[k] = max(tv[k], 0);
+      mine += tv[k];
+      cnt += tv[k] > 0 ? 1 : 0;
+    }
+    const int incl_k = (int)wave_prefix_sum((unsigned)mine), incl_c = (int)wave_prefix_sum((unsigned)cnt);
+    if (lane == 63) {
+      s_wsum[0][wave] = incl_k;
+      s_wsum[1][wave] = incl_c;
+    }
+    __syncthreads();
+    int run = incl_k - mine, rank = incl_c - cnt, tot_k = 0, tot_c = 0;
+#pragma unroll
+    for (int x = 0; x < nw; ++x) {
+      if (x < wave) {
+        run += s_wsum[0][x];
+        rank += s_wsum[1][x];
+      }
+      tot_k += s_wsum[0][x];
+      tot_c += s_wsum[1][x];
+    }
+#pragma unroll
+    for (int k = 0; k < kPlanMaxUnits / NT; ++k) {
+      const int u = u0 + k;
+      if (k < per && u < U) {
+        s_ustart[u] = run;
+        s_urank[u] = rank;
+        run += tv[k];
+        rank += tv[k] > 0 ? 1 : 0;
+      }
+    }
+    if (tid == 0) {
+      s_ustart[U] = tot_k;
+      s_urank[U] = tot_c;
+    }
+    __syncthreads();
+  }
+  const int t_all = s_ustart[U];
+  const int Q = max((t_all + W - 1) / W, p.q_min);        // keys per workgroup
+  const long long k0 = (long long)w * Q;
+  const int k1 = (int)min((long long)t_all, k0 + Q);
+
+  // a unit without keys has no workgroup: out = 0, lse = -inf written by workgroup u mod W
+  for (int u = w; u < U; u += W) {
+    if (s_ustart[u + 1] != s_ustart[u]) continue;
+    const int qr = p.independent ? u : u * G;
+    for (int x = tid; x < G * kD; x += NT) {
+      if (p.out_bf16) reinterpret_cast<bf16_t*>(p.out)[(size_t)qr * kD + x] = (bf16_t)0;
+      else reinterpret_cast<float*>(p.out)[(size_t)qr * kD + x] = 0.f;
+    }
+    if (tid < G && p.lse) p.lse[qr + tid] = -INFINITY;
+  }
+  if (k0 >= t_all) return;
+  SAAP_TRACE(1);
+
+  int u = last_not_above(s_ustart, 0, U, (int)k0);        // the unit that holds key k0 (it has keys)
+  for (int ks = (int)k0; ks < k1; ++u) {
+    const int us = s_ustart[u], ue = s_ustart[u + 1];
+    if (ue == us) continue;
+    // ---- my piece of unit u: its keys [a, b)
+    const int a = ks - us, b = min(k1, ue) - us;
+    ks = ue;
+    int kvu, qrow0;
+    if (p.independent) {
+      const int s = u / p.Hq, hq = u % p.Hq;
+      kvu = s * p.Hkv + hq / (p.Hq / p.Hkv);
+      qrow0 = u;
+    } else {
+      kvu = u;
+      qrow0 = u * G;
+    }
+    const T* Kb = reinterpret_cast<const T*>(p.K) + (size_t)kvu * p.rows * kD + sub * 8;
+    const T* Vb = reinterpret_cast<const T*>(p.V) + (size_t)kvu * p.rows * kD + sub * 8;
+    Vec8<TQ> qv[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) qv[g].load(reinterpret_cast<const TQ*>(p.q) + (size_t)(qrow0 + g) * kD + sub * 8);
+    float scale_log2 = p.scale_log2, vs = 1.f;
+    if constexpr (kFp8) {
+      scale_log2 *= p.kscale[kvu];
+      vs = p.vscale[kvu];
+    }
+    const int* tab = s_tab + u * p.ps;
+    if (!p.all_tables) {
+      // one unit's table at a time
+      tab = s_tab;
+      __syncthreads();                                    // the table of the unit before is dead
+      const int n4 = p.ps / 4;
+      const int4* src = reinterpret_cast<const int4*>(p.plan + (size_t)u * p.ps);
+      int4 r[kTabLoads];
+#pragma unroll
+      for (int k = 0; k < kTabLoads; ++k) {
+        const int i = tid + k * NT;
+        if (i < n4) r[k] = src[i];
+      }
+#pragma unroll
+      for (int k = 0; k < kTabLoads; ++k) {
+        const int i = tid + k * NT;
+        if (i < n4) reinterpret_cast<int4*>(s_tab)[i] = r[k];
+      }
+      __syncthreads();
+    }
+    const int* pre = tab + 1;                             // [nseg+1]
+    const int* rowoff = tab + p.nseg + 2;                 // [nseg]
+    // runs that hold the first and the last key of the piece: the per-key lookups search only these
+    const int ra = last_not_above(pre, 0, p.nseg, a), rb = last_not_above(pre, 0, p.nseg, b - 1);
+
+    float m = kNegBig, l = 0.f, O[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) O[g][e] = 0.f;
+
+    // Keys of (this processor, slot i) of the batch at `base`: base + i*NG + kp.  Slots past the end of
+    // the piece load nothing.
+    auto load_batch = [&](int base, Batch<T, KB>& bt) {
+      int row;
+      {
+        const int v = min(base + (sub & (KB - 1)) * NG + kp, b - 1);   // lane `sub` resolves slot sub % KB
+        const int j = last_not_above(pre, ra, rb + 1, v);
+        row = rowoff[j] + (v - pre[j]);
+        // a plan that breaks the contract (overlapping runs, a damaged index) must not turn into a
+        // read outside the cache
+        row = min(max(row, 0), (int)p.rows - 1);
+      }
+      bt.valid = 0u;
+      bt.heads = 0u;
+#pragma unroll
+      for (int i = 0; i < KB; ++i) {
+        const int r = __shfl(row, (lane & 48) + i);
+        if (base + i * NG + kp < b) {
+          bt.valid |= 1u << i;
+          bt.k[i].load_stream(Kb + (size_t)r * kD);
+          bt.v[i].load_stream(Vb + (size_t)r * kD);
+        } else {
+          bt.k[i] = Vec8<T>{};
+          bt.v[i] = Vec8<T>{};
+        }
+      }
+    };
+    auto consume = [&](const Batch<T, KB>& bt) { consume_batch<T, G, false>(bt, qv, scale_log2, sub, m, l, O); };
+    {
+      int base = a;
+      Batch<T, KB> cur;
+      load_batch(base, cur);
+      if constexpr (kPrefetch) {
+        for (base += chunk; base < b; base += chunk) {
+          Batch<T, KB> nxt;
+          load_batch(base, nxt);        // in flight while the current batch is consumed
+          __builtin_amdgcn_sched_barrier(0);
+          consume(cur);
+          cur = nxt;
+        }
+        consume(cur);
+      } else {
+        consume(cur);
+        for (base += chunk; base < b; base += chunk) {
+          load_batch(base, cur);
+          consume(cur);
+        }
+      }
+    }
+    SAAP_TRACE(3);
+
+    // ---- end of the piece: one partial result of unit u (or its final result if no other workgroup
+    // holds a piece of it)
+    wave_combine<G>(m, l, O);
+    const int w_first = us / Q, w_last = (ue - 1) / Q;
+    const int P = w_last - w_first + 1;
+    // slots are numbered along the global range: (workgroup, unit) pairs in order differ by one in
+    // w + rank(u), so a unit's partial results are consecutive
+    const size_t slot = (size_t)w + s_urank[u];
+    workgroup_combine<G, NT>(scratch, m, l, O, [&](int g, int e, float M, float L, float Ov) {
+      if (P == 1) {
+        const float r = L > 0.f ? vs * (Ov / L) : 0.f;
+        if (p.out_bf16) reinterpret_cast<bf16_t*>(p.out)[(size_t)(qrow0 + g) * kD + e] = (bf16_t)f32_to_bf16_bits(r);
+        else reinterpret_cast<float*>(p.out)[(size_t)(qrow0 + g) * kD + e] = r;
+        if (e == 0 && p.lse) p.lse[qrow0 + g] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
+      } else {
+        coherent_store(&p.part_o[(slot * G + g) * kD + e], Ov);
+        if (e == 0) {
+          coherent_store(&p.part_ml[(slot * G + g) * 2 + 0], M);
+          coherent_store(&p.part_ml[(slot * G + g) * 2 + 1], L);
+        }
+      }
+    });
+    if (P == 1) continue;
+    SAAP_TRACE(4);
+    wait_stores();
+    __syncthreads();
+    if (tid == 0) {
+      // Arrival counter of the unit: count in bits 0-15, sum of the arrivals' XCD numbers in bits 16-31,
+      // sum of their squares in bits 32-47.  sum = n*x and squares = n*x*x hold only if every arrival
+      // came from XCD x: then all partial results went through this XCD's L2.
+      const unsigned long long xcc = (unsigned long long)((unsigned)__builtin_amdgcn_s_getreg(20 | (3 << 11)) & 7u);
+      const unsigned long long old = __hip_atomic_fetch_add(&p.counters[u], 1ull | (xcc << 16) | ((xcc * xcc) << 32),
+                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned long long n = old & 0xffffull, sx = (old >> 16) & 0xffffull, sxx = (old >> 32) & 0xffffull;
+      s_last = n == (unsigned long long)(P - 1) ? ((sx == n * xcc && sxx == n * xcc * xcc) ? 2 : 1) : 0;
+    }
+    __syncthreads();
+    SAAP_TRACE(5);
+    if (!s_last) continue;
+    if (s_last == 2) {
+      // this XCD's L2 is coherent for its compute units: dropping this compute unit's L1 lines is enough
+      asm volatile("buffer_inv sc0" ::: "memory");
+    } else {
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
+    SAAP_TRACE(6);
+    final_merge<G, NT>(p.part_o, p.part_ml, (size_t)w_first + s_urank[u], P, qrow0, vs, p.out, p.out_bf16, p.lse, scratch);
+    SAAP_TRACE(8);
+    if (tid == 0) __hip_atomic_store(&p.counters[u], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+// Visit plan of every unit from its list of runs: one workgroup per unit.
+__global__ void __launch_bounds__(256) visit_plan_kernel(const int32_t* __restrict__ selected, const int32_t* __restrict__ off,
+                                                        const int32_t* __restrict__ len, int32_t* __restrict__ plan,
+                                                        int nsel, int resident, int runs, int ps, int Hq, int Hkv,
+                                                        int independent) {
+  __shared__ int s_wsum[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int unit = blockIdx.x;
+  const int kvu = independent ? (unit / Hq) * Hkv + (unit % Hq) / (Hq / Hkv) : unit;
+  const int nseg = nsel + (resident >= 0 ? 1 : 0);
+  const int32_t* lenu = len + (size_t)kvu * runs;
+  const int32_t* offu = off + (size_t)kvu * (runs + 1);
+  const int32_t* sel = selected ? selected + (size_t)unit * nsel : nullptr;
+  int32_t* pl = plan + (size_t)unit * ps;
+  const int per = (nseg + 255) / 256;
+  const int j0 = tid * per, j1 = min(j0 + per, nseg);
+  int mine = 0;
+  for (int j = j0; j < j1; ++j) {
+    const int b = j < nsel ? min(max(sel[j], 0), runs - 1) : resident;
+    mine += max(lenu[b], 0);
+  }
+  const int incl = (int)wave_prefix_sum((unsigned)mine);
+  if (lane == 63) s_wsum[wave] = incl;
+  __syncthreads();
+  int run = incl - mine, total = 0;
+  for (int x = 0; x < 4; ++x) {
+    if (x < wave) run += s_wsum[x];
+    total += s_wsum[x];
+  }
+  for (int j = j0; j < j1; ++j) {
+    const int b = j < nsel ? min(max(sel[j], 0), runs - 1) : resident;
+    run += max(lenu[b], 0);
+    pl[2 + j] = run;
+    pl[nseg + 2 + j] = offu[b];
+  }
+  if (tid == 0) {
+    pl[0] = total;
+    pl[1] = 0;
+  }
 }
 
 // bytes of one key's K row and V row
@@ -845,6 +1246,10 @@ int32_t launch_attn(const AttnParams& p, const LaunchPlan& lp, int G, int dtype,
 size_t attn_workspace_bytes(long long units, int G) {
   return (size_t)SAAP_WS_HEADER_BYTES + (size_t)units * kMaxP * G * (kD + 2) * sizeof(float);
 }
+// ... of the planned attention: one partial result per (workgroup, unit) pair that meets
+size_t planned_workspace_bytes(long long units, int G) {
+  return (size_t)SAAP_WS_HEADER_BYTES + (size_t)(kPlanMaxWgs + units) * G * (kD + 2) * sizeof(float);
+}
 
 }  // namespace saap
 
@@ -861,6 +1266,119 @@ static int32_t check_common(const void* q, const void* K, const void* V, void* o
   const int G = Hq / Hkv;
   if (G != 1 && G != 2 && G != 4 && G != 8) return SAAP_UNSUPPORTED;
   return SAAP_OK;
+}
+
+// ---- visit plans and the attention that follows them ---------------------------------------------
+
+static long long plan_units(int S, int Hq, int Hkv, int mode) { return mode == SAAP_INDEPENDENT ? (long long)S * Hq : (long long)S * Hkv; }
+
+extern "C" size_t saap_visit_plan_bytes(int32_t S, int32_t Hq, int32_t Hkv, int32_t nruns, int32_t mode) {
+  if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || nruns < 0 || nruns > SAAP_MAX_BUCKETS) return 0;
+  if (mode != SAAP_GROUP_SUM && mode != SAAP_INDEPENDENT) return 0;
+  return (size_t)plan_units(S, Hq, Hkv, mode) * plan_stride(nruns) * sizeof(int32_t);
+}
+
+extern "C" int32_t saap_build_visit_plan(const int32_t* selected, const int32_t* off, const int32_t* len,
+                                         int32_t nprobe, int32_t mode, int32_t resident_run, int32_t* plan,
+                                         int32_t S, int32_t Hq, int32_t Hkv, int32_t runs, void* stream) {
+  if (!off || !len || !plan || !aligned16(plan) || (nprobe > 0 && !selected)) return SAAP_INVALID_ARG;
+  if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || runs <= 0) return SAAP_INVALID_ARG;
+  if (mode != SAAP_GROUP_SUM && mode != SAAP_INDEPENDENT) return SAAP_INVALID_ARG;
+  if (nprobe < 0 || resident_run < -1 || resident_run >= runs) return SAAP_INVALID_ARG;
+  const int nseg = nprobe + (resident_run >= 0 ? 1 : 0);
+  if (nseg > runs) return SAAP_INVALID_ARG;
+  if (nseg > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
+  const long long units = plan_units(S, Hq, Hkv, mode);
+  hipLaunchKernelGGL(visit_plan_kernel, dim3((unsigned)units), dim3(256), 0, static_cast<hipStream_t>(stream), selected,
+                     off, len, plan, nprobe, resident_run, runs, plan_stride(nseg), Hq, Hkv,
+                     mode == SAAP_INDEPENDENT ? 1 : 0);
+  return launch_status();
+}
+
+template <typename T>
+static int32_t launch_planned(const PlanParams& p, int G, unsigned grid, size_t lds, hipStream_t stream) {
+#define SAAP_CASE(GG)                                                                                     \
+  case GG: {                                                                                              \
+    auto kern = attn_plan_kernel<T, GG, 512>;                                                             \
+    if (lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                      \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
+      return SAAP_HIP_ERROR;                                                                              \
+    saap_trace_arm();                                                                                     \
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, stream, p);                                      \
+    return launch_status();                                                                               \
+  }
+  switch (G) {
+    SAAP_CASE(1)
+    SAAP_CASE(2)
+    SAAP_CASE(4)
+    SAAP_CASE(8)
+  }
+#undef SAAP_CASE
+  return SAAP_UNSUPPORTED;
+}
+
+static int32_t planned_attention(const void* q, const void* Ksorted, const void* Vsorted, const float* kscale,
+                                 const float* vscale, const int32_t* plan, int32_t nruns, int32_t mode, float scale,
+                                 void* out, int32_t out_dtype, float* lse, int32_t S, int32_t Hq, int32_t Hkv,
+                                 int32_t Ncap, int32_t d, int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
+  int32_t st = check_common(q, Ksorted, Vsorted, out, S, Hq, Hkv, d, dtype, out_dtype, ws);
+  if (st != SAAP_OK) return st;
+  if (!plan || !aligned16(plan)) return SAAP_INVALID_ARG;
+  if (mode != SAAP_GROUP_SUM && mode != SAAP_INDEPENDENT) return SAAP_INVALID_ARG;
+  if (nruns < 0 || Ncap <= 0) return SAAP_INVALID_ARG;
+  if (dtype == kDtypeFp8 && (!kscale || !vscale)) return SAAP_INVALID_ARG;
+  const bool indep = mode == SAAP_INDEPENDENT;
+  const int G = indep ? 1 : Hq / Hkv;
+  const long long units = plan_units(S, Hq, Hkv, mode);
+  const int ps = plan_stride(nruns);
+  // every unit's keys are numbered in one 32-bit range
+  if (units > kPlanMaxUnits || ps > kPlanTableInts || units * (long long)Ncap >= (1ll << 31)) return SAAP_UNSUPPORTED;
+  if (ws_bytes < planned_workspace_bytes(units, G)) return SAAP_WORKSPACE_TOO_SMALL;
+
+  long long W = device_cus();
+  if (W > units * kMaxP) W = units * kMaxP;
+  if (W > kPlanMaxWgs) W = kPlanMaxWgs;
+  W = env_int("SAAP_PLAN_WGS", (int)W);
+  if (W < 1 || W > kPlanMaxWgs) return SAAP_INVALID_ARG;
+  constexpr int NT = 512;
+  PlanParams p{};
+  p.q = q; p.K = Ksorted; p.V = Vsorted; p.plan = plan; p.out = out; p.lse = lse;
+  p.counters = reinterpret_cast<unsigned long long*>(ws);
+  p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
+  p.part_o = p.part_ml + (size_t)(kPlanMaxWgs + units) * G * 2;
+  p.rows = Ncap; p.nseg = nruns; p.ps = ps; p.n_units = (int)units; p.Hq = Hq; p.Hkv = Hkv;
+  p.independent = indep ? 1 : 0; p.out_bf16 = out_dtype == SAAP_BF16;
+  p.all_tables = units * ps <= kPlanTableInts ? 1 : 0;
+  p.q_min = env_int("SAAP_PLAN_QMIN", (NT / 16) * (G == 8 ? 2 : 4));     // one batch of the workgroup
+  p.scale_log2 = scale * kLog2e; p.kscale = kscale; p.vscale = vscale;
+  const size_t ints = (size_t)2 * (units + 1) + 3 + (p.all_tables ? (size_t)units * ps : (size_t)ps);
+  const size_t f_combine = (size_t)(NT / 64) * G * (kD + 2);
+  const size_t f_merge = (size_t)W * G + 2 * G + 8 + (size_t)NT * 4;
+  const size_t lds = ints * sizeof(int) + (f_combine > f_merge ? f_combine : f_merge) * sizeof(float);
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (dtype == kDtypeFp8) return launch_planned<fp8_t>(p, G, (unsigned)W, lds, hs);
+  if (dtype == SAAP_BF16) return launch_planned<bf16_t>(p, G, (unsigned)W, lds, hs);
+  return launch_planned<float>(p, G, (unsigned)W, lds, hs);
+}
+
+extern "C" int32_t saap_planned_decode_attention(const void* q, const void* Ksorted, const void* Vsorted,
+                                                 const int32_t* plan, int32_t nruns, int32_t mode, float scale,
+                                                 void* out, int32_t out_dtype, float* lse, int32_t S, int32_t Hq,
+                                                 int32_t Hkv, int32_t Ncap, int32_t d, int32_t dtype, void* ws,
+                                                 size_t ws_bytes, void* stream) {
+  if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
+  return planned_attention(q, Ksorted, Vsorted, nullptr, nullptr, plan, nruns, mode, scale, out, out_dtype, lse, S, Hq,
+                           Hkv, Ncap, d, dtype, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t saap_planned_decode_attention_fp8(const void* q, const uint8_t* K8, const uint8_t* V8,
+                                                     const float* kscale, const float* vscale, const int32_t* plan,
+                                                     int32_t nruns, int32_t mode, float scale, void* out,
+                                                     int32_t out_dtype, float* lse, int32_t S, int32_t Hq, int32_t Hkv,
+                                                     int32_t Ncap, int32_t d, void* ws, size_t ws_bytes, void* stream) {
+  if (!kscale || !vscale) return SAAP_INVALID_ARG;
+  return planned_attention(q, K8, V8, kscale, vscale, plan, nruns, mode, scale, out, out_dtype, lse, S, Hq, Hkv, Ncap,
+                           d, kDtypeFp8, ws, ws_bytes, stream);
 }
 
 // Attention over the selected runs plus, if resident_run >= 0, one run that is always visited.

@@ -5,6 +5,7 @@
 namespace saap {
 
 size_t attn_workspace_bytes(long long units, int G);
+size_t planned_workspace_bytes(long long units, int G);
 size_t assign_workspace_bytes(long long rows);
 size_t build_workspace_bytes(long long units, int N, int B);
 size_t push_workspace_bytes(long long units, int B);
@@ -76,6 +77,11 @@ extern "C" size_t saap_workspace_bytes(int32_t op, const saap_shape* sh) {
       if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv) return 0;
       const bool indep = sh->mode == SAAP_INDEPENDENT;
       return attn_workspace_bytes(indep ? S * Hq : S * Hkv, indep ? 1 : (int)(Hq / Hkv));
+    }
+    case SAAP_OP_PLANNED_DECODE_ATTENTION: {
+      if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv) return 0;
+      const bool indep = sh->mode == SAAP_INDEPENDENT;
+      return planned_workspace_bytes(indep ? S * Hq : S * Hkv, indep ? 1 : (int)(Hq / Hkv));
     }
     case SAAP_OP_DENSE_DECODE_ATTENTION:
       if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv) return 0;

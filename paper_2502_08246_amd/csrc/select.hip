@@ -40,9 +40,50 @@ __device__ __forceinline__ float group_score(const float* sc, int heads, int B, 
   return g + 0.0f;                                                // -0 -> +0
 }
 
+// What the selection hands to the attention besides the ids: the visit plan of the list (total keys,
+// exclusive prefix of the run lengths, first rows; layout in saap.h).  `sel` holds the nsel ordered ids,
+// `lens` / `offs` the lengths and first rows of the unit's runs; the always-visited run, if any, comes
+// last.  Called by the whole workgroup after a barrier that made `sel` visible.
+struct PlanOut {
+  const int32_t* off;   // [kv units, runs+1] or null: no plan wanted
+  const int32_t* len;   // [kv units, runs]
+  int32_t* plan;        // [units, ps]
+  int runs, resident, ps;
+  unsigned lds_off;     // byte offset of the plan staging area in dynamic LDS: len [runs] | off [runs] | sel [nprobe]
+};
+
+__device__ __forceinline__ void emit_plan(const int* sel, const int* lens, const int* offs, int nsel, int resident,
+                                          int32_t* pl) {
+  __shared__ int s_psum[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nt = blockDim.x, nw = nt >> 6;
+  const int nseg = nsel + (resident >= 0 ? 1 : 0);
+  const int per = (nseg + nt - 1) / nt;
+  const int j0 = tid * per, j1 = min(j0 + per, nseg);
+  int mine = 0;
+  for (int j = j0; j < j1; ++j) mine += max(lens[j < nsel ? sel[j] : resident], 0);
+  const int incl = (int)wave_prefix_sum((unsigned)mine);
+  if (lane == 63) s_psum[wave] = incl;
+  __syncthreads();
+  int run = incl - mine, total = 0;
+  for (int x = 0; x < nw; ++x) {
+    if (x < wave) run += s_psum[x];
+    total += s_psum[x];
+  }
+  for (int j = j0; j < j1; ++j) {
+    const int b = j < nsel ? sel[j] : resident;
+    run += max(lens[b], 0);
+    pl[2 + j] = run;
+    pl[nseg + 2 + j] = offs[b];
+  }
+  if (tid == 0) {
+    pl[0] = total;
+    pl[1] = 0;
+  }
+}
+
 __global__ void __launch_bounds__(1024)
 select_kernel(const float* __restrict__ scores, int32_t* __restrict__ selected, int Hq, int Hkv, int B,
-              int nprobe, int independent, int n_pow2) {
+              int nprobe, int independent, int n_pow2, PlanOut po) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem);
   const int unit = blockIdx.x;
@@ -81,6 +122,16 @@ select_kernel(const float* __restrict__ scores, int32_t* __restrict__ selected, 
 
   for (int j = threadIdx.x; j < nprobe; j += blockDim.x)
     selected[(size_t)unit * nprobe + j] = (int32_t)(0xFFFFFFFFu - (unsigned)(keys[j] & 0xFFFFFFFFull));
+  if (po.off) {
+    // the ordered ids replace the sorted keys in LDS; lengths and first rows come from memory (this
+    // kernel serves lists that take most of the buckets, where the attention dwarfs the selection)
+    int* ids = reinterpret_cast<int*>(keys + n_pow2);
+    for (int j = threadIdx.x; j < nprobe; j += blockDim.x) ids[j] = (int)(0xFFFFFFFFu - (unsigned)(keys[j] & 0xFFFFFFFFull));
+    __syncthreads();
+    const int kvu = independent ? (unit / Hq) * Hkv + (unit % Hq) / G : unit;
+    emit_plan(ids, po.len + (size_t)kvu * po.runs, po.off + (size_t)kvu * (po.runs + 1), nprobe, po.resident,
+              po.plan + (size_t)unit * po.ps);
+  }
 }
 
 
@@ -166,7 +217,7 @@ __device__ __forceinline__ void softmax_group_scores(const float* __restrict__ z
 template <int EPT, bool LOGITS>
 __global__ void __launch_bounds__(1024)
 select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs, int32_t* __restrict__ selected,
-                    int Hq, int Hkv, int B, int nprobe, int independent, int n_sort, int cap) {
+                    int Hq, int Hkv, int B, int nprobe, int independent, int n_sort, int cap, PlanOut po) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned long long* sortbuf = reinterpret_cast<unsigned long long*>(smem);   // [cap] candidates, cap >= n_sort
   unsigned* eqbits = reinterpret_cast<unsigned*>(sortbuf + cap);               // [B/32 + 1]
@@ -180,6 +231,23 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
   const float* sc = scores + row0 * B;
 
   SAAP_TRACE(0);
+  // visit plan: the unit's run lengths and first rows are fetched in the same memory round trip as the
+  // scores and parked in LDS until the ordered list exists
+  int* s_len = reinterpret_cast<int*>(smem + po.lds_off);       // [runs]
+  int* s_off = s_len + po.runs;                                 // [runs]
+  int* s_sel = s_off + po.runs;                                 // [nprobe]
+  int lv[EPT + 1], ov[EPT + 1];
+  if (po.off) {
+    const int kvu = independent ? (unit / Hq) * Hkv + (unit % Hq) / G : unit;
+    const int32_t* lenu = po.len + (size_t)kvu * po.runs;
+    const int32_t* offu = po.off + (size_t)kvu * (po.runs + 1);
+#pragma unroll
+    for (int e = 0; e <= EPT; ++e) {
+      const int b = min(tid + e * nt, po.runs - 1);
+      lv[e] = lenu[b];
+      ov[e] = offu[b];
+    }
+  }
   unsigned key[EPT];
   {
     float gs[EPT];
@@ -201,6 +269,16 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
     }
 #pragma unroll
     for (int e = 0; e < EPT; ++e) key[e] = tid + e * nt < B ? float_order_key(gs[e]) : 0u;   // 0 sorts below every finite score
+  }
+  if (po.off) {
+#pragma unroll
+    for (int e = 0; e <= EPT; ++e) {
+      const int b = tid + e * nt;
+      if (b < po.runs) {
+        s_len[b] = lv[e];
+        s_off[b] = ov[e];
+      }
+    }
   }
   if (tid == 0) { s_cnt = 0u; s_neq = 0u; s_and = 0xFFFFFFFFu; s_or = 0u; }
   for (int i = tid; i < cap; i += nt) sortbuf[i] = 0ull;
@@ -330,6 +408,15 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
   }
   SAAP_TRACE(3);
   int32_t* out = selected + (size_t)unit * nprobe;
+  auto put = [&](unsigned place, int32_t id) {
+    out[place] = id;
+    if (po.off) s_sel[place] = id;
+  };
+  auto finish = [&]() {
+    if (!po.off) return;
+    __syncthreads();
+    emit_plan(s_sel, s_len, s_off, nprobe, po.resident, po.plan + (size_t)unit * po.ps);
+  };
   if (n_sort <= kRankSortMax && n_cand > kBucketRankMin) {
     // Long candidate lists: counting every larger key costs n^2 comparisons on one compute unit.
     // Instead the candidates are dealt into 256 buckets by the leading bits of (score image - lowest
@@ -380,9 +467,10 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
       const unsigned first = bbase[bk], n = cnt[bk];
       unsigned place = first;
       for (unsigned j = first; j < first + n; ++j) place += tmp[j] > mine ? 1u : 0u;
-      if (place < (unsigned)nprobe) out[place] = (int32_t)(0xFFFFFFFFu - (unsigned)(mine & 0xFFFFFFFFull));
+      if (place < (unsigned)nprobe) put(place, (int32_t)(0xFFFFFFFFu - (unsigned)(mine & 0xFFFFFFFFull)));
     }
     SAAP_TRACE(4);
+    finish();
     return;
   }
   if (n_sort <= kRankSortMax) {
@@ -406,8 +494,9 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
     }
     __syncthreads();
     for (int i = tid; i < n_cand; i += nt)
-      if (rank[i] < (unsigned)nprobe) out[rank[i]] = (int32_t)(0xFFFFFFFFu - (unsigned)(sortbuf[i] & 0xFFFFFFFFull));
+      if (rank[i] < (unsigned)nprobe) put(rank[i], (int32_t)(0xFFFFFFFFu - (unsigned)(sortbuf[i] & 0xFFFFFFFFull)));
     SAAP_TRACE(4);
+    finish();
     return;
   }
   for (int k = 2; k <= n_sort; k <<= 1) {
@@ -426,7 +515,8 @@ select_radix_kernel(const float* __restrict__ scores, float* __restrict__ probs,
       __syncthreads();
     }
   }
-  for (int j = tid; j < nprobe; j += nt) out[j] = (int32_t)(0xFFFFFFFFu - (unsigned)(sortbuf[j] & 0xFFFFFFFFull));
+  for (int j = tid; j < nprobe; j += nt) put((unsigned)j, (int32_t)(0xFFFFFFFFu - (unsigned)(sortbuf[j] & 0xFFFFFFFFull)));
+  finish();
 }
 
 }  // namespace
@@ -437,7 +527,8 @@ using namespace saap;
 // Shared body: `logits` false selects from `scores` as given; true applies the row softmax first
 // (and writes the probabilities to `probs` if it is not null).
 static int32_t select_impl(const float* scores, bool logits, float* probs, int32_t* selected, int32_t S,
-                           int32_t Hq, int32_t Hkv, int32_t B, int32_t nprobe, int32_t mode, void* stream) {
+                           int32_t Hq, int32_t Hkv, int32_t B, int32_t nprobe, int32_t mode, void* stream,
+                           PlanOut po = PlanOut{}) {
   if (!scores || !aligned16(scores) || !aligned16(probs)) return SAAP_INVALID_ARG;
   if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || B <= 0) return SAAP_INVALID_ARG;
   if (mode != SAAP_GROUP_SUM && mode != SAAP_INDEPENDENT) return SAAP_INVALID_ARG;
@@ -447,7 +538,9 @@ static int32_t select_impl(const float* scores, bool logits, float* probs, int32
     const int G = Hq / Hkv;
     if (G != 1 && G != 2 && G != 4 && G != 8) return SAAP_UNSUPPORTED;
   }
-  if (nprobe == 0) return SAAP_OK;
+  if (nprobe == 0)
+    return po.off ? saap_build_visit_plan(nullptr, po.off, po.len, 0, mode, po.resident, po.plan, S, Hq, Hkv, po.runs, stream)
+                  : SAAP_OK;
   if (!selected || !aligned16(selected)) return SAAP_INVALID_ARG;
   int n_pow2 = 2;
   while (n_pow2 < B) n_pow2 <<= 1;
@@ -473,18 +566,30 @@ static int32_t select_impl(const float* scores, bool logits, float* probs, int32
     // lists), the padded list itself where a bitonic network does the ordering
     const int cap = n_sort <= kRankSortMax ? (n_sort <= 128 ? 2 * n_sort : n_sort + 128) : n_sort;
     // sortbuf [cap] | bitmap [B/32 + 1, padded to 256 words and to an even count] | rank [cap] | bucketed copy [cap]
-    const size_t lds = (size_t)cap * sizeof(unsigned long long) + (size_t)bitmap_words(B) * sizeof(unsigned) +
-                       (n_sort <= kRankSortMax ? (size_t)cap * (sizeof(unsigned) + sizeof(unsigned long long)) : 0);
+    size_t lds = (size_t)cap * sizeof(unsigned long long) + (size_t)bitmap_words(B) * sizeof(unsigned) +
+                 (n_sort <= kRankSortMax ? (size_t)cap * (sizeof(unsigned) + sizeof(unsigned long long)) : 0);
+    if (po.off) {
+      lds = (lds + 15) & ~(size_t)15;
+      po.lds_off = (unsigned)lds;
+      lds += (size_t)(2 * po.runs + nprobe) * sizeof(int);
+    }
+    const bool big_lds = lds > 48 * 1024;
     saap_trace_arm();
     const dim3 grid((unsigned)units), block((unsigned)threads);
+#define SAAP_SELECT_LAUNCH(E, L)                                                                             \
+  do {                                                                                                       \
+    auto kern = select_radix_kernel<E, L>;                                                                   \
+    if (big_lds && hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                  \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)  \
+      return SAAP_HIP_ERROR;                                                                                 \
+    hipLaunchKernelGGL(kern, grid, block, lds, hs, scores, probs, selected, Hq, Hkv, B, nprobe, indep, n_sort, cap, po); \
+  } while (0)
 #define SAAP_SELECT_CASE(E)                                                                                  \
   case E:                                                                                                    \
     if (logits)                                                                                              \
-      hipLaunchKernelGGL((select_radix_kernel<E, true>), grid, block, lds, hs, scores, probs, selected, Hq, Hkv, B, \
-                         nprobe, indep, n_sort, cap);                                                        \
+      SAAP_SELECT_LAUNCH(E, true);                                                                           \
     else                                                                                                     \
-      hipLaunchKernelGGL((select_radix_kernel<E, false>), grid, block, lds, hs, scores, probs, selected, Hq, Hkv, B, \
-                         nprobe, indep, n_sort, cap);                                                        \
+      SAAP_SELECT_LAUNCH(E, false);                                                                          \
     break
     switch (ept) {
       SAAP_SELECT_CASE(1);
@@ -493,19 +598,20 @@ static int32_t select_impl(const float* scores, bool logits, float* probs, int32
       default: SAAP_SELECT_CASE(8);
     }
 #undef SAAP_SELECT_CASE
+#undef SAAP_SELECT_LAUNCH
     return launch_status();
   }
   int threads = n_pow2 / 2;
   if (threads < 64) threads = 64;
   if (threads > 1024) threads = 1024;
-  const size_t lds = (size_t)n_pow2 * sizeof(unsigned long long);
+  const size_t lds = (size_t)n_pow2 * sizeof(unsigned long long) + (po.off ? (size_t)nprobe * sizeof(int) : 0);
   if (lds > 48 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return SAAP_HIP_ERROR;
   }
   hipLaunchKernelGGL(select_kernel, dim3((unsigned)units), dim3((unsigned)threads), lds, hs, scores, selected, Hq,
-                     Hkv, B, nprobe, indep, n_pow2);
+                     Hkv, B, nprobe, indep, n_pow2, po);
   return launch_status();
 }
 
@@ -525,4 +631,24 @@ extern "C" int32_t saap_select_buckets_from_logits(const float* logits, float* p
   (void)ws_bytes;
   if (!logits) return SAAP_INVALID_ARG;
   return select_impl(logits, true, probs, selected, S, Hq, Hkv, B, nprobe, mode, stream);
+}
+
+extern "C" int32_t saap_select_buckets_planned(const float* scores, int32_t input_kind, float* probs,
+                                               const int32_t* off, const int32_t* len, int32_t resident_run,
+                                               int32_t* selected, int32_t* plan, int32_t S, int32_t Hq,
+                                               int32_t Hkv, int32_t B, int32_t nprobe, int32_t mode, void* ws,
+                                               size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  if (!off || !len || !plan || !aligned16(plan)) return SAAP_INVALID_ARG;
+  if (input_kind != SAAP_PROBS && input_kind != SAAP_LOGITS) return SAAP_INVALID_ARG;
+  if (resident_run != -1 && resident_run != B) return SAAP_INVALID_ARG;
+  if (nprobe + (resident_run >= 0 ? 1 : 0) > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
+  PlanOut po{};
+  po.off = off; po.len = len; po.plan = plan;
+  po.runs = B + (resident_run >= 0 ? 1 : 0);
+  po.resident = resident_run;
+  po.ps = (2 * (nprobe + (resident_run >= 0 ? 1 : 0)) + 2 + 3) & ~3;
+  return select_impl(scores, input_kind == SAAP_LOGITS, input_kind == SAAP_LOGITS ? probs : nullptr, selected, S, Hq,
+                     Hkv, B, nprobe, mode, stream, po);
 }
