@@ -58,6 +58,11 @@ def parse():
     ap.add_argument("--layers", type=int, default=1,
                     help="also time a decode step through this many layers, each with its own synthetic cache, "
                          "centroids, classifier and index (e.g. 32 with --workload cfg4_layer_262k)")
+    ap.add_argument("--path", choices=["plan", "list"], default="list",
+                    help="list (default): the attention reads the selected lists itself, one team of workgroups per "
+                         "list; plan: the selection writes the visit plan and the attention deals all lists' keys to "
+                         "the workgroups in equal shares (slower on the benchmark workloads, robust to lists of "
+                         "very different sizes)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of 256 MiB (reference for the HBM byte counters)")
     return ap.parse_args()
@@ -186,11 +191,21 @@ def main():
     def classify(i):
         saap.classify_queries(xq[i % T], W1, b1, W2, b2, cfg.Hkv, output_kind=saap.LOGITS, out=scores)
 
+    planned = args.path == "plan"
+    plan = torch.empty(saap.visit_plan_ints(cfg.S, cfg.Hq, cfg.Hkv, cfg.nprobe), dtype=torch.int32, device=dev)
+    plan_sets = torch.empty(T, plan.numel(), dtype=torch.int32, device=dev)
+
     def select(i):
-        saap.select_buckets_from_logits(scores, cfg.Hkv, cfg.nprobe, out=sel)
+        if planned:
+            saap.select_buckets_planned(scores, off, ln, cfg.Hkv, cfg.nprobe, input_kind=saap.LOGITS, out=sel, plan=plan)
+        else:
+            saap.select_buckets_from_logits(scores, cfg.Hkv, cfg.nprobe, out=sel)
 
     def attend(i):
-        saap.sparse_decode_attention(q[i % T], Ks, Vs, off, ln, sel, scale, out=out, lse=lse)
+        if planned:
+            saap.planned_decode_attention(q[i % T], Ks, Vs, plan, cfg.nprobe, scale, out=out, lse=lse)
+        else:
+            saap.sparse_decode_attention(q[i % T], Ks, Vs, off, ln, sel, scale, out=out, lse=lse)
 
     if with_append:
         # the T tokens whose keys get appended, drawn like the cache; replays append the same T keys
@@ -219,7 +234,8 @@ def main():
     # selections of every query set (for the byte accounting and the per-kernel loops)
     for t in range(T):
         classify(t)
-        saap.select_buckets_from_logits(scores, cfg.Hkv, cfg.nprobe, out=sel_sets[t])
+        saap.select_buckets_planned(scores, off, ln, cfg.Hkv, cfg.nprobe, input_kind=saap.LOGITS, out=sel_sets[t],
+                                    plan=plan_sets[t])
     torch.cuda.synchronize()
     keys_per_set = torch.gather(ln.unsqueeze(0).expand(T, -1, -1, -1).to(torch.int64), 3, sel_sets.to(torch.int64)).sum(dim=(1, 2, 3))
     keys_touched = float(keys_per_set.to(torch.float64).mean().item())   # per step (all sequences, all KV heads)
@@ -245,7 +261,10 @@ def main():
 
     # ---------------------------------------------------------------- per-call timings (events, same stream)
     def attend_set(i):
-        saap.sparse_decode_attention(q[i % T], Ks, Vs, off, ln, sel_sets[i % T], scale, out=out, lse=lse)
+        if planned:
+            saap.planned_decode_attention(q[i % T], Ks, Vs, plan_sets[i % T], cfg.nprobe, scale, out=out, lse=lse)
+        else:
+            saap.sparse_decode_attention(q[i % T], Ks, Vs, off, ln, sel_sets[i % T], scale, out=out, lse=lse)
 
     def dense(i):
         saap.dense_decode_attention(q[i % T], Ks, Vs, scale, off=off, ln=ln, out=out, lse=lse)

@@ -37,7 +37,9 @@ struct AttnParams {
   float* lse;             // [S,Hq] or null
   float* part_o;          // [units, P, G, d]
   float* part_ml;         // [units, P, G, 2]
-  unsigned long long* counters;   // [units] arrivals, eight 8-bit fields (one per XCD); zero on entry and on exit
+  unsigned long long* counters;   // [units * cstride] arrivals, eight 8-bit fields (one per XCD); zero on entry and on exit
+  int cstride;            // 8-byte words between the counters of two units (16: a cache line each, so that the arrivals
+                          // of different units do not queue at one line)
   long long rows;         // rows per kv unit
   int nseg;               // runs visited per unit (selected buckets + the always-visited run); list mode only
   int nsel;               // entries per unit in `selected` (the first nsel runs of the list)
@@ -284,7 +286,43 @@ __device__ __forceinline__ void workgroup_combine(float* scratch, float m, float
 // workgroup's threads form NT/kCols groups that take the partials round-robin, eight loads in flight
 // each, while one wave per head turns the partial maxima into weights.  `scratch` holds
 // P*G + 2G + 4 floats and NT float4.
-template <int G, int NT>
+// Loads of partial results that other XCDs may have written: with COHERENT they are agent-scope atomic
+// loads (two 8-byte loads per float4), which look past this XCD's L2, where a line of the workspace may
+// survive from an earlier launch.  Without it the caller has made its caches safe to read.
+template <bool COHERENT>
+__device__ __forceinline__ float2 merge_load2(const float2* p) {
+  if constexpr (COHERENT) {
+    const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
+  } else {
+    return *p;
+  }
+}
+typedef float f32x4_asm __attribute__((ext_vector_type(4)));
+// Eight 16-byte loads at agent scope (sc1: past this XCD's L2), issued back to back; entries with on[k]
+// false load the first address and are zeroed.  The loads are written in assembly because the compiler
+// offers atomic loads of at most 8 bytes; the wait that follows them names every destination, so no use
+// of the values can move before it.
+template <bool COHERENT>
+__device__ __forceinline__ void merge_load4x8(const float4* const (&ptr)[8], const bool (&on)[8], float4 (&v)[8]) {
+  if constexpr (COHERENT) {
+    f32x4_asm r[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(r[k]) : "v"(ptr[k]) : "memory");
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7])
+                 :
+                 : "memory");
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = on[k] ? make_float4(r[k].x, r[k].y, r[k].z, r[k].w) : make_float4(0.f, 0.f, 0.f, 0.f);
+  } else {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = on[k] ? *ptr[k] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+}
+
+template <int G, int NT, bool COHERENT = false>
 __device__ __forceinline__ void final_merge(const float* part_o, const float* part_ml, size_t slot0, int P, int qrow0,
                                             float vs, void* out, int out_bf16, float* lse, float* scratch) {
   constexpr int nw = NT / 64;
@@ -308,24 +346,31 @@ __device__ __forceinline__ void final_merge(const float* part_o, const float* pa
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
     const int pi = lane + 64 * k;
-    ml[k] = pi < P ? pml[(size_t)pi * G + g_w] : make_float2(kNegBig, 0.f);
+    ml[k] = pi < P ? merge_load2<COHERENT>(pml + (size_t)pi * G + g_w) : make_float2(kNegBig, 0.f);
   }
   float4 v[kInFlight];
+  auto load_round = [&](int first) {
+    const float4* ptr[kInFlight];
+    bool on[kInFlight];
 #pragma unroll
-  for (int k = 0; k < kInFlight; ++k) {
-    const int pi = pgrp + k * n_groups;
-    v[k] = pi < P ? po[(size_t)pi * kCols] : make_float4(0.f, 0.f, 0.f, 0.f);
-  }
+    for (int k = 0; k < kInFlight; ++k) {
+      const int pi = first + k * n_groups;
+      on[k] = pi < P;
+      ptr[k] = po + (size_t)(on[k] ? pi : 0) * kCols;
+    }
+    merge_load4x8<COHERENT>(ptr, on, v);
+  };
+  if constexpr (!COHERENT) load_round(pgrp);     // in flight while the weights are made (the assembly loads wait at once)
   for (int g = wave; g < G; g += nw) {
     if (g != g_w) {
 #pragma unroll
       for (int k = 0; k < 2; ++k) {
         const int pi = lane + 64 * k;
-        ml[k] = pi < P ? pml[(size_t)pi * G + g] : make_float2(kNegBig, 0.f);
+        ml[k] = pi < P ? merge_load2<COHERENT>(pml + (size_t)pi * G + g) : make_float2(kNegBig, 0.f);
       }
     }
     float mx = fmaxf(ml[0].x, ml[1].x);
-    for (int pi = lane + 128; pi < P; pi += 64) mx = fmaxf(mx, pml[(size_t)pi * G + g].x);   // more than 128 partials
+    for (int pi = lane + 128; pi < P; pi += 64) mx = fmaxf(mx, merge_load2<COHERENT>(pml + (size_t)pi * G + g).x);   // more than 128 partials
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
     float lsum = 0.f;
@@ -337,7 +382,7 @@ __device__ __forceinline__ void final_merge(const float* part_o, const float* pa
       lsum = fmaf(w, ml[k].y, lsum);
     }
     for (int pi = lane + 128; pi < P; pi += 64) {
-      const float2 t = pml[(size_t)pi * G + g];
+      const float2 t = merge_load2<COHERENT>(pml + (size_t)pi * G + g);
       const float w = fast_exp2(t.x - mx);
       s_w[pi * G + g] = w;
       lsum = fmaf(w, t.y, lsum);
@@ -349,6 +394,7 @@ __device__ __forceinline__ void final_merge(const float* part_o, const float* pa
       s_L[g] = lsum;
     }
   }
+  if constexpr (COHERENT) load_round(pgrp);
   __syncthreads();
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int p0 = pgrp;; p0 += n_groups * kInFlight) {
@@ -365,11 +411,7 @@ __device__ __forceinline__ void final_merge(const float* part_o, const float* pa
     }
     const int nxt = p0 + n_groups * kInFlight;
     if (nxt - pgrp >= P) break;     // uniform over the workgroup: depends on P and n_groups only
-#pragma unroll
-    for (int k = 0; k < kInFlight; ++k) {
-      const int pi = nxt + k * n_groups;
-      v[k] = pi < P ? po[(size_t)pi * kCols] : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
+    load_round(nxt);
   }
   if (pgrp < n_groups) s_acc[pgrp * kCols + colx] = acc;
   __syncthreads();
@@ -720,7 +762,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     // The arrival counter has one 8-bit field per XCD (P <= 128 fits): besides "am I last" it
     // tells the last workgroup whether every partial was written through its own XCD's L2.
     const unsigned xcc = (unsigned)__builtin_amdgcn_s_getreg(20 | (3 << 11)) & 7u;   // HW_REG_XCC_ID[3:0]
-    const unsigned long long old = __hip_atomic_fetch_add(&p.counters[unit], 1ull << (8 * xcc), __ATOMIC_RELAXED,
+    const unsigned long long old = __hip_atomic_fetch_add(&p.counters[(size_t)unit * p.cstride], 1ull << (8 * xcc), __ATOMIC_RELAXED,
                                                           __HIP_MEMORY_SCOPE_AGENT);
     unsigned total = 0;
 #pragma unroll
@@ -743,7 +785,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   final_merge<G, NT>(p.part_o, p.part_ml, (size_t)unit * p.P, p.P, qrow0, vs, p.out, p.out_bf16, p.lse,
                      reinterpret_cast<float*>(smem));
   SAAP_TRACE(8);
-  if (tid == 0) __hip_atomic_store(&p.counters[unit], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid == 0) __hip_atomic_store(&p.counters[(size_t)unit * p.cstride], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 
@@ -757,7 +799,8 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
 // the units are (Section 5 "On GPU" notes that one block per bucket makes the largest bucket set the
 // run time; with one team of workgroups per unit the largest unit does).  A workgroup whose share
 // crosses a unit boundary finishes one unit (partial result, Algorithm 2) and goes on with the next;
-// a unit is merged by the last of the workgroups that hold a piece of it.
+// a unit is merged by the last of the workgroups that hold a piece of it.  Inside a workgroup the waves
+// take batches of keys from the piece's counter, so a wave that memory serves late takes fewer.
 //
 // Plan layout per unit (stride ps = 2*nseg + 2 rounded up to a multiple of 4 ints):
 //   [0] T_u | [1 .. nseg+1] pre[0..nseg], pre[0] = 0, pre[j+1] = pre[j] + length of run j | [nseg+2 ..] first row of run j
@@ -770,7 +813,8 @@ struct PlanParams {
   float* lse;             // [S,Hq] or null
   float* part_o;          // [slots, G, d]
   float* part_ml;         // [slots, G, 2]
-  unsigned long long* counters;   // [units] arrivals; zero on entry and on exit
+  unsigned long long* counters;   // [units * cstride] arrivals; zero on entry and on exit
+  int cstride;            // 8-byte words between the counters of two units
   long long rows;         // rows per kv unit
   int nseg;               // runs per unit in the plan
   int ps;                 // ints per unit in the plan
@@ -780,6 +824,7 @@ struct PlanParams {
   int out_bf16;
   int all_tables;         // every unit's table is copied to LDS at the start (one memory round trip)
   int q_min;              // least number of keys per workgroup
+  int piece_cost;         // what starting a piece of a unit costs a workgroup, in keys it could have streamed instead
   float scale_log2;       // scale * log2(e)
   const float* kscale;    // 8-bit cache: [kv units] scale of the K codes, else null
   const float* vscale;
@@ -790,6 +835,28 @@ constexpr int kPlanTableInts = 16384;   // all units' tables fit LDS up to this 
 
 __host__ __device__ constexpr int plan_stride(int nseg) { return (2 * nseg + 2 + 3) & ~3; }
 
+// Pins a loaded value in its registers at this point of the program, so that the load is issued here
+// and not moved into the branch that consumes it (where each load would wait for the one before).
+__device__ __forceinline__ void issue_here(int4& v) { asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w)); }
+
+// largest j in [0, n) with a[j] <= v  (a non-decreasing, a[0] <= v), found by the whole wave at once: every
+// lane looks at one entry (every step-th one while more than 64 are left) and a ballot counts the entries
+// not above v, which form a prefix.  One or two LDS round trips where a binary search takes six to thirteen.
+// All lanes must call it with the same arguments.
+__device__ __forceinline__ int wave_last_not_above(const int* a, int n, int v, int lane) {
+  int lo = 0, len = n;
+  while (len > 64) {
+    const int step = (len + 63) >> 6;
+    const int idx = lo + lane * step;
+    const bool le = idx < lo + len && a[idx] <= v;
+    const int k = __popcll(__ballot(le)) - 1;
+    lo += k * step;
+    len = min(step, len - k * step);
+  }
+  const bool le = lane < len && a[lo + lane] <= v;
+  return lo + __popcll(__ballot(le)) - 1;
+}
+
 // largest j in [lo, hi) with a[j] <= v  (a non-decreasing, a[lo] <= v)
 __device__ __forceinline__ int last_not_above(const int* a, int lo, int hi, int v) {
   while (hi - lo > 1) {
@@ -799,45 +866,95 @@ __device__ __forceinline__ int last_not_above(const int* a, int lo, int hi, int 
   return lo;
 }
 
+constexpr int kPieceSlots = 2;          // pieces of one workgroup that may be open at the same time
+
+// The waves of a workgroup deposit the result of their keys of a piece in LDS; the last one to do so
+// combines them (Algorithm 2 over the nw partial results, two outputs per lane and head: features `lane`
+// and `lane + 64`).  emit(g, e, M, L, O) receives the merged values.  Called by one wave.
+template <int G, int nw, typename F>
+__device__ __forceinline__ void combine_deposits(const float* area, int lane, F emit) {
+  const float* w_o = area;                                // [nw][G][d] unnormalised outputs
+  const float* w_m = w_o + nw * G * kD;                   // [nw][G] maxima
+  const float* w_l = w_m + nw * G;                        // [nw][G] sums of weights
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float wj[nw];
+    float M = kNegBig;
+#pragma unroll
+    for (int j = 0; j < nw; ++j) {
+      wj[j] = w_m[j * G + g];
+      M = fmaxf(M, wj[j]);
+    }
+    float L = 0.f, o0 = 0.f, o1 = 0.f;
+#pragma unroll
+    for (int j = 0; j < nw; ++j) {
+      const float w = fast_exp2(wj[j] - M);
+      L = fmaf(w, w_l[j * G + g], L);
+      o0 = fmaf(w, w_o[(j * G + g) * kD + lane], o0);
+      o1 = fmaf(w, w_o[(j * G + g) * kD + 64 + lane], o1);
+    }
+    emit(g, lane, M, L, o0);
+    emit(g, lane + 64, M, L, o1);
+  }
+}
+
 template <typename T, int G, int NT>
 __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_wsum[2][16];
-  __shared__ int s_last;
+  __shared__ int s_next[kPieceSlots];     // next wave batch of the piece in the slot
+  __shared__ int s_done[kPieceSlots];     // waves that have deposited their result of it
+  __shared__ int s_gen[kPieceSlots];      // pieces the slot has served
+  __shared__ int s_npend;
+  __shared__ int s_pend[2][4];            // units this workgroup merges at the end: unit, first slot, partials, kind
 
   constexpr int nw = NT / 64;
   constexpr int KB = G == 8 ? 2 : 4;            // keys a key processor has in flight per batch
+  constexpr int WB = 4 * KB;                    // keys of a wave batch: KB consecutive keys for each of its 4 processors
   constexpr bool kPrefetch = sizeof(T) <= 2;    // fp32 rows are too wide to double-buffer
   constexpr bool kFp8 = sizeof(T) == 1;
-  constexpr int kTabLoads = kPlanTableInts / 4 / NT;   // 16-byte loads per thread that cover the largest table
+  constexpr int kDepositFloats = nw * G * (kD + 2);
   typedef typename DotType<T>::type TQ;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane & 15, grp = lane >> 4;
-  constexpr int NG = nw * 4;            // key processors in the workgroup
-  constexpr int chunk = NG * KB;        // keys the workgroup consumes per batch
-  const int kp = wave * 4 + grp;
-  const int U = p.n_units, W = (int)gridDim.x, w = (int)blockIdx.x;
+  const int U = p.n_units, W = (int)gridDim.x;
+  // Neighbouring shares go to one XCD (workgroups are handed to the XCDs in turn), so that most units are
+  // merged from partial results that never left that XCD's L2.  Only speed depends on it.
+  const int w = (W & 7) == 0 ? (int)(blockIdx.x & 7) * (W >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+  // The global range counts, before the keys of every unit, `F` positions that nobody reads: what a piece
+  // costs its workgroup besides streaming.  A workgroup whose share crosses into another unit therefore
+  // streams fewer keys than one that stays inside a unit, and both finish together.
+  const int F = p.piece_cost;
   SAAP_TRACE(0);
 
-  int* s_ustart = reinterpret_cast<int*>(smem);           // [U+1] first key of each unit in the global range
+  int* s_ustart = reinterpret_cast<int*>(smem);           // [U+1] start of each unit in the global range
   int* s_urank = s_ustart + (U + 1);                      // [U+1] units with keys before each unit
   int* s_tab = s_urank + (U + 1) + ((4 - (2 * (U + 1)) % 4) % 4);   // [U*ps] or [ps] plan tables (16-byte aligned)
-  float* scratch = reinterpret_cast<float*>(s_tab + (p.all_tables ? U * p.ps : p.ps));
+  float* scratch = reinterpret_cast<float*>(s_tab + (p.all_tables ? U * p.ps : p.ps));   // deposits; merge scratch at the end
 
-  // ---- totals of all units -> ranges of the units in the global key range
+  if (tid < kPieceSlots) {
+    s_next[tid] = 0;
+    s_done[tid] = 0;
+    s_gen[tid] = 0;
+  }
+  if (tid == 0) s_npend = 0;
+
+  // ---- totals of all units -> ranges of the units in the global range
   if (p.all_tables) {
+    // every load of a round goes out before the first store waits for one: unconditional, the index clamped
     const int n4 = U * p.ps / 4;
     const int4* src = reinterpret_cast<const int4*>(p.plan);
-    int4 r[kTabLoads];
+    for (int i0 = 0; i0 < n4; i0 += 8 * NT) {
+      int4 r[8];
 #pragma unroll
-    for (int k = 0; k < kTabLoads; ++k) {
-      const int i = tid + k * NT;
-      if (i < n4) r[k] = src[i];
-    }
+      for (int k = 0; k < 8; ++k) r[k] = src[min(i0 + tid + k * NT, n4 - 1)];
 #pragma unroll
-    for (int k = 0; k < kTabLoads; ++k) {
-      const int i = tid + k * NT;
-      if (i < n4) reinterpret_cast<int4*>(s_tab)[i] = r[k];
+      for (int k = 0; k < 8; ++k) issue_here(r[k]);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int i = i0 + tid + k * NT;
+        if (i < n4) reinterpret_cast<int4*>(s_tab)[i] = r[k];
+      }
     }
     __syncthreads();
   }
@@ -848,12 +965,14 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
 #pragma unroll
     for (int k = 0; k < kPlanMaxUnits / NT; ++k) {
       const int u = u0 + k;
-      tv[k] = (k < per && u < U) ? (p.all_tables ? s_tab[u * p.ps] : p.plan[(size_t)u * p.ps]) : 0;
+      const int uc = min(u, U - 1);
+      tv[k] = p.all_tables ? s_tab[uc * p.ps] : p.plan[(size_t)uc * p.ps];
+      if (k >= per || u >= U) tv[k] = 0;
     }
     int mine = 0, cnt = 0;
 #pragma unroll
     for (int k = 0; k < kPlanMaxUnits / NT; ++k) {
-      tv[k] = max(tv[k], 0);
+      tv[k] = tv[k] > 0 ? tv[k] + F : 0;                  // extent in the global range
       mine += tv[k];
       cnt += tv[k] > 0 ? 1 : 0;
     }
@@ -890,7 +1009,7 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
     __syncthreads();
   }
   const int t_all = s_ustart[U];
-  const int Q = max((t_all + W - 1) / W, p.q_min);        // keys per workgroup
+  const int Q = max((t_all + W - 1) / W, p.q_min);        // share of a workgroup
   const long long k0 = (long long)w * Q;
   const int k1 = (int)min((long long)t_all, k0 + Q);
 
@@ -907,13 +1026,21 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
   if (k0 >= t_all) return;
   SAAP_TRACE(1);
 
-  int u = last_not_above(s_ustart, 0, U, (int)k0);        // the unit that holds key k0 (it has keys)
+  // ---- the pieces of my share, one unit after the other.  The waves go through them on their own:
+  // inside a piece every wave takes the next batch of WB keys from the piece's counter until none is left
+  // (a wave that was held up simply takes fewer), deposits its result in the slot's LDS area and moves on;
+  // whoever deposits last combines the deposits and sends the piece's result off.  No workgroup barrier.
+  int piece = 0;
+  int u = wave_last_not_above(s_ustart, U, (int)k0, lane);   // the unit that holds position k0 (it has keys)
   for (int ks = (int)k0; ks < k1; ++u) {
     const int us = s_ustart[u], ue = s_ustart[u + 1];
     if (ue == us) continue;
-    // ---- my piece of unit u: its keys [a, b)
-    const int a = ks - us, b = min(k1, ue) - us;
+    const int rs = us + F;                                // the unit's keys follow its F unread positions
+    const int a = max(ks, rs) - rs, b = min(k1, ue) - rs; // my piece of unit u: its keys [a, b)
     ks = ue;
+    if (b <= a) continue;                                 // my share ends before the unit's first key
+    const int slot = piece % kPieceSlots, use = piece / kPieceSlots;
+    ++piece;
     int kvu, qrow0;
     if (p.independent) {
       const int s = u / p.Hq, hq = u % p.Hq;
@@ -933,30 +1060,46 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
       scale_log2 *= p.kscale[kvu];
       vs = p.vscale[kvu];
     }
+    SAAP_TRACE(12);
     const int* tab = s_tab + u * p.ps;
     if (!p.all_tables) {
-      // one unit's table at a time
+      // the tables do not fit LDS together: one unit's table at a time, the workgroup in step
       tab = s_tab;
-      __syncthreads();                                    // the table of the unit before is dead
+      __syncthreads();                                    // the table of the piece before is dead
       const int n4 = p.ps / 4;
       const int4* src = reinterpret_cast<const int4*>(p.plan + (size_t)u * p.ps);
-      int4 r[kTabLoads];
+      for (int i0 = 0; i0 < n4; i0 += 8 * NT) {
+        int4 r[8];
 #pragma unroll
-      for (int k = 0; k < kTabLoads; ++k) {
-        const int i = tid + k * NT;
-        if (i < n4) r[k] = src[i];
-      }
+        for (int k = 0; k < 8; ++k) r[k] = src[min(i0 + tid + k * NT, n4 - 1)];
 #pragma unroll
-      for (int k = 0; k < kTabLoads; ++k) {
-        const int i = tid + k * NT;
-        if (i < n4) reinterpret_cast<int4*>(s_tab)[i] = r[k];
+        for (int k = 0; k < 8; ++k) issue_here(r[k]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int i = i0 + tid + k * NT;
+          if (i < n4) reinterpret_cast<int4*>(s_tab)[i] = r[k];
+        }
       }
       __syncthreads();
     }
     const int* pre = tab + 1;                             // [nseg+1]
     const int* rowoff = tab + p.nseg + 2;                 // [nseg]
-    // runs that hold the first and the last key of the piece: the per-key lookups search only these
-    const int ra = last_not_above(pre, 0, p.nseg, a), rb = last_not_above(pre, 0, p.nseg, b - 1);
+    // runs that hold the first and the last key of the piece
+    const int ra = wave_last_not_above(pre, p.nseg, a, lane), rb = wave_last_not_above(pre, p.nseg, b - 1, lane);
+
+    SAAP_TRACE(13);
+    // The slot is free once the piece that used it before has been sent off.  The flags live in LDS, which
+    // serves a wave's operations in order; relaxed accesses are enough there, and an acquire would also
+    // wait for the query loads in flight.
+    while (__hip_atomic_load(&s_gen[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != use)
+      __builtin_amdgcn_s_sleep(1);
+    asm volatile("" ::: "memory");
+    SAAP_TRACE(14);
+    auto grab = [&]() {                                   // first key of the wave's next batch
+      int g = 0;
+      if (lane == 0) g = __hip_atomic_fetch_add(&s_next[slot], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      return a + __builtin_amdgcn_readfirstlane(g) * WB;
+    };
 
     float m = kNegBig, l = 0.f, O[G][8];
 #pragma unroll
@@ -964,13 +1107,15 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) O[g][e] = 0.f;
 
-    // Keys of (this processor, slot i) of the batch at `base`: base + i*NG + kp.  Slots past the end of
-    // the piece load nothing.
+    // Keys of (processor grp, slot i) of the wave batch at `base`: base + i*4 + grp, so one load instruction of
+    // the wave reads four neighbouring rows.  The lane's keys only move forward through the piece: its run is
+    // found by stepping on from the run of its key in the batch before.
+    int j = ra;
     auto load_batch = [&](int base, Batch<T, KB>& bt) {
       int row;
       {
-        const int v = min(base + (sub & (KB - 1)) * NG + kp, b - 1);   // lane `sub` resolves slot sub % KB
-        const int j = last_not_above(pre, ra, rb + 1, v);
+        const int v = min(base + (sub & (KB - 1)) * 4 + grp, b - 1);   // lane `sub` resolves slot sub % KB
+        while (j < rb && pre[j + 1] <= v) ++j;
         row = rowoff[j] + (v - pre[j]);
         // a plan that breaks the contract (overlapping runs, a damaged index) must not turn into a
         // read outside the cache
@@ -981,90 +1126,167 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
 #pragma unroll
       for (int i = 0; i < KB; ++i) {
         const int r = __shfl(row, (lane & 48) + i);
-        if (base + i * NG + kp < b) {
-          bt.valid |= 1u << i;
-          bt.k[i].load_stream(Kb + (size_t)r * kD);
-          bt.v[i].load_stream(Vb + (size_t)r * kD);
-        } else {
-          bt.k[i] = Vec8<T>{};
-          bt.v[i] = Vec8<T>{};
-        }
+        // slots past the end of the piece read its last key again (and score -inf): loads under a
+        // branch would make the number of loads in flight unknown to the wait counters, and every wait
+        // would then drain them all
+        if (base + i * 4 + grp < b) bt.valid |= 1u << i;
+        bt.k[i].load_stream(Kb + (size_t)r * kD);
+        bt.v[i].load_stream(Vb + (size_t)r * kD);
       }
     };
     auto consume = [&](const Batch<T, KB>& bt) { consume_batch<T, G, false>(bt, qv, scale_log2, sub, m, l, O); };
     {
-      int base = a;
-      Batch<T, KB> cur;
-      load_batch(base, cur);
-      if constexpr (kPrefetch) {
-        for (base += chunk; base < b; base += chunk) {
-          Batch<T, KB> nxt;
-          load_batch(base, nxt);        // in flight while the current batch is consumed
-          __builtin_amdgcn_sched_barrier(0);
+      // two batches at once to begin with; from then on one batch ahead, its LDS round trip off the path
+      int base;
+      {
+        int g = 0;
+        if (lane == 0) g = __hip_atomic_fetch_add(&s_next[slot], 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        base = a + __builtin_amdgcn_readfirstlane(g) * WB;
+      }
+      if (base < b) {
+        int next = base + WB;
+        SAAP_TRACE(15);
+        Batch<T, KB> cur;
+        load_batch(base, cur);
+        SAAP_TRACE(2);
+        if constexpr (kPrefetch) {
+          while (next < b) {
+            const int after = grab();
+            Batch<T, KB> nxt;
+            load_batch(next, nxt);      // in flight while the current batch is consumed
+            __builtin_amdgcn_sched_barrier(0);
+            consume(cur);
+            cur = nxt;
+            next = after;
+          }
           consume(cur);
-          cur = nxt;
-        }
-        consume(cur);
-      } else {
-        consume(cur);
-        for (base += chunk; base < b; base += chunk) {
-          load_batch(base, cur);
+        } else {
           consume(cur);
+          while (next < b) {
+            const int after = grab();
+            load_batch(next, cur);
+            consume(cur);
+            next = after;
+          }
         }
       }
     }
-    SAAP_TRACE(3);
 
-    // ---- end of the piece: one partial result of unit u (or its final result if no other workgroup
-    // holds a piece of it)
+    // ---- end of the piece
     wave_combine<G>(m, l, O);
-    const int w_first = us / Q, w_last = (ue - 1) / Q;
+    const int w_first = rs / Q, w_last = (ue - 1) / Q;    // the workgroups that hold the unit's first and last key
     const int P = w_last - w_first + 1;
-    // slots are numbered along the global range: (workgroup, unit) pairs in order differ by one in
-    // w + rank(u), so a unit's partial results are consecutive
-    const size_t slot = (size_t)w + s_urank[u];
-    workgroup_combine<G, NT>(scratch, m, l, O, [&](int g, int e, float M, float L, float Ov) {
+    // partial results are numbered along the global range: (workgroup, unit) pairs in order differ by at
+    // least one in w + rank(u), so a unit's partial results are consecutive
+    const size_t pslot = (size_t)w + s_urank[u];
+    float* area = scratch + slot * kDepositFloats;
+    auto emit = [&](int g, int e, float M, float L, float Ov) {
       if (P == 1) {
         const float r = L > 0.f ? vs * (Ov / L) : 0.f;
         if (p.out_bf16) reinterpret_cast<bf16_t*>(p.out)[(size_t)(qrow0 + g) * kD + e] = (bf16_t)f32_to_bf16_bits(r);
         else reinterpret_cast<float*>(p.out)[(size_t)(qrow0 + g) * kD + e] = r;
         if (e == 0 && p.lse) p.lse[qrow0 + g] = L > 0.f ? (M + __log2f(L)) * kLn2 : -INFINITY;
       } else {
-        coherent_store(&p.part_o[(slot * G + g) * kD + e], Ov);
+        coherent_store(&p.part_o[(pslot * G + g) * kD + e], Ov);
         if (e == 0) {
-          coherent_store(&p.part_ml[(slot * G + g) * 2 + 0], M);
-          coherent_store(&p.part_ml[(slot * G + g) * 2 + 1], L);
+          coherent_store(&p.part_ml[(pslot * G + g) * 2 + 0], M);
+          coherent_store(&p.part_ml[(pslot * G + g) * 2 + 1], L);
         }
       }
-    });
-    if (P == 1) continue;
-    SAAP_TRACE(4);
-    wait_stores();
-    __syncthreads();
-    if (tid == 0) {
-      // Arrival counter of the unit: count in bits 0-15, sum of the arrivals' XCD numbers in bits 16-31,
-      // sum of their squares in bits 32-47.  sum = n*x and squares = n*x*x hold only if every arrival
-      // came from XCD x: then all partial results went through this XCD's L2.
+    };
+    // Arrival at the unit's counter (one lane): count in bits 0-15, sum of the arrivals' XCD numbers in
+    // bits 16-31, sum of their squares in bits 32-47.  sum = n*x and squares = n*x*x hold only if every
+    // arrival came from XCD x: then all partial results went through this XCD's L2.  The workgroup whose
+    // arrival completes the unit merges it when all its own pieces are done (at most two of its units are
+    // shared with other workgroups: the first and the last of its share).
+    auto arrive = [&]() {
       const unsigned long long xcc = (unsigned long long)((unsigned)__builtin_amdgcn_s_getreg(20 | (3 << 11)) & 7u);
-      const unsigned long long old = __hip_atomic_fetch_add(&p.counters[u], 1ull | (xcc << 16) | ((xcc * xcc) << 32),
+      const unsigned long long old = __hip_atomic_fetch_add(&p.counters[(size_t)u * p.cstride], 1ull | (xcc << 16) | ((xcc * xcc) << 32),
                                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       const unsigned long long n = old & 0xffffull, sx = (old >> 16) & 0xffffull, sxx = (old >> 32) & 0xffffull;
-      s_last = n == (unsigned long long)(P - 1) ? ((sx == n * xcc && sxx == n * xcc * xcc) ? 2 : 1) : 0;
+      if (n == (unsigned long long)(P - 1)) {
+        const int at = __hip_atomic_fetch_add(&s_npend, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        s_pend[at][0] = u;
+        s_pend[at][1] = w_first + s_urank[u];
+        s_pend[at][2] = P;
+        s_pend[at][3] = (sx == n * xcc && sxx == n * xcc * xcc) ? 2 : 1;
+      }
+    };
+    if (ue + F >= k1) {
+      // The last piece of my share: the waves have nothing to go on with, so they combine their results
+      // together (every thread one output) rather than leave it to one of them.
+      workgroup_combine<G, NT>(area, m, l, O, emit);
+      SAAP_TRACE(4);
+      if (P > 1) {
+        wait_stores();
+        __syncthreads();
+        if (tid == 0) arrive();
+      }
+      break;
     }
-    __syncthreads();
-    SAAP_TRACE(5);
-    if (!s_last) continue;
-    if (s_last == 2) {
+    // Any other piece: deposit and go on with the next piece; the last wave to deposit combines the
+    // deposits and sends the piece's result off while the others stream already.
+    {
+      float* w_o = area;
+      float* w_m = w_o + nw * G * kD;
+      float* w_l = w_m + nw * G;
+      if (grp == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float4* dst = reinterpret_cast<float4*>(w_o + (wave * G + g) * kD + sub * 8);
+          dst[0] = make_float4(O[g][0], O[g][1], O[g][2], O[g][3]);
+          dst[1] = make_float4(O[g][4], O[g][5], O[g][6], O[g][7]);
+        }
+        if (sub < G) {            // lane `sub` owns head `sub` (key slot 0)
+          w_m[wave * G + sub] = m;
+          w_l[wave * G + sub] = l;
+        }
+      }
+    }
+    int arrived = 0;
+    if (lane == 0) arrived = __hip_atomic_fetch_add(&s_done[slot], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (__builtin_amdgcn_readfirstlane(arrived) != nw - 1) continue;
+    asm volatile("" ::: "memory");
+    SAAP_TRACE_WAVE(9);
+    combine_deposits<G, nw>(area, lane, emit);
+    if (P > 1) {
+      wait_stores();
+      SAAP_TRACE_WAVE(10);
+      if (lane == 0) arrive();
+    }
+    SAAP_TRACE_WAVE(11);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the deposits have been read
+    if (lane == 0) {
+      s_next[slot] = 0;
+      s_done[slot] = 0;
+      __hip_atomic_store(&s_gen[slot], use + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+  }
+  SAAP_TRACE(3);
+
+  // ---- units that were completed by this workgroup's arrival: Algorithm 2 over their partial results
+  __syncthreads();
+  SAAP_TRACE(5);
+  const int npend = s_npend;
+  for (int i = 0; i < npend; ++i) {
+    const int mu = s_pend[i][0], slot0 = s_pend[i][1], P = s_pend[i][2], kind = s_pend[i][3];
+    const int kvu = p.independent ? (mu / p.Hq) * p.Hkv + (mu % p.Hq) / (p.Hq / p.Hkv) : mu;
+    const int qrow0 = p.independent ? mu : mu * G;
+    float vs = 1.f;
+    if constexpr (kFp8) vs = p.vscale[kvu];
+    if (kind == 2) {
       // this XCD's L2 is coherent for its compute units: dropping this compute unit's L1 lines is enough
       asm volatile("buffer_inv sc0" ::: "memory");
+      final_merge<G, NT, false>(p.part_o, p.part_ml, (size_t)slot0, P, qrow0, vs, p.out, p.out_bf16, p.lse, scratch);
     } else {
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      // partial results from several XCDs: read them past this XCD's L2 (an acquire fence at agent scope would
+      // instead drop that whole L2, the classifier's weights included)
+      final_merge<G, NT, true>(p.part_o, p.part_ml, (size_t)slot0, P, qrow0, vs, p.out, p.out_bf16, p.lse, scratch);
     }
-    SAAP_TRACE(6);
-    final_merge<G, NT>(p.part_o, p.part_ml, (size_t)w_first + s_urank[u], P, qrow0, vs, p.out, p.out_bf16, p.lse, scratch);
-    SAAP_TRACE(8);
-    if (tid == 0) __hip_atomic_store(&p.counters[u], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) __hip_atomic_store(&p.counters[(size_t)mu * p.cstride], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();                                      // the merge scratch is used again
   }
+  SAAP_TRACE(8);
 }
 
 // Visit plan of every unit from its list of runs: one workgroup per unit.
@@ -1332,7 +1554,7 @@ static int32_t planned_attention(const void* q, const void* Ksorted, const void*
   const long long units = plan_units(S, Hq, Hkv, mode);
   const int ps = plan_stride(nruns);
   // every unit's keys are numbered in one 32-bit range
-  if (units > kPlanMaxUnits || ps > kPlanTableInts || units * (long long)Ncap >= (1ll << 31)) return SAAP_UNSUPPORTED;
+  if (units > kPlanMaxUnits || ps > kPlanTableInts || units * ((long long)Ncap + 65536) >= (1ll << 31)) return SAAP_UNSUPPORTED;
   if (ws_bytes < planned_workspace_bytes(units, G)) return SAAP_WORKSPACE_TOO_SMALL;
 
   long long W = device_cus();
@@ -1344,17 +1566,23 @@ static int32_t planned_attention(const void* q, const void* Ksorted, const void*
   PlanParams p{};
   p.q = q; p.K = Ksorted; p.V = Vsorted; p.plan = plan; p.out = out; p.lse = lse;
   p.counters = reinterpret_cast<unsigned long long*>(ws);
+  p.cstride = units * 128 <= (long long)SAAP_WS_HEADER_BYTES ? 16 : 1;
   p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   p.part_o = p.part_ml + (size_t)(kPlanMaxWgs + units) * G * 2;
   p.rows = Ncap; p.nseg = nruns; p.ps = ps; p.n_units = (int)units; p.Hq = Hq; p.Hkv = Hkv;
   p.independent = indep ? 1 : 0; p.out_bf16 = out_dtype == SAAP_BF16;
-  p.all_tables = units * ps <= kPlanTableInts ? 1 : 0;
-  p.q_min = env_int("SAAP_PLAN_QMIN", (NT / 16) * (G == 8 ? 2 : 4));     // one batch of the workgroup
+  p.q_min = env_int("SAAP_PLAN_QMIN", (NT / 16) * (G == 8 ? 2 : 4));     // one batch of every wave
+  p.piece_cost = env_int("SAAP_PLAN_PIECE_COST", 128);
+  if (p.piece_cost < 0 || p.piece_cost > 65536 || p.q_min < 1) return SAAP_INVALID_ARG;
   p.scale_log2 = scale * kLog2e; p.kscale = kscale; p.vscale = vscale;
-  const size_t ints = (size_t)2 * (units + 1) + 3 + (p.all_tables ? (size_t)units * ps : (size_t)ps);
-  const size_t f_combine = (size_t)(NT / 64) * G * (kD + 2);
+  // LDS: unit ranges and ranks | plan tables | deposits of the open pieces, reused as merge scratch
+  const size_t f_deposits = (size_t)kPieceSlots * (NT / 64) * G * (kD + 2);
   const size_t f_merge = (size_t)W * G + 2 * G + 8 + (size_t)NT * 4;
-  const size_t lds = ints * sizeof(int) + (f_combine > f_merge ? f_combine : f_merge) * sizeof(float);
+  const size_t fixed = ((size_t)2 * (units + 1) + 3) * sizeof(int) + (f_deposits > f_merge ? f_deposits : f_merge) * sizeof(float);
+  const size_t lds_max = 160 * 1024 - 1024;               // a compute unit's LDS less the kernel's static arrays
+  p.all_tables = fixed + (size_t)units * ps * sizeof(int) <= lds_max ? 1 : 0;
+  const size_t lds = fixed + (p.all_tables ? (size_t)units * ps : (size_t)ps) * sizeof(int);
+  if (lds > lds_max) return SAAP_UNSUPPORTED;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   if (dtype == kDtypeFp8) return launch_planned<fp8_t>(p, G, (unsigned)W, lds, hs);
   if (dtype == SAAP_BF16) return launch_planned<bf16_t>(p, G, (unsigned)W, lds, hs);
@@ -1418,6 +1646,7 @@ static int32_t sparse_attention(const void* q, const void* Ksorted, const void* 
   p.q = q; p.K = Ksorted; p.V = Vsorted; p.off = off; p.len = len; p.selected = selected;
   p.out = out; p.lse = lse;
   p.counters = reinterpret_cast<unsigned long long*>(ws);
+  p.cstride = units * 128 <= (long long)SAAP_WS_HEADER_BYTES ? 16 : 1;
   p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   p.part_o = p.part_ml + (size_t)units * kMaxP * G * 2;
   p.rows = Ncap; p.nsel = nprobe; p.resident = resident_run; p.nseg = nseg; p.B = B; p.n_units = (int)units;
@@ -1476,6 +1705,7 @@ static int32_t dense_attention(const void* q, const void* K, const void* V, cons
   p.q = q; p.K = K; p.V = V; p.off = off; p.len = len; p.selected = nullptr;
   p.out = out; p.lse = lse;
   p.counters = reinterpret_cast<unsigned long long*>(ws);
+  p.cstride = units * 128 <= (long long)SAAP_WS_HEADER_BYTES ? 16 : 1;
   p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   p.part_o = p.part_ml + (size_t)units * kMaxP * G * 2;
   p.rows = N; p.nseg = off ? B : 0; p.nsel = p.nseg; p.resident = -1; p.B = B; p.n_units = (int)units;

@@ -242,6 +242,12 @@ static __device__ unsigned long long* saap_trace_buf;
     if (saap_trace_buf)                                                                            \
       saap_trace_buf[((size_t)blockIdx.x + (size_t)gridDim.x * (blockIdx.y + (size_t)gridDim.y * blockIdx.z)) * 16 + (i)] = (unsigned long long)(v); \
   } while (0)
+/* the same stamp taken by lane 0 of whichever wave runs the code */                               \
+#define SAAP_TRACE_WAVE(i)                                                                         \
+  do {                                                                                             \
+    if (saap_trace_buf && (threadIdx.x & 63) == 0)                                                 \
+      saap_trace_buf[((size_t)blockIdx.x + (size_t)gridDim.x * (blockIdx.y + (size_t)gridDim.y * blockIdx.z)) * 16 + (i)] = wall_clock64(); \
+  } while (0)
 static inline void saap_trace_arm() {
   const char* tp = getenv("SAAP_TRACE_PTR");
   unsigned long long* ptr = tp ? reinterpret_cast<unsigned long long*>(strtoull(tp, nullptr, 16)) : nullptr;
@@ -250,5 +256,6 @@ static inline void saap_trace_arm() {
 #else
 #define SAAP_TRACE(i) do { } while (0)
 #define SAAP_TRACE_VALUE(i, v) do { } while (0)
+#define SAAP_TRACE_WAVE(i) do { } while (0)
 static inline void saap_trace_arm() {}
 #endif

@@ -197,11 +197,13 @@ def test_planned_attention_with_wildly_unequal_units(saap, S, Hkv, G, seed):
     assert_close(lse.cpu().numpy(), rl, "bf16", "unequal units lse")
     s_e, h_e = divmod(int(empty), Hkv)
     assert (out[s_e, h_e * G:(h_e + 1) * G] == 0).all() and torch.isneginf(lse[s_e, h_e * G:(h_e + 1) * G]).all()
-    # and the same launch twice more on the same workspace (arrival counters must come back to zero)
+    # and the same launch twice more on the same workspace (arrival counters must come back to zero).  Which
+    # wave takes which batch of keys depends on timing, so a repeat agrees in value, not bit for bit.
     for _ in range(2):
         o2, l2 = saap.planned_decode_attention(q[0], Ks, Vs, plan, nprobe, SCALE)
     torch.cuda.synchronize()
-    assert torch.equal(o2, out) and torch.equal(l2, lse)
+    assert_close(o2.cpu().numpy(), ro, "bf16", "repeat out")
+    assert torch.allclose(o2, out, rtol=1e-4, atol=1e-5) and torch.allclose(l2[torch.isfinite(lse)], lse[torch.isfinite(lse)], rtol=1e-5)
 
 
 def test_planned_attention_independent_lists_and_resident_run(saap):
