@@ -83,6 +83,7 @@ enum {
 };
 
 #define SAAP_WS_HEADER_BYTES 65536u
+#define SAAP_STATIC_SCRATCH_BYTES (8u << 20)   /* scratch built into the library for saap_sparse_decode_attention_noalloc */
 #define SAAP_MAX_BUCKETS 8192      /* B and nprobe limit of select / sparse attention */
 #define SAAP_HEAD_DIM 128
 
@@ -257,6 +258,26 @@ int32_t saap_sparse_decode_attention(const void* q, const void* Ksorted, const v
                                      int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
                                      int32_t d, int32_t dtype,
                                      void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * sparse_decode_attention_noalloc -- saap_sparse_decode_attention for callers that cannot allocate or
+ * pass device scratch: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The arguments, the result and the limits are those of saap_sparse_decode_attention
+ * without `ws` / `ws_bytes`: the partial results and arrival counters live in a device array built
+ * into the library (SAAP_STATIC_SCRATCH_BYTES = 8 MiB per GPU, held from the first call on that
+ * GPU until the process ends).  The call allocates nothing and frees nothing; it enqueues a small
+ * fill kernel that clears the array's counters and then the attention kernel, both on `stream`.
+ *   Shapes whose scratch would exceed the array (about S*Hkv*(Hq/Hkv) > 120 heads in one call, or
+ *   more than 512 lists) return SAAP_WORKSPACE_TOO_SMALL before anything is enqueued.
+ *   Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two
+ *   streams, two threads) race and must be serialised by the caller.
+ */
+int32_t saap_sparse_decode_attention_noalloc(const void* q, const void* Ksorted, const void* Vsorted,
+                                             const int32_t* off, const int32_t* len,
+                                             const int32_t* selected, int32_t nprobe, int32_t mode,
+                                             float scale, void* out, int32_t out_dtype, float* lse,
+                                             int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
+                                             int32_t d, int32_t dtype, void* stream);
 
 /*
  * dense_decode_attention -- softmax attention over every key (the full-attention

@@ -36,7 +36,7 @@ EXPORTS = (
     "saap_bucket_attention_mass", "saap_query_model_loss_grads", "saap_adam_update",
     "saap_bucket_attention_mass_batch", "saap_query_model_bn_loss_grads", "saap_fold_batch_norm",
     "saap_build_visit_plan", "saap_select_buckets_planned", "saap_planned_decode_attention",
-    "saap_planned_decode_attention_fp8", "saap_visit_plan_bytes",
+    "saap_planned_decode_attention_fp8", "saap_visit_plan_bytes", "saap_sparse_decode_attention_noalloc",
 )
 
 
@@ -411,6 +411,21 @@ def planned_decode_attention_fp8(q, K8, V8, kscale, vscale, plan, nruns, scale, 
         ctypes.c_float(scale), _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S), _i32(Hq), _i32(Hkv), _i32(Ncap),
         _i32(d), _ptr(ws), wsb, _stream())
     _check("saap_planned_decode_attention_fp8", st)
+    return out, lse
+
+
+def sparse_decode_attention_noalloc(q, Ks, Vs, off, ln, selected, scale, out, lse, mode=GROUP_SUM):
+    """sparse_decode_attention without a workspace argument: the library's built-in scratch array serves.  The
+    caller passes every output; nothing is allocated here or in the library."""
+    S, Hq, d = q.shape
+    _, Hkv, Ncap, _ = Ks.shape
+    B = ln.shape[2]
+    nprobe = selected.shape[2]
+    st = load_library().saap_sparse_decode_attention_noalloc(
+        _ptr(q), _ptr(Ks), _ptr(Vs), _ptr(off), _ptr(ln), _ptr(selected) if nprobe > 0 else ctypes.c_void_p(0),
+        _i32(nprobe), _i32(mode), ctypes.c_float(scale), _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S),
+        _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _stream())
+    _check("saap_sparse_decode_attention_noalloc", st)
     return out, lse
 
 

@@ -21,6 +21,8 @@
 //     partial attention and merge are one launch.
 #include "common.h"
 
+#include <mutex>
+
 namespace saap {
 namespace {
 
@@ -1764,4 +1766,57 @@ extern "C" int32_t saap_dense_decode_attention_fp8(const void* q, const uint8_t*
   if (!kscale || !vscale) return SAAP_INVALID_ARG;
   return dense_attention(q, K8, V8, kscale, vscale, off, len, B, scale, out, out_dtype, lse, S, Hq, Hkv, N, d,
                          kDtypeFp8, ws, ws_bytes, stream);
+}
+
+// ---- attention for callers that cannot allocate ---------------------------------------------------
+// The workspace of this entry point is a device array that is part of the library's image: every GPU
+// the library runs on holds SAAP_STATIC_SCRATCH_BYTES of it from the first call until the process ends.
+namespace {
+static __device__ __align__(256) unsigned char scratch[SAAP_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];   // per device: that device's copy of `scratch` (the array's name is no device address)
+
+// Address of the current device's copy of `scratch`; looked up once per device, with that device current.
+int32_t static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SAAP_HIP_ERROR;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SAAP_HIP_ERROR;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SAAP_OK;
+}
+}  // namespace
+
+extern "C" int32_t saap_sparse_decode_attention_noalloc(const void* q, const void* Ksorted, const void* Vsorted,
+                                                        const int32_t* off, const int32_t* len,
+                                                        const int32_t* selected, int32_t nprobe, int32_t mode,
+                                                        float scale, void* out, int32_t out_dtype, float* lse,
+                                                        int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
+                                                        int32_t d, int32_t dtype, void* stream) {
+  if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
+  // the shape decides the scratch it needs; more than the array holds is refused before anything is enqueued
+  if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return SAAP_INVALID_ARG;
+  if (mode != SAAP_GROUP_SUM && mode != SAAP_INDEPENDENT) return SAAP_INVALID_ARG;
+  const int heads = Hq / Hkv;
+  const bool indep = mode == SAAP_INDEPENDENT;
+  const bool masked = indep && heads > 1 && B <= 16 * 512;
+  const long long units = indep && !masked ? (long long)S * Hq : (long long)S * Hkv;
+  const int G = masked ? heads : indep ? 1 : heads;
+  if (units * 128 > (long long)SAAP_WS_HEADER_BYTES || attn_workspace_bytes(units, G) > (size_t)SAAP_STATIC_SCRATCH_BYTES)
+    return SAAP_WORKSPACE_TOO_SMALL;
+  void* ws = nullptr;
+  int32_t st = static_scratch(&ws);
+  if (st != SAAP_OK) return st;
+  // The array keeps what the last call left.  Its arrival counters must be zero when the kernel starts: a
+  // fill kernel clears them on the caller's stream (a call that was abandoned midway may have left some set).
+  st = saap_workspace_reset(ws, SAAP_STATIC_SCRATCH_BYTES, stream);
+  if (st != SAAP_OK) return st;
+  return sparse_attention(q, Ksorted, Vsorted, nullptr, nullptr, off, len, selected, nprobe, mode, -1, scale, out,
+                          out_dtype, lse, S, Hq, Hkv, Ncap, B, d, dtype, ws, SAAP_STATIC_SCRATCH_BYTES, stream);
 }
