@@ -116,13 +116,25 @@ def workspace_bytes(op: int, **shape) -> int:
 
 class _Workspace:
     """Device scratch handed to the calls.  Zero-filled once at allocation, which is what the
-    header of arrival counters needs; grown (and zero-filled again) on demand."""
+    header of arrival counters needs; grown (and zero-filled again) on demand.
+
+    A HIP graph that captured a call holds the RAW ADDRESS of the buffer it was given.  A buffer that has
+    been handed out is therefore never freed: when a larger one replaces it, the old one is kept alive, so a
+    graph captured earlier still replays into memory that belongs to the workspace.  Growing while the
+    current stream is capturing is refused (allocating there would also break the capture): run the call
+    once eagerly first, or pass ws= explicitly."""
 
     def __init__(self):
         self.buf = None
+        self.retired = []
 
     def get(self, nbytes: int, device) -> torch.Tensor:
         if self.buf is None or self.buf.numel() < nbytes or self.buf.device != torch.device(device):
+            if torch.cuda.is_current_stream_capturing():
+                raise RuntimeError("the shared SAAP workspace would have to grow during stream capture: call the "
+                                   "operation once eagerly before capturing, or pass ws=")
+            if self.buf is not None:
+                self.retired.append(self.buf)
             self.buf = torch.zeros(max(nbytes, WS_HEADER_BYTES), dtype=torch.uint8, device=device)
         return self.buf
 

@@ -530,6 +530,7 @@ using namespace saap;
 extern "C" int32_t saap_assign_keys(const void* x, const void* centroids, const float* bias,
                                     int32_t* bucket_ids, int32_t S, int32_t Hkv, int32_t N, int32_t B,
                                     int32_t d, int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
   if (!x || !centroids || !bucket_ids || !ws) return SAAP_INVALID_ARG;
   if (!aligned16(x) || !aligned16(centroids) || !aligned16(bucket_ids) || !aligned16(ws)) return SAAP_INVALID_ARG;
   if (S <= 0 || Hkv <= 0 || N <= 0 || B <= 0) return SAAP_INVALID_ARG;

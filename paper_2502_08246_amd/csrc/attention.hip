@@ -1505,6 +1505,7 @@ extern "C" size_t saap_visit_plan_bytes(int32_t S, int32_t Hq, int32_t Hkv, int3
 extern "C" int32_t saap_build_visit_plan(const int32_t* selected, const int32_t* off, const int32_t* len,
                                          int32_t nprobe, int32_t mode, int32_t resident_run, int32_t* plan,
                                          int32_t S, int32_t Hq, int32_t Hkv, int32_t runs, void* stream) {
+  begin_call();
   if (!off || !len || !plan || !aligned16(plan) || (nprobe > 0 && !selected)) return SAAP_INVALID_ARG;
   if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || runs <= 0) return SAAP_INVALID_ARG;
   if (mode != SAAP_GROUP_SUM && mode != SAAP_INDEPENDENT) return SAAP_INVALID_ARG;
@@ -1596,6 +1597,7 @@ extern "C" int32_t saap_planned_decode_attention(const void* q, const void* Ksor
                                                  void* out, int32_t out_dtype, float* lse, int32_t S, int32_t Hq,
                                                  int32_t Hkv, int32_t Ncap, int32_t d, int32_t dtype, void* ws,
                                                  size_t ws_bytes, void* stream) {
+  begin_call();
   if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
   return planned_attention(q, Ksorted, Vsorted, nullptr, nullptr, plan, nruns, mode, scale, out, out_dtype, lse, S, Hq,
                            Hkv, Ncap, d, dtype, ws, ws_bytes, stream);
@@ -1606,6 +1608,7 @@ extern "C" int32_t saap_planned_decode_attention_fp8(const void* q, const uint8_
                                                      int32_t nruns, int32_t mode, float scale, void* out,
                                                      int32_t out_dtype, float* lse, int32_t S, int32_t Hq, int32_t Hkv,
                                                      int32_t Ncap, int32_t d, void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
   if (!kscale || !vscale) return SAAP_INVALID_ARG;
   return planned_attention(q, K8, V8, kscale, vscale, plan, nruns, mode, scale, out, out_dtype, lse, S, Hq, Hkv, Ncap,
                            d, kDtypeFp8, ws, ws_bytes, stream);
@@ -1673,6 +1676,7 @@ extern "C" int32_t saap_sparse_decode_attention(const void* q, const void* Ksort
                                                 int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
                                                 int32_t d, int32_t dtype, void* ws, size_t ws_bytes,
                                                 void* stream) {
+  begin_call();
   return sparse_attention(q, Ksorted, Vsorted, nullptr, nullptr, off, len, selected, nprobe, mode, -1, scale, out,
                           out_dtype, lse, S, Hq, Hkv, Ncap, B, d, dtype, ws, ws_bytes, stream);
 }
@@ -1684,6 +1688,7 @@ extern "C" int32_t saap_windowed_decode_attention(const void* q, const void* Kso
                                                   int32_t out_dtype, float* lse, int32_t S, int32_t Hq,
                                                   int32_t Hkv, int32_t Ncap, int32_t runs, int32_t d,
                                                   int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
   return sparse_attention(q, Ksorted, Vsorted, nullptr, nullptr, off, len, selected, nprobe, mode, resident_run, scale,
                           out, out_dtype, lse, S, Hq, Hkv, Ncap, runs, d, dtype, ws, ws_bytes, stream);
 }
@@ -1727,6 +1732,7 @@ extern "C" int32_t saap_dense_decode_attention(const void* q, const void* K, con
                                                float scale, void* out, int32_t out_dtype, float* lse,
                                                int32_t S, int32_t Hq, int32_t Hkv, int32_t N, int32_t d,
                                                int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
   if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
   return dense_attention(q, K, V, nullptr, nullptr, off, len, B, scale, out, out_dtype, lse, S, Hq, Hkv, N, d, dtype,
                          ws, ws_bytes, stream);
@@ -1739,6 +1745,7 @@ extern "C" int32_t saap_sparse_decode_attention_fp8(const void* q, const uint8_t
                                                     float scale, void* out, int32_t out_dtype, float* lse,
                                                     int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
                                                     int32_t d, void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
   if (!kscale || !vscale) return SAAP_INVALID_ARG;
   return sparse_attention(q, K8, V8, kscale, vscale, off, len, selected, nprobe, mode, -1, scale, out, out_dtype, lse,
                           S, Hq, Hkv, Ncap, B, d, kDtypeFp8, ws, ws_bytes, stream);
@@ -1752,6 +1759,7 @@ extern "C" int32_t saap_windowed_decode_attention_fp8(const void* q, const uint8
                                                       int32_t out_dtype, float* lse, int32_t S, int32_t Hq,
                                                       int32_t Hkv, int32_t Ncap, int32_t runs, int32_t d, void* ws,
                                                       size_t ws_bytes, void* stream) {
+  begin_call();
   if (!kscale || !vscale) return SAAP_INVALID_ARG;
   return sparse_attention(q, K8, V8, kscale, vscale, off, len, selected, nprobe, mode, resident_run, scale, out,
                           out_dtype, lse, S, Hq, Hkv, Ncap, runs, d, kDtypeFp8, ws, ws_bytes, stream);
@@ -1763,6 +1771,7 @@ extern "C" int32_t saap_dense_decode_attention_fp8(const void* q, const uint8_t*
                                                    float scale, void* out, int32_t out_dtype, float* lse,
                                                    int32_t S, int32_t Hq, int32_t Hkv, int32_t N, int32_t d,
                                                    void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
   if (!kscale || !vscale) return SAAP_INVALID_ARG;
   return dense_attention(q, K8, V8, kscale, vscale, off, len, B, scale, out, out_dtype, lse, S, Hq, Hkv, N, d,
                          kDtypeFp8, ws, ws_bytes, stream);
@@ -1799,6 +1808,7 @@ extern "C" int32_t saap_sparse_decode_attention_noalloc(const void* q, const voi
                                                         float scale, void* out, int32_t out_dtype, float* lse,
                                                         int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
                                                         int32_t d, int32_t dtype, void* stream) {
+  begin_call();
   if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
   // the shape decides the scratch it needs; more than the array holds is refused before anything is enqueued
   if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return SAAP_INVALID_ARG;

@@ -372,6 +372,7 @@ extern "C" int32_t saap_classify_queries(const void* xq, const void* W1, const f
                                          const float* b2, int32_t Hw, float* scores, int32_t S, int32_t Hq,
                                          int32_t Hkv, int32_t d, int32_t hidden, int32_t B, int32_t dtype,
                                          int32_t output_kind, void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
   const bool linear = hidden == 0;      // one-layer model z = W2 x + b2, W2 [Hw,B,d]; W1 and b1 unused
   if (!xq || (!linear && !W1) || !W2 || !scores || !ws) return SAAP_INVALID_ARG;
   if (!aligned16(xq) || !aligned16(W1) || !aligned16(W2) || !aligned16(scores) || !aligned16(ws))

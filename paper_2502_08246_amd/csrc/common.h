@@ -40,6 +40,9 @@ inline int env_int(const char* name, int dflt) {
 // Compute units of the current device; 256 (MI355X) when the query fails.
 int device_cus();
 
+// Every entry point starts with begin_call(): an error that an earlier, unrelated HIP call of the process left
+// behind is dropped, so that launch_status() reports this call's launches only.
+inline void begin_call() { (void)hipGetLastError(); }
 inline int32_t launch_status() { return hipGetLastError() == hipSuccess ? SAAP_OK : SAAP_HIP_ERROR; }
 
 // ---- device side -------------------------------------------------------------------------

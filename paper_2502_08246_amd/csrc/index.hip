@@ -582,6 +582,7 @@ extern "C" int32_t saap_build_bucket_index(const int32_t* bucket_ids, const void
                                            void* Vsorted, int32_t S, int32_t Hkv, int32_t N, int32_t Ncap,
                                            int32_t B, int32_t d, int32_t dtype, int32_t slack, void* ws,
                                            size_t ws_bytes, void* stream) {
+  begin_call();
   return build_index(bucket_ids, K, V, off, len, idx, Ksorted, Vsorted, nullptr, S, Hkv, N, Ncap, B, d, dtype, slack,
                      0, 0, ws, ws_bytes, stream);
 }
@@ -592,6 +593,7 @@ extern "C" int32_t saap_build_windowed_index(const int32_t* bucket_ids, const vo
                                              int32_t N, int32_t Ncap, int32_t B, int32_t d, int32_t dtype,
                                              int32_t slack, int32_t n_sink, int32_t n_recent, void* ws,
                                              size_t ws_bytes, void* stream) {
+  begin_call();
   if (!resident_ids) return SAAP_INVALID_ARG;
   return build_index(bucket_ids, K, V, off, len, idx, Ksorted, Vsorted, resident_ids, S, Hkv, N, Ncap, B, d, dtype,
                      slack, n_sink, n_recent, ws, ws_bytes, stream);
@@ -604,6 +606,7 @@ extern "C" int32_t saap_window_push(const void* x_new, const void* k_new, const 
                                     int32_t* overflow_flag, int32_t S, int32_t Hkv, int32_t Ncap, int32_t B,
                                     int32_t d, int32_t dtype, int32_t n_sink, int32_t n_recent, void* ws,
                                     size_t ws_bytes, void* stream) {
+  begin_call();
   if (!x_new || !k_new || !v_new || !pos_new || !centroids || !off || !len || !idx || !Ksorted || !Vsorted ||
       !resident_ids || !new_bucket_ids || !overflow_flag || !ws)
     return SAAP_INVALID_ARG;
@@ -642,6 +645,7 @@ extern "C" int32_t saap_append_keys(const void* x_new, const void* k_new, const 
                                     void* Vsorted, int32_t* new_bucket_ids, int32_t* overflow_flag, int32_t S,
                                     int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype, void* ws,
                                     size_t ws_bytes, void* stream) {
+  begin_call();
   if (!x_new || !k_new || !v_new || !centroids || !off || !len || !idx || !Ksorted || !Vsorted ||
       !new_bucket_ids || !overflow_flag || !ws)
     return SAAP_INVALID_ARG;
@@ -712,6 +716,7 @@ extern "C" int32_t saap_append_keys_fp8(const void* x_new, const void* k_new, co
                                         const float* kscale, const float* vscale, int32_t* new_bucket_ids,
                                         int32_t* overflow_flag, int32_t S, int32_t Hkv, int32_t Ncap, int32_t B,
                                         int32_t d, void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
   return push_fp8(x_new, k_new, v_new, pos_new, centroids, bias, off, len, idx, K8, V8, kscale, vscale, nullptr,
                   new_bucket_ids, overflow_flag, S, Hkv, Ncap, B, d, 0, 0, ws, ws_bytes, stream);
 }
@@ -723,6 +728,7 @@ extern "C" int32_t saap_window_push_fp8(const void* x_new, const void* k_new, co
                                         int32_t* new_bucket_ids, int32_t* overflow_flag, int32_t S, int32_t Hkv,
                                         int32_t Ncap, int32_t B, int32_t d, int32_t n_sink, int32_t n_recent,
                                         void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
   if (!resident_ids) return SAAP_INVALID_ARG;
   return push_fp8(x_new, k_new, v_new, pos_new, centroids, bias, off, len, idx, K8, V8, kscale, vscale, resident_ids,
                   new_bucket_ids, overflow_flag, S, Hkv, Ncap, B, d, n_sink, n_recent, ws, ws_bytes, stream);
@@ -734,6 +740,7 @@ extern "C" int32_t saap_recompact_index(const int32_t* off, const int32_t* len, 
                                         int32_t* overflow_flag, int32_t S, int32_t Hkv, int32_t Ncap,
                                         int32_t Ncap_new, int32_t B, int32_t resident, int32_t d, int32_t dtype,
                                         int32_t slack_new, void* stream) {
+  begin_call();
   if (!off || !len || !idx || !Ksorted || !Vsorted || !off_new || !idx_new || !Ksorted_new || !Vsorted_new ||
       !overflow_flag)
     return SAAP_INVALID_ARG;

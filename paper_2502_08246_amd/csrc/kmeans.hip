@@ -79,6 +79,7 @@ extern "C" int32_t saap_update_centroids(const void* x_sorted, const int32_t* of
                                          const void* centroids_old, void* centroids_new, int32_t S, int32_t Hkv,
                                          int32_t Ncap, int32_t B, int32_t d, int32_t dtype, int32_t normalize,
                                          void* stream) {
+  begin_call();
   if (!x_sorted || !off || !len || !centroids_old || !centroids_new) return SAAP_INVALID_ARG;
   if (!aligned16(x_sorted) || !aligned16(centroids_old) || !aligned16(centroids_new)) return SAAP_INVALID_ARG;
   if (S <= 0 || Hkv <= 0 || Ncap <= 0 || B <= 0) return SAAP_INVALID_ARG;

@@ -260,6 +260,7 @@ extern "C" int32_t saap_bucket_attention_mass(const void* q, const void* Ksorted
                                               const int32_t* len, float scale, float* mass, float* lse, int32_t S,
                                               int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d,
                                               int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
   if (!q || !Ksorted || !off || !len || !mass || !ws) return SAAP_INVALID_ARG;
   if (!aligned16(q) || !aligned16(Ksorted) || !aligned16(ws)) return SAAP_INVALID_ARG;
   if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || Ncap <= 0 || B <= 0) return SAAP_INVALID_ARG;
@@ -298,6 +299,7 @@ extern "C" int32_t saap_bucket_attention_mass_batch(const void* q, const void* K
                                                     int32_t S, int32_t Hkv, int32_t R, int32_t Ncap, int32_t B,
                                                     int32_t d, int32_t dtype, void* ws, size_t ws_bytes,
                                                     void* stream) {
+  begin_call();
   if (!q || !Ksorted || !off || !len || !mass || !ws) return SAAP_INVALID_ARG;
   if (!aligned16(q) || !aligned16(Ksorted) || !aligned16(mass) || !aligned16(ws)) return SAAP_INVALID_ARG;
   if (S <= 0 || Hkv <= 0 || R <= 0 || Ncap <= 0 || B <= 0) return SAAP_INVALID_ARG;

@@ -15,17 +15,12 @@ size_t mass_batch_workspace_bytes(long long units, long long R, int B);
 size_t train_workspace_bytes(long long Hw, long long R, int d, int hidden, int B);
 
 int device_cus() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
-        prop.multiProcessorCount > 0)
-      cus = prop.multiProcessorCount;
-    else
-      cus = 256;
-  }
-  return cus;
+  // asked on every call: the caller may have switched devices since the last one
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+    return cus;
+  return 256;
 }
 
 namespace {
@@ -59,6 +54,7 @@ __global__ void __launch_bounds__(512) stream_read_kernel(const uint4* __restric
 using namespace saap;
 
 extern "C" int32_t saap_stream_read_probe(const void* src, size_t bytes, void* sink, size_t sink_bytes, void* stream) {
+  begin_call();
   if (!src || !sink || !aligned16(src) || !aligned16(sink) || bytes < 16) return SAAP_INVALID_ARG;
   // one workgroup of eight waves per compute unit: the shape that read fastest in a sweep of 128-512 threads
   // and 1-16 workgroups per compute unit (7.1 TB/s; 5.7-6.5 with more waves per compute unit)
@@ -116,6 +112,7 @@ extern "C" size_t saap_workspace_bytes(int32_t op, const saap_shape* sh) {
 }
 
 extern "C" int32_t saap_workspace_reset(void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
   if (!ws || !aligned16(ws) || ws_bytes < SAAP_WS_HEADER_BYTES) return SAAP_INVALID_ARG;
   const size_t n = SAAP_WS_HEADER_BYTES / sizeof(uint32_t);
   hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
@@ -136,6 +133,7 @@ extern "C" const char* saap_status_string(int32_t status) {
 }
 
 extern "C" int32_t saap_device_compute_units(void) {
+  begin_call();
   int dev = 0;
   hipDeviceProp_t prop;
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return -1;

@@ -82,6 +82,7 @@ using namespace saap;
 extern "C" int32_t saap_quantize_kv(const void* Ksorted, const void* Vsorted, uint8_t* K8, uint8_t* V8, float* kscale,
                                     float* vscale, int32_t S, int32_t Hkv, int32_t Ncap, int32_t d, int32_t dtype,
                                     void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
   if (!Ksorted || !Vsorted || !K8 || !V8 || !kscale || !vscale || !ws) return SAAP_INVALID_ARG;
   if (!aligned16(Ksorted) || !aligned16(Vsorted) || !aligned16(K8) || !aligned16(V8) || !aligned16(ws))
     return SAAP_INVALID_ARG;

@@ -618,6 +618,7 @@ static int32_t select_impl(const float* scores, bool logits, float* probs, int32
 extern "C" int32_t saap_select_buckets(const float* scores, int32_t* selected, int32_t S, int32_t Hq,
                                        int32_t Hkv, int32_t B, int32_t nprobe, int32_t mode, void* ws,
                                        size_t ws_bytes, void* stream) {
+  begin_call();
   (void)ws;
   (void)ws_bytes;
   return select_impl(scores, false, nullptr, selected, S, Hq, Hkv, B, nprobe, mode, stream);
@@ -627,6 +628,7 @@ extern "C" int32_t saap_select_buckets_from_logits(const float* logits, float* p
                                                    int32_t S, int32_t Hq, int32_t Hkv, int32_t B,
                                                    int32_t nprobe, int32_t mode, void* ws, size_t ws_bytes,
                                                    void* stream) {
+  begin_call();
   (void)ws;
   (void)ws_bytes;
   if (!logits) return SAAP_INVALID_ARG;
@@ -638,6 +640,7 @@ extern "C" int32_t saap_select_buckets_planned(const float* scores, int32_t inpu
                                                int32_t* selected, int32_t* plan, int32_t S, int32_t Hq,
                                                int32_t Hkv, int32_t B, int32_t nprobe, int32_t mode, void* ws,
                                                size_t ws_bytes, void* stream) {
+  begin_call();
   (void)ws;
   (void)ws_bytes;
   if (!off || !len || !plan || !aligned16(plan)) return SAAP_INVALID_ARG;

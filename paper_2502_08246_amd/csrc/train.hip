@@ -396,6 +396,7 @@ extern "C" int32_t saap_query_model_loss_grads(const void* x, const float* targe
                                                const saap_mlp_f32* grads, float* loss, int32_t Hw, int32_t R,
                                                int32_t d, int32_t hidden, int32_t B, int32_t x_dtype, void* ws,
                                                size_t ws_bytes, void* stream) {
+  begin_call();
   return loss_grads(x, target, params, grads, nullptr, loss, Hw, R, d, hidden, B, x_dtype, ws, ws_bytes, stream);
 }
 
@@ -403,6 +404,7 @@ extern "C" int32_t saap_query_model_bn_loss_grads(const void* x, const float* ta
                                                   const saap_mlp_f32* grads, const saap_batch_norm_f32* bn, float* loss,
                                                   int32_t Hw, int32_t R, int32_t d, int32_t hidden, int32_t B,
                                                   int32_t x_dtype, void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
   if (!bn) return SAAP_INVALID_ARG;
   return loss_grads(x, target, params, grads, bn, loss, Hw, R, d, hidden, B, x_dtype, ws, ws_bytes, stream);
 }
@@ -411,6 +413,7 @@ extern "C" int32_t saap_fold_batch_norm(const float* W1, const float* b1, const 
                                         const float* running_mean, const float* running_var, float eps, void* W1_out,
                                         float* b1_out, int32_t Hw, int32_t hidden, int32_t d, int32_t out_dtype,
                                         void* stream) {
+  begin_call();
   if (!W1 || !b1 || !gamma || !beta || !running_mean || !running_var || !W1_out || !b1_out) return SAAP_INVALID_ARG;
   if (Hw <= 0 || hidden <= 0 || d <= 0 || !(eps > 0.f)) return SAAP_INVALID_ARG;
   if (out_dtype != SAAP_F32 && out_dtype != SAAP_BF16) return SAAP_INVALID_ARG;
@@ -428,6 +431,7 @@ extern "C" int32_t saap_fold_batch_norm(const float* W1, const float* b1, const 
 
 extern "C" int32_t saap_adam_update(float* param, const float* grad, float* m, float* v, size_t n, int32_t step,
                                     float lr, float beta1, float beta2, float eps, void* stream) {
+  begin_call();
   if (!param || !grad || !m || !v) return SAAP_INVALID_ARG;
   if (n == 0 || step < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return SAAP_INVALID_ARG;
   // bias corrections 1 / (1 - beta^t), evaluated in double on the host

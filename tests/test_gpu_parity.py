@@ -596,3 +596,20 @@ def test_many_units_take_the_two_workgroups_per_compute_unit_shape(saap, dtype, 
         ro8, rl8 = ref.sparse_decode_attention(h(q[0]), Kd, Vd, r_off, r_ln, ident, all_np, SCALE)
         assert_close(out8.cpu().numpy(), ro8, dtype, "8-bit dense out")
         assert_close(lse8.cpu().numpy(), rl8, dtype, "8-bit dense lse")
+
+
+@pytest.mark.parametrize("hidden,B", [(64, 100), (48, 64), (0, 100), (1600, 64)])
+def test_classifier_shapes_outside_its_limits_are_refused_on_the_device_too(saap, hidden, B):
+    """hidden must be a multiple of 32 (at most 1536) and B a multiple of 16: anything else returns
+    SAAP_UNSUPPORTED before a kernel is enqueued, so the output buffer keeps what it held."""
+    S, Hq, Hkv = 2, 8, 2
+    g = torch.Generator(device=DEV).manual_seed(3)
+    xq = torch.randn(S, Hq, 128, generator=g, device=DEV).to(torch.bfloat16)
+    W1 = None if hidden == 0 else torch.randn(Hkv, hidden, 128, generator=g, device=DEV).to(torch.bfloat16)
+    W2 = torch.randn(Hkv, B, hidden if hidden else 128, generator=g, device=DEV).to(torch.bfloat16)
+    out = torch.full((S, Hq, B), -7.0, dtype=torch.float32, device=DEV)
+    with pytest.raises(saap.SaapError) as e:
+        saap.classify_queries(xq, W1, None, W2, None, Hkv, out=out)
+    torch.cuda.synchronize()
+    assert e.value.status == -2
+    assert (out == -7.0).all()
