@@ -181,6 +181,26 @@ def windowed_decode_attention(q, K, V, ids, selected, n_sink, n_recent, scale, B
     return out, lse
 
 
+def prefill_sparse_attention(q, K, V, ids, selected, pos0, n_sink, n_recent, scale, B):
+    """q [S,Tq,Hq,d]; position-ordered K,V [S,Hkv,Nt,d], ids [S,Hkv,Nt]; selected [S,Hkv,Tq,nprobe]; pos0 [S]
+    -> out float64 [S,Tq,Hq,d], lse float64 [S,Tq,Hq]."""
+    q = _f32(q)
+    K = _f32(K)
+    V = _f32(V)
+    ids = _i32(ids)
+    selected = _i32(selected)
+    pos0 = _i32(pos0)
+    S, Tq, Hq, d = q.shape
+    _, Hkv, Nt, _ = K.shape
+    nprobe = selected.shape[3]
+    assert selected.shape[:3] == (S, Hkv, Tq) and pos0.shape == (S,) and int(pos0.max()) + Tq <= Nt
+    out = np.empty((S, Tq, Hq, d), dtype=np.float64)
+    lse = np.empty((S, Tq, Hq), dtype=np.float64)
+    lib().ref_prefill_sparse_attention(_p(q), _p(K), _p(V), _p(ids), _p(selected), _p(pos0), nprobe, n_sink, n_recent,
+                                       ctypes.c_float(scale), _p(out), _p(lse), S, Hq, Hkv, Tq, Nt, B, d)
+    return out, lse
+
+
 def recompact_index(off, ln, idx, Ks, Vs, slack_new, Ncap_new, resident=False):
     """-> (off_new, idx_new, Ks_new, Vs_new, overflow flag); ln stays valid."""
     S, Hkv, Ncap, d = Ks.shape

@@ -19,7 +19,9 @@
  * against the format and its encoder against a nearest-value search,
  * closed forms (equal keys -> mean of values, one key -> its value), nprobe = B
  * equals dense attention, library softmax/matmul/argsort, CSR invariants, the
- * balanced-selectivity column of the paper's Table "nprobe_selectivity".
+ * balanced-selectivity column of the paper's Table "nprobe_selectivity"; the prefill-time
+ * attention reduces to causal softmax attention (every bucket listed) and, for one token, to the
+ * decode-time windowed attention.
  * Every function has at least one such pin.  The paper prints no numeric
  * attention output, score or index, so there is no worked example of those to
  * store: the pins come from the mathematics, the number format and the one
@@ -352,6 +354,42 @@ void ref_windowed_decode_attention(const float* q, const float* K, const float* 
     }
     attend_list(q + (size_t)t * d, K + u * Nt * d, V + u * Nt * d, members, c, (double)scale, d,
                 out + (size_t)t * d, lse ? lse + t : NULL);
+    free(members);
+    free(visit);
+  }
+}
+
+/* Prefill-time sparse attention.  The paper's Conclusion names it as the next step and defines
+ * nothing; the reading used here carries the decode-time rule (Section 3 "Per-head attention span",
+ * Section 4 "Beyond top-k", Section 5 "Batched queries") over to a block of Tq consecutive prompt
+ * tokens.  The query of token t of sequence s stands at position p = pos0[s] + t and sees, of the keys
+ * at positions n <= p (causal, its own key included), with L = p + 1 keys so far:
+ *     n < n_sink,  or  n >= L - n_recent,  or  ids[n] in the token's list selected[s,h,t,:],
+ * one list per token and KV head, shared by the G heads of the group.  Position-ordered tensors, no index:
+ * q [S,Tq,Hq,d], K,V [S,Hkv,Nt,d], ids [S,Hkv,Nt], selected [S,Hkv,Tq,nprobe], pos0 [S] with
+ * pos0 + Tq <= Nt; out [S,Tq,Hq,d], lse [S,Tq,Hq]. */
+void ref_prefill_sparse_attention(const float* q, const float* K, const float* V, const int32_t* ids,
+                                  const int32_t* selected, const int32_t* pos0, int nprobe, int n_sink,
+                                  int n_recent, float scale, double* out, double* lse, int S, int Hq,
+                                  int Hkv, int Tq, int Nt, int B, int d) {
+  int G = Hq / Hkv;
+  long rows = (long)S * Tq * Hq;
+#pragma omp parallel for num_threads(g_threads) schedule(dynamic)
+  for (long r = 0; r < rows; ++r) {
+    int hq = (int)(r % Hq), t = (int)((r / Hq) % Tq), s = (int)(r / ((long)Hq * Tq)), h = hq / G;
+    size_t u = (size_t)s * Hkv + h;
+    int L = pos0[s] + t + 1;                       /* keys the token can see at all */
+    const int32_t* sel = selected + (u * Tq + t) * nprobe;
+    char* visit = (char*)calloc((size_t)B, 1);
+    for (int j = 0; j < nprobe; ++j) visit[sel[j]] = 1;
+    int32_t* members = (int32_t*)malloc(sizeof(int32_t) * (size_t)(L > 0 ? L : 1));
+    long c = 0;
+    for (int n = 0; n < L; ++n) {
+      int b = ids[u * Nt + n];
+      if (n < n_sink || n >= L - n_recent || (b >= 0 && b < B && visit[b])) members[c++] = n;
+    }
+    attend_list(q + (size_t)r * d, K + u * Nt * d, V + u * Nt * d, members, c, (double)scale, d,
+                out + (size_t)r * d, lse ? lse + r : NULL);
     free(members);
     free(visit);
   }

@@ -32,6 +32,10 @@ MISTAKES = [
      "const int32_t* sel = selected + u * nprobe;\n    long count = 0;"),
     ("windowed attention: recent window one key short",
      "if (n < n_sink || n >= Nt - n_recent ||", "if (n < n_sink || n > Nt - n_recent ||"),
+    ("prefill attention: a token does not see its own key",
+     "int L = pos0[s] + t + 1;", "int L = pos0[s] + t;"),
+    ("prefill attention: every token reads the list of the block's first token",
+     "const int32_t* sel = selected + (u * Tq + t) * nprobe;", "const int32_t* sel = selected + (u * Tq) * nprobe;"),
     ("window_push: displaced row taken from the neighbouring slot", "ix[dst] = ix[j];", "ix[dst] = ix[j > 0 ? j - 1 : j];"),
     ("recompact_index: resident run shrunk to its occupied slots",
      "if (resident) on[B + 1] = on[B] + (o[B + 1] - o[B]);", "if (resident) on[B + 1] = on[B] + l[B];"),
