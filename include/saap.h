@@ -79,7 +79,8 @@ enum {
   SAAP_OP_BUCKET_ATTENTION_MASS = 8,
   SAAP_OP_QUERY_MODEL_LOSS_GRADS = 9,  /* shape: Hkv = weight sets, N = rows per set, d, hidden, B */
   SAAP_OP_BUCKET_ATTENTION_MASS_BATCH = 10,  /* shape: S, Hkv, N = queries per KV head, B */
-  SAAP_OP_PLANNED_DECODE_ATTENTION = 11      /* shape: S, Hq, Hkv, mode */
+  SAAP_OP_PLANNED_DECODE_ATTENTION = 11,     /* shape: S, Hq, Hkv, mode */
+  SAAP_OP_PREFILL_SPARSE_ATTENTION = 12      /* shape: S, Hq, Hkv, N = query tokens per sequence (Tq), nprobe */
 };
 
 #define SAAP_WS_HEADER_BYTES 65536u
@@ -647,6 +648,40 @@ int32_t saap_planned_decode_attention_fp8(const void* q, const uint8_t* K8, cons
                                           void* out, int32_t out_dtype, float* lse,
                                           int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t d,
                                           void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * prefill_sparse_attention -- sparse attention for a block of prompt tokens.  The paper's Conclusion
+ * names prefill-time sparse attention as the next step and defines nothing; this call carries the
+ * decode-time rule (Section 3 "Per-head attention span": attention sink and recent keys are always
+ * attended; Section 4 "Beyond top-k": every key of the listed buckets; Section 5 "Batched queries":
+ * one list for the G heads of a group) over to every token of the block:
+ *   the query of token t of sequence s stands at position p = pos0[s] + t and attends, of the
+ *   L = p + 1 keys at positions n <= p (causal, its own key included), those with
+ *       n < n_sink,  or  n >= L - n_recent,  or  bucket(n) in selected[s,h,t,:].
+ *   q [S,Tq,Hq,d] dtype (after RoPE), token-major as activations are
+ *   K, V [S,Hkv,Nt,d] dtype: the prompt's keys and values in position order (pos0 + Tq <= Nt)
+ *   Ksorted, Vsorted [S,Hkv,Ncap,d], off, len, idx: the bucket index over those Nt keys (or over
+ *     more of the prompt: members at positions > p are not attended), as saap_build_bucket_index wrote it
+ *   selected [S,Hkv,Tq,nprobe] int32: one list per token and KV head (distinct ids inside [0,B))
+ *   pos0 [S] int32, device;  out [S,Tq,Hq,d] of out_dtype;  lse [S,Tq,Hq] fp32 or NULL
+ * Sink and recent keys are read from K, V; of a listed bucket only the members between them are
+ * read from the sorted cache (they form one stretch of the bucket's rows, the members being
+ * stored in ascending position).  Every (token, KV head) pair gets a visit plan and the keys of all
+ * pairs are dealt to the workgroups in equal shares, as saap_planned_decode_attention does: the
+ * tokens of a block see very different numbers of keys.
+ * Limits: S*Tq*Hkv <= 4096 per call (longer blocks are split by the caller); the limits of
+ * saap_planned_decode_attention with nruns = nprobe + 2.
+ * Workspace: SAAP_OP_PREFILL_SPARSE_ATTENTION (S, Hq, Hkv, N = Tq, nprobe).
+ */
+int32_t saap_prefill_sparse_attention(const void* q, const void* K, const void* V,
+                                      const void* Ksorted, const void* Vsorted,
+                                      const int32_t* off, const int32_t* len, const int32_t* idx,
+                                      const int32_t* selected, const int32_t* pos0,
+                                      int32_t nprobe, int32_t n_sink, int32_t n_recent, float scale,
+                                      void* out, int32_t out_dtype, float* lse,
+                                      int32_t S, int32_t Hq, int32_t Hkv, int32_t Tq, int32_t Nt, int32_t Ncap,
+                                      int32_t B, int32_t d, int32_t dtype,
+                                      void* ws, size_t ws_bytes, void* stream);
 
 /*
  * append_keys_fp8 / window_push_fp8 -- saap_append_keys and saap_window_push on an 8-bit cache:

@@ -17,7 +17,7 @@ PROBS, LOGITS = 0, 1
 OP_ASSIGN_KEYS, OP_BUILD_BUCKET_INDEX, OP_CLASSIFY_QUERIES, OP_SELECT_BUCKETS = 0, 1, 2, 3
 OP_SPARSE_DECODE_ATTENTION, OP_DENSE_DECODE_ATTENTION, OP_APPEND_KEYS, OP_WINDOW_PUSH = 4, 5, 6, 7
 OP_BUCKET_ATTENTION_MASS, OP_QUERY_MODEL_LOSS_GRADS, OP_BUCKET_ATTENTION_MASS_BATCH = 8, 9, 10
-OP_PLANNED_DECODE_ATTENTION = 11
+OP_PLANNED_DECODE_ATTENTION, OP_PREFILL_SPARSE_ATTENTION = 11, 12
 WS_HEADER_BYTES = 65536
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -37,6 +37,7 @@ EXPORTS = (
     "saap_bucket_attention_mass_batch", "saap_query_model_bn_loss_grads", "saap_fold_batch_norm",
     "saap_build_visit_plan", "saap_select_buckets_planned", "saap_planned_decode_attention",
     "saap_planned_decode_attention_fp8", "saap_visit_plan_bytes", "saap_sparse_decode_attention_noalloc",
+    "saap_prefill_sparse_attention",
 )
 
 
@@ -423,6 +424,28 @@ def planned_decode_attention_fp8(q, K8, V8, kscale, vscale, plan, nruns, scale, 
         ctypes.c_float(scale), _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S), _i32(Hq), _i32(Hkv), _i32(Ncap),
         _i32(d), _ptr(ws), wsb, _stream())
     _check("saap_planned_decode_attention_fp8", st)
+    return out, lse
+
+
+def prefill_sparse_attention(q, K, V, Ks, Vs, off, ln, idx, selected, pos0, n_sink, n_recent, scale,
+                             out_dtype=torch.float32, out=None, lse=None, ws=None):
+    """q [S,Tq,Hq,d]; position-ordered K,V [S,Hkv,Nt,d]; Ks,Vs,off,ln,idx from build_bucket_index over them;
+    selected int32 [S,Hkv,Tq,nprobe]; pos0 int32 [S] -> out [S,Tq,Hq,d], lse fp32 [S,Tq,Hq]."""
+    S, Tq, Hq, d = q.shape
+    _, Hkv, Nt, _ = K.shape
+    Ncap = Ks.shape[2]
+    B = ln.shape[2]
+    nprobe = selected.shape[3]
+    dev = q.device
+    out = out if out is not None else torch.empty(S, Tq, Hq, d, dtype=out_dtype, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Tq, Hq, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_PREFILL_SPARSE_ATTENTION, dev, ws, S=S, Hq=Hq, Hkv=Hkv, N=Tq, nprobe=nprobe)
+    st = load_library().saap_prefill_sparse_attention(
+        _ptr(q), _ptr(K), _ptr(V), _ptr(Ks), _ptr(Vs), _ptr(off), _ptr(ln), _ptr(idx),
+        _ptr(selected) if nprobe > 0 else ctypes.c_void_p(0), _ptr(pos0), _i32(nprobe), _i32(n_sink), _i32(n_recent),
+        ctypes.c_float(scale), _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S), _i32(Hq), _i32(Hkv), _i32(Tq),
+        _i32(Nt), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _ptr(ws), wsb, _stream())
+    _check("saap_prefill_sparse_attention", st)
     return out, lse
 
 

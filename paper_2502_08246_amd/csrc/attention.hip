@@ -818,6 +818,10 @@ struct PlanParams {
   unsigned long long* counters;   // [units * cstride] arrivals; zero on entry and on exit
   int cstride;            // 8-byte words between the counters of two units
   long long rows;         // rows per kv unit
+  const void* K2;         // second pair of tensors [kv units, rows2, d] or null: plan rows from `rows` on mean row - rows of
+  const void* V2;         // these (prefill: the position-ordered keys beside the bucket-sorted ones)
+  long long rows2;
+  int tq;                 // units of one sequence that share a kv unit (query tokens per sequence; 1 at decode)
   int nseg;               // runs per unit in the plan
   int ps;                 // ints per unit in the plan
   int n_units;
@@ -1049,11 +1053,15 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
       kvu = s * p.Hkv + hq / (p.Hq / p.Hkv);
       qrow0 = u;
     } else {
-      kvu = u;
+      kvu = p.tq == 1 ? u : (u / (p.Hkv * p.tq)) * p.Hkv + u % p.Hkv;   // units are (sequence, token, KV head)
       qrow0 = u * G;
     }
     const T* Kb = reinterpret_cast<const T*>(p.K) + (size_t)kvu * p.rows * kD + sub * 8;
     const T* Vb = reinterpret_cast<const T*>(p.V) + (size_t)kvu * p.rows * kD + sub * 8;
+    // rows of the second pair of tensors, addressed so that plan row r >= p.rows lands on its row r - p.rows
+    const T* Kb2 = reinterpret_cast<const T*>(p.K2) + ((size_t)kvu * p.rows2 - (size_t)p.rows) * kD + sub * 8;
+    const T* Vb2 = reinterpret_cast<const T*>(p.V2) + ((size_t)kvu * p.rows2 - (size_t)p.rows) * kD + sub * 8;
+    const int row_end = (int)(p.rows + p.rows2);
     Vec8<TQ> qv[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) qv[g].load(reinterpret_cast<const TQ*>(p.q) + (size_t)(qrow0 + g) * kD + sub * 8);
@@ -1121,7 +1129,7 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
         row = rowoff[j] + (v - pre[j]);
         // a plan that breaks the contract (overlapping runs, a damaged index) must not turn into a
         // read outside the cache
-        row = min(max(row, 0), (int)p.rows - 1);
+        row = min(max(row, 0), row_end - 1);
       }
       bt.valid = 0u;
       bt.heads = 0u;
@@ -1132,8 +1140,9 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
         // branch would make the number of loads in flight unknown to the wait counters, and every wait
         // would then drain them all
         if (base + i * 4 + grp < b) bt.valid |= 1u << i;
-        bt.k[i].load_stream(Kb + (size_t)r * kD);
-        bt.v[i].load_stream(Vb + (size_t)r * kD);
+        const bool second = r >= (int)p.rows;
+        bt.k[i].load_stream((second ? Kb2 : Kb) + (size_t)r * kD);
+        bt.v[i].load_stream((second ? Vb2 : Vb) + (size_t)r * kD);
       }
     };
     auto consume = [&](const Batch<T, KB>& bt) { consume_batch<T, G, false>(bt, qv, scale_log2, sub, m, l, O); };
@@ -1272,7 +1281,8 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
   const int npend = s_npend;
   for (int i = 0; i < npend; ++i) {
     const int mu = s_pend[i][0], slot0 = s_pend[i][1], P = s_pend[i][2], kind = s_pend[i][3];
-    const int kvu = p.independent ? (mu / p.Hq) * p.Hkv + (mu % p.Hq) / (p.Hq / p.Hkv) : mu;
+    const int kvu = p.independent ? (mu / p.Hq) * p.Hkv + (mu % p.Hq) / (p.Hq / p.Hkv)
+                                  : p.tq == 1 ? mu : (mu / (p.Hkv * p.tq)) * p.Hkv + mu % p.Hkv;
     const int qrow0 = p.independent ? mu : mu * G;
     float vs = 1.f;
     if constexpr (kFp8) vs = p.vscale[kvu];
@@ -1325,6 +1335,80 @@ __global__ void __launch_bounds__(256) visit_plan_kernel(const int32_t* __restri
     run += max(lenu[b], 0);
     pl[2 + j] = run;
     pl[nseg + 2 + j] = offu[b];
+  }
+  if (tid == 0) {
+    pl[0] = total;
+    pl[1] = 0;
+  }
+}
+
+// Visit plans of a block of prompt tokens: one workgroup per (sequence, token, KV head).  The token at
+// position p sees, of the L = p + 1 keys so far, the first n_sink, the last n_recent and the members of its
+// listed buckets.  Runs of its plan: [0] the sink keys and [1] the recent keys, read from the position-ordered
+// tensors (plan rows from Ncap on), then one run per listed bucket: those members of the bucket that lie
+// between the sink and the recent keys.  The members of a bucket are stored in ascending position, so that
+// part is one stretch of the bucket's rows, found by two binary searches in `idx`.
+__global__ void __launch_bounds__(256) prefill_plan_kernel(const int32_t* __restrict__ selected, const int32_t* __restrict__ off,
+                                                          const int32_t* __restrict__ len, const int32_t* __restrict__ idx,
+                                                          const int32_t* __restrict__ pos0, int32_t* __restrict__ plan,
+                                                          int nprobe, int n_sink, int n_recent, int B, int Ncap, int Nt,
+                                                          int Tq, int Hkv, int ps) {
+  __shared__ int s_wsum[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int unit = blockIdx.x;                            // (s * Tq + t) * Hkv + h
+  const int h = unit % Hkv, t = (unit / Hkv) % Tq, s = unit / (Hkv * Tq);
+  const int kvu = s * Hkv + h;
+  const int L = min(max(pos0[s] + t + 1, 0), Nt);         // keys the token can see at all
+  const int sink_end = min(n_sink, L);                    // positions [0, sink_end) are the sink
+  const int recent_begin = max(sink_end, L - n_recent);   // positions [recent_begin, L) the recent keys
+  const int nseg = nprobe + 2;
+  const int32_t* lenu = len + (size_t)kvu * B;
+  const int32_t* offu = off + (size_t)kvu * (B + 1);
+  const int32_t* idxu = idx + (size_t)kvu * Ncap;
+  const int32_t* sel = selected + ((size_t)kvu * Tq + t) * nprobe;
+  int32_t* pl = plan + (size_t)unit * ps;
+  // first member of the run at `first` (n members, ascending positions) whose position is not below `bound`
+  auto lower = [&](int first, int n, int bound) {
+    int lo = 0, hi = n;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (idxu[first + mid] < bound) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+  };
+  const int per = (nseg + 255) / 256;
+  const int j0 = tid * per, j1 = min(j0 + per, nseg);
+  int mine = 0;
+  for (int j = j0; j < j1; ++j) {
+    int first, n;
+    if (j == 0) {
+      first = Ncap;
+      n = sink_end;
+    } else if (j == 1) {
+      first = Ncap + recent_begin;
+      n = L - recent_begin;
+    } else {
+      const int b = min(max(sel[j - 2], 0), B - 1);
+      const int o = offu[b], m = max(lenu[b], 0);
+      const int lo = lower(o, m, sink_end), hi = lower(o, m, recent_begin);
+      first = o + lo;
+      n = max(hi - lo, 0);
+    }
+    pl[nseg + 2 + j] = first;
+    pl[2 + j] = n;                                        // its length for now; the prefix below
+    mine += n;
+  }
+  const int incl = (int)wave_prefix_sum((unsigned)mine);
+  if (lane == 63) s_wsum[wave] = incl;
+  __syncthreads();
+  int run = incl - mine, total = 0;
+  for (int x = 0; x < 4; ++x) {
+    if (x < wave) run += s_wsum[x];
+    total += s_wsum[x];
+  }
+  for (int j = j0; j < j1; ++j) {
+    run += pl[2 + j];
+    pl[2 + j] = run;
   }
   if (tid == 0) {
     pl[0] = total;
@@ -1470,6 +1554,7 @@ int32_t launch_attn(const AttnParams& p, const LaunchPlan& lp, int G, int dtype,
 size_t attn_workspace_bytes(long long units, int G) {
   return (size_t)SAAP_WS_HEADER_BYTES + (size_t)units * kMaxP * G * (kD + 2) * sizeof(float);
 }
+size_t prefill_workspace_bytes(long long S, int Tq, int Hq, int Hkv, int nprobe);
 // ... of the planned attention: one partial result per (workgroup, unit) pair that meets
 size_t planned_workspace_bytes(long long units, int G) {
   return (size_t)SAAP_WS_HEADER_BYTES + (size_t)(kPlanMaxWgs + units) * G * (kD + 2) * sizeof(float);
@@ -1542,10 +1627,13 @@ static int32_t launch_planned(const PlanParams& p, int G, unsigned grid, size_t 
   return SAAP_UNSUPPORTED;
 }
 
+// K2, V2 (or null) with rows2 rows per (sequence, KV head): plan rows from Ncap on.  tq > 1: S counts
+// (sequence, token) pairs of which tq consecutive ones share the (sequence, KV head) tensors.
 static int32_t planned_attention(const void* q, const void* Ksorted, const void* Vsorted, const float* kscale,
                                  const float* vscale, const int32_t* plan, int32_t nruns, int32_t mode, float scale,
                                  void* out, int32_t out_dtype, float* lse, int32_t S, int32_t Hq, int32_t Hkv,
-                                 int32_t Ncap, int32_t d, int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
+                                 int32_t Ncap, int32_t d, int32_t dtype, void* ws, size_t ws_bytes, void* stream,
+                                 const void* K2 = nullptr, const void* V2 = nullptr, int32_t rows2 = 0, int32_t tq = 1) {
   int32_t st = check_common(q, Ksorted, Vsorted, out, S, Hq, Hkv, d, dtype, out_dtype, ws);
   if (st != SAAP_OK) return st;
   if (!plan || !aligned16(plan)) return SAAP_INVALID_ARG;
@@ -1557,7 +1645,10 @@ static int32_t planned_attention(const void* q, const void* Ksorted, const void*
   const long long units = plan_units(S, Hq, Hkv, mode);
   const int ps = plan_stride(nruns);
   // every unit's keys are numbered in one 32-bit range
-  if (units > kPlanMaxUnits || ps > kPlanTableInts || units * ((long long)Ncap + 65536) >= (1ll << 31)) return SAAP_UNSUPPORTED;
+  if (units > kPlanMaxUnits || ps > kPlanTableInts || units * ((long long)Ncap + rows2 + 65536) >= (1ll << 31))
+    return SAAP_UNSUPPORTED;
+  if (K2 && (!V2 || !aligned16(K2) || !aligned16(V2) || rows2 <= 0 || tq < 1 || S % tq != 0 || mode != SAAP_GROUP_SUM))
+    return SAAP_INVALID_ARG;
   if (ws_bytes < planned_workspace_bytes(units, G)) return SAAP_WORKSPACE_TOO_SMALL;
 
   long long W = device_cus();
@@ -1573,6 +1664,7 @@ static int32_t planned_attention(const void* q, const void* Ksorted, const void*
   p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   p.part_o = p.part_ml + (size_t)(kPlanMaxWgs + units) * G * 2;
   p.rows = Ncap; p.nseg = nruns; p.ps = ps; p.n_units = (int)units; p.Hq = Hq; p.Hkv = Hkv;
+  p.K2 = K2 ? K2 : Ksorted; p.V2 = K2 ? V2 : Vsorted; p.rows2 = K2 ? rows2 : 0; p.tq = tq;
   p.independent = indep ? 1 : 0; p.out_bf16 = out_dtype == SAAP_BF16;
   p.q_min = env_int("SAAP_PLAN_QMIN", (NT / 16) * (G == 8 ? 2 : 4));     // one batch of every wave
   p.piece_cost = env_int("SAAP_PLAN_PIECE_COST", 128);
@@ -1829,4 +1921,40 @@ extern "C" int32_t saap_sparse_decode_attention_noalloc(const void* q, const voi
   if (st != SAAP_OK) return st;
   return sparse_attention(q, Ksorted, Vsorted, nullptr, nullptr, off, len, selected, nprobe, mode, -1, scale, out,
                           out_dtype, lse, S, Hq, Hkv, Ncap, B, d, dtype, ws, SAAP_STATIC_SCRATCH_BYTES, stream);
+}
+
+// ---- prefill-time sparse attention: per-token visit plans, then the planned attention ----------------
+size_t saap::prefill_workspace_bytes(long long S, int Tq, int Hq, int Hkv, int nprobe) {
+  const long long units = S * Tq * Hkv;
+  return planned_workspace_bytes(units, Hq / Hkv) + (size_t)units * plan_stride(nprobe + 2) * sizeof(int32_t);
+}
+
+extern "C" int32_t saap_prefill_sparse_attention(const void* q, const void* K, const void* V, const void* Ksorted,
+                                                 const void* Vsorted, const int32_t* off, const int32_t* len,
+                                                 const int32_t* idx, const int32_t* selected, const int32_t* pos0,
+                                                 int32_t nprobe, int32_t n_sink, int32_t n_recent, float scale,
+                                                 void* out, int32_t out_dtype, float* lse, int32_t S, int32_t Hq,
+                                                 int32_t Hkv, int32_t Tq, int32_t Nt, int32_t Ncap, int32_t B,
+                                                 int32_t d, int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
+  if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
+  int32_t st = check_common(q, Ksorted, Vsorted, out, S, Hq, Hkv, d, dtype, out_dtype, ws);
+  if (st != SAAP_OK) return st;
+  if (!K || !V || !off || !len || !idx || !pos0 || (nprobe > 0 && !selected) || !aligned16(K) || !aligned16(V))
+    return SAAP_INVALID_ARG;
+  if (Tq <= 0 || Nt <= 0 || Ncap <= 0 || B <= 0 || nprobe < 0 || nprobe > B || n_sink < 0 || n_recent < 0)
+    return SAAP_INVALID_ARG;
+  if (nprobe + 2 > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
+  const long long units = (long long)S * Tq * Hkv;
+  if (units > kPlanMaxUnits) return SAAP_UNSUPPORTED;
+  if (ws_bytes < prefill_workspace_bytes(S, Tq, Hq, Hkv, nprobe)) return SAAP_WORKSPACE_TOO_SMALL;
+  const int ps = plan_stride(nprobe + 2);
+  const size_t att_bytes = planned_workspace_bytes(units, Hq / Hkv);
+  int32_t* plan = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + att_bytes);
+  hipLaunchKernelGGL(prefill_plan_kernel, dim3((unsigned)units), dim3(256), 0, static_cast<hipStream_t>(stream), selected,
+                     off, len, idx, pos0, plan, nprobe, n_sink, n_recent, B, Ncap, Nt, Tq, Hkv, ps);
+  st = launch_status();
+  if (st != SAAP_OK) return st;
+  return planned_attention(q, Ksorted, Vsorted, nullptr, nullptr, plan, nprobe + 2, SAAP_GROUP_SUM, scale, out, out_dtype,
+                           lse, S * Tq, Hq, Hkv, Ncap, d, dtype, ws, att_bytes, stream, K, V, Nt, Tq);
 }

@@ -6,6 +6,7 @@ namespace saap {
 
 size_t attn_workspace_bytes(long long units, int G);
 size_t planned_workspace_bytes(long long units, int G);
+size_t prefill_workspace_bytes(long long S, int Tq, int Hq, int Hkv, int nprobe);
 size_t assign_workspace_bytes(long long rows);
 size_t build_workspace_bytes(long long units, int N, int B);
 size_t push_workspace_bytes(long long units, int B);
@@ -79,6 +80,9 @@ extern "C" size_t saap_workspace_bytes(int32_t op, const saap_shape* sh) {
       const bool indep = sh->mode == SAAP_INDEPENDENT;
       return planned_workspace_bytes(indep ? S * Hq : S * Hkv, indep ? 1 : (int)(Hq / Hkv));
     }
+    case SAAP_OP_PREFILL_SPARSE_ATTENTION:
+      if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || sh->N <= 0 || sh->nprobe < 0) return 0;
+      return prefill_workspace_bytes(S, sh->N, (int)Hq, (int)Hkv, sh->nprobe);
     case SAAP_OP_DENSE_DECODE_ATTENTION:
       if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv) return 0;
       return attn_workspace_bytes(S * Hkv, (int)(Hq / Hkv));
