@@ -63,6 +63,10 @@ def parse():
                          "list; plan: the selection writes the visit plan and the attention deals all lists' keys to "
                          "the workgroups in equal shares (slower on the benchmark workloads, robust to lists of "
                          "very different sizes)")
+    ap.add_argument("--mixed-lengths", action="store_true",
+                    help="batched workloads: the sequences hold N, N, N/2, N/2, N/4, N/4, ... keys instead of N each "
+                         "(a serving batch of mixed context lengths; the keys beyond a sequence's length are left out "
+                         "of its index), which makes the lists of the batch very unequal")
     ap.add_argument("--no-fixed-cost", action="store_true",
                     help="skip the fixed-cost launches (same kernel, next to no bytes), so that a profiler's per-kernel "
                          "average covers real launches only")
@@ -165,13 +169,20 @@ def main():
     torch.cuda.synchronize()
     ws = saap.workspace(0, dev)
     rescored = int(ws[65536 + 16380:65536 + 16384].view(torch.int32).item())   # diagnostic word of assign_keys
+    seq_lengths = [cfg.N] * cfg.S
+    if args.mixed_lengths:
+        # an id outside [0,B) keeps a key out of the index: sequence s keeps its first N >> (s // 2) keys
+        seq_lengths = [max(cfg.N >> (s // 2), 1) for s in range(cfg.S)]
+        ids = ids.clone()
+        for s_i, n_s in enumerate(seq_lengths):
+            ids[s_i, :, n_s:] = -1
     index = saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, args.slack)
     torch.cuda.synchronize()
     ms_assign = timed(lambda i: saap.assign_keys(cache["x_keys"], cent, out=ids), 3, torch)
     ms_build = timed(lambda i: saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, args.slack), 3, torch)
     off, ln, idx, Ks, Vs = index
-    n_keys_total = cfg.S * cfg.Hkv * cfg.N
-    assign_flop = 2.0 * n_keys_total * cfg.B * cfg.d
+    n_keys_total = cfg.Hkv * sum(seq_lengths)
+    assign_flop = 2.0 * cfg.S * cfg.Hkv * cfg.N * cfg.B * cfg.d          # assign_keys ran on every key
     window = None
     if args.window:
         # the same cache indexed with a resident run (sink + recent keys); the step then also pushes
@@ -503,6 +514,7 @@ def main():
                      "classify_queries (logits) + select_buckets_from_logits + sparse_decode_attention")
                     + (" + append_keys" if with_append else ""),
             "slack": args.slack, "launch": "hip graph", "path": args.path,
+            "sequence_lengths": seq_lengths if args.mixed_lengths else None,
         },
         "roofline": {
             "kernel": ("attn_plan_kernel<bf16,G=4> (planned_decode_attention, partials + merge)" if planned else
