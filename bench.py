@@ -63,6 +63,10 @@ def parse():
                          "list; plan: the selection writes the visit plan and the attention deals all lists' keys to "
                          "the workgroups in equal shares (slower on the benchmark workloads, robust to lists of "
                          "very different sizes)")
+    ap.add_argument("--route", choices=["fused", "separate"], default="separate",
+                    help="separate (default): classify_queries and the selection as two calls; fused: classify_select, "
+                         "which at batch 1 runs the selection inside the classifier's output launch (measured no faster: "
+                         "13.5 against 13.1 us at the 128k workload)")
     ap.add_argument("--mixed-lengths", action="store_true",
                     help="batched workloads: the sequences hold N, N, N/2, N/2, N/4, N/4, ... keys instead of N each "
                          "(a serving batch of mixed context lengths; the keys beyond a sequence's length are left out "
@@ -238,9 +242,16 @@ def main():
         saap.append_keys(a_x[i % T], a_k[i % T], a_v[i % T], a_pos[i % T], cent, None, off, ln, idx, Ks, Vs,
                          overflow_flag=a_flag, new_ids=a_ids)
 
+    def route(i):
+        saap.classify_select(xq[i % T], W1, b1, W2, b2, cfg.Hkv, cfg.nprobe, off=off, ln=ln, logits=scores, out=sel,
+                             plan=plan if planned else None)
+
     def step(i):
-        classify(i)
-        select(i)
+        if args.route == "fused":
+            route(i)
+        else:
+            classify(i)
+            select(i)
         attend(i)
         if with_append:
             append(i)
@@ -291,6 +302,7 @@ def main():
     spread = np.percentile(np.array(g_attn.replay_ms_per_call(max(reps, 20))) * 1e3, [10, 50, 90])
     ms_classify = GraphLoop(classify, T, torch).timed_ms_per_call(reps)
     ms_select = GraphLoop(select, T, torch).timed_ms_per_call(reps)
+    ms_route = GraphLoop(route, T, torch).timed_ms_per_call(reps)
     ms_append = GraphLoop(append, T, torch).timed_ms_per_call(2) if with_append else None
     ms_dense = None if args.no_dense else GraphLoop(dense, 8, torch).timed_ms_per_call(3)
     # Fixed cost of the attention launch: the same call on the same lists with every bucket one key long, i.e.
@@ -510,10 +522,11 @@ def main():
         "config": {
             "workload": cfg.name, "S": cfg.S, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "d": cfg.d, "N": cfg.N, "B": cfg.B,
             "nprobe": cfg.nprobe, "classifier": f"{cfg.d}->{cfg.hidden}->{cfg.B}", "query_sets": T,
-            "step": ("classify_queries (logits) + select_buckets_planned + planned_decode_attention" if planned else
-                     "classify_queries (logits) + select_buckets_from_logits + sparse_decode_attention")
+            "step": (("classify_select" if args.route == "fused" else
+                      "classify_queries (logits) + " + ("select_buckets_planned" if planned else "select_buckets_from_logits"))
+                     + (" + planned_decode_attention" if planned else " + sparse_decode_attention"))
                     + (" + append_keys" if with_append else ""),
-            "slack": args.slack, "launch": "hip graph", "path": args.path,
+            "slack": args.slack, "launch": "hip graph", "path": args.path, "route": args.route,
             "sequence_lengths": seq_lengths if args.mixed_lengths else None,
         },
         "roofline": {
@@ -539,6 +552,7 @@ def main():
         "breakdown_us": {
             "classify_queries_logits": round(ms_classify * 1e3, 3),
             "select_buckets_from_logits": round(ms_select * 1e3, 3),
+            "classify_select": round(ms_route * 1e3, 3),
             "sparse_decode_attention": round(ms_attn * 1e3, 3),
             "dense_decode_attention": None if ms_dense is None else round(ms_dense * 1e3, 3),
             "append_keys": None if ms_append is None else round(ms_append * 1e3, 3),

@@ -237,6 +237,28 @@ int32_t saap_select_buckets_from_logits(const float* logits, float* probs, int32
                                         int32_t mode, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * classify_select -- the routing of a decode step in one call: saap_classify_queries with SAAP_LOGITS
+ * followed by saap_select_buckets_from_logits (or, with `plan` != NULL, saap_select_buckets_planned)
+ * in SAAP_GROUP_SUM mode: f_q of Section 4 for every query head, its distributions summed over the
+ * heads of a group and the nprobe best buckets taken (Section 5 "Batched queries").  The results are
+ * those of the separate calls, bit for bit.
+ *   logits [S,Hq,B] fp32, out; probs [S,Hq,B] fp32 out or NULL; selected [S,Hkv,nprobe] int32, out
+ *   plan: NULL, or the visit plan of the lists (then off, len and resident_run as in
+ *   saap_select_buckets_planned); the remaining arguments as in saap_classify_queries.
+ * At batch 1 with one weight set per KV head (S = 1, Hw = Hkv, bf16, B <= 4096) the selection runs inside
+ * the classifier's output launch: the last workgroup of a weight set to finish selects its list, so the
+ * step has one launch less.  Every other shape takes the separate launches.
+ * Workspace: SAAP_OP_CLASSIFY_QUERIES.
+ */
+int32_t saap_classify_select(const void* xq, const void* W1, const float* b1,
+                             const void* W2, const float* b2, int32_t Hw,
+                             float* logits, float* probs, int32_t* selected,
+                             const int32_t* off, const int32_t* len, int32_t resident_run, int32_t* plan,
+                             int32_t S, int32_t Hq, int32_t Hkv, int32_t d, int32_t hidden, int32_t B,
+                             int32_t nprobe, int32_t dtype,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/*
  * sparse_decode_attention -- exact softmax attention over the union of the
  * selected buckets (Section 4 "Beyond top-k"; Appendix F Algorithms 1 and 2:
  * partial attention with a running maximum, then a log-sum-exp merge):

@@ -37,7 +37,7 @@ EXPORTS = (
     "saap_bucket_attention_mass_batch", "saap_query_model_bn_loss_grads", "saap_fold_batch_norm",
     "saap_build_visit_plan", "saap_select_buckets_planned", "saap_planned_decode_attention",
     "saap_planned_decode_attention_fp8", "saap_visit_plan_bytes", "saap_sparse_decode_attention_noalloc",
-    "saap_prefill_sparse_attention",
+    "saap_prefill_sparse_attention", "saap_classify_select",
 )
 
 
@@ -295,6 +295,31 @@ def classify_queries(xq, W1, b1, W2, b2, Hkv, output_kind=PROBS, out=None, ws=No
                                               _stream())
     _check("saap_classify_queries", st)
     return scores
+
+
+def classify_select(xq, W1, b1, W2, b2, Hkv, nprobe, off=None, ln=None, resident_run=-1, want_plan=False, logits=None,
+                    probs=None, out=None, plan=None, ws=None):
+    """classify_queries (logits) + the group selection in one call. -> (logits [S,Hq,B], selected [S,Hkv,nprobe], plan
+    or None).  want_plan (or plan=) also writes the lists' visit plan, which needs off and ln."""
+    S, Hq, d = xq.shape
+    Hw, hidden, _ = W1.shape
+    B = W2.shape[1]
+    if W2.shape != (Hw, B, hidden) or W1.dtype != xq.dtype or W2.dtype != xq.dtype:
+        raise ValueError("W1 [Hw,hidden,d] and W2 [Hw,B,hidden] must match xq's dtype")
+    dev = xq.device
+    logits = logits if logits is not None else torch.empty(S, Hq, B, dtype=torch.float32, device=dev)
+    sel = out if out is not None else torch.empty(S, Hkv, nprobe, dtype=torch.int32, device=dev)
+    if want_plan or plan is not None:
+        if off is None or ln is None:
+            raise ValueError("a visit plan needs off and ln")
+        plan = _plan_buffer(plan, S, Hq, Hkv, nprobe + (1 if resident_run >= 0 else 0), GROUP_SUM, dev)
+    ws, wsb = _ws(OP_CLASSIFY_QUERIES, dev, ws, S=S, Hq=Hq, hidden=hidden)
+    st = load_library().saap_classify_select(
+        _ptr(xq), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _i32(Hw), _ptr(logits), _ptr(probs), _ptr(sel), _ptr(off),
+        _ptr(ln), _i32(resident_run), _ptr(plan), _i32(S), _i32(Hq), _i32(Hkv), _i32(d), _i32(hidden), _i32(B),
+        _i32(nprobe), _i32(_dtype_code(xq)), _ptr(ws), wsb, _stream())
+    _check("saap_classify_select", st)
+    return logits, sel, plan
 
 
 def select_buckets(scores, Hkv, nprobe, mode=GROUP_SUM, out=None, ws=None):

@@ -20,7 +20,7 @@
 // that a workgroup's loads are all in flight together; matrix operands are read from LDS with a
 // padded row pitch (no bank conflicts).  fp32 weights use v_mfma_f32_16x16x4_f32 with operands
 // straight from memory (correctness configuration, not tuned).
-#include "common.h"
+#include "select_body.h"
 
 namespace saap {
 namespace {
@@ -121,10 +121,22 @@ constexpr int kOutChunk = 512;      // hidden units per LDS pass of the output k
 constexpr int kOutThreads = 512;
 constexpr int kOutLoads = 16 * 128 / kOutThreads;     // 16-byte loads of activations per thread
 
-template <int SLAB>
+// FUSED: the selection of the decode step runs in this launch.  At batch 1 with one weight set per KV head the
+// workgroups of a weight set produce exactly the logits of one bucket list; they store them write-through, count
+// their arrival, and the last one to arrive runs the selection of that list (softmax, group sum, top nprobe, visit
+// plan) on the spot, reading the logits past its XCD's L2.  One launch and its dependent wait less per step.
+struct FusedSelect {
+  unsigned* counters;     // one per weight set, a cache line apart, zero on entry and on exit
+  float* probs;           // [Hq,B] or null
+  int32_t* selected;      // [Hkv,nprobe]
+  int Hkv, nprobe, n_sort, cap, ept, expect;
+  PlanOut po;
+};
+
+template <int SLAB, bool FUSED>
 __global__ void __launch_bounds__(kOutThreads)
 mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W2, const float* __restrict__ b2,
-                    float* __restrict__ scores, MlpShape sh) {
+                    float* __restrict__ scores, MlpShape sh, FusedSelect fs) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int w, mt, slab;
@@ -248,21 +260,48 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
   f32x4_t* s_part = reinterpret_cast<f32x4_t*>(smem);   // [8 waves][64 lanes]
   s_part[wave * 64 + lane] = acc;
   __syncthreads();
-  if (wave >= kTiles) return;
-  acc = s_part[wave * 64 + lane];
+  if constexpr (!FUSED) {
+    if (wave >= kTiles) return;
+  }
+  if (wave < kTiles) {
+    acc = s_part[wave * 64 + lane];
 #pragma unroll
-  for (int j = 1; j < KQ; ++j) acc += s_part[(wave + kTiles * j) * 64 + lane];
-  SAAP_TRACE(2);
-  const int bucket = b0 + wave * 16 + rc;
-  if (bucket < sh.B) {
-    const float bo = b2 ? b2[(size_t)w * sh.B + bucket] : 0.f;
+    for (int j = 1; j < KQ; ++j) acc += s_part[(wave + kTiles * j) * 64 + lane];
+    SAAP_TRACE(2);
+    const int bucket = b0 + wave * 16 + rc;
+    if (bucket < sh.B) {
+      const float bo = b2 ? b2[(size_t)w * sh.B + bucket] : 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int mm = mt * 16 + 4 * kg + i;
-      if (mm < sh.rows_per_set) scores[(size_t)query_row(sh, w, mm) * sh.B + bucket] = acc[i] + bo;
+      for (int i = 0; i < 4; ++i) {
+        const int mm = mt * 16 + 4 * kg + i;
+        if (mm < sh.rows_per_set) {
+          float* dst = scores + (size_t)query_row(sh, w, mm) * sh.B + bucket;
+          if constexpr (FUSED) __hip_atomic_store(dst, acc[i] + bo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          else *dst = acc[i] + bo;
+        }
+      }
     }
   }
   SAAP_TRACE(3);
+  if constexpr (FUSED) {
+    __shared__ int s_is_last;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the logits are out
+    __syncthreads();
+    if (tid == 0) {
+      unsigned* c = fs.counters + (size_t)w * 32;
+      const unsigned old = __hip_atomic_fetch_add(c, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_is_last = old == (unsigned)(fs.expect - 1);
+      if (s_is_last) __hip_atomic_store(c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!s_is_last) return;
+    // weight set w = KV head w: its G rows of logits are complete
+    switch (fs.ept) {
+      case 2: select_radix_body<2, true, true>(smem, w, scores, fs.probs, fs.selected, sh.Hq, fs.Hkv, sh.B, fs.nprobe, 0, fs.n_sort, fs.cap, fs.po); break;
+      case 4: select_radix_body<4, true, true>(smem, w, scores, fs.probs, fs.selected, sh.Hq, fs.Hkv, sh.B, fs.nprobe, 0, fs.n_sort, fs.cap, fs.po); break;
+      default: select_radix_body<8, true, true>(smem, w, scores, fs.probs, fs.selected, sh.Hq, fs.Hkv, sh.B, fs.nprobe, 0, fs.n_sort, fs.cap, fs.po); break;
+    }
+  }
 }
 
 // ---- fp32 (correctness configuration): operands straight from memory ------------------------------
@@ -368,6 +407,53 @@ size_t classify_workspace_bytes(long long rows, int hidden) {
 
 using namespace saap;
 
+// The two launches of the bf16 two-layer model; with `fs` the output kernel also selects (see FusedSelect).
+static int32_t launch_mlp_bf16(const void* xq, const void* W1, const float* b1, const void* W2, const float* b2,
+                               float* scores, float* hbuf, const MlpShape& sh, const FusedSelect* fs, hipStream_t hs) {
+  const int hidden = sh.hidden, B = sh.B, Hw = sh.Hw;
+  const int m_tiles = sh.m_pad / 16;
+  const unsigned g1 = (unsigned)((hidden + 63) / 64) * m_tiles * Hw;
+  // 64 buckets per workgroup when 32 would give more than one workgroup per compute unit: every
+  // workgroup reads its rows of the hidden activations (as many bytes as a 32-bucket slab of W2 for a
+  // full 16-row tile), so fewer, wider workgroups move fewer bytes (batch 8: 11.5 -> 8.8 us)
+  const bool wide = (long long)((B + 31) / 32) * m_tiles * Hw > (long long)device_cus();
+  const int slab_rows = wide ? 64 : 32;
+  const unsigned g2 = (unsigned)((B + slab_rows - 1) / slab_rows) * m_tiles * Hw;
+  hipLaunchKernelGGL(mlp_hidden_bf16_kernel<false>, dim3(g1), dim3(256), 0, hs, static_cast<const bf16_t*>(xq),
+                     static_cast<const bf16_t*>(W1), b1, hbuf, sh);
+  const int chunk = hidden < kOutChunk ? hidden : kOutChunk;
+  const int h_rows = sh.rows_per_set < 16 ? sh.rows_per_set : 16;
+  size_t lds = (size_t)(3 * h_rows + slab_rows) * (chunk + 8) * sizeof(bf16_t);
+  const size_t lds_part = (size_t)kOutThreads * sizeof(f32x4_t);      // partial products of the eight waves
+  if (lds < lds_part) lds = lds_part;
+  FusedSelect f{};
+  if (fs) {
+    f = *fs;
+    f.expect = (int)((B + slab_rows - 1) / slab_rows);
+    const SelectGeometry geo = select_geometry(B, f.nprobe, f.po.off != nullptr, f.po.runs);
+    f.n_sort = geo.n_sort;
+    f.cap = geo.cap;
+    f.po.lds_off = geo.plan_off;
+    if (lds < geo.lds) lds = geo.lds;
+  }
+  const void* kern = fs ? (wide ? reinterpret_cast<const void*>(mlp_out_bf16_kernel<64, true>)
+                                : reinterpret_cast<const void*>(mlp_out_bf16_kernel<32, true>))
+                        : (wide ? reinterpret_cast<const void*>(mlp_out_bf16_kernel<64, false>)
+                                : reinterpret_cast<const void*>(mlp_out_bf16_kernel<32, false>));
+  if (lds > 48 * 1024) {
+    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return SAAP_HIP_ERROR;
+  }
+  const bf16_t* w2 = static_cast<const bf16_t*>(W2);
+  if (fs) {
+    if (wide) hipLaunchKernelGGL((mlp_out_bf16_kernel<64, true>), dim3(g2), dim3(kOutThreads), lds, hs, hbuf, w2, b2, scores, sh, f);
+    else hipLaunchKernelGGL((mlp_out_bf16_kernel<32, true>), dim3(g2), dim3(kOutThreads), lds, hs, hbuf, w2, b2, scores, sh, f);
+  } else {
+    if (wide) hipLaunchKernelGGL((mlp_out_bf16_kernel<64, false>), dim3(g2), dim3(kOutThreads), lds, hs, hbuf, w2, b2, scores, sh, f);
+    else hipLaunchKernelGGL((mlp_out_bf16_kernel<32, false>), dim3(g2), dim3(kOutThreads), lds, hs, hbuf, w2, b2, scores, sh, f);
+  }
+  return SAAP_OK;
+}
+
 extern "C" int32_t saap_classify_queries(const void* xq, const void* W1, const float* b1, const void* W2,
                                          const float* b2, int32_t Hw, float* scores, int32_t S, int32_t Hq,
                                          int32_t Hkv, int32_t d, int32_t hidden, int32_t B, int32_t dtype,
@@ -404,28 +490,8 @@ extern "C" int32_t saap_classify_queries(const void* xq, const void* W1, const f
                          static_cast<const float*>(W2), b2, scores, sh);
     }
   } else if (dtype == SAAP_BF16) {
-    const unsigned g1 = (unsigned)((hidden + 63) / 64) * m_tiles * Hw;
-    // 64 buckets per workgroup when 32 would give more than one workgroup per compute unit: every
-    // workgroup reads its rows of the hidden activations (as many bytes as a 32-bucket slab of W2 for a
-    // full 16-row tile), so fewer, wider workgroups move fewer bytes (batch 8: 11.5 -> 8.8 us)
-    const bool wide = (long long)((B + 31) / 32) * m_tiles * Hw > (long long)device_cus();
-    const int slab_rows = wide ? 64 : 32;
-    const unsigned g2 = (unsigned)((B + slab_rows - 1) / slab_rows) * m_tiles * Hw;
-    hipLaunchKernelGGL(mlp_hidden_bf16_kernel<false>, dim3(g1), dim3(256), 0, hs, static_cast<const bf16_t*>(xq),
-                       static_cast<const bf16_t*>(W1), b1, hbuf, sh);
-    const int chunk = hidden < kOutChunk ? hidden : kOutChunk;
-    const int h_rows = sh.rows_per_set < 16 ? sh.rows_per_set : 16;
-    size_t lds = (size_t)(3 * h_rows + slab_rows) * (chunk + 8) * sizeof(bf16_t);
-    const size_t lds_part = (size_t)kOutThreads * sizeof(f32x4_t);      // partial products of the eight waves
-    if (lds < lds_part) lds = lds_part;
-    auto kern = wide ? mlp_out_bf16_kernel<64> : mlp_out_bf16_kernel<32>;
-    if (lds > 48 * 1024) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)lds) != hipSuccess)
-        return SAAP_HIP_ERROR;
-    }
-    hipLaunchKernelGGL(kern, dim3(g2), dim3(kOutThreads), lds, hs, hbuf, static_cast<const bf16_t*>(W2), b2, scores,
-                       sh);
+    const int32_t st = launch_mlp_bf16(xq, W1, b1, W2, b2, scores, hbuf, sh, nullptr, hs);
+    if (st != SAAP_OK) return st;
   } else {
     const dim3 g1((unsigned)((hidden / 16 + 3) / 4), (unsigned)m_tiles, (unsigned)Hw);
     const dim3 g2((unsigned)((B / 16 + 3) / 4), (unsigned)m_tiles, (unsigned)Hw);
@@ -437,4 +503,62 @@ extern "C" int32_t saap_classify_queries(const void* xq, const void* W1, const f
   if (output_kind == SAAP_PROBS)
     hipLaunchKernelGGL(softmax_rows_kernel, dim3((unsigned)(S * Hq)), dim3(256), 0, hs, scores, B);
   return launch_status();
+}
+
+// classify_queries (logits) and the selection of the decode step in one call.  At batch 1 with one weight set per
+// KV head (the benchmark setting) the selection runs inside the classifier's output launch; any other shape takes the
+// separate calls, with the same results.
+extern "C" int32_t saap_classify_select(const void* xq, const void* W1, const float* b1, const void* W2,
+                                        const float* b2, int32_t Hw, float* logits, float* probs,
+                                        int32_t* selected, const int32_t* off, const int32_t* len,
+                                        int32_t resident_run, int32_t* plan, int32_t S, int32_t Hq, int32_t Hkv,
+                                        int32_t d, int32_t hidden, int32_t B, int32_t nprobe, int32_t dtype,
+                                        void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
+  const bool with_plan = plan != nullptr;
+  if (with_plan && (!off || !len || !aligned16(plan))) return SAAP_INVALID_ARG;
+  if (!logits || !selected || !aligned16(selected)) return SAAP_INVALID_ARG;
+  if (resident_run != -1 && resident_run != B) return SAAP_INVALID_ARG;
+  if (nprobe < 0 || nprobe > B) return SAAP_INVALID_ARG;
+  const int G = Hkv > 0 && Hq % Hkv == 0 ? Hq / Hkv : 0;
+  SelectGeometry geo = select_geometry(B > 0 ? B : 1, nprobe, false, 0);
+  const bool fusable = dtype == SAAP_BF16 && hidden > 0 && S == 1 && Hw == Hkv && B <= 8 * kOutThreads && nprobe > 0 &&
+                       geo.n_sort < geo.n_pow2 && (G == 1 || G == 2 || G == 4 || G == 8) &&
+                       (size_t)Hw * 128 <= SAAP_WS_HEADER_BYTES;
+  if (!fusable) {
+    int32_t st = saap_classify_queries(xq, W1, b1, W2, b2, Hw, logits, S, Hq, Hkv, d, hidden, B, dtype, SAAP_LOGITS, ws,
+                                       ws_bytes, stream);
+    if (st != SAAP_OK) return st;
+    if (with_plan)
+      return saap_select_buckets_planned(logits, SAAP_LOGITS, probs, off, len, resident_run, selected, plan, S, Hq, Hkv, B,
+                                         nprobe, SAAP_GROUP_SUM, ws, ws_bytes, stream);
+    return saap_select_buckets_from_logits(logits, probs, selected, S, Hq, Hkv, B, nprobe, SAAP_GROUP_SUM, ws, ws_bytes,
+                                           stream);
+  }
+  // the checks of saap_classify_queries
+  if (!xq || !W1 || !W2 || !ws) return SAAP_INVALID_ARG;
+  if (!aligned16(xq) || !aligned16(W1) || !aligned16(W2) || !aligned16(logits) || !aligned16(ws) || !aligned16(probs))
+    return SAAP_INVALID_ARG;
+  if (Hq <= 0 || Hkv <= 0 || B <= 0) return SAAP_INVALID_ARG;
+  if (d != kD || hidden % 32 != 0 || B % 16 != 0 || B > SAAP_MAX_BUCKETS || hidden > 1536) return SAAP_UNSUPPORTED;
+  MlpShape sh;
+  sh.S = S; sh.Hq = Hq; sh.Hw = Hw; sh.hidden = hidden; sh.B = B;
+  sh.rows_per_set = S * (Hq / Hw);
+  sh.m_pad = (sh.rows_per_set + 15) / 16 * 16;
+  const size_t need = (size_t)SAAP_WS_HEADER_BYTES + (size_t)Hw * sh.m_pad * hidden * sizeof(float);
+  if (ws_bytes < need) return SAAP_WORKSPACE_TOO_SMALL;
+  float* hbuf = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
+  FusedSelect fs{};
+  fs.counters = reinterpret_cast<unsigned*>(ws);
+  fs.probs = probs; fs.selected = selected; fs.Hkv = Hkv; fs.nprobe = nprobe;
+  fs.ept = B <= 2 * kOutThreads ? 2 : B <= 4 * kOutThreads ? 4 : 8;
+  if (with_plan) {
+    fs.po.off = off; fs.po.len = len; fs.po.plan = plan;
+    fs.po.runs = B + (resident_run >= 0 ? 1 : 0);
+    fs.po.resident = resident_run;
+    fs.po.ps = (2 * (nprobe + (resident_run >= 0 ? 1 : 0)) + 2 + 3) & ~3;
+  }
+  saap_trace_arm();
+  const int32_t st = launch_mlp_bf16(xq, W1, b1, W2, b2, logits, hbuf, sh, &fs, static_cast<hipStream_t>(stream));
+  return st != SAAP_OK ? st : launch_status();
 }
