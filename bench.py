@@ -184,6 +184,17 @@ def main():
     torch.cuda.synchronize()
     ms_assign = timed(lambda i: saap.assign_keys(cache["x_keys"], cent, out=ids), 3, torch)
     ms_build = timed(lambda i: saap.build_bucket_index(ids, cache["K"], cache["V"], cfg.B, args.slack), 3, torch)
+    # what the matrix pipes sustain on a bare loop of assign_keys' instruction: on the keys' own values (random
+    # bf16), on small integers and on zeros; the published peak is reached on none of them
+    mfma_probe = {}
+    probe_sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    probe_ops = {"keys": cache["x_keys"].reshape(-1)[: 1 << 20],
+                 "small_integers": torch.randint(-2, 3, (1 << 20,), device=dev).to(torch.bfloat16),
+                 "zeros": torch.zeros(1 << 20, dtype=torch.bfloat16, device=dev)}
+    for name, ops_t in probe_ops.items():
+        flop_box = [saap.mfma_rate_probe(ops_t, 4096, probe_sink)]      # untimed first launch
+        ms_p = timed(lambda i: flop_box.append(saap.mfma_rate_probe(ops_t, 4096, probe_sink)), 3, torch)
+        mfma_probe[name] = round(flop_box[-1] / (ms_p * 1e-3) / 1e12, 1)
     off, ln, idx, Ks, Vs = index
     n_keys_total = cfg.Hkv * sum(seq_lengths)
     assign_flop = 2.0 * cfg.S * cfg.Hkv * cfg.N * cfg.B * cfg.d          # assign_keys ran on every key
@@ -568,6 +579,7 @@ def main():
             "assign_keys_TFLOPs": round(assign_flop / (ms_assign * 1e-3) / 1e12, 1),
             "assign_keys_frac_of_bf16_mfma_peak": round(assign_flop / (ms_assign * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
             "assign_keys_rescored": rescored,
+            "mfma_32x32x16_bf16_bare_loop_TFLOPs_by_operand_values": mfma_probe,
             "build_bucket_index_ms": round(ms_build, 3),
             "build_bucket_index_GBps": round(2.0 * n_keys_total * BYTES_PER_KEY / (ms_build * 1e-3) / 1e9, 1),
         },

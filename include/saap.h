@@ -113,6 +113,16 @@ int32_t saap_device_compute_units(void);
  * beside the published HBM peak. */
 int32_t saap_stream_read_probe(const void* src, size_t bytes, void* sink, size_t sink_bytes, void* stream);
 
+/* Measurement aid, not part of the method: every wave of `wgs_per_cu` (1..8) four-wave workgroups per
+ * compute unit runs `iters` rounds of eight independent v_mfma_f32_32x32x16_bf16 (the instruction of
+ * assign_keys) on operands it reads once from `operands` (device, bf16 values, `bytes` >= 64, 16-byte
+ * aligned; lanes wrap around the buffer), with no other memory traffic.  `*flop_out` (host, may be
+ * NULL) receives the floating-point operations of the launch; the caller times it.  `sink` (device,
+ * >= 4 bytes) is written practically never.  The rate depends on the operand VALUES (the device
+ * lowers its clock under the switching activity of random data), which is what this call shows. */
+int32_t saap_mfma_rate_probe(const void* operands, size_t bytes, int32_t iters, int32_t wgs_per_cu, void* sink,
+                             double* flop_out /* host */, void* stream);
+
 /*
  * assign_keys -- prefill-time assignment of keys to buckets.
  * Section 2 ("Vector search based on partitions", indexing step) and Section 4:

@@ -27,7 +27,7 @@ _lib = None
 EXPORTS = (
     "saap_workspace_bytes", "saap_workspace_reset", "saap_status_string", "saap_device_compute_units",
     "saap_assign_keys", "saap_build_bucket_index", "saap_append_keys", "saap_classify_queries",
-    "saap_select_buckets", "saap_sparse_decode_attention", "saap_dense_decode_attention", "saap_stream_read_probe",
+    "saap_select_buckets", "saap_sparse_decode_attention", "saap_dense_decode_attention", "saap_stream_read_probe", "saap_mfma_rate_probe",
     "saap_build_windowed_index", "saap_window_push", "saap_windowed_decode_attention",
     "saap_append_keys_fp8", "saap_window_push_fp8",
     "saap_select_buckets_from_logits", "saap_update_centroids", "saap_recompact_index",
@@ -169,6 +169,17 @@ def stream_read_probe(src: torch.Tensor, sink: torch.Tensor) -> None:
     st = load_library().saap_stream_read_probe(_ptr(src), ctypes.c_size_t(src.numel() * src.element_size()), _ptr(sink),
                                                ctypes.c_size_t(sink.numel() * sink.element_size()), _stream())
     _check("saap_stream_read_probe", st)
+
+
+def mfma_rate_probe(operands: torch.Tensor, iters: int, sink: torch.Tensor, wgs_per_cu: int = 2) -> float:
+    """Measurement aid: enqueues the bare matrix-instruction loop on `operands` (bf16 values) and returns the
+    floating-point operations of the launch (see saap_mfma_rate_probe)."""
+    flop = ctypes.c_double(0.0)
+    st = load_library().saap_mfma_rate_probe(_ptr(operands), ctypes.c_size_t(operands.numel() * operands.element_size()),
+                                             ctypes.c_int32(iters), ctypes.c_int32(wgs_per_cu), _ptr(sink), ctypes.byref(flop),
+                                             _stream())
+    _check("saap_mfma_rate_probe", st)
+    return flop.value
 
 
 def assign_keys(x, centroids, bias=None, out=None, ws=None):

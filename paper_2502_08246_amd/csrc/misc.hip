@@ -48,6 +48,32 @@ __global__ void __launch_bounds__(512) stream_read_kernel(const uint4* __restric
   for (int o = 32; o > 0; o >>= 1) acc ^= __shfl_xor(acc, o);
   if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], acc);
 }
+// `iters` rounds of eight independent v_mfma_f32_32x32x16_bf16 per wave on operands read once from `ops` (16 bytes
+// per lane and operand, the lane's offset wrapped to the buffer): what the matrix pipes sustain on THESE operand
+// values with nothing else in the way (no LDS, no global traffic inside the loop).
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 probe_bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float probe_f32x16;
+__global__ void __launch_bounds__(256) mfma_rate_kernel(const uint4* __restrict__ ops, size_t n16, int iters, float* __restrict__ sink) {
+  const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  union { uint4 u; probe_bf16x8 v; } a[2], b[2];
+  a[0].u = ops[(4 * t) % n16]; a[1].u = ops[(4 * t + 1) % n16];
+  b[0].u = ops[(4 * t + 2) % n16]; b[1].u = ops[(4 * t + 3) % n16];
+  probe_f32x16 acc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[c][e] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c & 1].v, b[(c >> 1) & 1].v, acc[c], 0, 0, 0);
+  }
+  float r = 0.f;
+#pragma unroll
+  for (int c = 0; c < 8; ++c)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) r += acc[c][e];
+  if (r == 12345.678f) sink[0] = r;      // keeps the loop alive; practically never taken
+}
 }  // namespace
 
 }  // namespace saap
@@ -63,6 +89,19 @@ extern "C" int32_t saap_stream_read_probe(const void* src, size_t bytes, void* s
   if (sink_bytes < (size_t)grid * sizeof(uint32_t)) return SAAP_WORKSPACE_TOO_SMALL;
   hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3((unsigned)env_int("SAAP_PROBE_THREADS", 512)), 0, static_cast<hipStream_t>(stream),
                      static_cast<const uint4*>(src), bytes / 16, static_cast<uint32_t*>(sink));
+  return launch_status();
+}
+
+extern "C" int32_t saap_mfma_rate_probe(const void* operands, size_t bytes, int32_t iters, int32_t wgs_per_cu, void* sink,
+                                        double* flop_out, void* stream) {
+  begin_call();
+  if (!operands || !sink || !aligned16(operands) || bytes < 64 || iters <= 0 || iters > (1 << 24) || wgs_per_cu <= 0 ||
+      wgs_per_cu > 8)
+    return SAAP_INVALID_ARG;
+  const unsigned grid = (unsigned)(device_cus() * wgs_per_cu);
+  if (flop_out) *flop_out = (double)grid * 4.0 * iters * 8.0 * (2.0 * 32 * 32 * 16);
+  hipLaunchKernelGGL(mfma_rate_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint4*>(operands), bytes / 16, (int)iters, static_cast<float*>(sink));
   return launch_status();
 }
 

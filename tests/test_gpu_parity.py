@@ -613,3 +613,16 @@ def test_classifier_shapes_outside_its_limits_are_refused_on_the_device_too(saap
     torch.cuda.synchronize()
     assert e.value.status == -2
     assert (out == -7.0).all()
+
+
+@pytest.mark.gpu
+def test_mfma_rate_probe_runs_and_counts_flop(saap):
+    # measurement aid: the launch completes, reports its operation count, and rejects bad arguments
+    ops = torch.randn(1 << 16, device="cuda").to(torch.bfloat16)
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    flop = saap.mfma_rate_probe(ops, 16, sink, wgs_per_cu=1)
+    torch.cuda.synchronize()
+    cus = saap.load_library().saap_device_compute_units()
+    assert flop == cus * 4 * 16 * 8 * 2.0 * 32 * 32 * 16
+    with pytest.raises(saap.SaapError):
+        saap.mfma_rate_probe(ops, 0, sink)
