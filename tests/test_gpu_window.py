@@ -76,6 +76,11 @@ def compare_state(gpu, want, W, what):
     ("bf16", 1, 4, 1, 40, 8, 64, 2, 100, 160),        # context shorter than the window: it fills, then slides
     ("bf16", 1, 4, 2, 2500, 16, 16, 0, 64, 70),       # no sink
     ("bf16", 1, 2, 1, 2100, 16, 16, 3, 0, 20),        # no ring: new keys go straight to their buckets
+    # the other dense blocks the paper tries (Section 6.5, "Dense context size"): 128+512, 1+511, 1+63;
+    # with no bucket visited (nprobe 0 in the loop below) the result is attention on sink + recent keys alone
+    ("bf16", 1, 4, 1, 5000, 32, 24, 128, 512, 40),
+    ("bf16", 1, 8, 2, 4000, 32, 24, 1, 511, 40),
+    ("bf16", 2, 4, 1, 3000, 16, 24, 1, 63, 80),
 ])
 def test_build_push_attend(saap, dtype, S, Hq, Hkv, N, B, slack, n_sink, n_recent, steps):
     cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(S=S, Hq=Hq, Hkv=Hkv, N=N + steps, B=B, nprobe=4, dtype=dtype, hidden=64)
