@@ -99,12 +99,108 @@ __device__ __forceinline__ void store_out(const AttnParams& p, int qrow, int e, 
   if (e == 0 && p.lse) p.lse[qrow] = l > 0.f ? (M + __log2f(l)) * kLn2 : -INFINITY;
 }
 
+// Scores on the matrix cores: an 8-bit cache read by groups of four heads.  The vector ALUs are what bounds
+// attention on 8-bit rows (half the bytes per key, the same instructions), and converting the key codes and
+// multiplying them with four heads is the larger part of that work; v_mfma_f32_16x16x32_fp8_fp8 takes the codes
+// as they are.  The value side stays on the vector ALUs: its sum runs over the keys, which a matrix operand
+// wants inside a lane, while a row in memory has the features there.
+template <typename T, int G>
+constexpr bool kMatrixScores = sizeof(T) == 1 && G == 4;
+// The value product on the matrix cores (see consume_batch): it needs no other layout of the loads.
+template <typename T, int G>
+constexpr bool kMatrixValues = sizeof(T) <= 2 && G == 4;
+
 // One batch of a key processor: KB rows of K and V, and which of them are real keys.
+// MM (matrix-core scores): the wave's 16 keys form the A operand instead, lane (m, kg) = (lane % 16, lane / 16)
+// holding bytes [kg*16, kg*16+16) of both 64-byte halves of the row of key m = 4*processor + slot.
+template <typename T, int KB, bool MM>
+struct BatchKeys {
+  Vec8<T> k[KB];
+};
 template <typename T, int KB>
-struct Batch {
-  Vec8<T> k[KB], v[KB];
+struct BatchKeys<T, KB, true> {
+  uint4 ka[2 * sizeof(T)];    // the 64-byte pieces of a row: two of 8-bit codes, four of bf16
+};
+template <typename T, int KB, bool MM = false>
+struct Batch : BatchKeys<T, KB, MM> {
+  Vec8<T> v[KB];
   unsigned valid;   // bit i: slot i holds a key of the range
   unsigned heads;   // MASKED kernels: bits 8i .. 8i+7 = heads that attend the key in slot i
+};
+
+// The query rows of a unit as the dot products want them.  Vector path: 8 features of each head per lane.
+template <typename T, int G, bool MM = kMatrixScores<T, G>>
+struct Queries {
+  typedef typename DotType<T>::type TQ;
+  Vec8<TQ> v[G];
+  // `scale_log2` is the factor that turns the lane's dot products into base-2 logits; the matrix path folds the
+  // scaling of its operand into it
+  __device__ __forceinline__ void load(const void* q, int qrow0, int sub, int /*grp*/, float& /*scale_log2*/) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) v[g].load(reinterpret_cast<const TQ*>(q) + (size_t)(qrow0 + g) * kD + sub * 8);
+  }
+};
+// Matrix path: the B operand.  Lane (n, kg) holds, for head n % 4, the features the A operand's lane (m, kg)
+// holds of its key: [kg*16, kg*16+16) of both halves of the row, as E4M3 codes.  A bf16 query has 8 significant
+// bits and a code 4, so the row is scaled by a power of two (largest element into [128, 256)) and split into
+// two rows of codes, hi = the nearest code and lo = the rest, which is a code exactly unless it falls below the
+// smallest one (2^-9 against a largest element >= 128: an error of 2^-17 of it at most).
+template <>
+struct Queries<fp8_t, 4, true> {
+  long hi[4], lo[4];          // [half * 2 + piece]: 8 codes each
+  __device__ __forceinline__ void load(const void* q, int qrow0, int sub, int grp, float& scale_log2) {
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const bf16_t* row = reinterpret_cast<const bf16_t*>(q) + (size_t)(qrow0 + (sub & 3)) * kD + grp * 16;
+    uint4 raw[4];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      raw[2 * h] = *reinterpret_cast<const uint4*>(row + h * 64);
+      raw[2 * h + 1] = *reinterpret_cast<const uint4*>(row + h * 64 + 8);
+    }
+    float x[32];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      Vec8<bf16_t> w;
+      w.r = raw[i];
+      w.to_float(x + 8 * i);
+    }
+    float big = 0.f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) big = fmaxf(big, fabsf(x[i]));
+    big = max_rows(big);                                  // the head's largest element, in all its lanes
+    const unsigned eb = (__float_as_uint(big) >> 23) & 0xffu;
+    const bool scaled = eb >= 8u && eb < 255u;
+    const float up = scaled ? __uint_as_float((261u - eb) << 23) : 1.f;     // 2^(7 - floor(log2 big))
+    const float down = scaled ? __uint_as_float((eb - 7u) << 23) : 1.f;     // its inverse
+    scale_log2 *= down;
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {                        // operand o: 8 codes from x[8o .. 8o+8)
+      int h32[2] = {0, 0}, l32[2] = {0, 0};
+#pragma unroll
+      for (int wd = 0; wd < 2; ++wd) {                   // word wd: codes of x[8o + 4wd .. 8o + 4wd + 4)
+        const float a = x[8 * o + 4 * wd] * up, b = x[8 * o + 4 * wd + 1] * up;
+        const float c = x[8 * o + 4 * wd + 2] * up, d = x[8 * o + 4 * wd + 3] * up;
+        h32[wd] = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, h32[wd], false);
+        h32[wd] = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, h32[wd], true);
+        const f32x2_t b0 = __builtin_amdgcn_cvt_pk_f32_fp8(h32[wd], false), b1 = __builtin_amdgcn_cvt_pk_f32_fp8(h32[wd], true);
+        l32[wd] = __builtin_amdgcn_cvt_pk_fp8_f32(a - b0[0], b - b0[1], l32[wd], false);
+        l32[wd] = __builtin_amdgcn_cvt_pk_fp8_f32(c - b1[0], d - b1[1], l32[wd], true);
+      }
+      hi[o] = (long)(((unsigned long long)(unsigned)h32[1] << 32) | (unsigned)h32[0]);
+      lo[o] = (long)(((unsigned long long)(unsigned)l32[1] << 32) | (unsigned)l32[0]);
+    }
+  }
+};
+// bf16 rows: the query rows are the B operand of v_mfma_f32_16x16x32_bf16 as they are; lane (n, kg) holds features
+// [32c + 8kg, 32c + 8kg + 8) of head n % 4 for the four k-steps c.
+template <>
+struct Queries<bf16_t, 4, true> {
+  bf16x8_t b[4];
+  __device__ __forceinline__ void load(const void* q, int qrow0, int sub, int grp, float& /*scale_log2*/) {
+    const bf16_t* row = reinterpret_cast<const bf16_t*>(q) + (size_t)(qrow0 + (sub & 3)) * kD + grp * 8;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) b[c] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(row + c * 32));
+  }
 };
 
 // One stage of the reduction of N partial sums over a 16-lane group.  The lane keeps the half
@@ -157,48 +253,180 @@ __device__ __forceinline__ float ror_sum(float x) {
 template <int L>
 __device__ __forceinline__ float group_bcast(float x) { return dpp_mov<0x150 + L>(x); }
 
+// The unnormalised outputs a lane accumulates: 8 features of each of the G heads.  Matrix path: one
+// accumulator of the matrix instruction per feature, whose four registers are the four heads.
+template <int G, bool MM>
+struct Accum {
+  float O[G][8];
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) O[g][e] = 0.f;
+  }
+  __device__ __forceinline__ void rows(float (&out)[G][8]) const {
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) out[g][e] = O[g][e];
+  }
+};
+template <>
+struct Accum<4, true> {
+  f32x4_t c[8];
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
+  __device__ __forceinline__ void rows(float (&out)[4][8]) const {
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) out[g][e] = c[e][g];
+  }
+};
+
 // One batch of Algorithm 1 for a key processor: scores of the batch's KB keys against the G heads, running
 // maximum / sum / output update.  `m` is the running maximum of the head the lane owns, `l` the sum of the
 // lane's own (key slot, head) weights, O the output slices of all G heads.
 template <typename T, int G, bool MASKED>
-__device__ __forceinline__ void consume_batch(const Batch<T, (G == 8 ? 2 : 4)>& bt,
-                                              const Vec8<typename DotType<T>::type> (&qv)[G], float scale_log2, int sub,
-                                              float& m, float& l, float (&O)[G][8]) {
+__device__ __forceinline__ void consume_batch(const Batch<T, (G == 8 ? 2 : 4), kMatrixScores<T, G>>& bt,
+                                              const Queries<T, G>& qv, float scale_log2, int sub,
+                                              float& m, float& l, Accum<G, kMatrixValues<T, G>>& acc_o) {
   constexpr int KB = G == 8 ? 2 : 4;
   constexpr int C = KB * G;
   typedef typename DotType<T>::type TQ;
   const int c_own = sub & (C - 1);              // the combination this lane owns after the reduction
   const int i_own = c_own / G;                  // ... its key slot
-  // partial dot products of the lane's 8 features, all (key slot, head) combinations ...
-  float d[C];
+  float dot;
+  if constexpr (kMatrixScores<T, G>) {
+    // S^T = K Q^T: 16 keys x 128 features against 4 heads (each in four columns), the hi and the lo codes of
+    // the queries on an accumulator each.  The result's lane (n, row) holds the scores of head n % 4 for the
+    // four slots of processor `row`: lane n keeps slot n / 4, which is the combination it owns.
+    f32x4_t acc_h = {0.f, 0.f, 0.f, 0.f}, acc_l = acc_h;
+    if constexpr (sizeof(T) == 2) {
+      // bf16 rows: four k-steps of 32 features on two accumulator chains
+      acc_h = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, bt.ka[0]), qv.b[0], acc_h, 0, 0, 0);
+      acc_l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, bt.ka[1]), qv.b[1], acc_l, 0, 0, 0);
+      acc_h = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, bt.ka[2]), qv.b[2], acc_h, 0, 0, 0);
+      acc_l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, bt.ka[3]), qv.b[3], acc_l, 0, 0, 0);
+    } else {
 #pragma unroll
-  for (int i = 0; i < KB; ++i) {
-    const Vec8<TQ> kw = dot_operand(bt.k[i]);
+    for (int h = 0; h < 2; ++h) {
+      const long a0 = (long)(((unsigned long long)bt.ka[h].y << 32) | bt.ka[h].x);
+      const long a1 = (long)(((unsigned long long)bt.ka[h].w << 32) | bt.ka[h].z);
+      acc_h = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a0, qv.hi[2 * h], acc_h, 0, 0, 0);
+      acc_l = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a0, qv.lo[2 * h], acc_l, 0, 0, 0);
+      acc_h = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a1, qv.hi[2 * h + 1], acc_h, 0, 0, 0);
+      acc_l = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a1, qv.lo[2 * h + 1], acc_l, 0, 0, 0);
+    }
+    }
+    const f32x4_t acc = acc_h + acc_l;
+    dot = i_own == 0 ? acc[0] : i_own == 1 ? acc[1] : i_own == 2 ? acc[2] : acc[3];
+  } else {
+    // partial dot products of the lane's 8 features, all (key slot, head) combinations ...
+    float d[C];
 #pragma unroll
-    for (int g = 0; g < G; ++g) d[i * G + g] = kw.dot(qv[g]);
+    for (int i = 0; i < KB; ++i) {
+      const Vec8<TQ> kw = dot_operand(bt.k[i]);
+#pragma unroll
+      for (int g = 0; g < G; ++g) d[i * G + g] = kw.dot(qv.v[g]);
+    }
+    // ... reduced over the 16 lanes so that each lane ends up with ONE complete score
+    dot = reduce_scatter16<C>(d, sub);
   }
-  // ... reduced over the 16 lanes so that each lane ends up with ONE complete score
-  const float dot = reduce_scatter16<C>(d, sub);
   bool live = (bt.valid >> i_own) & 1u;
   if constexpr (MASKED) live = live && ((bt.heads >> (8 * i_own + c_own % G)) & 1u);
   const float t = live ? dot * scale_log2 : -INFINITY;
   // Algorithm 1, one step per batch: the head's running maximum lives in the lanes that own it
-  const float bm = ror_max<G, C>(t);
+  float bm = ror_max<G, C>(t);
+  // matrix path: the value product below sums over the 16 keys of the wave, so its four processors keep ONE
+  // running maximum per head
+  if constexpr (kMatrixValues<T, G>) bm = max_rows(bm);
   const float mn = fmaxf(m, bm);
   if (__builtin_amdgcn_ballot_w64(mn > m) != 0ull) {      // some maximum moved: rescale (wave-uniform branch)
     const float alpha = fast_exp2(m - mn);
     l *= alpha;
+    if constexpr (kMatrixValues<T, G>) {
+      const f32x4_t ag = {group_bcast<0>(alpha), group_bcast<1>(alpha), group_bcast<2>(alpha), group_bcast<3>(alpha)};
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float ag;
-      if constexpr (G == 1) ag = alpha; else ag = g == 0 ? group_bcast<0>(alpha) : g == 1 ? group_bcast<1>(alpha) : g == 2 ? group_bcast<2>(alpha) : g == 3 ? group_bcast<3>(alpha) : g == 4 ? group_bcast<4>(alpha) : g == 5 ? group_bcast<5>(alpha) : g == 6 ? group_bcast<6>(alpha) : group_bcast<7>(alpha);
+      for (int e = 0; e < 8; ++e) acc_o.c[e] *= ag;
+    } else {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) O[g][e] *= ag;
+      for (int g = 0; g < G; ++g) {
+        float ag;
+        if constexpr (G == 1) ag = alpha; else ag = g == 0 ? group_bcast<0>(alpha) : g == 1 ? group_bcast<1>(alpha) : g == 2 ? group_bcast<2>(alpha) : g == 3 ? group_bcast<3>(alpha) : g == 4 ? group_bcast<4>(alpha) : g == 5 ? group_bcast<5>(alpha) : g == 6 ? group_bcast<6>(alpha) : group_bcast<7>(alpha);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc_o.O[g][e] *= ag;
+      }
     }
     m = mn;
   }
   const float pw = fast_exp2(t - m);          // weight of the lane's own (key slot, head)
   l += pw;
+  if constexpr (kMatrixValues<T, G>) {
+    // O += P V on the matrix cores, two v_mfma_f32_16x16x16_bf16 per feature e of the lane's eight: the sum runs
+    // over the wave's 16 keys, k = 4 * processor + slot.  A (weights): lane (m, row) holds head m's weights of
+    // the four slots of processor `row`; they sit in lanes m, m+4, m+8, m+12 of the row and come by row
+    // rotation (lanes 4..15 collect other combinations: rows of the product nobody reads).  A weight goes in as
+    // two bf16 numbers, its upper 16 bits and the rest rounded (16 significant bits together), one product each.
+    // B: lane (n, row) holds feature 8n + e of the same four keys, the lane's own V row pieces regrouped by
+    // feature (E4M3 -> bf16 is exact).  The result's rows 0..3 are the heads: register g of accumulator e, in the
+    // lanes of row 0, accumulates the output, summed over all four processors; what the other rows accumulate
+    // is never read.
+    typedef __bf16 bf16x2v_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x4v_t __attribute__((ext_vector_type(4)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const unsigned p_hi = __float_as_uint(pw) & 0xffff0000u;
+    const float p_rest = pw - __uint_as_float(p_hi);
+    const f32x2_t rest2 = {p_rest, p_rest};
+    const unsigned w0 = p_hi | (__builtin_bit_cast(unsigned, __builtin_convertvector(rest2, bf16x2v_t)) & 0xffffu);
+    // lane i <- lane i+4, i+8, i+12 (mod 16)
+    const unsigned w1 = dpp_u32<0x120 + 12>(w0), w2 = dpp_u32<0x120 + 8>(w0), w3 = dpp_u32<0x120 + 4>(w0);
+    const uint2 a_hi2 = make_uint2(__builtin_amdgcn_perm(w1, w0, 0x07060302u), __builtin_amdgcn_perm(w3, w2, 0x07060302u));
+    const uint2 a_lo2 = make_uint2(__builtin_amdgcn_perm(w1, w0, 0x05040100u), __builtin_amdgcn_perm(w3, w2, 0x05040100u));
+    const bf16x4v_t a = __builtin_bit_cast(bf16x4v_t, a_hi2), a_lo = __builtin_bit_cast(bf16x4v_t, a_lo2);
+    bf16x4v_t vb[8];                                       // B operands by feature
+    if constexpr (sizeof(T) == 2) {
+      // bf16 rows: word w of a row holds features 2w and 2w+1; the low (high) halves of the four slots' words are
+      // feature 2w (2w+1) of the four keys
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const unsigned s0 = w == 0 ? bt.v[0].r.x : w == 1 ? bt.v[0].r.y : w == 2 ? bt.v[0].r.z : bt.v[0].r.w;
+        const unsigned s1 = w == 0 ? bt.v[1].r.x : w == 1 ? bt.v[1].r.y : w == 2 ? bt.v[1].r.z : bt.v[1].r.w;
+        const unsigned s2 = w == 0 ? bt.v[2].r.x : w == 1 ? bt.v[2].r.y : w == 2 ? bt.v[2].r.z : bt.v[2].r.w;
+        const unsigned s3 = w == 0 ? bt.v[3].r.x : w == 1 ? bt.v[3].r.y : w == 2 ? bt.v[3].r.z : bt.v[3].r.w;
+        const uint2 even = make_uint2(__builtin_amdgcn_perm(s1, s0, 0x05040100u), __builtin_amdgcn_perm(s3, s2, 0x05040100u));
+        const uint2 odd = make_uint2(__builtin_amdgcn_perm(s1, s0, 0x07060302u), __builtin_amdgcn_perm(s3, s2, 0x07060302u));
+        vb[2 * w] = __builtin_bit_cast(bf16x4v_t, even);
+        vb[2 * w + 1] = __builtin_bit_cast(bf16x4v_t, odd);
+      }
+    } else {
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {                          // word w of a row's eight codes: features 4w .. 4w+3
+      const unsigned s0 = w ? bt.v[0].r.y : bt.v[0].r.x, s1 = w ? bt.v[1].r.y : bt.v[1].r.x;
+      const unsigned s2 = w ? bt.v[2].r.y : bt.v[2].r.x, s3 = w ? bt.v[3].r.y : bt.v[3].r.x;
+      // bytes of two slots interleaved, then pairs of those: (slot 0, 1, 2, 3) of one feature per word
+      const unsigned t01l = __builtin_amdgcn_perm(s1, s0, 0x05010400u), t01h = __builtin_amdgcn_perm(s1, s0, 0x07030602u);
+      const unsigned t23l = __builtin_amdgcn_perm(s3, s2, 0x05010400u), t23h = __builtin_amdgcn_perm(s3, s2, 0x07030602u);
+      const unsigned f[4] = {__builtin_amdgcn_perm(t23l, t01l, 0x05040100u), __builtin_amdgcn_perm(t23l, t01l, 0x07060302u),
+                             __builtin_amdgcn_perm(t23h, t01h, 0x05040100u), __builtin_amdgcn_perm(t23h, t01h, 0x07060302u)};
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        const int e = 4 * w + x;
+        const bf16x2v_t b01 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)f[x], 1.0f, false);
+        const bf16x2v_t b23 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)f[x], 1.0f, true);
+        const bf16x4v_t b = {b01[0], b01[1], b23[0], b23[1]};
+        vb[e] = b;
+      }
+    }
+    }
+    // the eight accumulators in turn, twice: no product waits for the one before it
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc_o.c[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, vb[e], acc_o.c[e], 0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc_o.c[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, vb[e], acc_o.c[e], 0, 0, 0);
+  } else {
   // every lane needs every weight of its group for the value update: broadcast from the owner
   float pb[C];
   pb[0] = group_bcast<0>(pw); pb[1] = group_bcast<1>(pw); pb[2] = group_bcast<2>(pw); pb[3] = group_bcast<3>(pw);
@@ -214,17 +442,24 @@ __device__ __forceinline__ void consume_batch(const Batch<T, (G == 8 ? 2 : 4)>& 
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) O[g][e] = fmaf(pb[i * G + g], vf[e], O[g][e]);
+      for (int e = 0; e < 8; ++e) acc_o.O[g][e] = fmaf(pb[i * G + g], vf[e], acc_o.O[g][e]);
+  }
   }
 }
 
 // End of a key range: the head's sum of weights is added up over the key slots, then the four key
 // processors of the wave are combined (Algorithm 2 on registers): common maximum per head, rescale, add
 // up across the four 16-lane rows.
-template <int G>
-__device__ __forceinline__ void wave_combine(float& m, float& l, float (&O)[G][8]) {
+template <int G, bool MM = false>
+__device__ __forceinline__ void wave_combine(float& m, float& l, const Accum<G, MM>& acc_o, float (&O)[G][8]) {
   constexpr int C = (G == 8 ? 2 : 4) * G;
   l = ror_sum<G, C>(l);
+  acc_o.rows(O);
+  if constexpr (MM) {
+    // matrix path: one running maximum for the wave, and the outputs (row 0) already hold the sum over its processors
+    l = sum_rows(l);
+    return;
+  }
   const float mw = max_rows(m);
   const float a = fast_exp2(m - mw);          // scale of this processor's sums for the lane's own head
   m = mw;
@@ -473,16 +708,17 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   const T* Kb = reinterpret_cast<const T*>(p.K) + (size_t)kvu * p.rows * kD + sub * 8;
   const T* Vb = reinterpret_cast<const T*>(p.V) + (size_t)kvu * p.rows * kD + sub * 8;
 
-  // query slices: 8 features of each of the G heads
-  Vec8<TQ> qv[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g) qv[g].load(reinterpret_cast<const TQ*>(p.q) + (size_t)(qrow0 + g) * kD + sub * 8);
   // 8-bit cache: the codes' scales fold into the score scale and into the final division
   float scale_log2 = p.scale_log2, vs = 1.f;
   if constexpr (kFp8) {
     scale_log2 *= p.kscale[kvu];
     vs = p.vscale[kvu];
   }
+  // the query rows of the G heads
+  constexpr bool MM = kMatrixScores<T, G>, MV = kMatrixValues<T, G>;
+  Queries<T, G> qv;
+  qv.load(p.q, qrow0, sub, grp, scale_log2);
+  const T* Kmm = reinterpret_cast<const T*>(p.K) + (size_t)kvu * p.rows * kD + grp * (16 / sizeof(T));   // matrix path: the lane's 16 bytes of a 64-byte piece
 
   constexpr int NG = nw * 4;            // key processors in the workgroup
   constexpr int chunk = NG * KB;        // keys the workgroup consumes per batch
@@ -661,18 +897,16 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
 
   // per lane: running maximum of its head, sum of its own (key slot, head) weights, and the
   // output slices of all G heads
-  float m = kNegBig, l = 0.f, O[G][8];
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) O[g][e] = 0.f;
+  float m = kNegBig, l = 0.f;
+  Accum<G, MV> acc_o;
+  acc_o.zero();
 
   // The virtual key range [0,T) is cut into chunks of NG*KB keys; chunk c belongs to
   // workgroup c % P, so neighbouring workgroups stream neighbouring memory at any moment.
   // Virtual key of (this processor, slot i) of the chunk at `base` is base + i*NG + kp.
   const long long stride = (long long)chunk * p.P;
 
-  auto load_batch = [&](long long base, int k, Batch<T, KB>& bt) {
+  auto load_batch = [&](long long base, int k, Batch<T, KB, MM>& bt) {
     int row, hmask = 0;
     {
       long long vl = base + (sub & (KB - 1)) * NG + kp;   // lane `sub` resolves slot sub % KB
@@ -695,27 +929,33 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     }
     bt.valid = 0u;
     bt.heads = 0u;
+    if constexpr (MM) {
+      // operand row m = lane % 16 is the key of (processor m / 4, slot m % 4), resolved by lane m % 4 of that processor
+      const int rk = __shfl(row, (sub >> 2) * 16 + (sub & 3));
+#pragma unroll
+      for (int c = 0; c < 2 * (int)sizeof(T); ++c) bt.ka[c] = stream_load16(Kmm + (size_t)rk * kD + c * (64 / sizeof(T)));
+    }
 #pragma unroll
     for (int i = 0; i < KB; ++i) {
       const int r = __shfl(row, (lane & 48) + i);
       if constexpr (MASKED) bt.heads |= (unsigned)__shfl(hmask, (lane & 48) + i) << (8 * i);
       if (base + i * NG + kp < T_total) bt.valid |= 1u << i;
-      bt.k[i].load_stream(Kb + (size_t)r * kD);
+      if constexpr (!MM) bt.k[i].load_stream(Kb + (size_t)r * kD);
       bt.v[i].load_stream(Vb + (size_t)r * kD);
     }
   };
 
-  auto consume = [&](const Batch<T, KB>& bt) { consume_batch<T, G, MASKED>(bt, qv, scale_log2, sub, m, l, O); };
+  auto consume = [&](const Batch<T, KB, MM>& bt) { consume_batch<T, G, MASKED>(bt, qv, scale_log2, sub, m, l, acc_o); };
 
   {
     long long base = (long long)wg * chunk;
     int k = 0;
     if (base < T_total) {
-      Batch<T, KB> cur;
+      Batch<T, KB, MM> cur;
       load_batch(base, k, cur);
       if constexpr (kPrefetch) {
         for (base += stride, ++k; base < T_total; base += stride, ++k) {
-          Batch<T, KB> nxt;
+          Batch<T, KB, MM> nxt;
           load_batch(base, k, nxt);     // in flight while the current batch is consumed
           // keep it that way: without the fence the scheduler starts on the current batch (and its
           // wait for memory) before the next batch's loads have been issued
@@ -735,7 +975,8 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   }
 
   SAAP_TRACE(3);
-  wave_combine<G>(m, l, O);
+  float O[G][8];
+  wave_combine<G, MV>(m, l, acc_o, O);
 
   // waves -> LDS (the index arrays are dead once every wave has passed the barrier inside)
   SAAP_TRACE(9);
@@ -1062,14 +1303,17 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
     const T* Kb2 = reinterpret_cast<const T*>(p.K2) + ((size_t)kvu * p.rows2 - (size_t)p.rows) * kD + sub * 8;
     const T* Vb2 = reinterpret_cast<const T*>(p.V2) + ((size_t)kvu * p.rows2 - (size_t)p.rows) * kD + sub * 8;
     const int row_end = (int)(p.rows + p.rows2);
-    Vec8<TQ> qv[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) qv[g].load(reinterpret_cast<const TQ*>(p.q) + (size_t)(qrow0 + g) * kD + sub * 8);
     float scale_log2 = p.scale_log2, vs = 1.f;
     if constexpr (kFp8) {
       scale_log2 *= p.kscale[kvu];
       vs = p.vscale[kvu];
     }
+    constexpr bool MM = kMatrixScores<T, G>, MV = kMatrixValues<T, G>;
+    Queries<T, G> qv;
+    qv.load(p.q, qrow0, sub, grp, scale_log2);
+    // matrix path: the lane's piece of a row, in either pair of tensors
+    const T* Kmm = reinterpret_cast<const T*>(p.K) + (size_t)kvu * p.rows * kD + grp * (16 / sizeof(T));
+    const T* Kmm2 = reinterpret_cast<const T*>(p.K2) + ((size_t)kvu * p.rows2 - (size_t)p.rows) * kD + grp * (16 / sizeof(T));
     SAAP_TRACE(12);
     const int* tab = s_tab + u * p.ps;
     if (!p.all_tables) {
@@ -1111,17 +1355,15 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
       return a + __builtin_amdgcn_readfirstlane(g) * WB;
     };
 
-    float m = kNegBig, l = 0.f, O[G][8];
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) O[g][e] = 0.f;
+    float m = kNegBig, l = 0.f;
+    Accum<G, MV> acc_o;
+    acc_o.zero();
 
     // Keys of (processor grp, slot i) of the wave batch at `base`: base + i*4 + grp, so one load instruction of
     // the wave reads four neighbouring rows.  The lane's keys only move forward through the piece: its run is
     // found by stepping on from the run of its key in the batch before.
     int j = ra;
-    auto load_batch = [&](int base, Batch<T, KB>& bt) {
+    auto load_batch = [&](int base, Batch<T, KB, MM>& bt) {
       int row;
       {
         const int v = min(base + (sub & (KB - 1)) * 4 + grp, b - 1);   // lane `sub` resolves slot sub % KB
@@ -1133,6 +1375,13 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
       }
       bt.valid = 0u;
       bt.heads = 0u;
+      if constexpr (MM) {
+        // operand row m = lane % 16 is the key of (processor m / 4, slot m % 4), resolved by lane m % 4 of that processor
+        const int rk = __shfl(row, (sub >> 2) * 16 + (sub & 3));
+        const T* src = (rk >= (int)p.rows ? Kmm2 : Kmm) + (size_t)rk * kD;
+#pragma unroll
+        for (int c = 0; c < 2 * (int)sizeof(T); ++c) bt.ka[c] = stream_load16(src + c * (64 / sizeof(T)));
+      }
 #pragma unroll
       for (int i = 0; i < KB; ++i) {
         const int r = __shfl(row, (lane & 48) + i);
@@ -1141,11 +1390,11 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
         // would then drain them all
         if (base + i * 4 + grp < b) bt.valid |= 1u << i;
         const bool second = r >= (int)p.rows;
-        bt.k[i].load_stream((second ? Kb2 : Kb) + (size_t)r * kD);
+        if constexpr (!MM) bt.k[i].load_stream((second ? Kb2 : Kb) + (size_t)r * kD);
         bt.v[i].load_stream((second ? Vb2 : Vb) + (size_t)r * kD);
       }
     };
-    auto consume = [&](const Batch<T, KB>& bt) { consume_batch<T, G, false>(bt, qv, scale_log2, sub, m, l, O); };
+    auto consume = [&](const Batch<T, KB, MM>& bt) { consume_batch<T, G, false>(bt, qv, scale_log2, sub, m, l, acc_o); };
     {
       // two batches at once to begin with; from then on one batch ahead, its LDS round trip off the path
       int base;
@@ -1157,13 +1406,13 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
       if (base < b) {
         int next = base + WB;
         SAAP_TRACE(15);
-        Batch<T, KB> cur;
+        Batch<T, KB, MM> cur;
         load_batch(base, cur);
         SAAP_TRACE(2);
         if constexpr (kPrefetch) {
           while (next < b) {
             const int after = grab();
-            Batch<T, KB> nxt;
+            Batch<T, KB, MM> nxt;
             load_batch(next, nxt);      // in flight while the current batch is consumed
             __builtin_amdgcn_sched_barrier(0);
             consume(cur);
@@ -1184,7 +1433,8 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
     }
 
     // ---- end of the piece
-    wave_combine<G>(m, l, O);
+    float O[G][8];
+    wave_combine<G, MV>(m, l, acc_o, O);
     const int w_first = rs / Q, w_last = (ue - 1) / Q;    // the workgroups that hold the unit's first and last key
     const int P = w_last - w_first + 1;
     // partial results are numbered along the global range: (workgroup, unit) pairs in order differ by at
