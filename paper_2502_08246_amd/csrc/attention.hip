@@ -19,6 +19,9 @@
 //     unit (through the workspace) are combined with the log-sum-exp merge of Algorithm 2.
 //     The last workgroup of a unit to arrive (atomic counter) performs the final merge, so
 //     partial attention and merge are one launch.
+//   * With four heads per KV head the value product P V runs on the matrix cores, the four
+//     keys a lane holds being the sum index of v_mfma_f32_16x16x16_bf16; the running maximum
+//     is then one per head and wave.  On an 8-bit cache the scores run there as well.
 #include "common.h"
 
 #include <mutex>
@@ -99,14 +102,17 @@ __device__ __forceinline__ void store_out(const AttnParams& p, int qrow, int e, 
   if (e == 0 && p.lse) p.lse[qrow] = l > 0.f ? (M + __log2f(l)) * kLn2 : -INFINITY;
 }
 
-// Scores on the matrix cores: an 8-bit cache read by groups of four heads.  The vector ALUs are what bounds
-// attention on 8-bit rows (half the bytes per key, the same instructions), and converting the key codes and
-// multiplying them with four heads is the larger part of that work; v_mfma_f32_16x16x32_fp8_fp8 takes the codes
-// as they are.  The value side stays on the vector ALUs: its sum runs over the keys, which a matrix operand
-// wants inside a lane, while a row in memory has the features there.
+// Groups of four heads use the matrix cores (see consume_batch).
+// Values, O += P V: for bf16 and 8-bit caches.  The sum runs over the keys, and the four keys a lane holds of a
+// row piece are the four k-values a lane contributes to v_mfma_f32_16x16x16_bf16, so the loads keep their layout
+// (16 lanes per row, whole cache lines).
+// Scores, S = K Q^T: for 8-bit caches only.  The sum runs over the features, so the operand wants lane (m, kg) to
+// hold a piece of row m: 16 different rows in 16 neighbouring lanes, a load that touches 16 cache lines per 16
+// lanes.  On 8-bit rows this still pays (v_mfma_f32_16x16x32_fp8_fp8 takes the codes as they are, where the
+// vector ALUs convert every code before they multiply it with four heads: 29 against 32 us at 8 x 128k); on
+// bf16 rows it does not (48 against 43 us there), v_dot2_f32_bf16 on whole cache lines is faster.
 template <typename T, int G>
 constexpr bool kMatrixScores = sizeof(T) == 1 && G == 4;
-// The value product on the matrix cores (see consume_batch): it needs no other layout of the loads.
 template <typename T, int G>
 constexpr bool kMatrixValues = sizeof(T) <= 2 && G == 4;
 
@@ -119,7 +125,7 @@ struct BatchKeys {
 };
 template <typename T, int KB>
 struct BatchKeys<T, KB, true> {
-  uint4 ka[2 * sizeof(T)];    // the 64-byte pieces of a row: two of 8-bit codes, four of bf16
+  uint4 ka[2];                // the two 64-byte halves of a row of codes
 };
 template <typename T, int KB, bool MM = false>
 struct Batch : BatchKeys<T, KB, MM> {
@@ -189,17 +195,6 @@ struct Queries<fp8_t, 4, true> {
       hi[o] = (long)(((unsigned long long)(unsigned)h32[1] << 32) | (unsigned)h32[0]);
       lo[o] = (long)(((unsigned long long)(unsigned)l32[1] << 32) | (unsigned)l32[0]);
     }
-  }
-};
-// bf16 rows: the query rows are the B operand of v_mfma_f32_16x16x32_bf16 as they are; lane (n, kg) holds features
-// [32c + 8kg, 32c + 8kg + 8) of head n % 4 for the four k-steps c.
-template <>
-struct Queries<bf16_t, 4, true> {
-  bf16x8_t b[4];
-  __device__ __forceinline__ void load(const void* q, int qrow0, int sub, int grp, float& /*scale_log2*/) {
-    const bf16_t* row = reinterpret_cast<const bf16_t*>(q) + (size_t)(qrow0 + (sub & 3)) * kD + grp * 8;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) b[c] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(row + c * 32));
   }
 };
 
@@ -304,13 +299,6 @@ __device__ __forceinline__ void consume_batch(const Batch<T, (G == 8 ? 2 : 4), k
     // the queries on an accumulator each.  The result's lane (n, row) holds the scores of head n % 4 for the
     // four slots of processor `row`: lane n keeps slot n / 4, which is the combination it owns.
     f32x4_t acc_h = {0.f, 0.f, 0.f, 0.f}, acc_l = acc_h;
-    if constexpr (sizeof(T) == 2) {
-      // bf16 rows: four k-steps of 32 features on two accumulator chains
-      acc_h = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, bt.ka[0]), qv.b[0], acc_h, 0, 0, 0);
-      acc_l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, bt.ka[1]), qv.b[1], acc_l, 0, 0, 0);
-      acc_h = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, bt.ka[2]), qv.b[2], acc_h, 0, 0, 0);
-      acc_l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, bt.ka[3]), qv.b[3], acc_l, 0, 0, 0);
-    } else {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const long a0 = (long)(((unsigned long long)bt.ka[h].y << 32) | bt.ka[h].x);
@@ -319,7 +307,6 @@ __device__ __forceinline__ void consume_batch(const Batch<T, (G == 8 ? 2 : 4), k
       acc_l = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a0, qv.lo[2 * h], acc_l, 0, 0, 0);
       acc_h = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a1, qv.hi[2 * h + 1], acc_h, 0, 0, 0);
       acc_l = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a1, qv.lo[2 * h + 1], acc_l, 0, 0, 0);
-    }
     }
     const f32x4_t acc = acc_h + acc_l;
     dot = i_own == 0 ? acc[0] : i_own == 1 ? acc[1] : i_own == 2 ? acc[2] : acc[3];
@@ -718,7 +705,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   constexpr bool MM = kMatrixScores<T, G>, MV = kMatrixValues<T, G>;
   Queries<T, G> qv;
   qv.load(p.q, qrow0, sub, grp, scale_log2);
-  const T* Kmm = reinterpret_cast<const T*>(p.K) + (size_t)kvu * p.rows * kD + grp * (16 / sizeof(T));   // matrix path: the lane's 16 bytes of a 64-byte piece
+  const T* Kmm = reinterpret_cast<const T*>(p.K) + (size_t)kvu * p.rows * kD + grp * 16;   // matrix path: the lane's 16 bytes of a 64-byte piece
 
   constexpr int NG = nw * 4;            // key processors in the workgroup
   constexpr int chunk = NG * KB;        // keys the workgroup consumes per batch
@@ -933,7 +920,7 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
       // operand row m = lane % 16 is the key of (processor m / 4, slot m % 4), resolved by lane m % 4 of that processor
       const int rk = __shfl(row, (sub >> 2) * 16 + (sub & 3));
 #pragma unroll
-      for (int c = 0; c < 2 * (int)sizeof(T); ++c) bt.ka[c] = stream_load16(Kmm + (size_t)rk * kD + c * (64 / sizeof(T)));
+      for (int c = 0; c < 2; ++c) bt.ka[c] = stream_load16(Kmm + (size_t)rk * kD + c * 64);
     }
 #pragma unroll
     for (int i = 0; i < KB; ++i) {
@@ -1312,8 +1299,8 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
     Queries<T, G> qv;
     qv.load(p.q, qrow0, sub, grp, scale_log2);
     // matrix path: the lane's piece of a row, in either pair of tensors
-    const T* Kmm = reinterpret_cast<const T*>(p.K) + (size_t)kvu * p.rows * kD + grp * (16 / sizeof(T));
-    const T* Kmm2 = reinterpret_cast<const T*>(p.K2) + ((size_t)kvu * p.rows2 - (size_t)p.rows) * kD + grp * (16 / sizeof(T));
+    const T* Kmm = reinterpret_cast<const T*>(p.K) + (size_t)kvu * p.rows * kD + grp * 16;
+    const T* Kmm2 = reinterpret_cast<const T*>(p.K2) + ((size_t)kvu * p.rows2 - (size_t)p.rows) * kD + grp * 16;
     SAAP_TRACE(12);
     const int* tab = s_tab + u * p.ps;
     if (!p.all_tables) {
@@ -1380,7 +1367,7 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
         const int rk = __shfl(row, (sub >> 2) * 16 + (sub & 3));
         const T* src = (rk >= (int)p.rows ? Kmm2 : Kmm) + (size_t)rk * kD;
 #pragma unroll
-        for (int c = 0; c < 2 * (int)sizeof(T); ++c) bt.ka[c] = stream_load16(src + c * (64 / sizeof(T)));
+        for (int c = 0; c < 2; ++c) bt.ka[c] = stream_load16(src + c * 64);
       }
 #pragma unroll
       for (int i = 0; i < KB; ++i) {
