@@ -468,7 +468,9 @@ template <int G, int NT, typename F>
 __device__ __forceinline__ void workgroup_combine(float* scratch, float m, float l, const float (&O)[G][8], F emit) {
   constexpr int nw = NT / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, sub = lane & 15, grp = lane >> 4;
+  SAAP_TRACE_WAVE(10);                                    // (debug builds) the last wave to get here stamps last
   __syncthreads();
+  SAAP_TRACE(11);
   float* w_o = scratch;                                   // [nw][G][d] unnormalised outputs
   float* w_m = w_o + nw * G * kD;                         // [nw][G] maxima
   float* w_l = w_m + nw * G;                              // [nw][G] sums of weights
@@ -485,6 +487,7 @@ __device__ __forceinline__ void workgroup_combine(float* scratch, float m, float
     }
   }
   __syncthreads();
+  SAAP_TRACE(13);
   for (int x = tid; x < G * kD; x += NT) {
     const int g = x / kD, e = x % kD;
     float mj[nw];
