@@ -131,6 +131,43 @@ def test_sparse_attention_fp8(saap, S, Hq, Hkv, N, B, nprobe, mode):
         assert_close(lse.cpu().numpy(), r_lse, "lse")
 
 
+def test_sparse_attention_fp8_query_ranges(saap):
+    """Groups of four heads take their scores on the matrix cores, where the bf16 query row is scaled by a power of
+    two and split into two rows of 8-bit codes: rows of zeros, tiny and huge rows, and a row whose elements span
+    twenty binades must all come out within the tolerance."""
+    S, Hq, Hkv, N, B, nprobe = 1, 8, 2, 6000, 32, 8
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(S=S, Hq=Hq, Hkv=Hkv, N=N, B=B, nprobe=nprobe, dtype="bf16", hidden=64)
+    cache = gen.make_cache(cfg, 53, DEV)
+    cent = gen.make_centroids(cfg, 53, DEV, cache, n_train=2048)
+    xq, q = gen.make_queries(cfg, 53, DEV, n_steps=1)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs = saap.build_bucket_index(ids, cache["K"], cache["V"], B, 3)
+    K8, V8, ks, vs = saap.quantize_kv(Ks, Vs)
+    qq = q[0].clone().float()                                    # [S, Hq, d]
+    g = torch.Generator(device="cpu").manual_seed(5)
+    qq[0, 0] = 0.0                                               # nothing to scale
+    qq[0, 1] *= 1e-30                                            # below the range that is scaled
+    qq[0, 2] *= 3e4                                              # scores in the thousands: one key takes all
+    qq[0, 3] *= torch.exp2(-20.0 * torch.rand(128, generator=g)).to(DEV)     # elements from 1 down to 2^-20 of the largest
+    qq[0, 5] = 0.0
+    qq[0, 5, 17] = 1.0                                           # a single feature
+    qq[0, 6] *= 2.0 ** -100
+    qb = qq.to(torch.bfloat16)
+    torch.cuda.synchronize()
+    h_idx = idx.cpu().numpy()
+    Kp = position_order(ref.dequantize_fp8(K8.cpu().numpy(), ks.cpu().numpy()), h_idx)
+    Vp = position_order(ref.dequantize_fp8(V8.cpu().numpy(), vs.cpu().numpy()), h_idx)
+    rng = np.random.default_rng(11)
+    sel_np = np.stack([np.stack([rng.permutation(B)[:nprobe] for _ in range(Hkv)]) for _ in range(S)]).astype(np.int32)
+    sel = torch.from_numpy(sel_np).to(DEV)
+    out, lse = saap.sparse_decode_attention_fp8(qb, K8, V8, ks, vs, off, ln, sel, SCALE)
+    torch.cuda.synchronize()
+    r_out, r_lse = ref.sparse_decode_attention(h(qb), Kp, Vp, off.cpu().numpy(), ln.cpu().numpy(), h_idx, sel_np,
+                                               np.float32(SCALE), 0)
+    assert_close(out.cpu().numpy(), r_out, "out")
+    assert_close(lse.cpu().numpy(), r_lse, "lse")
+
+
 def test_dense_attention_fp8_and_all_buckets(saap):
     """Dense attention on the 8-bit cache, packed and bucket-sorted, and the sparse call with every
     bucket selected: all equal the oracle's dense attention on the decoded values."""
