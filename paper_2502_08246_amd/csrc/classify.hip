@@ -82,6 +82,9 @@ mlp_hidden_bf16_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__
     const int unit = min(slab * 64 + prow + 16 * i, sh.hidden - 1);
     wr[i] = load16(W1 + ((size_t)w * sh.hidden + unit) * kD + pc * 8);
   }
+  // the bias of the lane's hidden unit travels with the weights: fetched after the products it would put one
+  // more memory round trip in front of the stores
+  const float bv = b1 ? b1[(size_t)w * sh.hidden + min(slab * 64 + wave * 16 + rc, sh.hidden - 1)] : 0.f;
   __builtin_amdgcn_sched_barrier(0);
   *reinterpret_cast<u32x4_t*>(s_x + prow * kPitchD + pc * 8) = xr;
 #pragma unroll
@@ -98,7 +101,6 @@ mlp_hidden_bf16_kernel(const bf16_t* __restrict__ xq, const bf16_t* __restrict__
     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
   }
   // accumulator i of this lane: row 4*kg + i, hidden unit `unit`
-  const float bv = b1 ? b1[(size_t)w * sh.hidden + unit] : 0.f;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = mt * 16 + 4 * kg + i;
@@ -158,6 +160,9 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
   // one accumulator per plane: three independent chains of matrix instructions, added at the end
   f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0, acc2 = acc0;
   SAAP_TRACE(0);
+  // the bias of the bucket this lane will write (waves 0 .. kTiles-1), fetched with the first weights: after the
+  // products it would put one more memory round trip in front of the stores
+  const float bo = b2 ? b2[(size_t)w * sh.B + min(b0 + (wave % kTiles) * 16 + rc, sh.B - 1)] : 0.f;
   for (int c0 = 0; c0 < sh.hidden; c0 += kOutChunk) {
     const int kc = min(kOutChunk, sh.hidden - c0);      // multiple of 32
     // all loads of the pass first: SLAB rows of W2 (kc/8 pieces each) and 16 rows of h (kc/4 pieces)
@@ -270,7 +275,6 @@ mlp_out_bf16_kernel(const float* __restrict__ hbuf, const bf16_t* __restrict__ W
     SAAP_TRACE(2);
     const int bucket = b0 + wave * 16 + rc;
     if (bucket < sh.B) {
-      const float bo = b2 ? b2[(size_t)w * sh.B + bucket] : 0.f;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int mm = mt * 16 + 4 * kg + i;
