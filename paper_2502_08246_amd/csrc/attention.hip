@@ -281,9 +281,97 @@ struct Accum<4, true> {
   }
 };
 
+// Scores of a wave batch on the matrix cores (8-bit cache, four heads): S^T = K Q^T, 16 keys x 128 features
+// against 4 heads (each in four columns), the hi and the lo codes of the queries on an accumulator each.  The
+// result's lane (n, row) holds the scores of head n % 4 for the four slots of processor `row`; lane n keeps slot
+// n / 4, the (slot, head) combination it owns in the softmax below.
+template <typename T>
+__device__ __forceinline__ float matrix_scores(const Batch<T, 4, true>& bt, const Queries<T, 4, true>& qv, int sub) {
+  f32x4_t acc_h = {0.f, 0.f, 0.f, 0.f}, acc_l = acc_h;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const long a0 = (long)(((unsigned long long)bt.ka[h].y << 32) | bt.ka[h].x);
+    const long a1 = (long)(((unsigned long long)bt.ka[h].w << 32) | bt.ka[h].z);
+    acc_h = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a0, qv.hi[2 * h], acc_h, 0, 0, 0);
+    acc_l = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a0, qv.lo[2 * h], acc_l, 0, 0, 0);
+    acc_h = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a1, qv.hi[2 * h + 1], acc_h, 0, 0, 0);
+    acc_l = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a1, qv.lo[2 * h + 1], acc_l, 0, 0, 0);
+  }
+  const f32x4_t acc = acc_h + acc_l;
+  const int slot = sub >> 2;
+  return slot == 0 ? acc[0] : slot == 1 ? acc[1] : slot == 2 ? acc[2] : acc[3];
+}
+
+// The B operands of the value product: for each of the lane's eight features e, that feature of the four keys
+// (slots) whose row pieces the lane holds, as bf16.
+typedef __bf16 bf16x2v_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4v_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void values_by_feature(const Vec8<bf16_t> (&v)[4], bf16x4v_t (&vb)[8]) {
+  // word w of a row piece holds features 2w and 2w+1: the low (high) halves of the four slots' words are
+  // feature 2w (2w+1) of the four keys
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const unsigned s0 = w == 0 ? v[0].r.x : w == 1 ? v[0].r.y : w == 2 ? v[0].r.z : v[0].r.w;
+    const unsigned s1 = w == 0 ? v[1].r.x : w == 1 ? v[1].r.y : w == 2 ? v[1].r.z : v[1].r.w;
+    const unsigned s2 = w == 0 ? v[2].r.x : w == 1 ? v[2].r.y : w == 2 ? v[2].r.z : v[2].r.w;
+    const unsigned s3 = w == 0 ? v[3].r.x : w == 1 ? v[3].r.y : w == 2 ? v[3].r.z : v[3].r.w;
+    const uint2 even = make_uint2(__builtin_amdgcn_perm(s1, s0, 0x05040100u), __builtin_amdgcn_perm(s3, s2, 0x05040100u));
+    const uint2 odd = make_uint2(__builtin_amdgcn_perm(s1, s0, 0x07060302u), __builtin_amdgcn_perm(s3, s2, 0x07060302u));
+    vb[2 * w] = __builtin_bit_cast(bf16x4v_t, even);
+    vb[2 * w + 1] = __builtin_bit_cast(bf16x4v_t, odd);
+  }
+}
+__device__ __forceinline__ void values_by_feature(const Vec8<fp8_t> (&v)[4], bf16x4v_t (&vb)[8]) {
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {                          // word w of a row piece: the codes of features 4w .. 4w+3
+    const unsigned s0 = w ? v[0].r.y : v[0].r.x, s1 = w ? v[1].r.y : v[1].r.x;
+    const unsigned s2 = w ? v[2].r.y : v[2].r.x, s3 = w ? v[3].r.y : v[3].r.x;
+    // bytes of two slots interleaved, then pairs of those: (slot 0, 1, 2, 3) of one feature per word
+    const unsigned t01l = __builtin_amdgcn_perm(s1, s0, 0x05010400u), t01h = __builtin_amdgcn_perm(s1, s0, 0x07030602u);
+    const unsigned t23l = __builtin_amdgcn_perm(s3, s2, 0x05010400u), t23h = __builtin_amdgcn_perm(s3, s2, 0x07030602u);
+    const unsigned f[4] = {__builtin_amdgcn_perm(t23l, t01l, 0x05040100u), __builtin_amdgcn_perm(t23l, t01l, 0x07060302u),
+                           __builtin_amdgcn_perm(t23h, t01h, 0x05040100u), __builtin_amdgcn_perm(t23h, t01h, 0x07060302u)};
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {                        // E4M3 -> bf16 is exact
+      const bf16x2v_t b01 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)f[x], 1.0f, false);
+      const bf16x2v_t b23 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)f[x], 1.0f, true);
+      vb[4 * w + x] = bf16x4v_t{b01[0], b01[1], b23[0], b23[1]};
+    }
+  }
+}
+
+// O += P V of a wave batch on the matrix cores (four heads), two v_mfma_f32_16x16x16_bf16 per feature e of the
+// lane's eight: the sum runs over the wave's 16 keys, k = 4 * processor + slot.
+// A (weights): lane (m, row) holds head m's weights of the four slots of processor `row`; they sit in lanes m, m+4,
+// m+8, m+12 of the row (`pw` is the weight of the lane's own (slot, head)) and come by row rotation; lanes 4..15
+// collect other combinations, rows of the product that nobody reads.  A weight goes in as two bf16 numbers, its
+// upper 16 bits and the rest rounded (16 significant bits together), one product each.
+// B: values_by_feature.  The result's rows 0..3 are the heads: register g of accumulator e, in the lanes of row 0,
+// accumulates the output summed over all four processors; what the other rows accumulate is never read.
+template <typename T>
+__device__ __forceinline__ void matrix_value_update(const Vec8<T> (&v)[4], float pw, Accum<4, true>& acc_o) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const unsigned p_hi = __float_as_uint(pw) & 0xffff0000u;
+  const float p_rest = pw - __uint_as_float(p_hi);
+  const f32x2_t rest2 = {p_rest, p_rest};
+  const unsigned w0 = p_hi | (__builtin_bit_cast(unsigned, __builtin_convertvector(rest2, bf16x2v_t)) & 0xffffu);
+  // lane i <- lane i+4, i+8, i+12 (mod 16)
+  const unsigned w1 = dpp_u32<0x120 + 12>(w0), w2 = dpp_u32<0x120 + 8>(w0), w3 = dpp_u32<0x120 + 4>(w0);
+  const uint2 a_hi2 = make_uint2(__builtin_amdgcn_perm(w1, w0, 0x07060302u), __builtin_amdgcn_perm(w3, w2, 0x07060302u));
+  const uint2 a_lo2 = make_uint2(__builtin_amdgcn_perm(w1, w0, 0x05040100u), __builtin_amdgcn_perm(w3, w2, 0x05040100u));
+  const bf16x4v_t a_hi = __builtin_bit_cast(bf16x4v_t, a_hi2), a_lo = __builtin_bit_cast(bf16x4v_t, a_lo2);
+  bf16x4v_t vb[8];
+  values_by_feature(v, vb);
+  // the eight accumulators in turn, twice: no product waits for the one before it
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc_o.c[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, vb[e], acc_o.c[e], 0, 0, 0);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc_o.c[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, vb[e], acc_o.c[e], 0, 0, 0);
+}
+
 // One batch of Algorithm 1 for a key processor: scores of the batch's KB keys against the G heads, running
 // maximum / sum / output update.  `m` is the running maximum of the head the lane owns, `l` the sum of the
-// lane's own (key slot, head) weights, O the output slices of all G heads.
+// lane's own (key slot, head) weights, acc_o the output slices of all G heads.
 template <typename T, int G, bool MASKED>
 __device__ __forceinline__ void consume_batch(const Batch<T, (G == 8 ? 2 : 4), kMatrixScores<T, G>>& bt,
                                               const Queries<T, G>& qv, float scale_log2, int sub,
@@ -295,21 +383,7 @@ __device__ __forceinline__ void consume_batch(const Batch<T, (G == 8 ? 2 : 4), k
   const int i_own = c_own / G;                  // ... its key slot
   float dot;
   if constexpr (kMatrixScores<T, G>) {
-    // S^T = K Q^T: 16 keys x 128 features against 4 heads (each in four columns), the hi and the lo codes of
-    // the queries on an accumulator each.  The result's lane (n, row) holds the scores of head n % 4 for the
-    // four slots of processor `row`: lane n keeps slot n / 4, which is the combination it owns.
-    f32x4_t acc_h = {0.f, 0.f, 0.f, 0.f}, acc_l = acc_h;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const long a0 = (long)(((unsigned long long)bt.ka[h].y << 32) | bt.ka[h].x);
-      const long a1 = (long)(((unsigned long long)bt.ka[h].w << 32) | bt.ka[h].z);
-      acc_h = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a0, qv.hi[2 * h], acc_h, 0, 0, 0);
-      acc_l = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a0, qv.lo[2 * h], acc_l, 0, 0, 0);
-      acc_h = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a1, qv.hi[2 * h + 1], acc_h, 0, 0, 0);
-      acc_l = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a1, qv.lo[2 * h + 1], acc_l, 0, 0, 0);
-    }
-    const f32x4_t acc = acc_h + acc_l;
-    dot = i_own == 0 ? acc[0] : i_own == 1 ? acc[1] : i_own == 2 ? acc[2] : acc[3];
+    dot = matrix_scores<T>(bt, qv, sub);
   } else {
     // partial dot products of the lane's 8 features, all (key slot, head) combinations ...
     float d[C];
@@ -327,8 +401,8 @@ __device__ __forceinline__ void consume_batch(const Batch<T, (G == 8 ? 2 : 4), k
   const float t = live ? dot * scale_log2 : -INFINITY;
   // Algorithm 1, one step per batch: the head's running maximum lives in the lanes that own it
   float bm = ror_max<G, C>(t);
-  // matrix path: the value product below sums over the 16 keys of the wave, so its four processors keep ONE
-  // running maximum per head
+  // matrix path: the value product sums over the 16 keys of the wave, so its four processors keep ONE running
+  // maximum per head
   if constexpr (kMatrixValues<T, G>) bm = max_rows(bm);
   const float mn = fmaxf(m, bm);
   if (__builtin_amdgcn_ballot_w64(mn > m) != 0ull) {      // some maximum moved: rescale (wave-uniform branch)
@@ -352,85 +426,25 @@ __device__ __forceinline__ void consume_batch(const Batch<T, (G == 8 ? 2 : 4), k
   const float pw = fast_exp2(t - m);          // weight of the lane's own (key slot, head)
   l += pw;
   if constexpr (kMatrixValues<T, G>) {
-    // O += P V on the matrix cores, two v_mfma_f32_16x16x16_bf16 per feature e of the lane's eight: the sum runs
-    // over the wave's 16 keys, k = 4 * processor + slot.  A (weights): lane (m, row) holds head m's weights of
-    // the four slots of processor `row`; they sit in lanes m, m+4, m+8, m+12 of the row and come by row
-    // rotation (lanes 4..15 collect other combinations: rows of the product nobody reads).  A weight goes in as
-    // two bf16 numbers, its upper 16 bits and the rest rounded (16 significant bits together), one product each.
-    // B: lane (n, row) holds feature 8n + e of the same four keys, the lane's own V row pieces regrouped by
-    // feature (E4M3 -> bf16 is exact).  The result's rows 0..3 are the heads: register g of accumulator e, in the
-    // lanes of row 0, accumulates the output, summed over all four processors; what the other rows accumulate
-    // is never read.
-    typedef __bf16 bf16x2v_t __attribute__((ext_vector_type(2)));
-    typedef __bf16 bf16x4v_t __attribute__((ext_vector_type(4)));
-    typedef float f32x2_t __attribute__((ext_vector_type(2)));
-    const unsigned p_hi = __float_as_uint(pw) & 0xffff0000u;
-    const float p_rest = pw - __uint_as_float(p_hi);
-    const f32x2_t rest2 = {p_rest, p_rest};
-    const unsigned w0 = p_hi | (__builtin_bit_cast(unsigned, __builtin_convertvector(rest2, bf16x2v_t)) & 0xffffu);
-    // lane i <- lane i+4, i+8, i+12 (mod 16)
-    const unsigned w1 = dpp_u32<0x120 + 12>(w0), w2 = dpp_u32<0x120 + 8>(w0), w3 = dpp_u32<0x120 + 4>(w0);
-    const uint2 a_hi2 = make_uint2(__builtin_amdgcn_perm(w1, w0, 0x07060302u), __builtin_amdgcn_perm(w3, w2, 0x07060302u));
-    const uint2 a_lo2 = make_uint2(__builtin_amdgcn_perm(w1, w0, 0x05040100u), __builtin_amdgcn_perm(w3, w2, 0x05040100u));
-    const bf16x4v_t a = __builtin_bit_cast(bf16x4v_t, a_hi2), a_lo = __builtin_bit_cast(bf16x4v_t, a_lo2);
-    bf16x4v_t vb[8];                                       // B operands by feature
-    if constexpr (sizeof(T) == 2) {
-      // bf16 rows: word w of a row holds features 2w and 2w+1; the low (high) halves of the four slots' words are
-      // feature 2w (2w+1) of the four keys
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const unsigned s0 = w == 0 ? bt.v[0].r.x : w == 1 ? bt.v[0].r.y : w == 2 ? bt.v[0].r.z : bt.v[0].r.w;
-        const unsigned s1 = w == 0 ? bt.v[1].r.x : w == 1 ? bt.v[1].r.y : w == 2 ? bt.v[1].r.z : bt.v[1].r.w;
-        const unsigned s2 = w == 0 ? bt.v[2].r.x : w == 1 ? bt.v[2].r.y : w == 2 ? bt.v[2].r.z : bt.v[2].r.w;
-        const unsigned s3 = w == 0 ? bt.v[3].r.x : w == 1 ? bt.v[3].r.y : w == 2 ? bt.v[3].r.z : bt.v[3].r.w;
-        const uint2 even = make_uint2(__builtin_amdgcn_perm(s1, s0, 0x05040100u), __builtin_amdgcn_perm(s3, s2, 0x05040100u));
-        const uint2 odd = make_uint2(__builtin_amdgcn_perm(s1, s0, 0x07060302u), __builtin_amdgcn_perm(s3, s2, 0x07060302u));
-        vb[2 * w] = __builtin_bit_cast(bf16x4v_t, even);
-        vb[2 * w + 1] = __builtin_bit_cast(bf16x4v_t, odd);
-      }
-    } else {
-#pragma unroll
-    for (int w = 0; w < 2; ++w) {                          // word w of a row's eight codes: features 4w .. 4w+3
-      const unsigned s0 = w ? bt.v[0].r.y : bt.v[0].r.x, s1 = w ? bt.v[1].r.y : bt.v[1].r.x;
-      const unsigned s2 = w ? bt.v[2].r.y : bt.v[2].r.x, s3 = w ? bt.v[3].r.y : bt.v[3].r.x;
-      // bytes of two slots interleaved, then pairs of those: (slot 0, 1, 2, 3) of one feature per word
-      const unsigned t01l = __builtin_amdgcn_perm(s1, s0, 0x05010400u), t01h = __builtin_amdgcn_perm(s1, s0, 0x07030602u);
-      const unsigned t23l = __builtin_amdgcn_perm(s3, s2, 0x05010400u), t23h = __builtin_amdgcn_perm(s3, s2, 0x07030602u);
-      const unsigned f[4] = {__builtin_amdgcn_perm(t23l, t01l, 0x05040100u), __builtin_amdgcn_perm(t23l, t01l, 0x07060302u),
-                             __builtin_amdgcn_perm(t23h, t01h, 0x05040100u), __builtin_amdgcn_perm(t23h, t01h, 0x07060302u)};
-#pragma unroll
-      for (int x = 0; x < 4; ++x) {
-        const int e = 4 * w + x;
-        const bf16x2v_t b01 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)f[x], 1.0f, false);
-        const bf16x2v_t b23 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)f[x], 1.0f, true);
-        const bf16x4v_t b = {b01[0], b01[1], b23[0], b23[1]};
-        vb[e] = b;
-      }
-    }
-    }
-    // the eight accumulators in turn, twice: no product waits for the one before it
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc_o.c[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, vb[e], acc_o.c[e], 0, 0, 0);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc_o.c[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, vb[e], acc_o.c[e], 0, 0, 0);
+    matrix_value_update<T>(bt.v, pw, acc_o);
   } else {
-  // every lane needs every weight of its group for the value update: broadcast from the owner
-  float pb[C];
-  pb[0] = group_bcast<0>(pw); pb[1] = group_bcast<1>(pw); pb[2] = group_bcast<2>(pw); pb[3] = group_bcast<3>(pw);
-  if constexpr (C >= 8) { pb[4] = group_bcast<4>(pw); pb[5] = group_bcast<5>(pw); pb[6] = group_bcast<6>(pw); pb[7] = group_bcast<7>(pw); }
-  if constexpr (C == 16) {
-    pb[8] = group_bcast<8>(pw); pb[9] = group_bcast<9>(pw); pb[10] = group_bcast<10>(pw); pb[11] = group_bcast<11>(pw);
-    pb[12] = group_bcast<12>(pw); pb[13] = group_bcast<13>(pw); pb[14] = group_bcast<14>(pw); pb[15] = group_bcast<15>(pw);
-  }
+    // every lane needs every weight of its group for the value update: broadcast from the owner
+    float pb[C];
+    pb[0] = group_bcast<0>(pw); pb[1] = group_bcast<1>(pw); pb[2] = group_bcast<2>(pw); pb[3] = group_bcast<3>(pw);
+    if constexpr (C >= 8) { pb[4] = group_bcast<4>(pw); pb[5] = group_bcast<5>(pw); pb[6] = group_bcast<6>(pw); pb[7] = group_bcast<7>(pw); }
+    if constexpr (C == 16) {
+      pb[8] = group_bcast<8>(pw); pb[9] = group_bcast<9>(pw); pb[10] = group_bcast<10>(pw); pb[11] = group_bcast<11>(pw);
+      pb[12] = group_bcast<12>(pw); pb[13] = group_bcast<13>(pw); pb[14] = group_bcast<14>(pw); pb[15] = group_bcast<15>(pw);
+    }
 #pragma unroll
-  for (int i = 0; i < KB; ++i) {
-    float vf[8];
-    bt.v[i].to_float(vf);
+    for (int i = 0; i < KB; ++i) {
+      float vf[8];
+      bt.v[i].to_float(vf);
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+      for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc_o.O[g][e] = fmaf(pb[i * G + g], vf[e], acc_o.O[g][e]);
-  }
+        for (int e = 0; e < 8; ++e) acc_o.O[g][e] = fmaf(pb[i * G + g], vf[e], acc_o.O[g][e]);
+    }
   }
 }
 
