@@ -71,6 +71,9 @@ def parse():
                     help="batched workloads: the sequences hold N, N, N/2, N/2, N/4, N/4, ... keys instead of N each "
                          "(a serving batch of mixed context lengths; the keys beyond a sequence's length are left out "
                          "of its index), which makes the lists of the batch very unequal")
+    ap.add_argument("--prefill-block", type=int, default=0, metavar="TQ",
+                    help="also time prefill_sparse_attention on the last TQ tokens of the context (1+2047 always attended, "
+                         "one list per token and KV head from the classifier); S * TQ * Hkv <= 4096")
     ap.add_argument("--no-fixed-cost", action="store_true",
                     help="skip the fixed-cost launches (same kernel, next to no bytes), so that a profiler's per-kernel "
                          "average covers real launches only")
@@ -412,6 +415,53 @@ def main():
         quality_result.update({"query_sets": TQ, "metric": "mean share of softmax attention mass inside the visited buckets",
                                "bucket_attention_mass_us": round(ms_mass * 1e3, 2)})
 
+    prefill_result = None
+    if args.prefill_block:
+        # a block of prompt tokens at the end of the context, every token with its own lists (reading of the
+        # Conclusion's "prefill-time sparse attention": the decode-time rule per token, causal)
+        Tq, p_sink, p_recent = args.prefill_block, 1, 2047
+        if cfg.S * Tq * cfg.Hkv > 4096 or Tq >= cfg.N - p_sink - p_recent or args.mixed_lengths or with_append:
+            print("bench.py --prefill-block: S * TQ * Hkv must be <= 4096, TQ well below N, equal lengths, a step without append", file=sys.stderr)
+            sys.exit(2)
+        xq_t, q_t = gen.make_queries(cfg, args.seed + 1, dev, n_steps=Tq)
+        xq_b = torch.stack(list(xq_t), 1).contiguous()            # [S,Tq,Hq,d]
+        q_b = torch.stack(list(q_t), 1).contiguous()
+        lg_b = saap.classify_queries(xq_b.view(cfg.S * Tq, cfg.Hq, cfg.d), W1, b1, W2, b2, cfg.Hkv, output_kind=saap.LOGITS)
+        sel_b = saap.select_buckets_from_logits(lg_b, cfg.Hkv, cfg.nprobe)
+        sel_b = sel_b.view(cfg.S, Tq, cfg.Hkv, cfg.nprobe).permute(0, 2, 1, 3).contiguous()      # [S,Hkv,Tq,nprobe]
+        pos0 = torch.full((cfg.S,), cfg.N - Tq, dtype=torch.int32, device=dev)
+        p_out = torch.empty(cfg.S, Tq, cfg.Hq, cfg.d, dtype=torch.float32, device=dev)
+        p_lse = torch.empty(cfg.S, Tq, cfg.Hq, dtype=torch.float32, device=dev)
+        p_off, p_ln, p_idx, p_Ks, p_Vs = index
+
+        def prefill_block(i):
+            saap.prefill_sparse_attention(q_b, cache["K"], cache["V"], p_Ks, p_Vs, p_off, p_ln, p_idx, sel_b, pos0, p_sink,
+                                          p_recent, scale, out=p_out, lse=p_lse)
+
+        ms_block = GraphLoop(prefill_block, 4, torch).timed_ms_per_call(5)
+        # keys each (token, KV head) attends: sink + recent + the listed buckets' members between them
+        visited = 0
+        first_hi = cfg.N - Tq + 1 - p_recent                       # token 0 attends bucket members at positions < first_hi
+        for s_i in range(cfg.S):
+            for h_i in range(cfg.Hkv):
+                row = ids[s_i, h_i].to(torch.int64)
+                counts = torch.bincount(row[p_sink:first_hi], minlength=cfg.B)
+                steps_in = torch.nn.functional.one_hot(row[first_hi:first_hi + Tq - 1], cfg.B).cumsum(0)
+                per_tok = torch.cat([counts[None], counts[None] + steps_in], 0)            # [Tq,B]
+                visited += int(torch.gather(per_tok, 1, sel_b[s_i, h_i].to(torch.int64)).sum().item())
+        visited += cfg.S * cfg.Hkv * Tq * (p_sink + p_recent)
+        prefill_result = {
+            "block_tokens": Tq, "n_sink": p_sink, "n_recent": p_recent, "nprobe": cfg.nprobe,
+            "prefill_sparse_attention_us_per_block": round(ms_block * 1e3, 2),
+            "us_per_token": round(ms_block * 1e3 / (cfg.S * Tq), 3),
+            "keys_attended_per_token_and_kv_head": round(visited / (cfg.S * cfg.Hkv * Tq), 1),
+            "bytes_per_block": visited * BYTES_PER_KEY,
+            "achieved_GBps": round(visited * BYTES_PER_KEY / (ms_block * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(visited * BYTES_PER_KEY / (ms_block * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "note": "every token reads its own keys (512 B per attended key); dense causal attention of the same block "
+                    "would read the whole context once per block",
+        }
+
     kv8_result = None
     if args.kv8:
         # the same index over an 8-bit copy of the sorted cache (256 bytes per visited key)
@@ -591,6 +641,8 @@ def main():
         result["model_step"] = layers_result
     if kv8_result:
         result["kv8"] = kv8_result
+    if prefill_result:
+        result["prefill_sparse_attention"] = prefill_result
     if quality_result:
         result["routing_quality"] = quality_result
     if with_append:
