@@ -835,15 +835,21 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
           s_off[b] = ov[k];
         }
       }
-#pragma unroll
-      for (int k = 0; k < 2; ++k) {
-        const int j = tid + k * NT;
-        if (j < nseg) pre[j + 1] = sv[k];               // bucket id for now
-      }
-      __syncthreads();
       int bsel[2];                                       // per <= 2 in this mode
-      for (int j = j0; j < j1; ++j) bsel[j - j0] = pre[j + 1];
-      __syncthreads();
+      if (per == 1) {
+        // thread j already holds entry j of the list
+        bsel[0] = sv[0];
+        __syncthreads();
+      } else {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+          const int j = tid + k * NT;
+          if (j < nseg) pre[j + 1] = sv[k];             // bucket id for now
+        }
+        __syncthreads();
+        for (int j = j0; j < j1; ++j) bsel[j - j0] = pre[j + 1];
+        __syncthreads();
+      }
       for (int j = j0; j < j1; ++j) {
         const int b = bsel[j - j0];
         const int ln = s_len[b];
