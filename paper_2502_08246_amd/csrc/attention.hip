@@ -19,9 +19,10 @@
 //     unit (through the workspace) are combined with the log-sum-exp merge of Algorithm 2.
 //     The last workgroup of a unit to arrive (atomic counter) performs the final merge, so
 //     partial attention and merge are one launch.
-//   * With four heads per KV head the value product P V runs on the matrix cores, the four
-//     keys a lane holds being the sum index of v_mfma_f32_16x16x16_bf16; the running maximum
-//     is then one per head and wave.  On an 8-bit cache the scores run there as well.
+//   * On bf16 and 8-bit caches the value product P V runs on the matrix cores, the keys a
+//     lane holds being the sum index of v_mfma_f32_16x16x16_bf16; the running maximum is then
+//     one per head and wave.  On an 8-bit cache with four heads per KV head the scores run
+//     there as well.
 #include "common.h"
 
 #include <mutex>
@@ -102,11 +103,11 @@ __device__ __forceinline__ void store_out(const AttnParams& p, int qrow, int e, 
   if (e == 0 && p.lse) p.lse[qrow] = l > 0.f ? (M + __log2f(l)) * kLn2 : -INFINITY;
 }
 
-// Groups of four heads use the matrix cores (see consume_batch).
-// Values, O += P V: for bf16 and 8-bit caches.  The sum runs over the keys, and the four keys a lane holds of a
+// bf16 and 8-bit caches use the matrix cores (see consume_batch).
+// Values, O += P V: for every group size.  The sum runs over the keys, and the four keys a lane holds of a
 // row piece are the four k-values a lane contributes to v_mfma_f32_16x16x16_bf16, so the loads keep their layout
 // (16 lanes per row, whole cache lines).
-// Scores, S = K Q^T: for 8-bit caches only.  The sum runs over the features, so the operand wants lane (m, kg) to
+// Scores, S = K Q^T: for 8-bit caches and groups of four heads only.  The sum runs over the features, so the operand wants lane (m, kg) to
 // hold a piece of row m: 16 different rows in 16 neighbouring lanes, a load that touches 16 cache lines per 16
 // lanes.  On 8-bit rows this still pays (v_mfma_f32_16x16x32_fp8_fp8 takes the codes as they are, where the
 // vector ALUs convert every code before they multiply it with four heads: 29 against 32 us at 8 x 128k); on
@@ -114,7 +115,7 @@ __device__ __forceinline__ void store_out(const AttnParams& p, int qrow, int e, 
 template <typename T, int G>
 constexpr bool kMatrixScores = sizeof(T) == 1 && G == 4;
 template <typename T, int G>
-constexpr bool kMatrixValues = sizeof(T) <= 2 && G == 4;
+constexpr bool kMatrixValues = sizeof(T) <= 2;
 
 // One batch of a key processor: KB rows of K and V, and which of them are real keys.
 // MM (matrix-core scores): the wave's 16 keys form the A operand instead, lane (m, kg) = (lane % 16, lane / 16)
@@ -266,18 +267,24 @@ struct Accum {
       for (int e = 0; e < 8; ++e) out[g][e] = O[g][e];
   }
 };
-template <>
-struct Accum<4, true> {
+// Rows 0..3 of the product (heads 0..3) are the registers of the lanes of row 0; with eight heads, rows 4..7 are
+// those of the lanes of row 1.
+template <int G>
+struct Accum<G, true> {
   f32x4_t c[8];
   __device__ __forceinline__ void zero() {
 #pragma unroll
     for (int e = 0; e < 8; ++e) c[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
-  __device__ __forceinline__ void rows(float (&out)[4][8]) const {
+  // out[g][e] in the lanes of row 0 (what the combination across waves reads)
+  __device__ __forceinline__ void rows(float (&out)[G][8]) const {
 #pragma unroll
-    for (int g = 0; g < 4; ++g)
+    for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) out[g][e] = c[e][g];
+      for (int e = 0; e < 8; ++e) {
+        if (g < 4) out[g][e] = c[e][g];
+        else out[g][e] = __shfl_down(c[e][g - 4], 16);
+      }
   }
 };
 
@@ -302,30 +309,39 @@ __device__ __forceinline__ float matrix_scores(const Batch<T, 4, true>& bt, cons
   return slot == 0 ? acc[0] : slot == 1 ? acc[1] : slot == 2 ? acc[2] : acc[3];
 }
 
-// The B operands of the value product: for each of the lane's eight features e, that feature of the four keys
-// (slots) whose row pieces the lane holds, as bf16.
+// The B operands of the value product: for each of the lane's eight features e, that feature of the KB keys
+// (slots) whose row pieces the lane holds, as bf16; with two slots the other two k-values are zero.
 typedef __bf16 bf16x2v_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x4v_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ void values_by_feature(const Vec8<bf16_t> (&v)[4], bf16x4v_t (&vb)[8]) {
-  // word w of a row piece holds features 2w and 2w+1: the low (high) halves of the four slots' words are
-  // feature 2w (2w+1) of the four keys
+template <int KB>
+__device__ __forceinline__ void values_by_feature(const Vec8<bf16_t> (&v)[KB], bf16x4v_t (&vb)[8]) {
+  // word w of a row piece holds features 2w and 2w+1: the low (high) halves of the slots' words are feature
+  // 2w (2w+1) of the keys
 #pragma unroll
   for (int w = 0; w < 4; ++w) {
-    const unsigned s0 = w == 0 ? v[0].r.x : w == 1 ? v[0].r.y : w == 2 ? v[0].r.z : v[0].r.w;
-    const unsigned s1 = w == 0 ? v[1].r.x : w == 1 ? v[1].r.y : w == 2 ? v[1].r.z : v[1].r.w;
-    const unsigned s2 = w == 0 ? v[2].r.x : w == 1 ? v[2].r.y : w == 2 ? v[2].r.z : v[2].r.w;
-    const unsigned s3 = w == 0 ? v[3].r.x : w == 1 ? v[3].r.y : w == 2 ? v[3].r.z : v[3].r.w;
-    const uint2 even = make_uint2(__builtin_amdgcn_perm(s1, s0, 0x05040100u), __builtin_amdgcn_perm(s3, s2, 0x05040100u));
-    const uint2 odd = make_uint2(__builtin_amdgcn_perm(s1, s0, 0x07060302u), __builtin_amdgcn_perm(s3, s2, 0x07060302u));
+    auto word = [&](int i) { return w == 0 ? v[i].r.x : w == 1 ? v[i].r.y : w == 2 ? v[i].r.z : v[i].r.w; };
+    const unsigned s0 = word(0), s1 = word(1);
+    uint2 even = make_uint2(__builtin_amdgcn_perm(s1, s0, 0x05040100u), 0u);
+    uint2 odd = make_uint2(__builtin_amdgcn_perm(s1, s0, 0x07060302u), 0u);
+    if constexpr (KB == 4) {
+      const unsigned s2 = word(2), s3 = word(3);
+      even.y = __builtin_amdgcn_perm(s3, s2, 0x05040100u);
+      odd.y = __builtin_amdgcn_perm(s3, s2, 0x07060302u);
+    }
     vb[2 * w] = __builtin_bit_cast(bf16x4v_t, even);
     vb[2 * w + 1] = __builtin_bit_cast(bf16x4v_t, odd);
   }
 }
-__device__ __forceinline__ void values_by_feature(const Vec8<fp8_t> (&v)[4], bf16x4v_t (&vb)[8]) {
+template <int KB>
+__device__ __forceinline__ void values_by_feature(const Vec8<fp8_t> (&v)[KB], bf16x4v_t (&vb)[8]) {
 #pragma unroll
   for (int w = 0; w < 2; ++w) {                          // word w of a row piece: the codes of features 4w .. 4w+3
     const unsigned s0 = w ? v[0].r.y : v[0].r.x, s1 = w ? v[1].r.y : v[1].r.x;
-    const unsigned s2 = w ? v[2].r.y : v[2].r.x, s3 = w ? v[3].r.y : v[3].r.x;
+    unsigned s2 = 0u, s3 = 0u;                           // code 0 is the value 0
+    if constexpr (KB == 4) {
+      s2 = w ? v[2].r.y : v[2].r.x;
+      s3 = w ? v[3].r.y : v[3].r.x;
+    }
     // bytes of two slots interleaved, then pairs of those: (slot 0, 1, 2, 3) of one feature per word
     const unsigned t01l = __builtin_amdgcn_perm(s1, s0, 0x05010400u), t01h = __builtin_amdgcn_perm(s1, s0, 0x07030602u);
     const unsigned t23l = __builtin_amdgcn_perm(s3, s2, 0x05010400u), t23h = __builtin_amdgcn_perm(s3, s2, 0x07030602u);
@@ -340,28 +356,35 @@ __device__ __forceinline__ void values_by_feature(const Vec8<fp8_t> (&v)[4], bf1
   }
 }
 
-// O += P V of a wave batch on the matrix cores (four heads), two v_mfma_f32_16x16x16_bf16 per feature e of the
-// lane's eight: the sum runs over the wave's 16 keys, k = 4 * processor + slot.
-// A (weights): lane (m, row) holds head m's weights of the four slots of processor `row`; they sit in lanes m, m+4,
-// m+8, m+12 of the row (`pw` is the weight of the lane's own (slot, head)) and come by row rotation; lanes 4..15
-// collect other combinations, rows of the product that nobody reads.  A weight goes in as two bf16 numbers, its
-// upper 16 bits and the rest rounded (16 significant bits together), one product each.
-// B: values_by_feature.  The result's rows 0..3 are the heads: register g of accumulator e, in the lanes of row 0,
-// accumulates the output summed over all four processors; what the other rows accumulate is never read.
-template <typename T>
-__device__ __forceinline__ void matrix_value_update(const Vec8<T> (&v)[4], float pw, Accum<4, true>& acc_o) {
+// O += P V of a wave batch on the matrix cores, two v_mfma_f32_16x16x16_bf16 per feature e of the lane's eight:
+// the sum runs over the wave's keys, k = 4 * processor + slot (two slots with eight heads: k-values 2 and 3 of
+// every processor are zero).
+// A (weights): lane (m, row) holds head m's weights of the slots of processor `row`; they sit in lanes m, m+G,
+// m+2G, ... of the row (`pw` is the weight of the lane's own (slot, head)) and come by row rotation; lanes from G
+// on collect other combinations, rows of the product that nobody reads.  A weight goes in as two bf16 numbers,
+// its upper 16 bits and the rest rounded (16 significant bits together), one product each.
+// B: values_by_feature.  The result's rows 0..G-1 are the heads (Accum), summed over all four processors; what
+// the other rows accumulate is never read.
+template <typename T, int G>
+__device__ __forceinline__ void matrix_value_update(const Vec8<T> (&v)[G == 8 ? 2 : 4], float pw, Accum<G, true>& acc_o) {
+  constexpr int KB = G == 8 ? 2 : 4;
   typedef float f32x2_t __attribute__((ext_vector_type(2)));
   const unsigned p_hi = __float_as_uint(pw) & 0xffff0000u;
   const float p_rest = pw - __uint_as_float(p_hi);
   const f32x2_t rest2 = {p_rest, p_rest};
   const unsigned w0 = p_hi | (__builtin_bit_cast(unsigned, __builtin_convertvector(rest2, bf16x2v_t)) & 0xffffu);
-  // lane i <- lane i+4, i+8, i+12 (mod 16)
-  const unsigned w1 = dpp_u32<0x120 + 12>(w0), w2 = dpp_u32<0x120 + 8>(w0), w3 = dpp_u32<0x120 + 4>(w0);
+  // slot j: lane i <- lane i + j*G (mod 16), a rotation by 16 - j*G
+  const unsigned w1 = dpp_u32<0x120 + ((16 - G) & 15)>(w0);
+  unsigned w2 = 0u, w3 = 0u;
+  if constexpr (KB == 4) {
+    w2 = dpp_u32<0x120 + ((16 - 2 * G) & 15)>(w0);
+    w3 = dpp_u32<0x120 + ((16 - 3 * G) & 15)>(w0);
+  }
   const uint2 a_hi2 = make_uint2(__builtin_amdgcn_perm(w1, w0, 0x07060302u), __builtin_amdgcn_perm(w3, w2, 0x07060302u));
   const uint2 a_lo2 = make_uint2(__builtin_amdgcn_perm(w1, w0, 0x05040100u), __builtin_amdgcn_perm(w3, w2, 0x05040100u));
   const bf16x4v_t a_hi = __builtin_bit_cast(bf16x4v_t, a_hi2), a_lo = __builtin_bit_cast(bf16x4v_t, a_lo2);
   bf16x4v_t vb[8];
-  values_by_feature(v, vb);
+  values_by_feature<KB>(v, vb);
   // the eight accumulators in turn, twice: no product waits for the one before it
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc_o.c[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, vb[e], acc_o.c[e], 0, 0, 0);
@@ -409,7 +432,13 @@ __device__ __forceinline__ void consume_batch(const Batch<T, (G == 8 ? 2 : 4), k
     const float alpha = fast_exp2(m - mn);
     l *= alpha;
     if constexpr (kMatrixValues<T, G>) {
-      const f32x4_t ag = {group_bcast<0>(alpha), group_bcast<1>(alpha), group_bcast<2>(alpha), group_bcast<3>(alpha)};
+      // register i of an accumulator is head i in the lanes of row 0 (head 4 + i in those of row 1 with eight
+      // heads); lane h of every row owns head h's factor
+      f32x4_t ag = {group_bcast<0>(alpha), group_bcast<1>(alpha), group_bcast<2>(alpha), group_bcast<3>(alpha)};
+      if constexpr (G == 8) {
+        const f32x4_t ag1 = {group_bcast<4>(alpha), group_bcast<5>(alpha), group_bcast<6>(alpha), group_bcast<7>(alpha)};
+        if ((threadIdx.x >> 4) & 1) ag = ag1;
+      }
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc_o.c[e] *= ag;
     } else {
@@ -426,7 +455,7 @@ __device__ __forceinline__ void consume_batch(const Batch<T, (G == 8 ? 2 : 4), k
   const float pw = fast_exp2(t - m);          // weight of the lane's own (key slot, head)
   l += pw;
   if constexpr (kMatrixValues<T, G>) {
-    matrix_value_update<T>(bt.v, pw, acc_o);
+    matrix_value_update<T, G>(bt.v, pw, acc_o);
   } else {
     // every lane needs every weight of its group for the value update: broadcast from the owner
     float pb[C];
