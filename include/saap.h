@@ -283,6 +283,9 @@ int32_t saap_classify_select(const void* xq, const void* W1, const float* b1,
  * list (B <= 8192; beyond that every head reads its list separately).
  * An empty selection gives out = 0, lse = -inf.
  * Bucket ids in `selected` must be distinct and inside [0,B).
+ * Arithmetic: scores, softmax weights, sums and the merge in fp32.  On bf16 caches the weighted sum
+ * of the values runs on the matrix cores, where a weight enters with 16 significant bits (two bf16
+ * parts) and a bf16 value exactly; fp32 caches use fp32 throughout.
  */
 int32_t saap_sparse_decode_attention(const void* q, const void* Ksorted, const void* Vsorted,
                                      const int32_t* off, const int32_t* len,
