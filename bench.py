@@ -63,8 +63,9 @@ def parse():
                          "list; plan: the selection writes the visit plan and the attention deals all lists' keys to "
                          "the workgroups in equal shares (slower on the benchmark workloads, robust to lists of "
                          "very different sizes)")
-    ap.add_argument("--route", choices=["fused", "separate"], default="separate",
-                    help="separate (default): classify_queries and the selection as two calls; fused: classify_select, "
+    ap.add_argument("--route", choices=["fused", "separate", "attend"], default="separate",
+                    help="separate (default): classify_queries, the selection and the attention as three calls; attend: "
+                         "select_attend, the selection inside the attention launch (list path); fused: classify_select, "
                          "which at batch 1 runs the selection inside the classifier's output launch (measured no faster: "
                          "13.5 against 13.1 us at the 128k workload)")
     ap.add_argument("--mixed-lengths", action="store_true",
@@ -260,19 +261,29 @@ def main():
         saap.classify_select(xq[i % T], W1, b1, W2, b2, cfg.Hkv, cfg.nprobe, off=off, ln=ln, logits=scores, out=sel,
                              plan=plan if planned else None)
 
+    scores_sets = torch.empty(T, cfg.S, cfg.Hq, cfg.B, dtype=torch.float32, device=dev)
+
+    def select_attend_set(i):
+        saap.select_attend(scores_sets[i % T], q[i % T], Ks, Vs, off, ln, cfg.nprobe, scale, selected=sel, out=out, lse=lse)
+
     def step(i):
-        if args.route == "fused":
-            route(i)
-        else:
+        if args.route == "attend":
             classify(i)
-            select(i)
-        attend(i)
+            saap.select_attend(scores, q[i % T], Ks, Vs, off, ln, cfg.nprobe, scale, selected=sel, out=out, lse=lse)
+        else:
+            if args.route == "fused":
+                route(i)
+            else:
+                classify(i)
+                select(i)
+            attend(i)
         if with_append:
             append(i)
 
     # selections of every query set (for the byte accounting and the per-kernel loops)
     for t in range(T):
         classify(t)
+        scores_sets[t].copy_(scores)
         saap.select_buckets_planned(scores, off, ln, cfg.Hkv, cfg.nprobe, input_kind=saap.LOGITS, out=sel_sets[t],
                                     plan=plan_sets[t])
     torch.cuda.synchronize()
@@ -299,6 +310,18 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     us_token_layer = wall_ms * 1e3 / cfg.S
+    # the same step with the selection inside the attention launch (select_attend), for the record beside `value`
+    alt_route = None
+    if args.route == "separate" and not planned:
+        def step_attend(i):
+            classify(i)
+            saap.select_attend(scores, q[i % T], Ks, Vs, off, ln, cfg.nprobe, scale, selected=sel, out=out, lse=lse)
+            if with_append:
+                append(i)
+
+        ms_alt = GraphLoop(step_attend, T, torch).timed_ms_per_call(max(1, args.steps // T))
+        alt_route = {"step": "classify_queries (logits) + select_attend" + (" + append_keys" if with_append else ""),
+                     "us_per_token_layer": round(ms_alt * 1e3 / cfg.S, 3), "how": "bench.py --route attend"}
 
     # ---------------------------------------------------------------- per-call timings (events, same stream)
     def attend_set(i):
@@ -317,6 +340,7 @@ def main():
     ms_classify = GraphLoop(classify, T, torch).timed_ms_per_call(reps)
     ms_select = GraphLoop(select, T, torch).timed_ms_per_call(reps)
     ms_route = GraphLoop(route, T, torch).timed_ms_per_call(reps)
+    ms_select_attend = GraphLoop(select_attend_set, T, torch).timed_ms_per_call(reps)
     ms_append = GraphLoop(append, T, torch).timed_ms_per_call(2) if with_append else None
     ms_dense = None if args.no_dense else GraphLoop(dense, 8, torch).timed_ms_per_call(3)
     # Fixed cost of the attention launch: the same call on the same lists with every bucket one key long, i.e.
@@ -583,7 +607,8 @@ def main():
         "config": {
             "workload": cfg.name, "S": cfg.S, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "d": cfg.d, "N": cfg.N, "B": cfg.B,
             "nprobe": cfg.nprobe, "classifier": f"{cfg.d}->{cfg.hidden}->{cfg.B}", "query_sets": T,
-            "step": (("classify_select" if args.route == "fused" else
+            "step": ("classify_queries (logits) + select_attend" if args.route == "attend" else
+                     ("classify_select" if args.route == "fused" else
                       "classify_queries (logits) + " + ("select_buckets_planned" if planned else "select_buckets_from_logits"))
                      + (" + planned_decode_attention" if planned else " + sparse_decode_attention"))
                     + (" + append_keys" if with_append else ""),
@@ -615,6 +640,7 @@ def main():
             "select_buckets_from_logits": round(ms_select * 1e3, 3),
             "classify_select": round(ms_route * 1e3, 3),
             "sparse_decode_attention": round(ms_attn * 1e3, 3),
+            "select_attend": round(ms_select_attend * 1e3, 3),
             "dense_decode_attention": None if ms_dense is None else round(ms_dense * 1e3, 3),
             "append_keys": None if ms_append is None else round(ms_append * 1e3, 3),
         },
@@ -643,6 +669,8 @@ def main():
         result["kv8"] = kv8_result
     if prefill_result:
         result["prefill_sparse_attention"] = prefill_result
+    if alt_route:
+        result["select_attend_route"] = alt_route
     if quality_result:
         result["routing_quality"] = quality_result
     if with_append:

@@ -296,6 +296,35 @@ int32_t saap_sparse_decode_attention(const void* q, const void* Ksorted, const v
                                      void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * select_attend -- saap_select_buckets_from_logits and saap_sparse_decode_attention in one call:
+ * the nprobe best buckets of every KV head's group (Section 5 "Batched queries": the classifier
+ * outputs of the G heads, here their softmax over the logits, are summed and the top nprobe taken,
+ * ordered by score descending, id ascending), then exact attention over those buckets (Section 4
+ * "Beyond top-k", Appendix F Algorithms 1 and 2).
+ *   logits [S,Hq,B] fp32 (saap_classify_queries with SAAP_LOGITS); selected [S,Hkv,nprobe] int32 is
+ *   an OUTPUT (the lists attended, identical to what saap_select_buckets_from_logits returns);
+ *   every other argument as in saap_sparse_decode_attention with mode SAAP_GROUP_SUM.
+ * For bf16 and 8-bit caches, 64 <= B <= 4096 and lists shorter than half of B (rounded up to powers
+ * of two) it is ONE launch: every workgroup of a (sequence, KV head) derives the list itself from
+ * the logits and goes on to attend, which saves a launch and a dependent memory round trip per
+ * decode step.  Other shapes run as the two calls; the results are the same either way.
+ * Workspace: SAAP_OP_SPARSE_DECODE_ATTENTION.
+ */
+int32_t saap_select_attend(const float* logits, const void* q, const void* Ksorted, const void* Vsorted,
+                           const int32_t* off, const int32_t* len, int32_t nprobe, float scale,
+                           int32_t* selected, void* out, int32_t out_dtype, float* lse,
+                           int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d,
+                           int32_t dtype, void* ws, size_t ws_bytes, void* stream);
+
+/* The same on an 8-bit cache written by saap_quantize_kv (q bf16). */
+int32_t saap_select_attend_fp8(const float* logits, const void* q, const uint8_t* K8, const uint8_t* V8,
+                               const float* kscale, const float* vscale, const int32_t* off,
+                               const int32_t* len, int32_t nprobe, float scale, int32_t* selected,
+                               void* out, int32_t out_dtype, float* lse,
+                               int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d,
+                               void* ws, size_t ws_bytes, void* stream);
+
+/*
  * sparse_decode_attention_noalloc -- saap_sparse_decode_attention for callers that cannot allocate or
  * pass device scratch: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  The arguments, the result and the limits are those of saap_sparse_decode_attention

@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     adam_update, append_keys, assign_keys, bucket_attention_mass, bucket_attention_mass_batch, build_bucket_index, build_windowed_index, classify_queries, dense_decode_attention,
     dense_decode_attention_fp8, quantize_kv, query_model_loss_grads, query_model_bn_loss_grads, fold_batch_norm, sparse_decode_attention_fp8,
     library_path, lloyd_iterations, load_library, recompact_index, select_buckets, select_buckets_from_logits, sparse_decode_attention, stream_read_probe, mfma_rate_probe, update_centroids, window_push, window_push_fp8, append_keys_fp8, windowed_decode_attention, windowed_decode_attention_fp8,
-    build_visit_plan, planned_decode_attention, planned_decode_attention_fp8, select_buckets_planned, visit_plan_ints, sparse_decode_attention_noalloc, prefill_sparse_attention, classify_select,
+    build_visit_plan, planned_decode_attention, planned_decode_attention_fp8, select_buckets_planned, visit_plan_ints, sparse_decode_attention_noalloc, prefill_sparse_attention, classify_select, select_attend, select_attend_fp8,
     workspace,
     workspace_bytes,
     workspace_reset,

@@ -37,7 +37,7 @@ EXPORTS = (
     "saap_bucket_attention_mass_batch", "saap_query_model_bn_loss_grads", "saap_fold_batch_norm",
     "saap_build_visit_plan", "saap_select_buckets_planned", "saap_planned_decode_attention",
     "saap_planned_decode_attention_fp8", "saap_visit_plan_bytes", "saap_sparse_decode_attention_noalloc",
-    "saap_prefill_sparse_attention", "saap_classify_select",
+    "saap_prefill_sparse_attention", "saap_classify_select", "saap_select_attend", "saap_select_attend_fp8",
 )
 
 
@@ -666,6 +666,47 @@ def sparse_decode_attention_fp8(q, K8, V8, kscale, vscale, off, ln, selected, sc
         _ptr(ws), wsb, _stream())
     _check("saap_sparse_decode_attention_fp8", st)
     return out, lse
+
+
+def select_attend(logits, q, Ks, Vs, off, ln, nprobe, scale, out_dtype=torch.float32, selected=None, out=None,
+                  lse=None, ws=None):
+    """select_buckets_from_logits + sparse_decode_attention in one call (one launch where the library can):
+    logits fp32 [S,Hq,B] -> (selected int32 [S,Hkv,nprobe], out [S,Hq,d], lse fp32 [S,Hq])."""
+    S, Hq, d = q.shape
+    _, Hkv, Ncap, _ = Ks.shape
+    B = ln.shape[2]
+    dev = q.device
+    selected = selected if selected is not None else torch.empty(S, Hkv, nprobe, dtype=torch.int32, device=dev)
+    out = out if out is not None else torch.empty(S, Hq, d, dtype=out_dtype, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Hq, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_SPARSE_DECODE_ATTENTION, dev, ws, S=S, Hq=Hq, Hkv=Hkv, mode=GROUP_SUM)
+    st = load_library().saap_select_attend(
+        _ptr(logits), _ptr(q), _ptr(Ks), _ptr(Vs), _ptr(off), _ptr(ln), _i32(nprobe), ctypes.c_float(scale),
+        _ptr(selected) if nprobe > 0 else ctypes.c_void_p(0), _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S),
+        _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _ptr(ws), wsb, _stream())
+    _check("saap_select_attend", st)
+    return selected, out, lse
+
+
+def select_attend_fp8(logits, q, K8, V8, kscale, vscale, off, ln, nprobe, scale, out_dtype=torch.float32,
+                      selected=None, out=None, lse=None, ws=None):
+    """select_attend on a cache written by quantize_kv; q bf16 [S,Hq,d]."""
+    if q.dtype != torch.bfloat16 or K8.dtype != torch.uint8 or V8.dtype != torch.uint8:
+        raise TypeError("q must be bf16, K8 and V8 uint8")
+    S, Hq, d = q.shape
+    _, Hkv, Ncap, _ = K8.shape
+    B = ln.shape[2]
+    dev = q.device
+    selected = selected if selected is not None else torch.empty(S, Hkv, nprobe, dtype=torch.int32, device=dev)
+    out = out if out is not None else torch.empty(S, Hq, d, dtype=out_dtype, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Hq, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_SPARSE_DECODE_ATTENTION, dev, ws, S=S, Hq=Hq, Hkv=Hkv, mode=GROUP_SUM)
+    st = load_library().saap_select_attend_fp8(
+        _ptr(logits), _ptr(q), _ptr(K8), _ptr(V8), _ptr(kscale), _ptr(vscale), _ptr(off), _ptr(ln), _i32(nprobe),
+        ctypes.c_float(scale), _ptr(selected) if nprobe > 0 else ctypes.c_void_p(0), _ptr(out), _i32(_dtype_code(out)),
+        _ptr(lse), _i32(S), _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _ptr(ws), wsb, _stream())
+    _check("saap_select_attend_fp8", st)
+    return selected, out, lse
 
 
 def dense_decode_attention_fp8(q, K8, V8, kscale, vscale, scale, off=None, ln=None, out_dtype=torch.float32,

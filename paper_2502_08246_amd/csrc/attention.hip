@@ -23,7 +23,7 @@
 //     lane holds being the sum index of v_mfma_f32_16x16x16_bf16; the running maximum is then
 //     one per head and wave.  On an 8-bit cache with four heads per KV head the scores run
 //     there as well.
-#include "common.h"
+#include "select_body.h"
 
 #include <mutex>
 
@@ -64,6 +64,12 @@ struct AttnParams {
   float scale_log2;       // scale * log2(e)
   const float* kscale;    // 8-bit cache: [kv units] scale of the K codes, else null
   const float* vscale;    // 8-bit cache: [kv units] scale of the V codes, else null
+  // selection in the same launch (kernels with SEL != 0): the classifier's logits; `selected` is then an output
+  const float* logits;    // [S,Hq,B]
+  int32_t* selected_out;  // [units, nsel], written by the first workgroup of every unit
+  int sel_n_sort, sel_cap;       // geometry of the selection (select_geometry)
+  unsigned sel_plan_off;  // byte offset of its staging area in LDS
+  unsigned sel_lds;       // bytes of LDS the selection uses; the run tables of the attention follow
 };
 constexpr int kDtypeFp8 = 2;   // internal dtype code of an 8-bit cache (queries are bf16)
 
@@ -710,7 +716,11 @@ __device__ __forceinline__ void final_merge(const float* part_o, const float* pa
 // MASKED (with LIST): every head of the group brings its own list of runs (independent routing).
 // The union of the lists is visited once; a key takes part only for the heads whose list holds
 // its run (the others see a score of -inf for it).
-template <typename T, int G, bool LIST, int NT, bool MASKED = false>
+// SEL != 0 (with LIST, 512 threads): the launch also selects.  Every workgroup of a unit runs the selection of
+// the unit's list from the classifier's logits itself (SEL buckets per thread), all of them arriving at the same
+// list, and goes on with it: one launch and one dependent memory round trip less per decode step than a
+// selection kernel in front, and no hand-over between workgroups.
+template <typename T, int G, bool LIST, int NT, bool MASKED = false, int SEL = 0>
 __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_wsum[16];
@@ -757,7 +767,9 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
   constexpr int chunk = NG * KB;        // keys the workgroup consumes per batch
   const int kp = wave * 4 + grp;
 
-  int* pre = reinterpret_cast<int*>(smem);          // [nseg+1] exclusive prefix of run lengths
+  // with the selection in the launch its LDS comes first and the tables form a visit plan row: total, pre, rowoff
+  int* tables = reinterpret_cast<int*>(smem + (SEL != 0 ? p.sel_lds : 0u));
+  int* pre = tables + (SEL != 0 ? 1 : 0);           // [nseg+1] exclusive prefix of run lengths
   int* rowoff = pre + (p.nseg + 1);                 // [nseg]   first row of each run
   int* seglo = rowoff + p.nseg;                     // [max_chunks] run holding the first key of my k-th chunk
   int* seghi = seglo + p.max_chunks;                // [max_chunks] run holding its last key
@@ -830,6 +842,19 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
       }
     __syncthreads();
     T_total = pre[nseg];
+  } else if constexpr (LIST && SEL != 0) {
+    PlanOut po{};
+    po.off = p.off;
+    po.len = p.len;
+    po.plan = tables;                               // the plan row goes to LDS (stride 0: this unit's row only)
+    po.runs = p.B;
+    po.resident = -1;
+    po.ps = 0;
+    po.lds_off = p.sel_plan_off;
+    select_radix_body<SEL, true, false>(smem, unit, p.logits, nullptr, wg == 0 ? p.selected_out : nullptr, p.Hq,
+                                                         p.Hkv, p.B, p.nsel, 0, p.sel_n_sort, p.sel_cap, po);
+    __syncthreads();
+    T_total = tables[0];
   } else if (LIST) {
     const int per = (nseg + NT - 1) / NT;
     const int j0 = tid * per, j1 = min(j0 + per, nseg);
@@ -1764,9 +1789,9 @@ LaunchPlan plan_launch(int n_units, long long est_keys_per_unit, long long max_k
   return lp;
 }
 
-template <typename T, int G, bool LIST, int NT, bool MASKED = false>
+template <typename T, int G, bool LIST, int NT, bool MASKED = false, int SEL = 0>
 int32_t launch_nt(const AttnParams& p, const LaunchPlan& lp, hipStream_t stream) {
-  auto kern = attn_kernel<T, G, LIST, NT, MASKED>;
+  auto kern = attn_kernel<T, G, LIST, NT, MASKED, SEL>;
   if (lp.lds > 48 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lp.lds) != hipSuccess)
@@ -2156,6 +2181,124 @@ extern "C" int32_t saap_dense_decode_attention_fp8(const void* q, const uint8_t*
   if (!kscale || !vscale) return SAAP_INVALID_ARG;
   return dense_attention(q, K8, V8, kscale, vscale, off, len, B, scale, out, out_dtype, lse, S, Hq, Hkv, N, d,
                          kDtypeFp8, ws, ws_bytes, stream);
+}
+
+// ---- selection and attention in one launch -------------------------------------------------------------
+namespace saap {
+namespace {
+template <typename T, int G>
+int32_t launch_selecting(const AttnParams& p, const LaunchPlan& lp, int ept, hipStream_t stream) {
+  switch (ept) {
+    case 2: return launch_nt<T, G, true, 512, false, 2>(p, lp, stream);
+    case 4: return launch_nt<T, G, true, 512, false, 4>(p, lp, stream);
+    default: return launch_nt<T, G, true, 512, false, 8>(p, lp, stream);
+  }
+}
+}  // namespace
+}  // namespace saap
+
+// Shapes the selecting kernels take: group lists, 1024-4096 buckets handled by 512 threads, a list short enough
+// for the radix selection, bf16 or 8-bit cache.  Anything else runs as the two calls.
+static int32_t select_attend(const float* logits, const void* q, const void* Ksorted, const void* Vsorted,
+                             const float* kscale, const float* vscale, const int32_t* off, const int32_t* len,
+                             int32_t nprobe, float scale, int32_t* selected, void* out, int32_t out_dtype, float* lse,
+                             int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype,
+                             void* ws, size_t ws_bytes, void* stream) {
+  int32_t st = check_common(q, Ksorted, Vsorted, out, S, Hq, Hkv, d, dtype, out_dtype, ws);
+  if (st != SAAP_OK) return st;
+  if (!logits || !aligned16(logits) || !off || !len || B <= 0 || Ncap <= 0 || nprobe < 0 || nprobe > B) return SAAP_INVALID_ARG;
+  if (nprobe > 0 && (!selected || !aligned16(selected))) return SAAP_INVALID_ARG;
+  if (dtype == kDtypeFp8 && (!kscale || !vscale)) return SAAP_INVALID_ARG;
+  const int G = Hq / Hkv;
+  const long long units = (long long)S * Hkv;
+  int n_pow2 = 2, n_sort = 2;
+  while (n_pow2 < B) n_pow2 <<= 1;
+  while (n_sort < nprobe) n_sort <<= 1;
+  const int ept = B <= 1024 ? 2 : B <= 2048 ? 4 : 8;
+  const SelectGeometry geo = select_geometry(B, nprobe, true, B);
+  // a workgroup has 64 KB of LDS: the selection's area and the run tables behind it must fit with room for the
+  // kernels' static arrays
+  const bool lds_fits = ((geo.lds + 15) & ~(size_t)15) + (size_t)(2 * nprobe + 2) * sizeof(int) <= 48 * 1024;
+  const bool one_launch = nprobe > 0 && (dtype == SAAP_BF16 || dtype == kDtypeFp8) && B >= 64 && B <= 4096 && n_sort < n_pow2 &&
+                          lds_fits && units * sizeof(unsigned long long) <= SAAP_WS_HEADER_BYTES &&
+                          env_int("SAAP_SELECT_ATTEND_FUSED", 1) != 0;
+  auto two_calls = [&]() -> int32_t {
+    const int32_t s1 = saap_select_buckets_from_logits(logits, nullptr, selected, S, Hq, Hkv, B, nprobe, SAAP_GROUP_SUM, nullptr, 0, stream);
+    if (s1 != SAAP_OK) return s1;
+    return sparse_attention(q, Ksorted, Vsorted, kscale, vscale, off, len, selected, nprobe, SAAP_GROUP_SUM, -1, scale, out,
+                            out_dtype, lse, S, Hq, Hkv, Ncap, B, d, dtype, ws, ws_bytes, stream);
+  };
+  if (!one_launch) return two_calls();
+  if (ws_bytes < attn_workspace_bytes(units, G)) return SAAP_WORKSPACE_TOO_SMALL;
+  AttnParams p{};
+  p.q = q; p.K = Ksorted; p.V = Vsorted; p.off = off; p.len = len; p.selected = nullptr;
+  p.logits = logits; p.selected_out = selected;
+  p.out = out; p.lse = lse;
+  p.counters = reinterpret_cast<unsigned long long*>(ws);
+  p.cstride = units * 128 <= (long long)SAAP_WS_HEADER_BYTES ? 16 : 1;
+  p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
+  p.part_o = p.part_ml + (size_t)units * kMaxP * G * 2;
+  p.rows = Ncap; p.nsel = nprobe; p.resident = -1; p.nseg = nprobe; p.B = B; p.n_units = (int)units;
+  p.Hq = Hq; p.Hkv = Hkv; p.independent = 0; p.masked_lists = 0;
+  p.out_bf16 = out_dtype == SAAP_BF16;
+  p.n_dense = 0; p.scale_log2 = scale * kLog2e; p.kscale = kscale; p.vscale = vscale;
+  const long long est = (long long)Ncap * nprobe / B;
+  LaunchPlan lp = plan_launch((int)units, est, Ncap, G, nprobe, true, B, true, key_bytes(dtype));
+  if (lp.threads != 512) return two_calls();               // only a tuning override asks for another shape
+  p.P = lp.P;
+  p.stage = 0;
+  p.max_chunks = lp.max_chunks;
+  p.use_table = (est + (long long)lp.P * (lp.threads / 16 * (G == 8 ? 2 : 4)) - 1) / ((long long)lp.P * (lp.threads / 16 * (G == 8 ? 2 : 4))) > 2;
+  p.sel_n_sort = geo.n_sort;
+  p.sel_cap = geo.cap;
+  p.sel_plan_off = geo.plan_off;
+  p.sel_lds = (unsigned)((geo.lds + 15) & ~(size_t)15);
+  // selection area, then the plan row (total, pre, rowoff) and the per-chunk tables; the combination and merge
+  // scratch of plan_launch overlays them later
+  const size_t need = (size_t)p.sel_lds + (size_t)(2 * nprobe + 2 + 2 * lp.max_chunks) * sizeof(int);
+  if (need > 60 * 1024) return two_calls();                // very long units on few workgroups: the chunk tables alone fill the LDS
+  if (need > lp.lds) lp.lds = need;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+#define SAAP_CASE(TT, GG) return launch_selecting<TT, GG>(p, lp, ept, hs)
+  if (dtype == kDtypeFp8) {
+    switch (G) {
+      case 1: SAAP_CASE(fp8_t, 1);
+      case 2: SAAP_CASE(fp8_t, 2);
+      case 4: SAAP_CASE(fp8_t, 4);
+      case 8: SAAP_CASE(fp8_t, 8);
+    }
+  } else {
+    switch (G) {
+      case 1: SAAP_CASE(bf16_t, 1);
+      case 2: SAAP_CASE(bf16_t, 2);
+      case 4: SAAP_CASE(bf16_t, 4);
+      case 8: SAAP_CASE(bf16_t, 8);
+    }
+  }
+#undef SAAP_CASE
+  return SAAP_UNSUPPORTED;
+}
+
+extern "C" int32_t saap_select_attend(const float* logits, const void* q, const void* Ksorted, const void* Vsorted,
+                                      const int32_t* off, const int32_t* len, int32_t nprobe, float scale,
+                                      int32_t* selected, void* out, int32_t out_dtype, float* lse, int32_t S,
+                                      int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype,
+                                      void* ws, size_t ws_bytes, void* stream) {
+  begin_call();
+  if (dtype != SAAP_BF16 && dtype != SAAP_F32) return SAAP_UNSUPPORTED;
+  return select_attend(logits, q, Ksorted, Vsorted, nullptr, nullptr, off, len, nprobe, scale, selected, out, out_dtype,
+                       lse, S, Hq, Hkv, Ncap, B, d, dtype, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t saap_select_attend_fp8(const float* logits, const void* q, const uint8_t* K8, const uint8_t* V8,
+                                          const float* kscale, const float* vscale, const int32_t* off,
+                                          const int32_t* len, int32_t nprobe, float scale, int32_t* selected,
+                                          void* out, int32_t out_dtype, float* lse, int32_t S, int32_t Hq,
+                                          int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, void* ws, size_t ws_bytes,
+                                          void* stream) {
+  begin_call();
+  return select_attend(logits, q, K8, V8, kscale, vscale, off, len, nprobe, scale, selected, out, out_dtype, lse, S, Hq,
+                       Hkv, Ncap, B, d, kDtypeFp8, ws, ws_bytes, stream);
 }
 
 // ---- attention for callers that cannot allocate ---------------------------------------------------

@@ -351,9 +351,9 @@ __device__ __forceinline__ void select_radix_body(unsigned char* smem, int unit,
     __syncthreads();
   }
   SAAP_TRACE(3);
-  int32_t* out = selected + (size_t)unit * nprobe;
+  int32_t* out = selected ? selected + (size_t)unit * nprobe : nullptr;   // null: the list is wanted in LDS only
   auto put = [&](unsigned place, int32_t id) {
-    out[place] = id;
+    if (out) out[place] = id;
     if (po.off) s_sel[place] = id;
   };
   auto finish = [&]() {
