@@ -418,27 +418,26 @@ __device__ __forceinline__ void select_radix_body(unsigned char* smem, int unit,
     return;
   }
   if (n_sort <= kRankSortMax) {
-    // keys are distinct: the place of a key is the number of larger keys.  The comparisons of one
-    // key are split over several threads: work item (key i, part) counts the larger keys in its
-    // slice and adds the count to rank[i]
-    unsigned* rank = eqbits + bitmap_words(B);         // [cap], zeroed below
-    for (int i = tid; i < n_cand; i += nt) rank[i] = 0u;
-    __syncthreads();
+    // keys are distinct: the place of a key is the number of larger keys.  The comparisons of one key are
+    // split over `parts` neighbouring lanes (a power of two, so they share a wave): each counts the larger
+    // keys in its slice, the counts are added up over those lanes, and the first of them places the key.
     if (tid == 0) SAAP_TRACE_VALUE(6, n_cand);
-    const int parts = nt >= 2 * n_cand ? nt / n_cand : 1;
+    int parts = 1;
+    while (parts < 64 && 2 * parts * n_cand <= nt) parts *= 2;
     const int slice = (n_cand + parts - 1) / parts;
-    for (int w = tid; w < n_cand * parts; w += nt) {
-      const int i = w % n_cand, part = w / n_cand;
-      const int j0 = part * slice, j1 = min(j0 + slice, n_cand);
-      const unsigned long long mine = sortbuf[i];
+    const int items = n_cand * parts;
+    for (int w0 = 0; w0 < items; w0 += nt) {             // uniform trip count: every lane takes part in the exchanges
+      const int w = w0 + tid;
+      const int i = w / parts, part = w % parts;
+      const bool real = w < items;
+      const int j0 = part * slice, j1 = real ? min(j0 + slice, n_cand) : j0;
+      const unsigned long long mine = sortbuf[real ? i : 0];
       unsigned cnt = 0u;
 #pragma unroll 8
       for (int j = j0; j < j1; ++j) cnt += sortbuf[j] > mine ? 1u : 0u;
-      if (cnt) atomicAdd(&rank[i], cnt);
+      for (int o = 1; o < parts; o <<= 1) cnt += (unsigned)__shfl_xor((int)cnt, o);
+      if (real && part == 0 && cnt < (unsigned)nprobe) put(cnt, (int32_t)(0xFFFFFFFFu - (unsigned)(mine & 0xFFFFFFFFull)));
     }
-    __syncthreads();
-    for (int i = tid; i < n_cand; i += nt)
-      if (rank[i] < (unsigned)nprobe) put(rank[i], (int32_t)(0xFFFFFFFFu - (unsigned)(sortbuf[i] & 0xFFFFFFFFull)));
     SAAP_TRACE(4);
     finish();
     return;
@@ -481,7 +480,7 @@ inline SelectGeometry select_geometry(int B, int nprobe, bool with_plan, int run
   // grows with the square of their number, another radix pass costs less than that for long
   // lists), the padded list itself where a bitonic network does the ordering
   g.cap = g.n_sort <= kRankSortMax ? (g.n_sort <= 128 ? 2 * g.n_sort : g.n_sort + 128) : g.n_sort;
-  // sortbuf [cap] | bitmap [B/32 + 1, padded to 256 words and to an even count] | rank [cap] | bucketed copy [cap]
+  // sortbuf [cap] | bitmap [B/32 + 1, padded to 256 words and to an even count] | spare words [cap] | bucketed copy [cap]
   g.lds = (size_t)g.cap * sizeof(unsigned long long) + (size_t)bitmap_words(B) * sizeof(unsigned) +
           (g.n_sort <= kRankSortMax ? (size_t)g.cap * (sizeof(unsigned) + sizeof(unsigned long long)) : 0);
   if (with_plan) {
