@@ -50,6 +50,23 @@ __device__ __forceinline__ void emit_plan(const int* sel, const int* lens, const
   __shared__ int s_psum[16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nt = blockDim.x, nw = nt >> 6;
   const int nseg = nsel + (resident >= 0 ? 1 : 0);
+  if (nseg <= 64) {
+    // one wave holds the whole list: its prefix sum needs no exchange between waves
+    if (wave == 0) {
+      const int b = lane < nseg ? (lane < nsel ? sel[lane] : resident) : 0;
+      const int mine = lane < nseg ? max(lens[b], 0) : 0;
+      const int incl = (int)wave_prefix_sum((unsigned)mine);
+      if (lane < nseg) {
+        pl[2 + lane] = incl;
+        pl[nseg + 2 + lane] = offs[b];
+      }
+      if (lane == 63) {
+        pl[0] = incl;
+        pl[1] = 0;
+      }
+    }
+    return;
+  }
   const int per = (nseg + nt - 1) / nt;
   const int j0 = tid * per, j1 = min(j0 + per, nseg);
   int mine = 0;
@@ -192,6 +209,12 @@ __device__ __forceinline__ void select_radix_body(unsigned char* smem, int unit,
       ov[e] = offu[b];
     }
   }
+  // the selection's counters and buffers start at zero; with logits the two barriers of the softmax below put
+  // this ahead of their first use, otherwise a barrier of its own does
+  if (tid == 0) { s_cnt = 0u; s_neq = 0u; s_and = 0xFFFFFFFFu; s_or = 0u; }
+  for (int i = tid; i < cap; i += nt) sortbuf[i] = 0ull;
+  for (int i = tid; i <= B / 32; i += nt) eqbits[i] = 0u;
+  for (int i = tid; i < 256; i += nt) s_hist[0][i] = 0u;
   unsigned key[EPT];
   {
     float gs[EPT];
@@ -224,11 +247,7 @@ __device__ __forceinline__ void select_radix_body(unsigned char* smem, int unit,
       }
     }
   }
-  if (tid == 0) { s_cnt = 0u; s_neq = 0u; s_and = 0xFFFFFFFFu; s_or = 0u; }
-  for (int i = tid; i < cap; i += nt) sortbuf[i] = 0ull;
-  for (int i = tid; i <= B / 32; i += nt) eqbits[i] = 0u;
-  for (int i = tid; i < 256; i += nt) s_hist[0][i] = 0u;
-  __syncthreads();
+  if constexpr (!LOGITS) __syncthreads();   // (the plan's staging area is read after several more barriers)
 
   // Bits shared by every score image need no pass (softmax outputs share most exponent bits,
   // which would otherwise pile all buckets into two or three histogram bins).
