@@ -392,6 +392,12 @@ def main():
             saap.windowed_decode_attention(q[i % T], w_Ks, w_Vs, w_off, w_ln, sel, cfg.B, scale, out=out, lse=lse)
             w_push(i)
 
+        def w_step_attend(i):
+            classify(i)
+            saap.select_attend(scores, q[i % T], w_Ks, w_Vs, w_off, w_ln, cfg.nprobe, scale, selected=sel, out=out, lse=lse,
+                               resident_run=cfg.B)
+            w_push(i)
+
         w_keys = torch.gather(w_ln[:, :, :cfg.B].unsqueeze(0).expand(T, -1, -1, -1).to(torch.int64), 3,
                               sel_sets.to(torch.int64)).sum(dim=(1, 2, 3)).to(torch.float64).mean().item()
         w_keys += float(w_ln[:, :, cfg.B].sum().item())
@@ -399,11 +405,13 @@ def main():
         ms_w_attn = GraphLoop(w_attend, T, torch).timed_ms_per_call(w_reps)
         ms_w_push = GraphLoop(w_push, T, torch).timed_ms_per_call(w_reps)
         ms_w_step = GraphLoop(w_step, T, torch).timed_ms_per_call(w_reps)
+        ms_w_step_attend = GraphLoop(w_step_attend, T, torch).timed_ms_per_call(w_reps)
         torch.cuda.synchronize()
         window_result = {
             "n_sink": n_sink, "n_recent": n_recent, "slack": 64,
             "step_us_per_token_layer": round(ms_w_step * 1e3 / cfg.S, 3),
             "step": "classify_queries + select_buckets + windowed_decode_attention + window_push",
+            "step_with_select_attend_us_per_token_layer": round(ms_w_step_attend * 1e3 / cfg.S, 3),
             "windowed_decode_attention_us": round(ms_w_attn * 1e3, 3),
             "window_push_us": round(ms_w_push * 1e3, 3),
             "bytes_per_launch": round(w_keys * BYTES_PER_KEY),

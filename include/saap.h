@@ -316,6 +316,16 @@ int32_t saap_select_attend(const float* logits, const void* q, const void* Ksort
                            int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d,
                            int32_t dtype, void* ws, size_t ws_bytes, void* stream);
 
+/* The same over an index with a resident run (saap_build_windowed_index): the attention sink and the recent
+ * keys (Section 3 "Per-head attention span") are visited after the selected buckets, as by
+ * saap_windowed_decode_attention.  B counts the buckets (the columns of `logits`); resident_run is B,
+ * or -1 for an index without such a run (then this is saap_select_attend). */
+int32_t saap_select_attend_windowed(const float* logits, const void* q, const void* Ksorted, const void* Vsorted,
+                                    const int32_t* off, const int32_t* len, int32_t nprobe, int32_t resident_run,
+                                    float scale, int32_t* selected, void* out, int32_t out_dtype, float* lse,
+                                    int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d,
+                                    int32_t dtype, void* ws, size_t ws_bytes, void* stream);
+
 /* The same on an 8-bit cache written by saap_quantize_kv (q bf16). */
 int32_t saap_select_attend_fp8(const float* logits, const void* q, const uint8_t* K8, const uint8_t* V8,
                                const float* kscale, const float* vscale, const int32_t* off,

@@ -37,7 +37,7 @@ EXPORTS = (
     "saap_bucket_attention_mass_batch", "saap_query_model_bn_loss_grads", "saap_fold_batch_norm",
     "saap_build_visit_plan", "saap_select_buckets_planned", "saap_planned_decode_attention",
     "saap_planned_decode_attention_fp8", "saap_visit_plan_bytes", "saap_sparse_decode_attention_noalloc",
-    "saap_prefill_sparse_attention", "saap_classify_select", "saap_select_attend", "saap_select_attend_fp8",
+    "saap_prefill_sparse_attention", "saap_classify_select", "saap_select_attend", "saap_select_attend_fp8", "saap_select_attend_windowed",
 )
 
 
@@ -669,9 +669,14 @@ def sparse_decode_attention_fp8(q, K8, V8, kscale, vscale, off, ln, selected, sc
 
 
 def select_attend(logits, q, Ks, Vs, off, ln, nprobe, scale, out_dtype=torch.float32, selected=None, out=None,
-                  lse=None, ws=None):
+                  lse=None, ws=None, resident_run=-1):
     """select_buckets_from_logits + sparse_decode_attention in one call (one launch where the library can):
-    logits fp32 [S,Hq,B] -> (selected int32 [S,Hkv,nprobe], out [S,Hq,d], lse fp32 [S,Hq])."""
+    logits fp32 [S,Hq,B] -> (selected int32 [S,Hkv,nprobe], out [S,Hq,d], lse fp32 [S,Hq]).  With
+    resident_run = B (an index from build_windowed_index: off [S,Hkv,B+2], ln [S,Hkv,B+1]) the always-visited run
+    is attended too, as by windowed_decode_attention."""
+    if resident_run >= 0:
+        return _select_attend_windowed(logits, q, Ks, Vs, off, ln, nprobe, resident_run, scale, out_dtype, selected, out,
+                                       lse, ws)
     S, Hq, d = q.shape
     _, Hkv, Ncap, _ = Ks.shape
     B = ln.shape[2]
@@ -685,6 +690,24 @@ def select_attend(logits, q, Ks, Vs, off, ln, nprobe, scale, out_dtype=torch.flo
         _ptr(selected) if nprobe > 0 else ctypes.c_void_p(0), _ptr(out), _i32(_dtype_code(out)), _ptr(lse), _i32(S),
         _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _ptr(ws), wsb, _stream())
     _check("saap_select_attend", st)
+    return selected, out, lse
+
+
+def _select_attend_windowed(logits, q, Ks, Vs, off, ln, nprobe, resident_run, scale, out_dtype, selected, out, lse, ws):
+    S, Hq, d = q.shape
+    _, Hkv, Ncap, _ = Ks.shape
+    B = ln.shape[2] - 1
+    dev = q.device
+    selected = selected if selected is not None else torch.empty(S, Hkv, nprobe, dtype=torch.int32, device=dev)
+    out = out if out is not None else torch.empty(S, Hq, d, dtype=out_dtype, device=dev)
+    lse = lse if lse is not None else torch.empty(S, Hq, dtype=torch.float32, device=dev)
+    ws, wsb = _ws(OP_SPARSE_DECODE_ATTENTION, dev, ws, S=S, Hq=Hq, Hkv=Hkv, mode=GROUP_SUM)
+    st = load_library().saap_select_attend_windowed(
+        _ptr(logits), _ptr(q), _ptr(Ks), _ptr(Vs), _ptr(off), _ptr(ln), _i32(nprobe), _i32(resident_run),
+        ctypes.c_float(scale), _ptr(selected) if nprobe > 0 else ctypes.c_void_p(0), _ptr(out), _i32(_dtype_code(out)),
+        _ptr(lse), _i32(S), _i32(Hq), _i32(Hkv), _i32(Ncap), _i32(B), _i32(d), _i32(_dtype_code(q)), _ptr(ws), wsb,
+        _stream())
+    _check("saap_select_attend_windowed", st)
     return selected, out, lse
 
 

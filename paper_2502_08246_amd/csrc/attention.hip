@@ -67,6 +67,7 @@ struct AttnParams {
   // selection in the same launch (kernels with SEL != 0): the classifier's logits; `selected` is then an output
   const float* logits;    // [S,Hq,B]
   int32_t* selected_out;  // [units, nsel], written by the first workgroup of every unit
+  int sel_B;              // buckets the logits cover (p.B counts the runs of the index: one more with a resident run)
   int sel_n_sort, sel_cap;       // geometry of the selection (select_geometry)
   unsigned sel_plan_off;  // byte offset of its staging area in LDS
   unsigned sel_lds;       // bytes of LDS the selection uses; the run tables of the attention follow
@@ -848,11 +849,11 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     po.len = p.len;
     po.plan = tables;                               // the plan row goes to LDS (stride 0: this unit's row only)
     po.runs = p.B;
-    po.resident = -1;
+    po.resident = p.resident;                       // the always-visited run, if any, closes the plan
     po.ps = 0;
     po.lds_off = p.sel_plan_off;
     select_radix_body<SEL, true, false>(smem, unit, p.logits, nullptr, wg == 0 ? p.selected_out : nullptr, p.Hq,
-                                                         p.Hkv, p.B, p.nsel, 0, p.sel_n_sort, p.sel_cap, po);
+                                        p.Hkv, p.sel_B, p.nsel, 0, p.sel_n_sort, p.sel_cap, po);
     __syncthreads();
     T_total = tables[0];
   } else if (LIST) {
@@ -2201,12 +2202,16 @@ int32_t launch_selecting(const AttnParams& p, const LaunchPlan& lp, int ept, hip
 // for the radix selection, bf16 or 8-bit cache.  Anything else runs as the two calls.
 static int32_t select_attend(const float* logits, const void* q, const void* Ksorted, const void* Vsorted,
                              const float* kscale, const float* vscale, const int32_t* off, const int32_t* len,
-                             int32_t nprobe, float scale, int32_t* selected, void* out, int32_t out_dtype, float* lse,
-                             int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype,
-                             void* ws, size_t ws_bytes, void* stream) {
+                             int32_t nprobe, int32_t resident_run, float scale, int32_t* selected, void* out,
+                             int32_t out_dtype, float* lse, int32_t S, int32_t Hq, int32_t Hkv, int32_t Ncap, int32_t B,
+                             int32_t d, int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
+  // B: buckets (columns of the logits); the index has one run more when a resident run is visited (its number is B)
   int32_t st = check_common(q, Ksorted, Vsorted, out, S, Hq, Hkv, d, dtype, out_dtype, ws);
   if (st != SAAP_OK) return st;
   if (!logits || !aligned16(logits) || !off || !len || B <= 0 || Ncap <= 0 || nprobe < 0 || nprobe > B) return SAAP_INVALID_ARG;
+  if (resident_run != -1 && resident_run != B) return SAAP_INVALID_ARG;
+  const int runs = B + (resident_run >= 0 ? 1 : 0);
+  const int nseg = nprobe + (resident_run >= 0 ? 1 : 0);
   if (nprobe > 0 && (!selected || !aligned16(selected))) return SAAP_INVALID_ARG;
   if (dtype == kDtypeFp8 && (!kscale || !vscale)) return SAAP_INVALID_ARG;
   const int G = Hq / Hkv;
@@ -2215,18 +2220,18 @@ static int32_t select_attend(const float* logits, const void* q, const void* Kso
   while (n_pow2 < B) n_pow2 <<= 1;
   while (n_sort < nprobe) n_sort <<= 1;
   const int ept = B <= 1024 ? 2 : B <= 2048 ? 4 : 8;
-  const SelectGeometry geo = select_geometry(B, nprobe, true, B);
+  const SelectGeometry geo = select_geometry(B, nprobe, true, runs);
   // a workgroup has 64 KB of LDS: the selection's area and the run tables behind it must fit with room for the
   // kernels' static arrays
-  const bool lds_fits = ((geo.lds + 15) & ~(size_t)15) + (size_t)(2 * nprobe + 2) * sizeof(int) <= 48 * 1024;
+  const bool lds_fits = ((geo.lds + 15) & ~(size_t)15) + (size_t)(2 * nseg + 2) * sizeof(int) <= 48 * 1024;
   const bool one_launch = nprobe > 0 && (dtype == SAAP_BF16 || dtype == kDtypeFp8) && B >= 64 && B <= 4096 && n_sort < n_pow2 &&
                           lds_fits && units * sizeof(unsigned long long) <= SAAP_WS_HEADER_BYTES &&
                           env_int("SAAP_SELECT_ATTEND_FUSED", 1) != 0;
   auto two_calls = [&]() -> int32_t {
     const int32_t s1 = saap_select_buckets_from_logits(logits, nullptr, selected, S, Hq, Hkv, B, nprobe, SAAP_GROUP_SUM, nullptr, 0, stream);
     if (s1 != SAAP_OK) return s1;
-    return sparse_attention(q, Ksorted, Vsorted, kscale, vscale, off, len, selected, nprobe, SAAP_GROUP_SUM, -1, scale, out,
-                            out_dtype, lse, S, Hq, Hkv, Ncap, B, d, dtype, ws, ws_bytes, stream);
+    return sparse_attention(q, Ksorted, Vsorted, kscale, vscale, off, len, selected, nprobe, SAAP_GROUP_SUM, resident_run,
+                            scale, out, out_dtype, lse, S, Hq, Hkv, Ncap, runs, d, dtype, ws, ws_bytes, stream);
   };
   if (!one_launch) return two_calls();
   if (ws_bytes < attn_workspace_bytes(units, G)) return SAAP_WORKSPACE_TOO_SMALL;
@@ -2238,12 +2243,13 @@ static int32_t select_attend(const float* logits, const void* q, const void* Kso
   p.cstride = units * 128 <= (long long)SAAP_WS_HEADER_BYTES ? 16 : 1;
   p.part_ml = reinterpret_cast<float*>(static_cast<char*>(ws) + SAAP_WS_HEADER_BYTES);
   p.part_o = p.part_ml + (size_t)units * kMaxP * G * 2;
-  p.rows = Ncap; p.nsel = nprobe; p.resident = -1; p.nseg = nprobe; p.B = B; p.n_units = (int)units;
+  p.rows = Ncap; p.nsel = nprobe; p.resident = resident_run; p.nseg = nseg; p.B = runs; p.sel_B = B; p.n_units = (int)units;
   p.Hq = Hq; p.Hkv = Hkv; p.independent = 0; p.masked_lists = 0;
   p.out_bf16 = out_dtype == SAAP_BF16;
   p.n_dense = 0; p.scale_log2 = scale * kLog2e; p.kscale = kscale; p.vscale = vscale;
-  const long long est = (long long)Ncap * nprobe / B;
-  LaunchPlan lp = plan_launch((int)units, est, Ncap, G, nprobe, true, B, true, key_bytes(dtype));
+  // expected keys per unit as in sparse_attention: balanced buckets, plus the paper's default window for the resident run
+  const long long est = (long long)Ncap * nprobe / runs + (resident_run >= 0 ? 2048 : 0);
+  LaunchPlan lp = plan_launch((int)units, est, Ncap, G, nseg, true, runs, true, key_bytes(dtype));
   if (lp.threads != 512) return two_calls();               // only a tuning override asks for another shape
   p.P = lp.P;
   p.stage = 0;
@@ -2255,7 +2261,7 @@ static int32_t select_attend(const float* logits, const void* q, const void* Kso
   p.sel_lds = (unsigned)((geo.lds + 15) & ~(size_t)15);
   // selection area, then the plan row (total, pre, rowoff) and the per-chunk tables; the combination and merge
   // scratch of plan_launch overlays them later
-  const size_t need = (size_t)p.sel_lds + (size_t)(2 * nprobe + 2 + 2 * lp.max_chunks) * sizeof(int);
+  const size_t need = (size_t)p.sel_lds + (size_t)(2 * nseg + 2 + 2 * lp.max_chunks) * sizeof(int);
   if (need > 60 * 1024) return two_calls();                // very long units on few workgroups: the chunk tables alone fill the LDS
   if (need > lp.lds) lp.lds = need;
   hipStream_t hs = static_cast<hipStream_t>(stream);
@@ -2286,8 +2292,20 @@ extern "C" int32_t saap_select_attend(const float* logits, const void* q, const 
                                       void* ws, size_t ws_bytes, void* stream) {
   begin_call();
   if (dtype != SAAP_BF16 && dtype != SAAP_F32) return SAAP_UNSUPPORTED;
-  return select_attend(logits, q, Ksorted, Vsorted, nullptr, nullptr, off, len, nprobe, scale, selected, out, out_dtype,
+  return select_attend(logits, q, Ksorted, Vsorted, nullptr, nullptr, off, len, nprobe, -1, scale, selected, out, out_dtype,
                        lse, S, Hq, Hkv, Ncap, B, d, dtype, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t saap_select_attend_windowed(const float* logits, const void* q, const void* Ksorted,
+                                               const void* Vsorted, const int32_t* off, const int32_t* len,
+                                               int32_t nprobe, int32_t resident_run, float scale, int32_t* selected,
+                                               void* out, int32_t out_dtype, float* lse, int32_t S, int32_t Hq,
+                                               int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype, void* ws,
+                                               size_t ws_bytes, void* stream) {
+  begin_call();
+  if (dtype != SAAP_BF16 && dtype != SAAP_F32) return SAAP_UNSUPPORTED;
+  return select_attend(logits, q, Ksorted, Vsorted, nullptr, nullptr, off, len, nprobe, resident_run, scale, selected, out,
+                       out_dtype, lse, S, Hq, Hkv, Ncap, B, d, dtype, ws, ws_bytes, stream);
 }
 
 extern "C" int32_t saap_select_attend_fp8(const float* logits, const void* q, const uint8_t* K8, const uint8_t* V8,
@@ -2297,7 +2315,7 @@ extern "C" int32_t saap_select_attend_fp8(const float* logits, const void* q, co
                                           int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, void* ws, size_t ws_bytes,
                                           void* stream) {
   begin_call();
-  return select_attend(logits, q, K8, V8, kscale, vscale, off, len, nprobe, scale, selected, out, out_dtype, lse, S, Hq,
+  return select_attend(logits, q, K8, V8, kscale, vscale, off, len, nprobe, -1, scale, selected, out, out_dtype, lse, S, Hq,
                        Hkv, Ncap, B, d, kDtypeFp8, ws, ws_bytes, stream);
 }
 

@@ -138,3 +138,33 @@ def test_select_attend_under_graph_replay(saap):
         e_sel, e_out, e_lse = saap.select_attend(all_logits[t], q[t], Ks, Vs, off, ln, nprobe, SCALE)
         torch.cuda.synchronize()
         assert torch.equal(sel, e_sel) and torch.equal(out, e_out) and torch.equal(lse, e_lse)
+
+
+@pytest.mark.parametrize("n_sink,n_recent,nprobe,B", [(1, 255, 20, 256), (4, 60, 0, 128), (1, 2047, 51, 1024)])
+def test_select_attend_with_a_resident_run(saap, n_sink, n_recent, nprobe, B):
+    """Over a windowed index the always-visited run is attended after the selected buckets: lists as the selection
+    alone gives them, attention bit for bit as windowed_decode_attention on those lists, and within the tolerance of
+    the oracle's position-based definition."""
+    S, Hq, Hkv, N = 1, 8, 2, 9000
+    cfg = gen.CONFIGS["cfg1_llama8b_128k"].replace(S=S, Hq=Hq, Hkv=Hkv, N=N, B=B, nprobe=max(nprobe, 1), dtype="bf16", hidden=64)
+    cache = gen.make_cache(cfg, 83, DEV)
+    cent = gen.make_centroids(cfg, 83, DEV, cache, n_train=4096)
+    _, q = gen.make_queries(cfg, 83, DEV, n_steps=1)
+    ids = saap.assign_keys(cache["x_keys"], cent)
+    off, ln, idx, Ks, Vs, res = saap.build_windowed_index(ids, cache["K"], cache["V"], B, 4, n_sink, n_recent)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(31)
+    logits = 3 * torch.randn(S, Hq, B, generator=g, device=DEV)
+    sel, out, lse = saap.select_attend(logits, q[0], Ks, Vs, off, ln, nprobe, SCALE, resident_run=B)
+    if nprobe > 0:
+        want_sel = saap.select_buckets_from_logits(logits, Hkv, nprobe)
+    else:
+        want_sel = torch.empty(S, Hkv, 0, dtype=torch.int32, device=DEV)
+    two_out, two_lse = saap.windowed_decode_attention(q[0], Ks, Vs, off, ln, want_sel, B, SCALE)
+    torch.cuda.synchronize()
+    assert torch.equal(sel, want_sel)
+    assert torch.equal(out, two_out) and torch.equal(lse, two_lse)
+    r_out, r_lse = ref.windowed_decode_attention(h(q[0]), h(cache["K"]), h(cache["V"]), ids.cpu().numpy(), sel.cpu().numpy(),
+                                                 n_sink, n_recent, np.float32(SCALE), B)
+    assert_close(out.cpu().numpy(), r_out, "out")
+    assert_close(lse.cpu().numpy(), r_lse, "lse")
