@@ -110,6 +110,22 @@ def test_random_shape(saap, case):
     close(out.cpu().numpy(), ro, dtype, "attention out")
     close(lse.cpu().numpy(), rl, dtype, "attention lse")
 
+    # selection and attention in one call: the lists of the selection from logits, the attention of the separate
+    # call on those lists to the last bit (group lists only; a list as long as the padded bucket count is refused
+    # like the selection from logits itself)
+    n_sort, n_pow2 = 2, 2
+    while n_sort < nprobe:
+        n_sort *= 2
+    while n_pow2 < B:
+        n_pow2 *= 2
+    if mode == 0 and 0 < nprobe and n_sort < n_pow2:
+        want_sel = saap.select_buckets_from_logits(logits, Hkv, nprobe)
+        two_out, two_lse = saap.windowed_decode_attention(q[0], Ks, Vs, off, ln, want_sel, resident, SCALE)
+        sa_sel, sa_out, sa_lse = saap.select_attend(logits, q[0], Ks, Vs, off, ln, nprobe, SCALE, resident_run=resident)
+        torch.cuda.synchronize()
+        assert torch.equal(sa_sel, want_sel), "select_attend lists"
+        assert torch.equal(sa_out, two_out) and torch.equal(sa_lse, two_lse), "select_attend attention"
+
     # the attention mass per bucket (plain index only: the resident run is no bucket)
     if not c["window"]:
         mass, mlse = saap.bucket_attention_mass(q[0], Ks, off, ln, SCALE)
