@@ -253,6 +253,10 @@ def test_cfg1_with_the_papers_window_and_fused_selection(saap):
                                                SCALE, cfg.B)
         close(out.cpu().numpy(), ro)
         close(lse.cpu().numpy(), rl)
+        # selection inside the attention launch, over the index with its resident run
+        sa_sel, sa_out, sa_lse = saap.select_attend(logits, q[t], Ks, Vs, off, ln, cfg.nprobe, SCALE, resident_run=cfg.B)
+        torch.cuda.synchronize()
+        assert torch.equal(sa_sel, sel) and torch.equal(sa_out, out) and torch.equal(sa_lse, lse)
         pos = torch.full((cfg.S,), Nt, dtype=torch.int32, device=DEV)
         nid, _ = saap.window_push(x[:, :, Nt].contiguous(), K[:, :, Nt].contiguous(), V[:, :, Nt].contiguous(), pos, cent, None,
                                   off, ln, idx, Ks, Vs, res, n_sink, n_recent, overflow_flag=flag)
@@ -339,6 +343,11 @@ def test_batch32_128k_sampled(saap):
         ro, rl = ref.sparse_decode_attention(h(q[t][st]), hK, hV, r_off, r_ln, r_idx, r_sel, SCALE)
         close(out[st].cpu().numpy(), ro)
         close(lse[st].cpu().numpy(), rl)
+        # the same step with the selection inside the attention launch (few workgroups per list, many chunks each:
+        # the per-chunk run tables are in use): the same lists and the same attention to the last bit
+        sa_sel, sa_out, sa_lse = saap.select_attend(logits, q[t], Ks, Vs, off, ln, cfg.nprobe, SCALE)
+        torch.cuda.synchronize()
+        assert torch.equal(sa_sel, sel) and torch.equal(sa_out, out) and torch.equal(sa_lse, lse)
     out_d, lse_d = saap.dense_decode_attention(q[0], cache["K"], cache["V"], SCALE)
     torch.cuda.synchronize()
     do, dl = ref.dense_decode_attention(h(q[0][st[:1]]), hK[:1], hV[:1], SCALE)
