@@ -343,7 +343,8 @@ int32_t saap_select_attend_fp8(const float* logits, const void* q, const uint8_t
  * GPU until the process ends).  The call allocates nothing and frees nothing; it enqueues a small
  * fill kernel that clears the array's counters and then the attention kernel, both on `stream`.
  *   Shapes whose scratch would exceed the array (about S*Hkv*(Hq/Hkv) > 120 heads in one call, or
- *   more than 512 lists) return SAAP_WORKSPACE_TOO_SMALL before anything is enqueued.
+ *   more than 512 lists) return SAAP_WORKSPACE_TOO_SMALL before anything is enqueued; so do invalid
+ *   arguments (the codes of saap_sparse_decode_attention), checked before the device is touched.
  *   Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two
  *   streams, two threads) race and must be serialised by the caller.
  */

@@ -1892,6 +1892,18 @@ static int32_t check_common(const void* q, const void* K, const void* V, void* o
   return SAAP_OK;
 }
 
+// The index and the bucket lists of the list-driven attention calls.
+static int32_t check_lists(const int32_t* off, const int32_t* len, const int32_t* selected, int nprobe, int mode,
+                           int resident_run, int Ncap, int B) {
+  if (!off || !len || (nprobe > 0 && !selected)) return SAAP_INVALID_ARG;
+  if (mode != SAAP_GROUP_SUM && mode != SAAP_INDEPENDENT) return SAAP_INVALID_ARG;
+  if (B <= 0 || Ncap <= 0 || nprobe < 0 || resident_run < -1 || resident_run >= B) return SAAP_INVALID_ARG;
+  const int nseg = nprobe + (resident_run >= 0 ? 1 : 0);
+  if (nseg > B) return SAAP_INVALID_ARG;
+  if (nseg > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
+  return SAAP_OK;
+}
+
 // ---- visit plans and the attention that follows them ---------------------------------------------
 
 static long long plan_units(int S, int Hq, int Hkv, int mode) { return mode == SAAP_INDEPENDENT ? (long long)S * Hq : (long long)S * Hkv; }
@@ -2032,12 +2044,9 @@ static int32_t sparse_attention(const void* q, const void* Ksorted, const void* 
                                 int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
   int32_t st = check_common(q, Ksorted, Vsorted, out, S, Hq, Hkv, d, dtype, out_dtype, ws);
   if (st != SAAP_OK) return st;
-  if (!off || !len || (nprobe > 0 && !selected)) return SAAP_INVALID_ARG;
-  if (mode != SAAP_GROUP_SUM && mode != SAAP_INDEPENDENT) return SAAP_INVALID_ARG;
-  if (B <= 0 || Ncap <= 0 || nprobe < 0 || resident_run < -1 || resident_run >= B) return SAAP_INVALID_ARG;
+  st = check_lists(off, len, selected, nprobe, mode, resident_run, Ncap, B);
+  if (st != SAAP_OK) return st;
   int nseg = nprobe + (resident_run >= 0 ? 1 : 0);
-  if (nseg > B) return SAAP_INVALID_ARG;
-  if (nseg > SAAP_MAX_BUCKETS) return SAAP_UNSUPPORTED;
   const bool indep = mode == SAAP_INDEPENDENT;
   // Independent routing of G > 1 heads that share a KV head: one unit per KV head visits the union
   // of the heads' lists once, each head attending only its own runs (masked kernels).  They hold
@@ -2352,9 +2361,12 @@ extern "C" int32_t saap_sparse_decode_attention_noalloc(const void* q, const voi
                                                         int32_t d, int32_t dtype, void* stream) {
   begin_call();
   if (dtype != SAAP_F32 && dtype != SAAP_BF16) return SAAP_INVALID_ARG;
+  // every argument is checked before the device is touched (the scratch is the one pointer that is not the caller's)
+  int32_t st = check_common(q, Ksorted, Vsorted, out, S, Hq, Hkv, d, dtype, out_dtype, /*ws=*/q);
+  if (st != SAAP_OK) return st;
+  st = check_lists(off, len, selected, nprobe, mode, -1, Ncap, B);
+  if (st != SAAP_OK) return st;
   // the shape decides the scratch it needs; more than the array holds is refused before anything is enqueued
-  if (S <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return SAAP_INVALID_ARG;
-  if (mode != SAAP_GROUP_SUM && mode != SAAP_INDEPENDENT) return SAAP_INVALID_ARG;
   const int heads = Hq / Hkv;
   const bool indep = mode == SAAP_INDEPENDENT;
   const bool masked = indep && heads > 1 && B <= 16 * 512;
@@ -2363,7 +2375,7 @@ extern "C" int32_t saap_sparse_decode_attention_noalloc(const void* q, const voi
   if (units * 128 > (long long)SAAP_WS_HEADER_BYTES || attn_workspace_bytes(units, G) > (size_t)SAAP_STATIC_SCRATCH_BYTES)
     return SAAP_WORKSPACE_TOO_SMALL;
   void* ws = nullptr;
-  int32_t st = static_scratch(&ws);
+  st = static_scratch(&ws);
   if (st != SAAP_OK) return st;
   // The array keeps what the last call left.  Its arrival counters must be zero when the kernel starts: a
   // fill kernel clears them on the caller's stream (a call that was abandoned midway may have left some set).

@@ -253,6 +253,77 @@ def test_invalid_arguments_of_the_later_calls_are_rejected_on_the_host(lib):
     assert adam(p=None) == -1 and adam(n=0) == -1 and adam(step=0) == -1 and adam(b1=1.0) == -1 and adam(b2=-0.1) == -1
 
 
+def test_invalid_arguments_of_select_attend_prefill_and_the_probe_are_rejected_on_the_host(lib):
+    """Selection inside the attention launch, prefill-time sparse attention, the matrix-rate probe and the
+    no-allocation entry point: every argument check fails before anything is enqueued."""
+    logits, q, K, V, off, ln, sel, out, lse, ws, ks, vs, idx, pos0 = _fake(14)
+    i32, f32 = ctypes.c_int32, ctypes.c_float
+    big, small = ctypes.c_size_t(1 << 30), ctypes.c_size_t(1024)
+
+    def attend(**kw):
+        a = dict(logits=logits, off=off, sel=sel, nprobe=4, Hq=4, Hkv=1, Ncap=1000, B=64, d=128, dt=1, odt=0, wsb=big)
+        a.update(kw)
+        return lib.saap_select_attend(a["logits"], q, K, V, a["off"], ln, i32(a["nprobe"]), f32(0.1), a["sel"], out,
+                                      i32(a["odt"]), lse, i32(1), i32(a["Hq"]), i32(a["Hkv"]), i32(a["Ncap"]), i32(a["B"]),
+                                      i32(a["d"]), i32(a["dt"]), ws, a["wsb"], None)
+
+    assert attend(logits=None) == -1 and attend(off=None) == -1 and attend(sel=None) == -1
+    assert attend(nprobe=65) == -1 and attend(nprobe=-1) == -1 and attend(B=0) == -1 and attend(Ncap=0) == -1
+    assert attend(odt=5) == -1
+    assert attend(dt=2) == -2                                         # the 8-bit cache has an entry point of its own
+    assert attend(logits=ctypes.c_void_p(4100)) == -1                 # rows of logits are read 16 bytes at a time
+    assert attend(d=64) == -2 and attend(Hq=3) == -2
+    assert attend(wsb=small) == -3
+
+    def attend_w(res):
+        return lib.saap_select_attend_windowed(logits, q, K, V, off, ln, i32(4), i32(res), f32(0.1), sel, out, i32(0), lse,
+                                               i32(1), i32(4), i32(1), i32(1000), i32(64), i32(128), i32(1), ws, big, None)
+
+    assert attend_w(3) == -1 and attend_w(65) == -1 and attend_w(-2) == -1   # the resident run is run B, or there is none
+
+    def attend8(**kw):
+        a = dict(ks=ks, vs=vs, nprobe=4, wsb=big)
+        a.update(kw)
+        return lib.saap_select_attend_fp8(logits, q, K, V, a["ks"], a["vs"], off, ln, i32(a["nprobe"]), f32(0.1), sel, out,
+                                          i32(0), lse, i32(1), i32(4), i32(1), i32(1000), i32(64), i32(128), ws, a["wsb"], None)
+
+    assert attend8(ks=None) == -1 and attend8(vs=None) == -1 and attend8(nprobe=65) == -1 and attend8(wsb=small) == -3
+
+    def prefill(**kw):
+        a = dict(K=K, idx=idx, pos0=pos0, sel=sel, nprobe=4, sink=1, recent=15, Tq=8, Nt=100, B=8, d=128, dt=1, wsb=big)
+        a.update(kw)
+        return lib.saap_prefill_sparse_attention(q, a["K"], V, K, V, off, ln, a["idx"], a["sel"], a["pos0"], i32(a["nprobe"]),
+                                                 i32(a["sink"]), i32(a["recent"]), f32(0.1), out, i32(0), lse, i32(1), i32(4),
+                                                 i32(1), i32(a["Tq"]), i32(a["Nt"]), i32(116), i32(a["B"]), i32(a["d"]),
+                                                 i32(a["dt"]), ws, a["wsb"], None)
+
+    assert prefill(K=None) == -1 and prefill(idx=None) == -1 and prefill(pos0=None) == -1 and prefill(sel=None) == -1
+    assert prefill(Tq=0) == -1 and prefill(Nt=0) == -1 and prefill(nprobe=9) == -1 and prefill(sink=-1) == -1
+    assert prefill(recent=-1) == -1 and prefill(dt=2) == -1
+    assert prefill(d=64) == -2 and prefill(wsb=small) == -3
+
+    flop = ctypes.c_double(0.0)
+
+    def probe(**kw):
+        a = dict(ops=q, bytes=4096, iters=10, per_cu=1, sink=out)
+        a.update(kw)
+        return lib.saap_mfma_rate_probe(a["ops"], ctypes.c_size_t(a["bytes"]), i32(a["iters"]), i32(a["per_cu"]), a["sink"],
+                                        ctypes.byref(flop), None)
+
+    assert probe(ops=None) == -1 and probe(sink=None) == -1 and probe(bytes=32) == -1 and probe(iters=0) == -1
+    assert probe(per_cu=0) == -1 and probe(ops=ctypes.c_void_p(4100)) == -1
+
+    def noalloc(**kw):
+        a = dict(q=q, sel=sel, nprobe=4, mode=0, Hq=4, Hkv=1, B=8, d=128, dt=1)
+        a.update(kw)
+        return lib.saap_sparse_decode_attention_noalloc(a["q"], K, V, off, ln, a["sel"], i32(a["nprobe"]), i32(a["mode"]),
+                                                        f32(0.1), out, i32(0), lse, i32(1), i32(a["Hq"]), i32(a["Hkv"]),
+                                                        i32(100), i32(a["B"]), i32(a["d"]), i32(a["dt"]), None)
+
+    assert noalloc(q=None) == -1 and noalloc(sel=None) == -1 and noalloc(nprobe=9) == -1 and noalloc(mode=3) == -1
+    assert noalloc(d=64) == -2 and noalloc(Hq=3) == -2
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
