@@ -10,9 +10,9 @@
 //     second-best score; the low 4 bits of a score carry the accumulator register number, so
 //     the running argmax costs 2.5 vector instructions per score (tag; max3 and med3 + max per pair).
 //   * re-scoring kernel: a key whose best two fp32 scores are closer than the accumulation error
-//     bound is scored again, 32 such keys of a head at a time: two more matrix-core passes find
-//     every centroid within the bound of the key's maximum, and only those (typically two) are
-//     scored in double precision.
+//     bound is scored again, 32 such keys of a head at a time: one more matrix-core pass (two
+//     beyond 1024 buckets) finds every centroid within the bound of the key's maximum, and only
+//     those (typically two) are scored in double precision.
 //   * fp32 inputs: a plain double-precision kernel scores every key against every centroid.
 // No score matrix is ever written to memory.
 #include "common.h"
@@ -293,23 +293,28 @@ assign_exact_f32_kernel(const float* __restrict__ x, const float* __restrict__ c
 
 // Re-scoring of the listed keys (bf16).  The keys are listed per KV head; a workgroup takes 32
 // consecutive entries of one head's list as the B operand of the matrix instruction (every wave
-// holds the same 32 keys) and its sixteen waves share out the centroid tiles, so a centroid row is
+// holds the same 32 keys) and its eight waves share out the centroid tiles, so a centroid row is
 // read once for 32 keys.
-//   pass 1: fp32 scores of all centroids on the matrix cores, running maximum per key;
-//   pass 2: the same instructions again (same results bit for bit); every centroid whose score is
-//           within the error bound of the key's maximum goes into a candidate list in LDS.  Any
-//           centroid that can be the double-precision argmax is among them, because both fp32
-//           scores carry at most half the bound as error; a score that does not compare (NaN)
-//           counts as a candidate;
+//   pass 1: fp32 scores of all centroids on the matrix cores, running maximum per key; a wave keeps
+//           the scores of its first kKeepTiles tiles in registers (all of them up to 1024 buckets)
+//           and has the loads of those tiles in flight together;
+//   pass 2: every centroid whose score is within the error bound of the key's maximum goes into a
+//           candidate list in LDS: from the kept scores, and for further tiles from the same
+//           instructions run again (same results bit for bit).  Any centroid that can be the
+//           double-precision argmax is among them, because both fp32 scores carry at most half the
+//           bound as error; a score that does not compare (NaN) counts as a candidate;
 //   pass 3: the candidates (typically two per key) in double precision, in order, one per thread;
-//           then one thread per key picks the largest, lowest id on ties.
+//           the largest per key, lowest id on ties, through LDS atomics (maximum of the scores in
+//           an order-preserving integer form, then minimum of the ids that reach it).
 // If the list overflows (degenerate keys, e.g. all scores equal) the group's keys are scored
 // against every centroid in double precision instead.
-// Grid: (workgroups per head, Hkv).  counters[h] = length of head h's list, counters[Hkv] =
+// Grid: (Hkv, workgroups per head), the head fastest, so that the few workgroups that find a group
+// of keys are the first to be dispatched.  counters[h] = length of head h's list, counters[Hkv] =
 // workgroups that have finished.
 constexpr int kGroupKeys = 32;
 constexpr int kCandCap = 2048;
-constexpr int kRescoreThreads = 1024, kRescoreWaves = kRescoreThreads / 64;
+constexpr int kRescoreThreads = 512, kRescoreWaves = kRescoreThreads / 64;
+constexpr int kKeepTiles = 4;      // matrix tiles per wave whose scores stay in registers between the passes
 
 // double-precision score of centroid row c against key row xr (in order), rows of 16-byte pieces
 __device__ __forceinline__ double score_bf16_f64(const uint4* __restrict__ xr, const uint4* __restrict__ c) {
@@ -342,6 +347,12 @@ __device__ __forceinline__ bool better(double s, int id, double best, int best_i
   return id >= 0 && (best_id < 0 || s > best || (s == best && id < best_id));
 }
 
+// Doubles as unsigned integers in the same order (no NaNs; -0 is turned into +0 first).
+__device__ __forceinline__ unsigned long long ordered_bits(double v) {
+  const unsigned long long u = (unsigned long long)__double_as_longlong(v + 0.0);
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+}
+
 __global__ void __launch_bounds__(kRescoreThreads)
 assign_rescore_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cent,
                       const float* __restrict__ bias, const float* __restrict__ cmax,
@@ -354,13 +365,15 @@ assign_rescore_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ c
   __shared__ int s_key[kGroupKeys];        // global row of each key of the group
   __shared__ unsigned s_ncand;
   __shared__ int s_cand[kCandCap];         // key << 24 | centroid
-  __shared__ double s_cscore[kCandCap];
+  __shared__ unsigned long long s_cscore[kCandCap];   // ordered_bits of the candidate's score
+  __shared__ unsigned long long s_kbest[kGroupKeys];
+  __shared__ int s_kid[kGroupKeys];
   __shared__ double s_wbest[kRescoreWaves];
   __shared__ int s_wid[kRescoreWaves];
   __shared__ int s_flag;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int h = blockIdx.y;
+  const int h = blockIdx.x;
   const unsigned n_rows = counters[h];
   const unsigned n_groups = (n_rows + kGroupKeys - 1) / kGroupKeys;
   rows += (size_t)h * list_cap;
@@ -368,7 +381,8 @@ assign_rescore_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ c
   const float* bu = bias ? bias + (size_t)h * B : nullptr;
   const int n_tiles = (B + kCentTile - 1) / kCentTile;
 
-  for (unsigned grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
+  SAAP_TRACE(0);
+  for (unsigned grp = blockIdx.y; grp < n_groups; grp += gridDim.y) {
     const unsigned first = grp * kGroupKeys;
     const int n_here = (int)min((unsigned)kGroupKeys, n_rows - first);
     // B operand: lane holds features 16*step + 8*half .. +7 of key `col` (idle columns repeat the last key)
@@ -384,35 +398,87 @@ assign_rescore_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ c
       xnorm2 += v.dot(v);
     }
     xnorm2 += __shfl_xor(xnorm2, 32);
-    if (tid < kGroupKeys) s_key[tid] = gk;
+    SAAP_TRACE(1);
+    if (tid < kGroupKeys) {
+      s_key[tid] = gk;
+      s_kbest[tid] = 0ull;
+      s_kid[tid] = 0x7fffffff;
+    }
     if (tid == 0) s_ncand = 0u;
 
     // scores of centroid tile t for the 32 keys: register r of this lane is centroid
     // 32*t + 8*(r/4) + 4*half + r%4 against key `col`
-    auto tile_scores = [&](int t) {
-      bf16x8_t a[8];
+    auto tile_load = [&](int t, bf16x8_t (&a)[8]) {
       const bf16_t* cr = cu + (size_t)min(t * kCentTile + col, B - 1) * kD + half * 8;
 #pragma unroll
       for (int st = 0; st < 8; ++st) a[st] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(cr + st * 16));
+    };
+    auto tile_product = [&](const bf16x8_t (&a)[8]) {
       f32x16_t acc = {0};
 #pragma unroll
       for (int st = 0; st < 8; ++st) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[st], xb[st], acc, 0, 0, 0);
       return acc;
     };
     auto centroid_of = [&](int t, int r) { return t * kCentTile + 8 * (r / 4) + 4 * half + (r % 4); };
-
-    float mx = -INFINITY;
-    for (int t = wave; t < n_tiles; t += kRescoreWaves) {
-      const f32x16_t acc = tile_scores(t);
+    // the scores that are compared: matrix product plus the centroid's bias (one fp32 addition)
+    auto add_bias = [&](f32x16_t& acc, int t) {
+      if (bu) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] += bu[min(centroid_of(t, r), B - 1)];
+      }
+    };
+    auto tile_scores = [&](int t) {
+      bf16x8_t a[8];
+      tile_load(t, a);
+      f32x16_t acc = tile_product(a);
+      add_bias(acc, t);
+      return acc;
+    };
+    auto tile_max = [&](const f32x16_t& acc, int t, float mx) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (centroid_of(t, r) < B) mx = fmaxf(mx, acc[r]);
+      return mx;
+    };
+    auto tile_candidates = [&](const f32x16_t& acc, int t, float lim) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int b = centroid_of(t, r);
-        if (b < B) mx = fmaxf(mx, acc[r] + (bu ? bu[b] : 0.f));
+        if (b < B && col < n_here && !(acc[r] < lim)) {
+          const unsigned i = atomicAdd(&s_ncand, 1u);
+          if (i < (unsigned)kCandCap) s_cand[i] = (col << 24) | b;
+        }
       }
+    };
+
+    // the wave's first kKeepTiles tiles: every load goes out before the first product (tiles past
+    // the end repeat the last one and are ignored below)
+    f32x16_t kept[kKeepTiles];
+    // the tile numbers are made opaque per group: as loop invariants the compiler computes every address of
+    // every tile (centroid rows, biases) ahead of the loop and spills them
+    int wave_t = wave;
+    asm volatile("" : "+v"(wave_t));
+    {
+      bf16x8_t a[kKeepTiles][8];
+#pragma unroll
+      for (int k = 0; k < kKeepTiles; ++k) tile_load(min(wave_t + k * kRescoreWaves, n_tiles - 1), a[k]);
+      __builtin_amdgcn_sched_barrier(0);     // left alone the compiler keeps three or four loads in flight
+#pragma unroll
+      for (int k = 0; k < kKeepTiles; ++k) kept[k] = tile_product(a[k]);
     }
+#pragma unroll
+    for (int k = 0; k < kKeepTiles; ++k) add_bias(kept[k], min(wave_t + k * kRescoreWaves, n_tiles - 1));
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kKeepTiles; ++k) {
+      const int t = wave_t + k * kRescoreWaves;
+      if (t < n_tiles) mx = tile_max(kept[k], t, mx);
+    }
+    for (int t = wave_t + kKeepTiles * kRescoreWaves; t < n_tiles; t += kRescoreWaves) mx = tile_max(tile_scores(t), t, mx);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     if (half == 0) s_max[wave][col] = mx;
     __syncthreads();
+    SAAP_TRACE(2);
     if (tid < kGroupKeys) {
       float m = s_max[0][tid];
       for (int w = 1; w < kRescoreWaves; ++w) m = fmaxf(m, s_max[w][tid]);
@@ -421,41 +487,36 @@ assign_rescore_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ c
     }
     __syncthreads();
     const float lim = s_lim[col];
-    for (int t = wave; t < n_tiles; t += kRescoreWaves) {
-      const f32x16_t acc = tile_scores(t);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int b = centroid_of(t, r);
-        const float sc = acc[r] + (bu ? bu[b < B ? b : 0] : 0.f);
-        if (b < B && col < n_here && !(sc < lim)) {
-          const unsigned i = atomicAdd(&s_ncand, 1u);
-          if (i < (unsigned)kCandCap) s_cand[i] = (col << 24) | b;
-        }
-      }
+    for (int k = 0; k < kKeepTiles; ++k) {
+      const int t = wave_t + k * kRescoreWaves;
+      if (t < n_tiles) tile_candidates(kept[k], t, lim);
     }
+    for (int t = wave_t + kKeepTiles * kRescoreWaves; t < n_tiles; t += kRescoreWaves) tile_candidates(tile_scores(t), t, lim);
     __syncthreads();
+    SAAP_TRACE(3);
     const unsigned n_cand = s_ncand;
+    if (tid == 0) SAAP_TRACE_VALUE(7, n_cand);
     if (n_cand <= (unsigned)kCandCap) {
       for (unsigned i = tid; i < n_cand; i += kRescoreThreads) {
         const int key = s_cand[i] >> 24, b = s_cand[i] & 0xffffff;
         double t = score_bf16_f64(reinterpret_cast<const uint4*>(x + (size_t)s_key[key] * kD),
                                   reinterpret_cast<const uint4*>(cu + (size_t)b * kD));
         if (bu) t += (double)bu[b];
-        s_cscore[i] = t;
+        const unsigned long long o = ordered_bits(t);
+        s_cscore[i] = o;
+        atomicMax(&s_kbest[key], o);
       }
       __syncthreads();
-      if (tid < n_here) {
-        double best = 0.0;
-        int best_id = -1;
-        for (unsigned i = 0; i < n_cand; ++i) {
-          const int key = s_cand[i] >> 24, b = s_cand[i] & 0xffffff;
-          if (key == tid && better(s_cscore[i], b, best, best_id)) {
-            best = s_cscore[i];
-            best_id = b;
-          }
-        }
-        ids[s_key[tid]] = best_id;
+      SAAP_TRACE(4);
+      for (unsigned i = tid; i < n_cand; i += kRescoreThreads) {
+        const int key = s_cand[i] >> 24, b = s_cand[i] & 0xffffff;
+        if (s_cscore[i] == s_kbest[key]) atomicMin(&s_kid[key], b);
       }
+      __syncthreads();
+      // every key has a candidate (its fp32 maximum is within the bound of itself)
+      if (tid < n_here) ids[s_key[tid]] = s_kid[tid];
+      SAAP_TRACE(5);
     } else {
       // too many candidates: every key of the group against every centroid in double precision
       for (int key = 0; key < n_here; ++key) {
@@ -514,6 +575,7 @@ assign_rescore_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ c
     __syncthreads();
     if (total) atomicAdd(stat, total);
   }
+  SAAP_TRACE(6);
 }
 
 }  // namespace
@@ -531,6 +593,7 @@ extern "C" int32_t saap_assign_keys(const void* x, const void* centroids, const 
                                     int32_t* bucket_ids, int32_t S, int32_t Hkv, int32_t N, int32_t B,
                                     int32_t d, int32_t dtype, void* ws, size_t ws_bytes, void* stream) {
   begin_call();
+  saap_trace_arm();
   if (!x || !centroids || !bucket_ids || !ws) return SAAP_INVALID_ARG;
   if (!aligned16(x) || !aligned16(centroids) || !aligned16(bucket_ids) || !aligned16(ws)) return SAAP_INVALID_ARG;
   if (S <= 0 || Hkv <= 0 || N <= 0 || B <= 0) return SAAP_INVALID_ARG;
@@ -570,7 +633,7 @@ extern "C" int32_t saap_assign_keys(const void* x, const void* centroids, const 
   unsigned* stat = reinterpret_cast<unsigned*>(cmax) + 4095;
   // workgroups per head: enough to fill the chip twice over all heads together
   const unsigned per_head = (unsigned)((cus * 2 + Hkv - 1) / Hkv);
-  hipLaunchKernelGGL(assign_rescore_kernel, dim3(per_head, (unsigned)Hkv), dim3(kRescoreThreads), 0, hs, xb, cb, bias, cmax,
+  hipLaunchKernelGGL(assign_rescore_kernel, dim3((unsigned)Hkv, per_head), dim3(kRescoreThreads), 0, hs, xb, cb, bias, cmax,
                      bucket_ids, flagged, n_flagged, stat, list_cap, Hkv, B, tol);
   return launch_status();
 }
