@@ -135,7 +135,22 @@ scatter_kernel(const int32_t* __restrict__ ids, const int32_t* __restrict__ slic
   const int slice = blockIdx.x, unit = blockIdx.y, lane = threadIdx.x;
   const int32_t* base = slice_base + ((size_t)unit * n_slices + slice) * B;
   const int32_t* o = off + (size_t)unit * ostride;
-  for (int b = lane; b < B; b += 64) s_next[b] = o[b] + base[b];
+  // eight pairs of loads in flight per lane: one at a time the 2 * B / 64 dependent round trips took as long as
+  // the scatter itself
+  for (int b0 = 0; b0 < B; b0 += 64 * 8) {
+    int ov[8], bv[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int b = min(b0 + u * 64 + lane, B - 1);
+      ov[u] = o[b];
+      bv[u] = base[b];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int b = b0 + u * 64 + lane;
+      if (b < B) s_next[b] = ov[u] + bv[u];
+    }
+  }
   __syncthreads();
   const int n0 = slice * kSlice, n1 = min(n0 + kSlice, N);
   const int32_t* idu = ids + (size_t)unit * N;
@@ -167,7 +182,9 @@ scatter_kernel(const int32_t* __restrict__ ids, const int32_t* __restrict__ slic
       ix[slot + rank] = n;
       if (rank == cnt - 1) s_next[b] = slot + cnt;
     }
-    __syncthreads();   // one wave: orders the LDS update before the next 64 positions
+    // one wave: its LDS accesses execute in order, so the update is seen by the next 64 positions.  No barrier:
+    // a barrier also waits for the index store above, one memory round trip per 64 positions
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   }
 }
 
