@@ -286,10 +286,23 @@ __device__ __forceinline__ void take_better(double& best, int& best_id, double o
     best_id = oid;
   }
 }
-// Best candidate of the wave, in every lane.
+// Best candidate of the wave, in every lane.  Inside the rows of 16 lanes the partners' candidates come over the
+// data-parallel primitives (three register moves per step); only the two steps between rows go through the LDS
+// crossbar.  All 64 lanes must be active.
+template <int CTRL>
+__device__ __forceinline__ void take_better_dpp(double& best, int& best_id) {
+  const unsigned long long u = (unsigned long long)__double_as_longlong(best);
+  const unsigned long long lo = dpp_u32<CTRL>((unsigned)u), hi = dpp_u32<CTRL>((unsigned)(u >> 32));
+  const int oid = (int)dpp_u32<CTRL>((unsigned)best_id);
+  take_better(best, best_id, __longlong_as_double((long long)((hi << 32) | lo)), oid);
+}
 __device__ __forceinline__ void wave_best(double& best, int& best_id) {
+  take_better_dpp<kDppXor1>(best, best_id);
+  take_better_dpp<kDppXor2>(best, best_id);
+  take_better_dpp<kDppHalfMirror>(best, best_id);
+  take_better_dpp<kDppMirror>(best, best_id);
 #pragma unroll
-  for (int sh = 32; sh > 0; sh >>= 1) {
+  for (int sh = 16; sh <= 32; sh <<= 1) {
     const double ob = __shfl_xor(best, sh);
     const int oid = __shfl_xor(best_id, sh);
     take_better(best, best_id, ob, oid);
@@ -335,6 +348,7 @@ window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, con
   // goes straight into its bucket, res_ids is not touched and pos_new may be null (idx gets -2).
   __shared__ double s_x[kD];
   const int slab = blockIdx.x, unit = blockIdx.y, h = unit % Hkv, lane = threadIdx.x;
+  SAAP_TRACE(0);
   const int W = n_sink + n_recent;
   const int32_t* o = off + (size_t)unit * (runs + 1);
   int32_t* l = len + (size_t)unit * runs;
@@ -382,6 +396,7 @@ window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, con
   s_x[lane] = to_f64<T>(x0);
   s_x[64 + lane] = to_f64<T>(x1);
   __syncthreads();
+  SAAP_TRACE(1);
   double best = 0.0;
   int best_id = -1;
   for (int c = 0; c < cpl; ++c) {                // ascending ids per lane: ties keep the lowest
@@ -392,7 +407,9 @@ window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, con
       take_better(best, best_id, t, bc);
     }
   }
+  SAAP_TRACE(2);
   wave_best(best, best_id);
+  SAAP_TRACE(3);
   if (P > 1) {
     if (lane == 0) {
       PushPartial* mine = part + (size_t)unit * P + slab;
@@ -404,15 +421,20 @@ window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, con
     unsigned old = 0;
     if (lane == 0) old = __hip_atomic_fetch_add(&counters[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     old = (unsigned)__shfl((int)old, 0);
+    SAAP_TRACE(4);
     if (old != (unsigned)(P - 1)) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    // every partial was stored through to the device's coherent level and acknowledged before its arrival was
+    // counted: loads of the same scope see it, and no cache has to be invalidated for them
     best = 0.0;
     best_id = -1;
     for (int i = lane; i < P; i += 64) {       // ascending slabs per lane
-      const PushPartial* q = part + (size_t)unit * P + i;
-      take_better(best, best_id, q->score, q->id);
+      PushPartial* q = part + (size_t)unit * P + i;
+      const double qs = __hip_atomic_load(&q->score, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int qi = __hip_atomic_load(&q->id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      take_better(best, best_id, qs, qi);
     }
     wave_best(best, best_id);
+    SAAP_TRACE(5);
     if (lane == 0) __hip_atomic_store(&counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
@@ -447,6 +469,7 @@ window_push_kernel(const T* __restrict__ x_new, const T* __restrict__ k_new, con
     Vu[(size_t)slot * kD + lane] = to_cache<C, T>(v0, v_inv);
     Vu[(size_t)slot * kD + 64 + lane] = to_cache<C, T>(v1, v_inv);
   }
+  SAAP_TRACE(6);
 }
 
 // ---- recompact: fresh slack behind every bucket without assigning the keys again ---------------
@@ -663,6 +686,7 @@ extern "C" int32_t saap_append_keys(const void* x_new, const void* k_new, const 
                                     int32_t Hkv, int32_t Ncap, int32_t B, int32_t d, int32_t dtype, void* ws,
                                     size_t ws_bytes, void* stream) {
   begin_call();
+  saap_trace_arm();
   if (!x_new || !k_new || !v_new || !centroids || !off || !len || !idx || !Ksorted || !Vsorted ||
       !new_bucket_ids || !overflow_flag || !ws)
     return SAAP_INVALID_ARG;
