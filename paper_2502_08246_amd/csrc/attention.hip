@@ -255,6 +255,18 @@ __device__ __forceinline__ float ror_sum(float x) {
 // value of lane L of the 16-lane group, in every lane of the group
 template <int L>
 __device__ __forceinline__ float group_bcast(float x) { return dpp_mov<0x150 + L>(x); }
+// the same for an integer and a lane number i < N that the unrolled caller knows at compile time (a register move
+// where a shuffle would go through the LDS crossbar)
+template <int N>
+__device__ __forceinline__ unsigned row_lane(int x, int i) {
+  static_assert(N <= 4, "lanes 0..3 of the group");
+  switch (i) {
+    case 0: return dpp_u32<0x150>((unsigned)x);
+    case 1: return dpp_u32<0x151>((unsigned)x);
+    case 2: return dpp_u32<0x152>((unsigned)x);
+    default: return dpp_u32<0x153>((unsigned)x);
+  }
+}
 
 // The unnormalised outputs a lane accumulates: 8 features of each of the G heads.  Matrix path: one
 // accumulator of the matrix instruction per feature, whose four registers are the four heads.
@@ -648,8 +660,7 @@ __device__ __forceinline__ void final_merge(const float* part_o, const float* pa
     }
     float mx = fmaxf(ml[0].x, ml[1].x);
     for (int pi = lane + 128; pi < P; pi += 64) mx = fmaxf(mx, merge_load2<COHERENT>(pml + (size_t)pi * G + g).x);   // more than 128 partials
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    mx = wave_max(mx);
     float lsum = 0.f;
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
@@ -664,8 +675,7 @@ __device__ __forceinline__ void final_merge(const float* part_o, const float* pa
       s_w[pi * G + g] = w;
       lsum = fmaf(w, t.y, lsum);
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) lsum += __shfl_xor(lsum, o);
+    lsum = wave_sum(lsum);
     if (lane == 0) {
       s_M[g] = mx;
       s_L[g] = lsum;
@@ -1002,8 +1012,8 @@ __global__ void __launch_bounds__(NT) attn_kernel(AttnParams p) {
     }
 #pragma unroll
     for (int i = 0; i < KB; ++i) {
-      const int r = __shfl(row, (lane & 48) + i);
-      if constexpr (MASKED) bt.heads |= (unsigned)__shfl(hmask, (lane & 48) + i) << (8 * i);
+      const int r = (int)row_lane<KB>(row, i);      // the row resolved by lane i of this 16-lane group
+      if constexpr (MASKED) bt.heads |= row_lane<KB>(hmask, i) << (8 * i);
       if (base + i * NG + kp < T_total) bt.valid |= 1u << i;
       if constexpr (!MM) bt.k[i].load_stream(Kb + (size_t)r * kD);
       bt.v[i].load_stream(Vb + (size_t)r * kD);
@@ -1449,7 +1459,7 @@ __global__ void __launch_bounds__(NT) attn_plan_kernel(PlanParams p) {
       }
 #pragma unroll
       for (int i = 0; i < KB; ++i) {
-        const int r = __shfl(row, (lane & 48) + i);
+        const int r = (int)row_lane<KB>(row, i);
         // slots past the end of the piece read its last key again (and score -inf): loads under a
         // branch would make the number of loads in flight unknown to the wait counters, and every wait
         // would then drain them all

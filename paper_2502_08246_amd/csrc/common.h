@@ -77,6 +77,26 @@ __device__ __forceinline__ float sum16(float x) {
   return x;
 }
 
+// Maximum / sum over the 64 lanes, in every lane: four register-move steps inside the rows of 16 lanes, then the
+// four row results are read as scalars (no LDS crossbar).  All 64 lanes must be active.
+__device__ __forceinline__ float wave_max(float x) {
+  x = fmaxf(x, dpp_mov<kDppXor1>(x));
+  x = fmaxf(x, dpp_mov<kDppXor2>(x));
+  x = fmaxf(x, dpp_mov<kDppHalfMirror>(x));
+  x = fmaxf(x, dpp_mov<kDppMirror>(x));
+  const int b = __float_as_int(x);
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(b, 0)), r1 = __int_as_float(__builtin_amdgcn_readlane(b, 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(b, 32)), r3 = __int_as_float(__builtin_amdgcn_readlane(b, 48));
+  return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+__device__ __forceinline__ float wave_sum(float x) {
+  x = sum16(x);
+  const int b = __float_as_int(x);
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(b, 0)), r1 = __int_as_float(__builtin_amdgcn_readlane(b, 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(b, 32)), r3 = __int_as_float(__builtin_amdgcn_readlane(b, 48));
+  return (r0 + r1) + (r2 + r3);
+}
+
 // ---- wave-wide scans and reductions on DPP (no LDS crossbar round trips) ------------------------
 template <int CTRL, int ROW_MASK = 0xf>
 __device__ __forceinline__ unsigned dpp_u32(unsigned x) {

@@ -287,8 +287,8 @@ __device__ __forceinline__ void take_better(double& best, int& best_id, double o
   }
 }
 // Best candidate of the wave, in every lane.  Inside the rows of 16 lanes the partners' candidates come over the
-// data-parallel primitives (three register moves per step); only the two steps between rows go through the LDS
-// crossbar.  All 64 lanes must be active.
+// data-parallel primitives (three register moves per step), between the rows over the row-swap instructions: no
+// step goes through the LDS crossbar.  All 64 lanes must be active.
 template <int CTRL>
 __device__ __forceinline__ void take_better_dpp(double& best, int& best_id) {
   const unsigned long long u = (unsigned long long)__double_as_longlong(best);
@@ -301,11 +301,25 @@ __device__ __forceinline__ void wave_best(double& best, int& best_id) {
   take_better_dpp<kDppXor2>(best, best_id);
   take_better_dpp<kDppHalfMirror>(best, best_id);
   take_better_dpp<kDppMirror>(best, best_id);
-#pragma unroll
-  for (int sh = 16; sh <= 32; sh <<= 1) {
-    const double ob = __shfl_xor(best, sh);
-    const int oid = __shfl_xor(best_id, sh);
-    take_better(best, best_id, ob, oid);
+  // between the rows: the row-swap instructions hand every lane its own candidate and that of the same lane one
+  // row (then two rows) away, in an order that is the same for the three words
+  {
+    const unsigned long long u = (unsigned long long)__double_as_longlong(best);
+    const auto lo = __builtin_amdgcn_permlane16_swap((unsigned)u, (unsigned)u, false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap((unsigned)(u >> 32), (unsigned)(u >> 32), false, false);
+    const auto id = __builtin_amdgcn_permlane16_swap((unsigned)best_id, (unsigned)best_id, false, false);
+    best = __longlong_as_double((long long)(((unsigned long long)hi[0] << 32) | lo[0]));
+    best_id = (int)id[0];
+    take_better(best, best_id, __longlong_as_double((long long)(((unsigned long long)hi[1] << 32) | lo[1])), (int)id[1]);
+  }
+  {
+    const unsigned long long u = (unsigned long long)__double_as_longlong(best);
+    const auto lo = __builtin_amdgcn_permlane32_swap((unsigned)u, (unsigned)u, false, false);
+    const auto hi = __builtin_amdgcn_permlane32_swap((unsigned)(u >> 32), (unsigned)(u >> 32), false, false);
+    const auto id = __builtin_amdgcn_permlane32_swap((unsigned)best_id, (unsigned)best_id, false, false);
+    best = __longlong_as_double((long long)(((unsigned long long)hi[0] << 32) | lo[0]));
+    best_id = (int)id[0];
+    take_better(best, best_id, __longlong_as_double((long long)(((unsigned long long)hi[1] << 32) | lo[1])), (int)id[1]);
   }
 }
 
