@@ -552,19 +552,24 @@ __device__ __forceinline__ void workgroup_combine(float* scratch, float m, float
   SAAP_TRACE(13);
   for (int x = tid; x < G * kD; x += NT) {
     const int g = x / kD, e = x % kD;
-    float mj[nw];
-    float M = kNegBig;
+    // every LDS read goes out before the first use: read, wait and use per wave would be eight round trips
+    float mj[nw], lj[nw], oj[nw];
 #pragma unroll
     for (int j = 0; j < nw; ++j) {
       mj[j] = w_m[j * G + g];
-      M = fmaxf(M, mj[j]);
+      lj[j] = w_l[j * G + g];
+      oj[j] = w_o[(j * G + g) * kD + e];
     }
+    __builtin_amdgcn_sched_barrier(0);
+    float M = kNegBig;
+#pragma unroll
+    for (int j = 0; j < nw; ++j) M = fmaxf(M, mj[j]);
     float L = 0.f, Ov = 0.f;
 #pragma unroll
     for (int j = 0; j < nw; ++j) {
       const float w = fast_exp2(mj[j] - M);
-      L = fmaf(w, w_l[j * G + g], L);
-      Ov = fmaf(w, w_o[(j * G + g) * kD + e], Ov);
+      L = fmaf(w, lj[j], L);
+      Ov = fmaf(w, oj[j], Ov);
     }
     emit(g, e, M, L, Ov);
   }
@@ -606,8 +611,21 @@ __device__ __forceinline__ void merge_load4x8(const float4* const (&ptr)[8], con
 #pragma unroll
     for (int k = 0; k < 8; ++k) v[k] = on[k] ? make_float4(r[k].x, r[k].y, r[k].z, r[k].w) : make_float4(0.f, 0.f, 0.f, 0.f);
   } else {
+    // every load is issued, on a valid address, before any value is looked at: as loads under the `on` branches
+    // they waited for one another (one memory round trip per partial result instead of one in all)
+    float4 r[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) v[k] = on[k] ? *ptr[k] : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int k = 0; k < 8; ++k) {
+      r[k] = *ptr[k];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      v[k].x = on[k] ? r[k].x : 0.f;
+      v[k].y = on[k] ? r[k].y : 0.f;
+      v[k].z = on[k] ? r[k].z : 0.f;
+      v[k].w = on[k] ? r[k].w : 0.f;
+    }
   }
 }
 
@@ -685,16 +703,18 @@ __device__ __forceinline__ void final_merge(const float* part_o, const float* pa
   __syncthreads();
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int p0 = pgrp;; p0 += n_groups * kInFlight) {
+    // the weights of the round first, all reads in flight together (a partial past the end was loaded as zeros
+    // and takes the last partial's weight)
+    float wv[kInFlight];
+#pragma unroll
+    for (int k = 0; k < kInFlight; ++k) wv[k] = s_w[min(p0 + k * n_groups, P - 1) * G + g_col];
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int k = 0; k < kInFlight; ++k) {
-      const int pi = p0 + k * n_groups;
-      if (pi < P) {
-        const float w = s_w[pi * G + g_col];
-        acc.x = fmaf(w, v[k].x, acc.x);
-        acc.y = fmaf(w, v[k].y, acc.y);
-        acc.z = fmaf(w, v[k].z, acc.z);
-        acc.w = fmaf(w, v[k].w, acc.w);
-      }
+      acc.x = fmaf(wv[k], v[k].x, acc.x);
+      acc.y = fmaf(wv[k], v[k].y, acc.y);
+      acc.z = fmaf(wv[k], v[k].z, acc.z);
+      acc.w = fmaf(wv[k], v[k].w, acc.w);
     }
     const int nxt = p0 + n_groups * kInFlight;
     if (nxt - pgrp >= P) break;     // uniform over the workgroup: depends on P and n_groups only
