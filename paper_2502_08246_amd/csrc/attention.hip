@@ -1220,20 +1220,26 @@ __device__ __forceinline__ void combine_deposits(const float* area, int lane, F 
   const float* w_l = w_m + nw * G;                        // [nw][G] sums of weights
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    float wj[nw];
-    float M = kNegBig;
+    // the head's LDS reads all go out before the first use
+    float wj[nw], lj[nw], a0[nw], a1[nw];
 #pragma unroll
     for (int j = 0; j < nw; ++j) {
       wj[j] = w_m[j * G + g];
-      M = fmaxf(M, wj[j]);
+      lj[j] = w_l[j * G + g];
+      a0[j] = w_o[(j * G + g) * kD + lane];
+      a1[j] = w_o[(j * G + g) * kD + 64 + lane];
     }
+    __builtin_amdgcn_sched_barrier(0);
+    float M = kNegBig;
+#pragma unroll
+    for (int j = 0; j < nw; ++j) M = fmaxf(M, wj[j]);
     float L = 0.f, o0 = 0.f, o1 = 0.f;
 #pragma unroll
     for (int j = 0; j < nw; ++j) {
       const float w = fast_exp2(wj[j] - M);
-      L = fmaf(w, w_l[j * G + g], L);
-      o0 = fmaf(w, w_o[(j * G + g) * kD + lane], o0);
-      o1 = fmaf(w, w_o[(j * G + g) * kD + 64 + lane], o1);
+      L = fmaf(w, lj[j], L);
+      o0 = fmaf(w, a0[j], o0);
+      o1 = fmaf(w, a1[j], o1);
     }
     emit(g, lane, M, L, o0);
     emit(g, lane + 64, M, L, o1);
