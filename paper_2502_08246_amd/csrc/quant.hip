@@ -14,6 +14,7 @@ namespace {
 
 constexpr int kQThreads = 256;
 constexpr int kQSlices = 64;      // workgroups per (tensor, unit) in both passes
+constexpr int kQUnroll = 4;       // 16-byte (bf16) loads a thread has in flight
 
 template <typename T>
 __global__ void __launch_bounds__(kQThreads)
@@ -22,13 +23,19 @@ absmax_kernel(const T* __restrict__ K, const T* __restrict__ V, unsigned* __rest
   const int unit = blockIdx.y, tensor = blockIdx.z;
   const T* x = (tensor ? V : K) + (size_t)unit * pieces * 8;
   float m = 0.f;
-  for (size_t i = (size_t)blockIdx.x * kQThreads + threadIdx.x; i < pieces; i += (size_t)kQSlices * kQThreads) {
-    Vec8<T> v;
-    v.load(x + i * 8);
-    float f[8];
-    v.to_float(f);
+  // four loads in flight per thread (a piece past the end reads the last one again: the maximum does not change)
+  const size_t step = (size_t)kQSlices * kQThreads;
+  for (size_t i = (size_t)blockIdx.x * kQThreads + threadIdx.x; i < pieces; i += kQUnroll * step) {
+    Vec8<T> v[kQUnroll];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf(f[e]));
+    for (int u = 0; u < kQUnroll; ++u) v[u].load_stream(x + min(i + u * step, pieces - 1) * 8);
+#pragma unroll
+    for (int u = 0; u < kQUnroll; ++u) {
+      float f[8];
+      v[u].to_float(f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf(f[e]));
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
@@ -55,17 +62,22 @@ quantize_kernel(const T* __restrict__ K, const T* __restrict__ V, uint8_t* __res
   const int e = amax > 0.f ? unit_exponent(amax) : 0;
   const float inv = ldexpf(1.f, -e);
   if (blockIdx.x == 0 && threadIdx.x == 0) (tensor ? vscale : kscale)[unit] = ldexpf(1.f, e);
-  for (size_t i = (size_t)blockIdx.x * kQThreads + threadIdx.x; i < pieces; i += (size_t)kQSlices * kQThreads) {
-    Vec8<T> v;
-    v.load(x + i * 8);
-    float f[8];
-    v.to_float(f);
-    int lo = 0, hi = 0;
-    lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[0] * inv, f[1] * inv, lo, false);
-    lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[2] * inv, f[3] * inv, lo, true);
-    hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[4] * inv, f[5] * inv, hi, false);
-    hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[6] * inv, f[7] * inv, hi, true);
-    y[i] = make_uint2((unsigned)lo, (unsigned)hi);
+  const size_t step = (size_t)kQSlices * kQThreads;
+  for (size_t i = (size_t)blockIdx.x * kQThreads + threadIdx.x; i < pieces; i += kQUnroll * step) {
+    Vec8<T> v[kQUnroll];
+#pragma unroll
+    for (int u = 0; u < kQUnroll; ++u) v[u].load_stream(x + min(i + u * step, pieces - 1) * 8);
+#pragma unroll
+    for (int u = 0; u < kQUnroll; ++u) {
+      float f[8];
+      v[u].to_float(f);
+      int lo = 0, hi = 0;
+      lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[0] * inv, f[1] * inv, lo, false);
+      lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[2] * inv, f[3] * inv, lo, true);
+      hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[4] * inv, f[5] * inv, hi, false);
+      hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[6] * inv, f[7] * inv, hi, true);
+      if (i + u * step < pieces) y[i + u * step] = make_uint2((unsigned)lo, (unsigned)hi);
+    }
   }
 }
 
