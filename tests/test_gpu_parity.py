@@ -475,6 +475,26 @@ def test_assign_keys_degenerate_rows(saap):
     assert (got[:, :, 100:300] == 0).all()
 
 
+@pytest.mark.parametrize("S,Hkv,N,B,bias", [(1, 2, 6000, 1024, False), (2, 1, 3000, 1536, True), (1, 1, 4000, 96, False)])
+def test_assign_keys_every_key_between_two_centroids(saap, S, Hkv, N, B, bias):
+    """Every key is the sum of two centroids, so its best two scores are close and all keys go through the
+    re-scoring pass: several groups of 32 keys per workgroup, more tiles per wave than it keeps scores for
+    (B = 1536), fewer tiles than waves (B = 96)."""
+    g = torch.Generator(device="cpu").manual_seed(97)
+    cent = torch.randn(Hkv, B, 128, generator=g).to(torch.bfloat16).to(DEV)
+    i0 = torch.randint(0, B, (S, Hkv, N), generator=g).to(DEV)
+    i1 = torch.randint(0, B, (S, Hkv, N), generator=g).to(DEV)
+    c = cent.float()
+    x = torch.stack([torch.stack([c[hh][i0[s, hh]] + c[hh][i1[s, hh]] for hh in range(Hkv)]) for s in range(S)])
+    x = x.to(torch.bfloat16).contiguous()
+    b = (-0.5 * c.pow(2).sum(-1)).contiguous() if bias else None
+    ids = saap.assign_keys(x, cent, b)
+    torch.cuda.synchronize()
+    want = ref.assign_keys(h(x), h(cent), None if b is None else h(b))
+    got = ids.cpu().numpy()
+    assert np.array_equal(got, want), f"{(got != want).sum()} of {got.size} ids differ"
+
+
 # ------------------------------------------------------------------------------ append
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_append_keys(saap, dtype):
