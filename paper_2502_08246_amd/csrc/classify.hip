@@ -8,7 +8,7 @@
 //                   units); h goes to the workspace in fp32.  With hidden = 0 the same kernel
 //                   without the ReLU is the whole (one-layer) model.
 //   output kernel   z = W2 h + b2: one workgroup of eight waves per (weight set, 16-row tile,
-//                   32 or 64 buckets), so that a 1024-bucket classifier for 8 KV heads fills all
+//                   32, 64 or 128 buckets), so that a 1024-bucket classifier for 8 KV heads fills all
 //                   256 compute units with about 40 KB of loads each.  What one compute unit
 //                   pulls from memory grows with the number of waves that have loads in flight,
 //                   hence eight waves with few loads each rather than two with many.
@@ -117,8 +117,8 @@ constexpr int kOutChunk = 512;      // hidden units per LDS pass of the output k
 // Eight waves per workgroup: what one compute unit pulls from memory grows with the number of
 // waves that have loads in flight (two waves were measured at a third of the rate of eight).
 // A workgroup takes SLAB = 32 buckets, or 64 when 32 would make more than one workgroup per compute
-// unit.  For the matrix products wave (t, kq) takes bucket tile t of the SLAB/16 and
-// every KQ-th k-step starting at kq (KQ = 8 / tiles); the KQ partial products of a tile are added
+// unit (128 when 64 still would and the tiles fit).  For the matrix products wave (t, kq) takes
+// bucket tile t of the SLAB/16 and every KQ-th k-step starting at kq (KQ = 8 / tiles); the KQ partial products of a tile are added
 // through LDS in a fixed order.
 constexpr int kOutThreads = 512;
 constexpr int kOutLoads = 16 * 128 / kOutThreads;     // 16-byte loads of activations per thread
@@ -421,7 +421,16 @@ static int32_t launch_mlp_bf16(const void* xq, const void* W1, const float* b1, 
   // workgroup reads its rows of the hidden activations (as many bytes as a 32-bucket slab of W2 for a
   // full 16-row tile), so fewer, wider workgroups move fewer bytes (batch 8: 11.5 -> 8.8 us)
   const bool wide = (long long)((B + 31) / 32) * m_tiles * Hw > (long long)device_cus();
-  const int slab_rows = wide ? 64 : 32;
+  int slab_rows = wide ? 64 : 32;
+  {
+    // 128 buckets when 64 would still give more than one workgroup per compute unit and the tiles fit the LDS of one
+    // (few rows per weight set): with one workgroup per compute unit all loads of the launch are in flight at once
+    // and no second round of workgroups waits behind the first (4096 buckets, batch 1: 12.7 -> 10.9 us)
+    const int rows = sh.rows_per_set < 16 ? sh.rows_per_set : 16;
+    const size_t lds128 = (size_t)(3 * rows + 128) * ((hidden < kOutChunk ? hidden : kOutChunk) + 8) * sizeof(bf16_t);
+    if (wide && (long long)((B + 63) / 64) * m_tiles * Hw > (long long)device_cus() && lds128 <= 150 * 1024)
+      slab_rows = 128;
+  }
   const unsigned g2 = (unsigned)((B + slab_rows - 1) / slab_rows) * m_tiles * Hw;
   hipLaunchKernelGGL(mlp_hidden_bf16_kernel<false>, dim3(g1), dim3(256), 0, hs, static_cast<const bf16_t*>(xq),
                      static_cast<const bf16_t*>(W1), b1, hbuf, sh);
@@ -440,22 +449,22 @@ static int32_t launch_mlp_bf16(const void* xq, const void* W1, const float* b1, 
     f.po.lds_off = geo.plan_off;
     if (lds < geo.lds) lds = geo.lds;
   }
-  const void* kern = fs ? (wide ? reinterpret_cast<const void*>(mlp_out_bf16_kernel<64, true>)
-                                : reinterpret_cast<const void*>(mlp_out_bf16_kernel<32, true>))
-                        : (wide ? reinterpret_cast<const void*>(mlp_out_bf16_kernel<64, false>)
-                                : reinterpret_cast<const void*>(mlp_out_bf16_kernel<32, false>));
-  if (lds > 48 * 1024) {
-    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return SAAP_HIP_ERROR;
-  }
-  const bf16_t* w2 = static_cast<const bf16_t*>(W2);
+  // the same slab width with and without the selection: the logits of both calls are then equal bit for bit
+  auto launch = [&](auto kernel) -> int32_t {
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return SAAP_HIP_ERROR;
+    hipLaunchKernelGGL(kernel, dim3(g2), dim3(kOutThreads), lds, hs, hbuf, static_cast<const bf16_t*>(W2), b2, scores, sh, f);
+    return SAAP_OK;
+  };
   if (fs) {
-    if (wide) hipLaunchKernelGGL((mlp_out_bf16_kernel<64, true>), dim3(g2), dim3(kOutThreads), lds, hs, hbuf, w2, b2, scores, sh, f);
-    else hipLaunchKernelGGL((mlp_out_bf16_kernel<32, true>), dim3(g2), dim3(kOutThreads), lds, hs, hbuf, w2, b2, scores, sh, f);
-  } else {
-    if (wide) hipLaunchKernelGGL((mlp_out_bf16_kernel<64, false>), dim3(g2), dim3(kOutThreads), lds, hs, hbuf, w2, b2, scores, sh, f);
-    else hipLaunchKernelGGL((mlp_out_bf16_kernel<32, false>), dim3(g2), dim3(kOutThreads), lds, hs, hbuf, w2, b2, scores, sh, f);
+    if (slab_rows == 128) return launch(mlp_out_bf16_kernel<128, true>);
+    if (slab_rows == 64) return launch(mlp_out_bf16_kernel<64, true>);
+    return launch(mlp_out_bf16_kernel<32, true>);
   }
-  return SAAP_OK;
+  if (slab_rows == 128) return launch(mlp_out_bf16_kernel<128, false>);
+  if (slab_rows == 64) return launch(mlp_out_bf16_kernel<64, false>);
+  return launch(mlp_out_bf16_kernel<32, false>);
 }
 
 extern "C" int32_t saap_classify_queries(const void* xq, const void* W1, const float* b1, const void* W2,
