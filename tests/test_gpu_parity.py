@@ -375,6 +375,8 @@ def test_limits_max_buckets_and_group_of_eight(saap):
     ("bf16", 5, 4, 1, 64, 4096, "q", False),
     ("bf16", 1, 32, 8, 1024, 1024, "kv", True),      # the paper's model size (Section 6.1: hidden layer of 1024)
     ("bf16", 2, 8, 2, 1536, 208, "kv", False),       # the largest hidden layer the kernels take
+    ("bf16", 1, 32, 8, 512, 4096, "kv", True),       # many buckets, few rows: 128 buckets per workgroup
+    ("bf16", 2, 16, 8, 256, 4000, "kv", False),      # the same with a ragged last slab
 ])
 def test_classify_queries(saap, dtype, S, Hq, Hkv, hidden, B, Hw_kind, bias):
     cfg = small("cfg1_llama8b_128k", S=S, Hq=Hq, Hkv=Hkv, N=16, B=B, hidden=hidden, dtype=dtype)
